@@ -1,0 +1,437 @@
+"""CPU oracle for the STaMP quantized linear layer (arXiv 2510.26771).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the HIP library is checked
+against.  Only tests, the smoke check and the benchmark's cpu_baseline leg may import it; the
+product path never does, and it shares no code with the HIP sources.
+
+What it computes is the paper's Algorithm "STaMP Linear" (section "Sequence Transform and Mixed
+Precision"), taken step by step:
+
+    X <- L X            sequence transform along the tokens (Haar DWT, section "Efficient
+                        Energy Concentration")
+    x_i <- Q(x_i; b_i)  per-token quantization (Background, Eq. 1), b_i = 8 for the first k
+                        transformed tokens and 4 for the rest (section "Optimal bit allocation")
+    Y <- X W            integer matrix product against per-output-channel quantized weights
+    Y <- L^-1 Y         inverse sequence transform (valid by the commutation identity of
+                        section "Method")
+    Y <- Y + bias
+
+STaMP is an approximation scheme, so the oracle is the algorithm itself rather than a closed
+form.  Two precisions are offered through the ``dtype`` argument of every floating-point step:
+
+* ``np.float64``: the definition, used by the CPU tests to pin the fp32 path (and available as
+  dense matrices through ``haar1d_matrix`` / ``haar2d_matrix``, which are written from the
+  textbook Haar basis functions, not from the butterfly recursion).
+* ``np.float32``: the bit reference.  Every add, subtract, multiply and divide below is one
+  individually rounded IEEE operation on numpy arrays (numpy never fuses a multiply with an
+  add), in the order written.  Quantized codes depend on these roundings, so the HIP path has
+  to reproduce the same operation order for the forward transform, the scale and the rounding.
+
+Readings of the paper where it is silent (each also listed in the design document):
+
+* Haar matrix: orthonormal (Theorem 1 needs an orthogonal L), detail = even minus odd,
+  approximations first ("pushes the energy in the first half"), Mallat ordering: after J levels
+  slot 0.. hold the coarsest approximations, then the details from coarse to fine.
+* One 1-D level: a = (x[2i] + x[2i+1]) * C, d = (x[2i] - x[2i+1]) * C with C = fl(1/sqrt 2).
+* 2-D: pyramid (recursion on the low-low quarter, "one quarter for 2D signal"); one 2-D level
+  on a 2x2 cell [[p, q], [u, v]] is t0=p+q, t1=p-q, t2=u+v, t3=u-v, LL=(t0+t2)/2, W=(t1+t3)/2,
+  H=(t0-t2)/2, D=(t1-t3)/2.  STaMP order in 2-D: final LL block row-major, then per level from
+  coarse to fine the blocks [W (top-right), H (bottom-left), D (bottom-right)], each row-major.
+* Quantizer: the benchmark configurations fix the symmetric specialisation of Eq. 1:
+  qmax = 2^(b-1) - 1, scale = absmax / qmax (range-based, no clipping, as in the Background
+  section), code = clamp(rne(x * (qmax / absmax)), -qmax, qmax).  A zero row gets scale 0 and
+  codes 0.  Rounding is round-half-to-even.
+* Weights: per output channel, absmax / 7, round to nearest, no range search.
+* W is [d_in, d_out] and Y = X W.
+
+parity unpinned: the paper prints no worked numeric example of a transformed or quantized
+vector, so absolute output values are pinned only through the invariants, closed forms, dense
+definitions and brute-force checks in tests/ (listed in the design document).
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+# fp32 nearest to 1/sqrt(2) (bit pattern 0x3F3504F3); in fp64 the fp64 nearest.
+_INV_SQRT2_F32 = np.float32(0.70710678118654752440)
+_INV_SQRT2_F64 = np.float64(0.70710678118654752440)
+
+
+def _c(dtype):
+    return _INV_SQRT2_F32 if np.dtype(dtype) == np.float32 else _INV_SQRT2_F64
+
+
+def _is_pow2(n: int) -> bool:
+    return n >= 1 and (n & (n - 1)) == 0
+
+
+# --------------------------------------------------------------------------------------
+# 1-D Haar DWT along axis 0 (tokens).  Section "Efficient Energy Concentration".
+# --------------------------------------------------------------------------------------
+
+def haar1d_forward(x: np.ndarray, levels: int, dtype=np.float32) -> np.ndarray:
+    """J-level orthonormal Haar DWT of x[s, ...] along axis 0, result in STaMP order.
+
+    Level l = 1..J acts on the first n = s / 2^(l-1) slots (the current approximation):
+    the n/2 sums go to slots [0, n/2), the n/2 differences to [n/2, n); slots >= n keep the
+    details of the earlier (finer) levels.
+    """
+    t = np.array(x, dtype=dtype, copy=True)
+    s = t.shape[0]
+    if not _is_pow2(s) or levels < 0 or (1 << levels) > s:
+        raise ValueError("seq_len must be a power of two and levels <= log2(seq_len)")
+    C = _c(dtype)
+    n = s
+    for _ in range(levels):
+        even = t[0:n:2].copy()
+        odd = t[1:n:2].copy()
+        t[0:n // 2] = (even + odd) * C
+        t[n // 2:n] = (even - odd) * C
+        n //= 2
+    return t
+
+
+def haar1d_inverse(t: np.ndarray, levels: int, dtype=np.float32) -> np.ndarray:
+    """Inverse of haar1d_forward: levels J..1, x[2i] = (a+d)*C, x[2i+1] = (a-d)*C."""
+    x = np.array(t, dtype=dtype, copy=True)
+    s = x.shape[0]
+    if not _is_pow2(s) or levels < 0 or (1 << levels) > s:
+        raise ValueError("seq_len must be a power of two and levels <= log2(seq_len)")
+    C = _c(dtype)
+    n = s >> (levels - 1) if levels > 0 else s
+    for _ in range(levels):
+        a = x[0:n // 2].copy()
+        d = x[n // 2:n].copy()
+        x[0:n:2] = (a + d) * C
+        x[1:n:2] = (a - d) * C
+        n *= 2
+    return x
+
+
+def haar1d_matrix(s: int, levels: int) -> np.ndarray:
+    """Dense fp64 L (s x s) of the J-level Haar DWT in STaMP order, from the basis functions.
+
+    Rows [0, s/2^J): box functions of length 2^J and height 2^(-J/2).
+    Row s/2^l + i (l = J..1, i < s/2^l): the wavelet of level l at position i: +2^(-l/2) on
+    tokens [i 2^l, i 2^l + 2^(l-1)), -2^(-l/2) on the following 2^(l-1) tokens.
+    """
+    L = np.zeros((s, s), dtype=np.float64)
+    J = levels
+    na = s >> J
+    for i in range(na):
+        L[i, i << J:(i + 1) << J] = 2.0 ** (-J / 2.0)
+    for l in range(J, 0, -1):
+        base = s >> l
+        half = 1 << (l - 1)
+        h = 2.0 ** (-l / 2.0)
+        for i in range(base):
+            L[base + i, (i << l):(i << l) + half] = h
+            L[base + i, (i << l) + half:(i + 1) << l] = -h
+    return L
+
+
+# --------------------------------------------------------------------------------------
+# 2-D Haar pyramid over an H x W token grid, token t = r * W + c.
+# --------------------------------------------------------------------------------------
+
+def haar2d_forward_grid(x: np.ndarray, grid_h: int, grid_w: int, levels: int, dtype=np.float32) -> np.ndarray:
+    """J-level 2-D Haar pyramid; returns the coefficient grid [H, W, ...] (Mallat layout:
+    LL top-left, width-difference band top-right, height-difference band bottom-left,
+    diagonal band bottom-right, recursion on the top-left quarter)."""
+    H, W = grid_h, grid_w
+    if not (_is_pow2(H) and _is_pow2(W)) or levels < 0 or (1 << levels) > min(H, W):
+        raise ValueError("grid sides must be powers of two and levels <= log2(min side)")
+    g = np.array(x, dtype=dtype, copy=True).reshape((H, W) + x.shape[1:])
+    half = np.dtype(dtype).type(0.5)
+    h, w = H, W
+    for _ in range(levels):
+        p = g[0:h:2, 0:w:2].copy()
+        q = g[0:h:2, 1:w:2].copy()
+        u = g[1:h:2, 0:w:2].copy()
+        v = g[1:h:2, 1:w:2].copy()
+        t0 = p + q
+        t1 = p - q
+        t2 = u + v
+        t3 = u - v
+        g[0:h // 2, 0:w // 2] = (t0 + t2) * half
+        g[0:h // 2, w // 2:w] = (t1 + t3) * half
+        g[h // 2:h, 0:w // 2] = (t0 - t2) * half
+        g[h // 2:h, w // 2:w] = (t1 - t3) * half
+        h //= 2
+        w //= 2
+    return g
+
+
+def haar2d_inverse_grid(g_in: np.ndarray, levels: int, dtype=np.float32) -> np.ndarray:
+    """Inverse of haar2d_forward_grid on a coefficient grid [H, W, ...]."""
+    g = np.array(g_in, dtype=dtype, copy=True)
+    H, W = g.shape[0], g.shape[1]
+    half = np.dtype(dtype).type(0.5)
+    h, w = (H >> (levels - 1), W >> (levels - 1)) if levels > 0 else (H, W)
+    for _ in range(levels):
+        cLL = g[0:h // 2, 0:w // 2].copy()
+        cW = g[0:h // 2, w // 2:w].copy()
+        cH = g[h // 2:h, 0:w // 2].copy()
+        cD = g[h // 2:h, w // 2:w].copy()
+        t0 = cLL + cH
+        t2 = cLL - cH
+        t1 = cW + cD
+        t3 = cW - cD
+        g[0:h:2, 0:w:2] = (t0 + t1) * half
+        g[0:h:2, 1:w:2] = (t0 - t1) * half
+        g[1:h:2, 0:w:2] = (t2 + t3) * half
+        g[1:h:2, 1:w:2] = (t2 - t3) * half
+        h *= 2
+        w *= 2
+    return g
+
+
+def stamp_order_2d(grid_h: int, grid_w: int, levels: int) -> np.ndarray:
+    """perm[p] = flat index (r * W + c) into the Mallat coefficient grid of STaMP slot p.
+
+    Slots: the final LL block row-major, then for l = J..1 the three detail blocks of level l
+    in the order top-right, bottom-left, bottom-right, each row-major.  Lowest frequencies first,
+    so "the first k tokens" are the coarsest coefficients.
+    """
+    H, W, J = grid_h, grid_w, levels
+    idx = np.arange(H * W, dtype=np.int64).reshape(H, W)
+    out = [idx[0:H >> J, 0:W >> J].ravel()]
+    for l in range(J, 0, -1):
+        h, w = H >> l, W >> l  # size of each band of level l
+        out.append(idx[0:h, w:2 * w].ravel())
+        out.append(idx[h:2 * h, 0:w].ravel())
+        out.append(idx[h:2 * h, w:2 * w].ravel())
+    return np.concatenate(out)
+
+
+def haar2d_forward(x: np.ndarray, grid_h: int, grid_w: int, levels: int, dtype=np.float32) -> np.ndarray:
+    """x[s = H*W, ...] -> transformed tokens [s, ...] in STaMP order."""
+    g = haar2d_forward_grid(x, grid_h, grid_w, levels, dtype)
+    flat = g.reshape((grid_h * grid_w,) + g.shape[2:])
+    return flat[stamp_order_2d(grid_h, grid_w, levels)]
+
+
+def haar2d_inverse(t: np.ndarray, grid_h: int, grid_w: int, levels: int, dtype=np.float32) -> np.ndarray:
+    """Inverse of haar2d_forward: STaMP-ordered tokens -> original token order."""
+    perm = stamp_order_2d(grid_h, grid_w, levels)
+    flat = np.empty(t.shape, dtype=dtype)
+    flat[perm] = np.asarray(t, dtype=dtype)
+    g = flat.reshape((grid_h, grid_w) + t.shape[1:])
+    x = haar2d_inverse_grid(g, levels, dtype)
+    return x.reshape(t.shape)
+
+
+def _phi(n: int, l: int, i: int) -> np.ndarray:
+    """Box function of level l at position i over n samples, unit norm."""
+    f = np.zeros(n)
+    f[i << l:(i + 1) << l] = 2.0 ** (-l / 2.0)
+    return f
+
+
+def _psi(n: int, l: int, i: int) -> np.ndarray:
+    """Haar wavelet of level l at position i over n samples, unit norm (+ first half, - second)."""
+    f = np.zeros(n)
+    half = 1 << (l - 1)
+    f[(i << l):(i << l) + half] = 2.0 ** (-l / 2.0)
+    f[(i << l) + half:(i + 1) << l] = -(2.0 ** (-l / 2.0))
+    return f
+
+
+def haar2d_matrix(grid_h: int, grid_w: int, levels: int) -> np.ndarray:
+    """Dense fp64 L (s x s) of the 2-D pyramid in STaMP order, from separable basis functions:
+    LL = phi(rows) x phi(cols); W band = phi(rows) x psi(cols) (difference along the width);
+    H band = psi(rows) x phi(cols); D band = psi(rows) x psi(cols)."""
+    H, W, J = grid_h, grid_w, levels
+    rows = []
+    for i in range(H >> J):
+        for j in range(W >> J):
+            rows.append(np.outer(_phi(H, J, i), _phi(W, J, j)).ravel())
+    for l in range(J, 0, -1):
+        h, w = H >> l, W >> l
+        for band in ("W", "H", "D"):
+            for i in range(h):
+                for j in range(w):
+                    fr = _phi(H, l, i) if band == "W" else _psi(H, l, i)
+                    fc = _phi(W, l, j) if band == "H" else _psi(W, l, j)
+                    rows.append(np.outer(fr, fc).ravel())
+    return np.stack(rows)
+
+
+# --------------------------------------------------------------------------------------
+# Transform dispatch
+# --------------------------------------------------------------------------------------
+
+def sequence_forward(x, xform: str, levels: int, grid_h: int = 0, grid_w: int = 0, dtype=np.float32):
+    """T = L X for one sequence x[s, ...]."""
+    if xform == "identity":
+        return np.array(x, dtype=dtype, copy=True)
+    if xform == "haar1d":
+        return haar1d_forward(x, levels, dtype)
+    if xform == "haar2d":
+        return haar2d_forward(x, grid_h, grid_w, levels, dtype)
+    raise ValueError(f"unknown transform {xform!r}")
+
+
+def sequence_inverse(t, xform: str, levels: int, grid_h: int = 0, grid_w: int = 0, dtype=np.float32):
+    """X = L^-1 T for one sequence t[s, ...]."""
+    if xform == "identity":
+        return np.array(t, dtype=dtype, copy=True)
+    if xform == "haar1d":
+        return haar1d_inverse(t, levels, dtype)
+    if xform == "haar2d":
+        return haar2d_inverse(t, grid_h, grid_w, levels, dtype)
+    raise ValueError(f"unknown transform {xform!r}")
+
+
+# --------------------------------------------------------------------------------------
+# Quantizer (Background, Eq. 1, symmetric absmax specialisation) and mixed precision
+# --------------------------------------------------------------------------------------
+
+def qmax_of(bits: int) -> int:
+    return (1 << (bits - 1)) - 1
+
+
+def token_bits(seq_len: int, k_hi: int, bits_hi: int = 8, bits_lo: int = 4) -> np.ndarray:
+    """b_i: bits_hi for the first k transformed tokens, bits_lo for the rest."""
+    b = np.full(seq_len, bits_lo, dtype=np.int32)
+    b[:k_hi] = bits_hi
+    return b
+
+
+def effective_bits(seq_len: int, k_hi: int, bits_hi: int = 8, bits_lo: int = 4) -> float:
+    """Average activation bit width of the two-level allocation."""
+    return (bits_hi * k_hi + bits_lo * (seq_len - k_hi)) / seq_len
+
+
+def quantize_tokens(T: np.ndarray, bits: np.ndarray, dtype=np.float32) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-token symmetric quantization of T[s, d] with bits[s].
+
+    a_i = max_j |T_ij|;  scale_i = a_i / qmax_i;  inv_i = qmax_i / a_i (two separate divisions);
+    code_ij = clamp(rne(T_ij * inv_i), -qmax_i, qmax_i).  Zero rows: scale = inv = 0.
+    Returns (codes int8 [s, d], scale [s]).
+    """
+    T = np.asarray(T, dtype=dtype)
+    ft = np.dtype(dtype).type
+    a = np.max(np.abs(T), axis=1)
+    qm = np.array([qmax_of(int(b)) for b in bits], dtype=dtype)
+    nz = a > 0
+    scale = np.zeros_like(a)
+    inv = np.zeros_like(a)
+    scale[nz] = a[nz] / qm[nz]
+    inv[nz] = qm[nz] / a[nz]
+    r = np.rint(T * inv[:, None])          # np.rint rounds half to even
+    r = np.minimum(np.maximum(r, -qm[:, None]), qm[:, None])
+    assert scale.dtype == np.dtype(dtype) and r.dtype == np.dtype(dtype) and ft is not None
+    return r.astype(np.int8), scale
+
+
+def dequantize_tokens(codes: np.ndarray, scale: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """Q^-1: code * scale."""
+    return codes.astype(dtype) * np.asarray(scale, dtype=dtype)[:, None]
+
+
+def quantize_weight(W: np.ndarray, bits_w: int = 4, dtype=np.float32) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-output-channel symmetric round-to-nearest quantization of W[d_in, d_out].
+
+    Returns (codes int8 [d_in, d_out], sw [d_out]).
+    """
+    codes_t, sw = quantize_tokens(np.ascontiguousarray(np.asarray(W, dtype=dtype).T),
+                                  np.full(W.shape[1], bits_w, dtype=np.int32), dtype)
+    return np.ascontiguousarray(codes_t.T), sw
+
+
+# --------------------------------------------------------------------------------------
+# Integer GEMM
+# --------------------------------------------------------------------------------------
+
+def int_gemm(q: np.ndarray, qw: np.ndarray) -> np.ndarray:
+    """acc[m, n] = sum_k q[m, k] * qw[k, n], exact, returned as int32.
+
+    Evaluated with the fp64 matrix product: every partial sum is an integer below 2^53 in
+    magnitude, so each fp64 operation is exact whatever the summation order.  The result is
+    checked to fit 24 bits, which the fp32 dequantization relies on."""
+    K = q.shape[1]
+    bound = float(K) * float(np.max(np.abs(q), initial=0)) * float(np.max(np.abs(qw), initial=0))
+    assert bound < 2.0 ** 53
+    acc = q.astype(np.float64) @ qw.astype(np.float64)
+    assert np.max(np.abs(acc), initial=0.0) < 2.0 ** 24, "accumulator exceeds the exact fp32 integer range"
+    out = acc.astype(np.int64)
+    assert np.array_equal(out.astype(np.float64), acc)
+    return out.astype(np.int32)
+
+
+# --------------------------------------------------------------------------------------
+# bf16 rounding of the output (round-to-nearest-even on the fp32 bit pattern)
+# --------------------------------------------------------------------------------------
+
+def round_to_bf16(y: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest bf16 value (ties to even), returned as fp32."""
+    u = np.ascontiguousarray(y, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return (r.astype(np.uint32) << np.uint32(16)).view(np.float32).reshape(np.shape(y))
+
+
+# --------------------------------------------------------------------------------------
+# The whole layer
+# --------------------------------------------------------------------------------------
+
+def quantize_activation(X: np.ndarray, xform: str, levels: int, k_hi: int, bits_hi: int = 8,
+                        bits_lo: int = 4, grid_h: int = 0, grid_w: int = 0,
+                        dtype=np.float32) -> Dict[str, np.ndarray]:
+    """Steps 1-2 of the algorithm for X[batch, s, d]: T = L X per sequence, then per-token
+    mixed-precision codes and scales, all in STaMP order."""
+    B, s, d = X.shape
+    bits = token_bits(s, k_hi, bits_hi, bits_lo)
+    T = np.empty((B, s, d), dtype=dtype)
+    codes = np.empty((B, s, d), dtype=np.int8)
+    scales = np.empty((B, s), dtype=dtype)
+    for b in range(B):
+        T[b] = sequence_forward(X[b], xform, levels, grid_h, grid_w, dtype)
+        codes[b], scales[b] = quantize_tokens(T[b], bits, dtype)
+    return {"T": T, "codes": codes, "scales": scales, "bits": bits}
+
+
+def linear_from_codes(codes: np.ndarray, scales: np.ndarray, qw: np.ndarray, sw: np.ndarray,
+                      xform: str, levels: int, grid_h: int = 0, grid_w: int = 0,
+                      bias: Optional[np.ndarray] = None, dtype=np.float32) -> Dict[str, np.ndarray]:
+    """Steps 3-5: integer GEMM, dequantization Y' = (float(acc) * scale_m) * sw_n, inverse
+    transform per sequence and output column, bias."""
+    B, s, d = codes.shape
+    N = qw.shape[1]
+    acc = np.empty((B, s, N), dtype=np.int32)
+    Yt = np.empty((B, s, N), dtype=dtype)
+    Y = np.empty((B, s, N), dtype=dtype)
+    sw = np.asarray(sw, dtype=dtype)
+    for b in range(B):
+        acc[b] = int_gemm(codes[b], qw)
+        Yt[b] = (acc[b].astype(dtype) * np.asarray(scales[b], dtype=dtype)[:, None]) * sw[None, :]
+        Y[b] = sequence_inverse(Yt[b], xform, levels, grid_h, grid_w, dtype)
+    if bias is not None:
+        Y = Y + np.asarray(bias, dtype=dtype)[None, None, :]
+    return {"acc": acc, "Yt": Yt, "Y": Y}
+
+
+def stamp_linear_forward(X: np.ndarray, W: np.ndarray, xform: str, levels: int, k_hi: int,
+                         bits_hi: int = 8, bits_lo: int = 4, bits_w: int = 4, grid_h: int = 0,
+                         grid_w: int = 0, bias: Optional[np.ndarray] = None,
+                         dtype=np.float32) -> Dict[str, np.ndarray]:
+    """Algorithm "STaMP Linear" end to end for X[batch, s, d_in], W[d_in, d_out]."""
+    qa = quantize_activation(X, xform, levels, k_hi, bits_hi, bits_lo, grid_h, grid_w, dtype)
+    qw, sw = quantize_weight(W, bits_w, dtype)
+    out = linear_from_codes(qa["codes"], qa["scales"], qw, sw, xform, levels, grid_h, grid_w, bias, dtype)
+    out.update(qa)
+    out.update({"qw": qw, "sw": sw})
+    return out
+
+
+def sqnr_db(ref: np.ndarray, approx: np.ndarray) -> float:
+    """10 log10(||ref||^2 / ||ref - approx||^2) (Experiments, set-up paragraph)."""
+    ref = np.asarray(ref, dtype=np.float64)
+    err = ref - np.asarray(approx, dtype=np.float64)
+    den = float(np.sum(err * err))
+    if den == 0.0:
+        return math.inf
+    return 10.0 * math.log10(float(np.sum(ref * ref)) / den)
