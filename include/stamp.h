@@ -1,0 +1,156 @@
+/*
+ * stamp.h - C ABI of the MI355X (gfx950) STaMP quantized linear layer.
+ *
+ * STaMP (Sequence Transform and Mixed Precision, arXiv 2510.26771) wraps a linear layer as
+ *
+ *     Y = L^-1( Q(L X) W ) + 1 bias^T            (section "Method", commutation identity;
+ *                                                  Algorithm "STaMP Linear")
+ *
+ * where L is an orthogonal transform along the sequence (token) dimension (here the Haar DWT of
+ * section "Efficient Energy Concentration", 1-D over a token stream or 2-D over an image-token
+ * grid), Q quantizes every transformed token with its own scale (Background, Eq. 1) at 8 bits
+ * for the first k tokens and 4 bits for the rest (section "Optimal bit allocation"), and W is
+ * quantized per output channel.
+ *
+ * General conventions
+ *   - Every pointer whose name ends in _dev is DEVICE memory owned by the caller; _host is host
+ *     memory.  The library never frees or keeps caller pointers beyond the call, except that
+ *     stamp_plan_create reads W and bias asynchronously on the given stream (keep them alive
+ *     until that stream has drained).
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  All compute
+ *     calls are asynchronous on that stream and never synchronize it.
+ *   - No call allocates device memory except stamp_plan_create (the plan owns its quantized
+ *     weights until stamp_plan_destroy).  Scratch memory comes in through `workspace_dev`.
+ *   - Every argument error is detected on the host BEFORE anything is launched and reported
+ *     through the return code; nothing is launched in that case.  A plan is immutable and may be
+ *     used from several streams at once with distinct workspaces.
+ *   - Non-finite inputs give unspecified numbers but never a fault.
+ *
+ * Tensor layouts
+ *   X        [batch, seq_len, d_in]  row-major, d_in contiguous, dtype x_dtype.
+ *   W        [d_in, d_out] row-major (w_is_out_by_in = 0) or [d_out, d_in] (= 1), dtype w_dtype.
+ *   Y        [batch, seq_len, d_out] row-major, dtype y_dtype, original token order.
+ *   Transformed tokens ("coefficients") are numbered in STaMP order: lowest frequencies first.
+ *     1-D, J levels: slot 0 = sum/sqrt(s); slot p >= 1 with m = floor(log2 p) is the Haar wavelet
+ *     of level J-m at position p-2^m (+ on its first half, - on its second half).
+ *     2-D, J levels over a grid_h x grid_w grid, token t = r*grid_w + c: the final low-low block
+ *     row-major, then for level J..1 the bands [difference along width, difference along height,
+ *     diagonal], each row-major.
+ *   The quantized activation is stored in the plan's PHYSICAL row order (a permutation of STaMP
+ *   order chosen so that one GEMM tile holds whole Haar sub-trees); stamp_plan_row_of_coeff
+ *   returns it.  With R = seq_len / k_hi and physical row r of sequence b:
+ *     scales  [batch, seq_len] float: scale of the coefficient at physical row r.
+ *     q_hi    [batch, k_hi, d_in] int8: the 8-bit tokens; STaMP slot p < k_hi is row p of q_hi
+ *             (its physical row is p*R).
+ *     q_lo    [batch, seq_len, d_in/2] bytes: the 4-bit tokens at their physical row; two's
+ *             complement nibbles, low nibble = even channel.  Rows r with r % R == 0 (the rows
+ *             whose coefficient lives in q_hi) are never written nor read.
+ */
+#ifndef STAMP_H_
+#define STAMP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct stamp_plan stamp_plan_t; /* opaque, library-owned */
+
+typedef enum {
+  STAMP_OK = 0,
+  STAMP_ERR_NULL = 1,        /* a required pointer is NULL */
+  STAMP_ERR_SHAPE = 2,       /* sizes inconsistent: seq_len not 2^J, grid_h*grid_w != seq_len, k_hi > seq_len, ... */
+  STAMP_ERR_UNSUPPORTED = 3, /* a valid STaMP setting this GPU library does not implement */
+  STAMP_ERR_WORKSPACE = 4,   /* workspace_bytes < stamp_plan_workspace_bytes(plan) or workspace NULL/misaligned */
+  STAMP_ERR_ALLOC = 5,       /* device allocation failed in stamp_plan_create */
+  STAMP_ERR_DEVICE = 6       /* a HIP runtime call failed (no GPU, launch error) */
+} stamp_status_t;
+
+typedef enum { STAMP_F32 = 0, STAMP_BF16 = 1 } stamp_dtype_t;
+typedef enum { STAMP_L_IDENTITY = 0, STAMP_L_HAAR1D = 1, STAMP_L_HAAR2D = 2 } stamp_xform_t;
+
+/* Everything the paper's statement of the layer leaves to the user: the shape of X (Background),
+ * the transform L and its depth (section "Efficient Energy Concentration"), the number k of
+ * high-precision tokens and the two bit widths (section "Optimal bit allocation"), and the
+ * weight bit width. */
+typedef struct {
+  int32_t batch, seq_len, d_in, d_out;
+  int32_t xform;            /* stamp_xform_t */
+  int32_t levels;           /* Haar levels J; must equal log2(seq_len) (2-D: log2(grid side)) */
+  int32_t grid_h, grid_w;   /* HAAR2D only; grid_h == grid_w, grid_h*grid_w == seq_len */
+  int32_t k_hi;             /* tokens kept at bits_hi; a power of two (2-D: a power of four) */
+  int32_t bits_hi, bits_lo, bits_w; /* 8, 4, 4 */
+  int32_t x_dtype, y_dtype, w_dtype; /* stamp_dtype_t; w_dtype must be STAMP_F32 */
+  int32_t w_is_out_by_in;   /* 0: W[d_in, d_out];  1: W[d_out, d_in] (the algorithm's X W^T) */
+} stamp_plan_desc_t;
+
+/* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):
+ *   xform HAAR1D with seq_len/k_hi in {8,16,32,64,128}, or HAAR2D with a square grid and
+ *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels = full depth; bits 8/4/4;
+ *   d_in a multiple of 32 and at most 8192; k_hi <= 256. */
+
+/* Validates desc, quantizes W per output channel (absmax/7, round to nearest even; section
+ * "Large Language Models", Set-up: round-to-nearest weights, one scale per output channel) into
+ * the layout the GEMM kernel reads, copies bias (fp32 [d_out], may be NULL).
+ * W_dev, bias_dev: device, read on hip_stream.  *out receives the plan. */
+stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_dev,
+                                 const float* bias_dev_or_null, void* hip_stream,
+                                 stamp_plan_t** out);
+
+/* Frees the plan's device memory.  The caller must have drained every stream using it. */
+stamp_status_t stamp_plan_destroy(stamp_plan_t* plan);
+
+/* Bytes of workspace any entry point below may need (256-byte aligned pointer expected). */
+size_t stamp_plan_workspace_bytes(const stamp_plan_t* plan);
+
+/* host_out[p] = physical row (0 <= row < seq_len) of STaMP slot p; a permutation. */
+stamp_status_t stamp_plan_row_of_coeff(const stamp_plan_t* plan, int32_t* host_out);
+
+/* Steps 1-2 of Algorithm "STaMP Linear": T = L X along the tokens, then per-token symmetric
+ * quantization of Eq. 1: scale_i = max_j|T_ij| / qmax_i, code = rne(T_ij * (qmax_i / max)),
+ * qmax = 127 for the first k_hi STaMP slots and 7 for the rest.  Outputs in the layouts above.
+ * One quantized activation may feed several linears (the paper's q/k/v fan-out). */
+stamp_status_t stamp_quantize_act(const stamp_plan_t* plan, const void* X_dev, int8_t* q_hi_dev,
+                                  uint8_t* q_lo_dev, float* scales_dev, void* workspace_dev,
+                                  size_t workspace_bytes, void* hip_stream);
+
+/* The whole layer, Algorithm "STaMP Linear": quantize_act, integer GEMM on int8 MFMA with i32
+ * accumulation, dequantization, inverse transform, bias, store Y. */
+stamp_status_t stamp_linear_forward(const stamp_plan_t* plan, const void* X_dev, void* Y_dev,
+                                    void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Steps 3-5 from an already quantized activation (buffers as written by stamp_quantize_act). */
+stamp_status_t stamp_linear_forward_q(const stamp_plan_t* plan, const int8_t* q_hi_dev,
+                                      const uint8_t* q_lo_dev, const float* scales_dev, void* Y_dev,
+                                      void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Step 4 alone: Y = L^-1 Yt for Yt_dev [batch, seq_len, n_cols] fp32 in STaMP order; adds the
+ * plan's bias when n_cols == d_out and a bias was given; Y_dev [batch, seq_len, n_cols] y_dtype. */
+stamp_status_t stamp_inverse(const stamp_plan_t* plan, const float* Yt_dev, int32_t n_cols,
+                             void* Y_dev, void* workspace_dev, size_t workspace_bytes,
+                             void* hip_stream);
+
+/* ---- parity / debug exports (not on the timed path) ---- */
+
+/* Step 3 alone: acc_dev[b*seq_len + p, n] = sum_c code[b, p, c] * qW[c, n], int32, rows in STaMP
+ * order. */
+stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* plan, const int8_t* q_hi_dev,
+                                    const uint8_t* q_lo_dev, int32_t* acc_dev, void* hip_stream);
+
+/* The plan's weight codes [d_in, d_out] int8 (values -7..7) and scales [d_out], copied to host.
+ * Synchronizes the device. */
+stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* plan, int8_t* qW_host, float* sw_host);
+
+/* Selects the implementation of steps 3-5: 0 = GEMM with the dequantization and the in-block
+ * inverse transform fused into its epilogue (default where the shape allows it), 1 = GEMM writing
+ * dequantized fp32 rows to the workspace followed by a separate inverse kernel. */
+stamp_status_t stamp_plan_set_unfused(stamp_plan_t* plan, int32_t unfused);
+
+const char* stamp_status_string(stamp_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STAMP_H_ */

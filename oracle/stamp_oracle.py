@@ -32,11 +32,18 @@ Readings of the paper where it is silent (each also listed in the design documen
 * Haar matrix: orthonormal (Theorem 1 needs an orthogonal L), detail = even minus odd,
   approximations first ("pushes the energy in the first half"), Mallat ordering: after J levels
   slot 0.. hold the coarsest approximations, then the details from coarse to fine.
-* One 1-D level: a = (x[2i] + x[2i+1]) * C, d = (x[2i] - x[2i+1]) * C with C = fl(1/sqrt 2).
+* Operation order of the transform (the paper gives none): a coefficient is the inner product
+  with its basis function, +-2^(-l/2) on the wavelet's two halves, so it is evaluated as
+  (sum of the first half - sum of the second half) * 2^(-l/2): the sums are built level by
+  level as plain pairwise sums A = x[2i] + x[2i+1], D = x[2i] - x[2i+1] (no scaling inside the
+  recursion), and each finished coefficient is multiplied ONCE by norm(l) = fl(2^(-l/2)) of its
+  level (exact for even l).  The inverse multiplies every coefficient by the same norm(l) first
+  and then runs plain butterflies x[2i] = a + d, x[2i+1] = a - d.
 * 2-D: pyramid (recursion on the low-low quarter, "one quarter for 2D signal"); one 2-D level
-  on a 2x2 cell [[p, q], [u, v]] is t0=p+q, t1=p-q, t2=u+v, t3=u-v, LL=(t0+t2)/2, W=(t1+t3)/2,
-  H=(t0-t2)/2, D=(t1-t3)/2.  STaMP order in 2-D: final LL block row-major, then per level from
-  coarse to fine the blocks [W (top-right), H (bottom-left), D (bottom-right)], each row-major.
+  on a 2x2 cell [[p, q], [u, v]] is t0=p+q, t1=p-q, t2=u+v, t3=u-v, LL=t0+t2, W=t1+t3,
+  H=t0-t2, D=t1-t3, and a finished level-l coefficient is multiplied once by 2^(-l) (exact).
+  STaMP order in 2-D: final LL block row-major, then per level from coarse to fine the blocks
+  [W (top-right), H (bottom-left), D (bottom-right)], each row-major.
 * Quantizer: the benchmark configurations fix the symmetric specialisation of Eq. 1:
   qmax = 2^(b-1) - 1, scale = absmax / qmax (range-based, no clipping, as in the Background
   section), code = clamp(rne(x * (qmax / absmax)), -qmax, qmax).  A zero row gets scale 0 and
@@ -55,13 +62,23 @@ from typing import Dict, Optional, Tuple
 
 import numpy as np
 
-# fp32 nearest to 1/sqrt(2) (bit pattern 0x3F3504F3); in fp64 the fp64 nearest.
-_INV_SQRT2_F32 = np.float32(0.70710678118654752440)
-_INV_SQRT2_F64 = np.float64(0.70710678118654752440)
+
+def haar_norm(level: int, dtype=np.float32):
+    """norm(l) = 2^(-l/2) rounded to dtype: a power of two for even l, else a power of two times
+    fl(1/sqrt 2) (fp32: bit pattern 0x3F3504F3 scaled)."""
+    ft = np.dtype(dtype).type
+    if level % 2 == 0:
+        return ft(2.0 ** (-(level // 2)))
+    return ft(ft(0.70710678118654752440) * ft(2.0 ** (-((level - 1) // 2))))
 
 
-def _c(dtype):
-    return _INV_SQRT2_F32 if np.dtype(dtype) == np.float32 else _INV_SQRT2_F64
+def _norms_1d(s: int, levels: int, dtype) -> np.ndarray:
+    """Per-slot normalisation of the J-level 1-D transform in STaMP order."""
+    nrm = np.empty(s, dtype=dtype)
+    nrm[0:s >> levels] = haar_norm(levels, dtype)
+    for l in range(levels, 0, -1):
+        nrm[s >> l:s >> (l - 1)] = haar_norm(l, dtype)
+    return nrm
 
 
 def _is_pow2(n: int) -> bool:
@@ -75,38 +92,41 @@ def _is_pow2(n: int) -> bool:
 def haar1d_forward(x: np.ndarray, levels: int, dtype=np.float32) -> np.ndarray:
     """J-level orthonormal Haar DWT of x[s, ...] along axis 0, result in STaMP order.
 
-    Level l = 1..J acts on the first n = s / 2^(l-1) slots (the current approximation):
-    the n/2 sums go to slots [0, n/2), the n/2 differences to [n/2, n); slots >= n keep the
-    details of the earlier (finer) levels.
+    Level l = 1..J acts on the first n = s / 2^(l-1) slots (the current block sums):
+    the n/2 pair sums go to slots [0, n/2), the n/2 pair differences to [n/2, n); slots >= n
+    keep the differences of the earlier (finer) levels.  Each slot is then multiplied once by
+    the norm of its level.
     """
     t = np.array(x, dtype=dtype, copy=True)
     s = t.shape[0]
     if not _is_pow2(s) or levels < 0 or (1 << levels) > s:
         raise ValueError("seq_len must be a power of two and levels <= log2(seq_len)")
-    C = _c(dtype)
     n = s
     for _ in range(levels):
         even = t[0:n:2].copy()
         odd = t[1:n:2].copy()
-        t[0:n // 2] = (even + odd) * C
-        t[n // 2:n] = (even - odd) * C
+        t[0:n // 2] = even + odd
+        t[n // 2:n] = even - odd
         n //= 2
-    return t
+    nrm = _norms_1d(s, levels, dtype)
+    return t * nrm.reshape((s,) + (1,) * (t.ndim - 1))
 
 
 def haar1d_inverse(t: np.ndarray, levels: int, dtype=np.float32) -> np.ndarray:
-    """Inverse of haar1d_forward: levels J..1, x[2i] = (a+d)*C, x[2i+1] = (a-d)*C."""
+    """Inverse (= transpose) of haar1d_forward: scale every slot by the norm of its level, then
+    levels J..1 of plain butterflies x[2i] = a + d, x[2i+1] = a - d."""
     x = np.array(t, dtype=dtype, copy=True)
     s = x.shape[0]
     if not _is_pow2(s) or levels < 0 or (1 << levels) > s:
         raise ValueError("seq_len must be a power of two and levels <= log2(seq_len)")
-    C = _c(dtype)
+    nrm = _norms_1d(s, levels, dtype)
+    x = x * nrm.reshape((s,) + (1,) * (x.ndim - 1))
     n = s >> (levels - 1) if levels > 0 else s
     for _ in range(levels):
         a = x[0:n // 2].copy()
         d = x[n // 2:n].copy()
-        x[0:n:2] = (a + d) * C
-        x[1:n:2] = (a - d) * C
+        x[0:n:2] = a + d
+        x[1:n:2] = a - d
         n *= 2
     return x
 
@@ -137,6 +157,19 @@ def haar1d_matrix(s: int, levels: int) -> np.ndarray:
 # 2-D Haar pyramid over an H x W token grid, token t = r * W + c.
 # --------------------------------------------------------------------------------------
 
+def _norms_2d_grid(H: int, W: int, levels: int, dtype) -> np.ndarray:
+    """Per-position normalisation 2^(-l) of the Mallat coefficient grid (level-l bands and, for
+    the remaining low-low block, l = J).  Exact powers of two."""
+    ft = np.dtype(dtype).type
+    nrm = np.empty((H, W), dtype=dtype)
+    for l in range(1, levels + 1):
+        h, w = H >> (l - 1), W >> (l - 1)
+        nrm[0:h, 0:w] = ft(2.0 ** (-l))     # overwritten below for the part that recurses further
+    if levels == 0:
+        nrm[:, :] = ft(1.0)
+    return nrm
+
+
 def haar2d_forward_grid(x: np.ndarray, grid_h: int, grid_w: int, levels: int, dtype=np.float32) -> np.ndarray:
     """J-level 2-D Haar pyramid; returns the coefficient grid [H, W, ...] (Mallat layout:
     LL top-left, width-difference band top-right, height-difference band bottom-left,
@@ -145,7 +178,6 @@ def haar2d_forward_grid(x: np.ndarray, grid_h: int, grid_w: int, levels: int, dt
     if not (_is_pow2(H) and _is_pow2(W)) or levels < 0 or (1 << levels) > min(H, W):
         raise ValueError("grid sides must be powers of two and levels <= log2(min side)")
     g = np.array(x, dtype=dtype, copy=True).reshape((H, W) + x.shape[1:])
-    half = np.dtype(dtype).type(0.5)
     h, w = H, W
     for _ in range(levels):
         p = g[0:h:2, 0:w:2].copy()
@@ -156,20 +188,20 @@ def haar2d_forward_grid(x: np.ndarray, grid_h: int, grid_w: int, levels: int, dt
         t1 = p - q
         t2 = u + v
         t3 = u - v
-        g[0:h // 2, 0:w // 2] = (t0 + t2) * half
-        g[0:h // 2, w // 2:w] = (t1 + t3) * half
-        g[h // 2:h, 0:w // 2] = (t0 - t2) * half
-        g[h // 2:h, w // 2:w] = (t1 - t3) * half
+        g[0:h // 2, 0:w // 2] = t0 + t2
+        g[0:h // 2, w // 2:w] = t1 + t3
+        g[h // 2:h, 0:w // 2] = t0 - t2
+        g[h // 2:h, w // 2:w] = t1 - t3
         h //= 2
         w //= 2
-    return g
+    return g * _norms_2d_grid(H, W, levels, dtype).reshape((H, W) + (1,) * (g.ndim - 2))
 
 
 def haar2d_inverse_grid(g_in: np.ndarray, levels: int, dtype=np.float32) -> np.ndarray:
     """Inverse of haar2d_forward_grid on a coefficient grid [H, W, ...]."""
     g = np.array(g_in, dtype=dtype, copy=True)
     H, W = g.shape[0], g.shape[1]
-    half = np.dtype(dtype).type(0.5)
+    g = g * _norms_2d_grid(H, W, levels, dtype).reshape((H, W) + (1,) * (g.ndim - 2))
     h, w = (H >> (levels - 1), W >> (levels - 1)) if levels > 0 else (H, W)
     for _ in range(levels):
         cLL = g[0:h // 2, 0:w // 2].copy()
@@ -180,10 +212,10 @@ def haar2d_inverse_grid(g_in: np.ndarray, levels: int, dtype=np.float32) -> np.n
         t2 = cLL - cH
         t1 = cW + cD
         t3 = cW - cD
-        g[0:h:2, 0:w:2] = (t0 + t1) * half
-        g[0:h:2, 1:w:2] = (t0 - t1) * half
-        g[1:h:2, 0:w:2] = (t2 + t3) * half
-        g[1:h:2, 1:w:2] = (t2 - t3) * half
+        g[0:h:2, 0:w:2] = t0 + t1
+        g[0:h:2, 1:w:2] = t0 - t1
+        g[1:h:2, 0:w:2] = t2 + t3
+        g[1:h:2, 1:w:2] = t2 - t3
         h *= 2
         w *= 2
     return g
