@@ -1,0 +1,514 @@
+// Activation path of the STaMP linear layer on gfx950: T = L X along the tokens (Haar DWT, paper
+// section "Efficient Energy Concentration"), per-token absmax scale and rounding to 8- or 4-bit
+// codes (Background Eq. 1 in its symmetric form; two-level allocation of section "Optimal bit
+// allocation").  X is read from HBM once and the transformed activation never goes to HBM.
+//
+// Floating-point contract (decides the integer codes, so it is fixed): every coefficient is the
+// difference (or sum) of two block sums built by plain pairwise fp32 adds, multiplied once by
+// norm(l) = fl(2^(-l/2)); absmax a over the row; scale = a / qmax; inv = qmax / a (IEEE
+// divisions); code = rne(fl(T * inv)).  This file is compiled with -ffp-contract=off.
+//
+// Kernels:
+//   k_bottom1d / k_bottom2d  one workgroup per (sequence, block of R tokens), all d_in channels;
+//                            each thread owns 8 channels for every token of the block, so the
+//                            butterflies stay in registers; only the per-row absmax crosses lanes
+//                            (DPP inside a wave, LDS atomic max across waves).  Emits the R-1
+//                            4-bit rows of the block and the block sum (fp32, to scratch).
+//   k_top                    the remaining levels over the k_hi block sums, in LDS, per channel
+//                            slice; writes the normalised 8-bit-row coefficients to scratch and
+//                            their per-row absmax with a global atomic max.
+//   k_quant_hi               rounds those k_hi rows to int8.
+#include <utility>
+
+#include "stamp_internal.h"
+
+namespace {
+
+constexpr float kInvSqrt2 = 0.70710678118654752440f;  // 0x3F3504F3
+constexpr float kMagicLo = 12582920.0f;               // 1.5 * 2^23 + 8: fp32 add rounds to integer (RNE), low 4 bits = code + 8
+constexpr uint32_t kMagicLoBits = 0x4B400000u;        // bit pattern of 1.5 * 2^23
+constexpr uint32_t kPackBias = kMagicLoBits * 0x11111111u;  // sum over 8 nibble positions of the pattern's high bits (mod 2^32)
+
+__device__ __forceinline__ float haar_norm(int level) {
+  // 2^(-level/2): a power of two for even levels, fl(1/sqrt 2) times a power of two for odd ones
+  return ldexpf((level & 1) ? kInvSqrt2 : 1.0f, -(level >> 1));
+}
+
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// max over the 64 lanes of a non-negative float's bit pattern; result is wave-uniform
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  int x = (int)v;
+  int y;
+  y = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
+  x = max(x, y);
+  y = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+  x = max(x, y);
+  y = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);  // row_half_mirror
+  x = max(x, y);
+  y = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);  // row_mirror
+  x = max(x, y);
+  int a = __builtin_amdgcn_readlane(x, 0);
+  int b = __builtin_amdgcn_readlane(x, 16);
+  int c = __builtin_amdgcn_readlane(x, 32);
+  int d = __builtin_amdgcn_readlane(x, 48);
+  return (uint32_t)max(max(a, b), max(c, d));
+}
+
+__device__ __forceinline__ uint32_t absbits(float f) { return __float_as_uint(f) & 0x7FFFFFFFu; }
+
+__device__ __forceinline__ uint32_t row_absmax_bits(const float (&v)[8]) {
+  float m = fmaxf(fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3]))),
+                  fmaxf(fmaxf(fabsf(v[4]), fabsf(v[5])), fmaxf(fabsf(v[6]), fabsf(v[7]))));
+  return __float_as_uint(m);
+}
+
+// 8 codes -> one dword of two's complement nibbles (channel c in nibble c).
+// p[c] = T * inv, |p| <= 7 (+1 ulp).  fl(p + magic) has rne(p) + 8 in its low 4 bits.
+__device__ __forceinline__ uint32_t pack8_int4(const float (&p)[8]) {
+  uint32_t acc = __float_as_uint(__fadd_rn(p[7], kMagicLo));
+#pragma unroll
+  for (int c = 6; c >= 0; --c) acc = (acc << 4) + __float_as_uint(__fadd_rn(p[c], kMagicLo));
+  return (acc - kPackBias) ^ 0x88888888u;
+}
+
+__device__ __forceinline__ void load8(const void* X, size_t elem_off, bool bf16, bool active, float (&v)[8]) {
+  if (!active) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) v[c] = 0.0f;
+    return;
+  }
+  if (bf16) {
+    const uint4 w = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(X) + elem_off);
+    v[0] = bf16lo(w.x); v[1] = bf16hi(w.x); v[2] = bf16lo(w.y); v[3] = bf16hi(w.y);
+    v[4] = bf16lo(w.z); v[5] = bf16hi(w.z); v[6] = bf16lo(w.w); v[7] = bf16hi(w.w);
+  } else {
+    const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(X) + elem_off);
+    const float4 a = p[0], b = p[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+}
+
+constexpr int trailing_ones(int x) { int n = 0; while (x & 1) { ++n; x >>= 1; } return n; }
+constexpr int cmin(int a, int b) { return a < b ? a : b; }
+
+// Shared tail of one streaming step: NR finished rows (unnormalised values rowv[r][0..7], level
+// and in-block position given per row) are reduced over the workgroup, scaled, rounded, packed and
+// stored.  `step` numbers the steps of this workgroup (rotating LDS buffers).
+struct RowMeta { int level; int e; };
+
+template <int NR, bool IS2D, typename MetaFn>
+__device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[32],
+                                           uint8_t* q_lo_blk /* row e=0 of this block */, float* scales_blk,
+                                           int d, int c0, bool active, int tid) {
+  const int lane = tid & 63;
+  const int buf = step % 3;
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const uint32_t m = wave_max_u32(row_absmax_bits(rowv[r]));
+    if (lane == 0) atomicMax(&s_max[buf][r], m);
+  }
+  __syncthreads();
+  if (tid < 32) s_max[(step + 2) % 3][tid] = 0u;
+  // lane r prepares row r: a = fl(absmaxU * norm); scale = a / 7; inv = 7 / a
+  float mul_lane = 0.0f;
+  {
+    const int r = lane < NR ? lane : 0;
+    const RowMeta rm = meta(r);
+    const float amaxU = __uint_as_float(s_max[buf][r]);
+    const float nrm = IS2D ? ldexpf(1.0f, -rm.level) : haar_norm(rm.level);
+    const float a = __fmul_rn(amaxU, nrm);
+    float scale = 0.0f, inv = 0.0f;
+    if (a > 0.0f) {
+      scale = __fdiv_rn(a, 7.0f);
+      inv = __fdiv_rn(7.0f, a);
+    }
+    // even 1-D levels and all 2-D levels have a power-of-two norm: fold it into the multiplier
+    const bool fold = IS2D || ((rm.level & 1) == 0);
+    mul_lane = fold ? __fmul_rn(inv, nrm) : inv;
+    if (tid < NR) scales_blk[rm.e] = scale;
+  }
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const RowMeta rm = meta(r);  // r is a compile-time constant here
+    const float mul = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mul_lane), r));
+    float p[8];
+    const bool fold = IS2D || ((rm.level & 1) == 0);
+    if (fold) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) p[c] = __fmul_rn(rowv[r][c], mul);
+    } else {
+      const float nrm = haar_norm(rm.level);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) p[c] = __fmul_rn(__fmul_rn(rowv[r][c], nrm), mul);
+    }
+    const uint32_t w = pack8_int4(p);
+    if (active) *reinterpret_cast<uint32_t*>(q_lo_blk + (size_t)rm.e * (size_t)(d >> 1) + (c0 >> 1)) = w;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// 1-D bottom kernel
+// ------------------------------------------------------------------------------------------
+template <int RLOG, int L, int IDX, int SLOT, int NP, int MAXR>
+__device__ __forceinline__ void chain1d(float (&cur)[8], float (&pend)[NP][8], float (&rowv)[MAXR][8],
+                                        float (&top)[8], bool& have_top) {
+  if constexpr (L == RLOG) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) top[c] = cur[c];
+    have_top = true;
+  } else if constexpr ((IDX & 1) != 0) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const float a = __fadd_rn(pend[L - 3][c], cur[c]);
+      rowv[SLOT][c] = __fsub_rn(pend[L - 3][c], cur[c]);
+      cur[c] = a;
+    }
+    chain1d<RLOG, L + 1, (IDX >> 1), SLOT + 1, NP, MAXR>(cur, pend, rowv, top, have_top);
+  } else {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pend[L - 3][c] = cur[c];
+  }
+}
+
+template <int RLOG, bool BF16, int IT, int NP>
+__device__ __forceinline__ void step1d(const void* X, size_t blk_elem_off, int d, int c0, bool active, int tid,
+                                       float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[32],
+                                       uint8_t* q_lo_blk, float* scales_blk) {
+  constexpr int R = 1 << RLOG;
+  constexpr int CH = cmin(trailing_ones(IT), RLOG - 3);
+  constexpr int NR = 7 + CH;
+  float rowv[NR][8];
+  float a2[2][8];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    float a1[2][8];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      float x0[8], x1[8];
+      const int t = 8 * IT + 4 * h + 2 * u;
+      load8(X, blk_elem_off + (size_t)t * d, BF16, active, x0);
+      load8(X, blk_elem_off + (size_t)(t + 1) * d, BF16, active, x1);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        a1[u][c] = __fadd_rn(x0[c], x1[c]);
+        rowv[2 * h + u][c] = __fsub_rn(x0[c], x1[c]);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      a2[h][c] = __fadd_rn(a1[0][c], a1[1][c]);
+      rowv[4 + h][c] = __fsub_rn(a1[0][c], a1[1][c]);
+    }
+  }
+  float cur[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    cur[c] = __fadd_rn(a2[0][c], a2[1][c]);
+    rowv[6][c] = __fsub_rn(a2[0][c], a2[1][c]);
+  }
+  bool have_top = false;
+  chain1d<RLOG, 3, IT, 7, NP, NR>(cur, pend, rowv, top, have_top);
+  (void)have_top;
+  auto meta = [](int r) -> RowMeta {
+    RowMeta m;
+    if (r < 4) { m.level = 1; m.e = (R >> 1) + 4 * IT + r; }
+    else if (r < 6) { m.level = 2; m.e = (R >> 2) + 2 * IT + (r - 4); }
+    else if (r == 6) { m.level = 3; m.e = (R >> 3) + IT; }
+    else { m.level = r - 3; m.e = (R >> (r - 3)) + (IT >> (r - 6)); }
+    return m;
+  };
+  flush_rows<NR, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, d, c0, active, tid);
+}
+
+template <int RLOG, bool BF16, int NP, int... ITS>
+__device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const void* X, size_t blk_elem_off, int d,
+                                      int c0, bool active, int tid, float (&pend)[NP][8], float (&top)[8],
+                                      uint32_t (*s_max)[32], uint8_t* q_lo_blk, float* scales_blk) {
+  (step1d<RLOG, BF16, ITS, NP>(X, blk_elem_off, d, c0, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
+}
+
+template <int RLOG, bool BF16>
+__global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
+                                                   float* __restrict__ scales, float* __restrict__ abot,
+                                                   uint32_t* __restrict__ rowmax, int s, int d, int k) {
+  constexpr int R = 1 << RLOG;
+  constexpr int NP = RLOG > 3 ? RLOG - 3 : 1;
+  __shared__ uint32_t s_max[3][32];
+  const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int c0 = tid * 8;
+  const bool active = c0 < d;
+  for (int i = tid; i < 96; i += blockDim.x) (&s_max[0][0])[i] = 0u;
+  if (tid == 0) rowmax[b * k + j] = 0u;
+  __syncthreads();
+  const size_t row0 = (size_t)b * s + (size_t)j * R;
+  float pend[NP][8];
+  float top[8];
+  run1d<RLOG, BF16, NP>(std::make_integer_sequence<int, R / 8>{}, X, row0 * d + c0, d, c0, active, tid, pend, top,
+                        s_max, q_lo + row0 * (size_t)(d >> 1), scales + row0);
+  if (active) {
+    float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
+    o[0] = make_float4(top[0], top[1], top[2], top[3]);
+    o[1] = make_float4(top[4], top[5], top[6], top[7]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// 2-D bottom kernel: block of g x g tokens (g = 2^RLOG, RLOG in {2,3}), streamed in 4x4 sub-blocks
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void cell2d(const float (&p)[8], const float (&q)[8], const float (&u)[8], const float (&v)[8],
+                                       float (&LL)[8], float (&W)[8], float (&H)[8], float (&D)[8]) {
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    const float t0 = __fadd_rn(p[c], q[c]);
+    const float t1 = __fsub_rn(p[c], q[c]);
+    const float t2 = __fadd_rn(u[c], v[c]);
+    const float t3 = __fsub_rn(u[c], v[c]);
+    LL[c] = __fadd_rn(t0, t2);
+    W[c] = __fadd_rn(t1, t3);
+    H[c] = __fsub_rn(t0, t2);
+    D[c] = __fsub_rn(t1, t3);
+  }
+}
+
+template <int RLOG, bool BF16, int SB>
+__device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int gridW, int d, int c0, bool active, int tid,
+                                       float (&pend)[4][8], float (&top)[8], uint32_t (*s_max)[32],
+                                       uint8_t* q_lo_blk, float* scales_blk) {
+  constexpr int g = 1 << RLOG;
+  constexpr int sby = (g == 4) ? 0 : (SB >> 1), sbx = (g == 4) ? 0 : (SB & 1);
+  constexpr bool LAST = (g == 8) && (SB == 3);
+  constexpr int NR = LAST ? 18 : 15;
+  float rowv[NR][8];
+  float ll1[4][8];
+#pragma unroll
+  for (int ci = 0; ci < 4; ++ci) {
+    const int cy = ci >> 1, cx = ci & 1;
+    float t[4][8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int y = 4 * sby + 2 * cy + (q >> 1), x = 4 * sbx + 2 * cx + (q & 1);
+      load8(X, blk_elem_off + ((size_t)y * gridW + x) * d, BF16, active, t[q]);
+    }
+    cell2d(t[0], t[1], t[2], t[3], ll1[ci], rowv[3 * ci + 0], rowv[3 * ci + 1], rowv[3 * ci + 2]);
+  }
+  float ll2[8];
+  cell2d(ll1[0], ll1[1], ll1[2], ll1[3], ll2, rowv[12], rowv[13], rowv[14]);
+  if constexpr (g == 4) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) top[c] = ll2[c];
+  } else if constexpr (LAST) {
+    cell2d(pend[0], pend[1], pend[2], ll2, top, rowv[15], rowv[16], rowv[17]);
+  } else {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pend[SB][c] = ll2[c];
+  }
+  auto meta = [](int r) -> RowMeta {
+    RowMeta m;
+    if (r < 12) {
+      const int ci = r / 3, bd = r - 3 * ci;
+      constexpr int g1 = g >> 1;
+      m.level = 1;
+      m.e = g1 * g1 * (1 + bd) + (2 * sby + (ci >> 1)) * g1 + (2 * sbx + (ci & 1));
+    } else if (r < 15) {
+      constexpr int g2 = g >> 2;
+      m.level = 2;
+      m.e = g2 * g2 * (1 + (r - 12)) + sby * g2 + sbx;
+    } else {
+      m.level = 3;
+      m.e = 1 + (r - 15);
+    }
+    return m;
+  };
+  flush_rows<NR, true>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, d, c0, active, tid);
+}
+
+template <int RLOG, bool BF16, int... SBS>
+__device__ __forceinline__ void run2d(std::integer_sequence<int, SBS...>, const void* X, size_t blk_elem_off, int gridW,
+                                      int d, int c0, bool active, int tid, float (&pend)[4][8], float (&top)[8],
+                                      uint32_t (*s_max)[32], uint8_t* q_lo_blk, float* scales_blk) {
+  (step2d<RLOG, BF16, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
+}
+
+template <int RLOG, bool BF16>
+__global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
+                                                  float* __restrict__ scales, float* __restrict__ abot,
+                                                  uint32_t* __restrict__ rowmax, int s, int d, int G, int gridW) {
+  constexpr int g = 1 << RLOG;
+  constexpr int R = g * g;
+  __shared__ uint32_t s_max[3][32];
+  const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int bi = j / G, bj = j - bi * G;
+  const int c0 = tid * 8;
+  const bool active = c0 < d;
+  const int k = G * G;
+  for (int i = tid; i < 96; i += blockDim.x) (&s_max[0][0])[i] = 0u;
+  if (tid == 0) rowmax[b * k + j] = 0u;
+  __syncthreads();
+  const size_t tok0 = (size_t)b * s + (size_t)(bi * g) * gridW + (size_t)bj * g;  // first token of the block
+  const size_t prow0 = (size_t)b * s + (size_t)j * R;                              // first physical row of the block
+  float pend[4][8];
+  float top[8];
+  run2d<RLOG, BF16>(std::make_integer_sequence<int, (g == 4 ? 1 : 4)>{}, X, tok0 * d + c0, gridW, d, c0, active, tid,
+                    pend, top, s_max, q_lo + prow0 * (size_t)(d >> 1), scales + prow0);
+  if (active) {
+    float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
+    o[0] = make_float4(top[0], top[1], top[2], top[3]);
+    o[1] = make_float4(top[4], top[5], top[6], top[7]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Top levels over the k block sums.  Workgroup = (32-channel slice, sequence); the k x 32 slice
+// sits in LDS and the butterflies run in place (stride 2^l).  Writes normalised coefficients in
+// STaMP order over abot (in place: each workgroup owns its slice) and the row absmax.
+// ------------------------------------------------------------------------------------------
+constexpr int kTopCh = 32;
+
+__global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t* __restrict__ rowmax, int k, int d,
+                                             int is2d, int G, int r_bottom) {
+  extern __shared__ float s_buf[];  // [k][kTopCh + 1]
+  const int b = blockIdx.y, c_base = blockIdx.x * kTopCh, tid = threadIdx.x;
+  const int ch = tid & (kTopCh - 1), grp = tid / kTopCh, ngrp = 256 / kTopCh;
+  const int stride = kTopCh + 1;
+  const bool cact = (c_base + ch) < d;
+  float* base = abot + (size_t)b * k * d;
+  for (int j = grp; j < k; j += ngrp) s_buf[j * stride + ch] = cact ? base[(size_t)j * d + c_base + ch] : 0.0f;
+  __syncthreads();
+  if (!is2d) {
+    for (int st = 2; st <= k; st <<= 1) {
+      const int npair = k / st;
+      for (int i = grp; i < npair; i += ngrp) {
+        float* pa = &s_buf[(i * st) * stride + ch];
+        float* pd = &s_buf[(i * st + (st >> 1)) * stride + ch];
+        const float x0 = *pa, x1 = *pd;
+        *pa = __fadd_rn(x0, x1);
+        *pd = __fsub_rn(x0, x1);
+      }
+      __syncthreads();
+    }
+  } else {
+    for (int st = 2; st <= G; st <<= 1) {
+      const int nc = G / st;
+      const int h = st >> 1;
+      for (int i = grp; i < nc * nc; i += ngrp) {
+        const int cy = i / nc, cx = i - cy * nc;
+        float* p00 = &s_buf[((cy * st) * G + cx * st) * stride + ch];
+        float* p01 = p00 + h * stride;
+        float* p10 = p00 + h * G * stride;
+        float* p11 = p10 + h * stride;
+        const float p = *p00, q = *p01, u = *p10, v = *p11;
+        const float t0 = __fadd_rn(p, q), t1 = __fsub_rn(p, q), t2 = __fadd_rn(u, v), t3 = __fsub_rn(u, v);
+        *p00 = __fadd_rn(t0, t2);
+        *p01 = __fadd_rn(t1, t3);
+        *p10 = __fsub_rn(t0, t2);
+        *p11 = __fsub_rn(t1, t3);
+      }
+      __syncthreads();
+    }
+  }
+  // normalise, scatter to STaMP order, row absmax over this slice
+  for (int q = grp; q < k; q += ngrp) {
+    int e, lvl_top;  // level counted within the top part (1 = first top level); slot 0 gets the deepest
+    if (!is2d) {
+      e = stamp_e_of_natural_1d(q, k);
+      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)k)) : (__builtin_ctz((unsigned)q) + 1);
+    } else {
+      const int y = q / G, x = q - y * G;
+      e = stamp_e_of_natural_2d(y, x, G);
+      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)G)) : (__builtin_ctz((unsigned)(y | x)) + 1);
+    }
+    const int level = r_bottom + lvl_top;
+    const float nrm = is2d ? ldexpf(1.0f, -level) : haar_norm(level);
+    const float t = __fmul_rn(s_buf[q * stride + ch], nrm);
+    if (cact) base[(size_t)e * d + c_base + ch] = t;
+    // max over the 32 channels of this row: lanes of one row are 32 consecutive lanes
+    int x = (int)absbits(t), yv;
+    yv = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false); x = max(x, yv);
+    yv = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false); x = max(x, yv);
+    yv = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); x = max(x, yv);
+    yv = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); x = max(x, yv);
+    yv = __shfl_xor(x, 16, 64); x = max(x, yv);
+    if (ch == 0) atomicMax(&rowmax[b * k + e], (uint32_t)x);
+  }
+}
+
+// one workgroup per 8-bit row
+__global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop, const uint32_t* __restrict__ rowmax,
+                                                  int8_t* __restrict__ q_hi, float* __restrict__ scales, int k, int d,
+                                                  int s, int R) {
+  const int p = blockIdx.x, b = blockIdx.y;
+  const float a = __uint_as_float(rowmax[b * k + p]);
+  float scale = 0.0f, inv = 0.0f;
+  if (a > 0.0f) {
+    scale = __fdiv_rn(a, 127.0f);
+    inv = __fdiv_rn(127.0f, a);
+  }
+  if (threadIdx.x == 0) scales[(size_t)b * s + (size_t)p * R] = scale;
+  const float* src = ttop + ((size_t)b * k + p) * d;
+  int8_t* dst = q_hi + ((size_t)b * k + p) * d;
+  for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
+    const float4 t = *reinterpret_cast<const float4*>(src + c);
+    const float v[4] = {t.x, t.y, t.z, t.w};
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float q = rintf(__fmul_rn(v[i], inv));
+      q = fminf(fmaxf(q, -127.0f), 127.0f);
+      w |= ((uint32_t)((int)q) & 0xFFu) << (8 * i);
+    }
+    *reinterpret_cast<uint32_t*>(dst + c) = w;
+  }
+}
+
+}  // namespace
+
+hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
+                                 float* abot, uint32_t* rowmax, hipStream_t st) {
+  const StampGeom& g = p->geom;
+  const int nthreads = ((g.d / 8 + 63) / 64) * 64;
+  dim3 grid(g.k, g.B);
+#define LAUNCH1D(RL)                                                                                      \
+  do {                                                                                                    \
+    if (g.x_bf16)                                                                                         \
+      hipLaunchKernelGGL((k_bottom1d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k); \
+    else                                                                                                  \
+      hipLaunchKernelGGL((k_bottom1d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k); \
+  } while (0)
+#define LAUNCH2D(RL)                                                                                      \
+  do {                                                                                                    \
+    if (g.x_bf16)                                                                                         \
+      hipLaunchKernelGGL((k_bottom2d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW); \
+    else                                                                                                  \
+      hipLaunchKernelGGL((k_bottom2d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW); \
+  } while (0)
+  if (!g.is2d) {
+    switch (g.r) {
+      case 3: LAUNCH1D(3); break;
+      case 4: LAUNCH1D(4); break;
+      case 5: LAUNCH1D(5); break;
+      case 6: LAUNCH1D(6); break;
+      case 7: LAUNCH1D(7); break;
+      default: return hipErrorInvalidValue;
+    }
+  } else {
+    if (nthreads > 512) return hipErrorInvalidValue;
+    switch (g.r) {
+      case 2: LAUNCH2D(2); break;
+      case 3: LAUNCH2D(3); break;
+      default: return hipErrorInvalidValue;
+    }
+  }
+#undef LAUNCH1D
+#undef LAUNCH2D
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t lds = (size_t)g.k * (kTopCh + 1) * sizeof(float);
+  hipLaunchKernelGGL(k_top, dim3((g.d + kTopCh - 1) / kTopCh, g.B), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d,
+                     g.G, g.r);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, q_hi, scales, g.k, g.d, g.s, g.R);
+  return hipGetLastError();
+}

@@ -1,0 +1,291 @@
+// Host side of the C ABI declared in include/stamp.h: argument validation (always before any HIP
+// call), plan construction, workspace layout and the launch sequences.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "stamp_internal.h"
+
+namespace {
+
+inline bool is_pow2(int64_t n) { return n >= 1 && (n & (n - 1)) == 0; }
+inline int ilog2(int64_t n) { int l = 0; while ((int64_t(1) << (l + 1)) <= n) ++l; return l; }
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok) {
+  if (d->batch < 1 || d->seq_len < 1 || d->d_in < 1 || d->d_out < 1) return STAMP_ERR_SHAPE;
+  if (d->xform != STAMP_L_IDENTITY && d->xform != STAMP_L_HAAR1D && d->xform != STAMP_L_HAAR2D) return STAMP_ERR_SHAPE;
+  if (d->k_hi < 0 || d->k_hi > d->seq_len) return STAMP_ERR_SHAPE;
+  if (d->bits_hi < 2 || d->bits_hi > 8 || d->bits_lo < 2 || d->bits_lo > 8 || d->bits_w < 2 || d->bits_w > 8)
+    return STAMP_ERR_SHAPE;
+  if (d->d_in % 2 != 0) return STAMP_ERR_SHAPE;
+  for (int32_t t : {d->x_dtype, d->y_dtype, d->w_dtype})
+    if (t != STAMP_F32 && t != STAMP_BF16) return STAMP_ERR_SHAPE;
+  if (d->w_is_out_by_in != 0 && d->w_is_out_by_in != 1) return STAMP_ERR_SHAPE;
+  if ((int64_t)d->batch * d->seq_len > (int64_t)1 << 30) return STAMP_ERR_SHAPE;
+
+  int J = 0, side = 0;
+  if (d->xform == STAMP_L_HAAR1D) {
+    if (!is_pow2(d->seq_len)) return STAMP_ERR_SHAPE;
+    J = ilog2(d->seq_len);
+    if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_HAAR2D) {
+    if (d->grid_h < 1 || d->grid_w < 1 || (int64_t)d->grid_h * d->grid_w != d->seq_len) return STAMP_ERR_SHAPE;
+    if (!is_pow2(d->grid_h) || !is_pow2(d->grid_w)) return STAMP_ERR_SHAPE;
+    side = d->grid_h < d->grid_w ? d->grid_h : d->grid_w;
+    J = ilog2(side);
+    if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
+  }
+
+  // ---- valid STaMP settings from here on; what follows is what this library implements ----
+  if (d->xform == STAMP_L_IDENTITY) return STAMP_ERR_UNSUPPORTED;
+  if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
+  if (d->w_dtype != STAMP_F32) return STAMP_ERR_UNSUPPORTED;
+  if (d->d_in % 32 != 0 || d->d_in > 8192) return STAMP_ERR_UNSUPPORTED;
+  if (d->levels != J) return STAMP_ERR_UNSUPPORTED;
+  if (d->k_hi < 1 || d->k_hi > 256 || !is_pow2(d->k_hi)) return STAMP_ERR_UNSUPPORTED;
+  const int R = d->seq_len / d->k_hi;
+
+  memset(g, 0, sizeof(*g));
+  g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
+  g->J = J; g->k = d->k_hi; g->R = R;
+  g->x_bf16 = d->x_dtype == STAMP_BF16;
+  g->y_bf16 = d->y_dtype == STAMP_BF16;
+  if (d->xform == STAMP_L_HAAR1D) {
+    g->is2d = 0;
+    g->r = ilog2(R);
+    if (g->r < 3 || g->r > 7) return STAMP_ERR_UNSUPPORTED;
+    *fused_ok = g->r <= 6;
+  } else {
+    if (d->grid_h != d->grid_w) return STAMP_ERR_UNSUPPORTED;
+    const int lk = ilog2(d->k_hi);
+    if (lk % 2 != 0) return STAMP_ERR_UNSUPPORTED;  // k must be a power of four
+    g->is2d = 1;
+    g->G = 1 << (lk / 2);
+    g->g = side / g->G;
+    g->r = ilog2(g->g);
+    g->gridW = d->grid_w;
+    if (g->r < 2 || g->r > 3) return STAMP_ERR_UNSUPPORTED;
+    if (d->d_in > 4096) return STAMP_ERR_UNSUPPORTED;
+    *fused_ok = 1;
+  }
+  return STAMP_OK;
+}
+
+void layout_workspace(stamp_plan* p) {
+  const StampGeom& g = p->geom;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  p->ws_abot = take((size_t)g.B * g.k * g.d * sizeof(float));
+  p->ws_rowmax = take((size_t)g.B * g.k * sizeof(uint32_t));
+  p->ws_qhi = take((size_t)g.B * g.k * g.d);
+  p->ws_qlo = take((size_t)g.B * g.s * (g.d / 2));
+  p->ws_scales = take((size_t)g.B * g.s * sizeof(float));
+  p->ws_ythi = take((size_t)g.B * g.k * g.N * sizeof(float));
+  p->ws_P = take((size_t)g.B * g.k * g.N * sizeof(float));
+  p->ws_ytlo = off;
+  if (p->unfused || !p->fused_ok) take((size_t)g.B * g.s * g.N * sizeof(float));
+  p->ws_total = off;
+}
+
+inline bool ws_ok(const stamp_plan* p, const void* ws, size_t bytes, size_t need) {
+  (void)p;
+  return ws != nullptr && (reinterpret_cast<uintptr_t>(ws) & 255) == 0 && bytes >= need;
+}
+
+inline uint8_t* at(void* ws, size_t off) { return reinterpret_cast<uint8_t*>(ws) + off; }
+
+stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t* q_lo, const float* scales, void* Y,
+                         void* ws, hipStream_t st) {
+  float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
+  float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
+  if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (p->fused_ok && !p->unfused) {
+    if (stamp_launch_gemm_lo(p, q_lo, scales, 2, Y, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  } else {
+    float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
+    if (stamp_launch_gemm_lo(p, q_lo, scales, 1, ytlo, nullptr, st) != hipSuccess) return STAMP_ERR_DEVICE;
+    if (stamp_launch_inverse_bottom(p, ytlo, 0, P, p->geom.N, p->bias_dev, Y, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  }
+  return STAMP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* stamp_status_string(stamp_status_t s) {
+  switch (s) {
+    case STAMP_OK: return "ok";
+    case STAMP_ERR_NULL: return "null pointer";
+    case STAMP_ERR_SHAPE: return "inconsistent shape or parameter";
+    case STAMP_ERR_UNSUPPORTED: return "setting not implemented by this library";
+    case STAMP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case STAMP_ERR_ALLOC: return "device allocation failed";
+    case STAMP_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_dev, const float* bias_dev,
+                                 void* hip_stream, stamp_plan_t** out) {
+  if (desc == nullptr || out == nullptr) return STAMP_ERR_NULL;
+  *out = nullptr;
+  StampGeom g;
+  int fused_ok = 0;
+  stamp_status_t vs = validate(desc, &g, &fused_ok);
+  if (vs != STAMP_OK) return vs;
+  if (W_dev == nullptr) return STAMP_ERR_NULL;
+
+  stamp_plan* p = new (std::nothrow) stamp_plan;
+  if (p == nullptr) return STAMP_ERR_ALLOC;
+  memset(p, 0, sizeof(*p));
+  p->desc = *desc;
+  p->geom = g;
+  p->fused_ok = fused_ok;
+  p->unfused = 0;
+  p->Kpad = ((g.d + 127) / 128) * 128;
+  p->Npad = ((g.N + 255) / 256) * 256;
+  layout_workspace(p);
+
+  // physical row of every STaMP slot
+  p->row_of_coeff = static_cast<int32_t*>(malloc(sizeof(int32_t) * (size_t)g.s));
+  if (p->row_of_coeff == nullptr) { delete p; return STAMP_ERR_ALLOC; }
+  for (int q = 0; q < g.k; ++q) p->row_of_coeff[q] = q * g.R;
+  for (int j = 0; j < g.k; ++j)
+    for (int e = 1; e < g.R; ++e) {
+      const int slot = g.is2d ? stamp_slot_of_block_e_2d(j / g.G, j % g.G, e, g.G) : stamp_slot_of_block_e_1d(j, e, g.k);
+      p->row_of_coeff[slot] = j * g.R + e;
+    }
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  uint32_t* colmax = nullptr;
+  bool ok = hipMalloc(reinterpret_cast<void**>(&p->qW_dev), (size_t)p->Npad * p->Kpad) == hipSuccess &&
+            hipMalloc(reinterpret_cast<void**>(&p->sw_dev), sizeof(float) * p->Npad) == hipSuccess &&
+            hipMalloc(reinterpret_cast<void**>(&colmax), sizeof(uint32_t) * g.N) == hipSuccess;
+  if (ok && bias_dev != nullptr) ok = hipMalloc(reinterpret_cast<void**>(&p->bias_dev), sizeof(float) * p->Npad) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    if (colmax) (void)hipFree(colmax);
+    stamp_plan_destroy(p);
+    return STAMP_ERR_ALLOC;
+  }
+  bool dev_ok = true;
+  if (bias_dev != nullptr) {
+    dev_ok = hipMemsetAsync(p->bias_dev, 0, sizeof(float) * p->Npad, st) == hipSuccess &&
+             hipMemcpyAsync(p->bias_dev, bias_dev, sizeof(float) * g.N, hipMemcpyDeviceToDevice, st) == hipSuccess;
+  }
+  if (dev_ok) dev_ok = stamp_launch_weight_quant(p, static_cast<const float*>(W_dev), st, colmax) == hipSuccess;
+  // the scratch column maxima must outlive the kernels just enqueued: hipFree waits for the device
+  (void)hipFree(colmax);
+  if (!dev_ok) {
+    stamp_plan_destroy(p);
+    return STAMP_ERR_DEVICE;
+  }
+  *out = p;
+  return STAMP_OK;
+}
+
+stamp_status_t stamp_plan_destroy(stamp_plan_t* p) {
+  if (p == nullptr) return STAMP_ERR_NULL;
+  if (p->qW_dev) (void)hipFree(p->qW_dev);
+  if (p->sw_dev) (void)hipFree(p->sw_dev);
+  if (p->bias_dev) (void)hipFree(p->bias_dev);
+  free(p->row_of_coeff);
+  delete p;
+  return STAMP_OK;
+}
+
+size_t stamp_plan_workspace_bytes(const stamp_plan_t* p) { return p ? p->ws_total : 0; }
+
+stamp_status_t stamp_plan_set_unfused(stamp_plan_t* p, int32_t unfused) {
+  if (p == nullptr) return STAMP_ERR_NULL;
+  p->unfused = unfused ? 1 : 0;
+  layout_workspace(p);
+  return STAMP_OK;
+}
+
+stamp_status_t stamp_plan_row_of_coeff(const stamp_plan_t* p, int32_t* host_out) {
+  if (p == nullptr || host_out == nullptr) return STAMP_ERR_NULL;
+  memcpy(host_out, p->row_of_coeff, sizeof(int32_t) * (size_t)p->geom.s);
+  return STAMP_OK;
+}
+
+stamp_status_t stamp_quantize_act(const stamp_plan_t* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
+                                  void* ws, size_t ws_bytes, void* hip_stream) {
+  if (p == nullptr || X == nullptr || q_hi == nullptr || q_lo == nullptr || scales == nullptr) return STAMP_ERR_NULL;
+  if (!ws_ok(p, ws, ws_bytes, p->ws_qhi)) return STAMP_ERR_WORKSPACE;  // needs the block sums and row maxima only
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, reinterpret_cast<float*>(at(ws, p->ws_abot)),
+                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)), st);
+  return e == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+}
+
+stamp_status_t stamp_linear_forward_q(const stamp_plan_t* p, const int8_t* q_hi, const uint8_t* q_lo,
+                                      const float* scales, void* Y, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (p == nullptr || q_hi == nullptr || q_lo == nullptr || scales == nullptr || Y == nullptr) return STAMP_ERR_NULL;
+  if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
+  return forward_q(p, q_hi, q_lo, scales, Y, ws, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+stamp_status_t stamp_linear_forward(const stamp_plan_t* p, const void* X, void* Y, void* ws, size_t ws_bytes,
+                                    void* hip_stream) {
+  if (p == nullptr || X == nullptr || Y == nullptr) return STAMP_ERR_NULL;
+  if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  int8_t* q_hi = reinterpret_cast<int8_t*>(at(ws, p->ws_qhi));
+  uint8_t* q_lo = at(ws, p->ws_qlo);
+  float* scales = reinterpret_cast<float*>(at(ws, p->ws_scales));
+  hipError_t e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, reinterpret_cast<float*>(at(ws, p->ws_abot)),
+                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)), st);
+  if (e != hipSuccess) return STAMP_ERR_DEVICE;
+  return forward_q(p, q_hi, q_lo, scales, Y, ws, st);
+}
+
+stamp_status_t stamp_inverse(const stamp_plan_t* p, const float* Yt, int32_t n_cols, void* Y, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+  if (p == nullptr || Yt == nullptr || Y == nullptr) return STAMP_ERR_NULL;
+  if (n_cols < 1) return STAMP_ERR_SHAPE;
+  const size_t need = (size_t)p->geom.B * p->geom.k * (size_t)n_cols * sizeof(float);
+  if (!ws_ok(p, ws, ws_bytes, need)) return STAMP_ERR_WORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  float* P = reinterpret_cast<float*>(ws);
+  if (stamp_launch_inverse_top(p, Yt, 1, n_cols, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  const float* bias = (n_cols == p->geom.N) ? p->bias_dev : nullptr;
+  if (stamp_launch_inverse_bottom(p, Yt, 1, P, n_cols, bias, Y, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  return STAMP_OK;
+}
+
+stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* p, const int8_t* q_hi, const uint8_t* q_lo, int32_t* acc,
+                                    void* hip_stream) {
+  if (p == nullptr || q_hi == nullptr || q_lo == nullptr || acc == nullptr) return STAMP_ERR_NULL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  // accumulator mode never reads the activation scales
+  if (stamp_launch_gemm_hi(p, q_hi, nullptr, 0, acc, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (stamp_launch_gemm_lo(p, q_lo, nullptr, 0, acc, nullptr, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  return STAMP_OK;
+}
+
+stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* p, int8_t* qW_host, float* sw_host) {
+  if (p == nullptr || qW_host == nullptr || sw_host == nullptr) return STAMP_ERR_NULL;
+  const int d = p->geom.d, N = p->geom.N;
+  int8_t* tmp = static_cast<int8_t*>(malloc((size_t)p->Npad * p->Kpad));
+  if (tmp == nullptr) return STAMP_ERR_ALLOC;
+  if (hipDeviceSynchronize() != hipSuccess ||
+      hipMemcpy(tmp, p->qW_dev, (size_t)p->Npad * p->Kpad, hipMemcpyDeviceToHost) != hipSuccess ||
+      hipMemcpy(sw_host, p->sw_dev, sizeof(float) * N, hipMemcpyDeviceToHost) != hipSuccess) {
+    free(tmp);
+    return STAMP_ERR_DEVICE;
+  }
+  for (int n = 0; n < N; ++n)
+    for (int c = 0; c < d; ++c) {
+      const int g16 = c >> 4, cc = c & 15, half = cc >> 3, c8 = cc & 7;
+      const int pos = half * 8 + (c8 & 1) * 4 + (c8 >> 1);
+      qW_host[(size_t)c * N + n] = (int8_t)(tmp[(size_t)n * p->Kpad + g16 * 16 + pos] / 16);
+    }
+  free(tmp);
+  return STAMP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Internal declarations shared by the HIP sources of the STaMP library (gfx950 only).
+#ifndef STAMP_INTERNAL_H_
+#define STAMP_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "stamp.h"
+
+#define STAMP_HD __host__ __device__ __forceinline__
+
+// ---------------------------------------------------------------------------------------------
+// Geometry of a plan.  The J-level transform is split at level r = log2(seq_len / k_hi) (1-D) or
+// log4 (2-D): the "bottom" r levels act inside aligned blocks of R tokens and produce the R-1
+// 4-bit rows of each block; the "top" J-r levels act on the k_hi block sums and produce the k_hi
+// 8-bit rows.
+// ---------------------------------------------------------------------------------------------
+struct StampGeom {
+  int32_t B, s, d, N;
+  int32_t is2d;      // 0: 1-D stream, 1: 2-D grid
+  int32_t J;         // total levels
+  int32_t r;         // bottom levels (inside a block)
+  int32_t R;         // tokens per block: 2^r (1-D) or 4^r (2-D)
+  int32_t k;         // number of blocks per sequence = k_hi
+  int32_t G;         // 2-D: blocks per grid side (k = G*G); 1-D: unused (0)
+  int32_t g;         // 2-D: tokens per block side (2^r); 1-D: unused (0)
+  int32_t gridW;     // 2-D: tokens per grid row
+  int32_t x_bf16;    // input dtype is bf16
+  int32_t y_bf16;    // output dtype is bf16
+};
+
+// Position inside a block ("e", 0 = the block sum, e >= 1 the in-block detail rows in STaMP
+// order) of the coefficient that the in-place butterfly network leaves at natural position q.
+// 1-D: in-place butterflies at stride 2^l leave the level-l difference of pair i at position
+// i*2^l + 2^(l-1).
+STAMP_HD int stamp_e_of_natural_1d(int q, int n /* block length, power of two */) {
+  if (q == 0) return 0;
+  int t = __builtin_ctz((unsigned)q);  // level - 1
+  return (n >> (t + 1)) + (q >> (t + 1));
+}
+
+// 2-D: natural position (y, x) in a g x g block; the in-place network leaves at
+// (2^l i + dy 2^(l-1), 2^l j + dx 2^(l-1)) the band (dy, dx) of level l: (0,1) = difference along
+// the width, (1,0) = along the height, (1,1) = diagonal.
+STAMP_HD int stamp_e_of_natural_2d(int y, int x, int g) {
+  if (y == 0 && x == 0) return 0;
+  int t = __builtin_ctz((unsigned)(y | x));  // level - 1
+  int by = (y >> t) & 1, bx = (x >> t) & 1;
+  int band = by ? (bx ? 2 : 1) : 0;          // W, H, D
+  int gl = g >> (t + 1);                     // side of each band of that level
+  return gl * gl * (1 + band) + (y >> (t + 1)) * gl + (x >> (t + 1));
+}
+
+// STaMP slot p (whole sequence) of in-block position e >= 1 of block j.
+// 1-D: e = 2^m + i  ->  p = (k + j) * 2^m + i.
+STAMP_HD int stamp_slot_of_block_e_1d(int j, int e, int k) {
+  int m = 31 - __builtin_clz((unsigned)e);
+  return ((k + j) << m) + (e - (1 << m));
+}
+
+// 2-D: block (bi, bj) of a G x G block grid, e = gl^2 (1 + band) + yy gl + xx  ->
+// p = (G gl)^2 (1 + band) + (bi gl + yy)(G gl) + bj gl + xx.
+STAMP_HD int stamp_slot_of_block_e_2d(int bi, int bj, int e, int G) {
+  int m = (31 - __builtin_clz((unsigned)e)) >> 1;  // gl = 2^m, since gl^2 <= e < 4 gl^2
+  int gl = 1 << m;
+  int band = (e >> (2 * m)) - 1;
+  int rem = e - ((1 + band) << (2 * m));
+  int yy = rem >> m, xx = rem & (gl - 1);
+  int Gl = G * gl;
+  return Gl * Gl * (1 + band) + (bi * gl + yy) * Gl + bj * gl + xx;
+}
+
+// Level (1 = finest) of in-block position e >= 1 in a block of R tokens.
+STAMP_HD int stamp_level_of_e_1d(int e, int r) { return r - (31 - __builtin_clz((unsigned)e)); }
+STAMP_HD int stamp_level_of_e_2d(int e, int r) { return r - ((31 - __builtin_clz((unsigned)e)) >> 1); }
+
+// ---------------------------------------------------------------------------------------------
+// The plan.
+// ---------------------------------------------------------------------------------------------
+struct stamp_plan {
+  stamp_plan_desc_t desc;
+  StampGeom geom;
+  int32_t Kpad, Npad;       // GEMM-padded depth and width of the stored weight
+  int8_t* qW_dev;           // [Npad][Kpad] int8: weight codes * 16, K order permuted per 16 channels
+  float* sw_dev;            // [Npad] weight scales (0 beyond d_out)
+  float* bias_dev;          // [Npad] bias or nullptr
+  int32_t* row_of_coeff;    // host, [s]
+  int32_t unfused;          // 1: separate inverse kernel
+  int32_t fused_ok;         // shape allows the fused epilogue
+  // workspace layout (byte offsets, 256-aligned)
+  size_t ws_abot, ws_rowmax, ws_qhi, ws_qlo, ws_scales, ws_ythi, ws_P, ws_ytlo, ws_total;
+};
+
+// ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
+hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStream_t st, uint32_t* colmax_tmp);
+hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo,
+                                 float* scales, float* abot, uint32_t* rowmax, hipStream_t st);
+// mode: 0 = int32 accumulators in STaMP row order (debug), 1 = dequantized fp32 rows (hi -> Yt_hi
+// [B*k, N], lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y.
+hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode,
+                                void* out, hipStream_t st);
+hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const float* scales, int mode,
+                                void* out, const float* P, hipStream_t st);
+hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* Yt_hi, int hi_row_stride_is_stamp,
+                                    int ncols, float* P, hipStream_t st);
+hipError_t stamp_launch_inverse_bottom(const stamp_plan* p, const float* Yt_lo, int src_is_stamp_order,
+                                       const float* P, int ncols, const float* bias, void* Y, hipStream_t st);
+
+#endif  // STAMP_INTERNAL_H_

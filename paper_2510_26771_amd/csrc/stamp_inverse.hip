@@ -1,0 +1,168 @@
+// Inverse sequence transform Y = L^-1 Y' = L^T Y' (step "Y <- L^-1 Y" of Algorithm "STaMP Linear";
+// L is orthogonal, Theorem 1) as two kernels mirroring the forward split:
+//   k_inverse_top     the J-r top levels: the k_hi coarse coefficients of every (sequence, column)
+//                     -> the k_hi block sums P (the level-r sums of the inverse).
+//   k_inverse_bottom  the r levels inside each block of R tokens, from P and the R-1 in-block
+//                     coefficients, then bias and the store in original token order.
+// Both work on a slice of 32 output columns held in LDS, butterflies in place (stride 2^l).
+// Every coefficient is multiplied by the norm 2^(-l/2) of its level first (either by the producer,
+// folded into the dequantization scale, or here when apply_norm is set); the butterflies are then
+// plain sums and differences.  The output tolerance does not depend on this order.
+#include "stamp_internal.h"
+
+namespace {
+
+constexpr int kCols = 32;
+constexpr int kStride = kCols + 1;
+constexpr float kInvSqrt2 = 0.70710678118654752440f;
+
+__device__ __forceinline__ float haar_norm_dev(int level, int is2d) {
+  return is2d ? ldexpf(1.0f, -level) : ldexpf((level & 1) ? kInvSqrt2 : 1.0f, -(level >> 1));
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// in-place inverse butterflies over n1 (1-D) or side x side (2-D) entries of s_buf[.][kStride]
+__device__ __forceinline__ void inverse_inplace(float* s_buf, int n, int side, int is2d, int ch, int grp, int ngrp) {
+  if (!is2d) {
+    for (int st = n; st >= 2; st >>= 1) {
+      const int npair = n / st;
+      for (int i = grp; i < npair; i += ngrp) {
+        float* pa = &s_buf[(i * st) * kStride + ch];
+        float* pd = &s_buf[(i * st + (st >> 1)) * kStride + ch];
+        const float a = *pa, dd = *pd;
+        *pa = a + dd;
+        *pd = a - dd;
+      }
+      __syncthreads();
+    }
+  } else {
+    for (int st = side; st >= 2; st >>= 1) {
+      const int nc = side / st, h = st >> 1;
+      for (int i = grp; i < nc * nc; i += ngrp) {
+        const int cy = i / nc, cx = i - cy * nc;
+        float* p00 = &s_buf[((cy * st) * side + cx * st) * kStride + ch];
+        float* p01 = p00 + h * kStride;
+        float* p10 = p00 + h * side * kStride;
+        float* p11 = p10 + h * kStride;
+        const float cLL = *p00, cW = *p01, cH = *p10, cD = *p11;
+        const float t0 = cLL + cH, t2 = cLL - cH, t1 = cW + cD, t3 = cW - cD;
+        *p00 = t0 + t1;
+        *p01 = t0 - t1;
+        *p10 = t2 + t3;
+        *p11 = t2 - t3;
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// src: hi rows; row of (b, p) = b * src_seq_rows + p.  P[(b*k + j) * ncols + n].
+__global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ src, int src_seq_rows, int apply_norm,
+                                                     float* __restrict__ P, int ncols, StampGeom g) {
+  extern __shared__ float s_buf[];  // [k][kStride]
+  const int b = blockIdx.y, n_base = blockIdx.x * kCols, tid = threadIdx.x;
+  const int ch = tid & (kCols - 1), grp = tid / kCols, ngrp = 256 / kCols;
+  const int n = n_base + ch;
+  const bool nact = n < ncols;
+  const int k = g.k;
+  for (int q = grp; q < k; q += ngrp) {
+    int e, lvl_top;
+    if (!g.is2d) {
+      e = stamp_e_of_natural_1d(q, k);
+      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)k)) : (__builtin_ctz((unsigned)q) + 1);
+    } else {
+      const int y = q / g.G, x = q - y * g.G;
+      e = stamp_e_of_natural_2d(y, x, g.G);
+      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)g.G)) : (__builtin_ctz((unsigned)(y | x)) + 1);
+    }
+    float v = nact ? src[((size_t)b * src_seq_rows + e) * ncols + n] : 0.0f;
+    if (apply_norm) v *= haar_norm_dev(g.r + lvl_top, g.is2d);
+    s_buf[q * kStride + ch] = v;
+  }
+  __syncthreads();
+  inverse_inplace(s_buf, k, g.G, g.is2d, ch, grp, ngrp);
+  for (int q = grp; q < k; q += ngrp)
+    if (nact) P[((size_t)b * k + q) * ncols + n] = s_buf[q * kStride + ch];
+}
+
+// src rows of block (b, j): physical (b*s + j*R + e) or STaMP slot order; Y [B, s, ncols].
+__global__ __launch_bounds__(256) void k_inverse_bottom(const float* __restrict__ src, int src_is_stamp, int apply_norm,
+                                                        const float* __restrict__ P, const float* __restrict__ bias,
+                                                        void* __restrict__ Y, int ncols, StampGeom g) {
+  extern __shared__ float s_buf[];  // [R][kStride]
+  const int j = blockIdx.y, b = blockIdx.z, n_base = blockIdx.x * kCols, tid = threadIdx.x;
+  const int ch = tid & (kCols - 1), grp = tid / kCols, ngrp = 256 / kCols;
+  const int n = n_base + ch;
+  const bool nact = n < ncols;
+  const int R = g.R;
+  const int bi = g.is2d ? j / g.G : 0, bj = g.is2d ? j - bi * g.G : 0;
+  for (int q = grp; q < R; q += ngrp) {
+    float v = 0.0f;
+    if (q == 0) {
+      if (nact) v = P[((size_t)b * g.k + j) * ncols + n];
+    } else {
+      int e, level;
+      if (!g.is2d) {
+        e = stamp_e_of_natural_1d(q, R);
+        level = __builtin_ctz((unsigned)q) + 1;
+      } else {
+        const int y = q / g.g, x = q - y * g.g;
+        e = stamp_e_of_natural_2d(y, x, g.g);
+        level = __builtin_ctz((unsigned)(y | x)) + 1;
+      }
+      size_t row;
+      if (src_is_stamp) {
+        const int p = g.is2d ? stamp_slot_of_block_e_2d(bi, bj, e, g.G) : stamp_slot_of_block_e_1d(j, e, g.k);
+        row = (size_t)b * g.s + p;
+      } else {
+        row = (size_t)b * g.s + (size_t)j * R + e;
+      }
+      if (nact) v = src[row * ncols + n];
+      if (apply_norm) v *= haar_norm_dev(level, g.is2d);
+    }
+    s_buf[q * kStride + ch] = v;
+  }
+  __syncthreads();
+  inverse_inplace(s_buf, R, g.g, g.is2d, ch, grp, ngrp);
+  const float bias_n = (bias != nullptr && nact) ? bias[n] : 0.0f;
+  for (int q = grp; q < R; q += ngrp) {
+    size_t tok;
+    if (!g.is2d) {
+      tok = (size_t)b * g.s + (size_t)j * R + q;
+    } else {
+      const int y = q / g.g, x = q - y * g.g;
+      tok = (size_t)b * g.s + (size_t)(bi * g.g + y) * g.gridW + (size_t)(bj * g.g + x);
+    }
+    if (nact) {
+      const float yv = s_buf[q * kStride + ch] + bias_n;
+      if (g.y_bf16) reinterpret_cast<uint16_t*>(Y)[tok * ncols + n] = f32_to_bf16_rne(yv);
+      else reinterpret_cast<float*>(Y)[tok * ncols + n] = yv;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* src, int src_is_stamp, int ncols, float* P,
+                                    hipStream_t st) {
+  const StampGeom& g = p->geom;
+  const size_t lds = (size_t)g.k * kStride * sizeof(float);
+  hipLaunchKernelGGL(k_inverse_top, dim3((ncols + kCols - 1) / kCols, g.B), dim3(256), lds, st, src,
+                     src_is_stamp ? g.s : g.k, src_is_stamp, P, ncols, g);
+  return hipGetLastError();
+}
+
+hipError_t stamp_launch_inverse_bottom(const stamp_plan* p, const float* src, int src_is_stamp, const float* P,
+                                       int ncols, const float* bias, void* Y, hipStream_t st) {
+  const StampGeom& g = p->geom;
+  const size_t lds = (size_t)g.R * kStride * sizeof(float);
+  hipLaunchKernelGGL(k_inverse_bottom, dim3((ncols + kCols - 1) / kCols, g.k, g.B), dim3(256), lds, st, src,
+                     src_is_stamp, src_is_stamp, P, bias, Y, ncols, g);
+  return hipGetLastError();
+}

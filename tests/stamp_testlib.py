@@ -1,0 +1,203 @@
+"""Shared helpers of the GPU parity tests: run the oracle and the HIP library on the same seeded
+inputs and compare them step by step.  The oracle is only ever called from here and from tests."""
+from __future__ import annotations
+
+import time
+from typing import Dict, Optional
+
+import numpy as np
+
+from gen import Workload, make_inputs
+from oracle import stamp_oracle as so
+
+XFORM_CODE = {"identity": 0, "haar1d": 1, "haar2d": 2}
+
+
+def log(msg: str):
+    print(f"[stamp-test {time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def plan_desc_for(w: Workload, y_dtype: str = "f32"):
+    import paper_2510_26771_amd as st
+    return st.PlanDesc(batch=w.batch, seq_len=w.seq_len, d_in=w.d_in, d_out=w.d_out, xform=XFORM_CODE[w.xform],
+                       levels=w.levels, grid_h=w.grid_h, grid_w=w.grid_w, k_hi=w.k_hi, bits_hi=w.bits_hi,
+                       bits_lo=w.bits_lo, bits_w=w.bits_w,
+                       x_dtype=st.STAMP_BF16 if w.x_dtype == "bf16" else st.STAMP_F32,
+                       y_dtype=st.STAMP_BF16 if y_dtype == "bf16" else st.STAMP_F32)
+
+
+def to_device_x(inp: dict, w: Workload):
+    import torch
+    if w.x_dtype == "bf16":
+        return torch.from_numpy(inp["X_store"].view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(inp["X_store"]).cuda()
+
+
+def unpack_int4(q_lo: np.ndarray) -> np.ndarray:
+    """[..., d/2] bytes -> [..., d] int8, low nibble = even channel, two's complement."""
+    lo = (q_lo & 0xF).astype(np.int8)
+    hi = (q_lo >> 4).astype(np.int8)
+    lo = np.where(lo >= 8, lo - 16, lo).astype(np.int8)
+    hi = np.where(hi >= 8, hi - 16, hi).astype(np.int8)
+    out = np.empty(q_lo.shape[:-1] + (q_lo.shape[-1] * 2,), dtype=np.int8)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    return out
+
+
+def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):
+    """Device buffers (physical row order) -> numpy codes [B, s, d] int8 and scales [B, s] in STaMP order."""
+    d = plan.desc
+    row = plan.row_of_coeff().astype(np.int64)
+    assert sorted(row.tolist()) == list(range(d.seq_len)), "row_of_coeff is not a permutation"
+    k = d.k_hi
+    assert np.array_equal(row[:k], np.arange(k) * (d.seq_len // k))
+    qh = q_hi.cpu().numpy()
+    ql = q_lo.cpu().numpy()
+    sc = scales.cpu().numpy()
+    codes = np.empty((d.batch, d.seq_len, d.d_in), dtype=np.int8)
+    codes[:, :k] = qh
+    codes[:, k:] = unpack_int4(ql[:, row[k:]])
+    return codes, sc[:, row]
+
+
+def near_boundary_mask(T: np.ndarray, scales: np.ndarray, bits: np.ndarray) -> np.ndarray:
+    """Elements whose fp32 value T * inv lies within 1 ulp of a rounding boundary (a half-integer)."""
+    qm = np.where(bits == 8, np.float32(127), np.float32(7)).astype(np.float32)
+    a = np.max(np.abs(T), axis=-1)
+    inv = np.zeros_like(a)
+    nz = a > 0
+    inv[nz] = (np.broadcast_to(qm, a.shape)[nz] / a[nz]).astype(np.float32)
+    p = (T * inv[..., None]).astype(np.float32)
+    h = np.floor(p) + np.float32(0.5)
+    return np.abs(p - h) <= np.spacing(np.abs(p).astype(np.float32))
+
+
+def compare_codes(gpu_codes, gpu_scales, ora: Dict[str, np.ndarray]) -> Dict[str, int]:
+    """Scales must match bit for bit; codes may differ only on near-boundary elements, by one step."""
+    assert gpu_scales.dtype == np.float32
+    bad_scales = int(np.count_nonzero(gpu_scales.view(np.uint32) != ora["scales"].view(np.uint32)))
+    assert bad_scales == 0, f"{bad_scales} scales differ from the oracle"
+    diff = gpu_codes.astype(np.int16) - ora["codes"].astype(np.int16)
+    n_mis = int(np.count_nonzero(diff))
+    n_near = 0
+    if n_mis:
+        near = near_boundary_mask(ora["T"], ora["scales"], ora["bits"][None, :].repeat(gpu_codes.shape[0], 0))
+        outside = (diff != 0) & ~near
+        assert not outside.any(), f"{int(outside.sum())} code mismatches away from a rounding boundary"
+        assert np.abs(diff).max() <= 1
+        n_near = n_mis
+    return {"code_mismatches": n_mis, "near_boundary_mismatches": n_near}
+
+
+def run_oracle(w: Workload, inp: dict, cols: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Oracle results; with `cols` the GEMM / inverse run on those output columns only."""
+    qa = so.quantize_activation(inp["X_f32"], w.xform, w.levels, w.k_hi, w.bits_hi, w.bits_lo, w.grid_h, w.grid_w)
+    qw, sw = so.quantize_weight(inp["W"], w.bits_w)
+    bias = inp["bias"]
+    if cols is not None:
+        qw_c, sw_c = qw[:, cols], sw[cols]
+        bias_c = None if bias is None else bias[cols]
+    else:
+        qw_c, sw_c, bias_c = qw, sw, bias
+    out = so.linear_from_codes(qa["codes"], qa["scales"], qw_c, sw_c, w.xform, w.levels, w.grid_h, w.grid_w, bias_c)
+    out.update(qa)
+    out.update({"qw": qw, "sw": sw})
+    return out
+
+
+def check_output(y_gpu: np.ndarray, y_ref: np.ndarray, y_is_bf16: bool, what: str) -> float:
+    """Output bar: max |y - ref| <= 1e-3 * max|ref| (fp32 stores); a bf16 store may add half a bf16
+    ulp of the element (2^-9 relative) on top, the rounding of the output format itself."""
+    y_gpu = y_gpu.astype(np.float64)
+    y_ref = y_ref.astype(np.float64)
+    scale = float(np.max(np.abs(y_ref)))
+    err = np.abs(y_gpu - y_ref)
+    tol = 1e-3 * scale
+    if y_is_bf16:
+        tol = tol + np.abs(y_ref) * 2.0 ** -8
+    worst = float(np.max(err - tol))
+    assert np.isfinite(y_gpu).all(), f"{what}: non-finite output"
+    assert worst <= 0.0, f"{what}: max err {float(err.max()):.3e} vs scale {scale:.3e}"
+    return float(err.max() / scale) if scale > 0 else 0.0
+
+
+def y_to_numpy(Y, y_is_bf16: bool) -> np.ndarray:
+    import torch
+    if y_is_bf16:
+        return Y.contiguous().view(torch.bfloat16).float().cpu().numpy()
+    return Y.cpu().numpy()
+
+
+def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: Optional[np.ndarray] = None,
+              check_acc: bool = True, check_unfused: bool = True) -> Dict[str, float]:
+    """Everything the ABI exposes, on one workload, against the oracle."""
+    import torch
+    import paper_2510_26771_amd as st
+
+    log(f"case {w.name}: B={w.batch} s={w.seq_len} d={w.d_in} N={w.d_out} {w.xform} k={w.k_hi} x={w.x_dtype} "
+        f"y={y_dtype} bias={with_bias} seed={w.seed}")
+    inp = make_inputs(w, with_bias=with_bias)
+    ora = run_oracle(w, inp, cols)
+    log("oracle done")
+    Xd = to_device_x(inp, w)
+    Wd = torch.from_numpy(inp["W"]).cuda()
+    bd = None if inp["bias"] is None else torch.from_numpy(inp["bias"]).cuda()
+    plan = st.StampPlan(plan_desc_for(w, y_dtype), Wd, bd)
+    report: Dict[str, float] = {}
+
+    # weights
+    qw, sw = plan.debug_weight_codes()
+    assert np.array_equal(qw, ora["qw"]), "weight codes differ"
+    assert np.array_equal(sw.view(np.uint32), ora["sw"].view(np.uint32)), "weight scales differ"
+
+    # activation codes and scales
+    ws = plan.alloc_workspace()
+    q_hi, q_lo, scales = plan.alloc_act_buffers()
+    plan.quantize_act(Xd, q_hi, q_lo, scales, ws)
+    torch.cuda.synchronize()
+    codes, sc = gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales)
+    report.update(compare_codes(codes, sc, ora))
+    log(f"codes ok: {report}")
+
+    # integer accumulators
+    sel = slice(None) if cols is None else cols
+    cols_t = None if cols is None else torch.from_numpy(np.asarray(cols, dtype=np.int64)).cuda()
+
+    def pick(t3):  # [B, s, N] device tensor -> the compared columns, on the host
+        return (t3 if cols_t is None else t3.index_select(2, cols_t)).cpu()
+
+    if check_acc:
+        acc = torch.empty((w.batch * w.seq_len, w.d_out), dtype=torch.int32, device="cuda")
+        plan.debug_gemm_acc(q_hi, q_lo, acc)
+        torch.cuda.synchronize()
+        acc_np = pick(acc.view(w.batch, w.seq_len, w.d_out)).numpy()
+        if report["code_mismatches"] == 0:
+            ref_acc = ora["acc"]
+        else:  # compare on the codes the GPU actually used (they differ only at counted boundaries)
+            ref_acc = np.stack([so.int_gemm(codes[b], ora["qw"][:, sel]) for b in range(w.batch)])
+        assert np.array_equal(acc_np, ref_acc), "int32 accumulators differ"
+        del acc
+        log("accumulators ok")
+
+    # the whole layer, fused (default) and unfused
+    y_bf16 = y_dtype == "bf16"
+    ydt = torch.int16 if y_bf16 else torch.float32
+    for unfused in ([False, True] if check_unfused else [False]):
+        plan.set_unfused(unfused)
+        ws = plan.alloc_workspace()
+        Y = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=ydt, device="cuda")
+        plan.linear_forward(Xd, Y, ws)
+        torch.cuda.synchronize()
+        y_np = y_to_numpy(pick(Y), y_bf16)
+        tag = "unfused" if unfused else "fused"
+        report[f"y_relerr_{tag}"] = check_output(y_np, ora["Y"], y_bf16, f"{w.name} {tag}")
+        # and from the separately quantized activation
+        Y2 = torch.zeros_like(Y)
+        plan.linear_forward_q(q_hi, q_lo, scales, Y2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y2), "linear_forward and quantize_act + linear_forward_q disagree"
+        del Y, Y2, ws
+    log(f"outputs ok: {report}")
+    plan.destroy()
+    return report

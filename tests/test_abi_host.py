@@ -1,0 +1,97 @@
+"""Host-side tests of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2510_26771_amd as st
+from paper_2510_26771_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(st.lib_path()):
+        from paper_2510_26771_amd.build import build
+        build(verbose=False)
+    return st.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    header = open(os.path.join(ROOT, "include", "stamp.h")).read()
+    declared = set(re.findall(r"\b(stamp_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    for code in range(7):
+        s = lib.stamp_status_string(code)
+        assert s and len(s) > 1
+
+
+def _create(lib, desc, W=1):
+    h = C.c_void_p()
+    # W is a fake non-null pointer: validation must fail before it is ever dereferenced
+    rc = lib.stamp_plan_create(C.byref(desc.to_c()), C.c_void_p(W) if W else None, None, None, C.byref(h))
+    assert not h.value
+    return rc
+
+
+def _good(**kw):
+    d = dict(batch=1, seq_len=256, d_in=512, d_out=512, xform=st.STAMP_L_HAAR1D, levels=8, k_hi=8,
+             x_dtype=st.STAMP_F32, y_dtype=st.STAMP_F32)
+    d.update(kw)
+    return st.PlanDesc(**d)
+
+
+@pytest.mark.parametrize("kw,expect", [
+    (dict(seq_len=250), 2),                                   # not a power of two
+    (dict(levels=9), 2),                                      # more levels than log2(seq_len)
+    (dict(levels=0), 2),
+    (dict(k_hi=257), 2),                                      # k > s
+    (dict(k_hi=-1), 2),
+    (dict(d_in=511), 2),                                      # odd d_in cannot be packed
+    (dict(batch=0), 2),
+    (dict(xform=7), 2),
+    (dict(bits_hi=9), 2),
+    (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=8, levels=3), 2),   # grid != seq_len
+    (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=5), 2),  # too many levels
+    (dict(levels=3), 3),                                      # partial depth: valid STaMP, not implemented
+    (dict(k_hi=12), 3),                                       # k not a power of two
+    (dict(k_hi=128), 3),                                      # blocks of 2 tokens
+    (dict(bits_lo=3), 3),
+    (dict(d_in=48), 3),                                       # d_in not a multiple of 32
+    (dict(xform=st.STAMP_L_IDENTITY, levels=0), 3),
+    (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=4, k_hi=8), 3),   # k not a power of four
+    (dict(xform=st.STAMP_L_HAAR2D, grid_h=32, grid_w=8, levels=3, k_hi=16), 3),   # non-square grid
+    (dict(w_dtype=st.STAMP_BF16), 3),
+])
+def test_plan_create_rejects_before_any_device_call(lib, kw, expect):
+    assert _create(lib, _good(**kw)) == expect
+
+
+def test_null_arguments(lib):
+    assert lib.stamp_plan_create(None, None, None, None, None) == 1
+    assert _create(lib, _good(), W=0) == 1
+    assert lib.stamp_plan_destroy(None) == 1
+    assert lib.stamp_plan_workspace_bytes(None) == 0
+    assert lib.stamp_plan_row_of_coeff(None, None) == 1
+    assert lib.stamp_quantize_act(None, None, None, None, None, None, 0, None) == 1
+    assert lib.stamp_linear_forward(None, None, None, None, 0, None) == 1
+    assert lib.stamp_linear_forward_q(None, None, None, None, None, None, 0, None) == 1
+    assert lib.stamp_inverse(None, None, 1, None, None, 0, None) == 1
+    assert lib.stamp_debug_gemm_acc(None, None, None, None, None) == 1
+    assert lib.stamp_debug_weight_codes(None, None, None) == 1
+    assert lib.stamp_plan_set_unfused(None, 1) == 1
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        binding.load_library()

@@ -1,0 +1,199 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Bars: scales, weight codes and int32 accumulators bit-exact; activation codes bit-exact except
+elements whose fp32 product lies within 1 ulp of a rounding boundary (counted, reported);
+outputs within max|err| <= 1e-3 * max|ref|.
+"""
+import numpy as np
+import pytest
+
+from gen import Workload, get_workload, make_inputs
+from oracle import stamp_oracle as so
+
+import stamp_testlib as tl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2510_26771_amd as st
+    st.load_library()  # fails loudly if the HIP library has not been built
+
+
+def _wl(name, **kw):
+    base = dict(name=name, batch=1, seq_len=256, d_in=256, d_out=256, xform="haar1d", levels=8, k_hi=8,
+                x_dtype="bf16", rho=0.9, n_outlier_channels=3, outlier_scale=30.0, w_std=0.02, seed=11)
+    base.update(kw)
+    return Workload(**base)
+
+
+def test_cfg1_small_config_all_steps():
+    r = tl.full_case(get_workload("cfg1"))
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+SMALL = [
+    # several M tiles, ragged N (two N tiles, the second mostly masked), K tail (160 -> 256)
+    _wl("r32_ragged", batch=3, seq_len=512, levels=9, k_hi=16, d_in=160, d_out=300, seed=21),
+    # M = 192 < one tile; blocks of 8 tokens
+    _wl("r8_small_m", batch=3, seq_len=64, levels=6, k_hi=8, d_in=96, d_out=64, seed=22),
+    _wl("r16", batch=2, seq_len=256, levels=8, k_hi=16, d_in=320, d_out=257, seed=23, first_token_scale=100.0),
+    _wl("r64_f32in", batch=2, seq_len=512, levels=9, k_hi=8, d_in=1024, d_out=512, x_dtype="f32", seed=24),
+    # blocks of 128 tokens: only the unfused inverse applies
+    _wl("r128", batch=1, seq_len=1024, levels=10, k_hi=8, d_in=128, d_out=256, seed=25),
+    # k = 1: a single block sum is the only 8-bit token
+    _wl("k1", batch=2, seq_len=64, levels=6, k_hi=1, d_in=64, d_out=96, seed=26),
+    # 2-D grids: 4x4 and 8x8 token blocks
+    _wl("g16_blk4", batch=2, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=16, d_in=96, d_out=130,
+        corr_len=4.0, seed=27),
+    _wl("g32_blk8", batch=1, seq_len=1024, xform="haar2d", levels=5, grid_h=32, grid_w=32, k_hi=16, d_in=288,
+        d_out=512, corr_len=8.0, seed=28),
+    _wl("g8_blk4", batch=3, seq_len=64, xform="haar2d", levels=3, grid_h=8, grid_w=8, k_hi=4, d_in=64, d_out=40,
+        corr_len=2.0, seed=29),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=[w.name for w in SMALL])
+def test_small_cases(w):
+    r = tl.full_case(w, with_bias=True)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+def test_bf16_output_and_bias():
+    tl.full_case(_wl("bf16_out", batch=2, seq_len=256, levels=8, k_hi=8, d_in=256, d_out=384, seed=31),
+                 with_bias=True, y_dtype="bf16")
+    tl.full_case(_wl("bf16_out_2d", batch=1, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=4,
+                     d_in=128, d_out=256, seed=32), with_bias=True, y_dtype="bf16")
+
+
+def test_degenerate_inputs():
+    """All-zero activation (every scale 0, every code 0, output = bias) and a constant activation
+    (only slot 0 is non-zero)."""
+    import torch
+    import paper_2510_26771_amd as st
+    w = _wl("zeros", batch=1, seq_len=256, levels=8, k_hi=8, d_in=128, d_out=256, x_dtype="f32")
+    inp = make_inputs(w, with_bias=True)
+    Wd = torch.from_numpy(inp["W"]).cuda()
+    bd = torch.from_numpy(inp["bias"]).cuda()
+    plan = st.StampPlan(tl.plan_desc_for(w, "f32"), Wd, bd)
+    ws = plan.alloc_workspace()
+    for fill in (0.0, 1.5):
+        X = np.full((1, 256, 128), fill, dtype=np.float32)
+        ora = so.stamp_linear_forward(X, inp["W"], "haar1d", 8, 8, bias=inp["bias"])
+        Xd = torch.from_numpy(X).cuda()
+        q_hi, q_lo, scales = plan.alloc_act_buffers()
+        plan.quantize_act(Xd, q_hi, q_lo, scales, ws)
+        codes, sc = tl.gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales)
+        assert np.array_equal(sc.view(np.uint32), ora["scales"].view(np.uint32))
+        assert np.array_equal(codes, ora["codes"])
+        if fill == 0.0:
+            assert not codes.any() and not sc.any()
+        Y = torch.empty((1, 256, 256), dtype=torch.float32, device="cuda")
+        plan.linear_forward(Xd, Y, ws)
+        torch.cuda.synchronize()
+        tl.check_output(Y.cpu().numpy(), ora["Y"], False, f"fill {fill}")
+    plan.destroy()
+
+
+def test_w_out_by_in_layout():
+    """W given as [d_out, d_in] (the algorithm's X W^T) yields the same plan as its transpose."""
+    import torch
+    import paper_2510_26771_amd as st
+    w = _wl("wT", batch=1, seq_len=256, levels=8, k_hi=8, d_in=128, d_out=200)
+    inp = make_inputs(w)
+    d1 = tl.plan_desc_for(w, "f32")
+    d2 = tl.plan_desc_for(w, "f32")
+    d2.w_is_out_by_in = 1
+    p1 = st.StampPlan(d1, torch.from_numpy(inp["W"]).cuda())
+    p2 = st.StampPlan(d2, torch.from_numpy(np.ascontiguousarray(inp["W"].T)).cuda())
+    q1, s1 = p1.debug_weight_codes()
+    q2, s2 = p2.debug_weight_codes()
+    assert np.array_equal(q1, q2) and np.array_equal(s1, s2)
+    ref_q, ref_s = so.quantize_weight(inp["W"])
+    assert np.array_equal(q1, ref_q) and np.array_equal(s1.view(np.uint32), ref_s.view(np.uint32))
+    p1.destroy()
+    p2.destroy()
+
+
+@pytest.mark.parametrize("case", ["1d", "2d"])
+def test_stamp_inverse_entry_point(case):
+    """stamp_inverse alone on random STaMP-ordered input against the oracle's inverse."""
+    import torch
+    import paper_2510_26771_amd as st
+    if case == "1d":
+        w = _wl("inv1d", batch=2, seq_len=512, levels=9, k_hi=16, d_in=64, d_out=96)
+    else:
+        w = _wl("inv2d", batch=2, seq_len=1024, xform="haar2d", levels=5, grid_h=32, grid_w=32, k_hi=16, d_in=64,
+                d_out=96)
+    inp = make_inputs(w, with_bias=True)
+    plan = st.StampPlan(tl.plan_desc_for(w, "f32"), torch.from_numpy(inp["W"]).cuda(),
+                        torch.from_numpy(inp["bias"]).cuda())
+    rng = np.random.default_rng(5)
+    for ncols in (96, 37):
+        Yt = rng.standard_normal((w.batch, w.seq_len, ncols)).astype(np.float32)
+        ref = np.stack([so.sequence_inverse(Yt[b], w.xform, w.levels, w.grid_h, w.grid_w) for b in range(w.batch)])
+        if ncols == w.d_out:
+            ref = ref + inp["bias"][None, None, :]
+        Y = torch.empty((w.batch, w.seq_len, ncols), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(plan.workspace_bytes(), w.batch * w.k_hi * ncols * 4), dtype=torch.uint8, device="cuda")
+        plan.inverse(torch.from_numpy(Yt).cuda(), ncols, Y, ws)
+        torch.cuda.synchronize()
+        err = np.max(np.abs(Y.cpu().numpy() - ref)) / np.max(np.abs(ref))
+        assert err <= 1e-5, err
+    plan.destroy()
+
+
+def test_workspace_errors_on_device():
+    import torch
+    import paper_2510_26771_amd as st
+    w = _wl("ws", batch=1, seq_len=256, levels=8, k_hi=8, d_in=128, d_out=256)
+    inp = make_inputs(w)
+    plan = st.StampPlan(tl.plan_desc_for(w, "f32"), torch.from_numpy(inp["W"]).cuda())
+    X = tl.to_device_x(inp, w)
+    Y = torch.empty((1, 256, 256), dtype=torch.float32, device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(st.StampError) as e:
+        plan.linear_forward(X, Y, small)
+    assert e.value.status == 4
+    ws = plan.alloc_workspace()
+    with pytest.raises(st.StampError) as e:
+        plan.linear_forward(X, Y, ws[1:])  # misaligned
+    assert e.value.status == 4
+    plan.destroy()
+
+
+# ------------------------------------------------------------------------------------------------
+# Full benchmark sizes, in the launch configuration bench.py times.  Stage A (codes, scales) is
+# compared in full; the GEMM / inverse on a seeded sample of output columns the oracle can afford
+# (the inverse needs whole columns, so the sample is by column).
+# ------------------------------------------------------------------------------------------------
+def _sample_cols(N, n, seed):
+    rng = np.random.default_rng(seed)
+    cols = np.sort(rng.choice(N, size=n, replace=False))
+    cols[0], cols[-1] = 0, N - 1  # always include both edges
+    return np.unique(cols)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_full_size_llm_and_dit(name):
+    w = get_workload(name)
+    r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 7), check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+@pytest.mark.timeout(900)
+def test_full_size_cfg3():
+    w = get_workload("cfg3")
+    r = tl.full_case(w, y_dtype="bf16", cols=_sample_cols(w.d_out, 48, 8), check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+@pytest.mark.timeout(1200)
+def test_full_size_cfg5_benchmark_workload():
+    w = get_workload("cfg5")
+    r = tl.full_case(w, y_dtype="bf16", cols=_sample_cols(w.d_out, 48, 9), check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
