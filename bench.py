@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the STaMP quantized linear forward on one MI355X.
+
+One "step" is one call of stamp_linear_forward (sequence Haar transform + mixed-precision
+quantization + int8 MFMA GEMM + dequantization + inverse transform + bf16 store) over one batch of
+seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
+
+
+def log(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def stage_time_ms(fn, iters, torch):
+    """Average duration of one launch sequence `fn`, HIP events on the current stream."""
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def read_traffic(workload_name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"gemm_lo_{workload_name}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, inp, ncols):
+    """The oracle, as it stands, on a bounded sample: ONE sequence of the workload through the whole
+    layer, the GEMM / dequantization / inverse on the first `ncols` output columns, that part's time
+    scaled by d_out / ncols."""
+    import numpy as np
+    from oracle import stamp_oracle as so
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    X = inp["X_f32"][:1]
+    t0 = time.perf_counter()
+    qa = so.quantize_activation(X, w.xform, w.levels, w.k_hi, w.bits_hi, w.bits_lo, w.grid_h, w.grid_w)
+    t1 = time.perf_counter()
+    qw, sw = so.quantize_weight(inp["W"][:, :ncols], w.bits_w)   # plan-time work, not counted
+    t2 = time.perf_counter()
+    so.linear_from_codes(qa["codes"], qa["scales"], qw, sw, w.xform, w.levels, w.grid_h, w.grid_w)
+    t3 = time.perf_counter()
+    t_total = (t1 - t0) + (t3 - t2) * (w.d_out / ncols)
+    return {
+        "value": w.seq_len / t_total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"1 of {w.batch} sequences ({w.seq_len} tokens): transform+quantization in full "
+                   f"({t1 - t0:.2f} s, single-threaded numpy), integer GEMM (fp64 BLAS, {threads} threads) + "
+                   f"dequantization + inverse on the first {ncols} of {w.d_out} output columns "
+                   f"({t3 - t2:.2f} s, scaled x{w.d_out / ncols:.1f})"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--stage-iters", type=int, default=10)
+    ap.add_argument("--cpu-cols", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the STaMP linear layer on ONE GPU; --gpus N with N > 1 is not "
+              "supported (how the path would shard is described in DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2510_26771_amd as st
+    from gen import get_workload, make_inputs
+    import stamp_testlib as tl
+
+    st.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    w = get_workload(args.workload)
+    log(f"generating {w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out}")
+    inp = make_inputs(w)
+    Xd = tl.to_device_x(inp, w)
+    Wd = torch.from_numpy(inp["W"]).cuda()
+    plan = st.StampPlan(tl.plan_desc_for(w, "bf16"), Wd)
+    torch.cuda.synchronize()
+    del Wd
+    if args.unfused:
+        plan.set_unfused(True)
+    ws = plan.alloc_workspace()
+    Y = torch.empty((w.batch, w.seq_len, w.d_out), dtype=torch.int16, device="cuda")
+
+    def step():
+        plan.linear_forward(Xd, Y, ws)
+
+    log("warmup")
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens = w.batch * w.seq_len
+    log(f"{ms_per_step:.3f} ms/step")
+
+    # ---- per-stage timings (HIP events on the launch stream) ----
+    q_hi, q_lo, scales = plan.alloc_act_buffers()
+    plan.quantize_act(Xd, q_hi, q_lo, scales, ws)
+    stages = {}
+    names = {0: "transform_quant_lo", 1: "transform_quant_hi", 2: "gemm_hi", 3: "inverse_top", 4: "gemm_lo"}
+    if args.unfused:
+        names[5] = "inverse_bottom"
+    for sid, nm in names.items():
+        stages[nm] = stage_time_ms(lambda: plan.debug_run_stage(sid, Xd, q_hi, q_lo, scales, Y, ws),
+                                   args.stage_iters, torch)
+    stages["quantize_act"] = stage_time_ms(lambda: plan.quantize_act(Xd, q_hi, q_lo, scales, ws), args.stage_iters, torch)
+    log("stages ms: " + ", ".join(f"{k}={v:.4f}" for k, v in stages.items()))
+
+    # dominant kernel: the GEMM over the 4-bit rows.  Algorithmic work: 2 * rows * d_in * d_out int ops
+    lo_rows = w.batch * (w.seq_len - w.k_hi)
+    gemm_ops = 2.0 * lo_rows * w.d_in * w.d_out
+    achieved_tops = gemm_ops / (stages["gemm_lo"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": achieved_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": achieved_tops / PEAK_INT8_TOPS, "traffic": read_traffic(w.name),
+                "kernel": "k_gemm (4-bit rows" + (", dequant only)" if args.unfused else ", fused dequant + in-block inverse)"),
+                "ops_per_launch": gemm_ops, "avg_launch_ms": stages["gemm_lo"]}
+    # transform + quantization stage against the HBM roofline: X read + packed codes + scales written
+    xbytes = 2 if w.x_dtype == "bf16" else 4
+    qa_bytes = (w.batch * w.seq_len * w.d_in * xbytes + w.batch * w.k_hi * w.d_in
+                + w.batch * (w.seq_len - w.k_hi) * w.d_in // 2 + w.batch * w.seq_len * 4)
+    qa_gbs = qa_bytes / (stages["quantize_act"] * 1e-3) / 1e9
+    lo_bytes = (w.batch * w.seq_len * w.d_in * xbytes + w.batch * (w.seq_len - w.k_hi) * w.d_in // 2
+                + w.batch * (w.seq_len - w.k_hi) * 4 + w.batch * w.k_hi * w.d_in * 4)
+    lo_gbs = lo_bytes / (stages["transform_quant_lo"] * 1e-3) / 1e9
+    roofline_quant = {"bound": "hbm", "achieved": qa_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                      "frac": qa_gbs / PEAK_HBM_GBS, "bytes_per_call": qa_bytes,
+                      "stage": "stamp_quantize_act (3 kernels)",
+                      "dominant_kernel": {"name": "k_bottom", "achieved": lo_gbs, "frac": lo_gbs / PEAK_HBM_GBS,
+                                          "bytes_per_launch": lo_bytes, "avg_launch_ms": stages["transform_quant_lo"]}}
+
+    out = {
+        "metric": "tokens/sec through STaMP linear fwd", "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out} "
+                               f"{w.xform} J={w.levels} k_hi={w.k_hi} W4A4(+{w.k_hi} int8 tokens), bf16 in/out",
+                   "path": "unfused" if args.unfused else "fused"},
+        "roofline": roofline, "roofline_quant": roofline_quant, "stages_ms": stages,
+    }
+    if not args.no_cpu_baseline:
+        log("cpu baseline (oracle)")
+        out["cpu_baseline"] = cpu_baseline(w, inp, min(args.cpu_cols, w.d_out))
+    plan.destroy()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

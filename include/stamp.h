@@ -143,6 +143,18 @@ stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* plan, const int8_t* q_hi
  * Synchronizes the device. */
 stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* plan, int8_t* qW_host, float* sw_host);
 
+/* Launches ONE stage of stamp_linear_forward on its own, so that a benchmark can time it between
+ * two events (buffers exactly as stamp_linear_forward lays them out; q_hi/q_lo/scales as written by
+ * stamp_quantize_act, workspace as used by the preceding stages).  stage:
+ *   0 bottom-levels transform + 4-bit quantization kernel   1 top levels + 8-bit rows
+ *   2 GEMM of the 8-bit rows                                3 top levels of the inverse
+ *   4 GEMM of the 4-bit rows (with the fused inverse unless the plan is set unfused)
+ *   5 in-block inverse kernel (unfused plans only) */
+stamp_status_t stamp_debug_run_stage(const stamp_plan_t* plan, int32_t stage, const void* X_dev,
+                                     int8_t* q_hi_dev, uint8_t* q_lo_dev, float* scales_dev,
+                                     void* Y_dev, void* workspace_dev, size_t workspace_bytes,
+                                     void* hip_stream);
+
 /* Selects the implementation of steps 3-5: 0 = GEMM with the dequantization and the in-block
  * inverse transform fused into its epilogue (default where the shape allows it), 1 = GEMM writing
  * dequantized fp32 rows to the workspace followed by a separate inverse kernel. */

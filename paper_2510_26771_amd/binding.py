@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "STAMP_OK", 1: "STAMP_ERR_NULL", 2: "STAMP_ERR_SHAPE", 3: "ST
 # every symbol include/stamp.h declares
 EXPORTS = ["stamp_plan_create", "stamp_plan_destroy", "stamp_plan_workspace_bytes", "stamp_plan_row_of_coeff",
            "stamp_quantize_act", "stamp_linear_forward", "stamp_linear_forward_q", "stamp_inverse",
-           "stamp_debug_gemm_acc", "stamp_debug_weight_codes", "stamp_plan_set_unfused", "stamp_status_string"]
+           "stamp_debug_gemm_acc", "stamp_debug_weight_codes", "stamp_debug_run_stage", "stamp_plan_set_unfused", "stamp_status_string"]
 
 
 class StampError(RuntimeError):
@@ -97,6 +97,8 @@ def load_library():
     lib.stamp_debug_gemm_acc.restype = C.c_int
     lib.stamp_debug_weight_codes.argtypes = [vp, vp, vp]
     lib.stamp_debug_weight_codes.restype = C.c_int
+    lib.stamp_debug_run_stage.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.stamp_debug_run_stage.restype = C.c_int
     lib.stamp_plan_set_unfused.argtypes = [vp, i32]
     lib.stamp_plan_set_unfused.restype = C.c_int
     lib.stamp_status_string.argtypes = [C.c_int]
@@ -181,6 +183,11 @@ class StampPlan:
     def debug_gemm_acc(self, q_hi, q_lo, acc, stream=None):
         _check(self.lib.stamp_debug_gemm_acc(self._h, _ptr(q_hi), _ptr(q_lo), _ptr(acc), _stream(stream)),
                "stamp_debug_gemm_acc")
+
+    def debug_run_stage(self, stage, X, q_hi, q_lo, scales, Y, workspace, stream=None):
+        _check(self.lib.stamp_debug_run_stage(self._h, int(stage), _ptr(X), _ptr(q_hi), _ptr(q_lo), _ptr(scales),
+                                              _ptr(Y), _ptr(workspace), workspace.numel(), _stream(stream)),
+               "stamp_debug_run_stage")
 
     def debug_weight_codes(self):
         import numpy as np

@@ -465,7 +465,7 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
 }  // namespace
 
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
-                                 float* abot, uint32_t* rowmax, hipStream_t st) {
+                                 float* abot, uint32_t* rowmax, hipStream_t st, int part) {
   const StampGeom& g = p->geom;
   const int nthreads = ((g.d / 8 + 63) / 64) * 64;
   dim3 grid(g.k, g.B);
@@ -483,7 +483,9 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
     else                                                                                                  \
       hipLaunchKernelGGL((k_bottom2d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW); \
   } while (0)
-  if (!g.is2d) {
+  if (!(part & 1)) {
+    // bottom kernel skipped
+  } else if (!g.is2d) {
     switch (g.r) {
       case 3: LAUNCH1D(3); break;
       case 4: LAUNCH1D(4); break;
@@ -504,6 +506,7 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
 #undef LAUNCH2D
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (!(part & 2)) return hipSuccess;
   const size_t lds = (size_t)g.k * (kTopCh + 1) * sizeof(float);
   hipLaunchKernelGGL(k_top, dim3((g.d + kTopCh - 1) / kTopCh, g.B), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d,
                      g.G, g.r);

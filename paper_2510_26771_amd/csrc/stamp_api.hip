@@ -267,6 +267,33 @@ stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* p, const int8_t* q_hi, c
   return STAMP_OK;
 }
 
+stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const void* X, int8_t* q_hi, uint8_t* q_lo,
+                                     float* scales, void* Y, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (p == nullptr || X == nullptr || q_hi == nullptr || q_lo == nullptr || scales == nullptr || Y == nullptr)
+    return STAMP_ERR_NULL;
+  if (stage < 0 || stage > 5) return STAMP_ERR_SHAPE;
+  if (stage == 5 && p->fused_ok && !p->unfused) return STAMP_ERR_UNSUPPORTED;
+  if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  float* abot = reinterpret_cast<float*>(at(ws, p->ws_abot));
+  uint32_t* rowmax = reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax));
+  float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
+  float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
+  float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
+  const bool fused = p->fused_ok && !p->unfused;
+  hipError_t e = hipSuccess;
+  switch (stage) {
+    case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 1); break;
+    case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 2); break;
+    case 2: e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st); break;
+    case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, st); break;
+    case 4: e = fused ? stamp_launch_gemm_lo(p, q_lo, scales, 2, Y, P, st)
+                      : stamp_launch_gemm_lo(p, q_lo, scales, 1, ytlo, nullptr, st); break;
+    case 5: e = stamp_launch_inverse_bottom(p, ytlo, 0, P, p->geom.N, p->bias_dev, Y, st); break;
+  }
+  return e == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+}
+
 stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* p, int8_t* qW_host, float* sw_host) {
   if (p == nullptr || qW_host == nullptr || sw_host == nullptr) return STAMP_ERR_NULL;
   const int d = p->geom.d, N = p->geom.N;

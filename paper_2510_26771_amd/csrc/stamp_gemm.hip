@@ -10,19 +10,26 @@
 // factors 16 are exact powers of two and are folded into the row scale.
 //
 // Tile: 256 x 256 outputs per workgroup of 4 waves (2 x 2), 128 x 128 per wave = 4 x 4 MFMA blocks
-// of 32 x 32; K step 128 codes; both operands staged in LDS K-major (row / column contiguous),
-// double buffered, one barrier per K step.
+// of 32 x 32 (256 accumulator registers per lane); K step of 128 codes.  Both operands are staged in
+// LDS K-major (one row / column = one contiguous run of 64 or 128 bytes) in 16-byte chunks whose slot
+// is XOR-swizzled with the row number, so that the 16 lanes of a fragment read hit 16 distinct
+// 16-byte bank groups; two stages, one barrier per K step.  Lane group kg (lane / 32) of an MFMA
+// takes channels [64 kg + 16 ks, +16) of the step in sub-step ks: any assignment is valid as long
+// as both operands use it, and this one makes every fragment read a whole 16-byte chunk.
+// Workgroups are renumbered so that the 32 workgroups resident on one XCD cover 8 x 4 neighbouring
+// tiles and share operand panels in that XCD's L2.
 #include "stamp_internal.h"
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));  // first-class 16-byte value (keeps staging arrays in registers)
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BN = 256, BK = 128;
-constexpr int kStrideA4 = 80;    // bytes per LDS row of packed 4-bit A (64 data + 16 pad)
-constexpr int kStrideB = 144;    // bytes per LDS row of int8 operand (128 data + 16 pad)
-constexpr int kEpiStride = 33;   // floats per row of the per-wave epilogue staging tile
+constexpr int kEpiStride = 33;  // floats per row of the per-wave epilogue staging tile
+constexpr int kNumXcd = 8;
+constexpr int kGroupM = 8;
 
 constexpr float kInvSqrt2 = 0.70710678118654752440f;
 
@@ -41,50 +48,9 @@ struct GemmArgs {
   int M;                 // rows of A
   int N, Npad, Kpad;
   int a_row_bytes;       // valid bytes per A row
+  size_t a_last16;       // byte offset of the last 16-byte chunk of A (loads are clamped to it)
   StampGeom g;
 };
-
-// ---- in-register inverse of one block: x[e], e = in-block STaMP position -> natural token order ----
-template <int R>
-__device__ __forceinline__ void inverse_block_1d(float (&x)[R]) {
-  // stage m: sums a[0 .. 2^m) sit in x[0 .. 2^m), differences in x[2^m .. 2^(m+1))
-  float t[R];
-#pragma unroll
-  for (int n = 1; n < R; n <<= 1) {
-#pragma unroll
-    for (int i = 0; i < n; ++i) {
-      t[2 * i] = x[i] + x[n + i];
-      t[2 * i + 1] = x[i] - x[n + i];
-    }
-#pragma unroll
-    for (int i = 0; i < 2 * n; ++i) x[i] = t[i];
-  }
-}
-
-// 2-D: x[e] -> natural (y * g + x) order of a g x g block
-template <int GS>
-__device__ __forceinline__ void inverse_block_2d(float (&x)[GS * GS]) {
-  float t[GS * GS];
-#pragma unroll
-  for (int n = 1; n < GS; n <<= 1) {  // current side of the sum grid
-    // sums in x[0 .. n*n) row-major; bands W,H,D of side n at x[n*n*(1+band) + ...]
-#pragma unroll
-    for (int i = 0; i < n; ++i) {
-#pragma unroll
-      for (int j = 0; j < n; ++j) {
-        const float cLL = x[i * n + j], cW = x[n * n + i * n + j], cH = x[2 * n * n + i * n + j],
-                    cD = x[3 * n * n + i * n + j];
-        const float t0 = cLL + cH, t2 = cLL - cH, t1 = cW + cD, t3 = cW - cD;
-        t[(2 * i) * (2 * n) + 2 * j] = t0 + t1;
-        t[(2 * i) * (2 * n) + 2 * j + 1] = t0 - t1;
-        t[(2 * i + 1) * (2 * n) + 2 * j] = t2 + t3;
-        t[(2 * i + 1) * (2 * n) + 2 * j + 1] = t2 - t3;
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 4 * n * n; ++i) x[i] = t[i];
-  }
-}
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -93,47 +59,116 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
+struct OutCol {  // where one lane stores the tokens of one block, one output column
+  void* Y;
+  size_t base;        // element index of token 0 of the block, this column
+  size_t tok_stride;  // N
+  size_t row_stride;  // 2-D: gridW * N
+  float bias;
+  int bf16;
+  __device__ __forceinline__ void put(size_t idx, float v) const {
+    v += bias;
+    if (bf16) reinterpret_cast<uint16_t*>(Y)[idx] = f32_to_bf16_rne(v);
+    else reinterpret_cast<float*>(Y)[idx] = v;
+  }
+};
+
+// Depth-first inverse of one block for one column: node (M, I) holds the level-(r-M) sum `a` of its
+// subtree; col[e * kEpiStride] is the in-block coefficient at STaMP position e.  Only O(r) values are
+// live at any time; every coefficient is read once.
+template <int RLOG, int M, int I>
+__device__ __forceinline__ void dfs1d(const float* col, float a, const OutCol& o) {
+  if constexpr (M == RLOG) {
+    o.put(o.base + (size_t)I * o.tok_stride, a);
+  } else {
+    const float d = col[((1 << M) + I) * kEpiStride];
+    dfs1d<RLOG, M + 1, 2 * I>(col, a + d, o);
+    dfs1d<RLOG, M + 1, 2 * I + 1>(col, a - d, o);
+  }
+}
+
+template <int RLOG, int M, int IY, int IX>
+__device__ __forceinline__ void dfs2d(const float* col, float a, const OutCol& o) {
+  if constexpr (M == RLOG) {
+    o.put(o.base + (size_t)IY * o.row_stride + (size_t)IX * o.tok_stride, a);
+  } else {
+    constexpr int gl = 1 << M;
+    constexpr int e0 = IY * gl + IX;
+    const float cW = col[(gl * gl + e0) * kEpiStride];
+    const float cH = col[(2 * gl * gl + e0) * kEpiStride];
+    const float cD = col[(3 * gl * gl + e0) * kEpiStride];
+    const float t0 = a + cH, t2 = a - cH, t1 = cW + cD, t3 = cW - cD;
+    dfs2d<RLOG, M + 1, 2 * IY, 2 * IX>(col, t0 + t1, o);
+    dfs2d<RLOG, M + 1, 2 * IY, 2 * IX + 1>(col, t0 - t1, o);
+    dfs2d<RLOG, M + 1, 2 * IY + 1, 2 * IX>(col, t2 + t3, o);
+    dfs2d<RLOG, M + 1, 2 * IY + 1, 2 * IX + 1>(col, t2 - t3, o);
+  }
+}
+
 // EPI: 0 = int32 accumulators to STaMP-ordered rows; 1 = dequantized fp32 rows (lo: physical rows of
 // [B*s][N]; hi: [B*k][N]); 2 = fused in-block inverse + bias -> Y (A_INT4 only); RB = log2 of the
 // block length for EPI 2 (1-D: tokens, 2-D: side).
 template <bool A_INT4, int EPI, int RB, bool IS2D>
 __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  constexpr int strideA = A_INT4 ? kStrideA4 : kStrideB;
-  constexpr int bytesA = BM * strideA, bytesB = BN * kStrideB;
+  constexpr int rowA = A_INT4 ? 64 : 128;       // bytes per A row per K step
+  constexpr int chA = rowA / 16;                // 16-byte chunks per A row (4 or 8)
+  constexpr int bytesA = BM * rowA, bytesB = BN * 128;
   constexpr int stage = bytesA + bytesB;
-  constexpr int a_chunks = A_INT4 ? 4 : 8;  // 16-byte chunks per A row per K step
+  constexpr int nA = chA;                       // A chunks per thread per step (256 rows * chA / 256 threads)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int ntn = a.Npad / BN;
-  const int tn = blockIdx.x % ntn, tm = blockIdx.x / ntn;
-  const int m0 = tm * BM, n0 = tn * BN;
+  const int l32 = lane & 31, kg = lane >> 5;
 
-  // global source of this thread: A row m0 + tid, B column n0 + tid
-  const int arow = min(m0 + tid, a.M - 1);
-  const uint8_t* gA = a.A + (size_t)arow * a.a_row_bytes;
-  const int8_t* gB = a.Bq + (size_t)(n0 + tid) * a.Kpad;
+  // ---- workgroup -> tile, XCD aware: consecutive ids on one XCD walk 8 M-tiles, then the next N-tile ----
+  const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
+  int tm, tn;
+  {
+    const int total = mt * nt;
+    const int bid = blockIdx.x;
+    const int xcd = bid % kNumXcd, local = bid / kNumXcd;
+    const int tall = total / kNumXcd, rem = total % kNumXcd;
+    const int sid = xcd * tall + min(xcd, rem) + local;
+    const int per_group = kGroupM * nt;
+    const int grp = sid / per_group, in_grp = sid - grp * per_group;
+    const int gm = min(kGroupM, mt - grp * kGroupM);
+    tm = grp * kGroupM + in_grp % gm;
+    tn = in_grp / gm;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
   const int KT = a.Kpad / BK;
 
-  uint4 ra[a_chunks], rb[8];
-  auto gload = [&](int kt) {
+  // ---- global -> LDS assignment: chunk q = i * 256 + tid of the tile, consecutive lanes = consecutive
+  //      chunks.  Row / column of chunk i is (row0 + i * rows_per_pass); its swizzled slot does not
+  //      depend on i, so one base address per operand and a uniform stride per pass suffice. ----
+  constexpr int rowsPerPassA = 256 / chA;  // 64 (4-bit) or 32 (8-bit) rows per pass of 256 threads
+  const int rowA0 = tid / chA, slotA = tid % chA;
+  const int cA = A_INT4 ? (slotA ^ ((rowA0 >> 2) & 3)) : (slotA ^ ((rowA0 >> 1) & 7));
+  const int koffA = cA * 16;
+  // Byte offset of this thread's chunk in pass i (rows beyond M re-read row M-1).  Chunks past the end
+  // of a row (K tail of the last step) are still loaded -- from the next row, clamped to the buffer --
+  // because the stored weights are zero there, so whatever codes arrive contribute nothing.
+  size_t offA[nA];
 #pragma unroll
-    for (int c = 0; c < a_chunks; ++c) {
-      const int off = kt * (A_INT4 ? 64 : 128) + c * 16;
-      ra[c] = (off < a.a_row_bytes) ? *reinterpret_cast<const uint4*>(gA + off) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int c = 0; c < 8; ++c) rb[c] = *reinterpret_cast<const uint4*>(gB + kt * BK + c * 16);
-  };
-  auto sstore = [&](int buf) {
-    uint8_t* sA = smem + buf * stage + tid * strideA;
-    uint8_t* sB = smem + buf * stage + bytesA + tid * kStrideB;
-#pragma unroll
-    for (int c = 0; c < a_chunks; ++c) *reinterpret_cast<uint4*>(sA + c * 16) = ra[c];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) *reinterpret_cast<uint4*>(sB + c * 16) = rb[c];
-  };
+  for (int i = 0; i < nA; ++i)
+    offA[i] = (size_t)min(m0 + rowA0 + i * rowsPerPassA, a.M - 1) * a.a_row_bytes + koffA;
+  const int colB0 = tid >> 3, slotB = tid & 7;
+  const int cB = slotB ^ ((colB0 >> 1) & 7);
+  const int8_t* gB0 = a.Bq + (size_t)(n0 + colB0) * a.Kpad + cB * 16;
+  const size_t strideB = (size_t)32 * a.Kpad;  // 32 columns per pass
+
+  // ---- LDS -> fragment addresses (bytes inside a stage).  The swizzle term of a row depends only on
+  //      lane bits, and sub-step ks enters through an XOR of bits 4-5, so per operand one base per lane
+  //      is enough: address(block i, ks) = (base ^ (ks << 4)) + i * block_stride. ----
+  int baseA, baseB;
+  {
+    const int r = wm * 128 + l32;
+    baseA = A_INT4 ? (r * 64 + (((2 * kg) ^ ((r >> 2) & 3)) << 4)) : (r * 128 + (((4 * kg) ^ ((r >> 1) & 7)) << 4));
+    const int n = wn * 128 + l32;
+    baseB = bytesA + n * 128 + (((4 * kg) ^ ((n >> 1) & 7)) << 4);
+  }
+  constexpr int blkA = 32 * rowA, blkB = 32 * 128;  // LDS bytes between consecutive 32-row blocks
 
   v16i acc[4][4];
 #pragma unroll
@@ -143,48 +178,109 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-  gload(0);
-  sstore(0);
+  u4 ra[nA], rb[8];
+
+  // prologue: step 0 -> stage 0
+  {
+#pragma unroll
+    for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i], a.a_last16));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB);
+#pragma unroll
+    for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(smem + (i * 256 + tid) * 16) = ra[i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<u4*>(smem + bytesA + (i * 256 + tid) * 16) = rb[i];
+  }
   __syncthreads();
 
-  const int l32 = lane & 31, kg = lane >> 5;
   for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) gload(kt + 1);
-    const uint8_t* sA = smem + buf * stage + (wm * 128 + l32) * strideA;
-    const uint8_t* sB = smem + buf * stage + bytesA + (wn * 128 + l32) * kStrideB;
+    const uint8_t* st = smem + (kt & 1) * stage;
+    const bool more = (kt + 1) < KT;
+    if (more) {
+      const int ka = (kt + 1) * rowA, kb = (kt + 1) * BK;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      v4i fa[4], fb[4];
+      for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i] + ka, a.a_last16));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB + kb);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    v4i fb[2][4];
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+      const u4 w = *reinterpret_cast<const u4*>(st + baseB + ni * blkB);
+      fb[0][ni][0] = (int)w.x; fb[0][ni][1] = (int)w.y; fb[0][ni][2] = (int)w.z; fb[0][ni][3] = (int)w.w;
+    }
+    if constexpr (A_INT4) {
+      u4 pa[4][2];
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
-        if constexpr (A_INT4) {
-          const uint2 w = *reinterpret_cast<const uint2*>(sA + mi * 32 * strideA + ks * 16 + kg * 8);
-          fa[mi][0] = (int)((w.x << 4) & 0xF0F0F0F0u);
-          fa[mi][1] = (int)(w.x & 0xF0F0F0F0u);
-          fa[mi][2] = (int)((w.y << 4) & 0xF0F0F0F0u);
-          fa[mi][3] = (int)(w.y & 0xF0F0F0F0u);
-        } else {
-          const uint4 w = *reinterpret_cast<const uint4*>(sA + mi * 32 * strideA + ks * 32 + kg * 16);
-          // natural channel order -> the order of the stored weights: evens then odds per 8 channels
-          fa[mi][0] = (int)__builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
-          fa[mi][1] = (int)__builtin_amdgcn_perm(w.y, w.x, 0x07050301u);
-          fa[mi][2] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x06040200u);
-          fa[mi][3] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x07050301u);
+        pa[mi][0] = *reinterpret_cast<const u4*>(st + baseA + mi * blkA);
+        pa[mi][1] = *reinterpret_cast<const u4*>(st + (baseA ^ 16) + mi * blkA);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (ks < 3) {
+#pragma unroll
+          for (int ni = 0; ni < 4; ++ni) {
+            const u4 w = *reinterpret_cast<const u4*>(st + (baseB ^ ((ks + 1) << 4)) + ni * blkB);
+            fb[(ks + 1) & 1][ni][0] = (int)w.x; fb[(ks + 1) & 1][ni][1] = (int)w.y;
+            fb[(ks + 1) & 1][ni][2] = (int)w.z; fb[(ks + 1) & 1][ni][3] = (int)w.w;
+          }
         }
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+          const u4 p = pa[mi][ks >> 1];
+          const uint32_t w0 = (ks & 1) ? p.z : p.x, w1 = (ks & 1) ? p.w : p.y;
+          v4i fa;
+          fa[0] = (int)((w0 << 4) & 0xF0F0F0F0u);
+          fa[1] = (int)(w0 & 0xF0F0F0F0u);
+          fa[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
+          fa[3] = (int)(w1 & 0xF0F0F0F0u);
+#pragma unroll
+          for (int ni = 0; ni < 4; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb[ks & 1][ni], acc[mi][ni], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
+    } else {
 #pragma unroll
-      for (int ni = 0; ni < 4; ++ni) {
-        const uint4 w = *reinterpret_cast<const uint4*>(sB + ni * 32 * kStrideB + ks * 32 + kg * 16);
-        fb[ni][0] = (int)w.x; fb[ni][1] = (int)w.y; fb[ni][2] = (int)w.z; fb[ni][3] = (int)w.w;
+      for (int ks = 0; ks < 4; ++ks) {
+        u4 wa[4];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) wa[mi] = *reinterpret_cast<const u4*>(st + (baseA ^ (ks << 4)) + mi * blkA);
+        if (ks < 3) {
+#pragma unroll
+          for (int ni = 0; ni < 4; ++ni) {
+            const u4 w = *reinterpret_cast<const u4*>(st + (baseB ^ ((ks + 1) << 4)) + ni * blkB);
+            fb[(ks + 1) & 1][ni][0] = (int)w.x; fb[(ks + 1) & 1][ni][1] = (int)w.y;
+            fb[(ks + 1) & 1][ni][2] = (int)w.z; fb[(ks + 1) & 1][ni][3] = (int)w.w;
+          }
+        }
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+          const u4 w = wa[mi];
+          // natural channel order -> the order of the stored weights: evens then odds per 8 channels
+          v4i fa;
+          fa[0] = (int)__builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
+          fa[1] = (int)__builtin_amdgcn_perm(w.y, w.x, 0x07050301u);
+          fa[2] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x06040200u);
+          fa[3] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x07050301u);
+#pragma unroll
+          for (int ni = 0; ni < 4; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb[ks & 1][ni], acc[mi][ni], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
     }
-    if (kt + 1 < KT) sstore(buf ^ 1);
+
+    if (more) {
+      uint8_t* so = smem + ((kt + 1) & 1) * stage;
+#pragma unroll
+      for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(so + (i * 256 + tid) * 16) = ra[i];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u4*>(so + bytesA + (i * 256 + tid) * 16) = rb[i];
+    }
     __syncthreads();
   }
 
@@ -193,8 +289,8 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   // + v % 4, column 32 ni + l % 32 of the wave tile.
   // ------------------------------------------------------------------------------------------
   const StampGeom& g = a.g;
-  float* s_rowfac = reinterpret_cast<float*>(smem);            // [256]
-  int* s_rowdst = reinterpret_cast<int*>(smem + 1024);         // [256] destination row or -1
+  float* s_rowfac = reinterpret_cast<float*>(smem);     // [256]
+  int* s_rowdst = reinterpret_cast<int*>(smem + 1024);  // [256] destination row or -1
   {
     const int m = m0 + tid;
     float fac = 0.0f;
@@ -252,8 +348,8 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
       }
     }
   } else {
-    // fused: per 32-column strip, dequantize into this wave's LDS tile [128][33], then each lane takes
-    // one column of one block, inverts it in registers and stores R tokens.
+    // fused: per 32-column strip, dequantize into this wave's LDS tile [128][33]; then each lane takes
+    // one column of one block at a time and runs the depth-first inverse, storing the block's tokens.
     constexpr int R = IS2D ? (1 << (2 * RB)) : (1 << RB);
     constexpr int nblk = 128 / R;  // blocks per wave tile
     float* s_tile = reinterpret_cast<float*>(smem + 2048) + wave * (128 * kEpiStride);
@@ -261,7 +357,12 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
     for (int ni = 0; ni < 4; ++ni) {
       const int n = n0 + wn * 128 + ni * 32 + l32;
       const float swn = a.sw[n];
-      const float bias_n = (a.bias != nullptr) ? a.bias[n] : 0.0f;
+      OutCol o;
+      o.Y = a.out;
+      o.tok_stride = (size_t)a.N;
+      o.row_stride = (size_t)g.gridW * a.N;
+      o.bias = (a.bias != nullptr) ? a.bias[n] : 0.0f;
+      o.bf16 = g.y_bf16;
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
@@ -271,35 +372,21 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
         }
       }
       __syncthreads();
+#pragma unroll 1
       for (int blk = kg; blk < nblk; blk += 2) {
         const int mrow = m0 + wm * 128 + blk * R;  // physical row of e = 0 of this block
         if (mrow < a.M && n < a.N) {
           const int b = mrow / g.s, pr = mrow - b * g.s;
           const int j = pr / g.R;
-          float x[R];
-#pragma unroll
-          for (int e = 1; e < R; ++e) x[e] = s_tile[(blk * R + e) * kEpiStride + l32];
-          x[0] = a.P[((size_t)b * g.k + j) * a.N + n];
-          size_t tok0;
-          int tstride_row;
+          const float top = a.P[((size_t)b * g.k + j) * a.N + n];
+          const float* col = s_tile + blk * R * kEpiStride + l32;
           if constexpr (IS2D) {
-            inverse_block_2d<(1 << RB)>(x);
             const int bi = j / g.G, bj = j - bi * g.G;
-            tok0 = (size_t)b * g.s + (size_t)(bi << RB) * g.gridW + (size_t)(bj << RB);
-            tstride_row = g.gridW;
+            o.base = ((size_t)b * g.s + (size_t)(bi << RB) * g.gridW + (size_t)(bj << RB)) * a.N + n;
+            dfs2d<RB, 0, 0, 0>(col, top, o);
           } else {
-            inverse_block_1d<R>(x);
-            tok0 = (size_t)b * g.s + (size_t)j * R;
-            tstride_row = 0;
-          }
-#pragma unroll
-          for (int t = 0; t < R; ++t) {
-            size_t tok;
-            if constexpr (IS2D) tok = tok0 + (size_t)(t >> RB) * tstride_row + (t & ((1 << RB) - 1));
-            else tok = tok0 + t;
-            const float y = x[t] + bias_n;
-            if (g.y_bf16) reinterpret_cast<uint16_t*>(a.out)[tok * a.N + n] = f32_to_bf16_rne(y);
-            else reinterpret_cast<float*>(a.out)[tok * a.N + n] = y;
+            o.base = ((size_t)b * g.s + (size_t)j * R) * a.N + n;
+            dfs1d<RB, 0, 0>(col, top, o);
           }
         }
       }
@@ -310,8 +397,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 
 template <bool A_INT4, int EPI, int RB, bool IS2D>
 hipError_t launch(const GemmArgs& a, hipStream_t st) {
-  constexpr int strideA = A_INT4 ? kStrideA4 : kStrideB;
-  constexpr size_t main_lds = 2 * (size_t)(BM * strideA + BN * kStrideB);
+  constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
   constexpr size_t epi_lds = 2048 + 4 * 128 * kEpiStride * sizeof(float);
   constexpr size_t lds = main_lds > epi_lds ? main_lds : epi_lds;
   static bool attr_set = false;
@@ -341,6 +427,7 @@ GemmArgs make_args(const stamp_plan* p, const float* scales, void* out) {
   a.A = nullptr;
   a.M = 0;
   a.a_row_bytes = 0;
+  a.a_last16 = 0;
   return a;
 }
 
@@ -352,6 +439,7 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
   a.A = reinterpret_cast<const uint8_t*>(q_hi);
   a.M = p->geom.B * p->geom.k;
   a.a_row_bytes = p->geom.d;
+  a.a_last16 = (size_t)a.M * a.a_row_bytes - 16;
   if (mode == 0) return launch<false, 0, 0, false>(a, st);
   if (mode == 1) return launch<false, 1, 0, false>(a, st);
   return hipErrorInvalidValue;
@@ -363,6 +451,7 @@ hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const 
   a.A = q_lo;
   a.M = p->geom.B * p->geom.s;
   a.a_row_bytes = p->geom.d / 2;
+  a.a_last16 = (size_t)a.M * a.a_row_bytes - 16;
   a.P = P;
   if (mode == 0) return launch<true, 0, 0, false>(a, st);
   if (mode == 1) return launch<true, 1, 0, false>(a, st);

@@ -93,8 +93,9 @@ struct stamp_plan {
 
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
 hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStream_t st, uint32_t* colmax_tmp);
+// part: 1 = bottom kernel only, 2 = top + 8-bit rows only, 3 = both
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo,
-                                 float* scales, float* abot, uint32_t* rowmax, hipStream_t st);
+                                 float* scales, float* abot, uint32_t* rowmax, hipStream_t st, int part = 3);
 // mode: 0 = int32 accumulators in STaMP row order (debug), 1 = dequantized fp32 rows (hi -> Yt_hi
 // [B*k, N], lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y.
 hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode,

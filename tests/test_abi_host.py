@@ -87,6 +87,7 @@ def test_null_arguments(lib):
     assert lib.stamp_inverse(None, None, 1, None, None, 0, None) == 1
     assert lib.stamp_debug_gemm_acc(None, None, None, None, None) == 1
     assert lib.stamp_debug_weight_codes(None, None, None) == 1
+    assert lib.stamp_debug_run_stage(None, 0, None, None, None, None, None, None, 0, None) == 1
     assert lib.stamp_plan_set_unfused(None, 1) == 1
 
 
