@@ -18,6 +18,8 @@
 // as both operands use it, and this one makes every fragment read a whole 16-byte chunk.
 // Workgroups are renumbered so that the 32 workgroups resident on one XCD cover 8 x 4 neighbouring
 // tiles and share operand panels in that XCD's L2.
+#include <cstdlib>
+
 #include "stamp_internal.h"
 
 namespace {
@@ -26,7 +28,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));  // first-class 16-byte value (keeps staging arrays in registers)
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int BM = 256, BK = 128;  // BN = 64 * NI (NI = 32-column MFMA blocks per wave along N)
 constexpr int kEpiStride = 33;  // floats per row of the per-wave epilogue staging tile
 constexpr int kNumXcd = 8;
 constexpr int kGroupM = 8;
@@ -108,8 +110,10 @@ __device__ __forceinline__ void dfs2d(const float* col, float a, const OutCol& o
 // EPI: 0 = int32 accumulators to STaMP-ordered rows; 1 = dequantized fp32 rows (lo: physical rows of
 // [B*s][N]; hi: [B*k][N]); 2 = fused in-block inverse + bias -> Y (A_INT4 only); RB = log2 of the
 // block length for EPI 2 (1-D: tokens, 2-D: side).
-template <bool A_INT4, int EPI, int RB, bool IS2D>
-__global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
+template <bool A_INT4, int EPI, int RB, bool IS2D, int NI>
+__global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs a) {
+  constexpr int BN = 64 * NI;
+  constexpr int nB = BN / 32;                   // B chunks per thread per step (BN columns * 8 chunks / 256 threads)
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   constexpr int rowA = A_INT4 ? 64 : 128;       // bytes per A row per K step
   constexpr int chA = rowA / 16;                // 16-byte chunks per A row (4 or 8)
@@ -118,7 +122,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   constexpr int nA = chA;                       // A chunks per thread per step (256 rows * chA / 256 threads)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 1, wn = wave & 1;  // wave tile: rows [128 wm, +128), columns [32 NI wn, +32 NI)
   const int l32 = lane & 31, kg = lane >> 5;
 
   // ---- workgroup -> tile, XCD aware: consecutive ids on one XCD walk 8 M-tiles, then the next N-tile ----
@@ -165,31 +169,31 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   {
     const int r = wm * 128 + l32;
     baseA = A_INT4 ? (r * 64 + (((2 * kg) ^ ((r >> 2) & 3)) << 4)) : (r * 128 + (((4 * kg) ^ ((r >> 1) & 7)) << 4));
-    const int n = wn * 128 + l32;
+    const int n = wn * (32 * NI) + l32;
     baseB = bytesA + n * 128 + (((4 * kg) ^ ((n >> 1) & 7)) << 4);
   }
   constexpr int blkA = 32 * rowA, blkB = 32 * 128;  // LDS bytes between consecutive 32-row blocks
 
-  v16i acc[4][4];
+  v16i acc[4][NI];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-  u4 ra[nA], rb[8];
+  u4 ra[nA], rb[nB];
 
   // prologue: step 0 -> stage 0
   {
 #pragma unroll
     for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i], a.a_last16));
 #pragma unroll
-    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB);
+    for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB);
 #pragma unroll
     for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(smem + (i * 256 + tid) * 16) = ra[i];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) *reinterpret_cast<u4*>(smem + bytesA + (i * 256 + tid) * 16) = rb[i];
+    for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(smem + bytesA + (i * 256 + tid) * 16) = rb[i];
   }
   __syncthreads();
 
@@ -201,13 +205,13 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 #pragma unroll
       for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i] + ka, a.a_last16));
 #pragma unroll
-      for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB + kb);
+      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB + kb);
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    v4i fb[2][4];
+    v4i fb[2][NI];
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
+    for (int ni = 0; ni < NI; ++ni) {
       const u4 w = *reinterpret_cast<const u4*>(st + baseB + ni * blkB);
       fb[0][ni][0] = (int)w.x; fb[0][ni][1] = (int)w.y; fb[0][ni][2] = (int)w.z; fb[0][ni][3] = (int)w.w;
     }
@@ -222,7 +226,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
       for (int ks = 0; ks < 4; ++ks) {
         if (ks < 3) {
 #pragma unroll
-          for (int ni = 0; ni < 4; ++ni) {
+          for (int ni = 0; ni < NI; ++ni) {
             const u4 w = *reinterpret_cast<const u4*>(st + (baseB ^ ((ks + 1) << 4)) + ni * blkB);
             fb[(ks + 1) & 1][ni][0] = (int)w.x; fb[(ks + 1) & 1][ni][1] = (int)w.y;
             fb[(ks + 1) & 1][ni][2] = (int)w.z; fb[(ks + 1) & 1][ni][3] = (int)w.w;
@@ -238,7 +242,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
           fa[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
           fa[3] = (int)(w1 & 0xF0F0F0F0u);
 #pragma unroll
-          for (int ni = 0; ni < 4; ++ni)
+          for (int ni = 0; ni < NI; ++ni)
             acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb[ks & 1][ni], acc[mi][ni], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -251,7 +255,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
         for (int mi = 0; mi < 4; ++mi) wa[mi] = *reinterpret_cast<const u4*>(st + (baseA ^ (ks << 4)) + mi * blkA);
         if (ks < 3) {
 #pragma unroll
-          for (int ni = 0; ni < 4; ++ni) {
+          for (int ni = 0; ni < NI; ++ni) {
             const u4 w = *reinterpret_cast<const u4*>(st + (baseB ^ ((ks + 1) << 4)) + ni * blkB);
             fb[(ks + 1) & 1][ni][0] = (int)w.x; fb[(ks + 1) & 1][ni][1] = (int)w.y;
             fb[(ks + 1) & 1][ni][2] = (int)w.z; fb[(ks + 1) & 1][ni][3] = (int)w.w;
@@ -267,7 +271,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
           fa[2] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x06040200u);
           fa[3] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x07050301u);
 #pragma unroll
-          for (int ni = 0; ni < 4; ++ni)
+          for (int ni = 0; ni < NI; ++ni)
             acc[mi][ni] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb[ks & 1][ni], acc[mi][ni], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 #pragma unroll
       for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(so + (i * 256 + tid) * 16) = ra[i];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<u4*>(so + bytesA + (i * 256 + tid) * 16) = rb[i];
+      for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(so + bytesA + (i * 256 + tid) * 16) = rb[i];
     }
     __syncthreads();
   }
@@ -328,8 +332,8 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
 
   if constexpr (EPI == 0 || EPI == 1) {
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-      const int n = n0 + wn * 128 + ni * 32 + l32;
+    for (int ni = 0; ni < NI; ++ni) {
+      const int n = n0 + wn * (32 * NI) + ni * 32 + l32;
       const float swn = a.sw[n];
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
@@ -354,8 +358,8 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
     constexpr int nblk = 128 / R;  // blocks per wave tile
     float* s_tile = reinterpret_cast<float*>(smem + 2048) + wave * (128 * kEpiStride);
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-      const int n = n0 + wn * 128 + ni * 32 + l32;
+    for (int ni = 0; ni < NI; ++ni) {
+      const int n = n0 + wn * (32 * NI) + ni * 32 + l32;
       const float swn = a.sw[n];
       OutCol o;
       o.Y = a.out;
@@ -395,21 +399,38 @@ __global__ __launch_bounds__(256) void k_gemm(const GemmArgs a) {
   }
 }
 
-template <bool A_INT4, int EPI, int RB, bool IS2D>
-hipError_t launch(const GemmArgs& a, hipStream_t st) {
+template <bool A_INT4, int EPI, int RB, bool IS2D, int NI>
+hipError_t launch_ni(const GemmArgs& a, hipStream_t st) {
+  constexpr int BN = 64 * NI;
   constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
   constexpr size_t epi_lds = 2048 + 4 * 128 * kEpiStride * sizeof(float);
   constexpr size_t lds = main_lds > epi_lds ? main_lds : epi_lds;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, NI>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
-  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D>), dim3(mt * nt), dim3(256), lds, st, a);
+  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, NI>), dim3(mt * nt), dim3(256), lds, st, a);
   return hipGetLastError();
+}
+
+// Tile width: 128 (two workgroups per CU, default) or 256 (one per CU); STAMP_GEMM_TILE_N overrides (tuning aid).
+int gemm_ni() {
+  static int ni = 0;
+  if (ni == 0) {
+    const char* e = getenv("STAMP_GEMM_TILE_N");
+    ni = (e != nullptr && atoi(e) == 256) ? 4 : 2;
+  }
+  return ni;
+}
+
+template <bool A_INT4, int EPI, int RB, bool IS2D>
+hipError_t launch(const GemmArgs& a, hipStream_t st) {
+  if (gemm_ni() == 4) return launch_ni<A_INT4, EPI, RB, IS2D, 4>(a, st);
+  return launch_ni<A_INT4, EPI, RB, IS2D, 2>(a, st);
 }
 
 GemmArgs make_args(const stamp_plan* p, const float* scales, void* out) {
