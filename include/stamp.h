@@ -42,9 +42,14 @@
  *     scales  [batch, seq_len] float: scale of the coefficient at physical row r.
  *     q_hi    [batch, k_hi, d_in] int8: the 8-bit tokens; STaMP slot p < k_hi is row p of q_hi
  *             (its physical row is p*R).
- *     q_lo    [batch, seq_len, d_in/2] bytes: the 4-bit tokens at their physical row; two's
- *             complement nibbles, low nibble = even channel.  Rows r with r % R == 0 (the rows
- *             whose coefficient lives in q_hi) are never written nor read.
+ *     q_lo    the 4-bit tokens at their physical row, two channels per byte (two's complement
+ *             nibbles, low nibble = even channel), tiled for the GEMM: with m = b*seq_len + r the
+ *             row over all sequences, Kp = d_in rounded up to 128 and Mp = batch*seq_len rounded
+ *             up to 256, the byte of channels (c, c+1), c even, is at
+ *               (((m / 256) * (Kp / 128) + c / 128) * 256 + m % 256) * 64 + (c % 128) / 2,
+ *             i.e. [Mp/256][Kp/128][256 rows][64 bytes]; the buffer holds Mp * Kp / 2 bytes.
+ *             Rows r with r % R == 0 (the rows whose coefficient lives in q_hi), rows >= batch *
+ *             seq_len and channels >= d_in are never written and their content is ignored.
  */
 #ifndef STAMP_H_
 #define STAMP_H_

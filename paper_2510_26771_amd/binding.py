@@ -201,6 +201,8 @@ class StampPlan:
         import torch
         d = self.desc
         q_hi = torch.empty((d.batch, d.k_hi, d.d_in), dtype=torch.int8, device=device)
-        q_lo = torch.zeros((d.batch, d.seq_len, d.d_in // 2), dtype=torch.uint8, device=device)
+        mp = -(-(d.batch * d.seq_len) // 256) * 256
+        kp = -(-d.d_in // 128) * 128
+        q_lo = torch.zeros(mp * kp // 2, dtype=torch.uint8, device=device)  # tiled, see include/stamp.h
         scales = torch.zeros((d.batch, d.seq_len), dtype=torch.float32, device=device)
         return q_hi, q_lo, scales

@@ -100,8 +100,8 @@ struct RowMeta { int level; int e; };
 
 template <int NR, bool IS2D, typename MetaFn>
 __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[32],
-                                           uint8_t* q_lo_blk /* row e=0 of this block */, float* scales_blk,
-                                           int d, int c0, bool active, int tid) {
+                                           uint8_t* q_lo_thr /* this thread's 4 bytes of row e=0 of the block */,
+                                           float* scales_blk, bool active, int tid) {
   const int lane = tid & 63;
   const int buf = step % 3;
 #pragma unroll
@@ -144,7 +144,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
       for (int c = 0; c < 8; ++c) p[c] = __fmul_rn(__fmul_rn(rowv[r][c], nrm), mul);
     }
     const uint32_t w = pack8_int4(p);
-    if (active) *reinterpret_cast<uint32_t*>(q_lo_blk + (size_t)rm.e * (size_t)(d >> 1) + (c0 >> 1)) = w;
+    if (active) *reinterpret_cast<uint32_t*>(q_lo_thr + rm.e * 64) = w;  // tiled layout: 64 bytes per row and K step
   }
 }
 
@@ -219,7 +219,7 @@ __device__ __forceinline__ void step1d(const void* X, size_t blk_elem_off, int d
     else { m.level = r - 3; m.e = (R >> (r - 3)) + (IT >> (r - 6)); }
     return m;
   };
-  flush_rows<NR, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, d, c0, active, tid);
+  flush_rows<NR, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, active, tid);
 }
 
 template <int RLOG, bool BF16, int NP, int... ITS>
@@ -232,7 +232,7 @@ __device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const 
 template <int RLOG, bool BF16>
 __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
                                                    float* __restrict__ scales, float* __restrict__ abot,
-                                                   uint32_t* __restrict__ rowmax, int s, int d, int k) {
+                                                   uint32_t* __restrict__ rowmax, int s, int d, int k, int Kpad) {
   constexpr int R = 1 << RLOG;
   constexpr int NP = RLOG > 3 ? RLOG - 3 : 1;
   __shared__ uint32_t s_max[3][32];
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, u
   float pend[NP][8];
   float top[8];
   run1d<RLOG, BF16, NP>(std::make_integer_sequence<int, R / 8>{}, X, row0 * d + c0, d, c0, active, tid, pend, top,
-                        s_max, q_lo + row0 * (size_t)(d >> 1), scales + row0);
+                        s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -321,7 +321,7 @@ __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int g
     }
     return m;
   };
-  flush_rows<NR, true>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, d, c0, active, tid);
+  flush_rows<NR, true>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, active, tid);
 }
 
 template <int RLOG, bool BF16, int... SBS>
@@ -334,7 +334,8 @@ __device__ __forceinline__ void run2d(std::integer_sequence<int, SBS...>, const 
 template <int RLOG, bool BF16>
 __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
                                                   float* __restrict__ scales, float* __restrict__ abot,
-                                                  uint32_t* __restrict__ rowmax, int s, int d, int G, int gridW) {
+                                                  uint32_t* __restrict__ rowmax, int s, int d, int G, int gridW,
+                                                  int Kpad) {
   constexpr int g = 1 << RLOG;
   constexpr int R = g * g;
   __shared__ uint32_t s_max[3][32];
@@ -351,7 +352,7 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
   float pend[4][8];
   float top[8];
   run2d<RLOG, BF16>(std::make_integer_sequence<int, (g == 4 ? 1 : 4)>{}, X, tok0 * d + c0, gridW, d, c0, active, tid,
-                    pend, top, s_max, q_lo + prow0 * (size_t)(d >> 1), scales + prow0);
+                    pend, top, s_max, q_lo + stamp_qlo_offset(prow0, c0, Kpad), scales + prow0);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -472,16 +473,16 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
 #define LAUNCH1D(RL)                                                                                      \
   do {                                                                                                    \
     if (g.x_bf16)                                                                                         \
-      hipLaunchKernelGGL((k_bottom1d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k); \
+      hipLaunchKernelGGL((k_bottom1d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k, p->Kpad); \
     else                                                                                                  \
-      hipLaunchKernelGGL((k_bottom1d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k); \
+      hipLaunchKernelGGL((k_bottom1d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k, p->Kpad); \
   } while (0)
 #define LAUNCH2D(RL)                                                                                      \
   do {                                                                                                    \
     if (g.x_bf16)                                                                                         \
-      hipLaunchKernelGGL((k_bottom2d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW); \
+      hipLaunchKernelGGL((k_bottom2d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW, p->Kpad); \
     else                                                                                                  \
-      hipLaunchKernelGGL((k_bottom2d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW); \
+      hipLaunchKernelGGL((k_bottom2d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW, p->Kpad); \
   } while (0)
   if (!(part & 1)) {
     // bottom kernel skipped

@@ -79,7 +79,7 @@ void layout_workspace(stamp_plan* p) {
   p->ws_abot = take((size_t)g.B * g.k * g.d * sizeof(float));
   p->ws_rowmax = take((size_t)g.B * g.k * sizeof(uint32_t));
   p->ws_qhi = take((size_t)g.B * g.k * g.d);
-  p->ws_qlo = take((size_t)g.B * g.s * (g.d / 2));
+  p->ws_qlo = take((size_t)p->Mpad * (p->Kpad / 2));
   p->ws_scales = take((size_t)g.B * g.s * sizeof(float));
   p->ws_ythi = take((size_t)g.B * g.k * g.N * sizeof(float));
   p->ws_P = take((size_t)g.B * g.k * g.N * sizeof(float));
@@ -147,6 +147,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   p->unfused = 0;
   p->Kpad = ((g.d + 127) / 128) * 128;
   p->Npad = ((g.N + 255) / 256) * 256;
+  p->Mpad = ((g.B * g.s + 255) / 256) * 256;
   layout_workspace(p);
 
   // physical row of every STaMP slot
@@ -309,7 +310,7 @@ stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* p, int8_t* qW_host, 
     for (int c = 0; c < d; ++c) {
       const int g16 = c >> 4, cc = c & 15, half = cc >> 3, c8 = cc & 7;
       const int pos = half * 8 + (c8 & 1) * 4 + (c8 >> 1);
-      qW_host[(size_t)c * N + n] = (int8_t)(tmp[(size_t)n * p->Kpad + g16 * 16 + pos] / 16);
+      qW_host[(size_t)c * N + n] = (int8_t)(tmp[stamp_w_offset(n, g16 * 16 + pos, p->Kpad)] / 16);
     }
   free(tmp);
   return STAMP_OK;

@@ -40,8 +40,8 @@ __device__ __forceinline__ float haar_norm_dev(int level, int is2d) {
 }
 
 struct GemmArgs {
-  const uint8_t* A;      // A_INT4: q_lo [M][d/2]; else q_hi [M][d]
-  const int8_t* Bq;      // [Npad][Kpad]
+  const uint8_t* A;      // A_INT4: q_lo tiled [Mpad/256][KT][256][64]; else q_hi [M][d]
+  const int8_t* Bq;      // tiled [Npad/128][Kpad/128][128][128]
   const float* scales;   // [B*s] physical order
   const float* sw;       // [Npad]
   const float* bias;     // [Npad] or nullptr
@@ -150,17 +150,27 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
   const int rowA0 = tid / chA, slotA = tid % chA;
   const int cA = A_INT4 ? (slotA ^ ((rowA0 >> 2) & 3)) : (slotA ^ ((rowA0 >> 1) & 7));
   const int koffA = cA * 16;
-  // Byte offset of this thread's chunk in pass i (rows beyond M re-read row M-1).  Chunks past the end
-  // of a row (K tail of the last step) are still loaded -- from the next row, clamped to the buffer --
-  // because the stored weights are zero there, so whatever codes arrive contribute nothing.
+  // Byte offset of this thread's chunk in pass i at K step 0, and the distance between K steps.
+  // 4-bit rows come tiled [M/256][KT][256 rows][64 bytes] (one contiguous 16 KB run per tile and step;
+  // rows beyond M and channels beyond d_in hold whatever is there: masked in the epilogue, or multiplied
+  // by the zero padding of the stored weights).  8-bit rows are plain row-major [M][d_in]: rows beyond M
+  // re-read row M-1, chunks past the end of a row are clamped into the buffer (zero weights there).
   size_t offA[nA];
+  const size_t kStepA = A_INT4 ? (size_t)(256 * 64) : (size_t)128;
 #pragma unroll
-  for (int i = 0; i < nA; ++i)
-    offA[i] = (size_t)min(m0 + rowA0 + i * rowsPerPassA, a.M - 1) * a.a_row_bytes + koffA;
+  for (int i = 0; i < nA; ++i) {
+    if constexpr (A_INT4)
+      offA[i] = ((size_t)tm * KT * 256 + (size_t)(rowA0 + i * rowsPerPassA)) * 64 + koffA;
+    else
+      offA[i] = (size_t)min(m0 + rowA0 + i * rowsPerPassA, a.M - 1) * a.a_row_bytes + koffA;
+  }
   const int colB0 = tid >> 3, slotB = tid & 7;
   const int cB = slotB ^ ((colB0 >> 1) & 7);
-  const int8_t* gB0 = a.Bq + (size_t)(n0 + colB0) * a.Kpad + cB * 16;
-  const size_t strideB = (size_t)32 * a.Kpad;  // 32 columns per pass
+  // stored weight: [Npad/128][KT][128 columns][128 bytes]; pass i of this thread is column colB0 + 32 i
+  const int8_t* gBp[nB];
+#pragma unroll
+  for (int i = 0; i < nB; ++i) gBp[i] = a.Bq + stamp_w_offset(n0 + colB0 + 32 * i, 0, a.Kpad) + cB * 16;
+  constexpr int kStepB = 128 * 128;  // bytes between consecutive K steps of one column tile
 
   // ---- LDS -> fragment addresses (bytes inside a stage).  The swizzle term of a row depends only on
   //      lane bits, and sub-step ks enters through an XOR of bits 4-5, so per operand one base per lane
@@ -184,28 +194,44 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
 
   u4 ra[nA], rb[nB];
 
-  // prologue: step 0 -> stage 0
+  // prologue: step 0 -> stage 0, step 1 -> registers
   {
 #pragma unroll
     for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i], a.a_last16));
 #pragma unroll
-    for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB);
+    for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gBp[i]);
 #pragma unroll
     for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(smem + (i * 256 + tid) * 16) = ra[i];
 #pragma unroll
     for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(smem + bytesA + (i * 256 + tid) * 16) = rb[i];
+    if (KT > 1) {
+#pragma unroll
+      for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i] + kStepA, a.a_last16));
+#pragma unroll
+      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gBp[i] + kStepB);
+    }
   }
   __syncthreads();
 
+  // Step kt: the registers hold step kt+1 (requested one step ago): write them to the idle stage, then
+  // request step kt+2 into the same registers, then run the MFMAs of step kt.  The stage written was
+  // last read in step kt-1, which every wave left before the barrier that ended it.
   for (int kt = 0; kt < KT; ++kt) {
     const uint8_t* st = smem + (kt & 1) * stage;
-    const bool more = (kt + 1) < KT;
-    if (more) {
-      const int ka = (kt + 1) * rowA, kb = (kt + 1) * BK;
+    if (kt + 1 < KT) {
+      uint8_t* so = smem + ((kt + 1) & 1) * stage;
+#pragma unroll
+      for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(so + (i * 256 + tid) * 16) = ra[i];
+#pragma unroll
+      for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(so + bytesA + (i * 256 + tid) * 16) = rb[i];
+    }
+    if (kt + 2 < KT) {
+      const size_t ka = (size_t)(kt + 2) * kStepA;
+      const size_t kb = (size_t)(kt + 2) * kStepB;
 #pragma unroll
       for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i] + ka, a.a_last16));
 #pragma unroll
-      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gB0 + i * strideB + kb);
+      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gBp[i] + kb);
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -278,13 +304,6 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
       }
     }
 
-    if (more) {
-      uint8_t* so = smem + ((kt + 1) & 1) * stage;
-#pragma unroll
-      for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(so + (i * 256 + tid) * 16) = ra[i];
-#pragma unroll
-      for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(so + bytesA + (i * 256 + tid) * 16) = rb[i];
-    }
     __syncthreads();
   }
 
@@ -472,7 +491,7 @@ hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const 
   a.A = q_lo;
   a.M = p->geom.B * p->geom.s;
   a.a_row_bytes = p->geom.d / 2;
-  a.a_last16 = (size_t)a.M * a.a_row_bytes - 16;
+  a.a_last16 = (size_t)p->Mpad * (p->Kpad / 2) - 16;
   a.P = P;
   if (mode == 0) return launch<true, 0, 0, false>(a, st);
   if (mode == 1) return launch<true, 1, 0, false>(a, st);

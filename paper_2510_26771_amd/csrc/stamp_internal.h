@@ -74,6 +74,18 @@ STAMP_HD int stamp_slot_of_block_e_2d(int bi, int bj, int e, int G) {
 STAMP_HD int stamp_level_of_e_1d(int e, int r) { return r - (31 - __builtin_clz((unsigned)e)); }
 STAMP_HD int stamp_level_of_e_2d(int e, int r) { return r - ((31 - __builtin_clz((unsigned)e)) >> 1); }
 
+// Byte offset of (output column n, permuted channel position c) in the stored weight:
+// [Npad/128][Kpad/128][128 columns][128 positions].
+STAMP_HD size_t stamp_w_offset(int n, int c, int Kpad) {
+  return (((size_t)(n >> 7) * (size_t)(Kpad >> 7) + (size_t)(c >> 7)) * 128 + (size_t)(n & 127)) * 128 + (size_t)(c & 127);
+}
+
+// Byte offset of (physical row m over all sequences, channel c) in the tiled 4-bit activation:
+// [Mpad/256][Kpad/128][256 rows][64 bytes], two channels per byte.
+STAMP_HD size_t stamp_qlo_offset(size_t m, int c, int Kpad) {
+  return (((m >> 8) * (size_t)(Kpad >> 7) + (size_t)(c >> 7)) * 256 + (m & 255)) * 64 + (size_t)((c & 127) >> 1);
+}
+
 // ---------------------------------------------------------------------------------------------
 // The plan.
 // ---------------------------------------------------------------------------------------------
@@ -81,7 +93,8 @@ struct stamp_plan {
   stamp_plan_desc_t desc;
   StampGeom geom;
   int32_t Kpad, Npad;       // GEMM-padded depth and width of the stored weight
-  int8_t* qW_dev;           // [Npad][Kpad] int8: weight codes * 16, K order permuted per 16 channels
+  int32_t Mpad;             // batch * seq_len rounded up to the GEMM's 256-row tile
+  int8_t* qW_dev;           // tiled int8 weight codes * 16 (see stamp_w_offset), K order permuted per 16 channels
   float* sw_dev;            // [Npad] weight scales (0 beyond d_out)
   float* bias_dev;          // [Npad] bias or nullptr
   int32_t* row_of_coeff;    // host, [s]

@@ -2,10 +2,12 @@
 // sw_n = max_c |W_cn| / 7 and code = rne(W_cn * (7 / max)) (round-to-nearest weights with one
 // scale per output channel, paper sections "Experiments" set-up and "Large Language Models").
 //
-// Stored layout for the GEMM: qW[Npad][Kpad] int8, output channel major, holding code * 16 (the
-// GEMM keeps 4-bit values in the high nibble of an int8).  Inside every group of 16 input
-// channels the order is [0,2,4,6, 1,3,5,7, 8,10,12,14, 9,11,13,15]: the order in which the GEMM's
-// nibble unpack of 8 packed activation bytes delivers its 16 channels.
+// Stored layout for the GEMM: int8 code * 16 (the GEMM keeps 4-bit values in the high nibble of an
+// int8), tiled as [Npad/128 column tiles][Kpad/128 K steps][128 columns][128 channels], so that what
+// one workgroup reads in one K step is one contiguous 16 KB run (spread over all memory channels)
+// instead of 128 rows a power-of-two stride apart.  Inside every group of 16 input channels the order
+// is [0,2,4,6, 1,3,5,7, 8,10,12,14, 9,11,13,15]: the order in which the GEMM's nibble unpack of 8
+// packed activation bytes delivers its 16 channels.
 #include "stamp_internal.h"
 
 namespace {
@@ -54,7 +56,7 @@ __global__ void k_w_quant(const float* __restrict__ W, const uint32_t* __restric
     }
     out[pos >> 2] |= ((uint32_t)q & 0xFFu) << (8 * (pos & 3));
   }
-  *reinterpret_cast<uint4*>(qW + (size_t)n * Kpad + (size_t)g16 * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+  *reinterpret_cast<uint4*>(qW + stamp_w_offset(n, g16 * 16, Kpad)) = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
 }  // namespace

@@ -53,7 +53,11 @@ def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):
     k = d.k_hi
     assert np.array_equal(row[:k], np.arange(k) * (d.seq_len // k))
     qh = q_hi.cpu().numpy()
-    ql = q_lo.cpu().numpy()
+    # q_lo is tiled [Mp/256][Kp/128][256 rows][64 bytes] (include/stamp.h): back to [batch, seq_len, d/2]
+    mp = -(-(d.batch * d.seq_len) // 256) * 256
+    kp = -(-d.d_in // 128) * 128
+    ql = q_lo.cpu().numpy().reshape(mp // 256, kp // 128, 256, 64).transpose(0, 2, 1, 3).reshape(mp, kp // 2)
+    ql = ql[:d.batch * d.seq_len, :d.d_in // 2].reshape(d.batch, d.seq_len, d.d_in // 2)
     sc = scales.cpu().numpy()
     codes = np.empty((d.batch, d.seq_len, d.d_in), dtype=np.int8)
     codes[:, :k] = qh
