@@ -82,7 +82,7 @@ void layout_workspace(stamp_plan* p) {
   p->ws_qlo = take((size_t)p->Mpad * (p->Kpad / 2));
   p->ws_scales = take((size_t)g.B * g.s * sizeof(float));
   p->ws_ythi = take((size_t)g.B * g.k * g.N * sizeof(float));
-  p->ws_P = take((size_t)g.B * g.k * g.N * sizeof(float));
+  p->ws_P = take((size_t)g.B * g.k * p->Npad * sizeof(float));
   p->ws_ytlo = off;
   if (p->unfused || !p->fused_ok) take((size_t)g.B * g.s * g.N * sizeof(float));
   p->ws_total = off;
@@ -100,13 +100,13 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
   float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
   float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
   if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
-  if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st) != hipSuccess) return STAMP_ERR_DEVICE;
   if (p->fused_ok && !p->unfused) {
     if (stamp_launch_gemm_lo(p, q_lo, scales, 2, Y, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
   } else {
     float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
     if (stamp_launch_gemm_lo(p, q_lo, scales, 1, ytlo, nullptr, st) != hipSuccess) return STAMP_ERR_DEVICE;
-    if (stamp_launch_inverse_bottom(p, ytlo, 0, P, p->geom.N, p->bias_dev, Y, st) != hipSuccess) return STAMP_ERR_DEVICE;
+    if (stamp_launch_inverse_bottom(p, ytlo, 0, P, p->Npad, p->geom.N, p->bias_dev, Y, st) != hipSuccess) return STAMP_ERR_DEVICE;
   }
   return STAMP_OK;
 }
@@ -252,9 +252,9 @@ stamp_status_t stamp_inverse(const stamp_plan_t* p, const float* Yt, int32_t n_c
   if (!ws_ok(p, ws, ws_bytes, need)) return STAMP_ERR_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   float* P = reinterpret_cast<float*>(ws);
-  if (stamp_launch_inverse_top(p, Yt, 1, n_cols, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (stamp_launch_inverse_top(p, Yt, 1, n_cols, P, n_cols, st) != hipSuccess) return STAMP_ERR_DEVICE;
   const float* bias = (n_cols == p->geom.N) ? p->bias_dev : nullptr;
-  if (stamp_launch_inverse_bottom(p, Yt, 1, P, n_cols, bias, Y, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (stamp_launch_inverse_bottom(p, Yt, 1, P, n_cols, n_cols, bias, Y, st) != hipSuccess) return STAMP_ERR_DEVICE;
   return STAMP_OK;
 }
 
@@ -287,10 +287,10 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
     case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 1); break;
     case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 2); break;
     case 2: e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st); break;
-    case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, st); break;
+    case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st); break;
     case 4: e = fused ? stamp_launch_gemm_lo(p, q_lo, scales, 2, Y, P, st)
                       : stamp_launch_gemm_lo(p, q_lo, scales, 1, ytlo, nullptr, st); break;
-    case 5: e = stamp_launch_inverse_bottom(p, ytlo, 0, P, p->geom.N, p->bias_dev, Y, st); break;
+    case 5: e = stamp_launch_inverse_bottom(p, ytlo, 0, P, p->Npad, p->geom.N, p->bias_dev, Y, st); break;
   }
   return e == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
 }

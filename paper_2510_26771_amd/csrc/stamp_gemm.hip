@@ -29,7 +29,7 @@ typedef uint32_t u4 __attribute__((ext_vector_type(4)));  // first-class 16-byte
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BK = 128;  // BN = 64 * NI (NI = 32-column MFMA blocks per wave along N)
-constexpr int kEpiStride = 33;  // floats per row of the per-wave epilogue staging tile
+constexpr int kEpiStride = 36;  // floats per row of the per-wave epilogue staging tile (16-byte aligned rows)
 constexpr int kNumXcd = 8;
 constexpr int kGroupM = 8;
 
@@ -45,7 +45,7 @@ struct GemmArgs {
   const float* scales;   // [B*s] physical order
   const float* sw;       // [Npad]
   const float* bias;     // [Npad] or nullptr
-  const float* P;        // [B*k][N] block sums of the inverse (fused mode)
+  const float* P;        // [B*k][Npad] block sums of the inverse (fused mode)
   void* out;
   int M;                 // rows of A
   int N, Npad, Kpad;
@@ -61,56 +61,86 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
-struct OutCol {  // where one lane stores the tokens of one block, one output column
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// Where one lane stores the tokens of one unit (a block or an aligned part of one): 4 adjacent output
+// columns per token, written as one 8-byte (bf16) or 16-byte (fp32) store when d_out allows it.
+template <bool YBF16>
+struct OutQuad {
   void* Y;
-  size_t base;        // element index of token 0 of the block, this column
-  size_t tok_stride;  // N
-  size_t row_stride;  // 2-D: gridW * N
-  float bias;
-  int bf16;
-  __device__ __forceinline__ void put(size_t idx, float v) const {
+  size_t base;        // element index of token 0 of the block, first of the 4 columns
+  size_t tok_stride;  // d_out
+  size_t row_stride;  // 2-D: grid_w * d_out
+  f4 bias;
+  int nvalid;         // how many of the 4 columns exist (d_out tail)
+  bool vec;           // d_out % 4 == 0: vector stores are aligned
+  __device__ __forceinline__ void put(size_t idx, f4 v) const {
     v += bias;
-    if (bf16) reinterpret_cast<uint16_t*>(Y)[idx] = f32_to_bf16_rne(v);
-    else reinterpret_cast<float*>(Y)[idx] = v;
+    if constexpr (YBF16) {
+      const uint32_t lo = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+      const uint32_t hi = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+      uint16_t* y = reinterpret_cast<uint16_t*>(Y) + idx;
+      if (vec) {
+        *reinterpret_cast<uint2*>(y) = make_uint2(lo, hi);
+      } else {
+        if (nvalid > 0) y[0] = (uint16_t)lo;
+        if (nvalid > 1) y[1] = (uint16_t)(lo >> 16);
+        if (nvalid > 2) y[2] = (uint16_t)hi;
+        if (nvalid > 3) y[3] = (uint16_t)(hi >> 16);
+      }
+    } else {
+      float* y = reinterpret_cast<float*>(Y) + idx;
+      if (vec) {
+        *reinterpret_cast<f4*>(y) = v;
+      } else {
+        if (nvalid > 0) y[0] = v[0];
+        if (nvalid > 1) y[1] = v[1];
+        if (nvalid > 2) y[2] = v[2];
+        if (nvalid > 3) y[3] = v[3];
+      }
+    }
   }
 };
 
-// Depth-first inverse of one block for one column: node (M, I) holds the level-(r-M) sum `a` of its
-// subtree; col[e * kEpiStride] is the in-block coefficient at STaMP position e.  Only O(r) values are
-// live at any time; every coefficient is read once.
-template <int RLOG, int M, int I>
-__device__ __forceinline__ void dfs1d(const float* col, float a, const OutCol& o) {
+// Depth-first inverse of one unit for 4 columns.  The unit is the subtree rooted at node (M0, h) of a
+// block's Haar tree; node (M, I) of that subtree holds the sum `a` of its tokens; tile[e * kEpiStride]
+// is the block's coefficient at in-block STaMP position e = 2^M + (h << (M - M0)) + I.  Only O(r)
+// values are live at any time and every coefficient is read once.
+template <int RLOG, int M0, int M, int I, bool YBF16>
+__device__ __forceinline__ void dfs1d(const float* tile, int h, f4 a, const OutQuad<YBF16>& o) {
   if constexpr (M == RLOG) {
-    o.put(o.base + (size_t)I * o.tok_stride, a);
+    o.put(o.base + (size_t)((h << (RLOG - M0)) + I) * o.tok_stride, a);
   } else {
-    const float d = col[((1 << M) + I) * kEpiStride];
-    dfs1d<RLOG, M + 1, 2 * I>(col, a + d, o);
-    dfs1d<RLOG, M + 1, 2 * I + 1>(col, a - d, o);
+    const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << M) + (h << (M - M0)) + I) * kEpiStride);
+    dfs1d<RLOG, M0, M + 1, 2 * I, YBF16>(tile, h, a + d, o);
+    dfs1d<RLOG, M0, M + 1, 2 * I + 1, YBF16>(tile, h, a - d, o);
   }
 }
 
-template <int RLOG, int M, int IY, int IX>
-__device__ __forceinline__ void dfs2d(const float* col, float a, const OutCol& o) {
+// 2-D: the unit is the quadtree node (M0, hy, hx) of a g x g block; bands W, H, D of level-node side
+// gl = 2^M sit at e = gl^2 (1 + band) + iy * gl + ix.
+template <int RLOG, int M0, int M, int IY, int IX, bool YBF16>
+__device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, const OutQuad<YBF16>& o) {
   if constexpr (M == RLOG) {
-    o.put(o.base + (size_t)IY * o.row_stride + (size_t)IX * o.tok_stride, a);
+    o.put(o.base + (size_t)((hy << (RLOG - M0)) + IY) * o.row_stride + (size_t)((hx << (RLOG - M0)) + IX) * o.tok_stride, a);
   } else {
     constexpr int gl = 1 << M;
-    constexpr int e0 = IY * gl + IX;
-    const float cW = col[(gl * gl + e0) * kEpiStride];
-    const float cH = col[(2 * gl * gl + e0) * kEpiStride];
-    const float cD = col[(3 * gl * gl + e0) * kEpiStride];
-    const float t0 = a + cH, t2 = a - cH, t1 = cW + cD, t3 = cW - cD;
-    dfs2d<RLOG, M + 1, 2 * IY, 2 * IX>(col, t0 + t1, o);
-    dfs2d<RLOG, M + 1, 2 * IY, 2 * IX + 1>(col, t0 - t1, o);
-    dfs2d<RLOG, M + 1, 2 * IY + 1, 2 * IX>(col, t2 + t3, o);
-    dfs2d<RLOG, M + 1, 2 * IY + 1, 2 * IX + 1>(col, t2 - t3, o);
+    const int e0 = ((hy << (M - M0)) + IY) * gl + ((hx << (M - M0)) + IX);
+    const f4 cW = *reinterpret_cast<const f4*>(tile + (gl * gl + e0) * kEpiStride);
+    const f4 cH = *reinterpret_cast<const f4*>(tile + (2 * gl * gl + e0) * kEpiStride);
+    const f4 cD = *reinterpret_cast<const f4*>(tile + (3 * gl * gl + e0) * kEpiStride);
+    const f4 t0 = a + cH, t2 = a - cH, t1 = cW + cD, t3 = cW - cD;
+    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX, YBF16>(tile, hy, hx, t0 + t1, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX + 1, YBF16>(tile, hy, hx, t0 - t1, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX, YBF16>(tile, hy, hx, t2 + t3, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX + 1, YBF16>(tile, hy, hx, t2 - t3, o);
   }
 }
 
 // EPI: 0 = int32 accumulators to STaMP-ordered rows; 1 = dequantized fp32 rows (lo: physical rows of
 // [B*s][N]; hi: [B*k][N]); 2 = fused in-block inverse + bias -> Y (A_INT4 only); RB = log2 of the
 // block length for EPI 2 (1-D: tokens, 2-D: side).
-template <bool A_INT4, int EPI, int RB, bool IS2D, int NI>
+template <bool A_INT4, int EPI, int RB, bool IS2D, int NI, bool YBF16>
 __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs a) {
   constexpr int BN = 64 * NI;
   constexpr int nB = BN / 32;                   // B chunks per thread per step (BN columns * 8 chunks / 256 threads)
@@ -150,26 +180,38 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
   const int rowA0 = tid / chA, slotA = tid % chA;
   const int cA = A_INT4 ? (slotA ^ ((rowA0 >> 2) & 3)) : (slotA ^ ((rowA0 >> 1) & 7));
   const int koffA = cA * 16;
-  // Byte offset of this thread's chunk in pass i at K step 0, and the distance between K steps.
+  // Addresses are a wave-uniform base (tile and K step) plus a per-thread 32-bit offset that never
+  // changes, so the per-step address arithmetic is scalar.
   // 4-bit rows come tiled [M/256][KT][256 rows][64 bytes] (one contiguous 16 KB run per tile and step;
   // rows beyond M and channels beyond d_in hold whatever is there: masked in the epilogue, or multiplied
   // by the zero padding of the stored weights).  8-bit rows are plain row-major [M][d_in]: rows beyond M
   // re-read row M-1, chunks past the end of a row are clamped into the buffer (zero weights there).
-  size_t offA[nA];
+  uint32_t offA[nA];
+  const uint8_t* baseGA = a.A;
   const size_t kStepA = A_INT4 ? (size_t)(256 * 64) : (size_t)128;
 #pragma unroll
   for (int i = 0; i < nA; ++i) {
-    if constexpr (A_INT4)
-      offA[i] = ((size_t)tm * KT * 256 + (size_t)(rowA0 + i * rowsPerPassA)) * 64 + koffA;
-    else
-      offA[i] = (size_t)min(m0 + rowA0 + i * rowsPerPassA, a.M - 1) * a.a_row_bytes + koffA;
+    if constexpr (A_INT4) {
+      offA[i] = (uint32_t)((rowA0 + i * rowsPerPassA) * 64 + koffA);
+    } else {
+      offA[i] = (uint32_t)(min(m0 + rowA0 + i * rowsPerPassA, a.M - 1) - m0) * (uint32_t)a.a_row_bytes + koffA;
+    }
   }
+  if constexpr (A_INT4) baseGA += (size_t)tm * KT * (256 * 64);
+  else baseGA += (size_t)m0 * a.a_row_bytes;
+  // byte offset (from baseGA) of the last 16-byte chunk that may be read
+  const size_t lastA = a.a_last16 - (size_t)(baseGA - a.A);
   const int colB0 = tid >> 3, slotB = tid & 7;
   const int cB = slotB ^ ((colB0 >> 1) & 7);
   // stored weight: [Npad/128][KT][128 columns][128 bytes]; pass i of this thread is column colB0 + 32 i
-  const int8_t* gBp[nB];
+  // (column tiles of 128: a 256-wide tile spans two of them, KT * 16 KB apart)
+  const int8_t* baseGB = a.Bq + stamp_w_offset(n0, 0, a.Kpad);
+  uint32_t offB[nB];
 #pragma unroll
-  for (int i = 0; i < nB; ++i) gBp[i] = a.Bq + stamp_w_offset(n0 + colB0 + 32 * i, 0, a.Kpad) + cB * 16;
+  for (int i = 0; i < nB; ++i) {
+    const int col = colB0 + 32 * i;
+    offB[i] = (uint32_t)(col >> 7) * (uint32_t)(KT * 128 * 128) + (uint32_t)((col & 127) * 128 + cB * 16);
+  }
   constexpr int kStepB = 128 * 128;  // bytes between consecutive K steps of one column tile
 
   // ---- LDS -> fragment addresses (bytes inside a stage).  The swizzle term of a row depends only on
@@ -193,22 +235,26 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
   u4 ra[nA], rb[nB];
+  // A chunk of pass i, KOFF bytes into the K dimension: tiled rows need no clamp (padded buffer)
+#define STAMP_LDA(KOFF)                                                                     \
+  (A_INT4 ? *reinterpret_cast<const u4*>(baseGA + (KOFF) + offA[i])                           \
+          : *reinterpret_cast<const u4*>(baseGA + min((size_t)(KOFF) + offA[i], lastA)))
 
   // prologue: step 0 -> stage 0, step 1 -> registers
   {
 #pragma unroll
-    for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i], a.a_last16));
+    for (int i = 0; i < nA; ++i) ra[i] = STAMP_LDA(0);
 #pragma unroll
-    for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gBp[i]);
+    for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(baseGB + offB[i]);
 #pragma unroll
     for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(smem + (i * 256 + tid) * 16) = ra[i];
 #pragma unroll
     for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(smem + bytesA + (i * 256 + tid) * 16) = rb[i];
     if (KT > 1) {
 #pragma unroll
-      for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i] + kStepA, a.a_last16));
+      for (int i = 0; i < nA; ++i) ra[i] = STAMP_LDA(kStepA);
 #pragma unroll
-      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gBp[i] + kStepB);
+      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(baseGB + kStepB + offB[i]);
     }
   }
   __syncthreads();
@@ -229,9 +275,9 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
       const size_t ka = (size_t)(kt + 2) * kStepA;
       const size_t kb = (size_t)(kt + 2) * kStepB;
 #pragma unroll
-      for (int i = 0; i < nA; ++i) ra[i] = *reinterpret_cast<const u4*>(a.A + min(offA[i] + ka, a.a_last16));
+      for (int i = 0; i < nA; ++i) ra[i] = STAMP_LDA(ka);
 #pragma unroll
-      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(gBp[i] + kb);
+      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(baseGB + kb + offB[i]);
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -307,6 +353,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
     __syncthreads();
   }
 
+#undef STAMP_LDA
   // ------------------------------------------------------------------------------------------
   // Epilogue.  Accumulator element v of lane l in block (mi, ni): row 32 mi + 8 (v / 4) + 4 (l / 32)
   // + v % 4, column 32 ni + l % 32 of the wave tile.
@@ -371,45 +418,74 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
       }
     }
   } else {
-    // fused: per 32-column strip, dequantize into this wave's LDS tile [128][33]; then each lane takes
-    // one column of one block at a time and runs the depth-first inverse, storing the block's tokens.
+    // fused: per 32-column strip, dequantize into this wave's LDS tile [128][kEpiStride]; then the wave's
+    // 8 groups of 8 lanes each take one unit (a block, or an aligned 16-token part of one) and 4 columns
+    // per lane, and run the depth-first inverse, storing the unit's tokens.
     constexpr int R = IS2D ? (1 << (2 * RB)) : (1 << RB);
-    constexpr int nblk = 128 / R;  // blocks per wave tile
+    constexpr int nblk = 128 / R;                                   // blocks per wave tile
+    constexpr int M0 = IS2D ? (RB == 3 ? 1 : 0) : (RB > 4 ? RB - 4 : 0);  // unit = subtree at depth M0
+    constexpr int U = IS2D ? (1 << (2 * M0)) : (1 << M0);           // units per block
+    constexpr int npass = (nblk * U) / 8;
     float* s_tile = reinterpret_cast<float*>(smem + 2048) + wave * (128 * kEpiStride);
+    // row factors of this lane's 64 accumulator rows, read before any staging write
+    f4 rf[4][4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        rf[mi][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + mi * 32 + 8 * q + 4 * kg);
+    const int c4 = (lane & 7) * 4, ug = lane >> 3;
+    OutQuad<YBF16> o;
+    o.Y = a.out;
+    o.tok_stride = (size_t)a.N;
+    o.row_stride = (size_t)g.gridW * a.N;
+    o.vec = (a.N & 3) == 0;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-      const int n = n0 + wn * (32 * NI) + ni * 32 + l32;
-      const float swn = a.sw[n];
-      OutCol o;
-      o.Y = a.out;
-      o.tok_stride = (size_t)a.N;
-      o.row_stride = (size_t)g.gridW * a.N;
-      o.bias = (a.bias != nullptr) ? a.bias[n] : 0.0f;
-      o.bf16 = g.y_bf16;
+      const int nw = n0 + wn * (32 * NI) + ni * 32;  // first column of the strip
+      const float swn = a.sw[nw + l32];
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int rw = mi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-          s_tile[rw * kEpiStride + l32] = ((float)acc[mi][ni][v] * s_rowfac[wm * 128 + rw]) * swn;
+          s_tile[rw * kEpiStride + l32] = ((float)acc[mi][ni][v] * rf[mi][v >> 2][v & 3]) * swn;
         }
       }
       __syncthreads();
-#pragma unroll 1
-      for (int blk = kg; blk < nblk; blk += 2) {
+      const int n = nw + c4;
+      o.nvalid = a.N - n;
+      o.bias = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + n) : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int pass = 0; pass < npass; ++pass) {
+        const int unit = pass * 8 + ug;
+        const int blk = unit / U, h = unit % U;
         const int mrow = m0 + wm * 128 + blk * R;  // physical row of e = 0 of this block
         if (mrow < a.M && n < a.N) {
           const int b = mrow / g.s, pr = mrow - b * g.s;
           const int j = pr / g.R;
-          const float top = a.P[((size_t)b * g.k + j) * a.N + n];
-          const float* col = s_tile + blk * R * kEpiStride + l32;
+          f4 top = *reinterpret_cast<const f4*>(a.P + ((size_t)b * g.k + j) * a.Npad + n);
+          const float* tile = s_tile + blk * R * kEpiStride + c4;
           if constexpr (IS2D) {
             const int bi = j / g.G, bj = j - bi * g.G;
             o.base = ((size_t)b * g.s + (size_t)(bi << RB) * g.gridW + (size_t)(bj << RB)) * a.N + n;
-            dfs2d<RB, 0, 0, 0>(col, top, o);
+            const int hy = h >> 1, hx = h & 1;
+            if constexpr (M0 == 1) {
+              const f4 cW = *reinterpret_cast<const f4*>(tile + 1 * kEpiStride);
+              const f4 cH = *reinterpret_cast<const f4*>(tile + 2 * kEpiStride);
+              const f4 cD = *reinterpret_cast<const f4*>(tile + 3 * kEpiStride);
+              const f4 t0 = top + cH, t2 = top - cH, t1 = cW + cD, t3 = cW - cD;
+              top = hy ? (hx ? (t2 - t3) : (t2 + t3)) : (hx ? (t0 - t1) : (t0 + t1));
+            }
+            dfs2d<RB, M0, M0, 0, 0, YBF16>(tile, hy, hx, top, o);
           } else {
             o.base = ((size_t)b * g.s + (size_t)j * R) * a.N + n;
-            dfs1d<RB, 0, 0>(col, top, o);
+#pragma unroll
+            for (int m = 0; m < M0; ++m) {
+              const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << m) + (h >> (M0 - m))) * kEpiStride);
+              top = ((h >> (M0 - m - 1)) & 1) ? (top - d) : (top + d);
+            }
+            dfs1d<RB, M0, M0, 0, YBF16>(tile, h, top, o);
           }
         }
       }
@@ -418,7 +494,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
   }
 }
 
-template <bool A_INT4, int EPI, int RB, bool IS2D, int NI>
+template <bool A_INT4, int EPI, int RB, bool IS2D, int NI, bool YBF16>
 hipError_t launch_ni(const GemmArgs& a, hipStream_t st) {
   constexpr int BN = 64 * NI;
   constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
@@ -426,13 +502,13 @@ hipError_t launch_ni(const GemmArgs& a, hipStream_t st) {
   constexpr size_t lds = main_lds > epi_lds ? main_lds : epi_lds;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, NI>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, NI, YBF16>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
-  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, NI>), dim3(mt * nt), dim3(256), lds, st, a);
+  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, NI, YBF16>), dim3(mt * nt), dim3(256), lds, st, a);
   return hipGetLastError();
 }
 
@@ -448,8 +524,15 @@ int gemm_ni() {
 
 template <bool A_INT4, int EPI, int RB, bool IS2D>
 hipError_t launch(const GemmArgs& a, hipStream_t st) {
-  if (gemm_ni() == 4) return launch_ni<A_INT4, EPI, RB, IS2D, 4>(a, st);
-  return launch_ni<A_INT4, EPI, RB, IS2D, 2>(a, st);
+  // the output type only matters to the fused epilogue
+  if constexpr (EPI == 2) {
+    if (a.g.y_bf16) {
+      if (gemm_ni() == 4) return launch_ni<A_INT4, EPI, RB, IS2D, 4, true>(a, st);
+      return launch_ni<A_INT4, EPI, RB, IS2D, 2, true>(a, st);
+    }
+  }
+  if (gemm_ni() == 4) return launch_ni<A_INT4, EPI, RB, IS2D, 4, false>(a, st);
+  return launch_ni<A_INT4, EPI, RB, IS2D, 2, false>(a, st);
 }
 
 GemmArgs make_args(const stamp_plan* p, const float* scales, void* out) {

@@ -115,9 +115,10 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
                                 void* out, hipStream_t st);
 hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const float* scales, int mode,
                                 void* out, const float* P, hipStream_t st);
+// P: block sums [B*k][ldP]
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* Yt_hi, int hi_row_stride_is_stamp,
-                                    int ncols, float* P, hipStream_t st);
+                                    int ncols, float* P, int ldP, hipStream_t st);
 hipError_t stamp_launch_inverse_bottom(const stamp_plan* p, const float* Yt_lo, int src_is_stamp_order,
-                                       const float* P, int ncols, const float* bias, void* Y, hipStream_t st);
+                                       const float* P, int ldP, int ncols, const float* bias, void* Y, hipStream_t st);
 
 #endif  // STAMP_INTERNAL_H_

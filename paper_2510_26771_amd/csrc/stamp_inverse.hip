@@ -62,9 +62,9 @@ __device__ __forceinline__ void inverse_inplace(float* s_buf, int n, int side, i
   }
 }
 
-// src: hi rows; row of (b, p) = b * src_seq_rows + p.  P[(b*k + j) * ncols + n].
+// src: hi rows; row of (b, p) = b * src_seq_rows + p.  P[(b*k + j) * ldP + n].
 __global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ src, int src_seq_rows, int apply_norm,
-                                                     float* __restrict__ P, int ncols, StampGeom g) {
+                                                     float* __restrict__ P, int ldP, int ncols, StampGeom g) {
   extern __shared__ float s_buf[];  // [k][kStride]
   const int b = blockIdx.y, n_base = blockIdx.x * kCols, tid = threadIdx.x;
   const int ch = tid & (kCols - 1), grp = tid / kCols, ngrp = 256 / kCols;
@@ -88,13 +88,14 @@ __global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ s
   __syncthreads();
   inverse_inplace(s_buf, k, g.G, g.is2d, ch, grp, ngrp);
   for (int q = grp; q < k; q += ngrp)
-    if (nact) P[((size_t)b * k + q) * ncols + n] = s_buf[q * kStride + ch];
+    if (nact) P[((size_t)b * k + q) * ldP + n] = s_buf[q * kStride + ch];
 }
 
 // src rows of block (b, j): physical (b*s + j*R + e) or STaMP slot order; Y [B, s, ncols].
 __global__ __launch_bounds__(256) void k_inverse_bottom(const float* __restrict__ src, int src_is_stamp, int apply_norm,
-                                                        const float* __restrict__ P, const float* __restrict__ bias,
-                                                        void* __restrict__ Y, int ncols, StampGeom g) {
+                                                        const float* __restrict__ P, int ldP,
+                                                        const float* __restrict__ bias, void* __restrict__ Y, int ncols,
+                                                        StampGeom g) {
   extern __shared__ float s_buf[];  // [R][kStride]
   const int j = blockIdx.y, b = blockIdx.z, n_base = blockIdx.x * kCols, tid = threadIdx.x;
   const int ch = tid & (kCols - 1), grp = tid / kCols, ngrp = 256 / kCols;
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(256) void k_inverse_bottom(const float* __restrict_
   for (int q = grp; q < R; q += ngrp) {
     float v = 0.0f;
     if (q == 0) {
-      if (nact) v = P[((size_t)b * g.k + j) * ncols + n];
+      if (nact) v = P[((size_t)b * g.k + j) * ldP + n];
     } else {
       int e, level;
       if (!g.is2d) {
@@ -150,19 +151,19 @@ __global__ __launch_bounds__(256) void k_inverse_bottom(const float* __restrict_
 }  // namespace
 
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* src, int src_is_stamp, int ncols, float* P,
-                                    hipStream_t st) {
+                                    int ldP, hipStream_t st) {
   const StampGeom& g = p->geom;
   const size_t lds = (size_t)g.k * kStride * sizeof(float);
   hipLaunchKernelGGL(k_inverse_top, dim3((ncols + kCols - 1) / kCols, g.B), dim3(256), lds, st, src,
-                     src_is_stamp ? g.s : g.k, src_is_stamp, P, ncols, g);
+                     src_is_stamp ? g.s : g.k, src_is_stamp, P, ldP, ncols, g);
   return hipGetLastError();
 }
 
 hipError_t stamp_launch_inverse_bottom(const stamp_plan* p, const float* src, int src_is_stamp, const float* P,
-                                       int ncols, const float* bias, void* Y, hipStream_t st) {
+                                       int ldP, int ncols, const float* bias, void* Y, hipStream_t st) {
   const StampGeom& g = p->geom;
   const size_t lds = (size_t)g.R * kStride * sizeof(float);
   hipLaunchKernelGGL(k_inverse_bottom, dim3((ncols + kCols - 1) / kCols, g.k, g.B), dim3(256), lds, st, src,
-                     src_is_stamp, src_is_stamp, P, bias, Y, ncols, g);
+                     src_is_stamp, src_is_stamp, P, ldP, bias, Y, ncols, g);
   return hipGetLastError();
 }
