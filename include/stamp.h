@@ -94,7 +94,7 @@ typedef struct {
 /* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):
  *   xform HAAR1D with seq_len/k_hi in {8,16,32,64,128}, or HAAR2D with a square grid and
  *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels = full depth; bits 8/4/4;
- *   d_in a multiple of 32 and at most 8192; k_hi <= 256. */
+ *   d_in a multiple of 32 and at most 8192 (4096 for fp32 input or 2-D grids); k_hi <= 256. */
 
 /* Validates desc, quantizes W per output channel (absmax/7, round to nearest even; section
  * "Large Language Models", Set-up: round-to-nearest weights, one scale per output channel) into

@@ -16,8 +16,8 @@
 //                            4-bit rows of the block and the block sum (fp32, to scratch).
 //   k_top                    the remaining levels over the k_hi block sums, in LDS, per channel
 //                            slice; writes the normalised 8-bit-row coefficients to scratch and
-//                            their per-row absmax with a global atomic max.
-//   k_quant_hi               rounds those k_hi rows to int8.
+//                            one partial absmax per (row, slice).
+//   k_quant_hi               reduces the partial maxima of a row and rounds the row to int8.
 #include <utility>
 
 #include "stamp_internal.h"
@@ -172,13 +172,48 @@ __device__ __forceinline__ void chain1d(float (&cur)[8], float (&pend)[NP][8], f
   }
 }
 
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+// The block's token rows are streamed through an LDS staging buffer by asynchronous global -> LDS
+// loads (no registers held while they are in flight): batch IT+1 (8 token rows) is requested as soon
+// as batch IT has been read out of the buffer into registers, and lands while batch IT is processed.
+// Every lane reads back exactly the 16-byte chunks it requested, so no barrier guards the buffer.
+// Layout: chunk (t, h) of thread tid at ((t * CPR + h) * nthreads + tid) * 16, CPR = 16-byte chunks
+// per thread and row (1 for bf16, 2 for fp32).
+template <bool BF16>
+__device__ __forceinline__ void request_batch(const uint8_t* X_thr /* this thread's 8 channels of row 0 of the batch */,
+                                              size_t row_bytes, uint8_t* stage, int nthreads, int wave, bool active) {
+  constexpr int CPR = BF16 ? 1 : 2;
+  if (active) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+      for (int h = 0; h < CPR; ++h)
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)(X_thr + (size_t)t * row_bytes + 16 * h),
+            (void __attribute__((address_space(3)))*)(stage + ((t * CPR + h) * nthreads + wave * 64) * 16), 16, 0, 0);
+  }
+}
+
 template <int RLOG, bool BF16, int IT, int NP>
-__device__ __forceinline__ void step1d(const void* X, size_t blk_elem_off, int d, int c0, bool active, int tid,
-                                       float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[32],
+__device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, uint8_t* stage, int nthreads, bool active,
+                                       int tid, float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[32],
                                        uint8_t* q_lo_blk, float* scales_blk) {
   constexpr int R = 1 << RLOG;
   constexpr int CH = cmin(trailing_ones(IT), RLOG - 3);
   constexpr int NR = 7 + CH;
+  constexpr int CPR = BF16 ? 1 : 2;
+  // batch IT out of the staging buffer (the compiler waits for the outstanding global -> LDS loads here)
+  u4 raw[8][CPR];
+#pragma unroll
+  for (int t = 0; t < 8; ++t)
+#pragma unroll
+    for (int h = 0; h < CPR; ++h)
+      raw[t][h] = *reinterpret_cast<const u4*>(stage + ((t * CPR + h) * nthreads + tid) * 16);
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the buffer has been read before it is requested again
+  if constexpr (IT + 1 < R / 8)
+    request_batch<BF16>(X_thr + (size_t)(8 * (IT + 1)) * row_bytes, row_bytes, stage, nthreads, tid >> 6, active);
+
   float rowv[NR][8];
   float a2[2][8];
 #pragma unroll
@@ -187,9 +222,24 @@ __device__ __forceinline__ void step1d(const void* X, size_t blk_elem_off, int d
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       float x0[8], x1[8];
-      const int t = 8 * IT + 4 * h + 2 * u;
-      load8(X, blk_elem_off + (size_t)t * d, BF16, active, x0);
-      load8(X, blk_elem_off + (size_t)(t + 1) * d, BF16, active, x1);
+      const int t = 4 * h + 2 * u;
+      if constexpr (BF16) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          x0[2 * w] = active ? bf16lo(raw[t][0][w]) : 0.0f;
+          x0[2 * w + 1] = active ? bf16hi(raw[t][0][w]) : 0.0f;
+          x1[2 * w] = active ? bf16lo(raw[t + 1][0][w]) : 0.0f;
+          x1[2 * w + 1] = active ? bf16hi(raw[t + 1][0][w]) : 0.0f;
+        }
+      } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          x0[w] = active ? __uint_as_float(raw[t][0][w]) : 0.0f;
+          x0[4 + w] = active ? __uint_as_float(raw[t][CPR - 1][w]) : 0.0f;
+          x1[w] = active ? __uint_as_float(raw[t + 1][0][w]) : 0.0f;
+          x1[4 + w] = active ? __uint_as_float(raw[t + 1][CPR - 1][w]) : 0.0f;
+        }
+      }
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         a1[u][c] = __fadd_rn(x0[c], x1[c]);
@@ -223,30 +273,34 @@ __device__ __forceinline__ void step1d(const void* X, size_t blk_elem_off, int d
 }
 
 template <int RLOG, bool BF16, int NP, int... ITS>
-__device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const void* X, size_t blk_elem_off, int d,
-                                      int c0, bool active, int tid, float (&pend)[NP][8], float (&top)[8],
-                                      uint32_t (*s_max)[32], uint8_t* q_lo_blk, float* scales_blk) {
-  (step1d<RLOG, BF16, ITS, NP>(X, blk_elem_off, d, c0, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
+__device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const uint8_t* X_thr, size_t row_bytes,
+                                      uint8_t* stage, int nthreads, bool active, int tid, float (&pend)[NP][8],
+                                      float (&top)[8], uint32_t (*s_max)[32], uint8_t* q_lo_blk, float* scales_blk) {
+  (step1d<RLOG, BF16, ITS, NP>(X_thr, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
 }
 
 template <int RLOG, bool BF16>
 __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
-                                                   float* __restrict__ scales, float* __restrict__ abot,
-                                                   uint32_t* __restrict__ rowmax, int s, int d, int k, int Kpad) {
+                                                   float* __restrict__ scales, float* __restrict__ abot, int s, int d,
+                                                   int k, int Kpad) {
   constexpr int R = 1 << RLOG;
   constexpr int NP = RLOG > 3 ? RLOG - 3 : 1;
+  extern __shared__ __attribute__((aligned(16))) uint8_t stage[];  // 8 rows x nthreads x (16 | 32) bytes
   __shared__ uint32_t s_max[3][32];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int nthreads = blockDim.x;
   const int c0 = tid * 8;
   const bool active = c0 < d;
-  for (int i = tid; i < 96; i += blockDim.x) (&s_max[0][0])[i] = 0u;
-  if (tid == 0) rowmax[b * k + j] = 0u;
-  __syncthreads();
+  const size_t esz = BF16 ? 2 : 4;
   const size_t row0 = (size_t)b * s + (size_t)j * R;
+  const uint8_t* X_thr = reinterpret_cast<const uint8_t*>(X) + (row0 * d + c0) * esz;
+  request_batch<BF16>(X_thr, (size_t)d * esz, stage, nthreads, tid >> 6, active);
+  for (int i = tid; i < 96; i += nthreads) (&s_max[0][0])[i] = 0u;
+  __syncthreads();
   float pend[NP][8];
   float top[8];
-  run1d<RLOG, BF16, NP>(std::make_integer_sequence<int, R / 8>{}, X, row0 * d + c0, d, c0, active, tid, pend, top,
-                        s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0);
+  run1d<RLOG, BF16, NP>(std::make_integer_sequence<int, R / 8>{}, X_thr, (size_t)d * esz, stage, nthreads, active, tid,
+                        pend, top, s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -345,7 +399,6 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
   const bool active = c0 < d;
   const int k = G * G;
   for (int i = tid; i < 96; i += blockDim.x) (&s_max[0][0])[i] = 0u;
-  if (tid == 0) rowmax[b * k + j] = 0u;
   __syncthreads();
   const size_t tok0 = (size_t)b * s + (size_t)(bi * g) * gridW + (size_t)bj * g;  // first token of the block
   const size_t prow0 = (size_t)b * s + (size_t)j * R;                              // first physical row of the block
@@ -367,7 +420,7 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
 // ------------------------------------------------------------------------------------------
 constexpr int kTopCh = 32;
 
-__global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t* __restrict__ rowmax, int k, int d,
+__global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t* __restrict__ rowmax_part, int k, int d,
                                              int is2d, int G, int r_bottom) {
   extern __shared__ float s_buf[];  // [k][kTopCh + 1]
   const int b = blockIdx.y, c_base = blockIdx.x * kTopCh, tid = threadIdx.x;
@@ -431,16 +484,24 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
     yv = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); x = max(x, yv);
     yv = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); x = max(x, yv);
     yv = __shfl_xor(x, 16, 64); x = max(x, yv);
-    if (ch == 0) atomicMax(&rowmax[b * k + e], (uint32_t)x);
+    if (ch == 0) rowmax_part[((size_t)b * k + e) * gridDim.x + blockIdx.x] = (uint32_t)x;
   }
 }
 
 // one workgroup per 8-bit row
-__global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop, const uint32_t* __restrict__ rowmax,
-                                                  int8_t* __restrict__ q_hi, float* __restrict__ scales, int k, int d,
-                                                  int s, int R) {
+__global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop, const uint32_t* __restrict__ rowmax_part,
+                                                  int nslices, int8_t* __restrict__ q_hi, float* __restrict__ scales,
+                                                  int k, int d, int s, int R) {
+  __shared__ uint32_t s_red[4];
   const int p = blockIdx.x, b = blockIdx.y;
-  const float a = __uint_as_float(rowmax[b * k + p]);
+  {
+    uint32_t m = 0u;
+    for (int i = threadIdx.x; i < nslices; i += 256) m = max(m, rowmax_part[((size_t)b * k + p) * nslices + i]);
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = m;
+    __syncthreads();
+  }
+  const float a = __uint_as_float(max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3])));
   float scale = 0.0f, inv = 0.0f;
   if (a > 0.0f) {
     scale = __fdiv_rn(a, 127.0f);
@@ -463,6 +524,24 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
   }
 }
 
+template <int RLOG, bool BF16>
+hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, float* scales, float* abot, int nthreads,
+                           hipStream_t st) {
+  const StampGeom& g = p->geom;
+  const size_t lds = (size_t)8 * nthreads * (BF16 ? 16 : 32);  // staging buffer: 8 token rows
+  if (lds > 160 * 1024 - 1024) return hipErrorInvalidValue;
+  static size_t attr_lds = 0;
+  if (lds > attr_lds) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bottom1d<RLOG, BF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_lds = lds;
+  }
+  hipLaunchKernelGGL((k_bottom1d<RLOG, BF16>), dim3(g.k, g.B), dim3(nthreads), lds, st, X, q_lo, scales, abot, g.s, g.d,
+                     g.k, p->Kpad);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
@@ -472,10 +551,9 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
   dim3 grid(g.k, g.B);
 #define LAUNCH1D(RL)                                                                                      \
   do {                                                                                                    \
-    if (g.x_bf16)                                                                                         \
-      hipLaunchKernelGGL((k_bottom1d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k, p->Kpad); \
-    else                                                                                                  \
-      hipLaunchKernelGGL((k_bottom1d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.k, p->Kpad); \
+    hipError_t le = g.x_bf16 ? launch_bottom1d<RL, true>(p, X, q_lo, scales, abot, nthreads, st)          \
+                             : launch_bottom1d<RL, false>(p, X, q_lo, scales, abot, nthreads, st);        \
+    if (le != hipSuccess) return le;                                                                      \
   } while (0)
 #define LAUNCH2D(RL)                                                                                      \
   do {                                                                                                    \
@@ -513,6 +591,7 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
                      g.G, g.r);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, q_hi, scales, g.k, g.d, g.s, g.R);
+  hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, (g.d + kTopCh - 1) / kTopCh, q_hi,
+                     scales, g.k, g.d, g.s, g.R);
   return hipGetLastError();
 }

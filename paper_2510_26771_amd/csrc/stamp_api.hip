@@ -55,6 +55,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     g->is2d = 0;
     g->r = ilog2(R);
     if (g->r < 3 || g->r > 7) return STAMP_ERR_UNSUPPORTED;
+    if (d->x_dtype == STAMP_F32 && d->d_in > 4096) return STAMP_ERR_UNSUPPORTED;  // LDS staging of fp32 rows
     *fused_ok = g->r <= 6;
   } else {
     if (d->grid_h != d->grid_w) return STAMP_ERR_UNSUPPORTED;
@@ -77,7 +78,7 @@ void layout_workspace(stamp_plan* p) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   p->ws_abot = take((size_t)g.B * g.k * g.d * sizeof(float));
-  p->ws_rowmax = take((size_t)g.B * g.k * sizeof(uint32_t));
+  p->ws_rowmax = take((size_t)g.B * g.k * ((g.d + 31) / 32) * sizeof(uint32_t));  // partial row maxima per 32-channel slice
   p->ws_qhi = take((size_t)g.B * g.k * g.d);
   p->ws_qlo = take((size_t)p->Mpad * (p->Kpad / 2));
   p->ws_scales = take((size_t)g.B * g.s * sizeof(float));
