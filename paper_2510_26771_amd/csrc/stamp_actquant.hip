@@ -97,26 +97,45 @@ constexpr int cmin(int a, int b) { return a < b ? a : b; }
 // and in-block position given per row) are reduced over the workgroup, scaled, rounded, packed and
 // stored.  `step` numbers the steps of this workgroup (rotating LDS buffers).
 struct RowMeta { int level; int e; };
+constexpr int kMaxRows = 18;  // most rows finished by one streaming step (2-D: 12 + 3 + 3)
 
-template <int NR, bool IS2D, typename MetaFn>
-__device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[32],
+// With DEFER the packed codes and the scale are handed back (wout[r], scale_out of lane r) instead of
+// being stored: the caller stores them one step later, so that the wait for the next batch of staged
+// rows does not also wait for stores that were only just issued.
+template <int NR, bool IS2D, bool DEFER, typename MetaFn>
+__device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[kMaxRows * 16],
                                            uint8_t* q_lo_thr /* this thread's 4 bytes of row e=0 of the block */,
-                                           float* scales_blk, bool active, int tid) {
-  const int lane = tid & 63;
-  const int buf = step % 3;
+                                           float* scales_blk, bool active, int tid, uint32_t (&wout)[kMaxRows],
+                                           float& scale_out) {
+  const int lane = tid & 63, wave = tid >> 6;
+  uint32_t* part = &s_max[0][0] + (step & 1) * (kMaxRows * 16);  // [row][wave] partial maxima, double buffered
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
     const uint32_t m = wave_max_u32(row_absmax_bits(rowv[r]));
-    if (lane == 0) atomicMax(&s_max[buf][r], m);
+    if (lane == 0) part[r * 16 + wave] = m;
   }
-  __syncthreads();
-  if (tid < 32) s_max[(step + 2) % 3][tid] = 0u;
+  // Workgroup barrier that waits for this wave's LDS traffic only: __syncthreads() would also wait for
+  // the global -> LDS loads of the next batch, which are meant to stay in flight across it.
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   // lane r prepares row r: a = fl(absmaxU * norm); scale = a / 7; inv = 7 / a
   float mul_lane = 0.0f;
   {
     const int r = lane < NR ? lane : 0;
     const RowMeta rm = meta(r);
-    const float amaxU = __uint_as_float(s_max[buf][r]);
+    const int nw = (int)(blockDim.x >> 6);
+    uint32_t mbits = 0u;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint4 v = *reinterpret_cast<const uint4*>(part + r * 16 + 4 * q);
+      if (4 * q + 0 < nw) mbits = max(mbits, v.x);
+      if (4 * q + 1 < nw) mbits = max(mbits, v.y);
+      if (4 * q + 2 < nw) mbits = max(mbits, v.z);
+      if (4 * q + 3 < nw) mbits = max(mbits, v.w);
+    }
+    const float amaxU = __uint_as_float(mbits);
     const float nrm = IS2D ? ldexpf(1.0f, -rm.level) : haar_norm(rm.level);
     const float a = __fmul_rn(amaxU, nrm);
     float scale = 0.0f, inv = 0.0f;
@@ -127,7 +146,8 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     // even 1-D levels and all 2-D levels have a power-of-two norm: fold it into the multiplier
     const bool fold = IS2D || ((rm.level & 1) == 0);
     mul_lane = fold ? __fmul_rn(inv, nrm) : inv;
-    if (tid < NR) scales_blk[rm.e] = scale;
+    if constexpr (DEFER) scale_out = scale;
+    else if (tid < NR) scales_blk[rm.e] = scale;
   }
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
@@ -144,138 +164,140 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
       for (int c = 0; c < 8; ++c) p[c] = __fmul_rn(__fmul_rn(rowv[r][c], nrm), mul);
     }
     const uint32_t w = pack8_int4(p);
-    if (active) *reinterpret_cast<uint32_t*>(q_lo_thr + rm.e * 64) = w;  // tiled layout: 64 bytes per row and K step
+    if constexpr (DEFER) wout[r] = w;
+    else if (active) *reinterpret_cast<uint32_t*>(q_lo_thr + rm.e * 64) = w;  // tiled layout: 64 bytes per row and K step
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // 1-D bottom kernel
 // ------------------------------------------------------------------------------------------
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+// level and in-block position of row r finished by streaming step IT (4 tokens) of a 1-D block of
+// 2^RLOG tokens: rows 0,1 = level-1 differences, row 2 = level 2, row r >= 3 = level r (carry chain)
+template <int RLOG, int IT>
+__device__ __forceinline__ RowMeta meta1d(int r) {
+  constexpr int R = 1 << RLOG;
+  RowMeta m;
+  if (r < 2) { m.level = 1; m.e = (R >> 1) + 2 * IT + r; }
+  else if (r == 2) { m.level = 2; m.e = (R >> 2) + IT; }
+  else { m.level = r; m.e = (R >> r) + (IT >> (r - 2)); }
+  return m;
+}
+
+// The block's token rows are streamed through an LDS staging buffer by asynchronous global -> LDS
+// loads (no registers are held while they are in flight): the buffer holds two batches of 4 token
+// rows; batch IT+2 is requested as soon as batch IT has been read out of its half into registers,
+// so two batches are always in flight or ready.  Every lane reads back exactly the 16-byte chunks it
+// requested, so no barrier guards the buffer, only this wave's own vmcnt.
+// Layout of one half: chunk (t, h) of thread tid at ((t * CPR + h) * nthreads + tid) * 16, CPR =
+// 16-byte chunks per thread and row (1 for bf16, 2 for fp32).
+template <bool BF16>
+__device__ __forceinline__ void request_batch(const uint8_t* X_thr /* this thread's 8 channels of row 0 of the batch */,
+                                              size_t row_bytes, uint8_t* half, int nthreads, int wave) {
+  constexpr int CPR = BF16 ? 1 : 2;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int h = 0; h < CPR; ++h)
+      __builtin_amdgcn_global_load_lds(
+          (const void __attribute__((address_space(1)))*)(X_thr + (size_t)t * row_bytes + 16 * h),
+          (void __attribute__((address_space(3)))*)(half + ((t * CPR + h) * nthreads + wave * 64) * 16), 16, 0, 0);
+}
+
 template <int RLOG, int L, int IDX, int SLOT, int NP, int MAXR>
-__device__ __forceinline__ void chain1d(float (&cur)[8], float (&pend)[NP][8], float (&rowv)[MAXR][8],
-                                        float (&top)[8], bool& have_top) {
+__device__ __forceinline__ void chain1d(float (&cur)[8], float (&pend)[NP][8], float (&rowv)[MAXR][8], float (&top)[8]) {
   if constexpr (L == RLOG) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) top[c] = cur[c];
-    have_top = true;
   } else if constexpr ((IDX & 1) != 0) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      const float a = __fadd_rn(pend[L - 3][c], cur[c]);
-      rowv[SLOT][c] = __fsub_rn(pend[L - 3][c], cur[c]);
+      const float a = __fadd_rn(pend[L - 2][c], cur[c]);
+      rowv[SLOT][c] = __fsub_rn(pend[L - 2][c], cur[c]);
       cur[c] = a;
     }
-    chain1d<RLOG, L + 1, (IDX >> 1), SLOT + 1, NP, MAXR>(cur, pend, rowv, top, have_top);
+    chain1d<RLOG, L + 1, (IDX >> 1), SLOT + 1, NP, MAXR>(cur, pend, rowv, top);
   } else {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) pend[L - 3][c] = cur[c];
-  }
-}
-
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-
-// The block's token rows are streamed through an LDS staging buffer by asynchronous global -> LDS
-// loads (no registers held while they are in flight): batch IT+1 (8 token rows) is requested as soon
-// as batch IT has been read out of the buffer into registers, and lands while batch IT is processed.
-// Every lane reads back exactly the 16-byte chunks it requested, so no barrier guards the buffer.
-// Layout: chunk (t, h) of thread tid at ((t * CPR + h) * nthreads + tid) * 16, CPR = 16-byte chunks
-// per thread and row (1 for bf16, 2 for fp32).
-template <bool BF16>
-__device__ __forceinline__ void request_batch(const uint8_t* X_thr /* this thread's 8 channels of row 0 of the batch */,
-                                              size_t row_bytes, uint8_t* stage, int nthreads, int wave, bool active) {
-  constexpr int CPR = BF16 ? 1 : 2;
-  if (active) {
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-#pragma unroll
-      for (int h = 0; h < CPR; ++h)
-        __builtin_amdgcn_global_load_lds(
-            (const void __attribute__((address_space(1)))*)(X_thr + (size_t)t * row_bytes + 16 * h),
-            (void __attribute__((address_space(3)))*)(stage + ((t * CPR + h) * nthreads + wave * 64) * 16), 16, 0, 0);
+    for (int c = 0; c < 8; ++c) pend[L - 2][c] = cur[c];
   }
 }
 
 template <int RLOG, bool BF16, int IT, int NP>
 __device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, uint8_t* stage, int nthreads, bool active,
-                                       int tid, float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[32],
+                                       int tid, float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[kMaxRows * 16],
                                        uint8_t* q_lo_blk, float* scales_blk) {
   constexpr int R = 1 << RLOG;
-  constexpr int CH = cmin(trailing_ones(IT), RLOG - 3);
-  constexpr int NR = 7 + CH;
+  constexpr int NIT = R / 4;
+  constexpr int CH = cmin(trailing_ones(IT), RLOG - 2);
+  constexpr int NR = 3 + CH;
   constexpr int CPR = BF16 ? 1 : 2;
-  // batch IT out of the staging buffer (the compiler waits for the outstanding global -> LDS loads here)
-  u4 raw[8][CPR];
+  uint8_t* half = stage + (IT & 1) * (4 * CPR * nthreads * 16);
+  // Wait until this wave's loads of batch IT have landed: everything requested after it (batch IT+1:
+  // 4 * CPR loads) may stay in flight.  Stores issued since also count, so this can only over-wait.
+  asm volatile("" ::: "memory");
+  if constexpr (IT + 1 < NIT) __builtin_amdgcn_s_waitcnt(0x0F70 | (4 * CPR));  // vmcnt(4 * CPR)
+  else __builtin_amdgcn_s_waitcnt(0x0F70);                                      // vmcnt(0)
+  asm volatile("" ::: "memory");
+  u4 raw[4][CPR];
 #pragma unroll
-  for (int t = 0; t < 8; ++t)
+  for (int t = 0; t < 4; ++t)
 #pragma unroll
     for (int h = 0; h < CPR; ++h)
-      raw[t][h] = *reinterpret_cast<const u4*>(stage + ((t * CPR + h) * nthreads + tid) * 16);
-  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the buffer has been read before it is requested again
-  if constexpr (IT + 1 < R / 8)
-    request_batch<BF16>(X_thr + (size_t)(8 * (IT + 1)) * row_bytes, row_bytes, stage, nthreads, tid >> 6, active);
+      raw[t][h] = *reinterpret_cast<const u4*>(half + ((t * CPR + h) * nthreads + tid) * 16);
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the half has been read before it is requested again
+  asm volatile("" ::: "memory");
+  if constexpr (IT + 2 < NIT)
+    request_batch<BF16>(X_thr + (size_t)(4 * (IT + 2)) * row_bytes, row_bytes, half, nthreads, tid >> 6);
 
   float rowv[NR][8];
-  float a2[2][8];
+  float a1[2][8];
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    float a1[2][8];
+  for (int u = 0; u < 2; ++u) {
+    float x0[8], x1[8];
+    const int t = 2 * u;
+    if constexpr (BF16) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      float x0[8], x1[8];
-      const int t = 4 * h + 2 * u;
-      if constexpr (BF16) {
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          x0[2 * w] = active ? bf16lo(raw[t][0][w]) : 0.0f;
-          x0[2 * w + 1] = active ? bf16hi(raw[t][0][w]) : 0.0f;
-          x1[2 * w] = active ? bf16lo(raw[t + 1][0][w]) : 0.0f;
-          x1[2 * w + 1] = active ? bf16hi(raw[t + 1][0][w]) : 0.0f;
-        }
-      } else {
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          x0[w] = active ? __uint_as_float(raw[t][0][w]) : 0.0f;
-          x0[4 + w] = active ? __uint_as_float(raw[t][CPR - 1][w]) : 0.0f;
-          x1[w] = active ? __uint_as_float(raw[t + 1][0][w]) : 0.0f;
-          x1[4 + w] = active ? __uint_as_float(raw[t + 1][CPR - 1][w]) : 0.0f;
-        }
+      for (int w = 0; w < 4; ++w) {
+        x0[2 * w] = bf16lo(raw[t][0][w]);
+        x0[2 * w + 1] = bf16hi(raw[t][0][w]);
+        x1[2 * w] = bf16lo(raw[t + 1][0][w]);
+        x1[2 * w + 1] = bf16hi(raw[t + 1][0][w]);
       }
+    } else {
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        a1[u][c] = __fadd_rn(x0[c], x1[c]);
-        rowv[2 * h + u][c] = __fsub_rn(x0[c], x1[c]);
+      for (int w = 0; w < 4; ++w) {
+        x0[w] = __uint_as_float(raw[t][0][w]);
+        x0[4 + w] = __uint_as_float(raw[t][CPR - 1][w]);
+        x1[w] = __uint_as_float(raw[t + 1][0][w]);
+        x1[4 + w] = __uint_as_float(raw[t + 1][CPR - 1][w]);
       }
     }
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      a2[h][c] = __fadd_rn(a1[0][c], a1[1][c]);
-      rowv[4 + h][c] = __fsub_rn(a1[0][c], a1[1][c]);
+      a1[u][c] = __fadd_rn(x0[c], x1[c]);
+      rowv[u][c] = __fsub_rn(x0[c], x1[c]);
     }
   }
   float cur[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
-    cur[c] = __fadd_rn(a2[0][c], a2[1][c]);
-    rowv[6][c] = __fsub_rn(a2[0][c], a2[1][c]);
+    cur[c] = __fadd_rn(a1[0][c], a1[1][c]);
+    rowv[2][c] = __fsub_rn(a1[0][c], a1[1][c]);
   }
-  bool have_top = false;
-  chain1d<RLOG, 3, IT, 7, NP, NR>(cur, pend, rowv, top, have_top);
-  (void)have_top;
-  auto meta = [](int r) -> RowMeta {
-    RowMeta m;
-    if (r < 4) { m.level = 1; m.e = (R >> 1) + 4 * IT + r; }
-    else if (r < 6) { m.level = 2; m.e = (R >> 2) + 2 * IT + (r - 4); }
-    else if (r == 6) { m.level = 3; m.e = (R >> 3) + IT; }
-    else { m.level = r - 3; m.e = (R >> (r - 3)) + (IT >> (r - 6)); }
-    return m;
-  };
-  flush_rows<NR, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, active, tid);
+  chain1d<RLOG, 2, IT, 3, NP, NR>(cur, pend, rowv, top);
+  auto meta = [](int r) -> RowMeta { return meta1d<RLOG, IT>(r); };
+  uint32_t wunused[kMaxRows];
+  float sunused;
+  flush_rows<NR, false, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, active, tid, wunused, sunused);
 }
 
 template <int RLOG, bool BF16, int NP, int... ITS>
 __device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const uint8_t* X_thr, size_t row_bytes,
                                       uint8_t* stage, int nthreads, bool active, int tid, float (&pend)[NP][8],
-                                      float (&top)[8], uint32_t (*s_max)[32], uint8_t* q_lo_blk, float* scales_blk) {
+                                      float (&top)[8], uint32_t (*s_max)[kMaxRows * 16], uint8_t* q_lo_blk, float* scales_blk) {
   (step1d<RLOG, BF16, ITS, NP>(X_thr, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
 }
 
@@ -284,23 +306,26 @@ __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, u
                                                    float* __restrict__ scales, float* __restrict__ abot, int s, int d,
                                                    int k, int Kpad) {
   constexpr int R = 1 << RLOG;
-  constexpr int NP = RLOG > 3 ? RLOG - 3 : 1;
-  extern __shared__ __attribute__((aligned(16))) uint8_t stage[];  // 8 rows x nthreads x (16 | 32) bytes
-  __shared__ uint32_t s_max[3][32];
+  constexpr int NP = RLOG > 2 ? RLOG - 2 : 1;
+  constexpr int CPR = BF16 ? 1 : 2;
+  extern __shared__ __attribute__((aligned(16))) uint8_t stage[];  // 2 halves x 4 rows x nthreads x (16 | 32) bytes
+  __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kMaxRows * 16];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int nthreads = blockDim.x;
   const int c0 = tid * 8;
   const bool active = c0 < d;
   const size_t esz = BF16 ? 2 : 4;
   const size_t row0 = (size_t)b * s + (size_t)j * R;
-  const uint8_t* X_thr = reinterpret_cast<const uint8_t*>(X) + (row0 * d + c0) * esz;
-  request_batch<BF16>(X_thr, (size_t)d * esz, stage, nthreads, tid >> 6, active);
-  for (int i = tid; i < 96; i += nthreads) (&s_max[0][0])[i] = 0u;
-  __syncthreads();
+  // threads beyond d_in / 8 (the workgroup is a whole number of waves) redo the last channel group:
+  // duplicates cannot change a row maximum, and they store nothing
+  const uint8_t* X_thr = reinterpret_cast<const uint8_t*>(X) + (row0 * d + min(c0, d - 8)) * esz;
+  const size_t row_bytes = (size_t)d * esz;
+  request_batch<BF16>(X_thr, row_bytes, stage, nthreads, tid >> 6);
+  if (R > 4) request_batch<BF16>(X_thr + 4 * row_bytes, row_bytes, stage + 4 * CPR * nthreads * 16, nthreads, tid >> 6);
   float pend[NP][8];
   float top[8];
-  run1d<RLOG, BF16, NP>(std::make_integer_sequence<int, R / 8>{}, X_thr, (size_t)d * esz, stage, nthreads, active, tid,
-                        pend, top, s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0);
+  run1d<RLOG, BF16, NP>(std::make_integer_sequence<int, R / 4>{}, X_thr, row_bytes, stage, nthreads, active, tid, pend,
+                        top, s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -328,7 +353,7 @@ __device__ __forceinline__ void cell2d(const float (&p)[8], const float (&q)[8],
 
 template <int RLOG, bool BF16, int SB>
 __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int gridW, int d, int c0, bool active, int tid,
-                                       float (&pend)[4][8], float (&top)[8], uint32_t (*s_max)[32],
+                                       float (&pend)[4][8], float (&top)[8], uint32_t (*s_max)[kMaxRows * 16],
                                        uint8_t* q_lo_blk, float* scales_blk) {
   constexpr int g = 1 << RLOG;
   constexpr int sby = (g == 4) ? 0 : (SB >> 1), sbx = (g == 4) ? 0 : (SB & 1);
@@ -375,13 +400,15 @@ __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int g
     }
     return m;
   };
-  flush_rows<NR, true>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, active, tid);
+  uint32_t wunused[kMaxRows];
+  float sunused;
+  flush_rows<NR, true, false>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, active, tid, wunused, sunused);
 }
 
 template <int RLOG, bool BF16, int... SBS>
 __device__ __forceinline__ void run2d(std::integer_sequence<int, SBS...>, const void* X, size_t blk_elem_off, int gridW,
                                       int d, int c0, bool active, int tid, float (&pend)[4][8], float (&top)[8],
-                                      uint32_t (*s_max)[32], uint8_t* q_lo_blk, float* scales_blk) {
+                                      uint32_t (*s_max)[kMaxRows * 16], uint8_t* q_lo_blk, float* scales_blk) {
   (step2d<RLOG, BF16, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
 }
 
@@ -392,14 +419,12 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
                                                   int Kpad) {
   constexpr int g = 1 << RLOG;
   constexpr int R = g * g;
-  __shared__ uint32_t s_max[3][32];
+  __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kMaxRows * 16];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int bi = j / G, bj = j - bi * G;
   const int c0 = tid * 8;
   const bool active = c0 < d;
   const int k = G * G;
-  for (int i = tid; i < 96; i += blockDim.x) (&s_max[0][0])[i] = 0u;
-  __syncthreads();
   const size_t tok0 = (size_t)b * s + (size_t)(bi * g) * gridW + (size_t)bj * g;  // first token of the block
   const size_t prow0 = (size_t)b * s + (size_t)j * R;                              // first physical row of the block
   float pend[4][8];
@@ -528,7 +553,7 @@ template <int RLOG, bool BF16>
 hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, float* scales, float* abot, int nthreads,
                            hipStream_t st) {
   const StampGeom& g = p->geom;
-  const size_t lds = (size_t)8 * nthreads * (BF16 ? 16 : 32);  // staging buffer: 8 token rows
+  const size_t lds = (size_t)8 * nthreads * (BF16 ? 16 : 32);  // staging buffer: 2 batches of 4 token rows
   if (lds > 160 * 1024 - 1024) return hipErrorInvalidValue;
   static size_t attr_lds = 0;
   if (lds > attr_lds) {
