@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--cpu-cols", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (int32 add), the "
+                         "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the STaMP linear layer on ONE GPU; --gpus N with N > 1 is not "
@@ -121,6 +124,12 @@ def main():
     def step():
         plan.linear_forward(Xd, Y, ws)
 
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     log("warmup")
     for _ in range(args.warmup):
         step()
