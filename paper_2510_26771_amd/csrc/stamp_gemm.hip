@@ -19,6 +19,7 @@
 // Workgroups are renumbered so that the 32 workgroups resident on one XCD cover 8 x 4 neighbouring
 // tiles and share operand panels in that XCD's L2.
 #include <cstdlib>
+#include <type_traits>
 
 #include "stamp_internal.h"
 
@@ -65,7 +66,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 // Where one lane stores the tokens of one unit (a block or an aligned part of one): 4 adjacent output
 // columns per token, written as one 8-byte (bf16) or 16-byte (fp32) store when d_out allows it.
-template <bool YBF16>
+template <bool YBF16, bool VEC>
 struct OutQuad {
   void* Y;
   size_t base;        // element index of token 0 of the block, first of the 4 columns
@@ -73,14 +74,13 @@ struct OutQuad {
   size_t row_stride;  // 2-D: grid_w * d_out
   f4 bias;
   int nvalid;         // how many of the 4 columns exist (d_out tail)
-  bool vec;           // d_out % 4 == 0: vector stores are aligned
   __device__ __forceinline__ void put(size_t idx, f4 v) const {
     v += bias;
     if constexpr (YBF16) {
       const uint32_t lo = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
       const uint32_t hi = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
       uint16_t* y = reinterpret_cast<uint16_t*>(Y) + idx;
-      if (vec) {
+      if constexpr (VEC) {
         *reinterpret_cast<uint2*>(y) = make_uint2(lo, hi);
       } else {
         if (nvalid > 0) y[0] = (uint16_t)lo;
@@ -90,7 +90,7 @@ struct OutQuad {
       }
     } else {
       float* y = reinterpret_cast<float*>(Y) + idx;
-      if (vec) {
+      if constexpr (VEC) {
         *reinterpret_cast<f4*>(y) = v;
       } else {
         if (nvalid > 0) y[0] = v[0];
@@ -106,21 +106,21 @@ struct OutQuad {
 // block's Haar tree; node (M, I) of that subtree holds the sum `a` of its tokens; tile[e * kEpiStride]
 // is the block's coefficient at in-block STaMP position e = 2^M + (h << (M - M0)) + I.  Only O(r)
 // values are live at any time and every coefficient is read once.
-template <int RLOG, int M0, int M, int I, bool YBF16>
-__device__ __forceinline__ void dfs1d(const float* tile, int h, f4 a, const OutQuad<YBF16>& o) {
+template <int RLOG, int M0, int M, int I, typename Out>
+__device__ __forceinline__ void dfs1d(const float* tile, int h, f4 a, const Out& o) {
   if constexpr (M == RLOG) {
     o.put(o.base + (size_t)((h << (RLOG - M0)) + I) * o.tok_stride, a);
   } else {
     const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << M) + (h << (M - M0)) + I) * kEpiStride);
-    dfs1d<RLOG, M0, M + 1, 2 * I, YBF16>(tile, h, a + d, o);
-    dfs1d<RLOG, M0, M + 1, 2 * I + 1, YBF16>(tile, h, a - d, o);
+    dfs1d<RLOG, M0, M + 1, 2 * I, Out>(tile, h, a + d, o);
+    dfs1d<RLOG, M0, M + 1, 2 * I + 1, Out>(tile, h, a - d, o);
   }
 }
 
 // 2-D: the unit is the quadtree node (M0, hy, hx) of a g x g block; bands W, H, D of level-node side
 // gl = 2^M sit at e = gl^2 (1 + band) + iy * gl + ix.
-template <int RLOG, int M0, int M, int IY, int IX, bool YBF16>
-__device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, const OutQuad<YBF16>& o) {
+template <int RLOG, int M0, int M, int IY, int IX, typename Out>
+__device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, const Out& o) {
   if constexpr (M == RLOG) {
     o.put(o.base + (size_t)((hy << (RLOG - M0)) + IY) * o.row_stride + (size_t)((hx << (RLOG - M0)) + IX) * o.tok_stride, a);
   } else {
@@ -130,10 +130,10 @@ __device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, c
     const f4 cH = *reinterpret_cast<const f4*>(tile + (2 * gl * gl + e0) * kEpiStride);
     const f4 cD = *reinterpret_cast<const f4*>(tile + (3 * gl * gl + e0) * kEpiStride);
     const f4 t0 = a + cH, t2 = a - cH, t1 = cW + cD, t3 = cW - cD;
-    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX, YBF16>(tile, hy, hx, t0 + t1, o);
-    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX + 1, YBF16>(tile, hy, hx, t0 - t1, o);
-    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX, YBF16>(tile, hy, hx, t2 + t3, o);
-    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX + 1, YBF16>(tile, hy, hx, t2 - t3, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX, Out>(tile, hy, hx, t0 + t1, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX + 1, Out>(tile, hy, hx, t0 - t1, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX, Out>(tile, hy, hx, t2 + t3, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX + 1, Out>(tile, hy, hx, t2 - t3, o);
   }
 }
 
@@ -234,51 +234,35 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-  u4 ra[nA], rb[nB];
-  // A chunk of pass i, KOFF bytes into the K dimension: tiled rows need no clamp (padded buffer)
-#define STAMP_LDA(KOFF)                                                                     \
-  (A_INT4 ? *reinterpret_cast<const u4*>(baseGA + (KOFF) + offA[i])                           \
-          : *reinterpret_cast<const u4*>(baseGA + min((size_t)(KOFF) + offA[i], lastA)))
+  // Operand staging: asynchronous global -> LDS loads (16 bytes per lane, a wave instruction fills 1 KB
+  // of contiguous LDS; the XOR swizzle is applied on the global-address side).  No registers are held
+  // while a K step is in flight and nothing has to be copied into LDS by the waves.
+#define STAMP_REQUEST(KSTEP, STG)                                                                          \
+  do {                                                                                                     \
+    uint8_t* so_ = smem + (STG) * stage + wave * 1024;                                                     \
+    const size_t ka_ = (size_t)(KSTEP) * kStepA, kb_ = (size_t)(KSTEP) * kStepB;                           \
+    _Pragma("unroll") for (int i = 0; i < nA; ++i) {                                                       \
+      const uint8_t* src_ = A_INT4 ? (baseGA + ka_ + offA[i]) : (baseGA + min(ka_ + offA[i], lastA));      \
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src_,                \
+                                       (void __attribute__((address_space(3)))*)(so_ + i * 4096), 16, 0, 0); \
+    }                                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < nB; ++i)                                                         \
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(baseGB + kb_ + offB[i]), \
+                                         (void __attribute__((address_space(3)))*)(so_ + bytesA + i * 4096), 16, 0, 0); \
+  } while (0)
 
-  // prologue: step 0 -> stage 0, step 1 -> registers
-  {
-#pragma unroll
-    for (int i = 0; i < nA; ++i) ra[i] = STAMP_LDA(0);
-#pragma unroll
-    for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(baseGB + offB[i]);
-#pragma unroll
-    for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(smem + (i * 256 + tid) * 16) = ra[i];
-#pragma unroll
-    for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(smem + bytesA + (i * 256 + tid) * 16) = rb[i];
-    if (KT > 1) {
-#pragma unroll
-      for (int i = 0; i < nA; ++i) ra[i] = STAMP_LDA(kStepA);
-#pragma unroll
-      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(baseGB + kStepB + offB[i]);
-    }
-  }
-  __syncthreads();
+  STAMP_REQUEST(0, 0);
 
-  // Step kt: the registers hold step kt+1 (requested one step ago): write them to the idle stage, then
-  // request step kt+2 into the same registers, then run the MFMAs of step kt.  The stage written was
-  // last read in step kt-1, which every wave left before the barrier that ended it.
+  // Step kt: wait for this wave's loads of step kt, then the workgroup barrier (every wave's loads of
+  // step kt have landed, and every wave has left step kt-1, whose stage is now free); request step kt+1
+  // into that free stage; run the MFMAs of step kt while it is in flight.
   for (int kt = 0; kt < KT; ++kt) {
     const uint8_t* st = smem + (kt & 1) * stage;
-    if (kt + 1 < KT) {
-      uint8_t* so = smem + ((kt + 1) & 1) * stage;
-#pragma unroll
-      for (int i = 0; i < nA; ++i) *reinterpret_cast<u4*>(so + (i * 256 + tid) * 16) = ra[i];
-#pragma unroll
-      for (int i = 0; i < nB; ++i) *reinterpret_cast<u4*>(so + bytesA + (i * 256 + tid) * 16) = rb[i];
-    }
-    if (kt + 2 < KT) {
-      const size_t ka = (size_t)(kt + 2) * kStepA;
-      const size_t kb = (size_t)(kt + 2) * kStepB;
-#pragma unroll
-      for (int i = 0; i < nA; ++i) ra[i] = STAMP_LDA(ka);
-#pragma unroll
-      for (int i = 0; i < nB; ++i) rb[i] = *reinterpret_cast<const u4*>(baseGB + kb + offB[i]);
-    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kt + 1 < KT) STAMP_REQUEST(kt + 1, (kt + 1) & 1);
     __builtin_amdgcn_sched_barrier(0);
 
     v4i fb[2][NI];
@@ -350,10 +334,10 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
       }
     }
 
-    __syncthreads();
   }
+  __syncthreads();
+#undef STAMP_REQUEST
 
-#undef STAMP_LDA
   // ------------------------------------------------------------------------------------------
   // Epilogue.  Accumulator element v of lane l in block (mi, ni): row 32 mi + 8 (v / 4) + 4 (l / 32)
   // + v % 4, column 32 ni + l % 32 of the wave tile.
@@ -435,11 +419,12 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
       for (int q = 0; q < 4; ++q)
         rf[mi][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + mi * 32 + 8 * q + 4 * kg);
     const int c4 = (lane & 7) * 4, ug = lane >> 3;
-    OutQuad<YBF16> o;
+    auto run_strips = [&](auto vec_tag) __attribute__((always_inline)) {
+    constexpr bool VEC = decltype(vec_tag)::value;
+    OutQuad<YBF16, VEC> o;
     o.Y = a.out;
     o.tok_stride = (size_t)a.N;
     o.row_stride = (size_t)g.gridW * a.N;
-    o.vec = (a.N & 3) == 0;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int nw = n0 + wn * (32 * NI) + ni * 32;  // first column of the strip
@@ -477,7 +462,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
               const f4 t0 = top + cH, t2 = top - cH, t1 = cW + cD, t3 = cW - cD;
               top = hy ? (hx ? (t2 - t3) : (t2 + t3)) : (hx ? (t0 - t1) : (t0 + t1));
             }
-            dfs2d<RB, M0, M0, 0, 0, YBF16>(tile, hy, hx, top, o);
+            dfs2d<RB, M0, M0, 0, 0, OutQuad<YBF16, VEC>>(tile, hy, hx, top, o);
           } else {
             o.base = ((size_t)b * g.s + (size_t)j * R) * a.N + n;
 #pragma unroll
@@ -485,12 +470,15 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
               const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << m) + (h >> (M0 - m))) * kEpiStride);
               top = ((h >> (M0 - m - 1)) & 1) ? (top - d) : (top + d);
             }
-            dfs1d<RB, M0, M0, 0, YBF16>(tile, h, top, o);
+            dfs1d<RB, M0, M0, 0, OutQuad<YBF16, VEC>>(tile, h, top, o);
           }
         }
       }
       __syncthreads();
     }
+    };
+    if ((a.N & 3) == 0) run_strips(std::true_type{});
+    else run_strips(std::false_type{});
   }
 }
 
