@@ -251,18 +251,23 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
                                          (void __attribute__((address_space(3)))*)(so_ + bytesA + i * 4096), 16, 0, 0); \
   } while (0)
 
-  STAMP_REQUEST(0, 0);
+  constexpr int NSTAGE = (NI == 4 && A_INT4) ? 3 : 2;  // LDS stages: loads run NSTAGE-1 K steps ahead of the MFMAs
+  constexpr int kLoadsPerStep = nA + nB;
+#pragma unroll
+  for (int p = 0; p < NSTAGE - 1; ++p)
+    if (p < KT) STAMP_REQUEST(p, p);
 
-  // Step kt: wait for this wave's loads of step kt, then the workgroup barrier (every wave's loads of
-  // step kt have landed, and every wave has left step kt-1, whose stage is now free); request step kt+1
-  // into that free stage; run the MFMAs of step kt while it is in flight.
+  // Step kt: wait for this wave's loads of step kt (the NSTAGE-2 younger steps stay in flight), then the
+  // workgroup barrier (every wave's loads of step kt have landed, and every wave has left step kt-1,
+  // whose stage is now free); request step kt+NSTAGE-1 into that free stage; run the MFMAs of step kt.
   for (int kt = 0; kt < KT; ++kt) {
-    const uint8_t* st = smem + (kt & 1) * stage;
+    const uint8_t* st = smem + (kt % NSTAGE) * stage;
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    if (NSTAGE == 3 && kt + 1 < KT) __builtin_amdgcn_s_waitcnt(0x0F70 | (kLoadsPerStep & 15) | ((kLoadsPerStep >> 4) << 14));  // vmcnt(one step's loads)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                                               // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + 1 < KT) STAMP_REQUEST(kt + 1, (kt + 1) & 1);
+    if (kt + NSTAGE - 1 < KT) STAMP_REQUEST(kt + NSTAGE - 1, (kt + NSTAGE - 1) % NSTAGE);
     __builtin_amdgcn_sched_barrier(0);
 
     v4i fb[2][NI];
@@ -437,7 +442,11 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
           s_tile[rw * kEpiStride + l32] = ((float)acc[mi][ni][v] * rf[mi][v >> 2][v & 3]) * swn;
         }
       }
-      __syncthreads();
+      // the staging tile is private to this wave: its own LDS writes only have to complete (the LDS
+      // executes one wave's operations in order), no workgroup barrier is needed
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      asm volatile("" ::: "memory");
       const int n = nw + c4;
       o.nvalid = a.N - n;
       o.bias = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + n) : (f4){0.0f, 0.0f, 0.0f, 0.0f};
@@ -474,7 +483,9 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
           }
         }
       }
-      __syncthreads();
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // this wave's reads of the tile are done before the next strip overwrites it
+      asm volatile("" ::: "memory");
     }
     };
     if ((a.N & 3) == 0) run_strips(std::true_type{});
@@ -485,7 +496,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
 template <bool A_INT4, int EPI, int RB, bool IS2D, int NI, bool YBF16>
 hipError_t launch_ni(const GemmArgs& a, hipStream_t st) {
   constexpr int BN = 64 * NI;
-  constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
+  constexpr size_t main_lds = ((NI == 4 && A_INT4) ? 3 : 2) * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
   constexpr size_t epi_lds = 2048 + 4 * 128 * kEpiStride * sizeof(float);
   constexpr size_t lds = main_lds > epi_lds ? main_lds : epi_lds;
   static bool attr_set = false;
