@@ -55,14 +55,10 @@ struct GemmArgs {
   StampGeom g;
 };
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 // Where one lane stores the tokens of one unit (a block or an aligned part of one): 4 adjacent output
 // columns per token, written as one 8-byte (bf16) or 16-byte (fp32) store when d_out allows it.
@@ -77,8 +73,9 @@ struct OutQuad {
   __device__ __forceinline__ void put(size_t idx, f4 v) const {
     v += bias;
     if constexpr (YBF16) {
-      const uint32_t lo = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-      const uint32_t hi = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+      // round-to-nearest-even pairs in hardware (v_cvt_pk_bf16_f32)
+      const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[0], v[1]}, bf2));
+      const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[2], v[3]}, bf2));
       uint16_t* y = reinterpret_cast<uint16_t*>(Y) + idx;
       if constexpr (VEC) {
         *reinterpret_cast<uint2*>(y) = make_uint2(lo, hi);
@@ -136,6 +133,17 @@ __device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, c
     dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX + 1, Out>(tile, hy, hx, t2 - t3, o);
   }
 }
+
+// Shape of the fused epilogue for block size RB: R tokens per block, units of at most 16 tokens (the
+// subtree at depth M0 of a block's tree), U units per block, npass passes of 8 units per wave tile.
+template <int RB, bool IS2D>
+struct EpiShape {
+  static constexpr int R = IS2D ? (1 << (2 * RB)) : (1 << RB);
+  static constexpr int nblk = 128 / R;
+  static constexpr int M0 = IS2D ? (RB == 3 ? 1 : 0) : (RB > 4 ? RB - 4 : 0);
+  static constexpr int U = IS2D ? (1 << (2 * M0)) : (1 << M0);
+  static constexpr int npass = (nblk * U) / 8;
+};
 
 // EPI: 0 = int32 accumulators to STaMP-ordered rows; 1 = dequantized fp32 rows (lo: physical rows of
 // [B*s][N]; hi: [B*k][N]); 2 = fused in-block inverse + bias -> Y (A_INT4 only); RB = log2 of the
@@ -250,6 +258,28 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
         __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(baseGB + kb_ + offB[i]), \
                                          (void __attribute__((address_space(3)))*)(so_ + bytesA + i * 4096), 16, 0, 0); \
   } while (0)
+
+  // Fused epilogue: its global operands (weight scales, bias, block sums P of this lane's units) are
+  // requested here, ahead of the main loop, so that their latency is not on the epilogue's path.
+  using ES = EpiShape<(EPI == 2 ? RB : 3), IS2D>;
+  [[maybe_unused]] float e_sw[NI];
+  [[maybe_unused]] f4 e_bias[NI];
+  [[maybe_unused]] f4 e_top[NI][ES::npass];
+  if constexpr (EPI == 2) {
+    const int c4 = (lane & 7) * 4, ug = lane >> 3;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int nw = n0 + wn * (32 * NI) + ni * 32;
+      e_sw[ni] = a.sw[nw + l32];
+      e_bias[ni] = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c4) : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int pass = 0; pass < ES::npass; ++pass) {
+        const int blk = (pass * 8 + ug) / ES::U;
+        const int mrow = min(m0 + wm * 128 + blk * ES::R, a.M - 1);
+        e_top[ni][pass] = *reinterpret_cast<const f4*>(a.P + (size_t)(mrow / a.g.R) * a.Npad + nw + c4);
+      }
+    }
+  }
 
   constexpr int NSTAGE = (NI == 4 && A_INT4) ? 3 : 2;  // LDS stages: loads run NSTAGE-1 K steps ahead of the MFMAs
   constexpr int kLoadsPerStep = nA + nB;
@@ -410,11 +440,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
     // fused: per 32-column strip, dequantize into this wave's LDS tile [128][kEpiStride]; then the wave's
     // 8 groups of 8 lanes each take one unit (a block, or an aligned 16-token part of one) and 4 columns
     // per lane, and run the depth-first inverse, storing the unit's tokens.
-    constexpr int R = IS2D ? (1 << (2 * RB)) : (1 << RB);
-    constexpr int nblk = 128 / R;                                   // blocks per wave tile
-    constexpr int M0 = IS2D ? (RB == 3 ? 1 : 0) : (RB > 4 ? RB - 4 : 0);  // unit = subtree at depth M0
-    constexpr int U = IS2D ? (1 << (2 * M0)) : (1 << M0);           // units per block
-    constexpr int npass = (nblk * U) / 8;
+    constexpr int R = ES::R, M0 = ES::M0, U = ES::U, npass = ES::npass;
     float* s_tile = reinterpret_cast<float*>(smem + 2048) + wave * (128 * kEpiStride);
     // row factors of this lane's 64 accumulator rows, read before any staging write
     f4 rf[4][4];
@@ -433,7 +459,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int nw = n0 + wn * (32 * NI) + ni * 32;  // first column of the strip
-      const float swn = a.sw[nw + l32];
+      const float swn = e_sw[ni];
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
@@ -449,7 +475,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
       asm volatile("" ::: "memory");
       const int n = nw + c4;
       o.nvalid = a.N - n;
-      o.bias = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + n) : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+      o.bias = e_bias[ni];
 #pragma unroll
       for (int pass = 0; pass < npass; ++pass) {
         const int unit = pass * 8 + ug;
@@ -458,7 +484,7 @@ __global__ __launch_bounds__(256, (NI == 2 ? 2 : 1)) void k_gemm(const GemmArgs 
         if (mrow < a.M && n < a.N) {
           const int b = mrow / g.s, pr = mrow - b * g.s;
           const int j = pr / g.R;
-          f4 top = *reinterpret_cast<const f4*>(a.P + ((size_t)b * g.k + j) * a.Npad + n);
+          f4 top = e_top[ni][pass];
           const float* tile = s_tile + blk * R * kEpiStride + c4;
           if constexpr (IS2D) {
             const int bi = j / g.G, bj = j - bi * g.G;
