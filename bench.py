@@ -91,6 +91,8 @@ def main():
     ap.add_argument("--cpu-cols", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--engine", choices=["int8", "fp6"], default="int8",
+                    help="matrix pipeline of the 4-bit rows' GEMM")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (int32 add), the "
                          "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -118,6 +120,7 @@ def main():
     del Wd
     if args.unfused:
         plan.set_unfused(True)
+    plan.set_gemm_engine(args.engine)
     ws = plan.alloc_workspace()
     Y = torch.empty((w.batch, w.seq_len, w.d_out), dtype=torch.int16, device="cuda")
 
@@ -148,6 +151,9 @@ def main():
     plan.quantize_act(Xd, q_hi, q_lo, scales, ws)
     stages = {}
     names = {0: "transform_quant_lo", 1: "transform_quant_hi", 2: "gemm_hi", 3: "inverse_top", 4: "gemm_lo"}
+    if args.engine == "fp6":
+        names = {0: "transform_quant_lo", 1: "transform_quant_hi", 2: "gemm_hi", 3: "inverse_top", 6: "repack_fp6",
+                 4: "gemm_lo"}
     if args.unfused:
         names[5] = "inverse_bottom"
     for sid, nm in names.items():

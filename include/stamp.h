@@ -154,7 +154,9 @@ stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* plan, int8_t* qW_hos
  *   0 bottom-levels transform + 4-bit quantization kernel   1 top levels + 8-bit rows
  *   2 GEMM of the 8-bit rows                                3 top levels of the inverse
  *   4 GEMM of the 4-bit rows (with the fused inverse unless the plan is set unfused)
- *   5 in-block inverse kernel (unfused plans only) */
+ *   5 in-block inverse kernel (unfused plans only)
+ *   6 conversion of the packed 4-bit rows to the FP6 engine's operand layout (FP6 engine only; with
+ *     that engine stage 4 is the GEMM alone and reads what stage 6 wrote to the workspace) */
 stamp_status_t stamp_debug_run_stage(const stamp_plan_t* plan, int32_t stage, const void* X_dev,
                                      int8_t* q_hi_dev, uint8_t* q_lo_dev, float* scales_dev,
                                      void* Y_dev, void* workspace_dev, size_t workspace_bytes,
@@ -164,6 +166,19 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* plan, int32_t stage, co
  * inverse transform fused into its epilogue (default where the shape allows it), 1 = GEMM writing
  * dequantized fp32 rows to the workspace followed by a separate inverse kernel. */
 stamp_status_t stamp_plan_set_unfused(stamp_plan_t* plan, int32_t unfused);
+
+/* Matrix pipeline that multiplies the 4-bit rows (step "Y <- X W" of Algorithm "STaMP Linear" for the
+ * rows quantized to bits_lo = 4 against the 4-bit weights).  Both compute the same integer sums
+ * acc[m, n] = sum_c code[m, c] * qW[c, n] exactly, so every result of the library is bit-identical
+ * under either setting:
+ *   STAMP_GEMM_INT8  the codes as int8, int8 x int8 -> int32 MFMA (default);
+ *   STAMP_GEMM_FP6   the codes as 6-bit floating point numbers code / 8 (E2M3, exact), FP6 x FP6 -> fp32
+ *                    MFMA at twice the rate per clock; the fp32 accumulator holds acc / 64 exactly
+ *                    (|acc| <= 49 d_in < 2^24).  Costs one conversion pass over the packed rows.
+ * The 8-bit rows always run on the int8 pipeline.  May be changed between calls; the workspace size
+ * does not depend on it.  Returns STAMP_ERR_UNSUPPORTED for any other value. */
+typedef enum { STAMP_GEMM_INT8 = 0, STAMP_GEMM_FP6 = 1 } stamp_gemm_engine_t;
+stamp_status_t stamp_plan_set_gemm_engine(stamp_plan_t* plan, int32_t engine);
 
 const char* stamp_status_string(stamp_status_t status);
 

@@ -21,7 +21,8 @@ STATUS_NAMES = {0: "STAMP_OK", 1: "STAMP_ERR_NULL", 2: "STAMP_ERR_SHAPE", 3: "ST
 # every symbol include/stamp.h declares
 EXPORTS = ["stamp_plan_create", "stamp_plan_destroy", "stamp_plan_workspace_bytes", "stamp_plan_row_of_coeff",
            "stamp_quantize_act", "stamp_linear_forward", "stamp_linear_forward_q", "stamp_inverse",
-           "stamp_debug_gemm_acc", "stamp_debug_weight_codes", "stamp_debug_run_stage", "stamp_plan_set_unfused", "stamp_status_string"]
+           "stamp_debug_gemm_acc", "stamp_debug_weight_codes", "stamp_debug_run_stage", "stamp_plan_set_unfused", "stamp_plan_set_gemm_engine",
+           "stamp_status_string"]
 
 
 class StampError(RuntimeError):
@@ -101,6 +102,8 @@ def load_library():
     lib.stamp_debug_run_stage.restype = C.c_int
     lib.stamp_plan_set_unfused.argtypes = [vp, i32]
     lib.stamp_plan_set_unfused.restype = C.c_int
+    lib.stamp_plan_set_gemm_engine.argtypes = [vp, i32]
+    lib.stamp_plan_set_gemm_engine.restype = C.c_int
     lib.stamp_status_string.argtypes = [C.c_int]
     lib.stamp_status_string.restype = C.c_char_p
     _lib = lib
@@ -155,6 +158,11 @@ class StampPlan:
         out = np.empty(self.desc.seq_len, dtype=np.int32)
         _check(self.lib.stamp_plan_row_of_coeff(self._h, out.ctypes.data_as(C.POINTER(C.c_int32))), "stamp_plan_row_of_coeff")
         return out
+
+    def set_gemm_engine(self, engine):
+        """engine: "int8" (default) or "fp6": the matrix pipeline that multiplies the 4-bit rows."""
+        code = {"int8": 0, "fp6": 1}[engine] if isinstance(engine, str) else int(engine)
+        _check(self.lib.stamp_plan_set_gemm_engine(self._h, code), "stamp_plan_set_gemm_engine")
 
     def set_unfused(self, unfused: bool):
         _check(self.lib.stamp_plan_set_unfused(self._h, int(bool(unfused))), "stamp_plan_set_unfused")

@@ -84,6 +84,7 @@ void layout_workspace(stamp_plan* p) {
   p->ws_scales = take((size_t)g.B * g.s * sizeof(float));
   p->ws_ythi = take((size_t)g.B * g.k * g.N * sizeof(float));
   p->ws_P = take((size_t)g.B * g.k * p->Npad * sizeof(float));
+  p->ws_a6 = take(stamp_a6_bytes(p));
   p->ws_ytlo = off;
   if (p->unfused || !p->fused_ok) take((size_t)g.B * g.s * g.N * sizeof(float));
   p->ws_total = off;
@@ -102,13 +103,19 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
   float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
   if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
   if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st) != hipSuccess) return STAMP_ERR_DEVICE;
-  if (p->fused_ok && !p->unfused) {
-    if (stamp_launch_gemm_lo(p, q_lo, scales, 2, Y, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  const bool fused = p->fused_ok && !p->unfused;
+  float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
+  if (p->engine == STAMP_GEMM_FP6) {
+    uint8_t* a6 = at(ws, p->ws_a6);
+    if (stamp_launch_repack6(p, q_lo, a6, st) != hipSuccess) return STAMP_ERR_DEVICE;
+    if (stamp_launch_gemm_lo6(p, a6, scales, fused ? 2 : 1, fused ? Y : ytlo, fused ? P : nullptr, st) != hipSuccess)
+      return STAMP_ERR_DEVICE;
   } else {
-    float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
-    if (stamp_launch_gemm_lo(p, q_lo, scales, 1, ytlo, nullptr, st) != hipSuccess) return STAMP_ERR_DEVICE;
-    if (stamp_launch_inverse_bottom(p, ytlo, 0, P, p->Npad, p->geom.N, p->bias_dev, Y, st) != hipSuccess) return STAMP_ERR_DEVICE;
+    if (stamp_launch_gemm_lo(p, q_lo, scales, fused ? 2 : 1, fused ? Y : ytlo, fused ? P : nullptr, st) != hipSuccess)
+      return STAMP_ERR_DEVICE;
   }
+  if (!fused && stamp_launch_inverse_bottom(p, ytlo, 0, P, p->Npad, p->geom.N, p->bias_dev, Y, st) != hipSuccess)
+    return STAMP_ERR_DEVICE;
   return STAMP_OK;
 }
 
@@ -164,6 +171,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   uint32_t* colmax = nullptr;
   bool ok = hipMalloc(reinterpret_cast<void**>(&p->qW_dev), (size_t)p->Npad * p->Kpad) == hipSuccess &&
+            hipMalloc(reinterpret_cast<void**>(&p->qW6_dev), stamp_b6_bytes(p)) == hipSuccess &&
             hipMalloc(reinterpret_cast<void**>(&p->sw_dev), sizeof(float) * p->Npad) == hipSuccess &&
             hipMalloc(reinterpret_cast<void**>(&colmax), sizeof(uint32_t) * g.N) == hipSuccess;
   if (ok && bias_dev != nullptr) ok = hipMalloc(reinterpret_cast<void**>(&p->bias_dev), sizeof(float) * p->Npad) == hipSuccess;
@@ -179,6 +187,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
              hipMemcpyAsync(p->bias_dev, bias_dev, sizeof(float) * g.N, hipMemcpyDeviceToDevice, st) == hipSuccess;
   }
   if (dev_ok) dev_ok = stamp_launch_weight_quant(p, static_cast<const float*>(W_dev), st, colmax) == hipSuccess;
+  if (dev_ok) dev_ok = stamp_launch_weight_quant6(p, static_cast<const float*>(W_dev), colmax, st) == hipSuccess;
   // the scratch column maxima must outlive the kernels just enqueued: hipFree waits for the device
   (void)hipFree(colmax);
   if (!dev_ok) {
@@ -192,6 +201,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
 stamp_status_t stamp_plan_destroy(stamp_plan_t* p) {
   if (p == nullptr) return STAMP_ERR_NULL;
   if (p->qW_dev) (void)hipFree(p->qW_dev);
+  if (p->qW6_dev) (void)hipFree(p->qW6_dev);
   if (p->sw_dev) (void)hipFree(p->sw_dev);
   if (p->bias_dev) (void)hipFree(p->bias_dev);
   free(p->row_of_coeff);
@@ -205,6 +215,13 @@ stamp_status_t stamp_plan_set_unfused(stamp_plan_t* p, int32_t unfused) {
   if (p == nullptr) return STAMP_ERR_NULL;
   p->unfused = unfused ? 1 : 0;
   layout_workspace(p);
+  return STAMP_OK;
+}
+
+stamp_status_t stamp_plan_set_gemm_engine(stamp_plan_t* p, int32_t engine) {
+  if (p == nullptr) return STAMP_ERR_NULL;
+  if (engine != STAMP_GEMM_INT8 && engine != STAMP_GEMM_FP6) return STAMP_ERR_UNSUPPORTED;
+  p->engine = engine;
   return STAMP_OK;
 }
 
@@ -265,6 +282,15 @@ stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* p, const int8_t* q_hi, c
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   // accumulator mode never reads the activation scales
   if (stamp_launch_gemm_hi(p, q_hi, nullptr, 0, acc, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (p->engine == STAMP_GEMM_FP6) {
+    // parity aid, not a timed path: the converted operand lives in a temporary of its own
+    uint8_t* a6 = nullptr;
+    if (hipMalloc(reinterpret_cast<void**>(&a6), stamp_a6_bytes(p)) != hipSuccess) { (void)hipGetLastError(); return STAMP_ERR_ALLOC; }
+    const bool ok = stamp_launch_repack6(p, q_lo, a6, st) == hipSuccess &&
+                    stamp_launch_gemm_lo6(p, a6, nullptr, 0, acc, nullptr, st) == hipSuccess;
+    (void)hipFree(a6);  // waits for the kernels above
+    return ok ? STAMP_OK : STAMP_ERR_DEVICE;
+  }
   if (stamp_launch_gemm_lo(p, q_lo, nullptr, 0, acc, nullptr, st) != hipSuccess) return STAMP_ERR_DEVICE;
   return STAMP_OK;
 }
@@ -273,7 +299,8 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
                                      float* scales, void* Y, void* ws, size_t ws_bytes, void* hip_stream) {
   if (p == nullptr || X == nullptr || q_hi == nullptr || q_lo == nullptr || scales == nullptr || Y == nullptr)
     return STAMP_ERR_NULL;
-  if (stage < 0 || stage > 5) return STAMP_ERR_SHAPE;
+  if (stage < 0 || stage > 6) return STAMP_ERR_SHAPE;
+  if (stage == 6 && p->engine != STAMP_GEMM_FP6) return STAMP_ERR_UNSUPPORTED;
   if (stage == 5 && p->fused_ok && !p->unfused) return STAMP_ERR_UNSUPPORTED;
   if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
@@ -289,8 +316,13 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
     case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 2); break;
     case 2: e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st); break;
     case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st); break;
-    case 4: e = fused ? stamp_launch_gemm_lo(p, q_lo, scales, 2, Y, P, st)
-                      : stamp_launch_gemm_lo(p, q_lo, scales, 1, ytlo, nullptr, st); break;
+    case 4:
+      if (p->engine == STAMP_GEMM_FP6)
+        e = stamp_launch_gemm_lo6(p, at(ws, p->ws_a6), scales, fused ? 2 : 1, fused ? Y : (void*)ytlo, fused ? P : nullptr, st);
+      else
+        e = stamp_launch_gemm_lo(p, q_lo, scales, fused ? 2 : 1, fused ? Y : (void*)ytlo, fused ? P : nullptr, st);
+      break;
+    case 6: e = stamp_launch_repack6(p, q_lo, at(ws, p->ws_a6), st); break;
     case 5: e = stamp_launch_inverse_bottom(p, ytlo, 0, P, p->Npad, p->geom.N, p->bias_dev, Y, st); break;
   }
   return e == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;

@@ -1,0 +1,275 @@
+// GEMM of the 4-bit rows of the STaMP linear layer on the FP6 matrix pipeline of gfx950 (step
+// "Y <- X W" of Algorithm "STaMP Linear" for the rows quantized to 4 bits against 4-bit weights).
+//
+// A 4-bit code c in [-7, 7] is held as the E2M3 number c / 8: sign bit, exponent field 0, mantissa
+// field |c| (a subnormal, so the six bits are just sign and magnitude).  v_mfma_f32_32x32x64_f8f6f4
+// multiplies such operands exactly and accumulates in fp32; every product is a multiple of 1/64 and a
+// whole sum stays below 2^24 / 64 in magnitude (d_in <= 8192, |c c'| <= 49), so the fp32 accumulator
+// holds acc / 64 EXACTLY, where acc is the integer sum the int8 pipeline computes: same result bit for
+// bit, at twice the matrix rate per clock.  The factor 64 is folded into the row scale.
+//
+// Operand layout ("planes"): per 256-row (128-column) tile and K step of 128 channels, 12 planes of
+// 256 (128) x 8 bytes.  The 32 codes that one lane feeds to one MFMA (channels 32 f .. 32 f + 31 of
+// the step, f = 0..3, as a little-endian stream of 6-bit fields = 24 bytes) are split into three
+// 8-byte parts p; plane 3 f + p holds part p of every row.  A fragment is then three 8-byte LDS reads
+// in which consecutive lanes read consecutive addresses (no bank conflicts, no swizzle), and the
+// global image equals the LDS image, so a K step is staged by plain asynchronous 16-byte copies.
+// MFMA k (0, 1) of a step consumes channels [64 k, 64 k + 64): lane group kg = lane / 32 takes f = 2 k + kg.
+#include "stamp_gemm_common.h"
+
+namespace {
+
+using namespace stamp_gemm;
+
+constexpr int kPlanes = 12;
+constexpr int kStageA6 = kPlanes * 256 * 8;  // 24 KB
+constexpr int kStageB6 = kPlanes * 128 * 8;  // 12 KB
+constexpr int kStage6 = kStageA6 + kStageB6;
+
+// eight two's-complement nibbles -> eight sign-magnitude 6-bit fields (48 bits)
+__device__ __forceinline__ uint64_t nib8_to_e2m3(uint32_t w) {
+  const uint32_t s = w & 0x88888888u;  // sign bit of every nibble
+  const uint32_t sg = s >> 3;          // 1 in every negative nibble
+  // |c|: complement the negative nibbles and add 1 (no carry leaves a nibble: ~c + 1 <= 7; the code -8 never occurs)
+  const uint32_t mag = ((w ^ (sg * 15u)) + sg) & 0x77777777u;
+  uint64_t out = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t c = ((mag >> (4 * j)) & 7u) | (((s >> (4 * j + 3)) & 1u) << 5);
+    out |= (uint64_t)c << (6 * j);
+  }
+  return out;
+}
+
+// 32 codes (one 16-byte chunk of packed nibbles, low nibble = even channel) -> 24 bytes
+__device__ __forceinline__ void chunk_to_e2m3(u4 w, uint64_t (&part)[3]) {
+  const uint64_t a = nib8_to_e2m3(w.x), b = nib8_to_e2m3(w.y), c = nib8_to_e2m3(w.z), d = nib8_to_e2m3(w.w);
+  part[0] = a | (b << 48);
+  part[1] = (b >> 16) | (c << 32);
+  part[2] = (c >> 32) | (d << 16);
+}
+
+// q_lo (tiled [Mpad/256][KT][256 rows][64 bytes], channels in natural order) -> planes.
+// One workgroup per (row tile, K step); thread = row, four fragments each.
+__global__ __launch_bounds__(256) void k_repack6(const uint8_t* __restrict__ q_lo, uint8_t* __restrict__ a6) {
+  const size_t blk = blockIdx.x;
+  const int row = threadIdx.x;
+  const uint8_t* src = q_lo + blk * (256 * 64) + row * 64;
+  uint8_t* dst = a6 + blk * kStageA6 + row * 8;
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+    const u4 w = *reinterpret_cast<const u4*>(src + (f << 4));
+    uint64_t part[3];
+    chunk_to_e2m3(w, part);
+#pragma unroll
+    for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * (256 * 8)) = part[p];
+  }
+}
+
+// Plan-time weight codes in the plane layout: per output channel n, code = rne(W_cn * (7 / max)) as in
+// the integer engine (round-to-nearest weights, one scale per output channel), stored as E2M3 c / 8.
+// One thread per (column, 32-channel fragment).
+__global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, const uint32_t* __restrict__ colmax,
+                                                  uint8_t* __restrict__ b6, int d, int N, int Kpad, int Npad, size_t sc,
+                                                  size_t sn) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  const int frag = blockIdx.y;  // 32-channel fragment over the whole depth
+  if (n >= Npad) return;
+  float inv = 0.0f;
+  if (n < N) {
+    const float a = __uint_as_float(colmax[n]);
+    if (a > 0.0f) inv = __fdiv_rn(7.0f, a);
+  }
+  uint64_t part[3] = {0, 0, 0};
+  uint64_t acc = 0;
+  int nbits = 0, o = 0;
+  for (int i = 0; i < 32; ++i) {
+    const int c = frag * 32 + i;
+    uint32_t code = 0;
+    if (n < N && c < d) {
+      float r = rintf(__fmul_rn(W[(size_t)c * sc + (size_t)n * sn], inv));
+      r = fminf(fmaxf(r, -7.0f), 7.0f);
+      const int q = (int)r;
+      code = (uint32_t)(q < 0 ? -q : q) | (q < 0 ? 32u : 0u);
+    }
+    acc |= (uint64_t)code << nbits;
+    nbits += 6;
+    if (nbits >= 64) {
+      part[o++] = acc;
+      nbits -= 64;
+      acc = (nbits > 0) ? ((uint64_t)code >> (6 - nbits)) : 0;
+    }
+  }
+  const int KT = Kpad >> 7;
+  const int kt = frag >> 2, f = frag & 3;
+  uint8_t* dst = b6 + ((size_t)(n >> 7) * KT + kt) * kStageB6 + (size_t)(n & 127) * 8;
+  for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * (128 * 8)) = part[p];
+}
+
+template <int EPI, int RB, bool IS2D, bool YBF16>
+__global__ __launch_bounds__(256, 2) void k_gemm6(const GemmArgs a) {
+  using Acc = AccF6Lo;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  constexpr int kMainBytes = 2 * kStage6;
+  constexpr int kRowInfoOff = (EPI == 2 && kTileBytes > kMainBytes) ? kTileBytes : kMainBytes;
+  constexpr int nA = kStageA6 / (256 * 16), nB = kStageB6 / (256 * 16);  // 16-byte chunks per thread and step: 6 and 3
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, kg = lane >> 5;
+  int tm, tn;
+  tile_of_block(a.M, a.Npad, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int KT = a.Kpad / BK;
+
+  // global image = LDS image: chunk i * 256 + tid of a stage goes to byte (i * 256 + tid) * 16
+  const uint8_t* gA = a.A + (size_t)tm * KT * kStageA6 + tid * 16;
+  const uint8_t* gB = a.Bq + (size_t)tn * KT * kStageB6 + tid * 16;
+#define STAMP_REQUEST6(KSTEP, STG)                                                                               \
+  do {                                                                                                           \
+    uint8_t* so_ = smem + (STG) * kStage6 + wave * 1024;                                                         \
+    const uint8_t* sa_ = gA + (size_t)(KSTEP) * kStageA6;                                                        \
+    const uint8_t* sb_ = gB + (size_t)(KSTEP) * kStageB6;                                                        \
+    _Pragma("unroll") for (int i = 0; i < nA; ++i)                                                               \
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * 4096),        \
+                                         (void __attribute__((address_space(3)))*)(so_ + i * 4096), 16, 0, 0);   \
+    _Pragma("unroll") for (int i = 0; i < nB; ++i)                                                               \
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sb_ + i * 4096),        \
+                                         (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * 4096), 16, 0, 0); \
+  } while (0)
+
+  // fragment addresses inside a stage: plane (2 k + kg) * 3 + p, row / column of this lane
+  const int baseA = (kg * 3) * (256 * 8) + (wm * 128 + l32) * 8;
+  const int baseB = kStageA6 + (kg * 3) * (128 * 8) + (wn * 64 + l32) * 8;
+
+  v16f acc[4][NI];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  STAMP_REQUEST6(0, 0);
+  EpiOperands<EPI, RB, IS2D> eo;
+  eo.request(a, m0, n0, lane, wm, wn);
+  store_row_info<Acc, EPI>(a, m0, tid, smem + kRowInfoOff);
+
+  // Step kt: this wave's loads of step kt have landed, workgroup barrier (all of step kt is visible and
+  // the stage of step kt-1 is free), request step kt+1 into the free stage, then the two MFMA rounds.
+  for (int kt = 0; kt < KT; ++kt) {
+    const uint8_t* st = smem + (kt & 1) * kStage6;
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kt + 1 < KT) STAMP_REQUEST6(kt + 1, (kt + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+
+    u2 fa[2][4][3], fb[2][NI][3];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+#pragma unroll
+      for (int p = 0; p < 3; ++p) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          fb[k][ni][p] = *reinterpret_cast<const u2*>(st + baseB + (k * 6 + p) * (128 * 8) + ni * (32 * 8));
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+          fa[k][mi][p] = *reinterpret_cast<const u2*>(st + baseA + (k * 6 + p) * (256 * 8) + mi * (32 * 8));
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      v8i vb[NI];
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        vb[ni] = (v8i){(int)fb[k][ni][0].x, (int)fb[k][ni][0].y, (int)fb[k][ni][1].x, (int)fb[k][ni][1].y,
+                       (int)fb[k][ni][2].x, (int)fb[k][ni][2].y, 0, 0};
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) {
+        const v8i va = (v8i){(int)fa[k][mi][0].x, (int)fa[k][mi][0].y, (int)fa[k][mi][1].x, (int)fa[k][mi][1].y,
+                             (int)fa[k][mi][2].x, (int)fa[k][mi][2].y, 0, 0};
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb[ni], acc[mi][ni], 2, 2, 0, 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __syncthreads();
+#undef STAMP_REQUEST6
+
+  epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave);
+}
+
+template <int EPI, int RB, bool IS2D, bool YBF16>
+hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
+  constexpr size_t main_lds = 2 * (size_t)kStage6;
+  constexpr size_t epi_lds = (EPI == 2) ? (size_t)kTileBytes : 0;
+  constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + 2048;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm6<EPI, RB, IS2D, YBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
+  hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16>), dim3(mt * nt), dim3(256), lds, st, a);
+  return hipGetLastError();
+}
+
+template <int EPI, int RB, bool IS2D>
+hipError_t launch(const GemmArgs& a, hipStream_t st) {
+  if constexpr (EPI == 2) {
+    if (a.g.y_bf16) return launch_y<EPI, RB, IS2D, true>(a, st);
+  }
+  return launch_y<EPI, RB, IS2D, false>(a, st);
+}
+
+}  // namespace
+
+size_t stamp_a6_bytes(const stamp_plan* p) { return (size_t)(p->Mpad / 256) * (p->Kpad / 128) * kStageA6; }
+size_t stamp_b6_bytes(const stamp_plan* p) { return (size_t)(p->Npad / 128) * (p->Kpad / 128) * kStageB6; }
+
+hipError_t stamp_launch_weight_quant6(const stamp_plan* p, const float* W, const uint32_t* colmax, hipStream_t st) {
+  const int d = p->geom.d, N = p->geom.N;
+  const size_t sc = p->desc.w_is_out_by_in ? 1 : (size_t)N;
+  const size_t sn = p->desc.w_is_out_by_in ? (size_t)d : 1;
+  hipLaunchKernelGGL(k_w_quant6, dim3((p->Npad + 255) / 256, p->Kpad / 32), dim3(256), 0, st, W, colmax, p->qW6_dev, d, N,
+                     p->Kpad, p->Npad, sc, sn);
+  return hipGetLastError();
+}
+
+hipError_t stamp_launch_repack6(const stamp_plan* p, const uint8_t* q_lo, uint8_t* a6, hipStream_t st) {
+  hipLaunchKernelGGL(k_repack6, dim3((p->Mpad / 256) * (p->Kpad / 128)), dim3(256), 0, st, q_lo, a6);
+  return hipGetLastError();
+}
+
+hipError_t stamp_launch_gemm_lo6(const stamp_plan* p, const uint8_t* a6, const float* scales, int mode, void* out,
+                                 const float* P, hipStream_t st) {
+  GemmArgs a = stamp_gemm_args(p, scales, out);
+  a.A = a6;
+  a.Bq = p->qW6_dev;
+  a.M = p->geom.B * p->geom.s;
+  a.P = P;
+  if (mode == 0) return launch<0, 0, false>(a, st);
+  if (mode == 1) return launch<1, 0, false>(a, st);
+  if (mode != 2) return hipErrorInvalidValue;
+  const StampGeom& g = p->geom;
+  if (!g.is2d) {
+    switch (g.r) {
+      case 3: return launch<2, 3, false>(a, st);
+      case 4: return launch<2, 4, false>(a, st);
+      case 5: return launch<2, 5, false>(a, st);
+      case 6: return launch<2, 6, false>(a, st);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  switch (g.r) {
+    case 2: return launch<2, 2, true>(a, st);
+    case 3: return launch<2, 3, true>(a, st);
+    default: return hipErrorInvalidValue;
+  }
+}

@@ -1,0 +1,374 @@
+// Device code shared by the GEMM kernels of the STaMP linear layer (gfx950): the workgroup -> tile
+// map, the per-row dequantization factors, and the epilogue (dequantization Y' = acc * scale_m * sw_n
+// of the Background section, then, in the fused mode, the in-block levels of the inverse sequence
+// transform by the commutation identity of section "Method", bias and the store of Y).
+//
+// Every kernel here computes a 256 x 128 output tile per workgroup of 4 waves (2 x 2); a wave owns
+// 128 x 64 outputs = 4 x 2 MFMA blocks of 32 x 32, 16 accumulator registers per block and lane:
+// element v of lane l of block (mi, ni) is row 32 mi + 8 (v / 4) + 4 (l / 32) + v % 4, column
+// 32 ni + l % 32 of the wave tile.
+#ifndef STAMP_GEMM_COMMON_H_
+#define STAMP_GEMM_COMMON_H_
+
+#include <type_traits>
+
+#include "stamp_internal.h"
+
+namespace stamp_gemm {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));  // first-class 16-byte value (keeps staging arrays in registers)
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+
+constexpr int BM = 256, BN = 128, BK = 128;
+constexpr int NI = 2;           // 32-column MFMA blocks per wave along N
+constexpr int kEpiStride = 36;  // floats per row of the per-wave epilogue staging tile (16-byte aligned rows)
+constexpr int kTileBytes = 4 * 128 * kEpiStride * 4;  // the four waves' staging tiles
+constexpr int kNumXcd = 8;
+constexpr int kGroupM = 8;
+
+constexpr float kInvSqrt2 = 0.70710678118654752440f;
+
+__device__ __forceinline__ float haar_norm_dev(int level, int is2d) {
+  return is2d ? ldexpf(1.0f, -level) : ldexpf((level & 1) ? kInvSqrt2 : 1.0f, -(level >> 1));
+}
+
+struct GemmArgs {
+  const uint8_t* A;      // activation codes in the layout of the kernel's operand format
+  const uint8_t* Bq;     // weight codes in the layout of the kernel's operand format
+  const float* scales;   // [B*s] physical order
+  const float* sw;       // [Npad]
+  const float* bias;     // [Npad] or nullptr
+  const float* P;        // [B*k][Npad] block sums of the inverse (fused mode)
+  void* out;
+  int M;                 // rows of A
+  int N, Npad, Kpad;
+  int a_row_bytes;       // 8-bit rows: valid bytes per A row
+  size_t a_last16;       // 8-bit rows: byte offset of the last 16-byte chunk of A (loads are clamped to it)
+  StampGeom g;
+};
+
+// How a kernel's accumulators map to the integer sum acc = sum_c code[m, c] * qW[c, n]:
+//   int8 MFMA, 4-bit rows: both operands are held as code * 16         -> register = 256 acc
+//   int8 MFMA, 8-bit rows: the weights are held as code * 16           -> register = 16 acc
+//   FP6 MFMA, 4-bit rows:  both operands are held as code / 8 (E2M3)   -> register = acc / 64 (exact in fp32)
+struct AccI8Lo {
+  typedef v16i V;
+  static constexpr bool kLoRows = true;
+  static constexpr float kToAcc = 1.0f / 256.0f;
+  static __device__ __forceinline__ int to_i32(int x) { return x >> 8; }
+};
+struct AccI8Hi {
+  typedef v16i V;
+  static constexpr bool kLoRows = false;
+  static constexpr float kToAcc = 1.0f / 16.0f;
+  static __device__ __forceinline__ int to_i32(int x) { return x >> 4; }
+};
+struct AccF6Lo {
+  typedef v16f V;
+  static constexpr bool kLoRows = true;
+  static constexpr float kToAcc = 64.0f;
+  static __device__ __forceinline__ int to_i32(float x) { return (int)(x * 64.0f); }
+};
+
+// workgroup -> tile, XCD aware: consecutive ids on one XCD walk 8 M-tiles, then the next N-tile, so
+// that the 32 workgroups resident on one XCD cover 8 x 4 neighbouring tiles and share operand panels
+// in that XCD's L2.
+__device__ __forceinline__ void tile_of_block(int M, int Npad, int& tm, int& tn) {
+  const int mt = (M + BM - 1) / BM, nt = Npad / BN;
+  const int total = mt * nt;
+  const int bid = blockIdx.x;
+  const int xcd = bid % kNumXcd, local = bid / kNumXcd;
+  const int tall = total / kNumXcd, rem = total % kNumXcd;
+  const int sid = xcd * tall + min(xcd, rem) + local;
+  const int per_group = kGroupM * nt;
+  const int grp = sid / per_group, in_grp = sid - grp * per_group;
+  const int gm = min(kGroupM, mt - grp * kGroupM);
+  tm = grp * kGroupM + in_grp % gm;
+  tn = in_grp / gm;
+}
+
+// Where one lane stores the tokens of one unit (a block or an aligned part of one): 4 adjacent output
+// columns per token, written as one 8-byte (bf16) or 16-byte (fp32) store when d_out allows it.
+template <bool YBF16, bool VEC>
+struct OutQuad {
+  void* Y;
+  size_t base;        // element index of token 0 of the block, first of the 4 columns
+  size_t tok_stride;  // d_out
+  size_t row_stride;  // 2-D: grid_w * d_out
+  f4 bias;
+  int nvalid;         // how many of the 4 columns exist (d_out tail)
+  __device__ __forceinline__ void put(size_t idx, f4 v) const {
+    v += bias;
+    if constexpr (YBF16) {
+      // round-to-nearest-even pairs in hardware (v_cvt_pk_bf16_f32)
+      const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[0], v[1]}, bf2));
+      const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[2], v[3]}, bf2));
+      uint16_t* y = reinterpret_cast<uint16_t*>(Y) + idx;
+      if constexpr (VEC) {
+        *reinterpret_cast<uint2*>(y) = make_uint2(lo, hi);
+      } else {
+        if (nvalid > 0) y[0] = (uint16_t)lo;
+        if (nvalid > 1) y[1] = (uint16_t)(lo >> 16);
+        if (nvalid > 2) y[2] = (uint16_t)hi;
+        if (nvalid > 3) y[3] = (uint16_t)(hi >> 16);
+      }
+    } else {
+      float* y = reinterpret_cast<float*>(Y) + idx;
+      if constexpr (VEC) {
+        *reinterpret_cast<f4*>(y) = v;
+      } else {
+        if (nvalid > 0) y[0] = v[0];
+        if (nvalid > 1) y[1] = v[1];
+        if (nvalid > 2) y[2] = v[2];
+        if (nvalid > 3) y[3] = v[3];
+      }
+    }
+  }
+};
+
+// Depth-first inverse of one unit for 4 columns.  The unit is the subtree rooted at node (M0, h) of a
+// block's Haar tree; node (M, I) of that subtree holds the sum `a` of its tokens; tile[e * kEpiStride]
+// is the block's coefficient at in-block STaMP position e = 2^M + (h << (M - M0)) + I.  Only O(r)
+// values are live at any time and every coefficient is read once.
+template <int RLOG, int M0, int M, int I, typename Out>
+__device__ __forceinline__ void dfs1d(const float* tile, int h, f4 a, const Out& o) {
+  if constexpr (M == RLOG) {
+    o.put(o.base + (size_t)((h << (RLOG - M0)) + I) * o.tok_stride, a);
+  } else {
+    const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << M) + (h << (M - M0)) + I) * kEpiStride);
+    dfs1d<RLOG, M0, M + 1, 2 * I, Out>(tile, h, a + d, o);
+    dfs1d<RLOG, M0, M + 1, 2 * I + 1, Out>(tile, h, a - d, o);
+  }
+}
+
+// 2-D: the unit is the quadtree node (M0, hy, hx) of a g x g block; bands W, H, D of level-node side
+// gl = 2^M sit at e = gl^2 (1 + band) + iy * gl + ix.
+template <int RLOG, int M0, int M, int IY, int IX, typename Out>
+__device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, const Out& o) {
+  if constexpr (M == RLOG) {
+    o.put(o.base + (size_t)((hy << (RLOG - M0)) + IY) * o.row_stride + (size_t)((hx << (RLOG - M0)) + IX) * o.tok_stride, a);
+  } else {
+    constexpr int gl = 1 << M;
+    const int e0 = ((hy << (M - M0)) + IY) * gl + ((hx << (M - M0)) + IX);
+    const f4 cW = *reinterpret_cast<const f4*>(tile + (gl * gl + e0) * kEpiStride);
+    const f4 cH = *reinterpret_cast<const f4*>(tile + (2 * gl * gl + e0) * kEpiStride);
+    const f4 cD = *reinterpret_cast<const f4*>(tile + (3 * gl * gl + e0) * kEpiStride);
+    const f4 t0 = a + cH, t2 = a - cH, t1 = cW + cD, t3 = cW - cD;
+    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX, Out>(tile, hy, hx, t0 + t1, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX + 1, Out>(tile, hy, hx, t0 - t1, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX, Out>(tile, hy, hx, t2 + t3, o);
+    dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX + 1, Out>(tile, hy, hx, t2 - t3, o);
+  }
+}
+
+// Shape of the fused epilogue for block size RB: R tokens per block, units of at most 16 tokens (the
+// subtree at depth M0 of a block's tree), U units per block, npass passes of 8 units per wave tile.
+template <int RB, bool IS2D>
+struct EpiShape {
+  static constexpr int R = IS2D ? (1 << (2 * RB)) : (1 << RB);
+  static constexpr int nblk = 128 / R;
+  static constexpr int M0 = IS2D ? (RB == 3 ? 1 : 0) : (RB > 4 ? RB - 4 : 0);
+  static constexpr int U = IS2D ? (1 << (2 * M0)) : (1 << M0);
+  static constexpr int npass = (nblk * U) / 8;
+};
+
+// Global operands of the fused epilogue (weight scales, bias, block sums P of this lane's units),
+// requested ahead of the main loop so that their latency is not on the epilogue's path.
+template <int EPI, int RB, bool IS2D>
+struct EpiOperands {
+  using ES = EpiShape<(EPI == 2 ? RB : 3), IS2D>;
+  float sw[NI];
+  f4 bias[NI];
+  f4 top[NI][ES::npass];
+  __device__ __forceinline__ void request(const GemmArgs& a, int m0, int n0, int lane, int wm, int wn) {
+    if constexpr (EPI == 2) {
+      const int c4 = (lane & 7) * 4, ug = lane >> 3, l32 = lane & 31;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+        const int nw = n0 + wn * (32 * NI) + ni * 32;
+        sw[ni] = a.sw[nw + l32];
+        bias[ni] = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c4) : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int pass = 0; pass < ES::npass; ++pass) {
+          const int blk = (pass * 8 + ug) / ES::U;
+          const int mrow = min(m0 + wm * 128 + blk * ES::R, a.M - 1);
+          top[ni][pass] = *reinterpret_cast<const f4*>(a.P + (size_t)(mrow / a.g.R) * a.Npad + nw + c4);
+        }
+      }
+    }
+  }
+};
+
+// Per-row dequantization factor (activation scale * Haar norm of the row's level * the operand
+// format's constant) and destination row of tile row `tid`, written to LDS at row_info (2 KB) before
+// the main loop; the main loop's barriers publish them.
+template <typename Acc, int EPI>
+__device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int tid, uint8_t* row_info) {
+  const StampGeom& g = a.g;
+  float* s_rowfac = reinterpret_cast<float*>(row_info);     // [256]
+  int* s_rowdst = reinterpret_cast<int*>(row_info + 1024);  // [256] destination row or -1
+  const int m = m0 + tid;
+  float fac = 0.0f;
+  int dst = -1;
+  if (m < a.M) {
+    if constexpr (Acc::kLoRows) {
+      const int b = m / g.s, pr = m - b * g.s;
+      const int j = pr / g.R, e = pr - j * g.R;
+      if (e != 0) {
+        const int level = g.is2d ? stamp_level_of_e_2d(e, g.r) : stamp_level_of_e_1d(e, g.r);
+        if constexpr (EPI != 0) fac = a.scales[m] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
+        if (EPI == 0) {
+          const int p = g.is2d ? stamp_slot_of_block_e_2d(j / g.G, j % g.G, e, g.G) : stamp_slot_of_block_e_1d(j, e, g.k);
+          dst = b * g.s + p;
+        } else {
+          dst = m;
+        }
+      }
+    } else {
+      const int b = m / g.k, p = m - b * g.k;
+      int level = g.J;
+      if (p > 0) {
+        const int lg = 31 - __builtin_clz((unsigned)p);
+        level = g.J - (g.is2d ? (lg >> 1) : lg);
+      }
+      if constexpr (EPI != 0)
+        fac = a.scales[(size_t)b * g.s + (size_t)p * g.R] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
+      dst = (EPI == 0) ? (b * g.s + p) : m;
+    }
+  }
+  s_rowfac[tid] = fac;
+  s_rowdst[tid] = dst;
+}
+
+// Epilogue of one workgroup tile; to be called after a workgroup barrier that follows the last read
+// of the operand stages (the fused mode reuses smem[0, kTileBytes) as staging).
+// EPI: 0 = integer sums to STaMP-ordered rows [B*s][N] int32; 1 = dequantized fp32 rows (4-bit rows:
+// physical rows of [B*s][N]; 8-bit rows: [B*k][N]); 2 = fused in-block inverse + bias -> Y (4-bit
+// rows only); RB = log2 of the block length for EPI 2 (1-D: tokens, 2-D: side).
+template <typename Acc, int EPI, int RB, bool IS2D, bool YBF16>
+__device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&acc)[4][NI], uint8_t* smem,
+                                         const uint8_t* row_info, const EpiOperands<EPI, RB, IS2D>& eo, int m0,
+                                         int n0, int lane, int wave) {
+  const StampGeom& g = a.g;
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, kg = lane >> 5;
+  const float* s_rowfac = reinterpret_cast<const float*>(row_info);
+  const int* s_rowdst = reinterpret_cast<const int*>(row_info + 1024);
+
+  if constexpr (EPI == 0 || EPI == 1) {
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int n = n0 + wn * (32 * NI) + ni * 32 + l32;
+      const float swn = a.sw[n];
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int rl = wm * 128 + mi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+          const int dst = s_rowdst[rl];
+          if (dst >= 0 && n < a.N) {
+            if constexpr (EPI == 0) {
+              reinterpret_cast<int32_t*>(a.out)[(size_t)dst * a.N + n] = Acc::to_i32(acc[mi][ni][v]);
+            } else {
+              reinterpret_cast<float*>(a.out)[(size_t)dst * a.N + n] = ((float)acc[mi][ni][v] * s_rowfac[rl]) * swn;
+            }
+          }
+        }
+      }
+    }
+  } else {
+    // fused: per 32-column strip, dequantize into this wave's LDS tile [128][kEpiStride]; then the wave's
+    // 8 groups of 8 lanes each take one unit (a block, or an aligned 16-token part of one) and 4 columns
+    // per lane, and run the depth-first inverse, storing the unit's tokens.
+    using ES = EpiShape<RB, IS2D>;
+    constexpr int R = ES::R, M0 = ES::M0, U = ES::U, npass = ES::npass;
+    float* s_tile = reinterpret_cast<float*>(smem) + wave * (128 * kEpiStride);
+    // row factors of this lane's 64 accumulator rows, read before any staging write
+    f4 rf[4][4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        rf[mi][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + mi * 32 + 8 * q + 4 * kg);
+    const int c4 = (lane & 7) * 4, ug = lane >> 3;
+    auto run_strips = [&](auto vec_tag) __attribute__((always_inline)) {
+      constexpr bool VEC = decltype(vec_tag)::value;
+      OutQuad<YBF16, VEC> o;
+      o.Y = a.out;
+      o.tok_stride = (size_t)a.N;
+      o.row_stride = (size_t)g.gridW * a.N;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+        const int nw = n0 + wn * (32 * NI) + ni * 32;  // first column of the strip
+        const float swn = eo.sw[ni];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int rw = mi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+            s_tile[rw * kEpiStride + l32] = ((float)acc[mi][ni][v] * rf[mi][v >> 2][v & 3]) * swn;
+          }
+        }
+        // the staging tile is private to this wave: its own LDS writes only have to complete (the LDS
+        // executes one wave's operations in order), no workgroup barrier is needed
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+        asm volatile("" ::: "memory");
+        const int n = nw + c4;
+        o.nvalid = a.N - n;
+        o.bias = eo.bias[ni];
+#pragma unroll
+        for (int pass = 0; pass < npass; ++pass) {
+          const int unit = pass * 8 + ug;
+          const int blk = unit / U, h = unit % U;
+          const int mrow = m0 + wm * 128 + blk * R;  // physical row of e = 0 of this block
+          if (mrow < a.M && n < a.N) {
+            const int b = mrow / g.s, pr = mrow - b * g.s;
+            const int j = pr / g.R;
+            f4 top = eo.top[ni][pass];
+            const float* tile = s_tile + blk * R * kEpiStride + c4;
+            if constexpr (IS2D) {
+              const int bi = j / g.G, bj = j - bi * g.G;
+              o.base = ((size_t)b * g.s + (size_t)(bi << RB) * g.gridW + (size_t)(bj << RB)) * a.N + n;
+              const int hy = h >> 1, hx = h & 1;
+              if constexpr (M0 == 1) {
+                const f4 cW = *reinterpret_cast<const f4*>(tile + 1 * kEpiStride);
+                const f4 cH = *reinterpret_cast<const f4*>(tile + 2 * kEpiStride);
+                const f4 cD = *reinterpret_cast<const f4*>(tile + 3 * kEpiStride);
+                const f4 t0 = top + cH, t2 = top - cH, t1 = cW + cD, t3 = cW - cD;
+                top = hy ? (hx ? (t2 - t3) : (t2 + t3)) : (hx ? (t0 - t1) : (t0 + t1));
+              }
+              dfs2d<RB, M0, M0, 0, 0, OutQuad<YBF16, VEC>>(tile, hy, hx, top, o);
+            } else {
+              o.base = ((size_t)b * g.s + (size_t)j * R) * a.N + n;
+#pragma unroll
+              for (int m = 0; m < M0; ++m) {
+                const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << m) + (h >> (M0 - m))) * kEpiStride);
+                top = ((h >> (M0 - m - 1)) & 1) ? (top - d) : (top + d);
+              }
+              dfs1d<RB, M0, M0, 0, OutQuad<YBF16, VEC>>(tile, h, top, o);
+            }
+          }
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // this wave's reads of the tile are done before the next strip overwrites it
+        asm volatile("" ::: "memory");
+      }
+    };
+    if ((a.N & 3) == 0) run_strips(std::true_type{});
+    else run_strips(std::false_type{});
+  }
+}
+
+}  // namespace stamp_gemm
+
+// arguments common to every GEMM launch of a plan (host)
+stamp_gemm::GemmArgs stamp_gemm_args(const stamp_plan* p, const float* scales, void* out);
+
+#endif  // STAMP_GEMM_COMMON_H_

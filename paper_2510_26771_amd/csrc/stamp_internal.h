@@ -98,10 +98,12 @@ struct stamp_plan {
   float* sw_dev;            // [Npad] weight scales (0 beyond d_out)
   float* bias_dev;          // [Npad] bias or nullptr
   int32_t* row_of_coeff;    // host, [s]
+  uint8_t* qW6_dev;         // the same weight codes as E2M3 numbers in the plane layout of the FP6 GEMM
+  int32_t engine;           // matrix pipeline of the 4-bit rows' GEMM: STAMP_GEMM_INT8 or STAMP_GEMM_FP6
   int32_t unfused;          // 1: separate inverse kernel
   int32_t fused_ok;         // shape allows the fused epilogue
   // workspace layout (byte offsets, 256-aligned)
-  size_t ws_abot, ws_rowmax, ws_qhi, ws_qlo, ws_scales, ws_ythi, ws_P, ws_ytlo, ws_total;
+  size_t ws_abot, ws_rowmax, ws_qhi, ws_qlo, ws_scales, ws_ythi, ws_P, ws_a6, ws_ytlo, ws_total;
 };
 
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
@@ -115,6 +117,14 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
                                 void* out, hipStream_t st);
 hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const float* scales, int mode,
                                 void* out, const float* P, hipStream_t st);
+// FP6 engine of the 4-bit rows: operand sizes, plan-time weight codes (colmax: bit patterns of the column
+// maxima, as left by stamp_launch_weight_quant), conversion of the packed 4-bit rows, and the GEMM (modes as above).
+size_t stamp_a6_bytes(const stamp_plan* p);
+size_t stamp_b6_bytes(const stamp_plan* p);
+hipError_t stamp_launch_weight_quant6(const stamp_plan* p, const float* W, const uint32_t* colmax, hipStream_t st);
+hipError_t stamp_launch_repack6(const stamp_plan* p, const uint8_t* q_lo, uint8_t* a6, hipStream_t st);
+hipError_t stamp_launch_gemm_lo6(const stamp_plan* p, const uint8_t* a6, const float* scales, int mode, void* out,
+                                 const float* P, hipStream_t st);
 // P: block sums [B*k][ldP]
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* Yt_hi, int hi_row_stride_is_stamp,
                                     int ncols, float* P, int ldP, hipStream_t st);

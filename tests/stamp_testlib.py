@@ -3,7 +3,7 @@ inputs and compare them step by step.  The oracle is only ever called from here 
 from __future__ import annotations
 
 import time
-from typing import Dict, Optional
+from typing import Tuple, Dict, Optional
 
 import numpy as np
 
@@ -134,8 +134,9 @@ def y_to_numpy(Y, y_is_bf16: bool) -> np.ndarray:
 
 
 def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: Optional[np.ndarray] = None,
-              check_acc: bool = True, check_unfused: bool = True) -> Dict[str, float]:
-    """Everything the ABI exposes, on one workload, against the oracle."""
+              check_acc: bool = True, check_unfused: bool = True,
+              engines: Tuple[str, ...] = ("int8", "fp6")) -> Dict[str, float]:
+    """Everything the ABI exposes, on one workload, against the oracle, under each GEMM engine."""
     import torch
     import paper_2510_26771_amd as st
 
@@ -172,36 +173,48 @@ def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: 
         return (t3 if cols_t is None else t3.index_select(2, cols_t)).cpu()
 
     if check_acc:
-        acc = torch.empty((w.batch * w.seq_len, w.d_out), dtype=torch.int32, device="cuda")
-        plan.debug_gemm_acc(q_hi, q_lo, acc)
-        torch.cuda.synchronize()
-        acc_np = pick(acc.view(w.batch, w.seq_len, w.d_out)).numpy()
         if report["code_mismatches"] == 0:
             ref_acc = ora["acc"]
         else:  # compare on the codes the GPU actually used (they differ only at counted boundaries)
             ref_acc = np.stack([so.int_gemm(codes[b], ora["qw"][:, sel]) for b in range(w.batch)])
-        assert np.array_equal(acc_np, ref_acc), "int32 accumulators differ"
-        del acc
+        for engine in engines:
+            plan.set_gemm_engine(engine)
+            acc = torch.full((w.batch * w.seq_len, w.d_out), -(2 ** 31), dtype=torch.int32, device="cuda")
+            plan.debug_gemm_acc(q_hi, q_lo, acc)
+            torch.cuda.synchronize()
+            acc_np = pick(acc.view(w.batch, w.seq_len, w.d_out)).numpy()
+            assert np.array_equal(acc_np, ref_acc), f"integer sums differ (engine {engine})"
+            del acc
         log("accumulators ok")
 
     # the whole layer, fused (default) and unfused
     y_bf16 = y_dtype == "bf16"
     ydt = torch.int16 if y_bf16 else torch.float32
-    for unfused in ([False, True] if check_unfused else [False]):
-        plan.set_unfused(unfused)
-        ws = plan.alloc_workspace()
-        Y = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=ydt, device="cuda")
-        plan.linear_forward(Xd, Y, ws)
-        torch.cuda.synchronize()
-        y_np = y_to_numpy(pick(Y), y_bf16)
-        tag = "unfused" if unfused else "fused"
-        report[f"y_relerr_{tag}"] = check_output(y_np, ora["Y"], y_bf16, f"{w.name} {tag}")
-        # and from the separately quantized activation
-        Y2 = torch.zeros_like(Y)
-        plan.linear_forward_q(q_hi, q_lo, scales, Y2, ws)
-        torch.cuda.synchronize()
-        assert torch.equal(Y, Y2), "linear_forward and quantize_act + linear_forward_q disagree"
-        del Y, Y2, ws
+    y_first = None
+    for engine in engines:
+        plan.set_gemm_engine(engine)
+        for unfused in ([False, True] if check_unfused else [False]):
+            plan.set_unfused(unfused)
+            ws = plan.alloc_workspace()
+            Y = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=ydt, device="cuda")
+            plan.linear_forward(Xd, Y, ws)
+            torch.cuda.synchronize()
+            y_np = y_to_numpy(pick(Y), y_bf16)
+            tag = ("unfused" if unfused else "fused") + ("" if engine == "int8" else "_" + engine)
+            report[f"y_relerr_{tag}"] = check_output(y_np, ora["Y"], y_bf16, f"{w.name} {tag}")
+            # and from the separately quantized activation
+            Y2 = torch.zeros_like(Y)
+            plan.linear_forward_q(q_hi, q_lo, scales, Y2, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(Y, Y2), "linear_forward and quantize_act + linear_forward_q disagree"
+            if not unfused:
+                # both engines compute the same integer sums, so the outputs agree bit for bit
+                if y_first is None:
+                    y_first = Y
+                else:
+                    assert torch.equal(Y, y_first), f"engine {engine} and engine {engines[0]} disagree"
+            del Y2, ws
+    del y_first
     log(f"outputs ok: {report}")
     plan.destroy()
     return report
