@@ -22,6 +22,9 @@ namespace {
 
 using namespace stamp_gemm;
 
+constexpr int BN = 128;                        // workgroup tile 256 x 128, 4 waves
+constexpr int kTileBytes = 4 * kWaveTileBytes;  // the four waves' epilogue staging tiles
+
 template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16>
 __global__ __launch_bounds__(256, 2) void k_gemm(const GemmArgs a) {
   using Acc = typename std::conditional<A_INT4, AccI8Lo, AccI8Hi>::type;
@@ -39,7 +42,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm(const GemmArgs a) {
   const int wm = wave >> 1, wn = wave & 1;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
   const int l32 = lane & 31, kg = lane >> 5;
   int tm, tn;
-  tile_of_block(a.M, a.Npad, tm, tn);
+  tile_of_block(a.M, a.Npad, BN, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int KT = a.Kpad / BK;
 
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm(const GemmArgs a) {
   __syncthreads();
 #undef STAMP_REQUEST
 
-  epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave);
+  epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave, wm, wn);
 }
 
 template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16>

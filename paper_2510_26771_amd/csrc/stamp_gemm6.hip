@@ -8,12 +8,14 @@
 // holds acc / 64 EXACTLY, where acc is the integer sum the int8 pipeline computes: same result bit for
 // bit, at twice the matrix rate per clock.  The factor 64 is folded into the row scale.
 //
-// Operand layout ("planes"): per 256-row (128-column) tile and K step of 128 channels, 12 planes of
-// 256 (128) x 8 bytes.  The 32 codes that one lane feeds to one MFMA (channels 32 f .. 32 f + 31 of
-// the step, f = 0..3, as a little-endian stream of 6-bit fields = 24 bytes) are split into three
-// 8-byte parts p; plane 3 f + p holds part p of every row.  A fragment is then three 8-byte LDS reads
-// in which consecutive lanes read consecutive addresses (no bank conflicts, no swizzle), and the
-// global image equals the LDS image, so a K step is staged by plain asynchronous 16-byte copies.
+// Operand layout ("planes"): the 32 codes that one lane feeds to one MFMA (channels 32 f .. 32 f + 31 of
+// a K step of 128 channels, f = 0..3, as a little-endian stream of 6-bit fields = 24 bytes) are split
+// into three 8-byte parts p; a plane holds part p of fragment f for 128 consecutive rows (columns).
+// Per tile and K step, activations: [2 row halves][12 planes 3 f + p][128 rows][8 bytes] = 24 KB, weights:
+// [12 planes][128 columns][8 bytes] = 12 KB.  A fragment is then three 8-byte LDS reads in which
+// consecutive lanes read consecutive addresses (no bank conflicts, no swizzle), the three parts of one
+// fragment are 1 KB apart (within reach of one two-address LDS read), and the global image equals the
+// LDS image, so a K step is staged by plain asynchronous 16-byte copies.
 // MFMA k (0, 1) of a step consumes channels [64 k, 64 k + 64): lane group kg = lane / 32 takes f = 2 k + kg.
 #include "stamp_gemm_common.h"
 
@@ -21,10 +23,14 @@ namespace {
 
 using namespace stamp_gemm;
 
-constexpr int kPlanes = 12;
-constexpr int kStageA6 = kPlanes * 256 * 8;  // 24 KB
-constexpr int kStageB6 = kPlanes * 128 * 8;  // 12 KB
-constexpr int kStage6 = kStageA6 + kStageB6;
+typedef int v6i __attribute__((ext_vector_type(6)));
+typedef uint32_t u6 __attribute__((ext_vector_type(6)));
+// the FP6 operand of the MFMA builtin is declared as 8 registers, of which the instruction reads 6
+__device__ __forceinline__ v8i widen(v6i x) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, 4, 5, -1, -1); }
+
+constexpr int kPlane = 128 * 8;               // bytes of one plane
+constexpr int kStageB6 = 12 * kPlane;         // 12 KB
+constexpr int kStageA6 = 2 * kStageB6;        // 24 KB
 
 // eight two's-complement nibbles -> eight sign-magnitude 6-bit fields (48 bits)
 __device__ __forceinline__ uint64_t nib8_to_e2m3(uint32_t w) {
@@ -55,14 +61,14 @@ __global__ __launch_bounds__(256) void k_repack6(const uint8_t* __restrict__ q_l
   const size_t blk = blockIdx.x;
   const int row = threadIdx.x;
   const uint8_t* src = q_lo + blk * (256 * 64) + row * 64;
-  uint8_t* dst = a6 + blk * kStageA6 + row * 8;
+  uint8_t* dst = a6 + blk * kStageA6 + (row >> 7) * kStageB6 + (row & 127) * 8;
 #pragma unroll
   for (int f = 0; f < 4; ++f) {
     const u4 w = *reinterpret_cast<const u4*>(src + (f << 4));
     uint64_t part[3];
     chunk_to_e2m3(w, part);
 #pragma unroll
-    for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * (256 * 8)) = part[p];
+    for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * kPlane) = part[p];
   }
 }
 
@@ -103,44 +109,69 @@ __global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, c
   const int KT = Kpad >> 7;
   const int kt = frag >> 2, f = frag & 3;
   uint8_t* dst = b6 + ((size_t)(n >> 7) * KT + kt) * kStageB6 + (size_t)(n & 127) * 8;
-  for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * (128 * 8)) = part[p];
+  for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * kPlane) = part[p];
 }
 
+// Workgroup: 8 waves (2 x 4), tile 256 x 256, one workgroup per CU with two waves on every SIMD, all
+// eight sharing one operand stage: 48 KB per K step for 256 x 256 x 128 products, a third less L2 -> LDS
+// traffic per product than two independent 256 x 128 workgroups would need (the FP6 pipeline consumes a K
+// step in half the time of the int8 one, which makes that traffic the bound).  Three stages: the loads of
+// steps kt+1 and kt+2 are in flight while step kt is multiplied.
+constexpr int BN6 = 256;
+constexpr int kWaves6 = 8;
+constexpr int kStage6 = kStageA6 + 2 * kStageB6;  // 48 KB
+constexpr int kNumStage6 = 3;
+constexpr int kTileBytes6 = kWaves6 * kWaveTileBytes;
+
 template <int EPI, int RB, bool IS2D, bool YBF16>
-__global__ __launch_bounds__(256, 2) void k_gemm6(const GemmArgs a) {
+__global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   using Acc = AccF6Lo;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  constexpr int kMainBytes = 2 * kStage6;
-  constexpr int kRowInfoOff = (EPI == 2 && kTileBytes > kMainBytes) ? kTileBytes : kMainBytes;
-  constexpr int nA = kStageA6 / (256 * 16), nB = kStageB6 / (256 * 16);  // 16-byte chunks per thread and step: 6 and 3
+  constexpr int kMainBytes = kNumStage6 * kStage6;
+  constexpr int kRowInfoOff = (EPI == 2 && kTileBytes6 > kMainBytes) ? kTileBytes6 : kMainBytes;
+  constexpr int nA = kStageA6 / (512 * 16), nB = 2 * kStageB6 / (512 * 16);  // 16-byte chunks per thread and step: 3 and 3
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
   const int l32 = lane & 31, kg = lane >> 5;
   int tm, tn;
-  tile_of_block(a.M, a.Npad, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
+  tile_of_block(a.M, a.Npad, BN6, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN6;
   const int KT = a.Kpad / BK;
 
-  // global image = LDS image: chunk i * 256 + tid of a stage goes to byte (i * 256 + tid) * 16
+  // global image = LDS image: chunk q = i * 512 + tid of an operand's stage goes to byte 16 q.  The
+  // weight stage is two column tiles of 128 (KT * 12 KB apart in memory): chunks 0..767 and 768..1535;
+  // the boundary falls between waves, so the source tile of a pass is wave-uniform.
   const uint8_t* gA = a.A + (size_t)tm * KT * kStageA6 + tid * 16;
-  const uint8_t* gB = a.Bq + (size_t)tn * KT * kStageB6 + tid * 16;
+  const uint8_t* gB[nB];
+#pragma unroll
+  for (int i = 0; i < nB; ++i) {
+    const int q = i * 512 + tid;
+    const int half = (i * 512 + wave * 64) >= 768 ? 1 : 0;
+    gB[i] = a.Bq + ((size_t)(2 * tn + half) * KT) * kStageB6 + (size_t)(q - half * 768) * 16;
+  }
 #define STAMP_REQUEST6(KSTEP, STG)                                                                               \
   do {                                                                                                           \
     uint8_t* so_ = smem + (STG) * kStage6 + wave * 1024;                                                         \
     const uint8_t* sa_ = gA + (size_t)(KSTEP) * kStageA6;                                                        \
-    const uint8_t* sb_ = gB + (size_t)(KSTEP) * kStageB6;                                                        \
     _Pragma("unroll") for (int i = 0; i < nA; ++i)                                                               \
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * 4096),        \
-                                         (void __attribute__((address_space(3)))*)(so_ + i * 4096), 16, 0, 0);   \
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * 8192),        \
+                                         (void __attribute__((address_space(3)))*)(so_ + i * 8192), 16, 0, 0);   \
     _Pragma("unroll") for (int i = 0; i < nB; ++i)                                                               \
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sb_ + i * 4096),        \
-                                         (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * 4096), 16, 0, 0); \
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(gB[i] + (size_t)(KSTEP) * kStageB6), \
+                                         (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * 8192), 16, 0, 0); \
   } while (0)
+  constexpr int kLoadsPerStep = nA + nB;
 
-  // fragment addresses inside a stage: plane (2 k + kg) * 3 + p, row / column of this lane
-  const int baseA = (kg * 3) * (256 * 8) + (wm * 128 + l32) * 8;
-  const int baseB = kStageA6 + (kg * 3) * (128 * 8) + (wn * 64 + l32) * 8;
+  // LDS byte addresses of part 0 of this lane's fragments of MFMA round 0 in stage 0: plane
+  // (2 k + kg) * 3 + p, row / column of this lane
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
+  uint32_t adrA[4], adrB[NI];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) adrA[mi] = (uint32_t)(wm * kStageB6 + (kg * 3) * kPlane + (mi * 32 + l32) * 8);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+    adrB[ni] = (uint32_t)(kStageA6 + (wn >> 1) * kStageB6 + (kg * 3) * kPlane + ((wn & 1) * 64 + ni * 32 + l32) * 8);
 
   v16f acc[4][NI];
 #pragma unroll
@@ -151,62 +182,87 @@ __global__ __launch_bounds__(256, 2) void k_gemm6(const GemmArgs a) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
   STAMP_REQUEST6(0, 0);
+  if (1 < KT) STAMP_REQUEST6(1, 1);
   EpiOperands<EPI, RB, IS2D> eo;
   eo.request(a, m0, n0, lane, wm, wn);
-  store_row_info<Acc, EPI>(a, m0, tid, smem + kRowInfoOff);
+  if (tid < 256) store_row_info<Acc, EPI>(a, m0, tid, smem + kRowInfoOff);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the epilogue operands and steps 0 and 1 have landed
+  asm volatile("" ::: "memory");
 
-  // Step kt: this wave's loads of step kt have landed, workgroup barrier (all of step kt is visible and
-  // the stage of step kt-1 is free), request step kt+1 into the free stage, then the two MFMA rounds.
+  // Step kt: this wave's loads of step kt have landed (those of step kt+1 may still be in flight);
+  // workgroup barrier (all of step kt is visible and the stage of step kt-1 is free); request step kt+2
+  // into that stage; then the two MFMA rounds.
+  int stg = 0;  // stage of step kt
   for (int kt = 0; kt < KT; ++kt) {
-    const uint8_t* st = smem + (kt & 1) * kStage6;
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    if (kt > 0) {
+      if (kt + 1 < KT) __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStep);  // vmcnt(one step's loads)
+      else __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + 1 < KT) STAMP_REQUEST6(kt + 1, (kt + 1) & 1);
+    if (kt + 2 < KT) STAMP_REQUEST6(kt + 2, (stg == 0 ? 2 : stg - 1));
     __builtin_amdgcn_sched_barrier(0);
 
-    u2 fa[2][4][3], fb[2][NI][3];
+    // The step's 12 fragments (per MFMA round k: 2 of the weights, 4 of the activations), each by one
+    // two-address read (parts 0 and 1 -> operand registers 0-3) and one 8-byte read (part 2 -> registers
+    // 4-5).  The reads are written out by hand, so that none is merged with a part of another fragment
+    // (which would cost register copies), and so are the waits: round 1's reads stay in flight under
+    // round 0's MFMAs.  A wait names the registers it covers, which keeps the MFMAs behind it.
+    const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
+    u4 alo[2][4], blo[2][NI];
+    u2 ahi[2][4], bhi[2][NI];
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
-#pragma unroll
-      for (int p = 0; p < 3; ++p) {
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          fb[k][ni][p] = *reinterpret_cast<const u2*>(st + baseB + (k * 6 + p) * (128 * 8) + ni * (32 * 8));
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-          fa[k][mi][p] = *reinterpret_cast<const u2*>(st + baseA + (k * 6 + p) * (256 * 8) + mi * (32 * 8));
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      v8i vb[NI];
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
-        vb[ni] = (v8i){(int)fb[k][ni][0].x, (int)fb[k][ni][0].y, (int)fb[k][ni][1].x, (int)fb[k][ni][1].y,
-                       (int)fb[k][ni][2].x, (int)fb[k][ni][2].y, 0, 0};
+        asm volatile("ds_read2st64_b64 %0, %2 offset0:%3 offset1:%4\n\tds_read_b64 %1, %2 offset:%5"
+                     : "=v"(blo[k][ni]), "=v"(bhi[k][ni])
+                     : "v"(sa + adrB[ni]), "n"(k * 12), "n"(k * 12 + 2), "n"(k * 6 * kPlane + 2 * kPlane));
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi) {
-        const v8i va = (v8i){(int)fa[k][mi][0].x, (int)fa[k][mi][0].y, (int)fa[k][mi][1].x, (int)fa[k][mi][1].y,
-                             (int)fa[k][mi][2].x, (int)fa[k][mi][2].y, 0, 0};
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb[ni], acc[mi][ni], 2, 2, 0, 0, 0, 0);
-      }
+      for (int mi = 0; mi < 4; ++mi)
+        asm volatile("ds_read2st64_b64 %0, %2 offset0:%3 offset1:%4\n\tds_read_b64 %1, %2 offset:%5"
+                     : "=v"(alo[k][mi]), "=v"(ahi[k][mi])
+                     : "v"(sa + adrA[mi]), "n"(k * 12), "n"(k * 12 + 2), "n"(k * 6 * kPlane + 2 * kPlane));
     }
+    v6i fa[2][4], fb[2][NI];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        fb[k][ni] = (v6i)(u6)__builtin_shufflevector(blo[k][ni], __builtin_shufflevector(bhi[k][ni], bhi[k][ni], 0, 1, -1, -1), 0, 1, 2, 3, 4, 5);
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+        fa[k][mi] = (v6i)(u6)__builtin_shufflevector(alo[k][mi], __builtin_shufflevector(ahi[k][mi], ahi[k][mi], 0, 1, -1, -1), 0, 1, 2, 3, 4, 5);
+    }
+    asm volatile("s_waitcnt lgkmcnt(12)"
+                 : "+v"(fa[0][0]), "+v"(fa[0][1]), "+v"(fa[0][2]), "+v"(fa[0][3]), "+v"(fb[0][0]), "+v"(fb[0][1]));
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[0][mi]), widen(fb[0][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fa[1][2]), "+v"(fa[1][3]), "+v"(fb[1][0]), "+v"(fb[1][1]));
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[1][mi]), widen(fb[1][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
+    stg = (stg == 2) ? 0 : stg + 1;
   }
   __syncthreads();
 #undef STAMP_REQUEST6
 
-  epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave);
+  epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave, wm, wn);
 }
 
 template <int EPI, int RB, bool IS2D, bool YBF16>
 hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
-  constexpr size_t main_lds = 2 * (size_t)kStage6;
-  constexpr size_t epi_lds = (EPI == 2) ? (size_t)kTileBytes : 0;
+  constexpr size_t main_lds = (size_t)kNumStage6 * kStage6;
+  constexpr size_t epi_lds = (EPI == 2) ? (size_t)kTileBytes6 : 0;
   constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + 2048;
   static bool attr_set = false;
   if (!attr_set) {
@@ -215,8 +271,8 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
-  hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16>), dim3(mt * nt), dim3(256), lds, st, a);
+  const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN6;
+  hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16>), dim3(mt * nt), dim3(512), lds, st, a);
   return hipGetLastError();
 }
 

@@ -3,7 +3,7 @@
 // of the Background section, then, in the fused mode, the in-block levels of the inverse sequence
 // transform by the commutation identity of section "Method", bias and the store of Y).
 //
-// Every kernel here computes a 256 x 128 output tile per workgroup of 4 waves (2 x 2); a wave owns
+// A workgroup computes 256 rows x 128 or 256 columns with 4 or 8 waves (2 x 2 or 2 x 4); a wave owns
 // 128 x 64 outputs = 4 x 2 MFMA blocks of 32 x 32, 16 accumulator registers per block and lane:
 // element v of lane l of block (mi, ni) is row 32 mi + 8 (v / 4) + 4 (l / 32) + v % 4, column
 // 32 ni + l % 32 of the wave tile.
@@ -26,10 +26,10 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 256, BN = 128, BK = 128;
+constexpr int BM = 256, BK = 128;
 constexpr int NI = 2;           // 32-column MFMA blocks per wave along N
 constexpr int kEpiStride = 36;  // floats per row of the per-wave epilogue staging tile (16-byte aligned rows)
-constexpr int kTileBytes = 4 * 128 * kEpiStride * 4;  // the four waves' staging tiles
+constexpr int kWaveTileBytes = 128 * kEpiStride * 4;  // one wave's staging tile of the fused epilogue
 constexpr int kNumXcd = 8;
 constexpr int kGroupM = 8;
 
@@ -80,8 +80,8 @@ struct AccF6Lo {
 // workgroup -> tile, XCD aware: consecutive ids on one XCD walk 8 M-tiles, then the next N-tile, so
 // that the 32 workgroups resident on one XCD cover 8 x 4 neighbouring tiles and share operand panels
 // in that XCD's L2.
-__device__ __forceinline__ void tile_of_block(int M, int Npad, int& tm, int& tn) {
-  const int mt = (M + BM - 1) / BM, nt = Npad / BN;
+__device__ __forceinline__ void tile_of_block(int M, int Npad, int bn, int& tm, int& tn) {
+  const int mt = (M + BM - 1) / BM, nt = Npad / bn;
   const int total = mt * nt;
   const int bid = blockIdx.x;
   const int xcd = bid % kNumXcd, local = bid / kNumXcd;
@@ -248,16 +248,17 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
 }
 
 // Epilogue of one workgroup tile; to be called after a workgroup barrier that follows the last read
-// of the operand stages (the fused mode reuses smem[0, kTileBytes) as staging).
+// of the operand stages (the fused mode reuses smem[0, waves * kWaveTileBytes) as staging).  Wave
+// `wave` of the workgroup owns rows [128 wm, +128) and columns [64 wn, +64) of the tile.
 // EPI: 0 = integer sums to STaMP-ordered rows [B*s][N] int32; 1 = dequantized fp32 rows (4-bit rows:
 // physical rows of [B*s][N]; 8-bit rows: [B*k][N]); 2 = fused in-block inverse + bias -> Y (4-bit
 // rows only); RB = log2 of the block length for EPI 2 (1-D: tokens, 2-D: side).
 template <typename Acc, int EPI, int RB, bool IS2D, bool YBF16>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&acc)[4][NI], uint8_t* smem,
                                          const uint8_t* row_info, const EpiOperands<EPI, RB, IS2D>& eo, int m0,
-                                         int n0, int lane, int wave) {
+                                         int n0, int lane, int wave, int wm, int wn) {
   const StampGeom& g = a.g;
-  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, kg = lane >> 5;
+  const int l32 = lane & 31, kg = lane >> 5;
   const float* s_rowfac = reinterpret_cast<const float*>(row_info);
   const int* s_rowdst = reinterpret_cast<const int*>(row_info + 1024);
 
