@@ -2,10 +2,13 @@
 """Benchmark of the STaMP quantized linear forward on one MI355X.
 
 One "step" is one call of stamp_linear_forward (sequence Haar transform + mixed-precision
-quantization + int8 MFMA GEMM + dequantization + inverse transform + bf16 store) over one batch of
-seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+quantization + integer GEMM on the matrix cores + dequantization + inverse transform + bf16 store)
+over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line:
+the throughput of the whole step, the roofline of the dominant kernel (the GEMM over the 4-bit rows,
+under the engine that the step ran with), the same kernel's figures under the other engine, the
+transform + quantization stage against HBM, per-stage times, and the oracle timed on the host.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--engine fp6|int8] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -21,6 +24,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
+PEAK_FP6_TFLOPS = 10100.0    # MI355X dense fp6 MFMA, TFLOP/s
 
 
 def log(msg):
@@ -40,9 +44,9 @@ def stage_time_ms(fn, iters, torch):
     return e0.elapsed_time(e1) / iters
 
 
-def read_traffic(workload_name):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
-    path = os.path.join(ROOT, "profiles", f"gemm_lo_{workload_name}_pmc.txt")
+def read_traffic(engine, workload_name):
+    """HBM bytes per launch of the engine's GEMM kernel from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"gemm_lo_{engine}_{workload_name}_pmc.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -52,8 +56,8 @@ def read_traffic(workload_name):
     return None
 
 
-def cpu_baseline(w, inp, ncols):
-    """The oracle, as it stands, on a bounded sample: ONE sequence of the workload through the whole
+def cpu_baseline(w, inp, ncols, nseq):
+    """The oracle, as it stands, on a bounded sample: `nseq` sequences of the workload through the whole
     layer, the GEMM / dequantization / inverse on the first `ncols` output columns, that part's time
     scaled by d_out / ncols."""
     import numpy as np
@@ -63,7 +67,8 @@ def cpu_baseline(w, inp, ncols):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    X = inp["X_f32"][:1]
+    nseq = min(nseq, w.batch)
+    X = inp["X_f32"][:nseq]
     t0 = time.perf_counter()
     qa = so.quantize_activation(X, w.xform, w.levels, w.k_hi, w.bits_hi, w.bits_lo, w.grid_h, w.grid_w)
     t1 = time.perf_counter()
@@ -73,8 +78,8 @@ def cpu_baseline(w, inp, ncols):
     t3 = time.perf_counter()
     t_total = (t1 - t0) + (t3 - t2) * (w.d_out / ncols)
     return {
-        "value": w.seq_len / t_total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": (f"1 of {w.batch} sequences ({w.seq_len} tokens): transform+quantization in full "
+        "value": nseq * w.seq_len / t_total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"{nseq} of {w.batch} sequences ({nseq * w.seq_len} tokens): transform+quantization in full "
                    f"({t1 - t0:.2f} s, single-threaded numpy), integer GEMM (fp64 BLAS, {threads} threads) + "
                    f"dequantization + inverse on the first {ncols} of {w.d_out} output columns "
                    f"({t3 - t2:.2f} s, scaled x{w.d_out / ncols:.1f})"),
@@ -84,15 +89,16 @@ def cpu_baseline(w, inp, ncols):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--stage-iters", type=int, default=10)
-    ap.add_argument("--cpu-cols", type=int, default=2048)
+    ap.add_argument("--cpu-cols", type=int, default=16384)
+    ap.add_argument("--cpu-seqs", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true")
-    ap.add_argument("--engine", choices=["int8", "fp6"], default="int8",
-                    help="matrix pipeline of the 4-bit rows' GEMM")
+    ap.add_argument("--engine", choices=["int8", "fp6"], default="fp6",
+                    help="matrix pipeline of the 4-bit rows' GEMM (the library's default is fp6)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (int32 add), the "
                          "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -149,27 +155,46 @@ def main():
     # ---- per-stage timings (HIP events on the launch stream) ----
     q_hi, q_lo, scales = plan.alloc_act_buffers()
     plan.quantize_act(Xd, q_hi, q_lo, scales, ws)
+
+    def run_stage(sid):
+        return stage_time_ms(lambda: plan.debug_run_stage(sid, Xd, q_hi, q_lo, scales, Y, ws), args.stage_iters, torch)
+
     stages = {}
-    names = {0: "transform_quant_lo", 1: "transform_quant_hi", 2: "gemm_hi", 3: "inverse_top", 4: "gemm_lo"}
+    names = {0: "transform_quant_lo", 1: "transform_quant_hi", 2: "gemm_hi", 3: "inverse_top"}
     if args.engine == "fp6":
-        names = {0: "transform_quant_lo", 1: "transform_quant_hi", 2: "gemm_hi", 3: "inverse_top", 6: "repack_fp6",
-                 4: "gemm_lo"}
+        names[6] = "repack_fp6"
+    names[4] = "gemm_lo"
     if args.unfused:
         names[5] = "inverse_bottom"
     for sid, nm in names.items():
-        stages[nm] = stage_time_ms(lambda: plan.debug_run_stage(sid, Xd, q_hi, q_lo, scales, Y, ws),
-                                   args.stage_iters, torch)
+        stages[nm] = run_stage(sid)
     stages["quantize_act"] = stage_time_ms(lambda: plan.quantize_act(Xd, q_hi, q_lo, scales, ws), args.stage_iters, torch)
     log("stages ms: " + ", ".join(f"{k}={v:.4f}" for k, v in stages.items()))
 
-    # dominant kernel: the GEMM over the 4-bit rows.  Algorithmic work: 2 * rows * d_in * d_out int ops
+    # the GEMM over the 4-bit rows under either engine.  Algorithmic work: 2 * rows * d_in * d_out operations
     lo_rows = w.batch * (w.seq_len - w.k_hi)
     gemm_ops = 2.0 * lo_rows * w.d_in * w.d_out
-    achieved_tops = gemm_ops / (stages["gemm_lo"] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "achieved": achieved_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": achieved_tops / PEAK_INT8_TOPS, "traffic": read_traffic(w.name),
-                "kernel": "k_gemm (4-bit rows" + (", dequant only)" if args.unfused else ", fused dequant + in-block inverse)"),
-                "ops_per_launch": gemm_ops, "avg_launch_ms": stages["gemm_lo"]}
+    epi = ", dequant only)" if args.unfused else ", fused dequant + in-block inverse)"
+
+    def gemm_roofline(engine, ms):
+        peak = PEAK_FP6_TFLOPS if engine == "fp6" else PEAK_INT8_TOPS
+        achieved = gemm_ops / (ms * 1e-3) / 1e12
+        sustained = st.mfma_rate(engine)
+        return {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s" if engine == "fp6" else "TOP/s",
+                "frac": achieved / peak, "traffic": read_traffic(engine, w.name),
+                "kernel": ("k_gemm6 (fp6 MFMA" if engine == "fp6" else "k_gemm (int8 MFMA") + ", 4-bit rows" + epi,
+                "ops_per_launch": gemm_ops, "avg_launch_ms": ms,
+                "mfma_only_rate_measured": sustained, "frac_of_mfma_only_rate": achieved / sustained if sustained else None}
+
+    roofline = gemm_roofline(args.engine, stages["gemm_lo"])
+    other = "int8" if args.engine == "fp6" else "fp6"
+    plan.set_gemm_engine(other)
+    if other == "fp6":
+        run_stage(6)
+    other_ms = run_stage(4)
+    plan.set_gemm_engine(args.engine)
+    roofline_other = gemm_roofline(other, other_ms)
+    log(f"gemm_lo under the {other} engine: {other_ms:.4f} ms")
     # transform + quantization stage against the HBM roofline: X read + packed codes + scales written
     xbytes = 2 if w.x_dtype == "bf16" else 4
     qa_bytes = (w.batch * w.seq_len * w.d_in * xbytes + w.batch * w.k_hi * w.d_in
@@ -187,15 +212,17 @@ def main():
     out = {
         "metric": "tokens/sec through STaMP linear fwd", "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp6" if args.engine == "fp6" else "int8", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out} "
                                f"{w.xform} J={w.levels} k_hi={w.k_hi} W4A4(+{w.k_hi} int8 tokens), bf16 in/out",
-                   "path": "unfused" if args.unfused else "fused"},
-        "roofline": roofline, "roofline_quant": roofline_quant, "stages_ms": stages,
+                   "path": "unfused" if args.unfused else "fused", "gemm_engine": args.engine},
+        "roofline": roofline, f"roofline_{other}_engine": roofline_other, "roofline_quant": roofline_quant,
+        "stages_ms": stages,
     }
     if not args.no_cpu_baseline:
         log("cpu baseline (oracle)")
-        out["cpu_baseline"] = cpu_baseline(w, inp, min(args.cpu_cols, w.d_out))
+        out["cpu_baseline"] = cpu_baseline(w, inp, min(args.cpu_cols, w.d_out), args.cpu_seqs)
     plan.destroy()
     print(json.dumps(out), flush=True)
 

@@ -171,14 +171,22 @@ stamp_status_t stamp_plan_set_unfused(stamp_plan_t* plan, int32_t unfused);
  * rows quantized to bits_lo = 4 against the 4-bit weights).  Both compute the same integer sums
  * acc[m, n] = sum_c code[m, c] * qW[c, n] exactly, so every result of the library is bit-identical
  * under either setting:
- *   STAMP_GEMM_INT8  the codes as int8, int8 x int8 -> int32 MFMA (default);
- *   STAMP_GEMM_FP6   the codes as 6-bit floating point numbers code / 8 (E2M3, exact), FP6 x FP6 -> fp32
- *                    MFMA at twice the rate per clock; the fp32 accumulator holds acc / 64 exactly
- *                    (|acc| <= 49 d_in < 2^24).  Costs one conversion pass over the packed rows.
+ *   STAMP_GEMM_FP6   (default) the codes as 6-bit floating point numbers code / 8 (E2M3, exact),
+ *                    FP6 x FP6 -> fp32 MFMA, twice the int8 rate per clock; the fp32 accumulator holds
+ *                    acc / 64 exactly (|acc| <= 49 d_in < 2^24).  Costs one conversion pass over the
+ *                    packed rows inside stamp_linear_forward(_q);
+ *   STAMP_GEMM_INT8  the codes as int8, int8 x int8 -> int32 MFMA.
  * The 8-bit rows always run on the int8 pipeline.  May be changed between calls; the workspace size
  * does not depend on it.  Returns STAMP_ERR_UNSUPPORTED for any other value. */
 typedef enum { STAMP_GEMM_INT8 = 0, STAMP_GEMM_FP6 = 1 } stamp_gemm_engine_t;
 stamp_status_t stamp_plan_set_gemm_engine(stamp_plan_t* plan, int32_t engine);
+
+/* Measurement aid (not part of the layer): the rate, in 1e12 operations per second, that the matrix
+ * pipeline of `engine` sustains on the current device over pseudo-random 4-bit codes held in registers,
+ * with no memory traffic: the ceiling that the GEMM of that engine can approach on such values (it
+ * lies below the data-sheet peak, because the clock under a matrix load depends on the operand data).
+ * Runs on the default stream, allocates 4 bytes, blocks for a few tens of milliseconds. */
+stamp_status_t stamp_debug_mfma_rate(int32_t engine, double* tera_ops_per_s_host);
 
 const char* stamp_status_string(stamp_status_t status);
 

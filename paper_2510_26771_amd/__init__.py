@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     StampPlan,
     PlanDesc,
     lib_path,
+    mfma_rate,
     load_library,
     STATUS_NAMES,
     STAMP_F32,

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "STAMP_OK", 1: "STAMP_ERR_NULL", 2: "STAMP_ERR_SHAPE", 3: "ST
 EXPORTS = ["stamp_plan_create", "stamp_plan_destroy", "stamp_plan_workspace_bytes", "stamp_plan_row_of_coeff",
            "stamp_quantize_act", "stamp_linear_forward", "stamp_linear_forward_q", "stamp_inverse",
            "stamp_debug_gemm_acc", "stamp_debug_weight_codes", "stamp_debug_run_stage", "stamp_plan_set_unfused", "stamp_plan_set_gemm_engine",
-           "stamp_status_string"]
+           "stamp_debug_mfma_rate", "stamp_status_string"]
 
 
 class StampError(RuntimeError):
@@ -104,6 +104,8 @@ def load_library():
     lib.stamp_plan_set_unfused.restype = C.c_int
     lib.stamp_plan_set_gemm_engine.argtypes = [vp, i32]
     lib.stamp_plan_set_gemm_engine.restype = C.c_int
+    lib.stamp_debug_mfma_rate.argtypes = [i32, C.POINTER(C.c_double)]
+    lib.stamp_debug_mfma_rate.restype = C.c_int
     lib.stamp_status_string.argtypes = [C.c_int]
     lib.stamp_status_string.restype = C.c_char_p
     _lib = lib
@@ -123,6 +125,15 @@ def _stream(stream) -> Optional[int]:
     import torch
     s = stream if stream is not None else torch.cuda.current_stream()
     return s.cuda_stream or None
+
+
+def mfma_rate(engine) -> float:
+    """Sustained rate (1e12 op/s) of the matrix pipeline of `engine` ("int8" / "fp6") on random 4-bit codes, no memory traffic."""
+    lib = load_library()
+    code = {"int8": 0, "fp6": 1}[engine] if isinstance(engine, str) else int(engine)
+    out = C.c_double(0.0)
+    _check(lib.stamp_debug_mfma_rate(code, C.byref(out)), "stamp_debug_mfma_rate")
+    return out.value
 
 
 class StampPlan:

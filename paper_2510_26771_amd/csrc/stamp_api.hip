@@ -153,6 +153,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   p->geom = g;
   p->fused_ok = fused_ok;
   p->unfused = 0;
+  p->engine = STAMP_GEMM_FP6;
   p->Kpad = ((g.d + 127) / 128) * 128;
   p->Npad = ((g.N + 255) / 256) * 256;
   p->Mpad = ((g.B * g.s + 255) / 256) * 256;

@@ -135,7 +135,7 @@ def y_to_numpy(Y, y_is_bf16: bool) -> np.ndarray:
 
 def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: Optional[np.ndarray] = None,
               check_acc: bool = True, check_unfused: bool = True,
-              engines: Tuple[str, ...] = ("int8", "fp6")) -> Dict[str, float]:
+              engines: Tuple[str, ...] = ("fp6", "int8")) -> Dict[str, float]:
     """Everything the ABI exposes, on one workload, against the oracle, under each GEMM engine."""
     import torch
     import paper_2510_26771_amd as st
@@ -200,7 +200,7 @@ def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: 
             plan.linear_forward(Xd, Y, ws)
             torch.cuda.synchronize()
             y_np = y_to_numpy(pick(Y), y_bf16)
-            tag = ("unfused" if unfused else "fused") + ("" if engine == "int8" else "_" + engine)
+            tag = ("unfused" if unfused else "fused") + "_" + engine
             report[f"y_relerr_{tag}"] = check_output(y_np, ora["Y"], y_bf16, f"{w.name} {tag}")
             # and from the separately quantized activation
             Y2 = torch.zeros_like(Y)

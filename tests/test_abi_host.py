@@ -89,6 +89,9 @@ def test_null_arguments(lib):
     assert lib.stamp_debug_weight_codes(None, None, None) == 1
     assert lib.stamp_debug_run_stage(None, 0, None, None, None, None, None, None, 0, None) == 1
     assert lib.stamp_plan_set_unfused(None, 1) == 1
+    assert lib.stamp_plan_set_gemm_engine(None, 1) == 1
+    assert lib.stamp_debug_mfma_rate(0, None) == 1
+    assert lib.stamp_debug_mfma_rate(7, None) == 1  # the null check comes first
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
