@@ -22,34 +22,36 @@ namespace {
 
 using namespace stamp_gemm;
 
-constexpr int BN = 128;                        // workgroup tile 256 x 128, 4 waves
-constexpr int kTileBytes = 4 * kWaveTileBytes;  // the four waves' epilogue staging tiles
 
-template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16>
-__global__ __launch_bounds__(256, 2) void k_gemm(const GemmArgs a) {
+// WN = waves along N: 2 -> 4 waves, tile 256 x 128, two workgroups per CU; 4 -> 8 waves, tile 256 x 256,
+// one workgroup per CU (fewer, larger tiles: for the few 8-bit rows, whose whole GEMM is one round of tiles).
+template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16, int WN>
+__global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const GemmArgs a) {
   using Acc = typename std::conditional<A_INT4, AccI8Lo, AccI8Hi>::type;
-  constexpr int nB = BN / 32;                   // B chunks per thread per step (BN columns * 8 chunks / 256 threads)
+  constexpr int BN = 64 * WN, NT = 128 * WN;    // tile width, threads
+  constexpr int kTileBytes = 2 * WN * kWaveTileBytes;  // the waves' epilogue staging tiles
+  constexpr int nB = BN * 8 / NT;               // B chunks per thread per step (BN columns * 8 chunks / NT threads)
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   constexpr int rowA = A_INT4 ? 64 : 128;       // bytes per A row per K step
   constexpr int chA = rowA / 16;                // 16-byte chunks per A row (4 or 8)
   constexpr int bytesA = BM * rowA, bytesB = BN * 128;
   constexpr int stage = bytesA + bytesB;
-  constexpr int nA = chA;                       // A chunks per thread per step (256 rows * chA / 256 threads)
+  constexpr int nA = 256 * chA / NT;            // A chunks per thread per step (256 rows * chA / NT threads)
   constexpr int kMainBytes = 2 * stage;
   constexpr int kRowInfoOff = (EPI == 2 && kTileBytes > kMainBytes) ? kTileBytes : kMainBytes;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
+  const int wm = wave / WN, wn = wave % WN;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
   const int l32 = lane & 31, kg = lane >> 5;
   int tm, tn;
   tile_of_block(a.M, a.Npad, BN, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int KT = a.Kpad / BK;
 
-  // ---- global -> LDS assignment: chunk q = i * 256 + tid of the tile, consecutive lanes = consecutive
+  // ---- global -> LDS assignment: chunk q = i * NT + tid of the tile, consecutive lanes = consecutive
   //      chunks.  Row / column of chunk i is (row0 + i * rows_per_pass); its swizzled slot does not
   //      depend on i, so one base address per operand and a uniform stride per pass suffice. ----
-  constexpr int rowsPerPassA = 256 / chA;  // 64 (4-bit) or 32 (8-bit) rows per pass of 256 threads
+  constexpr int rowsPerPassA = NT / chA;   // rows per pass of NT threads
   const int rowA0 = tid / chA, slotA = tid % chA;
   const int cA = A_INT4 ? (slotA ^ ((rowA0 >> 2) & 3)) : (slotA ^ ((rowA0 >> 1) & 7));
   const int koffA = cA * 16;
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm(const GemmArgs a) {
   uint32_t offB[nB];
 #pragma unroll
   for (int i = 0; i < nB; ++i) {
-    const int col = colB0 + 32 * i;
+    const int col = colB0 + (NT / 8) * i;
     offB[i] = (uint32_t)(col >> 7) * (uint32_t)(KT * 128 * 128) + (uint32_t)((col & 127) * 128 + cB * 16);
   }
   constexpr int kStepB = 128 * 128;  // bytes between consecutive K steps of one column tile
@@ -117,18 +119,18 @@ __global__ __launch_bounds__(256, 2) void k_gemm(const GemmArgs a) {
     _Pragma("unroll") for (int i = 0; i < nA; ++i) {                                                       \
       const uint8_t* src_ = A_INT4 ? (baseGA + ka_ + offA[i]) : (baseGA + min(ka_ + offA[i], lastA));      \
       __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src_,                \
-                                       (void __attribute__((address_space(3)))*)(so_ + i * 4096), 16, 0, 0); \
+                                       (void __attribute__((address_space(3)))*)(so_ + i * (NT * 16)), 16, 0, 0); \
     }                                                                                                      \
     _Pragma("unroll") for (int i = 0; i < nB; ++i)                                                         \
         __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(baseGB + kb_ + offB[i]), \
-                                         (void __attribute__((address_space(3)))*)(so_ + bytesA + i * 4096), 16, 0, 0); \
+                                         (void __attribute__((address_space(3)))*)(so_ + bytesA + i * (NT * 16)), 16, 0, 0); \
   } while (0)
 
 
   STAMP_REQUEST(0, 0);
   EpiOperands<EPI, RB, IS2D> eo;
   eo.request(a, m0, n0, lane, wm, wn);
-  store_row_info<Acc, EPI>(a, m0, tid, smem + kRowInfoOff);
+  if (NT == 256 || tid < 256) store_row_info<Acc, EPI>(a, m0, tid, smem + kRowInfoOff);
 
   // Step kt: wait for this wave's loads of step kt, then the workgroup barrier (every wave's loads of
   // step kt have landed, and every wave has left step kt-1, whose stage is now free); request step
@@ -218,20 +220,21 @@ __global__ __launch_bounds__(256, 2) void k_gemm(const GemmArgs a) {
   epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave, wm, wn);
 }
 
-template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16>
+template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16, int WN>
 hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
+  constexpr int BN = 64 * WN;
   constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
-  constexpr size_t epi_lds = (EPI == 2) ? (size_t)kTileBytes : 0;
+  constexpr size_t epi_lds = (EPI == 2) ? (size_t)(2 * WN * kWaveTileBytes) : 0;
   constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + 2048;  // + per-row factors and destinations
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, YBF16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
-  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, YBF16>), dim3(mt * nt), dim3(256), lds, st, a);
+  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>), dim3(mt * nt), dim3(128 * WN), lds, st, a);
   return hipGetLastError();
 }
 
@@ -239,9 +242,22 @@ template <bool A_INT4, int EPI, int RB, bool IS2D>
 hipError_t launch(const GemmArgs& a, hipStream_t st) {
   // the output type only matters to the fused epilogue
   if constexpr (EPI == 2) {
-    if (a.g.y_bf16) return launch_y<A_INT4, EPI, RB, IS2D, true>(a, st);
+    if (a.g.y_bf16) return launch_y<A_INT4, EPI, RB, IS2D, true, 2>(a, st);
   }
-  return launch_y<A_INT4, EPI, RB, IS2D, false>(a, st);
+  if constexpr (!A_INT4) {
+    // The 8-bit rows' GEMM keeps one 256 x 128 workgroup per CU (its stages hold unpacked int8 rows).  When
+    // that needs more than one round of tiles, 256 x 256 tiles (half as many, one round) finish sooner.
+    static int cus = 0;
+    if (cus == 0) {
+      int dev = 0;
+      if (hipGetDevice(&dev) != hipSuccess ||
+          hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    }
+    const int tiles128 = ((a.M + BM - 1) / BM) * (a.Npad / 128);
+    if (tiles128 > cus) return launch_y<A_INT4, EPI, RB, IS2D, false, 4>(a, st);
+  }
+  return launch_y<A_INT4, EPI, RB, IS2D, false, 2>(a, st);
 }
 
 }  // namespace
