@@ -24,12 +24,13 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
+typedef float f8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 constexpr int BM = 256, BK = 128;
 constexpr int NI = 2;           // 32-column MFMA blocks per wave along N
-constexpr int kEpiStride = 36;  // floats per row of the per-wave epilogue staging tile (16-byte aligned rows)
-constexpr int kWaveTileBytes = 128 * kEpiStride * 4;  // one wave's staging tile of the fused epilogue
+constexpr int kEpiStride = 68;  // floats per row of the per-wave epilogue staging tile (64 columns + 4, rows 16-byte aligned)
+constexpr int kWaveTileBytes = 64 * kEpiStride * 4;  // one wave's staging tile of the fused epilogue: 64 rows x 64 columns
 constexpr int kNumXcd = 8;
 constexpr int kGroupM = 8;
 
@@ -94,55 +95,67 @@ __device__ __forceinline__ void tile_of_block(int M, int Npad, int bn, int& tm, 
   tn = in_grp / gm;
 }
 
-// Where one lane stores the tokens of one unit (a block or an aligned part of one): 4 adjacent output
-// columns per token, written as one 8-byte (bf16) or 16-byte (fp32) store when d_out allows it.
+// Where one lane stores the tokens of one unit (an aligned part of a block): 8 adjacent output columns
+// per token, written as one 16-byte store (bf16) or two (fp32) when d_out allows it.  The 8 lanes of a
+// unit's group thus cover the wave tile's 64 columns: whole 128-byte lines of a bf16 Y.
 template <bool YBF16, bool VEC>
-struct OutQuad {
+struct OutOct {
   void* Y;
-  size_t base;        // element index of token 0 of the block, first of the 4 columns
+  size_t base;        // element index of token 0 of the block, first of the 8 columns
   size_t tok_stride;  // d_out
   size_t row_stride;  // 2-D: grid_w * d_out
-  f4 bias;
-  int nvalid;         // how many of the 4 columns exist (d_out tail)
-  __device__ __forceinline__ void put(size_t idx, f4 v) const {
+  f8 bias;
+  int nvalid;         // how many of the 8 columns exist (d_out tail)
+  __device__ __forceinline__ void put(size_t idx, f8 v) const {
     v += bias;
     if constexpr (YBF16) {
       // round-to-nearest-even pairs in hardware (v_cvt_pk_bf16_f32)
-      const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[0], v[1]}, bf2));
-      const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[2], v[3]}, bf2));
+      u4 w;
+      w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[0], v[1]}, bf2));
+      w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[2], v[3]}, bf2));
+      w.z = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[4], v[5]}, bf2));
+      w.w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[6], v[7]}, bf2));
       uint16_t* y = reinterpret_cast<uint16_t*>(Y) + idx;
       if constexpr (VEC) {
-        *reinterpret_cast<uint2*>(y) = make_uint2(lo, hi);
+        *reinterpret_cast<u4*>(y) = w;
       } else {
-        if (nvalid > 0) y[0] = (uint16_t)lo;
-        if (nvalid > 1) y[1] = (uint16_t)(lo >> 16);
-        if (nvalid > 2) y[2] = (uint16_t)hi;
-        if (nvalid > 3) y[3] = (uint16_t)(hi >> 16);
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+          if (t < nvalid) y[t] = (uint16_t)(w[t >> 1] >> (16 * (t & 1)));
       }
     } else {
       float* y = reinterpret_cast<float*>(Y) + idx;
       if constexpr (VEC) {
-        *reinterpret_cast<f4*>(y) = v;
+        *reinterpret_cast<f4*>(y) = (f4){v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f4*>(y + 4) = (f4){v[4], v[5], v[6], v[7]};
       } else {
-        if (nvalid > 0) y[0] = v[0];
-        if (nvalid > 1) y[1] = v[1];
-        if (nvalid > 2) y[2] = v[2];
-        if (nvalid > 3) y[3] = v[3];
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+          if (t < nvalid) y[t] = v[t];
       }
     }
   }
 };
 
-// Depth-first inverse of one unit for 4 columns.  The unit is the subtree rooted at node (M0, h) of a
-// block's Haar tree; node (M, I) of that subtree holds the sum `a` of its tokens; tile[e * kEpiStride]
-// is the block's coefficient at in-block STaMP position e = 2^M + (h << (M - M0)) + I.  Only O(r)
-// values are live at any time and every coefficient is read once.
+// One coefficient row of the staging tile for this lane's 8 columns.  The tile keeps the wave tile's
+// column c = 8 j + t at position 4 j + t (t < 4) or 32 + 4 j + (t - 4): the 8 lanes of a group then
+// read two contiguous runs of 128 bytes, and `tile` already points at position 4 j.
+__device__ __forceinline__ f8 tile_row(const float* tile, int e) {
+  const f4 lo = *reinterpret_cast<const f4*>(tile + e * kEpiStride);
+  const f4 hi = *reinterpret_cast<const f4*>(tile + e * kEpiStride + 32);
+  return (f8){lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
+
+// Depth-first inverse of one unit for 8 columns.  The unit is the subtree rooted at node (M0, h) of a
+// block's Haar tree; node (M, I) of that subtree holds the sum `a` of its tokens; row e of the tile is
+// the block's coefficient at in-block STaMP position e = 2^M + (h << (M - M0)) + I.  Only O(r) values
+// are live at any time and every coefficient is read once.
 template <int RLOG, int M0, int M, int I, typename Out>
-__device__ __forceinline__ void dfs1d(const float* tile, int h, f4 a, const Out& o) {
+__device__ __forceinline__ void dfs1d(const float* tile, int h, f8 a, const Out& o) {
   if constexpr (M == RLOG) {
     o.put(o.base + (size_t)((h << (RLOG - M0)) + I) * o.tok_stride, a);
   } else {
-    const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << M) + (h << (M - M0)) + I) * kEpiStride);
+    const f8 d = tile_row(tile, (1 << M) + (h << (M - M0)) + I);
     dfs1d<RLOG, M0, M + 1, 2 * I, Out>(tile, h, a + d, o);
     dfs1d<RLOG, M0, M + 1, 2 * I + 1, Out>(tile, h, a - d, o);
   }
@@ -151,16 +164,16 @@ __device__ __forceinline__ void dfs1d(const float* tile, int h, f4 a, const Out&
 // 2-D: the unit is the quadtree node (M0, hy, hx) of a g x g block; bands W, H, D of level-node side
 // gl = 2^M sit at e = gl^2 (1 + band) + iy * gl + ix.
 template <int RLOG, int M0, int M, int IY, int IX, typename Out>
-__device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, const Out& o) {
+__device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f8 a, const Out& o) {
   if constexpr (M == RLOG) {
     o.put(o.base + (size_t)((hy << (RLOG - M0)) + IY) * o.row_stride + (size_t)((hx << (RLOG - M0)) + IX) * o.tok_stride, a);
   } else {
     constexpr int gl = 1 << M;
     const int e0 = ((hy << (M - M0)) + IY) * gl + ((hx << (M - M0)) + IX);
-    const f4 cW = *reinterpret_cast<const f4*>(tile + (gl * gl + e0) * kEpiStride);
-    const f4 cH = *reinterpret_cast<const f4*>(tile + (2 * gl * gl + e0) * kEpiStride);
-    const f4 cD = *reinterpret_cast<const f4*>(tile + (3 * gl * gl + e0) * kEpiStride);
-    const f4 t0 = a + cH, t2 = a - cH, t1 = cW + cD, t3 = cW - cD;
+    const f8 cW = tile_row(tile, gl * gl + e0);
+    const f8 cH = tile_row(tile, 2 * gl * gl + e0);
+    const f8 cD = tile_row(tile, 3 * gl * gl + e0);
+    const f8 t0 = a + cH, t2 = a - cH, t1 = cW + cD, t3 = cW - cD;
     dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX, Out>(tile, hy, hx, t0 + t1, o);
     dfs2d<RLOG, M0, M + 1, 2 * IY, 2 * IX + 1, Out>(tile, hy, hx, t0 - t1, o);
     dfs2d<RLOG, M0, M + 1, 2 * IY + 1, 2 * IX, Out>(tile, hy, hx, t2 + t3, o);
@@ -168,15 +181,18 @@ __device__ __forceinline__ void dfs2d(const float* tile, int hy, int hx, f4 a, c
   }
 }
 
-// Shape of the fused epilogue for block size RB: R tokens per block, units of at most 16 tokens (the
-// subtree at depth M0 of a block's tree), U units per block, npass passes of 8 units per wave tile.
+// Shape of the fused epilogue for block size RB.  The wave tile's 128 rows are handled as two halves of
+// 64 rows (64 / R whole blocks of R tokens).  A unit is the subtree at depth M0 of a block's tree: 8
+// tokens in 1-D, 2 x 2 tokens in 2-D; U units per block; npass passes of 8 units (one per group of 8
+// lanes) cover a half.
 template <int RB, bool IS2D>
 struct EpiShape {
   static constexpr int R = IS2D ? (1 << (2 * RB)) : (1 << RB);
-  static constexpr int nblk = 128 / R;
-  static constexpr int M0 = IS2D ? (RB == 3 ? 1 : 0) : (RB > 4 ? RB - 4 : 0);
+  static constexpr int nblk = 64 / R;
+  static constexpr int M0 = IS2D ? (RB - 1) : (RB - 3);
   static constexpr int U = IS2D ? (1 << (2 * M0)) : (1 << M0);
   static constexpr int npass = (nblk * U) / 8;
+  static_assert(R <= 64 && M0 >= 0 && nblk * U >= 8, "block size outside the fused epilogue's range");
 };
 
 // Global operands of the fused epilogue (weight scales, bias, block sums P of this lane's units),
@@ -185,21 +201,27 @@ template <int EPI, int RB, bool IS2D>
 struct EpiOperands {
   using ES = EpiShape<(EPI == 2 ? RB : 3), IS2D>;
   float sw[NI];
-  f4 bias[NI];
-  f4 top[NI][ES::npass];
+  f8 bias;
+  f8 top[2][ES::npass];
   __device__ __forceinline__ void request(const GemmArgs& a, int m0, int n0, int lane, int wm, int wn) {
     if constexpr (EPI == 2) {
-      const int c4 = (lane & 7) * 4, ug = lane >> 3, l32 = lane & 31;
+      const int c8 = (lane & 7) * 8, ug = lane >> 3, l32 = lane & 31;
+      const int nw = n0 + wn * 64;
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int nw = n0 + wn * (32 * NI) + ni * 32;
-        sw[ni] = a.sw[nw + l32];
-        bias[ni] = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c4) : (f4){0.0f, 0.0f, 0.0f, 0.0f};
+      for (int ni = 0; ni < NI; ++ni) sw[ni] = a.sw[nw + ni * 32 + l32];
+      const f4 zero = (f4){0.0f, 0.0f, 0.0f, 0.0f};
+      const f4 b0 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8) : zero;
+      const f4 b1 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8 + 4) : zero;
+      bias = (f8){b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
 #pragma unroll
         for (int pass = 0; pass < ES::npass; ++pass) {
           const int blk = (pass * 8 + ug) / ES::U;
-          const int mrow = min(m0 + wm * 128 + blk * ES::R, a.M - 1);
-          top[ni][pass] = *reinterpret_cast<const f4*>(a.P + (size_t)(mrow / a.g.R) * a.Npad + nw + c4);
+          const int mrow = min(m0 + wm * 128 + hf * 64 + blk * ES::R, a.M - 1);
+          const float* src = a.P + (size_t)(mrow / a.g.R) * a.Npad + nw + c8;
+          const f4 p0 = *reinterpret_cast<const f4*>(src), p1 = *reinterpret_cast<const f4*>(src + 4);
+          top[hf][pass] = (f8){p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
         }
       }
     }
@@ -284,36 +306,45 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
       }
     }
   } else {
-    // fused: per 32-column strip, dequantize into this wave's LDS tile [128][kEpiStride]; then the wave's
-    // 8 groups of 8 lanes each take one unit (a block, or an aligned 16-token part of one) and 4 columns
-    // per lane, and run the depth-first inverse, storing the unit's tokens.
+    // fused: per half of 64 rows, dequantize into this wave's LDS tile [64][kEpiStride]; then the wave's
+    // 8 groups of 8 lanes each take one unit and 8 columns per lane, and run the depth-first inverse,
+    // storing the unit's tokens.
     using ES = EpiShape<RB, IS2D>;
     constexpr int R = ES::R, M0 = ES::M0, U = ES::U, npass = ES::npass;
-    float* s_tile = reinterpret_cast<float*>(smem) + wave * (128 * kEpiStride);
-    // row factors of this lane's 64 accumulator rows, read before any staging write
-    f4 rf[4][4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        rf[mi][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + mi * 32 + 8 * q + 4 * kg);
-    const int c4 = (lane & 7) * 4, ug = lane >> 3;
-    auto run_strips = [&](auto vec_tag) __attribute__((always_inline)) {
+    float* s_tile = reinterpret_cast<float*>(smem) + wave * (64 * kEpiStride);
+    const int c8 = (lane & 7) * 8, ug = lane >> 3;
+    // staging position of this lane's accumulator column 32 ni + l32 = 8 j + t (see tile_row)
+    const int pos0 = ((l32 & 4) ? 32 : 0) + 4 * (l32 >> 3) + (l32 & 3);
+    const int nw = n0 + wn * 64;  // first column of the wave tile
+    const int n = nw + c8;        // first of this lane's 8 output columns
+    auto run_halves = [&](auto vec_tag) __attribute__((always_inline)) {
       constexpr bool VEC = decltype(vec_tag)::value;
-      OutQuad<YBF16, VEC> o;
+      OutOct<YBF16, VEC> o;
       o.Y = a.out;
       o.tok_stride = (size_t)a.N;
       o.row_stride = (size_t)g.gridW * a.N;
+      o.nvalid = a.N - n;
+      o.bias = eo.bias;
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int nw = n0 + wn * (32 * NI) + ni * 32;  // first column of the strip
-        const float swn = eo.sw[ni];
+      for (int hf = 0; hf < 2; ++hf) {
+        // row factors of this lane's 32 accumulator rows of the half
+        f4 rf[2][4];
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
+        for (int mh = 0; mh < 2; ++mh)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int rw = mi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-            s_tile[rw * kEpiStride + l32] = ((float)acc[mi][ni][v] * rf[mi][v >> 2][v & 3]) * swn;
+          for (int q = 0; q < 4; ++q)
+            rf[mh][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + (2 * hf + mh) * 32 + 8 * q + 4 * kg);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+          const float swn = eo.sw[ni];
+#pragma unroll
+          for (int mh = 0; mh < 2; ++mh) {
+            const int mi = 2 * hf + mh;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int rw = mh * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+              s_tile[rw * kEpiStride + pos0 + 16 * ni] = ((float)acc[mi][ni][v] * rf[mh][v >> 2][v & 3]) * swn;
+            }
           }
         }
         // the staging tile is private to this wave: its own LDS writes only have to complete (the LDS
@@ -321,49 +352,52 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         asm volatile("" ::: "memory");
-        const int n = nw + c4;
-        o.nvalid = a.N - n;
-        o.bias = eo.bias[ni];
 #pragma unroll
         for (int pass = 0; pass < npass; ++pass) {
           const int unit = pass * 8 + ug;
           const int blk = unit / U, h = unit % U;
-          const int mrow = m0 + wm * 128 + blk * R;  // physical row of e = 0 of this block
+          const int mrow = m0 + wm * 128 + hf * 64 + blk * R;  // physical row of e = 0 of this block
           if (mrow < a.M && n < a.N) {
             const int b = mrow / g.s, pr = mrow - b * g.s;
             const int j = pr / g.R;
-            f4 top = eo.top[ni][pass];
-            const float* tile = s_tile + blk * R * kEpiStride + c4;
+            f8 top = eo.top[hf][pass];
+            const float* tile = s_tile + blk * R * kEpiStride + 4 * (lane & 7);
             if constexpr (IS2D) {
               const int bi = j / g.G, bj = j - bi * g.G;
               o.base = ((size_t)b * g.s + (size_t)(bi << RB) * g.gridW + (size_t)(bj << RB)) * a.N + n;
-              const int hy = h >> 1, hx = h & 1;
-              if constexpr (M0 == 1) {
-                const f4 cW = *reinterpret_cast<const f4*>(tile + 1 * kEpiStride);
-                const f4 cH = *reinterpret_cast<const f4*>(tile + 2 * kEpiStride);
-                const f4 cD = *reinterpret_cast<const f4*>(tile + 3 * kEpiStride);
-                const f4 t0 = top + cH, t2 = top - cH, t1 = cW + cD, t3 = cW - cD;
-                top = hy ? (hx ? (t2 - t3) : (t2 + t3)) : (hx ? (t0 - t1) : (t0 + t1));
+              const int hy = h >> M0, hx = h & ((1 << M0) - 1);
+              // walk from the block's root down to the unit's node: at level m the ancestor is node
+              // (hy >> (M0 - m), hx >> (M0 - m)); keep the quadrant that holds the unit
+#pragma unroll
+              for (int m = 0; m < M0; ++m) {
+                const int gl = 1 << m;
+                const int e0 = (hy >> (M0 - m)) * gl + (hx >> (M0 - m));
+                const f8 cW = tile_row(tile, gl * gl + e0);
+                const f8 cH = tile_row(tile, 2 * gl * gl + e0);
+                const f8 cD = tile_row(tile, 3 * gl * gl + e0);
+                const f8 t0 = top + cH, t2 = top - cH, t1 = cW + cD, t3 = cW - cD;
+                const int qy = (hy >> (M0 - m - 1)) & 1, qx = (hx >> (M0 - m - 1)) & 1;
+                top = qy ? (qx ? (t2 - t3) : (t2 + t3)) : (qx ? (t0 - t1) : (t0 + t1));
               }
-              dfs2d<RB, M0, M0, 0, 0, OutQuad<YBF16, VEC>>(tile, hy, hx, top, o);
+              dfs2d<RB, M0, M0, 0, 0, OutOct<YBF16, VEC>>(tile, hy, hx, top, o);
             } else {
               o.base = ((size_t)b * g.s + (size_t)j * R) * a.N + n;
 #pragma unroll
               for (int m = 0; m < M0; ++m) {
-                const f4 d = *reinterpret_cast<const f4*>(tile + ((1 << m) + (h >> (M0 - m))) * kEpiStride);
+                const f8 d = tile_row(tile, (1 << m) + (h >> (M0 - m)));
                 top = ((h >> (M0 - m - 1)) & 1) ? (top - d) : (top + d);
               }
-              dfs1d<RB, M0, M0, 0, OutQuad<YBF16, VEC>>(tile, h, top, o);
+              dfs1d<RB, M0, M0, 0, OutOct<YBF16, VEC>>(tile, h, top, o);
             }
           }
         }
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // this wave's reads of the tile are done before the next strip overwrites it
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // this wave's reads of the tile are done before the next half overwrites it
         asm volatile("" ::: "memory");
       }
     };
-    if ((a.N & 3) == 0) run_strips(std::true_type{});
-    else run_strips(std::false_type{});
+    if ((a.N & 7) == 0) run_halves(std::true_type{});
+    else run_halves(std::false_type{});
   }
 }
 
