@@ -12,7 +12,7 @@
 //   k_bottom1d / k_bottom2d  one workgroup per (sequence, block of R tokens), all d_in channels;
 //                            each thread owns 8 channels for every token of the block, so the
 //                            butterflies stay in registers; only the per-row absmax crosses lanes
-//                            (DPP inside a wave, LDS atomic max across waves).  Emits the R-1
+//                            (DPP inside a wave, per-wave partial maxima in LDS across waves).  Emits the R-1
 //                            4-bit rows of the block and the block sum (fp32, to scratch).
 //   k_top                    the remaining levels over the k_hi block sums, in LDS, per channel
 //                            slice; writes the normalised 8-bit-row coefficients to scratch and
@@ -99,14 +99,10 @@ constexpr int cmin(int a, int b) { return a < b ? a : b; }
 struct RowMeta { int level; int e; };
 constexpr int kMaxRows = 18;  // most rows finished by one streaming step (2-D: 12 + 3 + 3)
 
-// With DEFER the packed codes and the scale are handed back (wout[r], scale_out of lane r) instead of
-// being stored: the caller stores them one step later, so that the wait for the next batch of staged
-// rows does not also wait for stores that were only just issued.
-template <int NR, bool IS2D, bool DEFER, typename MetaFn>
+template <int NR, bool IS2D, typename MetaFn>
 __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[kMaxRows * 16],
                                            uint8_t* q_lo_thr /* this thread's 4 bytes of row e=0 of the block */,
-                                           float* scales_blk, bool active, int tid, uint32_t (&wout)[kMaxRows],
-                                           float& scale_out) {
+                                           float* scales_blk, bool active, int tid) {
   const int lane = tid & 63, wave = tid >> 6;
   uint32_t* part = &s_max[0][0] + (step & 1) * (kMaxRows * 16);  // [row][wave] partial maxima, double buffered
 #pragma unroll
@@ -146,8 +142,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     // even 1-D levels and all 2-D levels have a power-of-two norm: fold it into the multiplier
     const bool fold = IS2D || ((rm.level & 1) == 0);
     mul_lane = fold ? __fmul_rn(inv, nrm) : inv;
-    if constexpr (DEFER) scale_out = scale;
-    else if (tid < NR) scales_blk[rm.e] = scale;
+    if (tid < NR) scales_blk[rm.e] = scale;
   }
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
@@ -164,8 +159,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
       for (int c = 0; c < 8; ++c) p[c] = __fmul_rn(__fmul_rn(rowv[r][c], nrm), mul);
     }
     const uint32_t w = pack8_int4(p);
-    if constexpr (DEFER) wout[r] = w;
-    else if (active) *reinterpret_cast<uint32_t*>(q_lo_thr + rm.e * 64) = w;  // tiled layout: 64 bytes per row and K step
+    if (active) *reinterpret_cast<uint32_t*>(q_lo_thr + rm.e * 64) = w;  // tiled layout: 64 bytes per row and K step
   }
 }
 
@@ -289,9 +283,7 @@ __device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, u
   }
   chain1d<RLOG, 2, IT, 3, NP, NR>(cur, pend, rowv, top);
   auto meta = [](int r) -> RowMeta { return meta1d<RLOG, IT>(r); };
-  uint32_t wunused[kMaxRows];
-  float sunused;
-  flush_rows<NR, false, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, active, tid, wunused, sunused);
+  flush_rows<NR, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, active, tid);
 }
 
 template <int RLOG, bool BF16, int NP, int... ITS>
@@ -400,9 +392,7 @@ __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int g
     }
     return m;
   };
-  uint32_t wunused[kMaxRows];
-  float sunused;
-  flush_rows<NR, true, false>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, active, tid, wunused, sunused);
+  flush_rows<NR, true>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, active, tid);
 }
 
 template <int RLOG, bool BF16, int... SBS>
