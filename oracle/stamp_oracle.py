@@ -48,6 +48,15 @@ Readings of the paper where it is silent (each also listed in the design documen
   qmax = 2^(b-1) - 1, scale = absmax / qmax (range-based, no clipping, as in the Background
   section), code = clamp(rne(x * (qmax / absmax)), -qmax, qmax).  A zero row gets scale 0 and
   codes 0.  Rounding is round-half-to-even.
+* Asymmetric quantizer (what the paper's experiments use: "asymmetric quantization with minmax
+  scaling"; Eq. 1 in full): codes in [0, 2^b - 1], scale = range / (2^b - 1) (the printed scale is
+  its reciprocal: Eq. 1 divides by s, and the proof of the range bound uses range / (2^b - 1)),
+  integer offset z = rne(-min / scale) (Eq. 1 adds z to a rounded value and calls the result an
+  integer, so z is rounded; the printed z = -min / s is its real-valued form), code =
+  clamp(rne(x / scale) + z, 0, 2^b - 1), evaluated as rne(fl(x * inv)) with inv = (2^b - 1) / range.
+  The range of a token always contains 0 (min <- min(min, 0), max <- max(max, 0)): the paper does
+  not say what happens to a one-sided token; this keeps 0 exactly representable and z inside the
+  code range.  A zero row gets scale 0, z 0, codes 0.
 * Weights: per output channel, absmax / 7, round to nearest, no range search.
 * W is [d_in, d_out] and Y = X W.
 
@@ -365,6 +374,42 @@ def dequantize_tokens(codes: np.ndarray, scale: np.ndarray, dtype=np.float32) ->
     return codes.astype(dtype) * np.asarray(scale, dtype=dtype)[:, None]
 
 
+def qmax_unsigned(bits: int) -> int:
+    return (1 << bits) - 1
+
+
+def quantize_tokens_asym(T: np.ndarray, bits: np.ndarray, dtype=np.float32) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Per-token asymmetric min-max quantization of T[s, d] with bits[s] (Background, Eq. 1).
+
+    lo_i = min(min_j T_ij, 0), hi_i = max(max_j T_ij, 0), range_i = hi_i - lo_i;
+    scale_i = range_i / (2^b - 1);  inv_i = (2^b - 1) / range_i (two separate divisions);
+    z_i = rne(-(lo_i * inv_i));  code_ij = clamp(rne(T_ij * inv_i) + z_i, 0, 2^b - 1).
+    Zero rows: scale = inv = z = 0.  Returns (codes uint8 [s, d], scale [s], z [s] as integers
+    held in `dtype`).
+    """
+    T = np.asarray(T, dtype=dtype)
+    zero = np.zeros((), dtype=dtype)
+    lo = np.minimum(np.min(T, axis=1), zero)
+    hi = np.maximum(np.max(T, axis=1), zero)
+    rng = hi - lo
+    qm = np.array([qmax_unsigned(int(b)) for b in bits], dtype=dtype)
+    nz = rng > 0
+    scale = np.zeros_like(rng)
+    inv = np.zeros_like(rng)
+    scale[nz] = rng[nz] / qm[nz]
+    inv[nz] = qm[nz] / rng[nz]
+    z = np.rint(-(lo * inv)) + zero  # + 0 turns a -0 into +0
+    r = np.rint(T * inv[:, None]) + z[:, None]
+    r = np.minimum(np.maximum(r, zero), qm[:, None])
+    assert scale.dtype == np.dtype(dtype) and r.dtype == np.dtype(dtype) and z.dtype == np.dtype(dtype)
+    return r.astype(np.uint8), scale, z
+
+
+def dequantize_tokens_asym(codes: np.ndarray, scale: np.ndarray, z: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """Q^-1: (code - z) * scale."""
+    return (codes.astype(dtype) - np.asarray(z, dtype=dtype)[:, None]) * np.asarray(scale, dtype=dtype)[:, None]
+
+
 def quantize_weight(W: np.ndarray, bits_w: int = 4, dtype=np.float32) -> Tuple[np.ndarray, np.ndarray]:
     """Per-output-channel symmetric round-to-nearest quantization of W[d_in, d_out].
 
@@ -412,34 +457,53 @@ def round_to_bf16(y: np.ndarray) -> np.ndarray:
 
 def quantize_activation(X: np.ndarray, xform: str, levels: int, k_hi: int, bits_hi: int = 8,
                         bits_lo: int = 4, grid_h: int = 0, grid_w: int = 0,
-                        dtype=np.float32) -> Dict[str, np.ndarray]:
+                        dtype=np.float32, act_quant: str = "sym") -> Dict[str, np.ndarray]:
     """Steps 1-2 of the algorithm for X[batch, s, d]: T = L X per sequence, then per-token
-    mixed-precision codes and scales, all in STaMP order."""
+    mixed-precision codes and scales, all in STaMP order.  act_quant: "sym" (absmax, signed
+    codes) or "asym" (min-max, unsigned codes and integer offsets "zeros")."""
     B, s, d = X.shape
     bits = token_bits(s, k_hi, bits_hi, bits_lo)
     T = np.empty((B, s, d), dtype=dtype)
-    codes = np.empty((B, s, d), dtype=np.int8)
+    asym = act_quant == "asym"
+    assert asym or act_quant == "sym"
+    codes = np.empty((B, s, d), dtype=np.uint8 if asym else np.int8)
     scales = np.empty((B, s), dtype=dtype)
+    zeros = np.zeros((B, s), dtype=dtype)
     for b in range(B):
         T[b] = sequence_forward(X[b], xform, levels, grid_h, grid_w, dtype)
-        codes[b], scales[b] = quantize_tokens(T[b], bits, dtype)
-    return {"T": T, "codes": codes, "scales": scales, "bits": bits}
+        if asym:
+            codes[b], scales[b], zeros[b] = quantize_tokens_asym(T[b], bits, dtype)
+        else:
+            codes[b], scales[b] = quantize_tokens(T[b], bits, dtype)
+    out = {"T": T, "codes": codes, "scales": scales, "bits": bits}
+    if asym:
+        out["zeros"] = zeros
+    return out
 
 
 def linear_from_codes(codes: np.ndarray, scales: np.ndarray, qw: np.ndarray, sw: np.ndarray,
                       xform: str, levels: int, grid_h: int = 0, grid_w: int = 0,
-                      bias: Optional[np.ndarray] = None, dtype=np.float32) -> Dict[str, np.ndarray]:
+                      bias: Optional[np.ndarray] = None, dtype=np.float32,
+                      zeros: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """Steps 3-5: integer GEMM, dequantization Y' = (float(acc) * scale_m) * sw_n, inverse
-    transform per sequence and output column, bias."""
+    transform per sequence and output column, bias.  With integer offsets `zeros` (asymmetric
+    codes) the de-quantization (code - z) * scale of the Background section turns the sum into
+    acc[m, n] - z_m * sum_c qw[c, n], an exact integer, before it is scaled."""
     B, s, d = codes.shape
     N = qw.shape[1]
     acc = np.empty((B, s, N), dtype=np.int32)
     Yt = np.empty((B, s, N), dtype=dtype)
     Y = np.empty((B, s, N), dtype=dtype)
     sw = np.asarray(sw, dtype=dtype)
+    colsum = qw.astype(np.int64).sum(axis=0)
     for b in range(B):
         acc[b] = int_gemm(codes[b], qw)
-        Yt[b] = (acc[b].astype(dtype) * np.asarray(scales[b], dtype=dtype)[:, None]) * sw[None, :]
+        a = acc[b].astype(np.int64)
+        if zeros is not None:
+            zi = np.asarray(zeros[b]).astype(np.int64)
+            assert np.array_equal(zi.astype(np.float64), np.asarray(zeros[b], dtype=np.float64))
+            a = a - zi[:, None] * colsum[None, :]
+        Yt[b] = (a.astype(dtype) * np.asarray(scales[b], dtype=dtype)[:, None]) * sw[None, :]
         Y[b] = sequence_inverse(Yt[b], xform, levels, grid_h, grid_w, dtype)
     if bias is not None:
         Y = Y + np.asarray(bias, dtype=dtype)[None, None, :]
@@ -449,11 +513,12 @@ def linear_from_codes(codes: np.ndarray, scales: np.ndarray, qw: np.ndarray, sw:
 def stamp_linear_forward(X: np.ndarray, W: np.ndarray, xform: str, levels: int, k_hi: int,
                          bits_hi: int = 8, bits_lo: int = 4, bits_w: int = 4, grid_h: int = 0,
                          grid_w: int = 0, bias: Optional[np.ndarray] = None,
-                         dtype=np.float32) -> Dict[str, np.ndarray]:
+                         dtype=np.float32, act_quant: str = "sym") -> Dict[str, np.ndarray]:
     """Algorithm "STaMP Linear" end to end for X[batch, s, d_in], W[d_in, d_out]."""
-    qa = quantize_activation(X, xform, levels, k_hi, bits_hi, bits_lo, grid_h, grid_w, dtype)
+    qa = quantize_activation(X, xform, levels, k_hi, bits_hi, bits_lo, grid_h, grid_w, dtype, act_quant)
     qw, sw = quantize_weight(W, bits_w, dtype)
-    out = linear_from_codes(qa["codes"], qa["scales"], qw, sw, xform, levels, grid_h, grid_w, bias, dtype)
+    out = linear_from_codes(qa["codes"], qa["scales"], qw, sw, xform, levels, grid_h, grid_w, bias, dtype,
+                            zeros=qa.get("zeros"))
     out.update(qa)
     out.update({"qw": qw, "sw": sw})
     return out
