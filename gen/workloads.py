@@ -54,6 +54,8 @@ class Workload:
     first_token_scale: float = 1.0
     w_std: float = 0.02
     seed: int = 0
+    act_quant: str = "sym"   # "sym" (absmax, signed codes) or "asym" (min-max, unsigned codes + offsets)
+    mean_shift: float = 0.0   # constant added to every activation (skews the per-token ranges)
 
     @property
     def tokens(self) -> int:
@@ -125,6 +127,8 @@ def make_activation(w: Workload) -> np.ndarray:
         x[:, :, ch] *= np.float32(w.outlier_scale)
     if w.first_token_scale != 1.0:
         x[:, 0, :] *= np.float32(w.first_token_scale)
+    if w.mean_shift != 0.0:
+        x += np.float32(w.mean_shift)
     return x
 
 

@@ -39,7 +39,9 @@
  *   The quantized activation is stored in the plan's PHYSICAL row order (a permutation of STaMP
  *   order chosen so that one GEMM tile holds whole Haar sub-trees); stamp_plan_row_of_coeff
  *   returns it.  With R = seq_len / k_hi and physical row r of sequence b:
- *     scales  [batch, seq_len] float: scale of the coefficient at physical row r.
+ *     scales  [batch, seq_len] float: scale of the coefficient at physical row r.  Plans with
+ *             act_quant = STAMP_ACT_ASYMMETRIC use a buffer of [2][batch, seq_len] floats: the
+ *             scales, then the integer offsets z (as floats) in the same order.
  *     q_hi    [batch, k_hi, d_in] int8: the 8-bit tokens; STaMP slot p < k_hi is row p of q_hi
  *             (its physical row is p*R).
  *     q_lo    the 4-bit tokens at their physical row, two channels per byte (two's complement
@@ -75,6 +77,17 @@ typedef enum {
 
 typedef enum { STAMP_F32 = 0, STAMP_BF16 = 1 } stamp_dtype_t;
 typedef enum { STAMP_L_IDENTITY = 0, STAMP_L_HAAR1D = 1, STAMP_L_HAAR2D = 2 } stamp_xform_t;
+/* Activation quantizer (Background, Eq. 1), per transformed token i with b bits:
+ *   STAMP_ACT_SYMMETRIC   a = max_j |t_ij|, scale = a / (2^(b-1) - 1), code = rne(t * (1 / scale)) in
+ *                         [-(2^(b-1) - 1), 2^(b-1) - 1]; de-quantized value code * scale.
+ *   STAMP_ACT_ASYMMETRIC  Eq. 1 in full (the "asymmetric quantization with minmax scaling" of the
+ *                         Experiments set-up): lo = min(min_j t_ij, 0), hi = max(max_j t_ij, 0),
+ *                         scale = (hi - lo) / (2^b - 1), integer offset z = rne(-lo / scale),
+ *                         code = clamp(rne(t / scale) + z, 0, 2^b - 1); de-quantized value
+ *                         (code - z) * scale.  The library STORES code - 2^(b-1) (two's complement
+ *                         int8 / nibble) and returns z next to the scales.
+ * Either way scale and its reciprocal are two fp32 divisions and rne is round-half-to-even. */
+typedef enum { STAMP_ACT_SYMMETRIC = 0, STAMP_ACT_ASYMMETRIC = 1 } stamp_act_quant_t;
 
 /* Everything the paper's statement of the layer leaves to the user: the shape of X (Background),
  * the transform L and its depth (section "Efficient Energy Concentration"), the number k of
@@ -89,6 +102,7 @@ typedef struct {
   int32_t bits_hi, bits_lo, bits_w; /* 8, 4, 4 */
   int32_t x_dtype, y_dtype, w_dtype; /* stamp_dtype_t; w_dtype must be STAMP_F32 */
   int32_t w_is_out_by_in;   /* 0: W[d_in, d_out];  1: W[d_out, d_in] (the algorithm's X W^T) */
+  int32_t act_quant;        /* stamp_act_quant_t: which form of Eq. 1 quantizes the activation */
 } stamp_plan_desc_t;
 
 /* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):

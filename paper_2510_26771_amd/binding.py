@@ -34,7 +34,7 @@ class StampError(RuntimeError):
 class _Desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "seq_len", "d_in", "d_out", "xform", "levels", "grid_h", "grid_w", "k_hi", "bits_hi", "bits_lo",
-        "bits_w", "x_dtype", "y_dtype", "w_dtype", "w_is_out_by_in")]
+        "bits_w", "x_dtype", "y_dtype", "w_dtype", "w_is_out_by_in", "act_quant")]
 
 
 @dataclass
@@ -55,6 +55,7 @@ class PlanDesc:
     y_dtype: int = STAMP_BF16
     w_dtype: int = STAMP_F32
     w_is_out_by_in: int = 0
+    act_quant: int = 0  # 0 symmetric absmax, 1 asymmetric min-max
 
     def to_c(self) -> _Desc:
         return _Desc(**{n: int(getattr(self, n)) for n, _ in _Desc._fields_})
@@ -223,5 +224,7 @@ class StampPlan:
         mp = -(-(d.batch * d.seq_len) // 256) * 256
         kp = -(-d.d_in // 128) * 128
         q_lo = torch.zeros(mp * kp // 2, dtype=torch.uint8, device=device)  # tiled, see include/stamp.h
-        scales = torch.zeros((d.batch, d.seq_len), dtype=torch.float32, device=device)
+        # asymmetric plans: [2][batch, seq_len] = scales, then the integer offsets
+        shape = (2, d.batch, d.seq_len) if d.act_quant else (d.batch, d.seq_len)
+        scales = torch.zeros(shape, dtype=torch.float32, device=device)
         return q_hi, q_lo, scales

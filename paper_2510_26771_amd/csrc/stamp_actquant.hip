@@ -1,12 +1,16 @@
 // Activation path of the STaMP linear layer on gfx950: T = L X along the tokens (Haar DWT, paper
-// section "Efficient Energy Concentration"), per-token absmax scale and rounding to 8- or 4-bit
-// codes (Background Eq. 1 in its symmetric form; two-level allocation of section "Optimal bit
-// allocation").  X is read from HBM once and the transformed activation never goes to HBM.
+// section "Efficient Energy Concentration"), per-token scale and rounding to 8- or 4-bit codes
+// (Background Eq. 1, in its symmetric absmax form or in full with min-max range and integer offset;
+// two-level allocation of section "Optimal bit allocation").  X is read from HBM once and the
+// transformed activation never goes to HBM.
 //
 // Floating-point contract (decides the integer codes, so it is fixed): every coefficient is the
 // difference (or sum) of two block sums built by plain pairwise fp32 adds, multiplied once by
 // norm(l) = fl(2^(-l/2)); absmax a over the row; scale = a / qmax; inv = qmax / a (IEEE
-// divisions); code = rne(fl(T * inv)).  This file is compiled with -ffp-contract=off.
+// divisions); code = rne(fl(T * inv)).  Asymmetric form: hi = max(max T, 0), nlo = max(max -T, 0),
+// range = hi + nlo, scale = range / qmax, inv = qmax / range with qmax = 2^b - 1, z = rne(fl(nlo *
+// inv)), code = clamp(rne(fl(T * inv)) + z, 0, qmax), stored as code - 2^(b-1).  This file is
+// compiled with -ffp-contract=off.
 //
 // Kernels:
 //   k_bottom1d / k_bottom2d  one workgroup per (sequence, block of R tokens), all d_in channels;
@@ -73,6 +77,28 @@ __device__ __forceinline__ uint32_t pack8_int4(const float (&p)[8]) {
   return (acc - kPackBias) ^ 0x88888888u;
 }
 
+// Asymmetric form: p already clamped to [-z, 15 - z]; the nibble to store is that of q - 8 with
+// q = rne(p) + z.  The addend must be EVEN, or a tie p = n + 1/2 would be broken by the parity of the sum
+// instead of that of n: magic = 1.5 * 2^23 + 16 + (z - z % 2) puts rne(p) + z - z % 2 + 16 (15..31) into
+// the low bits; the 16s and the constant pattern bits leave with the bias, z % 2 is added to all eight
+// nibbles at once (no nibble exceeds 31 - 16 = 15), and the final XOR turns q into q - 8.
+__device__ __forceinline__ uint32_t pack8_uint4(const float (&p)[8], float z) {
+  const float zodd = z - 2.0f * floorf(0.5f * z);
+  const float magic = __fadd_rn(12582928.0f, z - zodd);  // 1.5 * 2^23 + 16 + even part of z
+  uint32_t acc = __float_as_uint(__fadd_rn(p[7], magic));
+#pragma unroll
+  for (int c = 6; c >= 0; --c) acc = (acc << 4) + __float_as_uint(__fadd_rn(p[c], magic));
+  return ((acc - (kPackBias + 0x11111110u)) + (zodd != 0.0f ? 0x11111111u : 0u)) ^ 0x88888888u;
+}
+
+// max over the 8 values of max(v, 0) and of max(-v, 0), as bit patterns of non-negative floats
+__device__ __forceinline__ void row_posneg_bits(const float (&v)[8], uint32_t& pos, uint32_t& neg) {
+  float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+  float mn = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7])));
+  pos = __float_as_uint(fmaxf(mx, 0.0f));
+  neg = __float_as_uint(fmaxf(-mn, 0.0f));
+}
+
 __device__ __forceinline__ void load8(const void* X, size_t elem_off, bool bf16, bool active, float (&v)[8]) {
   if (!active) {
 #pragma unroll
@@ -98,17 +124,29 @@ constexpr int cmin(int a, int b) { return a < b ? a : b; }
 // stored.  `step` numbers the steps of this workgroup (rotating LDS buffers).
 struct RowMeta { int level; int e; };
 constexpr int kMaxRows = 18;  // most rows finished by one streaming step (2-D: 12 + 3 + 3)
+constexpr int kPartWords = 2 * kMaxRows * 16;  // per-wave partial maxima of one step: [2 signs][row][wave]
 
-template <int NR, bool IS2D, typename MetaFn>
-__device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[kMaxRows * 16],
+// ASYM: the asymmetric form of the quantizer; zeros_off = distance (in floats) from a row's scale to its offset z.
+template <int NR, bool IS2D, bool ASYM, typename MetaFn>
+__device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[kPartWords],
                                            uint8_t* q_lo_thr /* this thread's 4 bytes of row e=0 of the block */,
-                                           float* scales_blk, bool active, int tid) {
+                                           float* scales_blk, size_t zeros_off, bool active, int tid) {
   const int lane = tid & 63, wave = tid >> 6;
-  uint32_t* part = &s_max[0][0] + (step & 1) * (kMaxRows * 16);  // [row][wave] partial maxima, double buffered
+  // [row][wave] partial maxima, double buffered; asymmetric: a second array for the negative parts
+  uint32_t* part = &s_max[0][0] + (step & 1) * kPartWords;
+  uint32_t* part_neg = part + kMaxRows * 16;
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
-    const uint32_t m = wave_max_u32(row_absmax_bits(rowv[r]));
-    if (lane == 0) part[r * 16 + wave] = m;
+    if constexpr (ASYM) {
+      uint32_t pos, neg;
+      row_posneg_bits(rowv[r], pos, neg);
+      pos = wave_max_u32(pos);
+      neg = wave_max_u32(neg);
+      if (lane == 0) { part[r * 16 + wave] = pos; part_neg[r * 16 + wave] = neg; }
+    } else {
+      const uint32_t m = wave_max_u32(row_absmax_bits(rowv[r]));
+      if (lane == 0) part[r * 16 + wave] = m;
+    }
   }
   // Workgroup barrier that waits for this wave's LDS traffic only: __syncthreads() would also wait for
   // the global -> LDS loads of the next batch, which are meant to stay in flight across it.
@@ -117,27 +155,43 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   // lane r prepares row r: a = fl(absmaxU * norm); scale = a / 7; inv = 7 / a
+  // (asymmetric: hi = fl(posU * norm), nlo = fl(negU * norm), range = hi + nlo, scale = range / 15,
+  //  inv = 15 / range, z = rne(fl(nlo * inv)))
   float mul_lane = 0.0f;
+  [[maybe_unused]] float z_lane = 0.0f;
   {
     const int r = lane < NR ? lane : 0;
     const RowMeta rm = meta(r);
     const int nw = (int)(blockDim.x >> 6);
-    uint32_t mbits = 0u;
+    auto reduce_waves = [&](const uint32_t* arr) {
+      uint32_t mbits = 0u;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const uint4 v = *reinterpret_cast<const uint4*>(part + r * 16 + 4 * q);
-      if (4 * q + 0 < nw) mbits = max(mbits, v.x);
-      if (4 * q + 1 < nw) mbits = max(mbits, v.y);
-      if (4 * q + 2 < nw) mbits = max(mbits, v.z);
-      if (4 * q + 3 < nw) mbits = max(mbits, v.w);
-    }
-    const float amaxU = __uint_as_float(mbits);
+      for (int q = 0; q < 4; ++q) {
+        const uint4 v = *reinterpret_cast<const uint4*>(arr + r * 16 + 4 * q);
+        if (4 * q + 0 < nw) mbits = max(mbits, v.x);
+        if (4 * q + 1 < nw) mbits = max(mbits, v.y);
+        if (4 * q + 2 < nw) mbits = max(mbits, v.z);
+        if (4 * q + 3 < nw) mbits = max(mbits, v.w);
+      }
+      return __uint_as_float(mbits);
+    };
     const float nrm = IS2D ? ldexpf(1.0f, -rm.level) : haar_norm(rm.level);
-    const float a = __fmul_rn(amaxU, nrm);
     float scale = 0.0f, inv = 0.0f;
-    if (a > 0.0f) {
-      scale = __fdiv_rn(a, 7.0f);
-      inv = __fdiv_rn(7.0f, a);
+    if constexpr (ASYM) {
+      const float hi = __fmul_rn(reduce_waves(part), nrm), nlo = __fmul_rn(reduce_waves(part_neg), nrm);
+      const float range = __fadd_rn(hi, nlo);
+      if (range > 0.0f) {
+        scale = __fdiv_rn(range, 15.0f);
+        inv = __fdiv_rn(15.0f, range);
+      }
+      z_lane = rintf(__fmul_rn(nlo, inv));
+      if (tid < NR) scales_blk[zeros_off + rm.e] = z_lane;
+    } else {
+      const float a = __fmul_rn(reduce_waves(part), nrm);
+      if (a > 0.0f) {
+        scale = __fdiv_rn(a, 7.0f);
+        inv = __fdiv_rn(7.0f, a);
+      }
     }
     // even 1-D levels and all 2-D levels have a power-of-two norm: fold it into the multiplier
     const bool fold = IS2D || ((rm.level & 1) == 0);
@@ -158,7 +212,16 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
 #pragma unroll
       for (int c = 0; c < 8; ++c) p[c] = __fmul_rn(__fmul_rn(rowv[r][c], nrm), mul);
     }
-    const uint32_t w = pack8_int4(p);
+    uint32_t w;
+    if constexpr (ASYM) {
+      const float z = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, z_lane), r));
+      const float lo = -z, hi = 15.0f - z;  // clamp before rounding = clamp after it (integer bounds)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) p[c] = __builtin_amdgcn_fmed3f(p[c], lo, hi);
+      w = pack8_uint4(p, z);
+    } else {
+      w = pack8_int4(p);
+    }
     if (active) *reinterpret_cast<uint32_t*>(q_lo_thr + rm.e * 64) = w;  // tiled layout: 64 bytes per row and K step
   }
 }
@@ -219,10 +282,10 @@ __device__ __forceinline__ void chain1d(float (&cur)[8], float (&pend)[NP][8], f
   }
 }
 
-template <int RLOG, bool BF16, int IT, int NP>
+template <int RLOG, bool BF16, bool ASYM, int IT, int NP>
 __device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, uint8_t* stage, int nthreads, bool active,
-                                       int tid, float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[kMaxRows * 16],
-                                       uint8_t* q_lo_blk, float* scales_blk) {
+                                       int tid, float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[kPartWords],
+                                       uint8_t* q_lo_blk, float* scales_blk, size_t zeros_off) {
   constexpr int R = 1 << RLOG;
   constexpr int NIT = R / 4;
   constexpr int CH = cmin(trailing_ones(IT), RLOG - 2);
@@ -283,25 +346,27 @@ __device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, u
   }
   chain1d<RLOG, 2, IT, 3, NP, NR>(cur, pend, rowv, top);
   auto meta = [](int r) -> RowMeta { return meta1d<RLOG, IT>(r); };
-  flush_rows<NR, false>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, active, tid);
+  flush_rows<NR, false, ASYM>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, zeros_off, active, tid);
 }
 
-template <int RLOG, bool BF16, int NP, int... ITS>
+template <int RLOG, bool BF16, bool ASYM, int NP, int... ITS>
 __device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const uint8_t* X_thr, size_t row_bytes,
                                       uint8_t* stage, int nthreads, bool active, int tid, float (&pend)[NP][8],
-                                      float (&top)[8], uint32_t (*s_max)[kMaxRows * 16], uint8_t* q_lo_blk, float* scales_blk) {
-  (step1d<RLOG, BF16, ITS, NP>(X_thr, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
+                                      float (&top)[8], uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, float* scales_blk,
+                                      size_t zeros_off) {
+  (step1d<RLOG, BF16, ASYM, ITS, NP>(X_thr, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk, scales_blk,
+                                     zeros_off), ...);
 }
 
-template <int RLOG, bool BF16>
+template <int RLOG, bool BF16, bool ASYM>
 __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
                                                    float* __restrict__ scales, float* __restrict__ abot, int s, int d,
-                                                   int k, int Kpad) {
+                                                   int k, int Kpad, size_t zeros_off) {
   constexpr int R = 1 << RLOG;
   constexpr int NP = RLOG > 2 ? RLOG - 2 : 1;
   constexpr int CPR = BF16 ? 1 : 2;
   extern __shared__ __attribute__((aligned(16))) uint8_t stage[];  // 2 halves x 4 rows x nthreads x (16 | 32) bytes
-  __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kMaxRows * 16];
+  __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kPartWords];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int nthreads = blockDim.x;
   const int c0 = tid * 8;
@@ -316,8 +381,8 @@ __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, u
   if (R > 4) request_batch<BF16>(X_thr + 4 * row_bytes, row_bytes, stage + 4 * CPR * nthreads * 16, nthreads, tid >> 6);
   float pend[NP][8];
   float top[8];
-  run1d<RLOG, BF16, NP>(std::make_integer_sequence<int, R / 4>{}, X_thr, row_bytes, stage, nthreads, active, tid, pend,
-                        top, s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0);
+  run1d<RLOG, BF16, ASYM, NP>(std::make_integer_sequence<int, R / 4>{}, X_thr, row_bytes, stage, nthreads, active, tid,
+                              pend, top, s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0, zeros_off);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -343,10 +408,10 @@ __device__ __forceinline__ void cell2d(const float (&p)[8], const float (&q)[8],
   }
 }
 
-template <int RLOG, bool BF16, int SB>
+template <int RLOG, bool BF16, bool ASYM, int SB>
 __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int gridW, int d, int c0, bool active, int tid,
-                                       float (&pend)[4][8], float (&top)[8], uint32_t (*s_max)[kMaxRows * 16],
-                                       uint8_t* q_lo_blk, float* scales_blk) {
+                                       float (&pend)[4][8], float (&top)[8], uint32_t (*s_max)[kPartWords],
+                                       uint8_t* q_lo_blk, float* scales_blk, size_t zeros_off) {
   constexpr int g = 1 << RLOG;
   constexpr int sby = (g == 4) ? 0 : (SB >> 1), sbx = (g == 4) ? 0 : (SB & 1);
   constexpr bool LAST = (g == 8) && (SB == 3);
@@ -392,24 +457,24 @@ __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int g
     }
     return m;
   };
-  flush_rows<NR, true>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, active, tid);
+  flush_rows<NR, true, ASYM>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, zeros_off, active, tid);
 }
 
-template <int RLOG, bool BF16, int... SBS>
+template <int RLOG, bool BF16, bool ASYM, int... SBS>
 __device__ __forceinline__ void run2d(std::integer_sequence<int, SBS...>, const void* X, size_t blk_elem_off, int gridW,
                                       int d, int c0, bool active, int tid, float (&pend)[4][8], float (&top)[8],
-                                      uint32_t (*s_max)[kMaxRows * 16], uint8_t* q_lo_blk, float* scales_blk) {
-  (step2d<RLOG, BF16, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, scales_blk), ...);
+                                      uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, float* scales_blk, size_t zeros_off) {
+  (step2d<RLOG, BF16, ASYM, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, scales_blk,
+                                 zeros_off), ...);
 }
 
-template <int RLOG, bool BF16>
+template <int RLOG, bool BF16, bool ASYM>
 __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
-                                                  float* __restrict__ scales, float* __restrict__ abot,
-                                                  uint32_t* __restrict__ rowmax, int s, int d, int G, int gridW,
-                                                  int Kpad) {
+                                                  float* __restrict__ scales, float* __restrict__ abot, int s, int d, int G,
+                                                  int gridW, int Kpad, size_t zeros_off) {
   constexpr int g = 1 << RLOG;
   constexpr int R = g * g;
-  __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kMaxRows * 16];
+  __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kPartWords];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int bi = j / G, bj = j - bi * G;
   const int c0 = tid * 8;
@@ -419,8 +484,8 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
   const size_t prow0 = (size_t)b * s + (size_t)j * R;                              // first physical row of the block
   float pend[4][8];
   float top[8];
-  run2d<RLOG, BF16>(std::make_integer_sequence<int, (g == 4 ? 1 : 4)>{}, X, tok0 * d + c0, gridW, d, c0, active, tid,
-                    pend, top, s_max, q_lo + stamp_qlo_offset(prow0, c0, Kpad), scales + prow0);
+  run2d<RLOG, BF16, ASYM>(std::make_integer_sequence<int, (g == 4 ? 1 : 4)>{}, X, tok0 * d + c0, gridW, d, c0, active, tid,
+                          pend, top, s_max, q_lo + stamp_qlo_offset(prow0, c0, Kpad), scales + prow0, zeros_off);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -435,8 +500,9 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
 // ------------------------------------------------------------------------------------------
 constexpr int kTopCh = 32;
 
+// asym: the partial maxima are of max(t, 0); those of max(-t, 0) follow npart words further on.
 __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t* __restrict__ rowmax_part, int k, int d,
-                                             int is2d, int G, int r_bottom) {
+                                             int is2d, int G, int r_bottom, int asym, size_t npart) {
   extern __shared__ float s_buf[];  // [k][kTopCh + 1]
   const int b = blockIdx.y, c_base = blockIdx.x * kTopCh, tid = threadIdx.x;
   const int ch = tid & (kTopCh - 1), grp = tid / kTopCh, ngrp = 256 / kTopCh;
@@ -493,36 +559,67 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
     const float t = __fmul_rn(s_buf[q * stride + ch], nrm);
     if (cact) base[(size_t)e * d + c_base + ch] = t;
     // max over the 32 channels of this row: lanes of one row are 32 consecutive lanes
-    int x = (int)absbits(t), yv;
-    yv = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false); x = max(x, yv);
-    yv = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false); x = max(x, yv);
-    yv = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); x = max(x, yv);
-    yv = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); x = max(x, yv);
-    yv = __shfl_xor(x, 16, 64); x = max(x, yv);
-    if (ch == 0) rowmax_part[((size_t)b * k + e) * gridDim.x + blockIdx.x] = (uint32_t)x;
+    auto max32 = [](int x) {
+      int yv;
+      yv = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false); x = max(x, yv);
+      yv = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false); x = max(x, yv);
+      yv = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); x = max(x, yv);
+      yv = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); x = max(x, yv);
+      yv = __shfl_xor(x, 16, 64); x = max(x, yv);
+      return x;
+    };
+    const size_t slot = ((size_t)b * k + e) * gridDim.x + blockIdx.x;
+    if (!asym) {
+      const int x = max32((int)absbits(t));
+      if (ch == 0) rowmax_part[slot] = (uint32_t)x;
+    } else {
+      const int xp = max32((int)__float_as_uint(fmaxf(t, 0.0f)));
+      const int xn = max32((int)__float_as_uint(fmaxf(-t, 0.0f)));
+      if (ch == 0) { rowmax_part[slot] = (uint32_t)xp; rowmax_part[npart + slot] = (uint32_t)xn; }
+    }
   }
 }
 
-// one workgroup per 8-bit row
+// one workgroup per 8-bit row.  asym: min-max form, the stored code is code - 128 and the offset z goes
+// zeros_off floats behind the row's scale.
 __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop, const uint32_t* __restrict__ rowmax_part,
                                                   int nslices, int8_t* __restrict__ q_hi, float* __restrict__ scales,
-                                                  int k, int d, int s, int R) {
-  __shared__ uint32_t s_red[4];
+                                                  int k, int d, int s, int R, int asym, size_t npart, size_t zeros_off) {
+  __shared__ uint32_t s_red[8];
   const int p = blockIdx.x, b = blockIdx.y;
   {
-    uint32_t m = 0u;
-    for (int i = threadIdx.x; i < nslices; i += 256) m = max(m, rowmax_part[((size_t)b * k + p) * nslices + i]);
+    uint32_t m = 0u, mneg = 0u;
+    for (int i = threadIdx.x; i < nslices; i += 256) {
+      const size_t slot = ((size_t)b * k + p) * nslices + i;
+      m = max(m, rowmax_part[slot]);
+      if (asym) mneg = max(mneg, rowmax_part[npart + slot]);
+    }
     m = wave_max_u32(m);
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = m;
+    mneg = wave_max_u32(mneg);
+    if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = m; s_red[4 + (threadIdx.x >> 6)] = mneg; }
     __syncthreads();
   }
   const float a = __uint_as_float(max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3])));
-  float scale = 0.0f, inv = 0.0f;
-  if (a > 0.0f) {
-    scale = __fdiv_rn(a, 127.0f);
-    inv = __fdiv_rn(127.0f, a);
+  const float nlo = __uint_as_float(max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7])));
+  float scale = 0.0f, inv = 0.0f, z = 0.0f;
+  if (!asym) {
+    if (a > 0.0f) {
+      scale = __fdiv_rn(a, 127.0f);
+      inv = __fdiv_rn(127.0f, a);
+    }
+  } else {
+    const float range = __fadd_rn(a, nlo);
+    if (range > 0.0f) {
+      scale = __fdiv_rn(range, 255.0f);
+      inv = __fdiv_rn(255.0f, range);
+    }
+    z = rintf(__fmul_rn(nlo, inv));
   }
-  if (threadIdx.x == 0) scales[(size_t)b * s + (size_t)p * R] = scale;
+  if (threadIdx.x == 0) {
+    scales[(size_t)b * s + (size_t)p * R] = scale;
+    if (asym) scales[zeros_off + (size_t)b * s + (size_t)p * R] = z;
+  }
+  const float qlo = asym ? 0.0f : -127.0f, qhi = asym ? 255.0f : 127.0f, shift = asym ? 128.0f : 0.0f;
   const float* src = ttop + ((size_t)b * k + p) * d;
   int8_t* dst = q_hi + ((size_t)b * k + p) * d;
   for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
@@ -531,15 +628,15 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
     uint32_t w = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      float q = rintf(__fmul_rn(v[i], inv));
-      q = fminf(fmaxf(q, -127.0f), 127.0f);
+      float q = __fadd_rn(rintf(__fmul_rn(v[i], inv)), z);
+      q = fminf(fmaxf(q, qlo), qhi) - shift;
       w |= ((uint32_t)((int)q) & 0xFFu) << (8 * i);
     }
     *reinterpret_cast<uint32_t*>(dst + c) = w;
   }
 }
 
-template <int RLOG, bool BF16>
+template <int RLOG, bool BF16, bool ASYM>
 hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, float* scales, float* abot, int nthreads,
                            hipStream_t st) {
   const StampGeom& g = p->geom;
@@ -547,13 +644,13 @@ hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, fl
   if (lds > 160 * 1024 - 1024) return hipErrorInvalidValue;
   static size_t attr_lds = 0;
   if (lds > attr_lds) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bottom1d<RLOG, BF16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bottom1d<RLOG, BF16, ASYM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_lds = lds;
   }
-  hipLaunchKernelGGL((k_bottom1d<RLOG, BF16>), dim3(g.k, g.B), dim3(nthreads), lds, st, X, q_lo, scales, abot, g.s, g.d,
-                     g.k, p->Kpad);
+  hipLaunchKernelGGL((k_bottom1d<RLOG, BF16, ASYM>), dim3(g.k, g.B), dim3(nthreads), lds, st, X, q_lo, scales, abot, g.s,
+                     g.d, g.k, p->Kpad, (size_t)g.B * g.s);
   return hipGetLastError();
 }
 
@@ -564,18 +661,22 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
   const StampGeom& g = p->geom;
   const int nthreads = ((g.d / 8 + 63) / 64) * 64;
   dim3 grid(g.k, g.B);
+  const size_t zeros_off = (size_t)g.B * g.s;
 #define LAUNCH1D(RL)                                                                                      \
   do {                                                                                                    \
-    hipError_t le = g.x_bf16 ? launch_bottom1d<RL, true>(p, X, q_lo, scales, abot, nthreads, st)          \
-                             : launch_bottom1d<RL, false>(p, X, q_lo, scales, abot, nthreads, st);        \
+    hipError_t le = g.asym ? (g.x_bf16 ? launch_bottom1d<RL, true, true>(p, X, q_lo, scales, abot, nthreads, st)     \
+                                       : launch_bottom1d<RL, false, true>(p, X, q_lo, scales, abot, nthreads, st))   \
+                           : (g.x_bf16 ? launch_bottom1d<RL, true, false>(p, X, q_lo, scales, abot, nthreads, st)    \
+                                       : launch_bottom1d<RL, false, false>(p, X, q_lo, scales, abot, nthreads, st)); \
     if (le != hipSuccess) return le;                                                                      \
   } while (0)
+#define LAUNCH2D_(RL, BF, AS)                                                                             \
+  hipLaunchKernelGGL((k_bottom2d<RL, BF, AS>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, g.s, g.d, g.G, g.gridW, \
+                     p->Kpad, zeros_off)
 #define LAUNCH2D(RL)                                                                                      \
   do {                                                                                                    \
-    if (g.x_bf16)                                                                                         \
-      hipLaunchKernelGGL((k_bottom2d<RL, true>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW, p->Kpad); \
-    else                                                                                                  \
-      hipLaunchKernelGGL((k_bottom2d<RL, false>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, rowmax, g.s, g.d, g.G, g.gridW, p->Kpad); \
+    if (g.asym) { if (g.x_bf16) LAUNCH2D_(RL, true, true); else LAUNCH2D_(RL, false, true); }             \
+    else { if (g.x_bf16) LAUNCH2D_(RL, true, false); else LAUNCH2D_(RL, false, false); }                  \
   } while (0)
   if (!(part & 1)) {
     // bottom kernel skipped
@@ -598,15 +699,18 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
   }
 #undef LAUNCH1D
 #undef LAUNCH2D
+#undef LAUNCH2D_
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (!(part & 2)) return hipSuccess;
   const size_t lds = (size_t)g.k * (kTopCh + 1) * sizeof(float);
-  hipLaunchKernelGGL(k_top, dim3((g.d + kTopCh - 1) / kTopCh, g.B), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d,
-                     g.G, g.r);
+  const int nslices = (g.d + kTopCh - 1) / kTopCh;
+  const size_t npart = (size_t)g.B * g.k * nslices;
+  hipLaunchKernelGGL(k_top, dim3(nslices, g.B), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d, g.G, g.r, g.asym,
+                     npart);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, (g.d + kTopCh - 1) / kTopCh, q_hi,
-                     scales, g.k, g.d, g.s, g.R);
+  hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, nslices, q_hi, scales, g.k, g.d, g.s, g.R,
+                     g.asym, npart, zeros_off);
   return hipGetLastError();
 }

@@ -22,6 +22,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   for (int32_t t : {d->x_dtype, d->y_dtype, d->w_dtype})
     if (t != STAMP_F32 && t != STAMP_BF16) return STAMP_ERR_SHAPE;
   if (d->w_is_out_by_in != 0 && d->w_is_out_by_in != 1) return STAMP_ERR_SHAPE;
+  if (d->act_quant != STAMP_ACT_SYMMETRIC && d->act_quant != STAMP_ACT_ASYMMETRIC) return STAMP_ERR_SHAPE;
   if ((int64_t)d->batch * d->seq_len > (int64_t)1 << 30) return STAMP_ERR_SHAPE;
 
   int J = 0, side = 0;
@@ -51,6 +52,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   g->J = J; g->k = d->k_hi; g->R = R;
   g->x_bf16 = d->x_dtype == STAMP_BF16;
   g->y_bf16 = d->y_dtype == STAMP_BF16;
+  g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
   if (d->xform == STAMP_L_HAAR1D) {
     g->is2d = 0;
     g->r = ilog2(R);
@@ -78,10 +80,10 @@ void layout_workspace(stamp_plan* p) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   p->ws_abot = take((size_t)g.B * g.k * g.d * sizeof(float));
-  p->ws_rowmax = take((size_t)g.B * g.k * ((g.d + 31) / 32) * sizeof(uint32_t));  // partial row maxima per 32-channel slice
+  p->ws_rowmax = take((size_t)2 * g.B * g.k * ((g.d + 31) / 32) * sizeof(uint32_t));  // partial row maxima (asymmetric: of both signs) per 32-channel slice
   p->ws_qhi = take((size_t)g.B * g.k * g.d);
   p->ws_qlo = take((size_t)p->Mpad * (p->Kpad / 2));
-  p->ws_scales = take((size_t)g.B * g.s * sizeof(float));
+  p->ws_scales = take((size_t)2 * g.B * g.s * sizeof(float));  // scales, then offsets (asymmetric plans)
   p->ws_ythi = take((size_t)g.B * g.k * g.N * sizeof(float));
   p->ws_P = take((size_t)g.B * g.k * p->Npad * sizeof(float));
   p->ws_a6 = take(stamp_a6_bytes(p));
@@ -174,6 +176,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   bool ok = hipMalloc(reinterpret_cast<void**>(&p->qW_dev), (size_t)p->Npad * p->Kpad) == hipSuccess &&
             hipMalloc(reinterpret_cast<void**>(&p->qW6_dev), stamp_b6_bytes(p)) == hipSuccess &&
             hipMalloc(reinterpret_cast<void**>(&p->sw_dev), sizeof(float) * p->Npad) == hipSuccess &&
+            hipMalloc(reinterpret_cast<void**>(&p->colsum_dev), sizeof(float) * p->Npad) == hipSuccess &&
             hipMalloc(reinterpret_cast<void**>(&colmax), sizeof(uint32_t) * g.N) == hipSuccess;
   if (ok && bias_dev != nullptr) ok = hipMalloc(reinterpret_cast<void**>(&p->bias_dev), sizeof(float) * p->Npad) == hipSuccess;
   if (!ok) {
@@ -204,6 +207,7 @@ stamp_status_t stamp_plan_destroy(stamp_plan_t* p) {
   if (p->qW_dev) (void)hipFree(p->qW_dev);
   if (p->qW6_dev) (void)hipFree(p->qW6_dev);
   if (p->sw_dev) (void)hipFree(p->sw_dev);
+  if (p->colsum_dev) (void)hipFree(p->colsum_dev);
   if (p->bias_dev) (void)hipFree(p->bias_dev);
   free(p->row_of_coeff);
   delete p;

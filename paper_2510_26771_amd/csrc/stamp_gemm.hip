@@ -225,7 +225,7 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
   constexpr int BN = 64 * WN;
   constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
   constexpr size_t epi_lds = (EPI == 2) ? (size_t)(2 * WN * kWaveTileBytes) : 0;
-  constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + 2048;  // + per-row factors and destinations
+  constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + kRowInfoBytes;  // + per-row factors, destinations, offsets
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>),
@@ -267,6 +267,7 @@ stamp_gemm::GemmArgs stamp_gemm_args(const stamp_plan* p, const float* scales, v
   a.Bq = reinterpret_cast<const uint8_t*>(p->qW_dev);
   a.scales = scales;
   a.sw = p->sw_dev;
+  a.colsum = p->colsum_dev;
   a.bias = p->bias_dev;
   a.P = nullptr;
   a.out = out;

@@ -1,10 +1,11 @@
 // GEMM of the 4-bit rows of the STaMP linear layer on the FP6 matrix pipeline of gfx950 (step
 // "Y <- X W" of Algorithm "STaMP Linear" for the rows quantized to 4 bits against 4-bit weights).
 //
-// A 4-bit code c in [-7, 7] is held as the E2M3 number c / 8: sign bit, exponent field 0, mantissa
-// field |c| (a subnormal, so the six bits are just sign and magnitude).  v_mfma_f32_32x32x64_f8f6f4
+// A 4-bit code c in [-8, 7] is held as the E2M3 number c / 8: for |c| < 8 sign bit, exponent field 0,
+// mantissa field |c| (a subnormal); |c| = 8 is 1.0 (exponent field 1, mantissa 0): either way the six
+// bits are just sign and 4-bit magnitude.  v_mfma_f32_32x32x64_f8f6f4
 // multiplies such operands exactly and accumulates in fp32; every product is a multiple of 1/64 and a
-// whole sum stays below 2^24 / 64 in magnitude (d_in <= 8192, |c c'| <= 49), so the fp32 accumulator
+// whole sum stays below 2^24 / 64 in magnitude (d_in <= 8192, |c c'| <= 56), so the fp32 accumulator
 // holds acc / 64 EXACTLY, where acc is the integer sum the int8 pipeline computes: same result bit for
 // bit, at twice the matrix rate per clock.  The factor 64 is folded into the row scale.
 //
@@ -36,12 +37,13 @@ constexpr int kStageA6 = 2 * kStageB6;        // 24 KB
 __device__ __forceinline__ uint64_t nib8_to_e2m3(uint32_t w) {
   const uint32_t s = w & 0x88888888u;  // sign bit of every nibble
   const uint32_t sg = s >> 3;          // 1 in every negative nibble
-  // |c|: complement the negative nibbles and add 1 (no carry leaves a nibble: ~c + 1 <= 7; the code -8 never occurs)
-  const uint32_t mag = ((w ^ (sg * 15u)) + sg) & 0x77777777u;
+  // |c|: complement the negative nibbles and add 1 (no carry leaves a nibble: ~c + 1 <= 8).  |c| = 8
+  // (the stored form of the asymmetric code 0) sets the low exponent bit: the E2M3 number 1.0 = 8 / 8.
+  const uint32_t mag = (w ^ (sg * 15u)) + sg;
   uint64_t out = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const uint32_t c = ((mag >> (4 * j)) & 7u) | (((s >> (4 * j + 3)) & 1u) << 5);
+    const uint32_t c = ((mag >> (4 * j)) & 15u) | (((s >> (4 * j + 3)) & 1u) << 5);
     out |= (uint64_t)c << (6 * j);
   }
   return out;
@@ -263,7 +265,7 @@ template <int EPI, int RB, bool IS2D, bool YBF16>
 hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
   constexpr size_t main_lds = (size_t)kNumStage6 * kStage6;
   constexpr size_t epi_lds = (EPI == 2) ? (size_t)kTileBytes6 : 0;
-  constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + 2048;
+  constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + kRowInfoBytes;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm6<EPI, RB, IS2D, YBF16>),

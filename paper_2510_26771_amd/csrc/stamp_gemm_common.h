@@ -31,6 +31,7 @@ constexpr int BM = 256, BK = 128;
 constexpr int NI = 2;           // 32-column MFMA blocks per wave along N
 constexpr int kEpiStride = 68;  // floats per row of the per-wave epilogue staging tile (64 columns + 4, rows 16-byte aligned)
 constexpr int kWaveTileBytes = 64 * kEpiStride * 4;  // one wave's staging tile of the fused epilogue: 64 rows x 64 columns
+constexpr int kRowInfoBytes = 3 * 1024;  // per-row factors, destinations and offsets of one 256-row tile
 constexpr int kNumXcd = 8;
 constexpr int kGroupM = 8;
 
@@ -43,7 +44,8 @@ __device__ __forceinline__ float haar_norm_dev(int level, int is2d) {
 struct GemmArgs {
   const uint8_t* A;      // activation codes in the layout of the kernel's operand format
   const uint8_t* Bq;     // weight codes in the layout of the kernel's operand format
-  const float* scales;   // [B*s] physical order
+  const float* scales;   // [B*s] physical order; asymmetric plans: followed by the [B*s] offsets z
+  const float* colsum;   // [Npad] sums of the weight codes per output column (asymmetric plans)
   const float* sw;       // [Npad]
   const float* bias;     // [Npad] or nullptr
   const float* P;        // [B*k][Npad] block sums of the inverse (fused mode)
@@ -59,21 +61,26 @@ struct GemmArgs {
 //   int8 MFMA, 4-bit rows: both operands are held as code * 16         -> register = 256 acc
 //   int8 MFMA, 8-bit rows: the weights are held as code * 16           -> register = 16 acc
 //   FP6 MFMA, 4-bit rows:  both operands are held as code / 8 (E2M3)   -> register = acc / 64 (exact in fp32)
+// kZeroShift = 2^(b-1): asymmetric codes are stored as code - kZeroShift, so the offset that goes with
+// the stored code is z - kZeroShift.
 struct AccI8Lo {
   typedef v16i V;
   static constexpr bool kLoRows = true;
+  static constexpr float kZeroShift = 8.0f;
   static constexpr float kToAcc = 1.0f / 256.0f;
   static __device__ __forceinline__ int to_i32(int x) { return x >> 8; }
 };
 struct AccI8Hi {
   typedef v16i V;
   static constexpr bool kLoRows = false;
+  static constexpr float kZeroShift = 128.0f;
   static constexpr float kToAcc = 1.0f / 16.0f;
   static __device__ __forceinline__ int to_i32(int x) { return x >> 4; }
 };
 struct AccF6Lo {
   typedef v16f V;
   static constexpr bool kLoRows = true;
+  static constexpr float kZeroShift = 8.0f;
   static constexpr float kToAcc = 64.0f;
   static __device__ __forceinline__ int to_i32(float x) { return (int)(x * 64.0f); }
 };
@@ -201,6 +208,7 @@ template <int EPI, int RB, bool IS2D>
 struct EpiOperands {
   using ES = EpiShape<(EPI == 2 ? RB : 3), IS2D>;
   float sw[NI];
+  float cs[NI];  // column sums of the weight codes (asymmetric plans)
   f8 bias;
   f8 top[2][ES::npass];
   __device__ __forceinline__ void request(const GemmArgs& a, int m0, int n0, int lane, int wm, int wn) {
@@ -208,7 +216,10 @@ struct EpiOperands {
       const int c8 = (lane & 7) * 8, ug = lane >> 3, l32 = lane & 31;
       const int nw = n0 + wn * 64;
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) sw[ni] = a.sw[nw + ni * 32 + l32];
+      for (int ni = 0; ni < NI; ++ni) {
+        sw[ni] = a.sw[nw + ni * 32 + l32];
+        cs[ni] = a.g.asym ? a.colsum[nw + ni * 32 + l32] : 0.0f;
+      }
       const f4 zero = (f4){0.0f, 0.0f, 0.0f, 0.0f};
       const f4 b0 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8) : zero;
       const f4 b1 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8 + 4) : zero;
@@ -229,23 +240,29 @@ struct EpiOperands {
 };
 
 // Per-row dequantization factor (activation scale * Haar norm of the row's level * the operand
-// format's constant) and destination row of tile row `tid`, written to LDS at row_info (2 KB) before
-// the main loop; the main loop's barriers publish them.
+// format's constant), destination row, and (asymmetric plans) the offset of the stored code in
+// accumulator units, of tile row `tid`, written to LDS at row_info (kRowInfoBytes) before the main
+// loop; the main loop's barriers publish them.
 template <typename Acc, int EPI>
 __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int tid, uint8_t* row_info) {
   const StampGeom& g = a.g;
   float* s_rowfac = reinterpret_cast<float*>(row_info);     // [256]
   int* s_rowdst = reinterpret_cast<int*>(row_info + 1024);  // [256] destination row or -1
+  float* s_rowz = reinterpret_cast<float*>(row_info + 2048);  // [256] (z - 2^(b-1)) / kToAcc
   const int m = m0 + tid;
-  float fac = 0.0f;
+  float fac = 0.0f, rz = 0.0f;
   int dst = -1;
+  const size_t zeros_off = (size_t)g.B * g.s;
   if (m < a.M) {
     if constexpr (Acc::kLoRows) {
       const int b = m / g.s, pr = m - b * g.s;
       const int j = pr / g.R, e = pr - j * g.R;
       if (e != 0) {
         const int level = g.is2d ? stamp_level_of_e_2d(e, g.r) : stamp_level_of_e_1d(e, g.r);
-        if constexpr (EPI != 0) fac = a.scales[m] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
+        if constexpr (EPI != 0) {
+          fac = a.scales[m] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
+          if (g.asym) rz = (a.scales[zeros_off + m] - Acc::kZeroShift) * (1.0f / Acc::kToAcc);
+        }
         if (EPI == 0) {
           const int p = g.is2d ? stamp_slot_of_block_e_2d(j / g.G, j % g.G, e, g.G) : stamp_slot_of_block_e_1d(j, e, g.k);
           dst = b * g.s + p;
@@ -260,13 +277,17 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
         const int lg = 31 - __builtin_clz((unsigned)p);
         level = g.J - (g.is2d ? (lg >> 1) : lg);
       }
-      if constexpr (EPI != 0)
-        fac = a.scales[(size_t)b * g.s + (size_t)p * g.R] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
+      if constexpr (EPI != 0) {
+        const size_t row = (size_t)b * g.s + (size_t)p * g.R;
+        fac = a.scales[row] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
+        if (g.asym) rz = (a.scales[zeros_off + row] - Acc::kZeroShift) * (1.0f / Acc::kToAcc);
+      }
       dst = (EPI == 0) ? (b * g.s + p) : m;
     }
   }
   s_rowfac[tid] = fac;
   s_rowdst[tid] = dst;
+  s_rowz[tid] = rz;
 }
 
 // Epilogue of one workgroup tile; to be called after a workgroup barrier that follows the last read
@@ -283,12 +304,14 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
   const int l32 = lane & 31, kg = lane >> 5;
   const float* s_rowfac = reinterpret_cast<const float*>(row_info);
   const int* s_rowdst = reinterpret_cast<const int*>(row_info + 1024);
+  const float* s_rowz = reinterpret_cast<const float*>(row_info + 2048);
 
   if constexpr (EPI == 0 || EPI == 1) {
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int n = n0 + wn * (32 * NI) + ni * 32 + l32;
       const float swn = a.sw[n];
+      const float csn = (EPI == 1 && g.asym) ? a.colsum[n] : 0.0f;
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
@@ -299,7 +322,9 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
             if constexpr (EPI == 0) {
               reinterpret_cast<int32_t*>(a.out)[(size_t)dst * a.N + n] = Acc::to_i32(acc[mi][ni][v]);
             } else {
-              reinterpret_cast<float*>(a.out)[(size_t)dst * a.N + n] = ((float)acc[mi][ni][v] * s_rowfac[rl]) * swn;
+              // asymmetric: the integer sum over (stored code - offset), exact in one fma
+              const float af = g.asym ? __builtin_fmaf(-s_rowz[rl], csn, (float)acc[mi][ni][v]) : (float)acc[mi][ni][v];
+              reinterpret_cast<float*>(a.out)[(size_t)dst * a.N + n] = (af * s_rowfac[rl]) * swn;
             }
           }
         }
@@ -327,23 +352,47 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
       o.bias = eo.bias;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        // row factors of this lane's 32 accumulator rows of the half
-        f4 rf[2][4];
+        if (!g.asym) {
+          // row factors of this lane's 32 accumulator rows of the half
+          f4 rf[2][4];
 #pragma unroll
-        for (int mh = 0; mh < 2; ++mh)
+          for (int mh = 0; mh < 2; ++mh)
 #pragma unroll
-          for (int q = 0; q < 4; ++q)
-            rf[mh][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + (2 * hf + mh) * 32 + 8 * q + 4 * kg);
+            for (int q = 0; q < 4; ++q)
+              rf[mh][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + (2 * hf + mh) * 32 + 8 * q + 4 * kg);
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-          const float swn = eo.sw[ni];
+          for (int ni = 0; ni < NI; ++ni) {
+            const float swn = eo.sw[ni];
+#pragma unroll
+            for (int mh = 0; mh < 2; ++mh) {
+              const int mi = 2 * hf + mh;
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int rw = mh * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                s_tile[rw * kEpiStride + pos0 + 16 * ni] = ((float)acc[mi][ni][v] * rf[mh][v >> 2][v & 3]) * swn;
+              }
+            }
+          }
+        } else {
+          // asymmetric codes: the integer sum over (stored code - offset) = acc - rowz * colsum, exact in
+          // one fma; four rows at a time, so that only their factors and offsets are live
 #pragma unroll
           for (int mh = 0; mh < 2; ++mh) {
             const int mi = 2 * hf + mh;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int rw = mh * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-              s_tile[rw * kEpiStride + pos0 + 16 * ni] = ((float)acc[mi][ni][v] * rf[mh][v >> 2][v & 3]) * swn;
+            for (int q = 0; q < 4; ++q) {
+              const int r0 = wm * 128 + mi * 32 + 8 * q + 4 * kg;
+              const f4 rf4 = *reinterpret_cast<const f4*>(s_rowfac + r0);
+              const f4 rz4 = *reinterpret_cast<const f4*>(s_rowz + r0);
+#pragma unroll
+              for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                for (int vv = 0; vv < 4; ++vv) {
+                  const int rw = mh * 32 + 8 * q + 4 * kg + vv;
+                  const float af = __builtin_fmaf(-rz4[vv], eo.cs[ni], (float)acc[mi][ni][4 * q + vv]);
+                  s_tile[rw * kEpiStride + pos0 + 16 * ni] = (af * rf4[vv]) * eo.sw[ni];
+                }
+              }
             }
           }
         }

@@ -27,6 +27,7 @@ struct StampGeom {
   int32_t gridW;     // 2-D: tokens per grid row
   int32_t x_bf16;    // input dtype is bf16
   int32_t y_bf16;    // output dtype is bf16
+  int32_t asym;      // asymmetric activation codes: stored code - 2^(b-1), offsets z next to the scales
 };
 
 // Position inside a block ("e", 0 = the block sum, e >= 1 the in-block detail rows in STaMP
@@ -97,6 +98,7 @@ struct stamp_plan {
   int8_t* qW_dev;           // tiled int8 weight codes * 16 (see stamp_w_offset), K order permuted per 16 channels
   float* sw_dev;            // [Npad] weight scales (0 beyond d_out)
   float* bias_dev;          // [Npad] bias or nullptr
+  float* colsum_dev;        // [Npad] sum over input channels of the weight codes (exact integers as fp32)
   int32_t* row_of_coeff;    // host, [s]
   uint8_t* qW6_dev;         // the same weight codes as E2M3 numbers in the plane layout of the FP6 GEMM
   int32_t engine;           // matrix pipeline of the 4-bit rows' GEMM: STAMP_GEMM_INT8 or STAMP_GEMM_FP6
@@ -109,6 +111,7 @@ struct stamp_plan {
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
 hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStream_t st, uint32_t* colmax_tmp);
 // part: 1 = bottom kernel only, 2 = top + 8-bit rows only, 3 = both
+// scales: [B*s] scales, followed by [B*s] offsets z for asymmetric plans
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo,
                                  float* scales, float* abot, uint32_t* rowmax, hipStream_t st, int part = 3);
 // mode: 0 = int32 accumulators in STaMP row order (debug), 1 = dequantized fp32 rows (hi -> Yt_hi

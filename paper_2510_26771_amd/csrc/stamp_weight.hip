@@ -59,6 +59,27 @@ __global__ void k_w_quant(const float* __restrict__ W, const uint32_t* __restric
   *reinterpret_cast<uint4*>(qW + stamp_w_offset(n, g16 * 16, Kpad)) = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
+// Sum over the input channels of the weight codes of every output column, an exact integer held in fp32
+// (|sum| <= 7 d_in): what the integer offset z of an asymmetric activation code multiplies, since
+// sum_c (code_mc - z_m) qW_cn = sum_c code_mc qW_cn - z_m sum_c qW_cn (de-quantization function of the
+// Background section).  Codes are recomputed from W exactly as k_w_quant does.
+__global__ void k_w_colsum(const float* __restrict__ W, const uint32_t* __restrict__ colmax, float* __restrict__ colsum,
+                           int d, int N, int Npad, size_t sc, size_t sn) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= Npad) return;
+  int sum = 0;
+  if (n < N) {
+    const float a = __uint_as_float(colmax[n]);
+    const float inv = a > 0.0f ? __fdiv_rn(7.0f, a) : 0.0f;
+    for (int c = 0; c < d; ++c) {
+      float r = rintf(__fmul_rn(W[(size_t)c * sc + (size_t)n * sn], inv));
+      r = fminf(fmaxf(r, -7.0f), 7.0f);
+      sum += (int)r;
+    }
+  }
+  colsum[n] = (float)sum;
+}
+
 }  // namespace
 
 hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStream_t st, uint32_t* colmax_tmp) {
@@ -71,5 +92,7 @@ hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStr
                      colmax_tmp, d, N, sc, sn, rows_per_block);
   hipLaunchKernelGGL(k_w_quant, dim3((p->Npad + 255) / 256, p->Kpad / 16), dim3(256), 0, st, W, colmax_tmp, p->qW_dev,
                      p->sw_dev, d, N, p->Kpad, p->Npad, sc, sn);
+  hipLaunchKernelGGL(k_w_colsum, dim3((p->Npad + 255) / 256), dim3(256), 0, st, W, colmax_tmp, p->colsum_dev, d, N, p->Npad,
+                     sc, sn);
   return hipGetLastError();
 }

@@ -62,6 +62,34 @@ def test_small_cases(w):
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
+# The asymmetric (min-max, Eq. 1 in full) form of the quantizer, on shifted activations so that the token
+# ranges are skewed and one-sided tokens occur: 1-D with several block sizes (fused and unfused inverse,
+# ragged shapes), fp32 input, both 2-D block sizes.
+ASYM = [
+    _wl("asym_r32_ragged", batch=3, seq_len=512, levels=9, k_hi=16, d_in=160, d_out=300, seed=41, act_quant="asym",
+        mean_shift=0.75),
+    _wl("asym_r8", batch=3, seq_len=64, levels=6, k_hi=8, d_in=96, d_out=64, seed=42, act_quant="asym", mean_shift=-2.0),
+    _wl("asym_r64_f32in", batch=2, seq_len=512, levels=9, k_hi=8, d_in=1024, d_out=512, x_dtype="f32", seed=43,
+        act_quant="asym", mean_shift=0.3, first_token_scale=50.0),
+    _wl("asym_r128", batch=1, seq_len=1024, levels=10, k_hi=8, d_in=128, d_out=256, seed=44, act_quant="asym"),
+    _wl("asym_g16_blk4", batch=2, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=16, d_in=96,
+        d_out=130, corr_len=4.0, seed=45, act_quant="asym", mean_shift=1.0),
+    _wl("asym_g32_blk8", batch=1, seq_len=1024, xform="haar2d", levels=5, grid_h=32, grid_w=32, k_hi=16, d_in=288,
+        d_out=512, corr_len=8.0, seed=46, act_quant="asym", mean_shift=-0.5),
+]
+
+
+@pytest.mark.parametrize("w", ASYM, ids=[w.name for w in ASYM])
+def test_asymmetric_quantizer_cases(w):
+    r = tl.full_case(w, with_bias=True)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+def test_asymmetric_bf16_output():
+    tl.full_case(_wl("asym_bf16_out", batch=2, seq_len=256, levels=8, k_hi=8, d_in=256, d_out=384, seed=47,
+                     act_quant="asym", mean_shift=0.5), with_bias=True, y_dtype="bf16")
+
+
 def test_bf16_output_and_bias():
     tl.full_case(_wl("bf16_out", batch=2, seq_len=256, levels=8, k_hi=8, d_in=256, d_out=384, seed=31),
                  with_bias=True, y_dtype="bf16")
@@ -86,7 +114,7 @@ def test_degenerate_inputs():
         Xd = torch.from_numpy(X).cuda()
         q_hi, q_lo, scales = plan.alloc_act_buffers()
         plan.quantize_act(Xd, q_hi, q_lo, scales, ws)
-        codes, sc = tl.gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales)
+        codes, sc, _ = tl.gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales)
         assert np.array_equal(sc.view(np.uint32), ora["scales"].view(np.uint32))
         assert np.array_equal(codes, ora["codes"])
         if fill == 0.0:
