@@ -70,11 +70,12 @@ def cpu_baseline(w, inp, ncols, nseq):
     nseq = min(nseq, w.batch)
     X = inp["X_f32"][:nseq]
     t0 = time.perf_counter()
-    qa = so.quantize_activation(X, w.xform, w.levels, w.k_hi, w.bits_hi, w.bits_lo, w.grid_h, w.grid_w)
+    qa = so.quantize_activation(X, w.xform, w.levels, w.k_hi, w.bits_hi, w.bits_lo, w.grid_h, w.grid_w,
+                                act_quant=w.act_quant)
     t1 = time.perf_counter()
     qw, sw = so.quantize_weight(inp["W"][:, :ncols], w.bits_w)   # plan-time work, not counted
     t2 = time.perf_counter()
-    so.linear_from_codes(qa["codes"], qa["scales"], qw, sw, w.xform, w.levels, w.grid_h, w.grid_w)
+    so.linear_from_codes(qa["codes"], qa["scales"], qw, sw, w.xform, w.levels, w.grid_h, w.grid_w, zeros=qa.get("zeros"))
     t3 = time.perf_counter()
     t_total = (t1 - t0) + (t3 - t2) * (w.d_out / ncols)
     return {
@@ -99,6 +100,9 @@ def main():
     ap.add_argument("--unfused", action="store_true")
     ap.add_argument("--engine", choices=["int8", "fp6"], default="fp6",
                     help="matrix pipeline of the 4-bit rows' GEMM (the library's default is fp6)")
+    ap.add_argument("--act-quant", choices=["sym", "asym"], default="sym",
+                    help="activation quantizer: symmetric absmax (the benchmark configurations) or the paper's "
+                         "asymmetric min-max form")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (int32 add), the "
                          "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -116,7 +120,7 @@ def main():
 
     st.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = get_workload(args.workload)
+    w = get_workload(args.workload, act_quant=args.act_quant)
     log(f"generating {w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out}")
     inp = make_inputs(w)
     Xd = tl.to_device_x(inp, w)
@@ -216,7 +220,8 @@ def main():
         "dtype": "fp6" if args.engine == "fp6" else "int8", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out} "
                                f"{w.xform} J={w.levels} k_hi={w.k_hi} W4A4(+{w.k_hi} int8 tokens), bf16 in/out",
-                   "path": "unfused" if args.unfused else "fused", "gemm_engine": args.engine},
+                   "path": "unfused" if args.unfused else "fused", "gemm_engine": args.engine,
+                   "act_quant": args.act_quant},
         "roofline": roofline, f"roofline_{other}_engine": roofline_other, "roofline_quant": roofline_quant,
         "stages_ms": stages,
     }

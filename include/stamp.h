@@ -108,7 +108,8 @@ typedef struct {
 /* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):
  *   xform HAAR1D with seq_len/k_hi in {8,16,32,64,128}, or HAAR2D with a square grid and
  *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels = full depth; bits 8/4/4;
- *   d_in a multiple of 32 and at most 8192 (4096 for fp32 input or 2-D grids); k_hi <= 256. */
+ *   d_in a multiple of 32 and at most 8192 (4096 for fp32 input or 2-D grids); k_hi <= 256;
+ *   act_quant symmetric or asymmetric. */
 
 /* Validates desc, quantizes W per output channel (absmax/7, round to nearest even; section
  * "Large Language Models", Set-up: round-to-nearest weights, one scale per output channel) into
@@ -154,7 +155,8 @@ stamp_status_t stamp_inverse(const stamp_plan_t* plan, const float* Yt_dev, int3
 /* ---- parity / debug exports (not on the timed path) ---- */
 
 /* Step 3 alone: acc_dev[b*seq_len + p, n] = sum_c code[b, p, c] * qW[c, n], int32, rows in STaMP
- * order. */
+ * order; `code` is the STORED code (asymmetric plans: the unsigned code minus 2^(b-1)).  With the FP6
+ * engine selected the converted operand lives in a temporary that this call allocates and frees. */
 stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* plan, const int8_t* q_hi_dev,
                                     const uint8_t* q_lo_dev, int32_t* acc_dev, void* hip_stream);
 

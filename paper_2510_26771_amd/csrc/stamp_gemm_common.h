@@ -375,23 +375,27 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
           }
         } else {
           // asymmetric codes: the integer sum over (stored code - offset) = acc - rowz * colsum, exact in
-          // one fma; four rows at a time, so that only their factors and offsets are live
+          // one fma; four rows at a time, their factors and offsets read one group ahead of the staging
+          // writes (LDS operations execute in order, and a read placed after a write would wait for it)
+          const int rbase = wm * 128 + 2 * hf * 32 + 4 * kg;
+          f4 rf_n = *reinterpret_cast<const f4*>(s_rowfac + rbase);
+          f4 rz_n = *reinterpret_cast<const f4*>(s_rowz + rbase);
 #pragma unroll
-          for (int mh = 0; mh < 2; ++mh) {
-            const int mi = 2 * hf + mh;
+          for (int gq = 0; gq < 8; ++gq) {
+            const int mh = gq >> 2, q = gq & 3, mi = 2 * hf + mh;
+            const f4 rf4 = rf_n, rz4 = rz_n;
+            if (gq + 1 < 8) {
+              const int r1 = rbase + ((gq + 1) >> 2) * 32 + 8 * ((gq + 1) & 3);
+              rf_n = *reinterpret_cast<const f4*>(s_rowfac + r1);
+              rz_n = *reinterpret_cast<const f4*>(s_rowz + r1);
+            }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int r0 = wm * 128 + mi * 32 + 8 * q + 4 * kg;
-              const f4 rf4 = *reinterpret_cast<const f4*>(s_rowfac + r0);
-              const f4 rz4 = *reinterpret_cast<const f4*>(s_rowz + r0);
+            for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-              for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-                for (int vv = 0; vv < 4; ++vv) {
-                  const int rw = mh * 32 + 8 * q + 4 * kg + vv;
-                  const float af = __builtin_fmaf(-rz4[vv], eo.cs[ni], (float)acc[mi][ni][4 * q + vv]);
-                  s_tile[rw * kEpiStride + pos0 + 16 * ni] = (af * rf4[vv]) * eo.sw[ni];
-                }
+              for (int vv = 0; vv < 4; ++vv) {
+                const int rw = mh * 32 + 8 * q + 4 * kg + vv;
+                const float af = __builtin_fmaf(-rz4[vv], eo.cs[ni], (float)acc[mi][ni][4 * q + vv]);
+                s_tile[rw * kEpiStride + pos0 + 16 * ni] = (af * rf4[vv]) * eo.sw[ni];
               }
             }
           }

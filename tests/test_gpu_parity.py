@@ -213,6 +213,15 @@ def test_full_size_llm_and_dit(name):
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_full_size_asymmetric_quantizer(name):
+    """The paper's own quantizer (asymmetric min-max) on the LLM and image-token shapes at full size."""
+    w = get_workload(name, act_quant="asym")
+    r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 11), check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
 @pytest.mark.timeout(900)
 def test_full_size_cfg3():
     w = get_workload("cfg3")
