@@ -31,9 +31,11 @@
  *   W        [d_in, d_out] row-major (w_is_out_by_in = 0) or [d_out, d_in] (= 1), dtype w_dtype.
  *   Y        [batch, seq_len, d_out] row-major, dtype y_dtype, original token order.
  *   Transformed tokens ("coefficients") are numbered in STaMP order: lowest frequencies first.
- *     1-D, J levels: slot 0 = sum/sqrt(s); slot p >= 1 with m = floor(log2 p) is the Haar wavelet
- *     of level J-m at position p-2^m (+ on its first half, - on its second half).
- *     2-D, J levels over a grid_h x grid_w grid, token t = r*grid_w + c: the final low-low block
+ *     1-D, J levels over s tokens: slots 0 .. s/2^J - 1 are the level-J approximations (sums of 2^J
+ *     consecutive tokens / 2^(J/2)); slot p >= s/2^J with m = floor(log2 p) is the Haar wavelet of
+ *     level log2(s) - m at position p - 2^m (+ on its first half, - on its second half).  With
+ *     J = log2(s): slot 0 = sum/sqrt(s).
+ *     2-D, J levels over a grid_h x grid_w grid, token t = r*grid_w + c: the level-J low-low block
  *     row-major, then for level J..1 the bands [difference along width, difference along height,
  *     diagonal], each row-major.
  *   The quantized activation is stored in the plan's PHYSICAL row order (a permutation of STaMP
@@ -96,7 +98,7 @@ typedef enum { STAMP_ACT_SYMMETRIC = 0, STAMP_ACT_ASYMMETRIC = 1 } stamp_act_qua
 typedef struct {
   int32_t batch, seq_len, d_in, d_out;
   int32_t xform;            /* stamp_xform_t */
-  int32_t levels;           /* Haar levels J; must equal log2(seq_len) (2-D: log2(grid side)) */
+  int32_t levels;           /* Haar levels J, 1 <= J <= log2(seq_len) (2-D: log2 of the grid side) */
   int32_t grid_h, grid_w;   /* HAAR2D only; grid_h == grid_w, grid_h*grid_w == seq_len */
   int32_t k_hi;             /* tokens kept at bits_hi; a power of two (2-D: a power of four) */
   int32_t bits_hi, bits_lo, bits_w; /* 8, 4, 4 */
@@ -107,7 +109,9 @@ typedef struct {
 
 /* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):
  *   xform HAAR1D with seq_len/k_hi in {8,16,32,64,128}, or HAAR2D with a square grid and
- *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels = full depth; bits 8/4/4;
+ *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels J >= log2(seq_len/k_hi) (2-D: log4), i.e.
+ *   k_hi >= the number of level-J approximations, so that every 4-bit token is a wavelet coefficient
+ *   (full depth, or e.g. the 3-level transform of a 64x64 grid with k_hi = 64); bits 8/4/4;
  *   d_in a multiple of 32 and at most 8192 (4096 for fp32 input or 2-D grids); k_hi <= 256;
  *   act_quant symmetric or asymmetric. */
 

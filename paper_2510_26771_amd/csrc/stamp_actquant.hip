@@ -501,8 +501,9 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
 constexpr int kTopCh = 32;
 
 // asym: the partial maxima are of max(t, 0); those of max(-t, 0) follow npart words further on.
+// L = number of top levels (0: the block sums are only normalised).
 __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t* __restrict__ rowmax_part, int k, int d,
-                                             int is2d, int G, int r_bottom, int asym, size_t npart) {
+                                             int is2d, int G, int r_bottom, int L, int asym, size_t npart) {
   extern __shared__ float s_buf[];  // [k][kTopCh + 1]
   const int b = blockIdx.y, c_base = blockIdx.x * kTopCh, tid = threadIdx.x;
   const int ch = tid & (kTopCh - 1), grp = tid / kTopCh, ngrp = 256 / kTopCh;
@@ -512,7 +513,7 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
   for (int j = grp; j < k; j += ngrp) s_buf[j * stride + ch] = cact ? base[(size_t)j * d + c_base + ch] : 0.0f;
   __syncthreads();
   if (!is2d) {
-    for (int st = 2; st <= k; st <<= 1) {
+    for (int st = 2; st <= (1 << L); st <<= 1) {
       const int npair = k / st;
       for (int i = grp; i < npair; i += ngrp) {
         float* pa = &s_buf[(i * st) * stride + ch];
@@ -524,7 +525,7 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
       __syncthreads();
     }
   } else {
-    for (int st = 2; st <= G; st <<= 1) {
+    for (int st = 2; st <= (1 << L); st <<= 1) {
       const int nc = G / st;
       const int h = st >> 1;
       for (int i = grp; i < nc * nc; i += ngrp) {
@@ -547,12 +548,10 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
   for (int q = grp; q < k; q += ngrp) {
     int e, lvl_top;  // level counted within the top part (1 = first top level); slot 0 gets the deepest
     if (!is2d) {
-      e = stamp_e_of_natural_1d(q, k);
-      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)k)) : (__builtin_ctz((unsigned)q) + 1);
+      e = stamp_top_slot_1d(q, k, L, &lvl_top);
     } else {
       const int y = q / G, x = q - y * G;
-      e = stamp_e_of_natural_2d(y, x, G);
-      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)G)) : (__builtin_ctz((unsigned)(y | x)) + 1);
+      e = stamp_top_slot_2d(y, x, G, L, &lvl_top);
     }
     const int level = r_bottom + lvl_top;
     const float nrm = is2d ? ldexpf(1.0f, -level) : haar_norm(level);
@@ -706,7 +705,7 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
   const size_t lds = (size_t)g.k * (kTopCh + 1) * sizeof(float);
   const int nslices = (g.d + kTopCh - 1) / kTopCh;
   const size_t npart = (size_t)g.B * g.k * nslices;
-  hipLaunchKernelGGL(k_top, dim3(nslices, g.B), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d, g.G, g.r, g.asym,
+  hipLaunchKernelGGL(k_top, dim3(nslices, g.B), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d, g.G, g.r, g.L, g.asym,
                      npart);
   e = hipGetLastError();
   if (e != hipSuccess) return e;

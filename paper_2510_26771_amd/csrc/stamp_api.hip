@@ -43,13 +43,12 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
   if (d->w_dtype != STAMP_F32) return STAMP_ERR_UNSUPPORTED;
   if (d->d_in % 32 != 0 || d->d_in > 8192) return STAMP_ERR_UNSUPPORTED;
-  if (d->levels != J) return STAMP_ERR_UNSUPPORTED;
   if (d->k_hi < 1 || d->k_hi > 256 || !is_pow2(d->k_hi)) return STAMP_ERR_UNSUPPORTED;
   const int R = d->seq_len / d->k_hi;
 
   memset(g, 0, sizeof(*g));
   g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
-  g->J = J; g->k = d->k_hi; g->R = R;
+  g->J = d->levels; g->k = d->k_hi; g->R = R;
   g->x_bf16 = d->x_dtype == STAMP_BF16;
   g->y_bf16 = d->y_dtype == STAMP_BF16;
   g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
@@ -57,6 +56,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     g->is2d = 0;
     g->r = ilog2(R);
     if (g->r < 3 || g->r > 7) return STAMP_ERR_UNSUPPORTED;
+    if (d->levels < g->r) return STAMP_ERR_UNSUPPORTED;  // fewer levels than a block holds: 4-bit approximation rows
     if (d->x_dtype == STAMP_F32 && d->d_in > 4096) return STAMP_ERR_UNSUPPORTED;  // LDS staging of fp32 rows
     *fused_ok = g->r <= 6;
   } else {
@@ -69,9 +69,11 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     g->r = ilog2(g->g);
     g->gridW = d->grid_w;
     if (g->r < 2 || g->r > 3) return STAMP_ERR_UNSUPPORTED;
+    if (d->levels < g->r) return STAMP_ERR_UNSUPPORTED;
     if (d->d_in > 4096) return STAMP_ERR_UNSUPPORTED;
     *fused_ok = 1;
   }
+  g->L = g->J - g->r;
   return STAMP_OK;
 }
 

@@ -272,11 +272,7 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
       }
     } else {
       const int b = m / g.k, p = m - b * g.k;
-      int level = g.J;
-      if (p > 0) {
-        const int lg = 31 - __builtin_clz((unsigned)p);
-        level = g.J - (g.is2d ? (lg >> 1) : lg);
-      }
+      const int level = stamp_level_of_top_slot(p, g.k, g.G, g.is2d, g.r, g.L);
       if constexpr (EPI != 0) {
         const size_t row = (size_t)b * g.s + (size_t)p * g.R;
         fac = a.scales[row] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;

@@ -18,7 +18,8 @@
 struct StampGeom {
   int32_t B, s, d, N;
   int32_t is2d;      // 0: 1-D stream, 1: 2-D grid
-  int32_t J;         // total levels
+  int32_t J;         // total levels of the transform (plan argument)
+  int32_t L;         // top levels J - r: levels applied to the k block sums (0 = the block sums themselves)
   int32_t r;         // bottom levels (inside a block)
   int32_t R;         // tokens per block: 2^r (1-D) or 4^r (2-D)
   int32_t k;         // number of blocks per sequence = k_hi
@@ -50,6 +51,31 @@ STAMP_HD int stamp_e_of_natural_2d(int y, int x, int g) {
   int band = by ? (bx ? 2 : 1) : 0;          // W, H, D
   int gl = g >> (t + 1);                     // side of each band of that level
   return gl * gl * (1 + band) + (y >> (t + 1)) * gl + (x >> (t + 1));
+}
+
+// Top part, L levels over n block sums (1-D) / G x G block sums (2-D): STaMP slot (< n, < G*G) of the
+// coefficient that L in-place butterfly levels leave at natural position q / (y, x), and its level counted
+// within the top part (L for the remaining approximations, which come first in STaMP order).
+STAMP_HD int stamp_top_slot_1d(int q, int n, int L, int* lvl_top) {
+  const int t = (q == 0) ? 32 : __builtin_ctz((unsigned)q);
+  if (t >= L) { *lvl_top = L; return q >> L; }
+  *lvl_top = t + 1;
+  return (n >> (t + 1)) + (q >> (t + 1));
+}
+STAMP_HD int stamp_top_slot_2d(int y, int x, int G, int L, int* lvl_top) {
+  const int t = ((y | x) == 0) ? 32 : __builtin_ctz((unsigned)(y | x));
+  if (t >= L) { *lvl_top = L; return (y >> L) * (G >> L) + (x >> L); }
+  *lvl_top = t + 1;
+  return stamp_e_of_natural_2d(y, x, G);
+}
+// Level (counted over the whole transform) of the 8-bit STaMP slot p.
+STAMP_HD int stamp_level_of_top_slot(int p, int k, int G, int is2d, int r, int L) {
+  if (!is2d) {
+    if (p < (k >> L)) return r + L;
+    return r + (31 - __builtin_clz((unsigned)k)) - (31 - __builtin_clz((unsigned)p));
+  }
+  if (p < (G >> L) * (G >> L)) return r + L;
+  return r + (31 - __builtin_clz((unsigned)G)) - ((31 - __builtin_clz((unsigned)p)) >> 1);
 }
 
 // STaMP slot p (whole sequence) of in-block position e >= 1 of block j.

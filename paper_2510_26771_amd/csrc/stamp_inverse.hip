@@ -27,10 +27,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
-// in-place inverse butterflies over n1 (1-D) or side x side (2-D) entries of s_buf[.][kStride]
-__device__ __forceinline__ void inverse_inplace(float* s_buf, int n, int side, int is2d, int ch, int grp, int ngrp) {
+// in-place inverse butterflies, `levels` levels (strides 2^levels .. 2), over n (1-D) or side x side (2-D)
+// entries of s_buf[.][kStride]
+__device__ __forceinline__ void inverse_inplace(float* s_buf, int n, int side, int is2d, int levels, int ch, int grp,
+                                                int ngrp) {
   if (!is2d) {
-    for (int st = n; st >= 2; st >>= 1) {
+    for (int st = 1 << levels; st >= 2; st >>= 1) {
       const int npair = n / st;
       for (int i = grp; i < npair; i += ngrp) {
         float* pa = &s_buf[(i * st) * kStride + ch];
@@ -42,7 +44,7 @@ __device__ __forceinline__ void inverse_inplace(float* s_buf, int n, int side, i
       __syncthreads();
     }
   } else {
-    for (int st = side; st >= 2; st >>= 1) {
+    for (int st = 1 << levels; st >= 2; st >>= 1) {
       const int nc = side / st, h = st >> 1;
       for (int i = grp; i < nc * nc; i += ngrp) {
         const int cy = i / nc, cx = i - cy * nc;
@@ -74,19 +76,17 @@ __global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ s
   for (int q = grp; q < k; q += ngrp) {
     int e, lvl_top;
     if (!g.is2d) {
-      e = stamp_e_of_natural_1d(q, k);
-      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)k)) : (__builtin_ctz((unsigned)q) + 1);
+      e = stamp_top_slot_1d(q, k, g.L, &lvl_top);
     } else {
       const int y = q / g.G, x = q - y * g.G;
-      e = stamp_e_of_natural_2d(y, x, g.G);
-      lvl_top = (q == 0) ? (31 - __builtin_clz((unsigned)g.G)) : (__builtin_ctz((unsigned)(y | x)) + 1);
+      e = stamp_top_slot_2d(y, x, g.G, g.L, &lvl_top);
     }
     float v = nact ? src[((size_t)b * src_seq_rows + e) * ncols + n] : 0.0f;
     if (apply_norm) v *= haar_norm_dev(g.r + lvl_top, g.is2d);
     s_buf[q * kStride + ch] = v;
   }
   __syncthreads();
-  inverse_inplace(s_buf, k, g.G, g.is2d, ch, grp, ngrp);
+  inverse_inplace(s_buf, k, g.G, g.is2d, g.L, ch, grp, ngrp);
   for (int q = grp; q < k; q += ngrp)
     if (nact) P[((size_t)b * k + q) * ldP + n] = s_buf[q * kStride + ch];
 }
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void k_inverse_bottom(const float* __restrict_
     s_buf[q * kStride + ch] = v;
   }
   __syncthreads();
-  inverse_inplace(s_buf, R, g.g, g.is2d, ch, grp, ngrp);
+  inverse_inplace(s_buf, R, g.g, g.is2d, g.r, ch, grp, ngrp);
   const float bias_n = (bias != nullptr && nact) ? bias[n] : 0.0f;
   for (int q = grp; q < R; q += ngrp) {
     size_t tok;

@@ -90,6 +90,29 @@ def test_asymmetric_bf16_output():
                      act_quant="asym", mean_shift=0.5), with_bias=True, y_dtype="bf16")
 
 
+# Partial depth: J levels with log2(block size) <= J < full depth; the 8-bit tokens are then the level-J
+# approximations followed by the details of the levels above the blocks (J = 3 on a 64 x 64 grid with 64
+# 8-bit tokens is the paper's own image-model setting: the 8-bit tokens are the whole low-low band).
+PARTIAL = [
+    _wl("part_r8_L0", batch=2, seq_len=512, levels=3, k_hi=64, d_in=128, d_out=192, seed=51),
+    _wl("part_r32_L2", batch=2, seq_len=512, levels=7, k_hi=16, d_in=160, d_out=300, seed=52),
+    _wl("part_r64_L1_asym", batch=1, seq_len=1024, levels=7, k_hi=16, d_in=256, d_out=256, seed=53, act_quant="asym",
+        mean_shift=0.4),
+    _wl("part_g16_blk4_L0", batch=2, seq_len=256, xform="haar2d", levels=2, grid_h=16, grid_w=16, k_hi=16, d_in=96,
+        d_out=130, corr_len=4.0, seed=54),
+    _wl("part_g32_blk4_L2", batch=1, seq_len=1024, xform="haar2d", levels=4, grid_h=32, grid_w=32, k_hi=64, d_in=96,
+        d_out=128, corr_len=6.0, seed=55),
+    _wl("part_g32_blk8_L1", batch=1, seq_len=1024, xform="haar2d", levels=4, grid_h=32, grid_w=32, k_hi=16, d_in=288,
+        d_out=512, corr_len=8.0, seed=56),
+]
+
+
+@pytest.mark.parametrize("w", PARTIAL, ids=[w.name for w in PARTIAL])
+def test_partial_depth_cases(w):
+    r = tl.full_case(w, with_bias=True)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
 def test_bf16_output_and_bias():
     tl.full_case(_wl("bf16_out", batch=2, seq_len=256, levels=8, k_hi=8, d_in=256, d_out=384, seed=31),
                  with_bias=True, y_dtype="bf16")
@@ -146,13 +169,18 @@ def test_w_out_by_in_layout():
     p2.destroy()
 
 
-@pytest.mark.parametrize("case", ["1d", "2d"])
+@pytest.mark.parametrize("case", ["1d", "2d", "1d_partial", "2d_partial"])
 def test_stamp_inverse_entry_point(case):
     """stamp_inverse alone on random STaMP-ordered input against the oracle's inverse."""
     import torch
     import paper_2510_26771_amd as st
     if case == "1d":
         w = _wl("inv1d", batch=2, seq_len=512, levels=9, k_hi=16, d_in=64, d_out=96)
+    elif case == "1d_partial":
+        w = _wl("inv1d_partial", batch=2, seq_len=512, levels=6, k_hi=16, d_in=64, d_out=96)
+    elif case == "2d_partial":
+        w = _wl("inv2d_partial", batch=2, seq_len=1024, xform="haar2d", levels=3, grid_h=32, grid_w=32, k_hi=16,
+                d_in=64, d_out=96)
     else:
         w = _wl("inv2d", batch=2, seq_len=1024, xform="haar2d", levels=5, grid_h=32, grid_w=32, k_hi=16, d_in=64,
                 d_out=96)
@@ -219,6 +247,15 @@ def test_full_size_asymmetric_quantizer(name):
     """The paper's own quantizer (asymmetric min-max) on the LLM and image-token shapes at full size."""
     w = get_workload(name, act_quant="asym")
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 11), check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+@pytest.mark.timeout(600)
+def test_full_size_image_tokens_three_levels():
+    """cfg4's 64 x 64 grid with the 3-level transform of the paper's image-model experiments: the 64 8-bit
+    tokens are exactly the low-low band, 8 x 8 token blocks hold all three levels."""
+    w = get_workload("cfg4", levels=3)
+    r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 12), check_unfused=False)
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
