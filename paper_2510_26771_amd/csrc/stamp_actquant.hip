@@ -28,6 +28,8 @@
 
 namespace {
 
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
 constexpr float kInvSqrt2 = 0.70710678118654752440f;  // 0x3F3504F3
 constexpr float kMagicLo = 12582920.0f;               // 1.5 * 2^23 + 8: fp32 add rounds to integer (RNE), low 4 bits = code + 8
 constexpr uint32_t kMagicLoBits = 0x4B400000u;        // bit pattern of 1.5 * 2^23
@@ -129,8 +131,13 @@ constexpr int kPartWords = 2 * kMaxRows * 16;  // per-wave partial maxima of one
 // ASYM: the asymmetric form of the quantizer; zeros_off = distance (in floats) from a row's scale to its offset z.
 template <int NR, bool IS2D, bool ASYM, typename MetaFn>
 __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[kPartWords],
-                                           uint8_t* q_lo_thr /* this thread's 4 bytes of row e=0 of the block */,
+                                           uint8_t* q_lo_blk /* row e=0 of the block, channel 0 (workgroup-uniform) */,
+                                           uint32_t q_off /* this thread's byte offset inside a row */,
                                            float* scales_blk, size_t zeros_off, bool active, int tid) {
+  // Values derived from the thread index are recomputed in every step from an opaque copy: cheap, and it
+  // keeps them from being carried (and spilled: a scratch reload waits for ALL outstanding memory
+  // operations, the asynchronous loads of the next batches included) across the whole unrolled kernel.
+  asm volatile("" : "+v"(tid));
   const int lane = tid & 63, wave = tid >> 6;
   // [row][wave] partial maxima, double buffered; asymmetric: a second array for the negative parts
   uint32_t* part = &s_max[0][0] + (step & 1) * kPartWords;
@@ -163,15 +170,25 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     const int r = lane < NR ? lane : 0;
     const RowMeta rm = meta(r);
     const int nw = (int)(blockDim.x >> 6);
+    // The partial maxima are read by hand-written LDS reads: the compiler cannot tell this array from the
+    // staging buffer that the asynchronous global -> LDS loads of the NEXT batches are writing, and would
+    // make every ordinary LDS read here wait for all of them (vmcnt(0)), i.e. serialise memory and compute.
     auto reduce_waves = [&](const uint32_t* arr) {
+      const uint32_t adr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint32_t*)(arr + r * 16);
+      u4 v0, v1, v2, v3;
+      asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:16\n\tds_read_b128 %2, %4 offset:32\n\t"
+                   "ds_read_b128 %3, %4 offset:48\n\ts_waitcnt lgkmcnt(0)"
+                   : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+                   : "v"(adr)
+                   : "memory");
+      const u4 vv[4] = {v0, v1, v2, v3};
       uint32_t mbits = 0u;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const uint4 v = *reinterpret_cast<const uint4*>(arr + r * 16 + 4 * q);
-        if (4 * q + 0 < nw) mbits = max(mbits, v.x);
-        if (4 * q + 1 < nw) mbits = max(mbits, v.y);
-        if (4 * q + 2 < nw) mbits = max(mbits, v.z);
-        if (4 * q + 3 < nw) mbits = max(mbits, v.w);
+        if (4 * q + 0 < nw) mbits = max(mbits, vv[q].x);
+        if (4 * q + 1 < nw) mbits = max(mbits, vv[q].y);
+        if (4 * q + 2 < nw) mbits = max(mbits, vv[q].z);
+        if (4 * q + 3 < nw) mbits = max(mbits, vv[q].w);
       }
       return __uint_as_float(mbits);
     };
@@ -222,15 +239,13 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     } else {
       w = pack8_int4(p);
     }
-    if (active) *reinterpret_cast<uint32_t*>(q_lo_thr + rm.e * 64) = w;  // tiled layout: 64 bytes per row and K step
+    if (active) *reinterpret_cast<uint32_t*>(q_lo_blk + rm.e * 64 + q_off) = w;  // tiled layout: 64 bytes per row and K step
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // 1-D bottom kernel
 // ------------------------------------------------------------------------------------------
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-
 // level and in-block position of row r finished by streaming step IT (4 tokens) of a 1-D block of
 // 2^RLOG tokens: rows 0,1 = level-1 differences, row 2 = level 2, row r >= 3 = level r (carry chain)
 template <int RLOG, int IT>
@@ -251,7 +266,8 @@ __device__ __forceinline__ RowMeta meta1d(int r) {
 // Layout of one half: chunk (t, h) of thread tid at ((t * CPR + h) * nthreads + tid) * 16, CPR =
 // 16-byte chunks per thread and row (1 for bf16, 2 for fp32).
 template <bool BF16>
-__device__ __forceinline__ void request_batch(const uint8_t* X_thr /* this thread's 8 channels of row 0 of the batch */,
+__device__ __forceinline__ void request_batch(const uint8_t* X_row /* row 0 of the batch, channel 0 (workgroup-uniform) */,
+                                              uint32_t x_off /* byte offset of this thread's 8 channels in a row */,
                                               size_t row_bytes, uint8_t* half, int nthreads, int wave) {
   constexpr int CPR = BF16 ? 1 : 2;
 #pragma unroll
@@ -259,7 +275,7 @@ __device__ __forceinline__ void request_batch(const uint8_t* X_thr /* this threa
 #pragma unroll
     for (int h = 0; h < CPR; ++h)
       __builtin_amdgcn_global_load_lds(
-          (const void __attribute__((address_space(1)))*)(X_thr + (size_t)t * row_bytes + 16 * h),
+          (const void __attribute__((address_space(1)))*)(X_row + (size_t)t * row_bytes + 16 * h + x_off),
           (void __attribute__((address_space(3)))*)(half + ((t * CPR + h) * nthreads + wave * 64) * 16), 16, 0, 0);
 }
 
@@ -283,9 +299,10 @@ __device__ __forceinline__ void chain1d(float (&cur)[8], float (&pend)[NP][8], f
 }
 
 template <int RLOG, bool BF16, bool ASYM, int IT, int NP>
-__device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, uint8_t* stage, int nthreads, bool active,
-                                       int tid, float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[kPartWords],
-                                       uint8_t* q_lo_blk, float* scales_blk, size_t zeros_off) {
+__device__ __forceinline__ void step1d(const uint8_t* X_blk, uint32_t x_off, size_t row_bytes, uint8_t* stage, int nthreads,
+                                       bool active, int tid, float (&pend)[NP][8], float (&top)[8],
+                                       uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk,
+                                       size_t zeros_off) {
   constexpr int R = 1 << RLOG;
   constexpr int NIT = R / 4;
   constexpr int CH = cmin(trailing_ones(IT), RLOG - 2);
@@ -299,15 +316,19 @@ __device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, u
   else __builtin_amdgcn_s_waitcnt(0x0F70);                                      // vmcnt(0)
   asm volatile("" ::: "memory");
   u4 raw[4][CPR];
+  {
+    int tid_l = tid;
+    asm volatile("" : "+v"(tid_l));  // see flush_rows: recomputed, not carried
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int h = 0; h < CPR; ++h)
-      raw[t][h] = *reinterpret_cast<const u4*>(half + ((t * CPR + h) * nthreads + tid) * 16);
+      for (int h = 0; h < CPR; ++h)
+        raw[t][h] = *reinterpret_cast<const u4*>(half + ((t * CPR + h) * nthreads + tid_l) * 16);
+  }
   __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the half has been read before it is requested again
   asm volatile("" ::: "memory");
   if constexpr (IT + 2 < NIT)
-    request_batch<BF16>(X_thr + (size_t)(4 * (IT + 2)) * row_bytes, row_bytes, half, nthreads, tid >> 6);
+    request_batch<BF16>(X_blk + (size_t)(4 * (IT + 2)) * row_bytes, x_off, row_bytes, half, nthreads, tid >> 6);
 
   float rowv[NR][8];
   float a1[2][8];
@@ -346,16 +367,16 @@ __device__ __forceinline__ void step1d(const uint8_t* X_thr, size_t row_bytes, u
   }
   chain1d<RLOG, 2, IT, 3, NP, NR>(cur, pend, rowv, top);
   auto meta = [](int r) -> RowMeta { return meta1d<RLOG, IT>(r); };
-  flush_rows<NR, false, ASYM>(rowv, meta, IT, s_max, q_lo_blk, scales_blk, zeros_off, active, tid);
+  flush_rows<NR, false, ASYM>(rowv, meta, IT, s_max, q_lo_blk, q_off, scales_blk, zeros_off, active, tid);
 }
 
 template <int RLOG, bool BF16, bool ASYM, int NP, int... ITS>
-__device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const uint8_t* X_thr, size_t row_bytes,
-                                      uint8_t* stage, int nthreads, bool active, int tid, float (&pend)[NP][8],
-                                      float (&top)[8], uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, float* scales_blk,
-                                      size_t zeros_off) {
-  (step1d<RLOG, BF16, ASYM, ITS, NP>(X_thr, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk, scales_blk,
-                                     zeros_off), ...);
+__device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const uint8_t* X_blk, uint32_t x_off,
+                                      size_t row_bytes, uint8_t* stage, int nthreads, bool active, int tid,
+                                      float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[kPartWords],
+                                      uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk, size_t zeros_off) {
+  (step1d<RLOG, BF16, ASYM, ITS, NP>(X_blk, x_off, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk, q_off,
+                                     scales_blk, zeros_off), ...);
 }
 
 template <int RLOG, bool BF16, bool ASYM>
@@ -375,14 +396,17 @@ __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, u
   const size_t row0 = (size_t)b * s + (size_t)j * R;
   // threads beyond d_in / 8 (the workgroup is a whole number of waves) redo the last channel group:
   // duplicates cannot change a row maximum, and they store nothing
-  const uint8_t* X_thr = reinterpret_cast<const uint8_t*>(X) + (row0 * d + min(c0, d - 8)) * esz;
+  // addresses = workgroup-uniform base + a 32-bit per-thread offset (keeps the per-thread state small)
+  const uint8_t* X_blk = reinterpret_cast<const uint8_t*>(X) + row0 * d * esz;
+  const uint32_t x_off = (uint32_t)(min(c0, d - 8) * (int)esz);
+  const uint32_t q_off = (uint32_t)(stamp_qlo_offset(0, c0, Kpad));
   const size_t row_bytes = (size_t)d * esz;
-  request_batch<BF16>(X_thr, row_bytes, stage, nthreads, tid >> 6);
-  if (R > 4) request_batch<BF16>(X_thr + 4 * row_bytes, row_bytes, stage + 4 * CPR * nthreads * 16, nthreads, tid >> 6);
+  request_batch<BF16>(X_blk, x_off, row_bytes, stage, nthreads, tid >> 6);
+  if (R > 4) request_batch<BF16>(X_blk + 4 * row_bytes, x_off, row_bytes, stage + 4 * CPR * nthreads * 16, nthreads, tid >> 6);
   float pend[NP][8];
   float top[8];
-  run1d<RLOG, BF16, ASYM, NP>(std::make_integer_sequence<int, R / 4>{}, X_thr, row_bytes, stage, nthreads, active, tid,
-                              pend, top, s_max, q_lo + stamp_qlo_offset(row0, c0, Kpad), scales + row0, zeros_off);
+  run1d<RLOG, BF16, ASYM, NP>(std::make_integer_sequence<int, R / 4>{}, X_blk, x_off, row_bytes, stage, nthreads, active,
+                              tid, pend, top, s_max, q_lo + stamp_qlo_offset(row0, 0, Kpad), q_off, scales + row0, zeros_off);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -411,7 +435,7 @@ __device__ __forceinline__ void cell2d(const float (&p)[8], const float (&q)[8],
 template <int RLOG, bool BF16, bool ASYM, int SB>
 __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int gridW, int d, int c0, bool active, int tid,
                                        float (&pend)[4][8], float (&top)[8], uint32_t (*s_max)[kPartWords],
-                                       uint8_t* q_lo_blk, float* scales_blk, size_t zeros_off) {
+                                       uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk, size_t zeros_off) {
   constexpr int g = 1 << RLOG;
   constexpr int sby = (g == 4) ? 0 : (SB >> 1), sbx = (g == 4) ? 0 : (SB & 1);
   constexpr bool LAST = (g == 8) && (SB == 3);
@@ -457,14 +481,15 @@ __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int g
     }
     return m;
   };
-  flush_rows<NR, true, ASYM>(rowv, meta, SB, s_max, q_lo_blk, scales_blk, zeros_off, active, tid);
+  flush_rows<NR, true, ASYM>(rowv, meta, SB, s_max, q_lo_blk, q_off, scales_blk, zeros_off, active, tid);
 }
 
 template <int RLOG, bool BF16, bool ASYM, int... SBS>
 __device__ __forceinline__ void run2d(std::integer_sequence<int, SBS...>, const void* X, size_t blk_elem_off, int gridW,
                                       int d, int c0, bool active, int tid, float (&pend)[4][8], float (&top)[8],
-                                      uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, float* scales_blk, size_t zeros_off) {
-  (step2d<RLOG, BF16, ASYM, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, scales_blk,
+                                      uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk,
+                                      size_t zeros_off) {
+  (step2d<RLOG, BF16, ASYM, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, q_off, scales_blk,
                                  zeros_off), ...);
 }
 
@@ -485,7 +510,8 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
   float pend[4][8];
   float top[8];
   run2d<RLOG, BF16, ASYM>(std::make_integer_sequence<int, (g == 4 ? 1 : 4)>{}, X, tok0 * d + c0, gridW, d, c0, active, tid,
-                          pend, top, s_max, q_lo + stamp_qlo_offset(prow0, c0, Kpad), scales + prow0, zeros_off);
+                          pend, top, s_max, q_lo + stamp_qlo_offset(prow0, 0, Kpad), (uint32_t)stamp_qlo_offset(0, c0, Kpad),
+                          scales + prow0, zeros_off);
   if (active) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
