@@ -9,15 +9,16 @@
 // holds acc / 64 EXACTLY, where acc is the integer sum the int8 pipeline computes: same result bit for
 // bit, at twice the matrix rate per clock.  The factor 64 is folded into the row scale.
 //
-// Operand layout ("planes"): the 32 codes that one lane feeds to one MFMA (channels 32 f .. 32 f + 31 of
-// a K step of 128 channels, f = 0..3, as a little-endian stream of 6-bit fields = 24 bytes) are split
-// into three 8-byte parts p; a plane holds part p of fragment f for 128 consecutive rows (columns).
-// Per tile and K step, activations: [2 row halves][12 planes 3 f + p][128 rows][8 bytes] = 24 KB, weights:
-// [12 planes][128 columns][8 bytes] = 12 KB.  A fragment is then three 8-byte LDS reads in which
-// consecutive lanes read consecutive addresses (no bank conflicts, no swizzle), the three parts of one
-// fragment are 1 KB apart (within reach of one two-address LDS read), and the global image equals the
-// LDS image, so a K step is staged by plain asynchronous 16-byte copies.
-// MFMA k (0, 1) of a step consumes channels [64 k, 64 k + 64): lane group kg = lane / 32 takes f = 2 k + kg.
+// Operand layout: the 32 codes that one lane feeds to one MFMA (channels 32 f .. 32 f + 31 of a K step of
+// 128 channels, f = 0..3) are a little-endian stream of 6-bit fields = 24 bytes.  MFMA round k (0, 1) of a
+// step consumes channels [64 k, 64 k + 64): lane group kg = lane / 32 takes f = 2 k + kg, so over a step a
+// lane needs fragments kg and 2 + kg of its row: 48 bytes, kept as three 16-byte parts.  Per block of 32
+// rows (columns) and K step: [3 parts][2 kg][32 rows][16 bytes] = 3 KB, so that the 64 lanes of a wave read
+// 1 KB of consecutive addresses with one 16-byte LDS read (no bank conflicts, no swizzle; 16-byte reads
+// move 1.75x the bytes per clock of 8-byte ones on this chip, and at 8 bytes the fragment reads of a step
+// take as long as its MFMAs).  Per tile and K step, activations: 8 blocks = 24 KB, weights: 4 blocks = 12 KB
+// per 128 columns.  The global image equals the LDS image, so a K step is staged by plain asynchronous
+// 16-byte copies.
 #include "stamp_gemm_common.h"
 
 namespace {
@@ -29,8 +30,9 @@ typedef uint32_t u6 __attribute__((ext_vector_type(6)));
 // the FP6 operand of the MFMA builtin is declared as 8 registers, of which the instruction reads 6
 __device__ __forceinline__ v8i widen(v6i x) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, 4, 5, -1, -1); }
 
-constexpr int kPlane = 128 * 8;               // bytes of one plane
-constexpr int kStageB6 = 12 * kPlane;         // 12 KB
+constexpr int kPart = 2 * 32 * 16;            // bytes of one part of a 32-row block: 1 KB
+constexpr int kBlock6 = 3 * kPart;            // a 32-row block of one K step: 3 KB
+constexpr int kStageB6 = 4 * kBlock6;         // 128 columns: 12 KB
 constexpr int kStageA6 = 2 * kStageB6;        // 24 KB
 
 // eight two's-complement nibbles -> eight sign-magnitude 6-bit fields (48 bits)
@@ -57,24 +59,23 @@ __device__ __forceinline__ void chunk_to_e2m3(u4 w, uint64_t (&part)[3]) {
   part[2] = (c >> 32) | (d << 16);
 }
 
-// q_lo (tiled [Mpad/256][KT][256 rows][64 bytes], channels in natural order) -> planes.
-// One workgroup per (row tile, K step); thread = row, four fragments each.
-__global__ __launch_bounds__(256) void k_repack6(const uint8_t* __restrict__ q_lo, uint8_t* __restrict__ a6) {
+// q_lo (tiled [Mpad/256][KT][256 rows][64 bytes], channels in natural order) -> FP6 operand layout.
+// One workgroup per (row tile, K step); thread = (row, kg): fragments kg and 2 + kg, three 16-byte stores.
+__global__ __launch_bounds__(512) void k_repack6(const uint8_t* __restrict__ q_lo, uint8_t* __restrict__ a6) {
   const size_t blk = blockIdx.x;
-  const int row = threadIdx.x;
-  const uint8_t* src = q_lo + blk * (256 * 64) + row * 64;
-  uint8_t* dst = a6 + blk * kStageA6 + (row >> 7) * kStageB6 + (row & 127) * 8;
-#pragma unroll
-  for (int f = 0; f < 4; ++f) {
-    const u4 w = *reinterpret_cast<const u4*>(src + (f << 4));
-    uint64_t part[3];
-    chunk_to_e2m3(w, part);
-#pragma unroll
-    for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * kPlane) = part[p];
-  }
+  const int row = threadIdx.x & 255, kg = threadIdx.x >> 8;
+  const uint8_t* src = q_lo + blk * (256 * 64) + row * 64 + kg * 16;
+  uint8_t* dst = a6 + blk * kStageA6 + (row >> 5) * kBlock6 + kg * 512 + (row & 31) * 16;
+  uint64_t lo[3], hi[3];
+  chunk_to_e2m3(*reinterpret_cast<const u4*>(src), lo);
+  chunk_to_e2m3(*reinterpret_cast<const u4*>(src + 32), hi);
+  typedef uint64_t ul2 __attribute__((ext_vector_type(2)));
+  *reinterpret_cast<ul2*>(dst) = ul2{lo[0], lo[1]};
+  *reinterpret_cast<ul2*>(dst + kPart) = ul2{lo[2], hi[0]};
+  *reinterpret_cast<ul2*>(dst + 2 * kPart) = ul2{hi[1], hi[2]};
 }
 
-// Plan-time weight codes in the plane layout: per output channel n, code = rne(W_cn * (7 / max)) as in
+// Plan-time weight codes in that layout: per output channel n, code = rne(W_cn * (7 / max)) as in
 // the integer engine (round-to-nearest weights, one scale per output channel), stored as E2M3 c / 8.
 // One thread per (column, 32-channel fragment).
 __global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, const uint32_t* __restrict__ colmax,
@@ -110,8 +111,12 @@ __global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, c
   }
   const int KT = Kpad >> 7;
   const int kt = frag >> 2, f = frag & 3;
-  uint8_t* dst = b6 + ((size_t)(n >> 7) * KT + kt) * kStageB6 + (size_t)(n & 127) * 8;
-  for (int p = 0; p < 3; ++p) *reinterpret_cast<uint64_t*>(dst + (f * 3 + p) * kPlane) = part[p];
+  // fragment f is the (f >> 1)-th half of the 48-byte stream of lane group kg = f & 1
+  uint8_t* dst = b6 + ((size_t)(n >> 7) * KT + kt) * kStageB6 + (size_t)((n & 127) >> 5) * kBlock6 + (f & 1) * 512 + (n & 31) * 16;
+  for (int p = 0; p < 3; ++p) {
+    const int off = (f >> 1) * 24 + p * 8;
+    *reinterpret_cast<uint64_t*>(dst + (off >> 4) * kPart + (off & 15)) = part[p];
+  }
 }
 
 // Workgroup: 8 waves (2 x 4), tile 256 x 256, one workgroup per CU with two waves on every SIMD, all
@@ -165,15 +170,14 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   } while (0)
   constexpr int kLoadsPerStep = nA + nB;
 
-  // LDS byte addresses of part 0 of this lane's fragments of MFMA round 0 in stage 0: plane
-  // (2 k + kg) * 3 + p, row / column of this lane
+  // LDS byte addresses of part 0 of this lane's 48 bytes in stage 0: 32-row block, then lane * 16
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
   uint32_t adrA[4], adrB[NI];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi) adrA[mi] = (uint32_t)(wm * kStageB6 + (kg * 3) * kPlane + (mi * 32 + l32) * 8);
+  for (int mi = 0; mi < 4; ++mi) adrA[mi] = (uint32_t)((wm * 4 + mi) * kBlock6 + lane * 16);
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni)
-    adrB[ni] = (uint32_t)(kStageA6 + (wn >> 1) * kStageB6 + (kg * 3) * kPlane + ((wn & 1) * 64 + ni * 32 + l32) * 8);
+    adrB[ni] = (uint32_t)(kStageA6 + (wn >> 1) * kStageB6 + ((wn & 1) * 2 + ni) * kBlock6 + lane * 16);
 
   v16f acc[4][NI];
 #pragma unroll
@@ -207,46 +211,44 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     if (kt + 2 < KT) STAMP_REQUEST6(kt + 2, (stg == 0 ? 2 : stg - 1));
     __builtin_amdgcn_sched_barrier(0);
 
-    // The step's 12 fragments (per MFMA round k: 2 of the weights, 4 of the activations), each by one
-    // two-address read (parts 0 and 1 -> operand registers 0-3) and one 8-byte read (part 2 -> registers
-    // 4-5).  The reads are written out by hand, so that none is merged with a part of another fragment
-    // (which would cost register copies), and so are the waits: round 1's reads stay in flight under
-    // round 0's MFMAs.  A wait names the registers it covers, which keeps the MFMAs behind it.
+    // The step's 12 fragments (per MFMA round k: 2 of the weights, 4 of the activations) arrive as 6 x 3
+    // 16-byte reads: parts 0 and 1 hold round 0's fragment (6 registers) and the first 2 registers of round
+    // 1's, part 2 the rest.  The reads are written out by hand and so are the waits: the part-2 reads stay
+    // in flight under round 0's MFMAs.  A wait names the registers it covers, which keeps the MFMAs behind it.
     const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
-    u4 alo[2][4], blo[2][NI];
-    u2 ahi[2][4], bhi[2][NI];
+    u4 a0[4], a1[4], a2[4], b0[NI], b1[NI], b2[NI];
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int ni = 0; ni < NI; ++ni)
+      asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3"
+                   : "=v"(b0[ni]), "=v"(b1[ni]) : "v"(sa + adrB[ni]), "n"(kPart));
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-        asm volatile("ds_read2st64_b64 %0, %2 offset0:%3 offset1:%4\n\tds_read_b64 %1, %2 offset:%5"
-                     : "=v"(blo[k][ni]), "=v"(bhi[k][ni])
-                     : "v"(sa + adrB[ni]), "n"(k * 12), "n"(k * 12 + 2), "n"(k * 6 * kPlane + 2 * kPlane));
+    for (int mi = 0; mi < 4; ++mi)
+      asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3"
+                   : "=v"(a0[mi]), "=v"(a1[mi]) : "v"(sa + adrA[mi]), "n"(kPart));
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-        asm volatile("ds_read2st64_b64 %0, %2 offset0:%3 offset1:%4\n\tds_read_b64 %1, %2 offset:%5"
-                     : "=v"(alo[k][mi]), "=v"(ahi[k][mi])
-                     : "v"(sa + adrA[mi]), "n"(k * 12), "n"(k * 12 + 2), "n"(k * 6 * kPlane + 2 * kPlane));
-    }
+    for (int ni = 0; ni < NI; ++ni)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b2[ni]) : "v"(sa + adrB[ni]), "n"(2 * kPart));
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a2[mi]) : "v"(sa + adrA[mi]), "n"(2 * kPart));
+    asm volatile("s_waitcnt lgkmcnt(6)"
+                 : "+v"(a0[0]), "+v"(a0[1]), "+v"(a0[2]), "+v"(a0[3]), "+v"(b0[0]), "+v"(b0[1]),
+                   "+v"(a1[0]), "+v"(a1[1]), "+v"(a1[2]), "+v"(a1[3]), "+v"(b1[0]), "+v"(b1[1]));
     v6i fa[2][4], fb[2][NI];
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int ni = 0; ni < NI; ++ni) fb[0][ni] = (v6i)(u6)__builtin_shufflevector(b0[ni], b1[ni], 0, 1, 2, 3, 4, 5);
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-        fb[k][ni] = (v6i)(u6)__builtin_shufflevector(blo[k][ni], __builtin_shufflevector(bhi[k][ni], bhi[k][ni], 0, 1, -1, -1), 0, 1, 2, 3, 4, 5);
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-        fa[k][mi] = (v6i)(u6)__builtin_shufflevector(alo[k][mi], __builtin_shufflevector(ahi[k][mi], ahi[k][mi], 0, 1, -1, -1), 0, 1, 2, 3, 4, 5);
-    }
-    asm volatile("s_waitcnt lgkmcnt(12)"
-                 : "+v"(fa[0][0]), "+v"(fa[0][1]), "+v"(fa[0][2]), "+v"(fa[0][3]), "+v"(fb[0][0]), "+v"(fb[0][1]));
+    for (int mi = 0; mi < 4; ++mi) fa[0][mi] = (v6i)(u6)__builtin_shufflevector(a0[mi], a1[mi], 0, 1, 2, 3, 4, 5);
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
         acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[0][mi]), widen(fb[0][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fa[1][2]), "+v"(fa[1][3]), "+v"(fb[1][0]), "+v"(fb[1][1]));
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a2[0]), "+v"(a2[1]), "+v"(a2[2]), "+v"(a2[3]), "+v"(b2[0]), "+v"(b2[1]));
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) fb[1][ni] = (v6i)(u6)__builtin_shufflevector(b1[ni], b2[ni], 2, 3, 4, 5, 6, 7);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) fa[1][mi] = (v6i)(u6)__builtin_shufflevector(a1[mi], a2[mi], 2, 3, 4, 5, 6, 7);
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
@@ -301,7 +303,7 @@ hipError_t stamp_launch_weight_quant6(const stamp_plan* p, const float* W, const
 }
 
 hipError_t stamp_launch_repack6(const stamp_plan* p, const uint8_t* q_lo, uint8_t* a6, hipStream_t st) {
-  hipLaunchKernelGGL(k_repack6, dim3((p->Mpad / 256) * (p->Kpad / 128)), dim3(256), 0, st, q_lo, a6);
+  hipLaunchKernelGGL(k_repack6, dim3((p->Mpad / 256) * (p->Kpad / 128)), dim3(512), 0, st, q_lo, a6);
   return hipGetLastError();
 }
 

@@ -126,7 +126,7 @@ struct stamp_plan {
   float* bias_dev;          // [Npad] bias or nullptr
   float* colsum_dev;        // [Npad] sum over input channels of the weight codes (exact integers as fp32)
   int32_t* row_of_coeff;    // host, [s]
-  uint8_t* qW6_dev;         // the same weight codes as E2M3 numbers in the plane layout of the FP6 GEMM
+  uint8_t* qW6_dev;         // the same weight codes as E2M3 numbers in the operand layout of the FP6 GEMM
   int32_t engine;           // matrix pipeline of the 4-bit rows' GEMM: STAMP_GEMM_INT8 or STAMP_GEMM_FP6
   int32_t unfused;          // 1: separate inverse kernel
   int32_t fused_ok;         // shape allows the fused epilogue
