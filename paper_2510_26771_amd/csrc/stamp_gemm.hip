@@ -40,7 +40,7 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   constexpr int kMainBytes = 2 * stage;
   constexpr int kRowInfoOff = (EPI == 2 && kTileBytes > kMainBytes) ? kTileBytes : kMainBytes;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
   const int wm = wave / WN, wn = wave % WN;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
   const int l32 = lane & 31, kg = lane >> 5;
   int tm, tn;

@@ -138,7 +138,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   constexpr int kRowInfoOff = (EPI == 2 && kTileBytes6 > kMainBytes) ? kTileBytes6 : kMainBytes;
   constexpr int nA = kStageA6 / (512 * 16), nB = 2 * kStageB6 / (512 * 16);  // 16-byte chunks per thread and step: 3 and 3
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
   const int wm = wave >> 2, wn = wave & 3;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
   const int l32 = lane & 31, kg = lane >> 5;
   int tm, tn;
@@ -213,18 +213,19 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
 
     // The step's 12 fragments (per MFMA round k: 2 of the weights, 4 of the activations) arrive as 6 x 3
     // 16-byte reads: parts 0 and 1 hold round 0's fragment (6 registers) and the first 2 registers of round
-    // 1's, part 2 the rest.  The reads are written out by hand and so are the waits: the part-2 reads stay
-    // in flight under round 0's MFMAs.  A wait names the registers it covers, which keeps the MFMAs behind it.
+    // 1's, part 2 the rest.  The reads are written out by hand (outputs of a two-read statement are early-clobber: the
+    // address register must outlive the first read) and so are the waits: the part-2 reads stay in flight
+    // under round 0's MFMAs.  A wait names the registers it covers, which keeps the MFMAs behind it.
     const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
     u4 a0[4], a1[4], a2[4], b0[NI], b1[NI], b2[NI];
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
       asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3"
-                   : "=v"(b0[ni]), "=v"(b1[ni]) : "v"(sa + adrB[ni]), "n"(kPart));
+                   : "=&v"(b0[ni]), "=&v"(b1[ni]) : "v"(sa + adrB[ni]), "n"(kPart));
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
       asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3"
-                   : "=v"(a0[mi]), "=v"(a1[mi]) : "v"(sa + adrA[mi]), "n"(kPart));
+                   : "=&v"(a0[mi]), "=&v"(a1[mi]) : "v"(sa + adrA[mi]), "n"(kPart));
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b2[ni]) : "v"(sa + adrB[ni]), "n"(2 * kPart));

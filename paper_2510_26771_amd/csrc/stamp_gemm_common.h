@@ -111,10 +111,13 @@ struct OutOct {
   size_t base;        // element index of token 0 of the block, first of the 8 columns
   size_t tok_stride;  // d_out
   size_t row_stride;  // 2-D: grid_w * d_out
-  f8 bias;
+  f8 scale;           // weight scales of the 8 columns
+  f8 offset;          // block sum of the unit's block + bias, per column
   int nvalid;         // how many of the 8 columns exist (d_out tail)
+  // v = the token's sum of +-detail coefficients, still without the weight scale: one fma per output
   __device__ __forceinline__ void put(size_t idx, f8 v) const {
-    v += bias;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = __builtin_fmaf(v[t], scale[t], offset[t]);
     if constexpr (YBF16) {
       // round-to-nearest-even pairs in hardware (v_cvt_pk_bf16_f32)
       u4 w;
@@ -124,7 +127,7 @@ struct OutOct {
       w.w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v[6], v[7]}, bf2));
       uint16_t* y = reinterpret_cast<uint16_t*>(Y) + idx;
       if constexpr (VEC) {
-        *reinterpret_cast<u4*>(y) = w;
+        __builtin_nontemporal_store(w, reinterpret_cast<u4*>(y));  // Y is not read again here: keep it out of the way of the operands in L2
       } else {
 #pragma unroll
         for (int t = 0; t < 8; ++t)
@@ -133,8 +136,8 @@ struct OutOct {
     } else {
       float* y = reinterpret_cast<float*>(Y) + idx;
       if constexpr (VEC) {
-        *reinterpret_cast<f4*>(y) = (f4){v[0], v[1], v[2], v[3]};
-        *reinterpret_cast<f4*>(y + 4) = (f4){v[4], v[5], v[6], v[7]};
+        __builtin_nontemporal_store((f4){v[0], v[1], v[2], v[3]}, reinterpret_cast<f4*>(y));
+        __builtin_nontemporal_store((f4){v[4], v[5], v[6], v[7]}, reinterpret_cast<f4*>(y + 4));
       } else {
 #pragma unroll
         for (int t = 0; t < 8; ++t)
@@ -154,7 +157,9 @@ __device__ __forceinline__ f8 tile_row(const float* tile, int e) {
 }
 
 // Depth-first inverse of one unit for 8 columns.  The unit is the subtree rooted at node (M0, h) of a
-// block's Haar tree; node (M, I) of that subtree holds the sum `a` of its tokens; row e of the tile is
+// block's Haar tree; node (M, I) of that subtree holds in `a` the signed sum of the detail coefficients on
+// the path from the block's root (the block sum and the weight scale are applied by Out::put: the inverse
+// is linear along the tokens, so the per-column scale can wait until the end); row e of the tile is
 // the block's coefficient at in-block STaMP position e = 2^M + (h << (M - M0)) + I.  Only O(r) values
 // are live at any time and every coefficient is read once.
 template <int RLOG, int M0, int M, int I, typename Out>
@@ -207,8 +212,8 @@ struct EpiShape {
 template <int EPI, int RB, bool IS2D>
 struct EpiOperands {
   using ES = EpiShape<(EPI == 2 ? RB : 3), IS2D>;
-  float sw[NI];
   float cs[NI];  // column sums of the weight codes (asymmetric plans)
+  f8 sw8;        // weight scales of this lane's 8 output columns
   f8 bias;
   f8 top[2][ES::npass];
   __device__ __forceinline__ void request(const GemmArgs& a, int m0, int n0, int lane, int wm, int wn) {
@@ -217,9 +222,10 @@ struct EpiOperands {
       const int nw = n0 + wn * 64;
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) {
-        sw[ni] = a.sw[nw + ni * 32 + l32];
         cs[ni] = a.g.asym ? a.colsum[nw + ni * 32 + l32] : 0.0f;
       }
+      const f4 s0 = *reinterpret_cast<const f4*>(a.sw + nw + c8), s1 = *reinterpret_cast<const f4*>(a.sw + nw + c8 + 4);
+      sw8 = (f8){s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
       const f4 zero = (f4){0.0f, 0.0f, 0.0f, 0.0f};
       const f4 b0 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8) : zero;
       const f4 b1 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8 + 4) : zero;
@@ -327,7 +333,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
       }
     }
   } else {
-    // fused: per half of 64 rows, dequantize into this wave's LDS tile [64][kEpiStride]; then the wave's
+    // fused: per half of 64 rows, scale by the row factors into this wave's LDS tile [64][kEpiStride]; then the wave's
     // 8 groups of 8 lanes each take one unit and 8 columns per lane, and run the depth-first inverse,
     // storing the unit's tokens.
     using ES = EpiShape<RB, IS2D>;
@@ -345,7 +351,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
       o.tok_stride = (size_t)a.N;
       o.row_stride = (size_t)g.gridW * a.N;
       o.nvalid = a.N - n;
-      o.bias = eo.bias;
+      o.scale = eo.sw8;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
         if (!g.asym) {
@@ -358,14 +364,13 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
               rf[mh][q] = *reinterpret_cast<const f4*>(s_rowfac + wm * 128 + (2 * hf + mh) * 32 + 8 * q + 4 * kg);
 #pragma unroll
           for (int ni = 0; ni < NI; ++ni) {
-            const float swn = eo.sw[ni];
 #pragma unroll
             for (int mh = 0; mh < 2; ++mh) {
               const int mi = 2 * hf + mh;
 #pragma unroll
               for (int v = 0; v < 16; ++v) {
                 const int rw = mh * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                s_tile[rw * kEpiStride + pos0 + 16 * ni] = ((float)acc[mi][ni][v] * rf[mh][v >> 2][v & 3]) * swn;
+                s_tile[rw * kEpiStride + pos0 + 16 * ni] = (float)acc[mi][ni][v] * rf[mh][v >> 2][v & 3];
               }
             }
           }
@@ -391,7 +396,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
               for (int vv = 0; vv < 4; ++vv) {
                 const int rw = mh * 32 + 8 * q + 4 * kg + vv;
                 const float af = __builtin_fmaf(-rz4[vv], eo.cs[ni], (float)acc[mi][ni][4 * q + vv]);
-                s_tile[rw * kEpiStride + pos0 + 16 * ni] = (af * rf4[vv]) * eo.sw[ni];
+                s_tile[rw * kEpiStride + pos0 + 16 * ni] = af * rf4[vv];
               }
             }
           }
@@ -409,7 +414,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
           if (mrow < a.M && n < a.N) {
             const int b = mrow / g.s, pr = mrow - b * g.s;
             const int j = pr / g.R;
-            f8 top = eo.top[hf][pass];
+            o.offset = eo.top[hf][pass] + eo.bias;
+            f8 top = (f8){0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};  // signed detail sum on the path to the unit
             const float* tile = s_tile + blk * R * kEpiStride + 4 * (lane & 7);
             if constexpr (IS2D) {
               const int bi = j / g.G, bj = j - bi * g.G;
