@@ -86,7 +86,7 @@ void layout_workspace(stamp_plan* p) {
   p->ws_qhi = take((size_t)g.B * g.k * g.d);
   p->ws_qlo = take((size_t)p->Mpad * (p->Kpad / 2));
   p->ws_scales = take((size_t)2 * g.B * g.s * sizeof(float));  // scales, then offsets (asymmetric plans)
-  p->ws_ythi = take((size_t)g.B * g.k * g.N * sizeof(float));
+  p->ws_ythi = take((size_t)p->hi_ksplit * g.B * g.k * g.N * sizeof(float));  // partial rows per part of a split depth
   p->ws_P = take((size_t)g.B * g.k * p->Npad * sizeof(float));
   p->ws_a6 = take(stamp_a6_bytes(p));
   p->ws_ytlo = off;
@@ -106,7 +106,7 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
   float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
   float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
   if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
-  if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit) != hipSuccess) return STAMP_ERR_DEVICE;
   const bool fused = p->fused_ok && !p->unfused;
   float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
   if (p->engine == STAMP_GEMM_FP6) {
@@ -161,6 +161,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   p->Kpad = ((g.d + 127) / 128) * 128;
   p->Npad = ((g.N + 255) / 256) * 256;
   p->Mpad = ((g.B * g.s + 255) / 256) * 256;
+  p->hi_ksplit = stamp_hi_ksplit(p);
   layout_workspace(p);
 
   // physical row of every STaMP slot
@@ -322,7 +323,7 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
     case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 1); break;
     case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 2); break;
     case 2: e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st); break;
-    case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st); break;
+    case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit); break;
     case 4:
       if (p->engine == STAMP_GEMM_FP6)
         e = stamp_launch_gemm_lo6(p, at(ws, p->ws_a6), scales, fused ? 2 : 1, fused ? Y : (void*)ytlo, fused ? P : nullptr, st);

@@ -26,7 +26,8 @@ using namespace stamp_gemm;
 // WN = waves along N: 2 -> 4 waves, tile 256 x 128, two workgroups per CU; 4 -> 8 waves, tile 256 x 256,
 // one workgroup per CU (fewer, larger tiles: for the few 8-bit rows, whose whole GEMM is one round of tiles).
 template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16, int WN>
-__global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const GemmArgs a) {
+__global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const GemmArgs a_in) {
+  GemmArgs a = a_in;
   using Acc = typename std::conditional<A_INT4, AccI8Lo, AccI8Hi>::type;
   constexpr int BN = 64 * WN, NT = 128 * WN;    // tile width, threads
   constexpr int kTileBytes = 2 * WN * kWaveTileBytes;  // the waves' epilogue staging tiles
@@ -44,9 +45,22 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   const int wm = wave / WN, wn = wave % WN;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
   const int l32 = lane & 31, kg = lane >> 5;
   int tm, tn;
-  tile_of_block(a.M, a.Npad, BN, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
   const int KT = a.Kpad / BK;
+  int kt0 = 0, kt1 = KT;  // K steps of this workgroup
+  if constexpr (!A_INT4 && EPI == 1) {
+    // split depth: partial dequantized rows per part (the consumer adds them); the zero-point term of
+    // asymmetric codes goes with part 0 only
+    int split = 0;
+    if (a.ksplit > 1) tile_of_block_split(a.M, a.ksplit, tm, tn, split);
+    else tile_of_block(a.M, a.Npad, BN, tm, tn);
+    kt0 = (int)((long long)KT * split / a.ksplit);
+    kt1 = (int)((long long)KT * (split + 1) / a.ksplit);
+    a.out = reinterpret_cast<float*>(a.out) + (size_t)split * a.split_stride;
+    if (split > 0) a.g.asym = 0;
+  } else {
+    tile_of_block(a.M, a.Npad, BN, tm, tn);
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
 
   // ---- global -> LDS assignment: chunk q = i * NT + tid of the tile, consecutive lanes = consecutive
   //      chunks.  Row / column of chunk i is (row0 + i * rows_per_pass); its swizzled slot does not
@@ -127,7 +141,7 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   } while (0)
 
 
-  STAMP_REQUEST(0, 0);
+  STAMP_REQUEST(kt0, 0);
   EpiOperands<EPI, RB, IS2D> eo;
   eo.request(a, m0, n0, lane, wm, wn);
   if (NT == 256 || tid < 256) store_row_info<Acc, EPI>(a, m0, tid, smem + kRowInfoOff);
@@ -135,13 +149,13 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   // Step kt: wait for this wave's loads of step kt, then the workgroup barrier (every wave's loads of
   // step kt have landed, and every wave has left step kt-1, whose stage is now free); request step
   // kt+1 into that free stage; run the MFMAs of step kt.
-  for (int kt = 0; kt < KT; ++kt) {
-    const uint8_t* st = smem + (kt & 1) * stage;
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const uint8_t* st = smem + ((kt - kt0) & 1) * stage;
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + 1 < KT) STAMP_REQUEST(kt + 1, (kt + 1) & 1);
+    if (kt + 1 < kt1) STAMP_REQUEST(kt + 1, (kt + 1 - kt0) & 1);
     __builtin_amdgcn_sched_barrier(0);
 
     v4i fb[2][NI];
@@ -234,7 +248,8 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
     attr_set = true;
   }
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
-  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>), dim3(mt * nt), dim3(128 * WN), lds, st, a);
+  const int split = (!A_INT4 && EPI == 1) ? a.ksplit : 1;
+  hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>), dim3(mt * nt * split), dim3(128 * WN), lds, st, a);
   return hipGetLastError();
 }
 
@@ -245,22 +260,45 @@ hipError_t launch(const GemmArgs& a, hipStream_t st) {
     if (a.g.y_bf16) return launch_y<A_INT4, EPI, RB, IS2D, true, 2>(a, st);
   }
   if constexpr (!A_INT4) {
-    // The 8-bit rows' GEMM keeps one 256 x 128 workgroup per CU (its stages hold unpacked int8 rows).  When
-    // that needs more than one round of tiles, 256 x 256 tiles (half as many, one round) finish sooner.
-    static int cus = 0;
-    if (cus == 0) {
-      int dev = 0;
-      if (hipGetDevice(&dev) != hipSuccess ||
-          hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
-    }
-    const int tiles128 = ((a.M + BM - 1) / BM) * (a.Npad / 128);
-    if (tiles128 > cus) return launch_y<A_INT4, EPI, RB, IS2D, false, 4>(a, st);
+    if (stamp_hi_wide_tiles(a.M, a.Npad)) return launch_y<A_INT4, EPI, RB, IS2D, false, 4>(a, st);
   }
   return launch_y<A_INT4, EPI, RB, IS2D, false, 2>(a, st);
 }
 
 }  // namespace
+
+namespace {
+int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+  }
+  return cus;
+}
+}  // namespace
+
+// The 8-bit rows' GEMM keeps one 256 x 128 workgroup per CU (its stages hold unpacked int8 rows).  When
+// that needs more than one round of tiles, 256 x 256 tiles (half as many, one round) finish sooner.
+bool stamp_hi_wide_tiles(int M, int Npad) {
+  const int tiles128 = ((M + stamp_gemm::BM - 1) / stamp_gemm::BM) * (Npad / 128);
+  return tiles128 > device_cus();
+}
+
+// The few 8-bit rows make few tiles: when they would leave most CUs idle, the depth of every tile is split
+// over 2..4 workgroups (partial rows, added by the top inverse).
+int stamp_hi_ksplit(const stamp_plan* p) {
+  const int M = p->geom.B * p->geom.k;
+  const int mt = (M + stamp_gemm::BM - 1) / stamp_gemm::BM;
+  const int tiles = mt * (p->Npad / (stamp_hi_wide_tiles(M, p->Npad) ? 256 : 128));
+  const int KT = p->Kpad / stamp_gemm::BK;
+  int s = device_cus() / tiles;
+  if (s > 4) s = 4;
+  while (s > 1 && KT / s < 2) --s;
+  return s < 2 ? 1 : s;
+}
 
 stamp_gemm::GemmArgs stamp_gemm_args(const stamp_plan* p, const float* scales, void* out) {
   stamp_gemm::GemmArgs a;
@@ -279,6 +317,8 @@ stamp_gemm::GemmArgs stamp_gemm_args(const stamp_plan* p, const float* scales, v
   a.M = 0;
   a.a_row_bytes = 0;
   a.a_last16 = 0;
+  a.ksplit = 1;
+  a.split_stride = 0;
   return a;
 }
 
@@ -290,7 +330,11 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
   a.a_row_bytes = p->geom.d;
   a.a_last16 = (size_t)a.M * a.a_row_bytes - 16;
   if (mode == 0) return launch<false, 0, 0, false>(a, st);
-  if (mode == 1) return launch<false, 1, 0, false>(a, st);
+  if (mode == 1) {
+    a.ksplit = p->hi_ksplit;
+    a.split_stride = (size_t)a.M * a.N;
+    return launch<false, 1, 0, false>(a, st);
+  }
   return hipErrorInvalidValue;
 }
 

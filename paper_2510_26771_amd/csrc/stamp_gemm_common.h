@@ -54,6 +54,8 @@ struct GemmArgs {
   int N, Npad, Kpad;
   int a_row_bytes;       // 8-bit rows: valid bytes per A row
   size_t a_last16;       // 8-bit rows: byte offset of the last 16-byte chunk of A (loads are clamped to it)
+  int ksplit;            // 8-bit rows, dequantized mode: the depth is split over this many workgroups per tile,
+  size_t split_stride;   // each writing its partial rows to out + split * split_stride (floats)
   StampGeom g;
 };
 
@@ -100,6 +102,16 @@ __device__ __forceinline__ void tile_of_block(int M, int Npad, int bn, int& tm, 
   const int gm = min(kGroupM, mt - grp * kGroupM);
   tm = grp * kGroupM + in_grp % gm;
   tn = in_grp / gm;
+}
+
+// Split depth (few tiles, most CUs idle otherwise): `ksplit` consecutive workgroups share a tile; no
+// regard to the XCDs.
+__device__ __forceinline__ void tile_of_block_split(int M, int ksplit, int& tm, int& tn, int& split) {
+  const int mt = (M + BM - 1) / BM;
+  const int tile = blockIdx.x / ksplit;
+  split = blockIdx.x - tile * ksplit;
+  tm = tile % mt;
+  tn = tile / mt;
 }
 
 // Where one lane stores the tokens of one unit (an aligned part of a block): 8 adjacent output columns

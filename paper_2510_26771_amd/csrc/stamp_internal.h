@@ -128,6 +128,7 @@ struct stamp_plan {
   int32_t* row_of_coeff;    // host, [s]
   uint8_t* qW6_dev;         // the same weight codes as E2M3 numbers in the operand layout of the FP6 GEMM
   int32_t engine;           // matrix pipeline of the 4-bit rows' GEMM: STAMP_GEMM_INT8 or STAMP_GEMM_FP6
+  int32_t hi_ksplit;        // parts the depth of the 8-bit rows' GEMM is split into (partial rows in the workspace)
   int32_t unfused;          // 1: separate inverse kernel
   int32_t fused_ok;         // shape allows the fused epilogue
   // workspace layout (byte offsets, 256-aligned)
@@ -141,7 +142,9 @@ hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStr
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo,
                                  float* scales, float* abot, uint32_t* rowmax, hipStream_t st, int part = 3);
 // mode: 0 = int32 accumulators in STaMP row order (debug), 1 = dequantized fp32 rows (hi -> Yt_hi
-// [B*k, N], lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y.
+// [hi_ksplit][B*k, N] partial rows, lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y.
+bool stamp_hi_wide_tiles(int M, int Npad);
+int stamp_hi_ksplit(const stamp_plan* p);
 hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode,
                                 void* out, hipStream_t st);
 hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const float* scales, int mode,
@@ -154,9 +157,9 @@ hipError_t stamp_launch_weight_quant6(const stamp_plan* p, const float* W, const
 hipError_t stamp_launch_repack6(const stamp_plan* p, const uint8_t* q_lo, uint8_t* a6, hipStream_t st);
 hipError_t stamp_launch_gemm_lo6(const stamp_plan* p, const uint8_t* a6, const float* scales, int mode, void* out,
                                  const float* P, hipStream_t st);
-// P: block sums [B*k][ldP]
+// P: block sums [B*k][ldP]; nparts partial sources (each B*k*ncols floats apart) are added while reading
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* Yt_hi, int hi_row_stride_is_stamp,
-                                    int ncols, float* P, int ldP, hipStream_t st);
+                                    int ncols, float* P, int ldP, hipStream_t st, int nparts = 1);
 hipError_t stamp_launch_inverse_bottom(const stamp_plan* p, const float* Yt_lo, int src_is_stamp_order,
                                        const float* P, int ldP, int ncols, const float* bias, void* Y, hipStream_t st);
 

@@ -64,9 +64,11 @@ __device__ __forceinline__ void inverse_inplace(float* s_buf, int n, int side, i
   }
 }
 
-// src: hi rows; row of (b, p) = b * src_seq_rows + p.  P[(b*k + j) * ldP + n].
+// src: hi rows; row of (b, p) = b * src_seq_rows + p; nparts partial copies, part_stride floats apart, are
+// added in order.  P[(b*k + j) * ldP + n].
 __global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ src, int src_seq_rows, int apply_norm,
-                                                     float* __restrict__ P, int ldP, int ncols, StampGeom g) {
+                                                     float* __restrict__ P, int ldP, int ncols, StampGeom g, int nparts,
+                                                     size_t part_stride) {
   extern __shared__ float s_buf[];  // [k][kStride]
   const int b = blockIdx.y, n_base = blockIdx.x * kCols, tid = threadIdx.x;
   const int ch = tid & (kCols - 1), grp = tid / kCols, ngrp = 256 / kCols;
@@ -81,7 +83,12 @@ __global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ s
       const int y = q / g.G, x = q - y * g.G;
       e = stamp_top_slot_2d(y, x, g.G, g.L, &lvl_top);
     }
-    float v = nact ? src[((size_t)b * src_seq_rows + e) * ncols + n] : 0.0f;
+    float v = 0.0f;
+    if (nact) {
+      const size_t idx = ((size_t)b * src_seq_rows + e) * ncols + n;
+      v = src[idx];
+      for (int part = 1; part < nparts; ++part) v += src[idx + part * part_stride];
+    }
     if (apply_norm) v *= haar_norm_dev(g.r + lvl_top, g.is2d);
     s_buf[q * kStride + ch] = v;
   }
@@ -151,11 +158,11 @@ __global__ __launch_bounds__(256) void k_inverse_bottom(const float* __restrict_
 }  // namespace
 
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* src, int src_is_stamp, int ncols, float* P,
-                                    int ldP, hipStream_t st) {
+                                    int ldP, hipStream_t st, int nparts) {
   const StampGeom& g = p->geom;
   const size_t lds = (size_t)g.k * kStride * sizeof(float);
   hipLaunchKernelGGL(k_inverse_top, dim3((ncols + kCols - 1) / kCols, g.B), dim3(256), lds, st, src,
-                     src_is_stamp ? g.s : g.k, src_is_stamp, P, ldP, ncols, g);
+                     src_is_stamp ? g.s : g.k, src_is_stamp, P, ldP, ncols, g, nparts, (size_t)g.B * g.k * (size_t)ncols);
   return hipGetLastError();
 }
 
