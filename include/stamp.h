@@ -112,8 +112,9 @@ typedef struct {
  *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels J >= log2(seq_len/k_hi) (2-D: log4), i.e.
  *   k_hi >= the number of level-J approximations, so that every 4-bit token is a wavelet coefficient
  *   (full depth, or e.g. the 3-level transform of a 64x64 grid with k_hi = 64); bits 8/4/4;
- *   d_in a multiple of 32 and at most 8192 (4096 for fp32 input or 2-D grids); k_hi <= 256;
- *   act_quant symmetric or asymmetric. */
+ *   d_in a multiple of 32 and at most 32768 (above 8192, or 4096 for fp32 input or 2-D grids, the transform
+ *   + quantization kernel splits the channels over workgroups and reads X twice: row ranges, then codes);
+ *   k_hi <= 256; act_quant symmetric or asymmetric. */
 
 /* Validates desc, quantizes W per output channel (absmax/7, round to nearest even; section
  * "Large Language Models", Set-up: round-to-nearest weights, one scale per output channel) into

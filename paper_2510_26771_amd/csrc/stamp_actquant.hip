@@ -128,12 +128,30 @@ struct RowMeta { int level; int e; };
 constexpr int kMaxRows = 18;  // most rows finished by one streaming step (2-D: 12 + 3 + 3)
 constexpr int kPartWords = 2 * kMaxRows * 16;  // per-wave partial maxima of one step: [2 signs][row][wave]
 
+// Channel split.  A workgroup covers at most 1024 (1-D) / 512 (2-D) threads x 8 channels; wider layers
+// are split over blockIdx.z and run in two passes, because a row's range spans all channels:
+//   PASS 1  transform, reduce each row over the workgroup's channels, write the partial maxima
+//           gpart[sign][split][B*s] (no codes);
+//   PASS 2  transform again, take each row's maximum over the splits from LDS (s_amax[sign][e], filled
+//           from gpart before the first step), quantize and store.
+//   PASS 0  is the single-pass kernel (one workgroup sees all channels).
+struct SplitArgs {
+  uint32_t* gpart;     // partial row maxima (bit patterns), PASS 1 writes / PASS 2 reads
+  size_t part_rows;    // B * s
+  int nsplit;
+  int c_split;         // channels per split (a multiple of 8)
+};
+constexpr int kMaxBlockRows = 128;
+
 // ASYM: the asymmetric form of the quantizer; zeros_off = distance (in floats) from a row's scale to its offset z.
-template <int NR, bool IS2D, bool ASYM, typename MetaFn>
+template <int NR, bool IS2D, bool ASYM, int PASS, typename MetaFn>
 __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, int step, uint32_t (*s_max)[kPartWords],
                                            uint8_t* q_lo_blk /* row e=0 of the block, channel 0 (workgroup-uniform) */,
                                            uint32_t q_off /* this thread's byte offset inside a row */,
-                                           float* scales_blk, size_t zeros_off, bool active, int tid) {
+                                           float* scales_blk, size_t zeros_off, bool active, int tid,
+                                           uint32_t* gpart_blk /* PASS 1: this split's partial maxima of the block's row e=0 */,
+                                           size_t gpart_neg /* PASS 1: distance to the negative parts */,
+                                           const uint32_t* s_amax /* PASS 2: [2][kMaxBlockRows] */, bool write_scales) {
   // Values derived from the thread index are recomputed in every step from an opaque copy: cheap, and it
   // keeps them from being carried (and spilled: a scratch reload waits for ALL outstanding memory
   // operations, the asynchronous loads of the next batches included) across the whole unrolled kernel.
@@ -142,6 +160,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
   // [row][wave] partial maxima, double buffered; asymmetric: a second array for the negative parts
   uint32_t* part = &s_max[0][0] + (step & 1) * kPartWords;
   uint32_t* part_neg = part + kMaxRows * 16;
+  if constexpr (PASS != 2) {
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
     if constexpr (ASYM) {
@@ -161,6 +180,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
   __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
+  }
   // lane r prepares row r: a = fl(absmaxU * norm); scale = a / 7; inv = 7 / a
   // (asymmetric: hi = fl(posU * norm), nlo = fl(negU * norm), range = hi + nlo, scale = range / 15,
   //  inv = 15 / range, z = rne(fl(nlo * inv)))
@@ -174,6 +194,14 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     // staging buffer that the asynchronous global -> LDS loads of the NEXT batches are writing, and would
     // make every ordinary LDS read here wait for all of them (vmcnt(0)), i.e. serialise memory and compute.
     auto reduce_waves = [&](const uint32_t* arr) {
+      if constexpr (PASS == 2) {
+        // the row's maximum over all channels, reduced before the first step
+        const uint32_t adr1 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint32_t*)(
+            s_amax + (arr == part ? 0 : kMaxBlockRows) + rm.e);
+        uint32_t bits;
+        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(bits) : "v"(adr1) : "memory");
+        return __uint_as_float(bits);
+      }
       const uint32_t adr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint32_t*)(arr + r * 16);
       u4 v0, v1, v2, v3;
       asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:16\n\tds_read_b128 %2, %4 offset:32\n\t"
@@ -192,6 +220,15 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
       }
       return __uint_as_float(mbits);
     };
+    if constexpr (PASS == 1) {
+      const float mpos = reduce_waves(part);
+      if (tid < NR) gpart_blk[rm.e] = __float_as_uint(mpos);
+      if constexpr (ASYM) {
+        const float mneg = reduce_waves(part_neg);
+        if (tid < NR) gpart_blk[gpart_neg + rm.e] = __float_as_uint(mneg);
+      }
+      return;
+    }
     const float nrm = IS2D ? ldexpf(1.0f, -rm.level) : haar_norm(rm.level);
     float scale = 0.0f, inv = 0.0f;
     if constexpr (ASYM) {
@@ -202,7 +239,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
         inv = __fdiv_rn(15.0f, range);
       }
       z_lane = rintf(__fmul_rn(nlo, inv));
-      if (tid < NR) scales_blk[zeros_off + rm.e] = z_lane;
+      if (tid < NR && write_scales) scales_blk[zeros_off + rm.e] = z_lane;
     } else {
       const float a = __fmul_rn(reduce_waves(part), nrm);
       if (a > 0.0f) {
@@ -213,7 +250,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     // even 1-D levels and all 2-D levels have a power-of-two norm: fold it into the multiplier
     const bool fold = IS2D || ((rm.level & 1) == 0);
     mul_lane = fold ? __fmul_rn(inv, nrm) : inv;
-    if (tid < NR) scales_blk[rm.e] = scale;
+    if (tid < NR && write_scales) scales_blk[rm.e] = scale;
   }
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
@@ -298,11 +335,12 @@ __device__ __forceinline__ void chain1d(float (&cur)[8], float (&pend)[NP][8], f
   }
 }
 
-template <int RLOG, bool BF16, bool ASYM, int IT, int NP>
+template <int RLOG, bool BF16, bool ASYM, int PASS, int IT, int NP>
 __device__ __forceinline__ void step1d(const uint8_t* X_blk, uint32_t x_off, size_t row_bytes, uint8_t* stage, int nthreads,
                                        bool active, int tid, float (&pend)[NP][8], float (&top)[8],
                                        uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk,
-                                       size_t zeros_off) {
+                                       size_t zeros_off, uint32_t* gpart_blk, size_t gpart_neg, const uint32_t* s_amax,
+                                       bool write_scales) {
   constexpr int R = 1 << RLOG;
   constexpr int NIT = R / 4;
   constexpr int CH = cmin(trailing_ones(IT), RLOG - 2);
@@ -367,47 +405,72 @@ __device__ __forceinline__ void step1d(const uint8_t* X_blk, uint32_t x_off, siz
   }
   chain1d<RLOG, 2, IT, 3, NP, NR>(cur, pend, rowv, top);
   auto meta = [](int r) -> RowMeta { return meta1d<RLOG, IT>(r); };
-  flush_rows<NR, false, ASYM>(rowv, meta, IT, s_max, q_lo_blk, q_off, scales_blk, zeros_off, active, tid);
+  flush_rows<NR, false, ASYM, PASS>(rowv, meta, IT, s_max, q_lo_blk, q_off, scales_blk, zeros_off, active, tid, gpart_blk,
+                                    gpart_neg, s_amax, write_scales);
 }
 
-template <int RLOG, bool BF16, bool ASYM, int NP, int... ITS>
+template <int RLOG, bool BF16, bool ASYM, int PASS, int NP, int... ITS>
 __device__ __forceinline__ void run1d(std::integer_sequence<int, ITS...>, const uint8_t* X_blk, uint32_t x_off,
                                       size_t row_bytes, uint8_t* stage, int nthreads, bool active, int tid,
                                       float (&pend)[NP][8], float (&top)[8], uint32_t (*s_max)[kPartWords],
-                                      uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk, size_t zeros_off) {
-  (step1d<RLOG, BF16, ASYM, ITS, NP>(X_blk, x_off, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk, q_off,
-                                     scales_blk, zeros_off), ...);
+                                      uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk, size_t zeros_off,
+                                      uint32_t* gpart_blk, size_t gpart_neg, const uint32_t* s_amax, bool write_scales) {
+  (step1d<RLOG, BF16, ASYM, PASS, ITS, NP>(X_blk, x_off, row_bytes, stage, nthreads, active, tid, pend, top, s_max, q_lo_blk,
+                                           q_off, scales_blk, zeros_off, gpart_blk, gpart_neg, s_amax, write_scales), ...);
 }
 
-template <int RLOG, bool BF16, bool ASYM>
+// PASS 2: every row's maximum over the splits -> s_amax[sign][e] (before the first step; ordinary loads)
+template <bool ASYM>
+__device__ __forceinline__ void gather_row_maxima(const SplitArgs& sp, size_t row0, int R, int tid, uint32_t* s_amax) {
+  if (tid < R) {
+    uint32_t mpos = 0u, mneg = 0u;
+    for (int q = 0; q < sp.nsplit; ++q) {
+      mpos = max(mpos, sp.gpart[(size_t)q * sp.part_rows + row0 + tid]);
+      if constexpr (ASYM) mneg = max(mneg, sp.gpart[((size_t)sp.nsplit + q) * sp.part_rows + row0 + tid]);
+    }
+    s_amax[tid] = mpos;
+    s_amax[kMaxBlockRows + tid] = mneg;
+  }
+  __syncthreads();
+}
+
+template <int RLOG, bool BF16, bool ASYM, int PASS>
 __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
                                                    float* __restrict__ scales, float* __restrict__ abot, int s, int d,
-                                                   int k, int Kpad, size_t zeros_off) {
+                                                   int k, int Kpad, size_t zeros_off, SplitArgs sp) {
   constexpr int R = 1 << RLOG;
   constexpr int NP = RLOG > 2 ? RLOG - 2 : 1;
   constexpr int CPR = BF16 ? 1 : 2;
   extern __shared__ __attribute__((aligned(16))) uint8_t stage[];  // 2 halves x 4 rows x nthreads x (16 | 32) bytes
   __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kPartWords];
+  __shared__ uint32_t s_amax[PASS == 2 ? 2 * kMaxBlockRows : 1];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int nthreads = blockDim.x;
-  const int c0 = tid * 8;
-  const bool active = c0 < d;
+  // channels of this workgroup: [c_lo, c_hi)
+  const int c_lo = (PASS == 0) ? 0 : (int)blockIdx.z * sp.c_split;
+  const int c_hi = (PASS == 0) ? d : min(d, c_lo + sp.c_split);
+  const int c0 = c_lo + tid * 8;
+  const bool active = c0 < c_hi;
   const size_t esz = BF16 ? 2 : 4;
   const size_t row0 = (size_t)b * s + (size_t)j * R;
+  if constexpr (PASS == 2) gather_row_maxima<ASYM>(sp, row0, R, tid, s_amax);
   // threads beyond d_in / 8 (the workgroup is a whole number of waves) redo the last channel group:
   // duplicates cannot change a row maximum, and they store nothing
   // addresses = workgroup-uniform base + a 32-bit per-thread offset (keeps the per-thread state small)
   const uint8_t* X_blk = reinterpret_cast<const uint8_t*>(X) + row0 * d * esz;
-  const uint32_t x_off = (uint32_t)(min(c0, d - 8) * (int)esz);
-  const uint32_t q_off = (uint32_t)(stamp_qlo_offset(0, c0, Kpad));
+  const uint32_t x_off = (uint32_t)(min(c0, c_hi - 8) * (int)esz);
+  const uint32_t q_off = (uint32_t)(stamp_qlo_offset(0, min(c0, c_hi - 8), Kpad));
   const size_t row_bytes = (size_t)d * esz;
   request_batch<BF16>(X_blk, x_off, row_bytes, stage, nthreads, tid >> 6);
   if (R > 4) request_batch<BF16>(X_blk + 4 * row_bytes, x_off, row_bytes, stage + 4 * CPR * nthreads * 16, nthreads, tid >> 6);
   float pend[NP][8];
   float top[8];
-  run1d<RLOG, BF16, ASYM, NP>(std::make_integer_sequence<int, R / 4>{}, X_blk, x_off, row_bytes, stage, nthreads, active,
-                              tid, pend, top, s_max, q_lo + stamp_qlo_offset(row0, 0, Kpad), q_off, scales + row0, zeros_off);
-  if (active) {
+  uint32_t* gpart_blk = (PASS == 1) ? sp.gpart + (size_t)blockIdx.z * sp.part_rows + row0 : nullptr;
+  run1d<RLOG, BF16, ASYM, PASS, NP>(std::make_integer_sequence<int, R / 4>{}, X_blk, x_off, row_bytes, stage, nthreads, active,
+                                    tid, pend, top, s_max, q_lo + stamp_qlo_offset(row0, 0, Kpad), q_off, scales + row0,
+                                    zeros_off, gpart_blk, (size_t)sp.nsplit * sp.part_rows, s_amax,
+                                    PASS == 0 || blockIdx.z == 0);
+  if (active && PASS != 1) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
     o[1] = make_float4(top[4], top[5], top[6], top[7]);
@@ -432,10 +495,11 @@ __device__ __forceinline__ void cell2d(const float (&p)[8], const float (&q)[8],
   }
 }
 
-template <int RLOG, bool BF16, bool ASYM, int SB>
+template <int RLOG, bool BF16, bool ASYM, int PASS, int SB>
 __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int gridW, int d, int c0, bool active, int tid,
                                        float (&pend)[4][8], float (&top)[8], uint32_t (*s_max)[kPartWords],
-                                       uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk, size_t zeros_off) {
+                                       uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk, size_t zeros_off,
+                                       uint32_t* gpart_blk, size_t gpart_neg, const uint32_t* s_amax, bool write_scales) {
   constexpr int g = 1 << RLOG;
   constexpr int sby = (g == 4) ? 0 : (SB >> 1), sbx = (g == 4) ? 0 : (SB & 1);
   constexpr bool LAST = (g == 8) && (SB == 3);
@@ -481,38 +545,46 @@ __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int g
     }
     return m;
   };
-  flush_rows<NR, true, ASYM>(rowv, meta, SB, s_max, q_lo_blk, q_off, scales_blk, zeros_off, active, tid);
+  flush_rows<NR, true, ASYM, PASS>(rowv, meta, SB, s_max, q_lo_blk, q_off, scales_blk, zeros_off, active, tid, gpart_blk,
+                                   gpart_neg, s_amax, write_scales);
 }
 
-template <int RLOG, bool BF16, bool ASYM, int... SBS>
+template <int RLOG, bool BF16, bool ASYM, int PASS, int... SBS>
 __device__ __forceinline__ void run2d(std::integer_sequence<int, SBS...>, const void* X, size_t blk_elem_off, int gridW,
                                       int d, int c0, bool active, int tid, float (&pend)[4][8], float (&top)[8],
                                       uint32_t (*s_max)[kPartWords], uint8_t* q_lo_blk, uint32_t q_off, float* scales_blk,
-                                      size_t zeros_off) {
-  (step2d<RLOG, BF16, ASYM, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, q_off, scales_blk,
-                                 zeros_off), ...);
+                                      size_t zeros_off, uint32_t* gpart_blk, size_t gpart_neg, const uint32_t* s_amax,
+                                      bool write_scales) {
+  (step2d<RLOG, BF16, ASYM, PASS, SBS>(X, blk_elem_off, gridW, d, c0, active, tid, pend, top, s_max, q_lo_blk, q_off,
+                                       scales_blk, zeros_off, gpart_blk, gpart_neg, s_amax, write_scales), ...);
 }
 
-template <int RLOG, bool BF16, bool ASYM>
+template <int RLOG, bool BF16, bool ASYM, int PASS>
 __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, uint8_t* __restrict__ q_lo,
                                                   float* __restrict__ scales, float* __restrict__ abot, int s, int d, int G,
-                                                  int gridW, int Kpad, size_t zeros_off) {
+                                                  int gridW, int Kpad, size_t zeros_off, SplitArgs sp) {
   constexpr int g = 1 << RLOG;
   constexpr int R = g * g;
   __shared__ __attribute__((aligned(16))) uint32_t s_max[2][kPartWords];
+  __shared__ uint32_t s_amax[PASS == 2 ? 2 * kMaxBlockRows : 1];
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int bi = j / G, bj = j - bi * G;
-  const int c0 = tid * 8;
-  const bool active = c0 < d;
+  const int c_lo = (PASS == 0) ? 0 : (int)blockIdx.z * sp.c_split;
+  const int c_hi = (PASS == 0) ? d : min(d, c_lo + sp.c_split);
+  const int c0 = c_lo + tid * 8;
+  const bool active = c0 < c_hi;
   const int k = G * G;
   const size_t tok0 = (size_t)b * s + (size_t)(bi * g) * gridW + (size_t)bj * g;  // first token of the block
   const size_t prow0 = (size_t)b * s + (size_t)j * R;                              // first physical row of the block
+  if constexpr (PASS == 2) gather_row_maxima<ASYM>(sp, prow0, R, tid, s_amax);
   float pend[4][8];
   float top[8];
-  run2d<RLOG, BF16, ASYM>(std::make_integer_sequence<int, (g == 4 ? 1 : 4)>{}, X, tok0 * d + c0, gridW, d, c0, active, tid,
-                          pend, top, s_max, q_lo + stamp_qlo_offset(prow0, 0, Kpad), (uint32_t)stamp_qlo_offset(0, c0, Kpad),
-                          scales + prow0, zeros_off);
-  if (active) {
+  uint32_t* gpart_blk = (PASS == 1) ? sp.gpart + (size_t)blockIdx.z * sp.part_rows + prow0 : nullptr;
+  run2d<RLOG, BF16, ASYM, PASS>(std::make_integer_sequence<int, (g == 4 ? 1 : 4)>{}, X, tok0 * d + c0, gridW, d, c0, active,
+                                tid, pend, top, s_max, q_lo + stamp_qlo_offset(prow0, 0, Kpad),
+                                (uint32_t)stamp_qlo_offset(0, c0, Kpad), scales + prow0, zeros_off, gpart_blk,
+                                (size_t)sp.nsplit * sp.part_rows, s_amax, PASS == 0 || blockIdx.z == 0);
+  if (active && PASS != 1) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
     o[1] = make_float4(top[4], top[5], top[6], top[7]);
@@ -661,43 +733,70 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
   }
 }
 
-template <int RLOG, bool BF16, bool ASYM>
-hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, float* scales, float* abot, int nthreads,
-                           hipStream_t st) {
+template <int RLOG, bool BF16, bool ASYM, int PASS>
+hipError_t launch_bottom1d_pass(const stamp_plan* p, const void* X, uint8_t* q_lo, float* scales, float* abot, int nthreads,
+                                const SplitArgs& sp, hipStream_t st) {
   const StampGeom& g = p->geom;
   const size_t lds = (size_t)8 * nthreads * (BF16 ? 16 : 32);  // staging buffer: 2 batches of 4 token rows
-  if (lds > 160 * 1024 - 1024) return hipErrorInvalidValue;
+  if (lds > 160 * 1024 - 2048) return hipErrorInvalidValue;
   static size_t attr_lds = 0;
   if (lds > attr_lds) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bottom1d<RLOG, BF16, ASYM>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bottom1d<RLOG, BF16, ASYM, PASS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_lds = lds;
   }
-  hipLaunchKernelGGL((k_bottom1d<RLOG, BF16, ASYM>), dim3(g.k, g.B), dim3(nthreads), lds, st, X, q_lo, scales, abot, g.s,
-                     g.d, g.k, p->Kpad, (size_t)g.B * g.s);
+  hipLaunchKernelGGL((k_bottom1d<RLOG, BF16, ASYM, PASS>), dim3(g.k, g.B, PASS == 0 ? 1 : sp.nsplit), dim3(nthreads), lds, st,
+                     X, q_lo, scales, abot, g.s, g.d, g.k, p->Kpad, (size_t)g.B * g.s, sp);
   return hipGetLastError();
+}
+
+// one pass when a workgroup can hold all channels, else maxima pass + quantization pass over channel splits
+template <int RLOG, bool BF16, bool ASYM>
+hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, float* scales, float* abot, int nthreads,
+                           const SplitArgs& sp, hipStream_t st) {
+  if (sp.nsplit == 1) return launch_bottom1d_pass<RLOG, BF16, ASYM, 0>(p, X, q_lo, scales, abot, nthreads, sp, st);
+  hipError_t e = launch_bottom1d_pass<RLOG, BF16, ASYM, 1>(p, X, q_lo, scales, abot, nthreads, sp, st);
+  if (e != hipSuccess) return e;
+  return launch_bottom1d_pass<RLOG, BF16, ASYM, 2>(p, X, q_lo, scales, abot, nthreads, sp, st);
 }
 
 }  // namespace
 
-hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
-                                 float* abot, uint32_t* rowmax, hipStream_t st, int part) {
+int stamp_actquant_nsplit(const stamp_plan* p) {
   const StampGeom& g = p->geom;
-  const int nthreads = ((g.d / 8 + 63) / 64) * 64;
+  const int dmax = (g.is2d || !g.x_bf16) ? 4096 : 8192;  // channels one workgroup can hold
+  return (g.d + dmax - 1) / dmax;
+}
+
+hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
+                                 float* abot, uint32_t* rowmax, uint32_t* gpart, hipStream_t st, int part) {
+  const StampGeom& g = p->geom;
+  SplitArgs sp;
+  sp.gpart = gpart;
+  sp.part_rows = (size_t)g.B * g.s;
+  sp.nsplit = stamp_actquant_nsplit(p);
+  sp.c_split = (sp.nsplit == 1) ? g.d : (((g.d + sp.nsplit - 1) / sp.nsplit + 511) / 512) * 512;
+  if (sp.nsplit > 1 && gpart == nullptr) return hipErrorInvalidValue;
+  const int nthreads = ((sp.c_split / 8 + 63) / 64) * 64;
   dim3 grid(g.k, g.B);
   const size_t zeros_off = (size_t)g.B * g.s;
 #define LAUNCH1D(RL)                                                                                      \
   do {                                                                                                    \
-    hipError_t le = g.asym ? (g.x_bf16 ? launch_bottom1d<RL, true, true>(p, X, q_lo, scales, abot, nthreads, st)     \
-                                       : launch_bottom1d<RL, false, true>(p, X, q_lo, scales, abot, nthreads, st))   \
-                           : (g.x_bf16 ? launch_bottom1d<RL, true, false>(p, X, q_lo, scales, abot, nthreads, st)    \
-                                       : launch_bottom1d<RL, false, false>(p, X, q_lo, scales, abot, nthreads, st)); \
+    hipError_t le = g.asym ? (g.x_bf16 ? launch_bottom1d<RL, true, true>(p, X, q_lo, scales, abot, nthreads, sp, st)     \
+                                       : launch_bottom1d<RL, false, true>(p, X, q_lo, scales, abot, nthreads, sp, st))   \
+                           : (g.x_bf16 ? launch_bottom1d<RL, true, false>(p, X, q_lo, scales, abot, nthreads, sp, st)    \
+                                       : launch_bottom1d<RL, false, false>(p, X, q_lo, scales, abot, nthreads, sp, st)); \
     if (le != hipSuccess) return le;                                                                      \
   } while (0)
+#define LAUNCH2D__(RL, BF, AS, PASS)                                                                      \
+  hipLaunchKernelGGL((k_bottom2d<RL, BF, AS, PASS>), dim3(g.k, g.B, PASS == 0 ? 1 : sp.nsplit), dim3(nthreads), 0, st, X, \
+                     q_lo, scales, abot, g.s, g.d, g.G, g.gridW, p->Kpad, zeros_off, sp)
 #define LAUNCH2D_(RL, BF, AS)                                                                             \
-  hipLaunchKernelGGL((k_bottom2d<RL, BF, AS>), grid, dim3(nthreads), 0, st, X, q_lo, scales, abot, g.s, g.d, g.G, g.gridW, \
-                     p->Kpad, zeros_off)
+  do {                                                                                                    \
+    if (sp.nsplit == 1) { LAUNCH2D__(RL, BF, AS, 0); }                                                    \
+    else { LAUNCH2D__(RL, BF, AS, 1); LAUNCH2D__(RL, BF, AS, 2); }                                        \
+  } while (0)
 #define LAUNCH2D(RL)                                                                                      \
   do {                                                                                                    \
     if (g.asym) { if (g.x_bf16) LAUNCH2D_(RL, true, true); else LAUNCH2D_(RL, false, true); }             \
@@ -725,6 +824,7 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
 #undef LAUNCH1D
 #undef LAUNCH2D
 #undef LAUNCH2D_
+#undef LAUNCH2D__
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (!(part & 2)) return hipSuccess;

@@ -42,7 +42,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   if (d->xform == STAMP_L_IDENTITY) return STAMP_ERR_UNSUPPORTED;
   if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
   if (d->w_dtype != STAMP_F32) return STAMP_ERR_UNSUPPORTED;
-  if (d->d_in % 32 != 0 || d->d_in > 8192) return STAMP_ERR_UNSUPPORTED;
+  if (d->d_in % 32 != 0 || d->d_in > 32768) return STAMP_ERR_UNSUPPORTED;  // wider than one workgroup holds: channel splits, two passes
   if (d->k_hi < 1 || d->k_hi > 256 || !is_pow2(d->k_hi)) return STAMP_ERR_UNSUPPORTED;
   const int R = d->seq_len / d->k_hi;
 
@@ -57,7 +57,6 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     g->r = ilog2(R);
     if (g->r < 3 || g->r > 7) return STAMP_ERR_UNSUPPORTED;
     if (d->levels < g->r) return STAMP_ERR_UNSUPPORTED;  // fewer levels than a block holds: 4-bit approximation rows
-    if (d->x_dtype == STAMP_F32 && d->d_in > 4096) return STAMP_ERR_UNSUPPORTED;  // LDS staging of fp32 rows
     *fused_ok = g->r <= 6;
   } else {
     if (d->grid_h != d->grid_w) return STAMP_ERR_UNSUPPORTED;
@@ -70,7 +69,6 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     g->gridW = d->grid_w;
     if (g->r < 2 || g->r > 3) return STAMP_ERR_UNSUPPORTED;
     if (d->levels < g->r) return STAMP_ERR_UNSUPPORTED;
-    if (d->d_in > 4096) return STAMP_ERR_UNSUPPORTED;
     *fused_ok = 1;
   }
   g->L = g->J - g->r;
@@ -83,6 +81,10 @@ void layout_workspace(stamp_plan* p) {
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   p->ws_abot = take((size_t)g.B * g.k * g.d * sizeof(float));
   p->ws_rowmax = take((size_t)2 * g.B * g.k * ((g.d + 31) / 32) * sizeof(uint32_t));  // partial row maxima (asymmetric: of both signs) per 32-channel slice
+  {
+    const int nsplit = stamp_actquant_nsplit(p);
+    p->ws_gpart = take(nsplit > 1 ? (size_t)2 * nsplit * g.B * g.s * sizeof(uint32_t) : 0);  // row maxima per channel split
+  }
   p->ws_qhi = take((size_t)g.B * g.k * g.d);
   p->ws_qlo = take((size_t)p->Mpad * (p->Kpad / 2));
   p->ws_scales = take((size_t)2 * g.B * g.s * sizeof(float));  // scales, then offsets (asymmetric plans)
@@ -245,7 +247,8 @@ stamp_status_t stamp_quantize_act(const stamp_plan_t* p, const void* X, int8_t* 
   if (!ws_ok(p, ws, ws_bytes, p->ws_qhi)) return STAMP_ERR_WORKSPACE;  // needs the block sums and row maxima only
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   hipError_t e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, reinterpret_cast<float*>(at(ws, p->ws_abot)),
-                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)), st);
+                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)),
+                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_gpart)), st);
   return e == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
 }
 
@@ -265,7 +268,8 @@ stamp_status_t stamp_linear_forward(const stamp_plan_t* p, const void* X, void* 
   uint8_t* q_lo = at(ws, p->ws_qlo);
   float* scales = reinterpret_cast<float*>(at(ws, p->ws_scales));
   hipError_t e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, reinterpret_cast<float*>(at(ws, p->ws_abot)),
-                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)), st);
+                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)),
+                                       reinterpret_cast<uint32_t*>(at(ws, p->ws_gpart)), st);
   if (e != hipSuccess) return STAMP_ERR_DEVICE;
   return forward_q(p, q_hi, q_lo, scales, Y, ws, st);
 }
@@ -314,14 +318,15 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   float* abot = reinterpret_cast<float*>(at(ws, p->ws_abot));
   uint32_t* rowmax = reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax));
+  uint32_t* gpart = reinterpret_cast<uint32_t*>(at(ws, p->ws_gpart));
   float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
   float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
   float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
   const bool fused = p->fused_ok && !p->unfused;
   hipError_t e = hipSuccess;
   switch (stage) {
-    case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 1); break;
-    case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, st, 2); break;
+    case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 1); break;
+    case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 2); break;
     case 2: e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st); break;
     case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit); break;
     case 4:

@@ -132,15 +132,17 @@ struct stamp_plan {
   int32_t unfused;          // 1: separate inverse kernel
   int32_t fused_ok;         // shape allows the fused epilogue
   // workspace layout (byte offsets, 256-aligned)
-  size_t ws_abot, ws_rowmax, ws_qhi, ws_qlo, ws_scales, ws_ythi, ws_P, ws_a6, ws_ytlo, ws_total;
+  size_t ws_abot, ws_rowmax, ws_gpart, ws_qhi, ws_qlo, ws_scales, ws_ythi, ws_P, ws_a6, ws_ytlo, ws_total;
 };
 
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
 hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStream_t st, uint32_t* colmax_tmp);
 // part: 1 = bottom kernel only, 2 = top + 8-bit rows only, 3 = both
 // scales: [B*s] scales, followed by [B*s] offsets z for asymmetric plans
+// gpart: [2][nsplit][B*s] partial row maxima when the channels are split over workgroups (nsplit > 1), else unused
+int stamp_actquant_nsplit(const stamp_plan* p);
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo,
-                                 float* scales, float* abot, uint32_t* rowmax, hipStream_t st, int part = 3);
+                                 float* scales, float* abot, uint32_t* rowmax, uint32_t* gpart, hipStream_t st, int part = 3);
 // mode: 0 = int32 accumulators in STaMP row order (debug), 1 = dequantized fp32 rows (hi -> Yt_hi
 // [hi_ksplit][B*k, N] partial rows, lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y.
 bool stamp_hi_wide_tiles(int M, int Npad);

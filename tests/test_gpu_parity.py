@@ -113,6 +113,29 @@ def test_partial_depth_cases(w):
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
+# Layers wider than one workgroup of the transform kernel holds (8192 bf16 channels in 1-D, 4096 for fp32
+# input and in 2-D): the channels are split over workgroups and the kernel runs twice (row maxima, then
+# codes).  Shapes of real layers: an LLM down-projection (d_in 11008 / 14336), the second MLP layer of an
+# image transformer on an 8 x 8-blocked grid (d_in 4608); ragged splits; both quantizer forms.
+WIDE = [
+    _wl("wide_1d_11008", batch=1, seq_len=256, levels=8, k_hi=8, d_in=11008, d_out=192, seed=61,
+        n_outlier_channels=30, outlier_scale=40.0),
+    _wl("wide_1d_14336_asym", batch=2, seq_len=128, levels=7, k_hi=16, d_in=14336, d_out=130, seed=62, act_quant="asym",
+        mean_shift=0.5, n_outlier_channels=40),
+    _wl("wide_1d_f32in_4128", batch=1, seq_len=256, levels=8, k_hi=4, d_in=4128, d_out=128, x_dtype="f32", seed=63),
+    _wl("wide_2d_4608", batch=1, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=4, d_in=4608,
+        d_out=160, corr_len=4.0, seed=64, n_outlier_channels=12),
+    _wl("wide_2d_blk4_8224_asym", batch=1, seq_len=64, xform="haar2d", levels=3, grid_h=8, grid_w=8, k_hi=4, d_in=8224,
+        d_out=64, corr_len=2.0, seed=65, act_quant="asym", mean_shift=-0.3),
+]
+
+
+@pytest.mark.parametrize("w", WIDE, ids=[w.name for w in WIDE])
+def test_wide_layers_channel_split(w):
+    r = tl.full_case(w, with_bias=True)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
 def test_bf16_output_and_bias():
     tl.full_case(_wl("bf16_out", batch=2, seq_len=256, levels=8, k_hi=8, d_in=256, d_out=384, seed=31),
                  with_bias=True, y_dtype="bf16")
