@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--act-quant", choices=["sym", "asym"], default="sym",
                     help="activation quantizer: symmetric absmax (the benchmark configurations) or the paper's "
                          "asymmetric min-max form")
+    ap.add_argument("--d-in", type=int, default=0, help="override the workload's d_in (e.g. the layer that follows it)")
+    ap.add_argument("--d-out", type=int, default=0, help="override the workload's d_out")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (int32 add), the "
                          "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -120,7 +122,8 @@ def main():
 
     st.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = get_workload(args.workload, act_quant=args.act_quant)
+    over = {k: v for k, v in (("d_in", args.d_in), ("d_out", args.d_out)) if v > 0}
+    w = get_workload(args.workload, act_quant=args.act_quant, **over)
     log(f"generating {w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out}")
     inp = make_inputs(w)
     Xd = tl.to_device_x(inp, w)

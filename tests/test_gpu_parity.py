@@ -282,6 +282,17 @@ def test_full_size_image_tokens_three_levels():
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_full_size_second_mlp_layer(name):
+    """The layer that follows cfg2 / cfg4 in its model (d_in and d_out swapped: 11008 -> 4096 on the LLM stream,
+    4608 -> 1152 on the 64 x 64 grid): wider than one workgroup of the transform kernel holds."""
+    base = get_workload(name)
+    w = get_workload(name, d_in=base.d_out, d_out=base.d_in, seed=base.seed + 50)
+    r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 64, 13), check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
 @pytest.mark.timeout(900)
 def test_full_size_cfg3():
     w = get_workload("cfg3")
