@@ -216,6 +216,29 @@ def main():
                       "dominant_kernel": {"name": "k_bottom", "achieved": lo_gbs, "frac": lo_gbs / PEAK_HBM_GBS,
                                           "bytes_per_launch": lo_bytes, "avg_launch_ms": stages["transform_quant_lo"]}}
 
+    # The same layer without the sequence transform (identity plan: per-token quantization of X itself, the same
+    # k tokens at 8 bits, same GEMM engines and epilogue stores): what the transform and its inverse cost here.
+    # The paper reports this cost only as +4.8 % latency of one whole denoising step on an A100 (3-level DWT around
+    # floating-point layers), so its figure is context, not a baseline for this number.
+    from dataclasses import replace as _replace
+    wi = _replace(w, xform="identity", levels=0, grid_h=0, grid_w=0)
+    plan_i = st.StampPlan(tl.plan_desc_for(wi, "bf16"), torch.from_numpy(inp["W"]).cuda())
+    plan_i.set_gemm_engine(args.engine)
+    ws_i = plan_i.alloc_workspace()
+    for _ in range(args.warmup):
+        plan_i.linear_forward(Xd, Y, ws_i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan_i.linear_forward(Xd, Y, ws_i)
+    torch.cuda.synchronize()
+    ident_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    plan_i.destroy()
+    del ws_i
+    log(f"same layer without the sequence transform: {ident_ms:.3f} ms/step")
+    transform_cost = {"ms_per_step_without_transform": ident_ms, "overhead_frac": ms_per_step / ident_ms - 1.0,
+                      "what": "identity plan: same quantizer, bit allocation, GEMM engine and stores, no Haar transform / inverse"}
+
     out = {
         "metric": "tokens/sec through STaMP linear fwd", "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -226,7 +249,7 @@ def main():
                    "path": "unfused" if args.unfused else "fused", "gemm_engine": args.engine,
                    "act_quant": args.act_quant},
         "roofline": roofline, f"roofline_{other}_engine": roofline_other, "roofline_quant": roofline_quant,
-        "stages_ms": stages,
+        "stages_ms": stages, "transform_cost": transform_cost,
     }
     if not args.no_cpu_baseline:
         log("cpu baseline (oracle)")

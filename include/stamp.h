@@ -78,6 +78,10 @@ typedef enum {
 } stamp_status_t;
 
 typedef enum { STAMP_F32 = 0, STAMP_BF16 = 1 } stamp_dtype_t;
+/* Sequence transform L.  STAMP_L_IDENTITY: none (levels = 0), for the layers the paper leaves
+ * un-transformed (Experiments set-up: inputs without sequence structure) and as the baseline the
+ * transform's cost is measured against: tokens are quantized as they are, the first k_hi of every
+ * sequence at bits_hi, STaMP order = physical row order = token order, nothing is inverted. */
 typedef enum { STAMP_L_IDENTITY = 0, STAMP_L_HAAR1D = 1, STAMP_L_HAAR2D = 2 } stamp_xform_t;
 /* Activation quantizer (Background, Eq. 1), per transformed token i with b bits:
  *   STAMP_ACT_SYMMETRIC   a = max_j |t_ij|, scale = a / (2^(b-1) - 1), code = rne(t * (1 / scale)) in
@@ -108,6 +112,7 @@ typedef struct {
 } stamp_plan_desc_t;
 
 /* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):
+ *   xform IDENTITY with levels 0, any seq_len and 0 <= k_hi <= 256; or
  *   xform HAAR1D with seq_len/k_hi in {8,16,32,64,128}, or HAAR2D with a square grid and
  *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels J >= log2(seq_len/k_hi) (2-D: log4), i.e.
  *   k_hi >= the number of level-J approximations, so that every 4-bit token is a wavelet coefficient
@@ -152,7 +157,8 @@ stamp_status_t stamp_linear_forward_q(const stamp_plan_t* plan, const int8_t* q_
                                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* Step 4 alone: Y = L^-1 Yt for Yt_dev [batch, seq_len, n_cols] fp32 in STaMP order; adds the
- * plan's bias when n_cols == d_out and a bias was given; Y_dev [batch, seq_len, n_cols] y_dtype. */
+ * plan's bias when n_cols == d_out and a bias was given; Y_dev [batch, seq_len, n_cols] y_dtype.
+ * STAMP_ERR_UNSUPPORTED for a plan without transform. */
 stamp_status_t stamp_inverse(const stamp_plan_t* plan, const float* Yt_dev, int32_t n_cols,
                              void* Y_dev, void* workspace_dev, size_t workspace_bytes,
                              void* hip_stream);
@@ -177,7 +183,9 @@ stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* plan, int8_t* qW_hos
  *   4 GEMM of the 4-bit rows (with the fused inverse unless the plan is set unfused)
  *   5 in-block inverse kernel (unfused plans only)
  *   6 conversion of the packed 4-bit rows to the FP6 engine's operand layout (FP6 engine only; with
- *     that engine stage 4 is the GEMM alone and reads what stage 6 wrote to the workspace) */
+ *     that engine stage 4 is the GEMM alone and reads what stage 6 wrote to the workspace)
+ * Plans without transform: 0 the quantization kernel, 2 GEMM of the 8-bit rows, 3 their output pass,
+ * 6 and 4 as above; 1 and 5 return STAMP_ERR_UNSUPPORTED. */
 stamp_status_t stamp_debug_run_stage(const stamp_plan_t* plan, int32_t stage, const void* X_dev,
                                      int8_t* q_hi_dev, uint8_t* q_lo_dev, float* scales_dev,
                                      void* Y_dev, void* workspace_dev, size_t workspace_bytes,

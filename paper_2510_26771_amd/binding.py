@@ -220,7 +220,8 @@ class StampPlan:
     def alloc_act_buffers(self, device="cuda"):
         import torch
         d = self.desc
-        q_hi = torch.empty((d.batch, d.k_hi, d.d_in), dtype=torch.int8, device=device)
+        # at least one row, so that the pointer is valid when a plan without transform keeps no 8-bit token
+        q_hi = torch.empty((d.batch, max(d.k_hi, 1), d.d_in), dtype=torch.int8, device=device)
         mp = -(-(d.batch * d.seq_len) // 256) * 256
         kp = -(-d.d_in // 128) * 128
         q_lo = torch.zeros(mp * kp // 2, dtype=torch.uint8, device=device)  # tiled, see include/stamp.h

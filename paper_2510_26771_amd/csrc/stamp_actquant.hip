@@ -733,6 +733,83 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Plans without a sequence transform (the layers the paper leaves un-transformed, and the baseline the
+// transform's cost is measured against): per-token quantization of X itself (Background, Eq. 1), tokens
+// 0..k-1 of every sequence at 8 bits, the rest at 4 bits.  One workgroup per token: the row is read twice
+// (range, then codes; the second read comes from cache).
+// ------------------------------------------------------------------------------------------
+template <bool BF16, bool ASYM>
+__global__ __launch_bounds__(256) void k_quant_rows(const void* __restrict__ X, int8_t* __restrict__ q_hi,
+                                                    uint8_t* __restrict__ q_lo, float* __restrict__ scales, int s, int d,
+                                                    int k, int Kpad, size_t zeros_off) {
+  __shared__ uint32_t s_red[8];
+  const int pr = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const size_t m = (size_t)b * s + pr;
+  const size_t xoff = m * (size_t)d;
+  uint32_t mpos = 0u, mneg = 0u;
+  for (int c = tid * 8; c < d; c += 256 * 8) {
+    float v[8];
+    load8(X, xoff + c, BF16, true, v);
+    if constexpr (ASYM) {
+      uint32_t pos, neg;
+      row_posneg_bits(v, pos, neg);
+      mpos = max(mpos, pos);
+      mneg = max(mneg, neg);
+    } else {
+      mpos = max(mpos, row_absmax_bits(v));
+    }
+  }
+  mpos = wave_max_u32(mpos);
+  mneg = wave_max_u32(mneg);
+  if ((tid & 63) == 0) { s_red[tid >> 6] = mpos; s_red[4 + (tid >> 6)] = mneg; }
+  __syncthreads();
+  const float a = __uint_as_float(max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3])));
+  const float nlo = __uint_as_float(max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7])));
+  const bool hi = pr < k;
+  const float qmax = ASYM ? (hi ? 255.0f : 15.0f) : (hi ? 127.0f : 7.0f);
+  const float range = ASYM ? __fadd_rn(a, nlo) : a;
+  float scale = 0.0f, inv = 0.0f, z = 0.0f;
+  if (range > 0.0f) {
+    scale = __fdiv_rn(range, qmax);
+    inv = __fdiv_rn(qmax, range);
+  }
+  if constexpr (ASYM) z = rintf(__fmul_rn(nlo, inv));
+  if (tid == 0) {
+    scales[m] = scale;
+    if constexpr (ASYM) scales[zeros_off + m] = z;
+  }
+  for (int c = tid * 8; c < d; c += 256 * 8) {
+    float v[8];
+    load8(X, xoff + c, BF16, true, v);
+    if (hi) {
+      const float qlo = ASYM ? 0.0f : -127.0f, qhi = ASYM ? 255.0f : 127.0f, shift = ASYM ? 128.0f : 0.0f;
+      uint32_t w[2] = {0u, 0u};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float q = __fadd_rn(rintf(__fmul_rn(v[i], inv)), z);
+        q = fminf(fmaxf(q, qlo), qhi) - shift;
+        w[i >> 2] |= ((uint32_t)((int)q) & 0xFFu) << (8 * (i & 3));
+      }
+      *reinterpret_cast<uint2*>(q_hi + ((size_t)b * k + pr) * d + c) = make_uint2(w[0], w[1]);
+    } else {
+      float pq[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pq[i] = __fmul_rn(v[i], inv);
+      uint32_t w;
+      if constexpr (ASYM) {
+        const float lo = -z, hib = 15.0f - z;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pq[i] = __builtin_amdgcn_fmed3f(pq[i], lo, hib);
+        w = pack8_uint4(pq, z);
+      } else {
+        w = pack8_int4(pq);
+      }
+      *reinterpret_cast<uint32_t*>(q_lo + stamp_qlo_offset(m, c, Kpad)) = w;
+    }
+  }
+}
+
 template <int RLOG, bool BF16, bool ASYM, int PASS>
 hipError_t launch_bottom1d_pass(const stamp_plan* p, const void* X, uint8_t* q_lo, float* scales, float* abot, int nthreads,
                                 const SplitArgs& sp, hipStream_t st) {
@@ -765,6 +842,7 @@ hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, fl
 
 int stamp_actquant_nsplit(const stamp_plan* p) {
   const StampGeom& g = p->geom;
+  if (g.ident) return 1;
   const int dmax = (g.is2d || !g.x_bf16) ? 4096 : 8192;  // channels one workgroup can hold
   return (g.d + dmax - 1) / dmax;
 }
@@ -772,6 +850,19 @@ int stamp_actquant_nsplit(const stamp_plan* p) {
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
                                  float* abot, uint32_t* rowmax, uint32_t* gpart, hipStream_t st, int part) {
   const StampGeom& g = p->geom;
+  if (g.ident) {
+    if (!(part & 1)) return hipSuccess;
+    const dim3 grid_rows(g.s, g.B);
+    const size_t zoff = (size_t)g.B * g.s;
+    if (g.asym) {
+      if (g.x_bf16) hipLaunchKernelGGL((k_quant_rows<true, true>), grid_rows, dim3(256), 0, st, X, q_hi, q_lo, scales, g.s, g.d, g.k, p->Kpad, zoff);
+      else hipLaunchKernelGGL((k_quant_rows<false, true>), grid_rows, dim3(256), 0, st, X, q_hi, q_lo, scales, g.s, g.d, g.k, p->Kpad, zoff);
+    } else {
+      if (g.x_bf16) hipLaunchKernelGGL((k_quant_rows<true, false>), grid_rows, dim3(256), 0, st, X, q_hi, q_lo, scales, g.s, g.d, g.k, p->Kpad, zoff);
+      else hipLaunchKernelGGL((k_quant_rows<false, false>), grid_rows, dim3(256), 0, st, X, q_hi, q_lo, scales, g.s, g.d, g.k, p->Kpad, zoff);
+    }
+    return hipGetLastError();
+  }
   SplitArgs sp;
   sp.gpart = gpart;
   sp.part_rows = (size_t)g.B * g.s;

@@ -36,22 +36,31 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     side = d->grid_h < d->grid_w ? d->grid_h : d->grid_w;
     J = ilog2(side);
     if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
+  } else if (d->levels != 0) {
+    return STAMP_ERR_SHAPE;  // no transform, no levels
   }
 
   // ---- valid STaMP settings from here on; what follows is what this library implements ----
-  if (d->xform == STAMP_L_IDENTITY) return STAMP_ERR_UNSUPPORTED;
   if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
   if (d->w_dtype != STAMP_F32) return STAMP_ERR_UNSUPPORTED;
   if (d->d_in % 32 != 0 || d->d_in > 32768) return STAMP_ERR_UNSUPPORTED;  // wider than one workgroup holds: channel splits, two passes
-  if (d->k_hi < 1 || d->k_hi > 256 || !is_pow2(d->k_hi)) return STAMP_ERR_UNSUPPORTED;
-  const int R = d->seq_len / d->k_hi;
-
   memset(g, 0, sizeof(*g));
   g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
-  g->J = d->levels; g->k = d->k_hi; g->R = R;
+  g->J = d->levels; g->k = d->k_hi;
   g->x_bf16 = d->x_dtype == STAMP_BF16;
   g->y_bf16 = d->y_dtype == STAMP_BF16;
   g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
+  if (d->xform == STAMP_L_IDENTITY) {
+    // tokens quantized as they are: any number of 8-bit tokens (none included), no blocks, no inverse
+    if (d->k_hi > 256) return STAMP_ERR_UNSUPPORTED;
+    g->ident = 1;
+    g->R = 1;
+    *fused_ok = 1;
+    return STAMP_OK;
+  }
+  if (d->k_hi < 1 || d->k_hi > 256 || !is_pow2(d->k_hi)) return STAMP_ERR_UNSUPPORTED;
+  const int R = d->seq_len / d->k_hi;
+  g->R = R;
   if (d->xform == STAMP_L_HAAR1D) {
     g->is2d = 0;
     g->r = ilog2(R);
@@ -107,6 +116,20 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
                          void* ws, hipStream_t st) {
   float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
   float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
+  if (p->geom.ident) {
+    // no transform: the 8-bit rows' GEMM (partial rows) + their output pass, then the 4-bit rows straight to Y
+    if (p->geom.k > 0) {
+      if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
+      if (stamp_launch_hi_rows_out(p, ythi, Y, st, p->hi_ksplit) != hipSuccess) return STAMP_ERR_DEVICE;
+    }
+    if (p->geom.k == p->geom.s) return STAMP_OK;
+    if (p->engine == STAMP_GEMM_FP6) {
+      uint8_t* a6i = at(ws, p->ws_a6);
+      if (stamp_launch_repack6(p, q_lo, a6i, st) != hipSuccess) return STAMP_ERR_DEVICE;
+      return stamp_launch_gemm_lo6(p, a6i, scales, 3, Y, nullptr, st) == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+    }
+    return stamp_launch_gemm_lo(p, q_lo, scales, 3, Y, nullptr, st) == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+  }
   if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
   if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit) != hipSuccess) return STAMP_ERR_DEVICE;
   const bool fused = p->fused_ok && !p->unfused;
@@ -169,8 +192,11 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   // physical row of every STaMP slot
   p->row_of_coeff = static_cast<int32_t*>(malloc(sizeof(int32_t) * (size_t)g.s));
   if (p->row_of_coeff == nullptr) { delete p; return STAMP_ERR_ALLOC; }
-  for (int q = 0; q < g.k; ++q) p->row_of_coeff[q] = q * g.R;
-  for (int j = 0; j < g.k; ++j)
+  if (g.ident)
+    for (int q = 0; q < g.s; ++q) p->row_of_coeff[q] = q;
+  else
+    for (int q = 0; q < g.k; ++q) p->row_of_coeff[q] = q * g.R;
+  for (int j = 0; j < g.k && !g.ident; ++j)
     for (int e = 1; e < g.R; ++e) {
       const int slot = g.is2d ? stamp_slot_of_block_e_2d(j / g.G, j % g.G, e, g.G) : stamp_slot_of_block_e_1d(j, e, g.k);
       p->row_of_coeff[slot] = j * g.R + e;
@@ -278,6 +304,7 @@ stamp_status_t stamp_inverse(const stamp_plan_t* p, const float* Yt, int32_t n_c
                              void* hip_stream) {
   if (p == nullptr || Yt == nullptr || Y == nullptr) return STAMP_ERR_NULL;
   if (n_cols < 1) return STAMP_ERR_SHAPE;
+  if (p->geom.ident) return STAMP_ERR_UNSUPPORTED;  // nothing to invert
   const size_t need = (size_t)p->geom.B * p->geom.k * (size_t)n_cols * sizeof(float);
   if (!ws_ok(p, ws, ws_bytes, need)) return STAMP_ERR_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
@@ -293,7 +320,7 @@ stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* p, const int8_t* q_hi, c
   if (p == nullptr || q_hi == nullptr || q_lo == nullptr || acc == nullptr) return STAMP_ERR_NULL;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   // accumulator mode never reads the activation scales
-  if (stamp_launch_gemm_hi(p, q_hi, nullptr, 0, acc, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (p->geom.k > 0 && stamp_launch_gemm_hi(p, q_hi, nullptr, 0, acc, st) != hipSuccess) return STAMP_ERR_DEVICE;
   if (p->engine == STAMP_GEMM_FP6) {
     // parity aid, not a timed path: the converted operand lives in a temporary of its own
     uint8_t* a6 = nullptr;
@@ -324,6 +351,22 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
   float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
   const bool fused = p->fused_ok && !p->unfused;
   hipError_t e = hipSuccess;
+  if (p->geom.ident) {
+    // stages of a plan without a transform: 0 quantization, 2 the 8-bit rows' GEMM, 3 their output pass,
+    // 6 FP6 conversion, 4 the 4-bit rows' GEMM; 1 and 5 do not exist
+    switch (stage) {
+      case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 1); break;
+      case 2: if (p->geom.k > 0) e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st); break;
+      case 3: e = stamp_launch_hi_rows_out(p, ythi, Y, st, p->hi_ksplit); break;
+      case 4:
+        if (p->engine == STAMP_GEMM_FP6) e = stamp_launch_gemm_lo6(p, at(ws, p->ws_a6), scales, 3, Y, nullptr, st);
+        else e = stamp_launch_gemm_lo(p, q_lo, scales, 3, Y, nullptr, st);
+        break;
+      case 6: e = stamp_launch_repack6(p, q_lo, at(ws, p->ws_a6), st); break;
+      default: return STAMP_ERR_UNSUPPORTED;
+    }
+    return e == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+  }
   switch (stage) {
     case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 1); break;
     case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 2); break;

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   constexpr int stage = bytesA + bytesB;
   constexpr int nA = 256 * chA / NT;            // A chunks per thread per step (256 rows * chA / NT threads)
   constexpr int kMainBytes = 2 * stage;
-  constexpr int kRowInfoOff = (EPI == 2 && kTileBytes > kMainBytes) ? kTileBytes : kMainBytes;
+  constexpr int kRowInfoOff = (EPI >= 2 && kTileBytes > kMainBytes) ? kTileBytes : kMainBytes;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
   const int wm = wave / WN, wn = wave % WN;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
@@ -238,7 +238,7 @@ template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16, int WN>
 hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
   constexpr int BN = 64 * WN;
   constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
-  constexpr size_t epi_lds = (EPI == 2) ? (size_t)(2 * WN * kWaveTileBytes) : 0;
+  constexpr size_t epi_lds = (EPI >= 2) ? (size_t)(2 * WN * kWaveTileBytes) : 0;
   constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + kRowInfoBytes;  // + per-row factors, destinations, offsets
   static bool attr_set = false;
   if (!attr_set) {
@@ -256,7 +256,7 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
 template <bool A_INT4, int EPI, int RB, bool IS2D>
 hipError_t launch(const GemmArgs& a, hipStream_t st) {
   // the output type only matters to the fused epilogue
-  if constexpr (EPI == 2) {
+  if constexpr (EPI >= 2) {
     if (a.g.y_bf16) return launch_y<A_INT4, EPI, RB, IS2D, true, 2>(a, st);
   }
   if constexpr (!A_INT4) {
@@ -291,6 +291,7 @@ bool stamp_hi_wide_tiles(int M, int Npad) {
 // over 2..4 workgroups (partial rows, added by the top inverse).
 int stamp_hi_ksplit(const stamp_plan* p) {
   const int M = p->geom.B * p->geom.k;
+  if (M == 0) return 1;
   const int mt = (M + stamp_gemm::BM - 1) / stamp_gemm::BM;
   const int tiles = mt * (p->Npad / (stamp_hi_wide_tiles(M, p->Npad) ? 256 : 128));
   const int KT = p->Kpad / stamp_gemm::BK;
@@ -348,6 +349,7 @@ hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const 
   a.P = P;
   if (mode == 0) return launch<true, 0, 0, false>(a, st);
   if (mode == 1) return launch<true, 1, 0, false>(a, st);
+  if (mode == 3) return launch<true, 3, 0, false>(a, st);
   if (mode != 2) return hipErrorInvalidValue;
   const StampGeom& g = p->geom;
   if (!g.is2d) {

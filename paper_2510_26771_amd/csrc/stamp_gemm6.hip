@@ -135,7 +135,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   using Acc = AccF6Lo;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   constexpr int kMainBytes = kNumStage6 * kStage6;
-  constexpr int kRowInfoOff = (EPI == 2 && kTileBytes6 > kMainBytes) ? kTileBytes6 : kMainBytes;
+  constexpr int kRowInfoOff = (EPI >= 2 && kTileBytes6 > kMainBytes) ? kTileBytes6 : kMainBytes;
   constexpr int nA = kStageA6 / (512 * 16), nB = 2 * kStageB6 / (512 * 16);  // 16-byte chunks per thread and step: 3 and 3
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
 template <int EPI, int RB, bool IS2D, bool YBF16>
 hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
   constexpr size_t main_lds = (size_t)kNumStage6 * kStage6;
-  constexpr size_t epi_lds = (EPI == 2) ? (size_t)kTileBytes6 : 0;
+  constexpr size_t epi_lds = (EPI >= 2) ? (size_t)kTileBytes6 : 0;
   constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + kRowInfoBytes;
   static bool attr_set = false;
   if (!attr_set) {
@@ -283,7 +283,7 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
 
 template <int EPI, int RB, bool IS2D>
 hipError_t launch(const GemmArgs& a, hipStream_t st) {
-  if constexpr (EPI == 2) {
+  if constexpr (EPI >= 2) {
     if (a.g.y_bf16) return launch_y<EPI, RB, IS2D, true>(a, st);
   }
   return launch_y<EPI, RB, IS2D, false>(a, st);
@@ -317,6 +317,7 @@ hipError_t stamp_launch_gemm_lo6(const stamp_plan* p, const uint8_t* a6, const f
   a.P = P;
   if (mode == 0) return launch<0, 0, false>(a, st);
   if (mode == 1) return launch<1, 0, false>(a, st);
+  if (mode == 3) return launch<3, 0, false>(a, st);
   if (mode != 2) return hipErrorInvalidValue;
   const StampGeom& g = p->geom;
   if (!g.is2d) {

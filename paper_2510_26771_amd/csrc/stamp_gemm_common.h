@@ -229,7 +229,7 @@ struct EpiOperands {
   f8 bias;
   f8 top[2][ES::npass];
   __device__ __forceinline__ void request(const GemmArgs& a, int m0, int n0, int lane, int wm, int wn) {
-    if constexpr (EPI == 2) {
+    if constexpr (EPI == 2 || EPI == 3) {
       const int c8 = (lane & 7) * 8, ug = lane >> 3, l32 = lane & 31;
       const int nw = n0 + wn * 64;
 #pragma unroll
@@ -242,6 +242,7 @@ struct EpiOperands {
       const f4 b0 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8) : zero;
       const f4 b1 = (a.bias != nullptr) ? *reinterpret_cast<const f4*>(a.bias + nw + c8 + 4) : zero;
       bias = (f8){b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+      if constexpr (EPI == 2) {
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
 #pragma unroll
@@ -252,6 +253,7 @@ struct EpiOperands {
           const f4 p0 = *reinterpret_cast<const f4*>(src), p1 = *reinterpret_cast<const f4*>(src + 4);
           top[hf][pass] = (f8){p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
         }
+      }
       }
     }
   }
@@ -271,7 +273,26 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
   float fac = 0.0f, rz = 0.0f;
   int dst = -1;
   const size_t zeros_off = (size_t)g.B * g.s;
-  if (m < a.M) {
+  if (m < a.M && g.ident) {
+    // no sequence transform: row = token, level 0 (norm 1); tokens 0..k-1 of a sequence are the 8-bit rows
+    size_t row;
+    bool mine;
+    if constexpr (Acc::kLoRows) {
+      row = (size_t)m;
+      mine = (m % g.s) >= g.k;
+    } else {
+      const int b = m / g.k;
+      row = (size_t)b * g.s + (size_t)(m - b * g.k);
+      mine = true;
+    }
+    if (mine) {
+      if constexpr (EPI != 0) {
+        fac = a.scales[row] * Acc::kToAcc;
+        if (g.asym) rz = (a.scales[zeros_off + row] - Acc::kZeroShift) * (1.0f / Acc::kToAcc);
+      }
+      dst = (Acc::kLoRows || EPI == 0) ? (int)row : m;
+    }
+  } else if (m < a.M) {
     if constexpr (Acc::kLoRows) {
       const int b = m / g.s, pr = m - b * g.s;
       const int j = pr / g.R, e = pr - j * g.R;
@@ -309,7 +330,8 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
 // `wave` of the workgroup owns rows [128 wm, +128) and columns [64 wn, +64) of the tile.
 // EPI: 0 = integer sums to STaMP-ordered rows [B*s][N] int32; 1 = dequantized fp32 rows (4-bit rows:
 // physical rows of [B*s][N]; 8-bit rows: [B*k][N]); 2 = fused in-block inverse + bias -> Y (4-bit
-// rows only); RB = log2 of the block length for EPI 2 (1-D: tokens, 2-D: side).
+// rows only); RB = log2 of the block length for EPI 2 (1-D: tokens, 2-D: side); 3 = plans without a
+// sequence transform: dequantized rows + bias -> Y through the same staging (4-bit rows only).
 template <typename Acc, int EPI, int RB, bool IS2D, bool YBF16>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&acc)[4][NI], uint8_t* smem,
                                          const uint8_t* row_info, const EpiOperands<EPI, RB, IS2D>& eo, int m0,
@@ -348,8 +370,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
     // fused: per half of 64 rows, scale by the row factors into this wave's LDS tile [64][kEpiStride]; then the wave's
     // 8 groups of 8 lanes each take one unit and 8 columns per lane, and run the depth-first inverse,
     // storing the unit's tokens.
-    using ES = EpiShape<RB, IS2D>;
-    constexpr int R = ES::R, M0 = ES::M0, U = ES::U, npass = ES::npass;
+    using ES = EpiShape<(EPI == 2 ? RB : 3), IS2D>;
+    [[maybe_unused]] constexpr int R = ES::R, M0 = ES::M0, U = ES::U, npass = ES::npass;
     float* s_tile = reinterpret_cast<float*>(smem) + wave * (64 * kEpiStride);
     const int c8 = (lane & 7) * 8, ug = lane >> 3;
     // staging position of this lane's accumulator column 32 ni + l32 = 8 j + t (see tile_row)
@@ -418,6 +440,16 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         asm volatile("" ::: "memory");
+        if constexpr (EPI == 3) {
+          // identity plans: the staged rows are the output rows; 8 lanes write one row's 64 columns
+          o.offset = eo.bias;
+#pragma unroll
+          for (int pass = 0; pass < 8; ++pass) {
+            const int rw = pass * 8 + ug;
+            const int dst = s_rowdst[wm * 128 + hf * 64 + rw];
+            if (dst >= 0 && n < a.N) o.put((size_t)dst * a.N + n, tile_row(s_tile + 4 * (lane & 7), rw));
+          }
+        } else {
 #pragma unroll
         for (int pass = 0; pass < npass; ++pass) {
           const int unit = pass * 8 + ug;
@@ -457,6 +489,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
               dfs1d<RB, M0, M0, 0, OutOct<YBF16, VEC>>(tile, h, top, o);
             }
           }
+        }
         }
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0xC07F);  // this wave's reads of the tile are done before the next half overwrites it

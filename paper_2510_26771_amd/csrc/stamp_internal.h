@@ -29,6 +29,7 @@ struct StampGeom {
   int32_t x_bf16;    // input dtype is bf16
   int32_t y_bf16;    // output dtype is bf16
   int32_t asym;      // asymmetric activation codes: stored code - 2^(b-1), offsets z next to the scales
+  int32_t ident;     // no sequence transform: tokens 0..k-1 are the 8-bit rows, physical row = token (J = r = 0, R = 1)
 };
 
 // Position inside a block ("e", 0 = the block sum, e >= 1 the in-block detail rows in STaMP
@@ -144,7 +145,8 @@ int stamp_actquant_nsplit(const stamp_plan* p);
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo,
                                  float* scales, float* abot, uint32_t* rowmax, uint32_t* gpart, hipStream_t st, int part = 3);
 // mode: 0 = int32 accumulators in STaMP row order (debug), 1 = dequantized fp32 rows (hi -> Yt_hi
-// [hi_ksplit][B*k, N] partial rows, lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y.
+// [hi_ksplit][B*k, N] partial rows, lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y,
+// 3 = lo rows of an identity plan: dequantized + bias -> Y.
 bool stamp_hi_wide_tiles(int M, int Npad);
 int stamp_hi_ksplit(const stamp_plan* p);
 hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode,
@@ -159,6 +161,8 @@ hipError_t stamp_launch_weight_quant6(const stamp_plan* p, const float* W, const
 hipError_t stamp_launch_repack6(const stamp_plan* p, const uint8_t* q_lo, uint8_t* a6, hipStream_t st);
 hipError_t stamp_launch_gemm_lo6(const stamp_plan* p, const uint8_t* a6, const float* scales, int mode, void* out,
                                  const float* P, hipStream_t st);
+// identity plans: 8-bit rows' dequantized partial rows [nparts][B*k][N] (+ bias) -> Y rows of tokens 0..k-1
+hipError_t stamp_launch_hi_rows_out(const stamp_plan* p, const float* Yt_hi, void* Y, hipStream_t st, int nparts);
 // P: block sums [B*k][ldP]; nparts partial sources (each B*k*ncols floats apart) are added while reading
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* Yt_hi, int hi_row_stride_is_stamp,
                                     int ncols, float* P, int ldP, hipStream_t st, int nparts = 1);

@@ -157,6 +157,33 @@ __global__ __launch_bounds__(256) void k_inverse_bottom(const float* __restrict_
 
 }  // namespace
 
+namespace {
+// identity plans: sum of the partial dequantized 8-bit rows + bias -> rows of tokens 0..k-1 of Y
+__global__ __launch_bounds__(256) void k_hi_rows_out(const float* __restrict__ src, int nparts, size_t part_stride,
+                                                     const float* __restrict__ bias, void* __restrict__ Y, int k, int s, int N,
+                                                     int y_bf16) {
+  const int row = blockIdx.y;  // b * k + p
+  const int b = row / k, p = row - b * k;
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  const size_t idx = (size_t)row * N + n;
+  float v = src[idx];
+  for (int part = 1; part < nparts; ++part) v += src[idx + part * part_stride];
+  if (bias != nullptr) v += bias[n];
+  const size_t o = ((size_t)b * s + p) * N + n;
+  if (y_bf16) reinterpret_cast<uint16_t*>(Y)[o] = f32_to_bf16_rne(v);
+  else reinterpret_cast<float*>(Y)[o] = v;
+}
+}  // namespace
+
+hipError_t stamp_launch_hi_rows_out(const stamp_plan* p, const float* Yt_hi, void* Y, hipStream_t st, int nparts) {
+  const StampGeom& g = p->geom;
+  if (g.k == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_hi_rows_out, dim3((g.N + 255) / 256, g.B * g.k), dim3(256), 0, st, Yt_hi, nparts,
+                     (size_t)g.B * g.k * (size_t)g.N, p->bias_dev, Y, g.k, g.s, g.N, g.y_bf16);
+  return hipGetLastError();
+}
+
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* src, int src_is_stamp, int ncols, float* P,
                                     int ldP, hipStream_t st, int nparts) {
   const StampGeom& g = p->geom;

@@ -53,8 +53,11 @@ def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):
     row = plan.row_of_coeff().astype(np.int64)
     assert sorted(row.tolist()) == list(range(d.seq_len)), "row_of_coeff is not a permutation"
     k = d.k_hi
-    assert np.array_equal(row[:k], np.arange(k) * (d.seq_len // k))
-    qh = q_hi.cpu().numpy()
+    if d.xform == XFORM_CODE["identity"]:
+        assert np.array_equal(row, np.arange(d.seq_len))  # no transform: STaMP order is token order
+    else:
+        assert np.array_equal(row[:k], np.arange(k) * (d.seq_len // k))
+    qh = q_hi.cpu().numpy()[:, :k]
     # q_lo is tiled [Mp/256][Kp/128][256 rows][64 bytes] (include/stamp.h): back to [batch, seq_len, d/2]
     mp = -(-(d.batch * d.seq_len) // 256) * 256
     kp = -(-d.d_in // 128) * 128

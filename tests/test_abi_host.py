@@ -67,7 +67,8 @@ def _good(**kw):
     (dict(bits_lo=3), 3),
     (dict(d_in=48), 3),                                       # d_in not a multiple of 32
     (dict(d_in=32800), 3),                                    # wider than the channel splits go
-    (dict(xform=st.STAMP_L_IDENTITY, levels=0), 3),
+    (dict(xform=st.STAMP_L_IDENTITY, levels=2), 2),          # no transform has no levels
+    (dict(xform=st.STAMP_L_IDENTITY, levels=0, k_hi=300, seq_len=512), 3),   # more than 256 8-bit tokens
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=4, k_hi=8), 3),   # k not a power of four
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=32, grid_w=8, levels=3, k_hi=16), 3),   # non-square grid
     (dict(w_dtype=st.STAMP_BF16), 3),

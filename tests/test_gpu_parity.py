@@ -136,6 +136,99 @@ def test_wide_layers_channel_split(w):
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
+# Plans without a sequence transform: the layers the paper leaves un-transformed and the baseline the
+# transform's cost is measured against.  Per-token quantization of X itself, tokens 0..k-1 at 8 bits (k any
+# number, none included), ragged shapes, both quantizer forms, both engines, bf16 and fp32 output.
+IDENT = [
+    _wl("ident_k8", xform="identity", levels=0, batch=3, seq_len=200, k_hi=8, d_in=160, d_out=300, seed=71),
+    _wl("ident_k0", xform="identity", levels=0, batch=2, seq_len=256, k_hi=0, d_in=256, d_out=130, seed=72),
+    _wl("ident_k5_asym", xform="identity", levels=0, batch=2, seq_len=333, k_hi=5, d_in=96, d_out=257, seed=73,
+        act_quant="asym", mean_shift=0.6),
+    _wl("ident_f32in_wide", xform="identity", levels=0, batch=1, seq_len=128, k_hi=64, d_in=8800, d_out=64, x_dtype="f32",
+        seed=74, first_token_scale=100.0),
+]
+
+
+@pytest.mark.parametrize("w", IDENT, ids=[w.name for w in IDENT])
+def test_identity_transform_cases(w):
+    r = tl.full_case(w, with_bias=True, check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    tl.full_case(w, with_bias=True, check_unfused=False, y_dtype="bf16", check_acc=False)
+
+
+def _random_workload(seed: int) -> Workload:
+    """A valid plan drawn from the whole supported set (shape, transform, depth, quantizer form)."""
+    rng = np.random.default_rng(1000 + seed)
+    kind = rng.choice(["haar1d", "haar2d", "identity"], p=[0.5, 0.35, 0.15])
+    d_in = int(rng.integers(1, 25)) * 32
+    d_out = int(rng.integers(1, 520))
+    batch = int(rng.integers(1, 4))
+    kw = dict(batch=batch, d_in=d_in, d_out=d_out, seed=2000 + seed, x_dtype=str(rng.choice(["bf16", "f32"])),
+              act_quant=str(rng.choice(["sym", "asym"])), mean_shift=float(rng.choice([0.0, 0.5, -1.0])),
+              n_outlier_channels=int(rng.integers(0, 4)), outlier_scale=25.0)
+    if kind == "haar1d":
+        r = int(rng.integers(3, 8))               # block of 8..128 tokens
+        lk = int(rng.integers(0, 5))              # 1..16 8-bit tokens
+        s = (1 << r) << lk
+        return _wl(f"rnd{seed}_1d_r{r}_k{1 << lk}", xform="haar1d", seq_len=s, k_hi=1 << lk,
+                   levels=int(rng.integers(r, r + lk + 1)), **kw)
+    if kind == "haar2d":
+        r = int(rng.integers(2, 4))               # 4 x 4 or 8 x 8 token blocks
+        lg = int(rng.integers(0, 3))              # 1, 4 or 16 blocks
+        side = (1 << r) << lg
+        return _wl(f"rnd{seed}_2d_b{1 << r}_g{side}", xform="haar2d", seq_len=side * side, grid_h=side, grid_w=side,
+                   k_hi=1 << (2 * lg), levels=int(rng.integers(r, r + lg + 1)), corr_len=float(rng.choice([2.0, 6.0])), **kw)
+    return _wl(f"rnd{seed}_ident", xform="identity", levels=0, seq_len=int(rng.integers(1, 400)),
+               k_hi=0, **kw) if rng.random() < 0.3 else \
+        _wl(f"rnd{seed}_ident_k", xform="identity", levels=0, seq_len=int(rng.integers(40, 400)),
+            k_hi=int(rng.integers(1, 40)), **kw)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_valid_plans(seed):
+    """Seeded sweep over the supported set: every plan the library accepts must meet the same bars."""
+    w = _random_workload(seed)
+    rng = np.random.default_rng(3000 + seed)
+    r = tl.full_case(w, with_bias=bool(rng.integers(0, 2)), y_dtype=str(rng.choice(["f32", "bf16"])),
+                     check_unfused=w.xform != "identity")
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+def test_forward_under_hip_graph_capture():
+    """stamp_linear_forward only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+    memset): it can be captured into a HIP graph, and every replay reproduces the eager result bit for bit."""
+    import torch
+    import paper_2510_26771_amd as st
+    for w in (_wl("graph_1d", batch=2, seq_len=512, levels=9, k_hi=16, d_in=160, d_out=300, seed=81),
+              _wl("graph_2d", batch=1, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=4, d_in=96,
+                  d_out=128, seed=82, act_quant="asym")):
+        inp = make_inputs(w, with_bias=True)
+        plan = st.StampPlan(tl.plan_desc_for(w, "bf16"), torch.from_numpy(inp["W"]).cuda(),
+                            torch.from_numpy(inp["bias"]).cuda())
+        X = tl.to_device_x(inp, w)
+        ws = plan.alloc_workspace()
+        Y_eager = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=torch.int16, device="cuda")
+        plan.linear_forward(X, Y_eager, ws)           # also sets the kernels' attributes before the capture
+        torch.cuda.synchronize()
+        Y = torch.zeros_like(Y_eager)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            plan.linear_forward(X, Y, ws)             # warm-up on the capture stream
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                plan.linear_forward(X, Y, ws)
+        torch.cuda.current_stream().wait_stream(side)
+        for it in range(3):
+            Y.fill_(-1)                               # eager work and a synchronisation between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Y, Y_eager), f"{w.name}: replay {it} differs from the eager result"
+        plan.destroy()
+
+
 def test_bf16_output_and_bias():
     tl.full_case(_wl("bf16_out", batch=2, seq_len=256, levels=8, k_hi=8, d_in=256, d_out=384, seed=31),
                  with_bias=True, y_dtype="bf16")
