@@ -156,6 +156,14 @@ def test_identity_transform_cases(w):
     tl.full_case(w, with_bias=True, check_unfused=False, y_dtype="bf16", check_acc=False)
 
 
+def test_many_rows_few_channels():
+    """2^18 token rows (1024 row tiles, several rounds of workgroups on every XCD), narrow layer: the tile numbering,
+    the row-indexed buffers and the 64-bit offsets at a row count 8 times the benchmark's."""
+    w = _wl("many_rows", batch=32, seq_len=8192, levels=13, k_hi=128, d_in=64, d_out=96, seed=91)
+    r = tl.full_case(w, with_bias=True, y_dtype="bf16", check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
 def _random_workload(seed: int) -> Workload:
     """A valid plan drawn from the whole supported set (shape, transform, depth, quantizer form)."""
     rng = np.random.default_rng(1000 + seed)
