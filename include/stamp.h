@@ -40,12 +40,14 @@
  *     diagonal], each row-major.
  *   The quantized activation is stored in the plan's PHYSICAL row order (a permutation of STaMP
  *   order chosen so that one GEMM tile holds whole Haar sub-trees); stamp_plan_row_of_coeff
- *   returns it.  With R = seq_len / k_hi and physical row r of sequence b:
+ *   returns it.  With n_top = stamp_plan_hi_rows(plan) (k_hi, or the number of level-J approximations if
+ *   that is larger), R = seq_len / n_top and physical row r of sequence b:
  *     scales  [batch, seq_len] float: scale of the coefficient at physical row r.  Plans with
  *             act_quant = STAMP_ACT_ASYMMETRIC use a buffer of [2][batch, seq_len] floats: the
  *             scales, then the integer offsets z (as floats) in the same order.
- *     q_hi    [batch, k_hi, d_in] int8: the 8-bit tokens; STaMP slot p < k_hi is row p of q_hi
- *             (its physical row is p*R).
+ *     q_hi    [batch, n_top, d_in] int8: STaMP slot p < n_top is row p of q_hi (its physical row is
+ *             p*R): the k_hi 8-bit tokens and, when the transform leaves more approximations than
+ *             k_hi, the remaining approximations, whose 4-bit codes are held as int8 values.
  *     q_lo    the 4-bit tokens at their physical row, two channels per byte (two's complement
  *             nibbles, low nibble = even channel), tiled for the GEMM: with m = b*seq_len + r the
  *             row over all sequences, Kp = d_in rounded up to 128 and Mp = batch*seq_len rounded
@@ -113,10 +115,11 @@ typedef struct {
 
 /* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):
  *   xform IDENTITY with levels 0, any seq_len and 0 <= k_hi <= 256; or
- *   xform HAAR1D with seq_len/k_hi in {8,16,32,64,128}, or HAAR2D with a square grid and
- *   seq_len/k_hi in {16,64} (4x4 or 8x8 token blocks); levels J >= log2(seq_len/k_hi) (2-D: log4), i.e.
- *   k_hi >= the number of level-J approximations, so that every 4-bit token is a wavelet coefficient
- *   (full depth, or e.g. the 3-level transform of a 64x64 grid with k_hi = 64); bits 8/4/4;
+ *   xform HAAR1D or HAAR2D (square grid) of any depth J, with n_top = max(k_hi, approximations left by J
+ *   levels) <= 256 and seq_len/n_top in {8,16,32,64,128} (1-D) or {16,64} (2-D: 4x4 or 8x8 token blocks);
+ *   k_hi a power of two (four in 2-D) when k_hi >= the number of approximations, any 0 <= k_hi below it
+ *   (e.g. the 3-level transform of 2048 tokens with 64 8-bit tokens: 256 approximations, 192 of them at
+ *   4 bits); bits 8/4/4;
  *   d_in a multiple of 32 and at most 32768 (above 8192, or 4096 for fp32 input or 2-D grids, the transform
  *   + quantization kernel splits the channels over workgroups and reads X twice: row ranges, then codes);
  *   k_hi <= 256; act_quant symmetric or asymmetric. */
@@ -134,6 +137,10 @@ stamp_status_t stamp_plan_destroy(stamp_plan_t* plan);
 
 /* Bytes of workspace any entry point below may need (256-byte aligned pointer expected). */
 size_t stamp_plan_workspace_bytes(const stamp_plan_t* plan);
+
+/* Rows per sequence of the q_hi buffer: max(k_hi, number of approximation coefficients the J-level
+ * transform leaves); k_hi for plans without transform; 0 for a NULL plan. */
+int32_t stamp_plan_hi_rows(const stamp_plan_t* plan);
 
 /* host_out[p] = physical row (0 <= row < seq_len) of STaMP slot p; a permutation. */
 stamp_status_t stamp_plan_row_of_coeff(const stamp_plan_t* plan, int32_t* host_out);

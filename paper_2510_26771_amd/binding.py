@@ -19,7 +19,8 @@ STATUS_NAMES = {0: "STAMP_OK", 1: "STAMP_ERR_NULL", 2: "STAMP_ERR_SHAPE", 3: "ST
                 4: "STAMP_ERR_WORKSPACE", 5: "STAMP_ERR_ALLOC", 6: "STAMP_ERR_DEVICE"}
 
 # every symbol include/stamp.h declares
-EXPORTS = ["stamp_plan_create", "stamp_plan_destroy", "stamp_plan_workspace_bytes", "stamp_plan_row_of_coeff",
+EXPORTS = ["stamp_plan_create", "stamp_plan_destroy", "stamp_plan_workspace_bytes", "stamp_plan_hi_rows",
+           "stamp_plan_row_of_coeff",
            "stamp_quantize_act", "stamp_linear_forward", "stamp_linear_forward_q", "stamp_inverse",
            "stamp_debug_gemm_acc", "stamp_debug_weight_codes", "stamp_debug_run_stage", "stamp_plan_set_unfused", "stamp_plan_set_gemm_engine",
            "stamp_debug_mfma_rate", "stamp_status_string"]
@@ -85,6 +86,8 @@ def load_library():
     lib.stamp_plan_destroy.restype = C.c_int
     lib.stamp_plan_workspace_bytes.argtypes = [vp]
     lib.stamp_plan_workspace_bytes.restype = sz
+    lib.stamp_plan_hi_rows.argtypes = [vp]
+    lib.stamp_plan_hi_rows.restype = i32
     lib.stamp_plan_row_of_coeff.argtypes = [vp, C.POINTER(i32)]
     lib.stamp_plan_row_of_coeff.restype = C.c_int
     lib.stamp_quantize_act.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
@@ -165,6 +168,10 @@ class StampPlan:
     def workspace_bytes(self) -> int:
         return int(self.lib.stamp_plan_workspace_bytes(self._h))
 
+    def hi_rows(self) -> int:
+        """Rows per sequence of the q_hi buffer (k_hi, or the number of approximations if that is larger)."""
+        return int(self.lib.stamp_plan_hi_rows(self._h))
+
     def row_of_coeff(self):
         import numpy as np
         out = np.empty(self.desc.seq_len, dtype=np.int32)
@@ -220,8 +227,8 @@ class StampPlan:
     def alloc_act_buffers(self, device="cuda"):
         import torch
         d = self.desc
-        # at least one row, so that the pointer is valid when a plan without transform keeps no 8-bit token
-        q_hi = torch.empty((d.batch, max(d.k_hi, 1), d.d_in), dtype=torch.int8, device=device)
+        # at least one row, so that the pointer is valid when a plan keeps no 8-bit token at all
+        q_hi = torch.empty((d.batch, max(self.hi_rows(), 1), d.d_in), dtype=torch.int8, device=device)
         mp = -(-(d.batch * d.seq_len) // 256) * 256
         kp = -(-d.d_in // 128) * 128
         q_lo = torch.zeros(mp * kp // 2, dtype=torch.uint8, device=device)  # tiled, see include/stamp.h

@@ -681,7 +681,8 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
 // zeros_off floats behind the row's scale.
 __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop, const uint32_t* __restrict__ rowmax_part,
                                                   int nslices, int8_t* __restrict__ q_hi, float* __restrict__ scales,
-                                                  int k, int d, int s, int R, int asym, size_t npart, size_t zeros_off) {
+                                                  int k, int khi, int d, int s, int R, int asym, size_t npart,
+                                                  size_t zeros_off) {
   __shared__ uint32_t s_red[8];
   const int p = blockIdx.x, b = blockIdx.y;
   {
@@ -698,17 +699,20 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
   }
   const float a = __uint_as_float(max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3])));
   const float nlo = __uint_as_float(max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7])));
+  // rows beyond the first khi are 4-bit rows (same data path, codes held as int8)
+  const bool row8 = p < khi;
+  const float qmax_s = row8 ? 127.0f : 7.0f, qmax_u = row8 ? 255.0f : 15.0f;
   float scale = 0.0f, inv = 0.0f, z = 0.0f;
   if (!asym) {
     if (a > 0.0f) {
-      scale = __fdiv_rn(a, 127.0f);
-      inv = __fdiv_rn(127.0f, a);
+      scale = __fdiv_rn(a, qmax_s);
+      inv = __fdiv_rn(qmax_s, a);
     }
   } else {
     const float range = __fadd_rn(a, nlo);
     if (range > 0.0f) {
-      scale = __fdiv_rn(range, 255.0f);
-      inv = __fdiv_rn(255.0f, range);
+      scale = __fdiv_rn(range, qmax_u);
+      inv = __fdiv_rn(qmax_u, range);
     }
     z = rintf(__fmul_rn(nlo, inv));
   }
@@ -716,7 +720,7 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
     scales[(size_t)b * s + (size_t)p * R] = scale;
     if (asym) scales[zeros_off + (size_t)b * s + (size_t)p * R] = z;
   }
-  const float qlo = asym ? 0.0f : -127.0f, qhi = asym ? 255.0f : 127.0f, shift = asym ? 128.0f : 0.0f;
+  const float qlo = asym ? 0.0f : -qmax_s, qhi = asym ? qmax_u : qmax_s, shift = asym ? (row8 ? 128.0f : 8.0f) : 0.0f;
   const float* src = ttop + ((size_t)b * k + p) * d;
   int8_t* dst = q_hi + ((size_t)b * k + p) * d;
   for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
@@ -926,7 +930,7 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
                      npart);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, nslices, q_hi, scales, g.k, g.d, g.s, g.R,
+  hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, nslices, q_hi, scales, g.k, g.khi, g.d, g.s, g.R,
                      g.asym, npart, zeros_off);
   return hipGetLastError();
 }

@@ -46,7 +46,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   if (d->d_in % 32 != 0 || d->d_in > 32768) return STAMP_ERR_UNSUPPORTED;  // wider than one workgroup holds: channel splits, two passes
   memset(g, 0, sizeof(*g));
   g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
-  g->J = d->levels; g->k = d->k_hi;
+  g->J = d->levels; g->k = g->khi = d->k_hi;
   g->x_bf16 = d->x_dtype == STAMP_BF16;
   g->y_bf16 = d->y_dtype == STAMP_BF16;
   g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
@@ -58,26 +58,45 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     *fused_ok = 1;
     return STAMP_OK;
   }
-  if (d->k_hi < 1 || d->k_hi > 256 || !is_pow2(d->k_hi)) return STAMP_ERR_UNSUPPORTED;
-  const int R = d->seq_len / d->k_hi;
-  g->R = R;
+  // Blocks.  With at least as many 8-bit tokens as level-J approximations, the blocks hold seq_len / k_hi tokens
+  // (the top part runs the remaining levels over the k_hi block sums).  With fewer, the blocks hold the 2^J
+  // (4^J) tokens of one approximation, the top part is the approximations themselves, and those beyond the
+  // first k_hi are 4-bit rows that stay with the 8-bit rows' data path (4-bit codes held as int8).
   if (d->xform == STAMP_L_HAAR1D) {
     g->is2d = 0;
-    g->r = ilog2(R);
+    const int na = d->seq_len >> d->levels;
+    if (d->k_hi >= na) {
+      if (d->k_hi < 1 || !is_pow2(d->k_hi)) return STAMP_ERR_UNSUPPORTED;
+      g->k = g->khi = d->k_hi;
+    } else {
+      g->k = na;
+      g->khi = d->k_hi;
+    }
+    if (g->k > 256) return STAMP_ERR_UNSUPPORTED;
+    g->R = d->seq_len / g->k;
+    g->r = ilog2(g->R);
     if (g->r < 3 || g->r > 7) return STAMP_ERR_UNSUPPORTED;
-    if (d->levels < g->r) return STAMP_ERR_UNSUPPORTED;  // fewer levels than a block holds: 4-bit approximation rows
     *fused_ok = g->r <= 6;
   } else {
     if (d->grid_h != d->grid_w) return STAMP_ERR_UNSUPPORTED;
-    const int lk = ilog2(d->k_hi);
-    if (lk % 2 != 0) return STAMP_ERR_UNSUPPORTED;  // k must be a power of four
+    const int sa = side >> d->levels;  // approximations per grid side
+    if (d->k_hi >= sa * sa) {
+      const int lk = ilog2(d->k_hi);
+      if (d->k_hi < 1 || !is_pow2(d->k_hi) || lk % 2 != 0) return STAMP_ERR_UNSUPPORTED;  // k must be a power of four
+      g->G = 1 << (lk / 2);
+      g->k = g->khi = d->k_hi;
+    } else {
+      g->G = sa;
+      g->k = sa * sa;
+      g->khi = d->k_hi;
+    }
+    if (g->k > 256) return STAMP_ERR_UNSUPPORTED;
     g->is2d = 1;
-    g->G = 1 << (lk / 2);
+    g->R = d->seq_len / g->k;
     g->g = side / g->G;
     g->r = ilog2(g->g);
     g->gridW = d->grid_w;
     if (g->r < 2 || g->r > 3) return STAMP_ERR_UNSUPPORTED;
-    if (d->levels < g->r) return STAMP_ERR_UNSUPPORTED;
     *fused_ok = 1;
   }
   g->L = g->J - g->r;
@@ -246,6 +265,8 @@ stamp_status_t stamp_plan_destroy(stamp_plan_t* p) {
 }
 
 size_t stamp_plan_workspace_bytes(const stamp_plan_t* p) { return p ? p->ws_total : 0; }
+
+int32_t stamp_plan_hi_rows(const stamp_plan_t* p) { return p ? p->geom.k : 0; }
 
 stamp_status_t stamp_plan_set_unfused(stamp_plan_t* p, int32_t unfused) {
   if (p == nullptr) return STAMP_ERR_NULL;

@@ -315,7 +315,8 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
       if constexpr (EPI != 0) {
         const size_t row = (size_t)b * g.s + (size_t)p * g.R;
         fac = a.scales[row] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
-        if (g.asym) rz = (a.scales[zeros_off + row] - Acc::kZeroShift) * (1.0f / Acc::kToAcc);
+        // top rows beyond the first khi carry 4-bit codes: their stored form is code - 8
+        if (g.asym) rz = (a.scales[zeros_off + row] - (p < g.khi ? Acc::kZeroShift : 8.0f)) * (1.0f / Acc::kToAcc);
       }
       dst = (EPI == 0) ? (b * g.s + p) : m;
     }

@@ -22,7 +22,8 @@ struct StampGeom {
   int32_t L;         // top levels J - r: levels applied to the k block sums (0 = the block sums themselves)
   int32_t r;         // bottom levels (inside a block)
   int32_t R;         // tokens per block: 2^r (1-D) or 4^r (2-D)
-  int32_t k;         // number of blocks per sequence = k_hi
+  int32_t k;         // number of blocks per sequence = rows of the top part (held as int8 codes, q_hi)
+  int32_t khi;       // how many of them are 8-bit rows (k_hi); the others carry 4-bit codes (J < log2(seq_len / k_hi))
   int32_t G;         // 2-D: blocks per grid side (k = G*G); 1-D: unused (0)
   int32_t g;         // 2-D: tokens per block side (2^r); 1-D: unused (0)
   int32_t gridW;     // 2-D: tokens per grid row

@@ -52,8 +52,10 @@ def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):
     d = plan.desc
     row = plan.row_of_coeff().astype(np.int64)
     assert sorted(row.tolist()) == list(range(d.seq_len)), "row_of_coeff is not a permutation"
-    k = d.k_hi
+    k = plan.hi_rows()  # rows kept in q_hi: the 8-bit tokens and any further approximation coefficients
+    assert k >= d.k_hi
     if d.xform == XFORM_CODE["identity"]:
+        assert k == d.k_hi
         assert np.array_equal(row, np.arange(d.seq_len))  # no transform: STaMP order is token order
     else:
         assert np.array_equal(row[:k], np.arange(k) * (d.seq_len // k))
@@ -69,8 +71,8 @@ def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):
     codes[:, k:] = unpack_int4(ql[:, row[k:]])
     if d.act_quant:
         assert sc.shape == (2, d.batch, d.seq_len)
-        codes[:, :k] += 128
-        codes[:, k:] += 8
+        codes[:, :d.k_hi] += 128
+        codes[:, d.k_hi:] += 8
         assert codes.min() >= 0
         return codes.astype(np.uint8), sc[0][:, row], sc[1][:, row]
     return codes.astype(np.int8), sc[:, row], None

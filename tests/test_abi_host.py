@@ -61,7 +61,7 @@ def _good(**kw):
     (dict(bits_hi=9), 2),
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=8, levels=3), 2),   # grid != seq_len
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=5), 2),  # too many levels
-    (dict(levels=3), 3),                                      # fewer levels than a block of seq_len/k_hi = 32 tokens holds
+    (dict(seq_len=4096, levels=3), 3),                        # 512 approximations: more than the top part holds
     (dict(k_hi=12), 3),                                       # k not a power of two
     (dict(k_hi=128), 3),                                      # blocks of 2 tokens
     (dict(bits_lo=3), 3),

@@ -107,6 +107,22 @@ PARTIAL = [
 ]
 
 
+# Fewer 8-bit tokens than the transform leaves approximations (the paper's language-model setting: 3 levels,
+# 64 8-bit tokens, so of the s / 8 approximations only the first 64 are 8-bit): the blocks are the 2^J (4^J) tokens
+# of one approximation, and the 4-bit approximations travel with the 8-bit rows.  k_hi need not be a power of two.
+FEWER_HI = [
+    _wl("few_1d_J3_k8", batch=2, seq_len=512, levels=3, k_hi=8, d_in=128, d_out=192, seed=57),
+    _wl("few_1d_J4_k5_asym", batch=2, seq_len=1024, levels=4, k_hi=5, d_in=160, d_out=300, seed=58, act_quant="asym",
+        mean_shift=0.4),
+    _wl("few_1d_J5_k0", batch=1, seq_len=2048, levels=5, k_hi=0, d_in=96, d_out=130, seed=59),
+    _wl("few_2d_J2_k16", batch=1, seq_len=1024, xform="haar2d", levels=2, grid_h=32, grid_w=32, k_hi=16, d_in=96,
+        d_out=128, corr_len=6.0, seed=60),
+    _wl("few_2d_J3_k3_asym", batch=2, seq_len=4096, xform="haar2d", levels=3, grid_h=64, grid_w=64, k_hi=3, d_in=64,
+        d_out=72, corr_len=8.0, seed=66, act_quant="asym", mean_shift=-0.5),
+]
+PARTIAL = PARTIAL + FEWER_HI
+
+
 @pytest.mark.parametrize("w", PARTIAL, ids=[w.name for w in PARTIAL])
 def test_partial_depth_cases(w):
     r = tl.full_case(w, with_bias=True)
@@ -178,12 +194,18 @@ def _random_workload(seed: int) -> Workload:
         r = int(rng.integers(3, 8))               # block of 8..128 tokens
         lk = int(rng.integers(0, 5))              # 1..16 8-bit tokens
         s = (1 << r) << lk
+        if rng.random() < 0.3:                    # fewer 8-bit tokens than approximations: blocks = 2^J tokens
+            return _wl(f"rnd{seed}_1d_J{r}_few", xform="haar1d", seq_len=s, k_hi=int(rng.integers(0, 1 << lk)),
+                       levels=r, **kw)
         return _wl(f"rnd{seed}_1d_r{r}_k{1 << lk}", xform="haar1d", seq_len=s, k_hi=1 << lk,
                    levels=int(rng.integers(r, r + lk + 1)), **kw)
     if kind == "haar2d":
         r = int(rng.integers(2, 4))               # 4 x 4 or 8 x 8 token blocks
         lg = int(rng.integers(0, 3))              # 1, 4 or 16 blocks
         side = (1 << r) << lg
+        if rng.random() < 0.3:
+            return _wl(f"rnd{seed}_2d_J{r}_few", xform="haar2d", seq_len=side * side, grid_h=side, grid_w=side,
+                       k_hi=int(rng.integers(0, 1 << (2 * lg))), levels=r, corr_len=4.0, **kw)
         return _wl(f"rnd{seed}_2d_b{1 << r}_g{side}", xform="haar2d", seq_len=side * side, grid_h=side, grid_w=side,
                    k_hi=1 << (2 * lg), levels=int(rng.integers(r, r + lg + 1)), corr_len=float(rng.choice([2.0, 6.0])), **kw)
     return _wl(f"rnd{seed}_ident", xform="identity", levels=0, seq_len=int(rng.integers(1, 400)),
@@ -192,7 +214,7 @@ def _random_workload(seed: int) -> Workload:
             k_hi=int(rng.integers(1, 40)), **kw)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(32))
 def test_random_valid_plans(seed):
     """Seeded sweep over the supported set: every plan the library accepts must meet the same bars."""
     w = _random_workload(seed)
@@ -391,6 +413,15 @@ def test_full_size_second_mlp_layer(name):
     base = get_workload(name)
     w = get_workload(name, d_in=base.d_out, d_out=base.d_in, seed=base.seed + 50)
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 64, 13), check_unfused=False)
+    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+
+
+@pytest.mark.timeout(600)
+def test_full_size_llm_three_levels_64_hi_tokens():
+    """cfg2's shape in the setting of the paper's language-model experiments: 3 levels, 64 8-bit tokens (of the 256
+    approximations the first 64 are 8-bit, the other 192 are 4-bit rows), asymmetric min-max quantizer."""
+    w = get_workload("cfg2", levels=3, act_quant="asym")
+    r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 14), check_unfused=False)
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
