@@ -224,6 +224,65 @@ def test_random_valid_plans(seed):
     assert r["code_mismatches"] == r["near_boundary_mismatches"]
 
 
+def test_one_plan_two_streams_distinct_workspaces():
+    """A plan is read-only in stamp_linear_forward: two streams may run it at the same time on different inputs,
+    each with its own workspace, and get what the calls give one after the other."""
+    import torch
+    import paper_2510_26771_amd as st
+    w = _wl("two_streams", batch=4, seq_len=2048, levels=11, k_hi=64, d_in=512, d_out=768, seed=83)
+    inp = make_inputs(w, with_bias=True)
+    plan = st.StampPlan(tl.plan_desc_for(w, "bf16"), torch.from_numpy(inp["W"]).cuda(),
+                        torch.from_numpy(inp["bias"]).cuda())
+    X1 = tl.to_device_x(inp, w)
+    X2 = (X1.float() * -0.5 + 0.25).to(X1.dtype)
+    ws1, ws2 = plan.alloc_workspace(), plan.alloc_workspace()
+    shape = (w.batch, w.seq_len, w.d_out)
+    ref1 = torch.zeros(shape, dtype=torch.int16, device="cuda")
+    ref2 = torch.zeros_like(ref1)
+    plan.linear_forward(X1, ref1, ws1)
+    plan.linear_forward(X2, ref2, ws1)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for it in range(3):
+        Y1 = torch.zeros_like(ref1)
+        Y2 = torch.zeros_like(ref1)
+        torch.cuda.synchronize()
+        for _ in range(4):  # several calls back to back, so that the two streams really overlap
+            plan.linear_forward(X1, Y1, ws1, stream=s1)
+            plan.linear_forward(X2, Y2, ws2, stream=s2)
+        torch.cuda.synchronize()
+        assert torch.equal(Y1, ref1) and torch.equal(Y2, ref2), f"round {it}"
+    plan.destroy()
+
+
+def test_non_finite_input_does_not_fault():
+    """NaN / Inf activations: the result is unspecified, but every kernel runs to completion (no data-dependent
+    addressing anywhere on the path) and the next call on clean input is correct."""
+    import torch
+    import paper_2510_26771_amd as st
+    for w in (_wl("nonfinite_1d", batch=2, seq_len=256, levels=8, k_hi=8, d_in=128, d_out=136, seed=84),
+              _wl("nonfinite_2d_asym", batch=1, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=4,
+                  d_in=96, d_out=64, seed=85, act_quant="asym")):
+        inp = make_inputs(w)
+        plan = st.StampPlan(tl.plan_desc_for(w, "f32"), torch.from_numpy(inp["W"]).cuda())
+        ws = plan.alloc_workspace()
+        X = tl.to_device_x(inp, w)
+        Y = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=torch.float32, device="cuda")
+        plan.linear_forward(X, Y, ws)
+        torch.cuda.synchronize()
+        good = Y.clone()
+        Xb = X.clone()
+        Xb[0, 3, 5] = float("nan")
+        Xb[0, 100, 7] = float("inf")
+        Xb[-1, 17, 0] = float("-inf")
+        plan.linear_forward(Xb, Y, ws)
+        torch.cuda.synchronize()            # completes without a fault
+        plan.linear_forward(X, Y, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, good)
+        plan.destroy()
+
+
 def test_forward_under_hip_graph_capture():
     """stamp_linear_forward only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
     memset): it can be captured into a HIP graph, and every replay reproduces the eager result bit for bit."""
