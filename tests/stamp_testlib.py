@@ -95,7 +95,9 @@ def near_boundary_mask(T: np.ndarray, bits: np.ndarray, asym: bool) -> np.ndarra
 
 
 def compare_codes(gpu_codes, gpu_scales, gpu_zeros, ora: Dict[str, np.ndarray]) -> Dict[str, int]:
-    """Scales (and offsets) must match bit for bit; codes may differ only on near-boundary elements, by one step."""
+    """Scales, offsets and codes must match the oracle bit for bit.  Both sides round the same fp32 products, so even
+    the elements that sit within 1 ulp of a rounding boundary agree; if that ever fails, the message says how many
+    of the mismatches are such elements (those the bar would tolerate) and how many are not."""
     assert gpu_scales.dtype == np.float32
     bad_scales = int(np.count_nonzero(gpu_scales.view(np.uint32) != ora["scales"].view(np.uint32)))
     assert bad_scales == 0, f"{bad_scales} scales differ from the oracle"
@@ -105,14 +107,12 @@ def compare_codes(gpu_codes, gpu_scales, gpu_zeros, ora: Dict[str, np.ndarray]) 
     assert gpu_codes.dtype == ora["codes"].dtype
     diff = gpu_codes.astype(np.int16) - ora["codes"].astype(np.int16)
     n_mis = int(np.count_nonzero(diff))
-    n_near = 0
     if n_mis:
         near = near_boundary_mask(ora["T"], ora["bits"][None, :].repeat(gpu_codes.shape[0], 0), asym)
-        outside = (diff != 0) & ~near
-        assert not outside.any(), f"{int(outside.sum())} code mismatches away from a rounding boundary"
-        assert np.abs(diff).max() <= 1
-        n_near = n_mis
-    return {"code_mismatches": n_mis, "near_boundary_mismatches": n_near}
+        outside = int(((diff != 0) & ~near).sum())
+        raise AssertionError(f"{n_mis} codes differ from the oracle: {n_mis - outside} within 1 ulp of a rounding "
+                             f"boundary, {outside} away from one; largest step {int(np.abs(diff).max())}")
+    return {"code_mismatches": 0, "near_boundary_mismatches": 0}
 
 
 def run_oracle(w: Workload, inp: dict, cols: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
@@ -197,14 +197,12 @@ def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: 
 
     if check_acc:
         if w.act_quant == "asym":
-            # the library multiplies the STORED codes, code - 2^(b-1) (of the codes the GPU produced)
+            # the library multiplies the STORED codes, code - 2^(b-1)
             shift = np.where(np.arange(w.seq_len) < w.k_hi, 128, 8).astype(np.int16)
-            stored = codes.astype(np.int16) - shift[None, :, None]
+            stored = ora["codes"].astype(np.int16) - shift[None, :, None]
             ref_acc = np.stack([so.int_gemm(stored[b], ora["qw"][:, sel]) for b in range(w.batch)])
-        elif report["code_mismatches"] == 0:
+        else:
             ref_acc = ora["acc"]
-        else:  # compare on the codes the GPU actually used (they differ only at counted boundaries)
-            ref_acc = np.stack([so.int_gemm(codes[b], ora["qw"][:, sel]) for b in range(w.batch)])
         for engine in engines:
             plan.set_gemm_engine(engine)
             acc = torch.full((w.batch * w.seq_len, w.d_out), -(2 ** 31), dtype=torch.int32, device="cuda")
@@ -219,12 +217,6 @@ def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: 
     y_bf16 = y_dtype == "bf16"
     ydt = torch.int16 if y_bf16 else torch.float32
     y_ref = ora["Y"]
-    if report["code_mismatches"] != 0:
-        # the few codes that sit on a rounding boundary (counted above) may legitimately differ by one step;
-        # the output is then compared with the oracle's steps 3-5 applied to the codes the GPU produced
-        bias = inp["bias"] if cols is None or inp["bias"] is None else inp["bias"][cols]
-        y_ref = so.linear_from_codes(codes, sc, ora["qw"][:, sel], ora["sw"][sel], w.xform, w.levels, w.grid_h, w.grid_w,
-                                     bias, zeros=zs)["Y"]
     y_first = None
     for engine in engines:
         plan.set_gemm_engine(engine)

@@ -1,7 +1,7 @@
 """GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
 
-Bars: scales, weight codes and int32 accumulators bit-exact; activation codes bit-exact except
-elements whose fp32 product lies within 1 ulp of a rounding boundary (counted, reported);
+Bars: scales, offsets, weight codes, activation codes and int32 accumulators bit-exact (the benchmark spec would
+tolerate codes that differ where the fp32 product lies within 1 ulp of a rounding boundary: none do);
 outputs within max|err| <= 1e-3 * max|ref|.
 """
 import numpy as np
@@ -32,7 +32,7 @@ def _wl(name, **kw):
 
 def test_cfg1_small_config_all_steps():
     r = tl.full_case(get_workload("cfg1"))
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 SMALL = [
@@ -59,7 +59,7 @@ SMALL = [
 @pytest.mark.parametrize("w", SMALL, ids=[w.name for w in SMALL])
 def test_small_cases(w):
     r = tl.full_case(w, with_bias=True)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 # The asymmetric (min-max, Eq. 1 in full) form of the quantizer, on shifted activations so that the token
@@ -82,7 +82,7 @@ ASYM = [
 @pytest.mark.parametrize("w", ASYM, ids=[w.name for w in ASYM])
 def test_asymmetric_quantizer_cases(w):
     r = tl.full_case(w, with_bias=True)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 def test_asymmetric_bf16_output():
@@ -126,7 +126,7 @@ PARTIAL = PARTIAL + FEWER_HI
 @pytest.mark.parametrize("w", PARTIAL, ids=[w.name for w in PARTIAL])
 def test_partial_depth_cases(w):
     r = tl.full_case(w, with_bias=True)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 # Layers wider than one workgroup of the transform kernel holds (8192 bf16 channels in 1-D, 4096 for fp32
@@ -149,7 +149,7 @@ WIDE = [
 @pytest.mark.parametrize("w", WIDE, ids=[w.name for w in WIDE])
 def test_wide_layers_channel_split(w):
     r = tl.full_case(w, with_bias=True)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 # Plans without a sequence transform: the layers the paper leaves un-transformed and the baseline the
@@ -168,7 +168,7 @@ IDENT = [
 @pytest.mark.parametrize("w", IDENT, ids=[w.name for w in IDENT])
 def test_identity_transform_cases(w):
     r = tl.full_case(w, with_bias=True, check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
     tl.full_case(w, with_bias=True, check_unfused=False, y_dtype="bf16", check_acc=False)
 
 
@@ -177,7 +177,7 @@ def test_many_rows_few_channels():
     the row-indexed buffers and the 64-bit offsets at a row count 8 times the benchmark's."""
     w = _wl("many_rows", batch=32, seq_len=8192, levels=13, k_hi=128, d_in=64, d_out=96, seed=91)
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 def _random_workload(seed: int) -> Workload:
@@ -221,7 +221,7 @@ def test_random_valid_plans(seed):
     rng = np.random.default_rng(3000 + seed)
     r = tl.full_case(w, with_bias=bool(rng.integers(0, 2)), y_dtype=str(rng.choice(["f32", "bf16"])),
                      check_unfused=w.xform != "identity")
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 def test_one_plan_two_streams_distinct_workspaces():
@@ -443,7 +443,7 @@ def _sample_cols(N, n, seed):
 def test_full_size_llm_and_dit(name):
     w = get_workload(name)
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 7), check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 @pytest.mark.timeout(600)
@@ -452,7 +452,7 @@ def test_full_size_asymmetric_quantizer(name):
     """The paper's own quantizer (asymmetric min-max) on the LLM and image-token shapes at full size."""
     w = get_workload(name, act_quant="asym")
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 11), check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 @pytest.mark.timeout(600)
@@ -461,7 +461,7 @@ def test_full_size_image_tokens_three_levels():
     tokens are exactly the low-low band, 8 x 8 token blocks hold all three levels."""
     w = get_workload("cfg4", levels=3)
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 12), check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 @pytest.mark.timeout(600)
@@ -472,7 +472,7 @@ def test_full_size_second_mlp_layer(name):
     base = get_workload(name)
     w = get_workload(name, d_in=base.d_out, d_out=base.d_in, seed=base.seed + 50)
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 64, 13), check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 @pytest.mark.timeout(600)
@@ -481,18 +481,18 @@ def test_full_size_llm_three_levels_64_hi_tokens():
     approximations the first 64 are 8-bit, the other 192 are 4-bit rows), asymmetric min-max quantizer."""
     w = get_workload("cfg2", levels=3, act_quant="asym")
     r = tl.full_case(w, with_bias=True, y_dtype="bf16", cols=_sample_cols(w.d_out, 96, 14), check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 @pytest.mark.timeout(900)
 def test_full_size_cfg3():
     w = get_workload("cfg3")
     r = tl.full_case(w, y_dtype="bf16", cols=_sample_cols(w.d_out, 48, 8), check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
 
 
 @pytest.mark.timeout(1200)
 def test_full_size_cfg5_benchmark_workload():
     w = get_workload("cfg5")
     r = tl.full_case(w, y_dtype="bf16", cols=_sample_cols(w.d_out, 48, 9), check_unfused=False)
-    assert r["code_mismatches"] == r["near_boundary_mismatches"]
+    assert r["code_mismatches"] == 0
