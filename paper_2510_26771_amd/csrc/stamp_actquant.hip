@@ -506,14 +506,40 @@ __device__ __forceinline__ void step2d(const void* X, size_t blk_elem_off, int g
   constexpr int NR = LAST ? 18 : 15;
   float rowv[NR][8];
   float ll1[4][8];
+  // all 16 tokens of the sub-block are requested before the first cell is computed (one memory latency per
+  // sub-block instead of one per cell); the raw words give way to finished rows as the cells are consumed
+  constexpr int WPT = BF16 ? 1 : 2;  // 16-byte words per token and thread
+  uint4 raw[16][WPT];
+#pragma unroll
+  for (int tkn = 0; tkn < 16; ++tkn) {
+    const int ci = tkn >> 2, q = tkn & 3;
+    const int y = 4 * sby + 2 * (ci >> 1) + (q >> 1), x = 4 * sbx + 2 * (ci & 1) + (q & 1);
+    const size_t eoff = blk_elem_off + ((size_t)y * gridW + x) * d;
+#pragma unroll
+    for (int h = 0; h < WPT; ++h) {
+      if (active) {
+        raw[tkn][h] = BF16 ? *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(X) + eoff)
+                           : *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(X) + eoff + 4 * h);
+      } else {
+        raw[tkn][h] = make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
+  }
 #pragma unroll
   for (int ci = 0; ci < 4; ++ci) {
-    const int cy = ci >> 1, cx = ci & 1;
     float t[4][8];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int y = 4 * sby + 2 * cy + (q >> 1), x = 4 * sbx + 2 * cx + (q & 1);
-      load8(X, blk_elem_off + ((size_t)y * gridW + x) * d, BF16, active, t[q]);
+      const uint4 w0 = raw[4 * ci + q][0];
+      if constexpr (BF16) {
+        t[q][0] = bf16lo(w0.x); t[q][1] = bf16hi(w0.x); t[q][2] = bf16lo(w0.y); t[q][3] = bf16hi(w0.y);
+        t[q][4] = bf16lo(w0.z); t[q][5] = bf16hi(w0.z); t[q][6] = bf16lo(w0.w); t[q][7] = bf16hi(w0.w);
+      } else {
+        const uint4 w1 = raw[4 * ci + q][WPT - 1];
+        t[q][0] = __uint_as_float(w0.x); t[q][1] = __uint_as_float(w0.y); t[q][2] = __uint_as_float(w0.z);
+        t[q][3] = __uint_as_float(w0.w); t[q][4] = __uint_as_float(w1.x); t[q][5] = __uint_as_float(w1.y);
+        t[q][6] = __uint_as_float(w1.z); t[q][7] = __uint_as_float(w1.w);
+      }
     }
     cell2d(t[0], t[1], t[2], t[3], ll1[ci], rowv[3 * ci + 0], rowv[3 * ci + 1], rowv[3 * ci + 2]);
   }
