@@ -111,7 +111,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the STaMP linear layer on ONE GPU; --gpus N with N > 1 is not "
-              "supported (how the path would shard is described in DESIGN.md).", file=sys.stderr)
+              "supported (sequences are independent: the batch would be sharded without communication).",
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -62,7 +62,7 @@ class Workload:
         return self.batch * self.seq_len
 
 
-# The five benchmark configurations, in the order the benchmark spec lists them.
+# The five benchmark configurations, smallest first; cfg5 is the one the benchmark times.
 WORKLOADS: Dict[str, Workload] = {
     "cfg1": Workload("cfg1", 1, 256, 512, 512, "haar1d", 8, k_hi=8, x_dtype="f32", rho=0.95,
                      n_outlier_channels=4, outlier_scale=20.0, w_std=0.02, seed=0),

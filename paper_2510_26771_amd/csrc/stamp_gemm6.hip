@@ -10,7 +10,7 @@
 // bit, at twice the matrix rate per clock.  The factor 64 is folded into the row scale.
 //
 // Operand layout: the 32 codes that one lane feeds to one MFMA (channels 32 f .. 32 f + 31 of a K step of
-// 128 channels, f = 0..3) are a little-endian stream of 6-bit fields = 24 bytes.  MFMA round k (0, 1) of a
+// 128 channels, f = 0..3) are a little-endian stream of 6-bit fields = 24 bytes.  MFMA half k (0, 1) of a
 // step consumes channels [64 k, 64 k + 64): lane group kg = lane / 32 takes f = 2 k + kg, so over a step a
 // lane needs fragments kg and 2 + kg of its row: 48 bytes, kept as three 16-byte parts.  Per block of 32
 // rows (columns) and K step: [3 parts][2 kg][32 rows][16 bytes] = 3 KB, so that the 64 lanes of a wave read
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
 
   // Step kt: this wave's loads of step kt have landed (those of step kt+1 may still be in flight);
   // workgroup barrier (all of step kt is visible and the stage of step kt-1 is free); request step kt+2
-  // into that stage; then the two MFMA rounds.
+  // into that stage; then the two MFMA halves of the step.
   int stg = 0;  // stage of step kt
   for (int kt = 0; kt < KT; ++kt) {
     asm volatile("" ::: "memory");
@@ -211,11 +211,12 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     if (kt + 2 < KT) STAMP_REQUEST6(kt + 2, (stg == 0 ? 2 : stg - 1));
     __builtin_amdgcn_sched_barrier(0);
 
-    // The step's 12 fragments (per MFMA round k: 2 of the weights, 4 of the activations) arrive as 6 x 3
-    // 16-byte reads: parts 0 and 1 hold round 0's fragment (6 registers) and the first 2 registers of round
-    // 1's, part 2 the rest.  The reads are written out by hand (outputs of a two-read statement are early-clobber: the
-    // address register must outlive the first read) and so are the waits: the part-2 reads stay in flight
-    // under round 0's MFMAs.  A wait names the registers it covers, which keeps the MFMAs behind it.
+    // The step's 12 fragments (per MFMA half k: 2 of the weights, 4 of the activations) arrive as 6 x 3
+    // 16-byte reads: parts 0 and 1 hold the first half's fragment (6 registers) and the first 2 registers of
+    // the second half's, part 2 the rest.  The reads are written out by hand (outputs of a two-read statement
+    // are early-clobber: the address register must outlive the first read) and so are the waits: the part-2
+    // reads stay in flight under the first half's MFMAs.  A wait names the registers it covers, which keeps
+    // the MFMAs behind it.
     const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
     u4 a0[4], a1[4], a2[4], b0[NI], b1[NI], b2[NI];
 #pragma unroll
