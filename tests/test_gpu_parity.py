@@ -162,6 +162,10 @@ IDENT = [
         act_quant="asym", mean_shift=0.6),
     _wl("ident_f32in_wide", xform="identity", levels=0, batch=1, seq_len=128, k_hi=64, d_in=8800, d_out=64, x_dtype="f32",
         seed=74, first_token_scale=100.0),
+    # every token at 8 bits (k = s): the 4-bit rows' GEMM has nothing to do
+    _wl("ident_all_8bit", xform="identity", levels=0, batch=3, seq_len=96, k_hi=96, d_in=128, d_out=200, seed=75),
+    _wl("ident_all_8bit_asym", xform="identity", levels=0, batch=1, seq_len=256, k_hi=256, d_in=64, d_out=64, seed=76,
+        act_quant="asym", mean_shift=0.2),
 ]
 
 
