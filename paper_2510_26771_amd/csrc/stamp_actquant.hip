@@ -846,13 +846,9 @@ hipError_t launch_bottom1d_pass(const stamp_plan* p, const void* X, uint8_t* q_l
   const StampGeom& g = p->geom;
   const size_t lds = (size_t)8 * nthreads * (BF16 ? 16 : 32);  // staging buffer: 2 batches of 4 token rows
   if (lds > 160 * 1024 - 2048) return hipErrorInvalidValue;
-  static size_t attr_lds = 0;
-  if (lds > attr_lds) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bottom1d<RLOG, BF16, ASYM, PASS>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_lds = lds;
-  }
+  static size_t lds_done[kStampMaxDevices] = {};
+  hipError_t e = stamp_allow_lds(reinterpret_cast<const void*>(&k_bottom1d<RLOG, BF16, ASYM, PASS>), lds, lds_done);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((k_bottom1d<RLOG, BF16, ASYM, PASS>), dim3(g.k, g.B, PASS == 0 ? 1 : sp.nsplit), dim3(nthreads), lds, st,
                      X, q_lo, scales, abot, g.s, g.d, g.k, p->Kpad, (size_t)g.B * g.s, sp);
   return hipGetLastError();

@@ -240,13 +240,9 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
   constexpr size_t main_lds = 2 * (size_t)(BM * (A_INT4 ? 64 : 128) + BN * 128);
   constexpr size_t epi_lds = (EPI >= 2) ? (size_t)(2 * WN * kWaveTileBytes) : 0;
   constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + kRowInfoBytes;  // + per-row factors, destinations, offsets
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static size_t lds_done[kStampMaxDevices] = {};
+  hipError_t e = stamp_allow_lds(reinterpret_cast<const void*>(&k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>), lds, lds_done);
+  if (e != hipSuccess) return e;
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN;
   const int split = (!A_INT4 && EPI == 1) ? a.ksplit : 1;
   hipLaunchKernelGGL((k_gemm<A_INT4, EPI, RB, IS2D, YBF16, WN>), dim3(mt * nt * split), dim3(128 * WN), lds, st, a);

@@ -270,13 +270,9 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
   constexpr size_t main_lds = (size_t)kNumStage6 * kStage6;
   constexpr size_t epi_lds = (EPI >= 2) ? (size_t)kTileBytes6 : 0;
   constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + kRowInfoBytes;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm6<EPI, RB, IS2D, YBF16>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static size_t lds_done[kStampMaxDevices] = {};
+  hipError_t e = stamp_allow_lds(reinterpret_cast<const void*>(&k_gemm6<EPI, RB, IS2D, YBF16>), lds, lds_done);
+  if (e != hipSuccess) return e;
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN6;
   hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16>), dim3(mt * nt), dim3(512), lds, st, a);
   return hipGetLastError();

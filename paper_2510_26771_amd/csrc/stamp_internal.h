@@ -137,6 +137,20 @@ struct stamp_plan {
   size_t ws_abot, ws_rowmax, ws_gpart, ws_qhi, ws_qlo, ws_scales, ws_ythi, ws_P, ws_a6, ws_ytlo, ws_total;
 };
 
+// Dynamic-LDS limit of a kernel, raised once per device and kernel (the attribute belongs to the device's
+// copy of the function): `done` is the kernel's own table, one size per device.
+constexpr int kStampMaxDevices = 64;
+inline hipError_t stamp_allow_lds(const void* kernel, size_t bytes, size_t (&done)[kStampMaxDevices]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kStampMaxDevices) return hipErrorInvalidDevice;
+  if (bytes <= done[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) done[dev] = bytes;
+  return e;
+}
+
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
 hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStream_t st, uint32_t* colmax_tmp);
 // part: 1 = bottom kernel only, 2 = top + 8-bit rows only, 3 = both
