@@ -105,6 +105,7 @@ def main():
                          "asymmetric min-max form")
     ap.add_argument("--d-in", type=int, default=0, help="override the workload's d_in (e.g. the layer that follows it)")
     ap.add_argument("--d-out", type=int, default=0, help="override the workload's d_out")
+    ap.add_argument("--levels", type=int, default=0, help="override the transform depth (the paper's experiments use 3)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (int32 add), the "
                          "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -123,7 +124,7 @@ def main():
 
     st.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    over = {k: v for k, v in (("d_in", args.d_in), ("d_out", args.d_out)) if v > 0}
+    over = {k: v for k, v in (("d_in", args.d_in), ("d_out", args.d_out), ("levels", args.levels)) if v > 0}
     w = get_workload(args.workload, act_quant=args.act_quant, **over)
     log(f"generating {w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out}")
     inp = make_inputs(w)

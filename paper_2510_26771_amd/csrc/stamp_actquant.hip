@@ -140,6 +140,8 @@ struct SplitArgs {
   size_t part_rows;    // B * s
   int nsplit;
   int c_split;         // channels per split (a multiple of 8)
+  int8_t* q_hi;        // non-null: the plan has no top levels (L = 0), so the block sum is itself a finished
+  int khi;             // coefficient and the bottom kernel quantizes it (8 bits for blocks < khi, else 4)
 };
 constexpr int kMaxBlockRows = 128;
 
@@ -278,6 +280,51 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     }
     if (active) *reinterpret_cast<uint32_t*>(q_lo_blk + rm.e * 64 + q_off) = w;  // tiled layout: 64 bytes per row and K step
   }
+}
+
+// Plans without top levels: the block sum, times the norm of the blocks' level, is STaMP slot j.  The whole
+// workgroup reduces its range over the channels and quantizes it like any other top row: 8 bits for the first
+// khi slots, 4-bit codes held as int8 beyond.  Called after the last streaming step (no loads in flight).
+template <bool IS2D, bool ASYM>
+__device__ __forceinline__ void finish_top_row(const float (&top)[8], int level, uint32_t* part /* >= 32 words, free */,
+                                               int8_t* q_hi_row, float* scale_out, size_t zeros_off, bool row8,
+                                               bool active, int tid) {
+  const int lane = tid & 63, wave = tid >> 6, nw = (int)(blockDim.x >> 6);
+  const float nrm = IS2D ? ldexpf(1.0f, -level) : haar_norm(level);
+  float t[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) t[c] = __fmul_rn(top[c], nrm);
+  uint32_t pos, neg = 0u;
+  if constexpr (ASYM) row_posneg_bits(t, pos, neg);
+  else pos = row_absmax_bits(t);
+  pos = wave_max_u32(pos);
+  neg = wave_max_u32(neg);
+  if (lane == 0) { part[wave] = pos; part[16 + wave] = neg; }
+  __syncthreads();
+  uint32_t mp = 0u, mn = 0u;
+  for (int i = 0; i < nw; ++i) { mp = max(mp, part[i]); mn = max(mn, part[16 + i]); }
+  const float a = __uint_as_float(mp), nlo = __uint_as_float(mn);
+  const float qmax = ASYM ? (row8 ? 255.0f : 15.0f) : (row8 ? 127.0f : 7.0f);
+  const float range = ASYM ? __fadd_rn(a, nlo) : a;
+  float scale = 0.0f, inv = 0.0f, z = 0.0f;
+  if (range > 0.0f) {
+    scale = __fdiv_rn(range, qmax);
+    inv = __fdiv_rn(qmax, range);
+  }
+  if constexpr (ASYM) z = rintf(__fmul_rn(nlo, inv));
+  if (tid == 0) {
+    scale_out[0] = scale;
+    if constexpr (ASYM) scale_out[zeros_off] = z;
+  }
+  const float qlo = ASYM ? 0.0f : -qmax, qhi = qmax, shift = ASYM ? (row8 ? 128.0f : 8.0f) : 0.0f;
+  uint32_t w[2] = {0u, 0u};
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float q = __fadd_rn(rintf(__fmul_rn(t[i], inv)), z);
+    q = fminf(fmaxf(q, qlo), qhi) - shift;
+    w[i >> 2] |= ((uint32_t)((int)q) & 0xFFu) << (8 * (i & 3));
+  }
+  if (active) *reinterpret_cast<uint2*>(q_hi_row) = make_uint2(w[0], w[1]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -470,6 +517,14 @@ __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, u
                                     tid, pend, top, s_max, q_lo + stamp_qlo_offset(row0, 0, Kpad), q_off, scales + row0,
                                     zeros_off, gpart_blk, (size_t)sp.nsplit * sp.part_rows, s_amax,
                                     PASS == 0 || blockIdx.z == 0);
+  if constexpr (PASS == 0) {
+    if (sp.q_hi != nullptr) {
+      // s_max[R/4 & 1] was last used two steps ago: every thread has passed a barrier since
+      finish_top_row<false, ASYM>(top, RLOG, &s_max[(R / 4) & 1][0], sp.q_hi + ((size_t)b * k + j) * d + c0, scales + row0,
+                                  zeros_off, j < sp.khi, active, tid);
+      return;
+    }
+  }
   if (active && PASS != 1) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -610,6 +665,14 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
                                 tid, pend, top, s_max, q_lo + stamp_qlo_offset(prow0, 0, Kpad),
                                 (uint32_t)stamp_qlo_offset(0, c0, Kpad), scales + prow0, zeros_off, gpart_blk,
                                 (size_t)sp.nsplit * sp.part_rows, s_amax, PASS == 0 || blockIdx.z == 0);
+  if constexpr (PASS == 0) {
+    if (sp.q_hi != nullptr) {
+      constexpr int nsteps = (g == 4) ? 1 : 4;
+      finish_top_row<true, ASYM>(top, RLOG, &s_max[nsteps & 1][0], sp.q_hi + ((size_t)b * k + j) * d + c0, scales + prow0,
+                                 zeros_off, j < sp.khi, active, tid);
+      return;
+    }
+  }
   if (active && PASS != 1) {
     float4* o = reinterpret_cast<float4*>(abot + ((size_t)b * k + j) * d + c0);
     o[0] = make_float4(top[0], top[1], top[2], top[3]);
@@ -866,6 +929,10 @@ hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, fl
 
 }  // namespace
 
+bool stamp_top_in_bottom(const stamp_plan* p) {
+  return !p->geom.ident && p->geom.L == 0 && stamp_actquant_nsplit(p) == 1;
+}
+
 int stamp_actquant_nsplit(const stamp_plan* p) {
   const StampGeom& g = p->geom;
   if (g.ident) return 1;
@@ -895,6 +962,10 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
   sp.nsplit = stamp_actquant_nsplit(p);
   sp.c_split = (sp.nsplit == 1) ? g.d : (((g.d + sp.nsplit - 1) / sp.nsplit + 511) / 512) * 512;
   if (sp.nsplit > 1 && gpart == nullptr) return hipErrorInvalidValue;
+  // no top levels: the bottom kernel finishes the block sums itself (one launch instead of three)
+  const bool top_in_bottom = stamp_top_in_bottom(p);
+  sp.q_hi = top_in_bottom ? q_hi : nullptr;
+  sp.khi = g.khi;
   const int nthreads = ((sp.c_split / 8 + 63) / 64) * 64;
   dim3 grid(g.k, g.B);
   const size_t zeros_off = (size_t)g.B * g.s;
@@ -944,7 +1015,7 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
 #undef LAUNCH2D__
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (!(part & 2)) return hipSuccess;
+  if (!(part & 2) || top_in_bottom) return hipSuccess;
   const size_t lds = (size_t)g.k * (kTopCh + 1) * sizeof(float);
   const int nslices = (g.d + kTopCh - 1) / kTopCh;
   const size_t npart = (size_t)g.B * g.k * nslices;

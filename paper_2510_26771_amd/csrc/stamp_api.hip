@@ -149,8 +149,12 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
     }
     return stamp_launch_gemm_lo(p, q_lo, scales, 3, Y, nullptr, st) == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
   }
-  if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
-  if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit) != hipSuccess) return STAMP_ERR_DEVICE;
+  if (stamp_hi_rows_are_block_sums(p)) {
+    if (stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad) != hipSuccess) return STAMP_ERR_DEVICE;
+  } else {
+    if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
+    if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit) != hipSuccess) return STAMP_ERR_DEVICE;
+  }
   const bool fused = p->fused_ok && !p->unfused;
   float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
   if (p->engine == STAMP_GEMM_FP6) {
@@ -391,8 +395,13 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
   switch (stage) {
     case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 1); break;
     case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 2); break;
-    case 2: e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st); break;
-    case 3: e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit); break;
+    case 2:
+      e = stamp_hi_rows_are_block_sums(p) ? stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad)
+                                          : stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st);
+      break;
+    case 3:  // nothing to launch when the plan has no top levels
+      if (!stamp_hi_rows_are_block_sums(p)) e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit);
+      break;
     case 4:
       if (p->engine == STAMP_GEMM_FP6)
         e = stamp_launch_gemm_lo6(p, at(ws, p->ws_a6), scales, fused ? 2 : 1, fused ? Y : (void*)ytlo, fused ? P : nullptr, st);

@@ -283,11 +283,15 @@ bool stamp_hi_wide_tiles(int M, int Npad) {
   return tiles128 > device_cus();
 }
 
+// Plans without top levels: the dequantized top rows ARE the block sums P of the inverse (the top inverse has
+// nothing to do), so the 8-bit rows' GEMM writes them where the 4-bit rows' epilogue reads them.
+bool stamp_hi_rows_are_block_sums(const stamp_plan* p) { return !p->geom.ident && p->geom.L == 0; }
+
 // The few 8-bit rows make few tiles: when they would leave most CUs idle, the depth of every tile is split
 // over 2..4 workgroups (partial rows, added by the top inverse).
 int stamp_hi_ksplit(const stamp_plan* p) {
   const int M = p->geom.B * p->geom.k;
-  if (M == 0) return 1;
+  if (M == 0 || stamp_hi_rows_are_block_sums(p)) return 1;  // no partial rows when the GEMM writes the block sums itself
   const int mt = (M + stamp_gemm::BM - 1) / stamp_gemm::BM;
   const int tiles = mt * (p->Npad / (stamp_hi_wide_tiles(M, p->Npad) ? 256 : 128));
   const int KT = p->Kpad / stamp_gemm::BK;
@@ -314,13 +318,14 @@ stamp_gemm::GemmArgs stamp_gemm_args(const stamp_plan* p, const float* scales, v
   a.M = 0;
   a.a_row_bytes = 0;
   a.a_last16 = 0;
+  a.ld_out = p->geom.N;
   a.ksplit = 1;
   a.split_stride = 0;
   return a;
 }
 
 hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode, void* out,
-                                hipStream_t st) {
+                                hipStream_t st, int ld_out) {
   GemmArgs a = stamp_gemm_args(p, scales, out);
   a.A = reinterpret_cast<const uint8_t*>(q_hi);
   a.M = p->geom.B * p->geom.k;
@@ -328,6 +333,7 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
   a.a_last16 = (size_t)a.M * a.a_row_bytes - 16;
   if (mode == 0) return launch<false, 0, 0, false>(a, st);
   if (mode == 1) {
+    if (ld_out > 0) a.ld_out = ld_out;
     a.ksplit = p->hi_ksplit;
     a.split_stride = (size_t)a.M * a.N;
     return launch<false, 1, 0, false>(a, st);

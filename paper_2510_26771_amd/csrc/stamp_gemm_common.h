@@ -54,6 +54,7 @@ struct GemmArgs {
   int N, Npad, Kpad;
   int a_row_bytes;       // 8-bit rows: valid bytes per A row
   size_t a_last16;       // 8-bit rows: byte offset of the last 16-byte chunk of A (loads are clamped to it)
+  int ld_out;            // dequantized mode (EPI 1): floats between consecutive rows of `out`
   int ksplit;            // 8-bit rows, dequantized mode: the depth is split over this many workgroups per tile,
   size_t split_stride;   // each writing its partial rows to out + split * split_stride (floats)
   StampGeom g;
@@ -361,7 +362,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
             } else {
               // asymmetric: the integer sum over (stored code - offset), exact in one fma
               const float af = g.asym ? __builtin_fmaf(-s_rowz[rl], csn, (float)acc[mi][ni][v]) : (float)acc[mi][ni][v];
-              reinterpret_cast<float*>(a.out)[(size_t)dst * a.N + n] = (af * s_rowfac[rl]) * swn;
+              reinterpret_cast<float*>(a.out)[(size_t)dst * a.ld_out + n] = (af * s_rowfac[rl]) * swn;
             }
           }
         }

@@ -157,6 +157,8 @@ hipError_t stamp_launch_weight_quant(const stamp_plan* p, const float* W, hipStr
 // scales: [B*s] scales, followed by [B*s] offsets z for asymmetric plans
 // gpart: [2][nsplit][B*s] partial row maxima when the channels are split over workgroups (nsplit > 1), else unused
 int stamp_actquant_nsplit(const stamp_plan* p);
+// plans without top levels and without channel splits: the bottom kernel also quantizes the block sums (no k_top, no k_quant_hi)
+bool stamp_top_in_bottom(const stamp_plan* p);
 hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo,
                                  float* scales, float* abot, uint32_t* rowmax, uint32_t* gpart, hipStream_t st, int part = 3);
 // mode: 0 = int32 accumulators in STaMP row order (debug), 1 = dequantized fp32 rows (hi -> Yt_hi
@@ -164,8 +166,10 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
 // 3 = lo rows of an identity plan: dequantized + bias -> Y.
 bool stamp_hi_wide_tiles(int M, int Npad);
 int stamp_hi_ksplit(const stamp_plan* p);
+// ld_out > 0 (mode 1): row stride of `out` in floats instead of d_out
 hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode,
-                                void* out, hipStream_t st);
+                                void* out, hipStream_t st, int ld_out = 0);
+bool stamp_hi_rows_are_block_sums(const stamp_plan* p);
 hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const float* scales, int mode,
                                 void* out, const float* P, hipStream_t st);
 // FP6 engine of the 4-bit rows: operand sizes, plan-time weight codes (colmax: bit patterns of the column
