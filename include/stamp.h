@@ -191,6 +191,8 @@ stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* plan, int8_t* qW_hos
  *   5 in-block inverse kernel (unfused plans only)
  *   6 conversion of the packed 4-bit rows to the FP6 engine's operand layout (FP6 engine only; with
  *     that engine stage 4 is the GEMM alone and reads what stage 6 wrote to the workspace)
+ * Plans whose transform has no levels above the blocks: stage 0 also quantizes the block sums, stage 2 writes
+ * the block sums of the inverse itself, stages 1 and 3 launch nothing.
  * Plans without transform: 0 the quantization kernel, 2 GEMM of the 8-bit rows, 3 their output pass,
  * 6 and 4 as above; 1 and 5 return STAMP_ERR_UNSUPPORTED. */
 stamp_status_t stamp_debug_run_stage(const stamp_plan_t* plan, int32_t stage, const void* X_dev,
