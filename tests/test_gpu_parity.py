@@ -228,6 +228,58 @@ def test_random_valid_plans(seed):
     assert r["code_mismatches"] == 0
 
 
+@pytest.mark.parametrize("case", ["1d", "2d_asym", "1d_fewer_hi"])
+def test_forward_q_from_buffers_packed_on_the_host(case):
+    """stamp_linear_forward_q on code / scale buffers that the HOST packs from the oracle's results, following only
+    the layout that include/stamp.h documents (physical row order, tiled nibbles, stored asymmetric codes): the
+    documented layout is the one the GEMM path reads."""
+    import torch
+    import paper_2510_26771_amd as st
+    if case == "1d":
+        w = _wl("hostpack_1d", batch=2, seq_len=512, levels=9, k_hi=16, d_in=160, d_out=200, seed=86)
+    elif case == "2d_asym":
+        w = _wl("hostpack_2d", batch=1, seq_len=1024, xform="haar2d", levels=5, grid_h=32, grid_w=32, k_hi=16, d_in=96,
+                d_out=136, seed=87, act_quant="asym", mean_shift=0.4)
+    else:
+        w = _wl("hostpack_few", batch=2, seq_len=512, levels=3, k_hi=5, d_in=128, d_out=96, seed=88, act_quant="asym")
+    inp = make_inputs(w, with_bias=True)
+    ora = tl.run_oracle(w, inp)
+    plan = st.StampPlan(tl.plan_desc_for(w, "f32"), torch.from_numpy(inp["W"]).cuda(), torch.from_numpy(inp["bias"]).cuda())
+    row = plan.row_of_coeff().astype(np.int64)       # physical row of STaMP slot p
+    n_top = plan.hi_rows()
+    B, s, d = w.batch, w.seq_len, w.d_in
+    asym = w.act_quant == "asym"
+    codes = ora["codes"].astype(np.int16)            # [B, s, d] in STaMP order
+    if asym:                                         # stored form: code - 2^(b-1), b = 8 for the first k_hi slots
+        codes = codes - np.where(np.arange(s) < w.k_hi, 128, 8).astype(np.int16)[None, :, None]
+    q_hi = np.ascontiguousarray(codes[:, :n_top].astype(np.int8))
+    # q_lo: byte of channels (c, c + 1) of row m = b * s + r at (((m/256)*(Kp/128) + c/128)*256 + m%256)*64 + (c%128)/2
+    mp, kp = -(-(B * s) // 256) * 256, -(-d // 128) * 128
+    q_lo = np.zeros(mp * kp // 2, dtype=np.uint8)
+    phys = np.zeros((B, s, d), dtype=np.int16)
+    phys[:, row[n_top:]] = codes[:, n_top:]
+    nib = (phys & 0xF).astype(np.uint8)
+    byte = (nib[:, :, 0::2] | (nib[:, :, 1::2] << 4)).reshape(B * s, d // 2)
+    m = np.arange(B * s)[:, None]
+    c = (2 * np.arange(d // 2))[None, :]
+    q_lo[(((m // 256) * (kp // 128) + c // 128) * 256 + m % 256) * 64 + (c % 128) // 2] = byte
+    scales = np.zeros((2, B, s) if asym else (B, s), dtype=np.float32)
+    if asym:
+        scales[0][:, row] = ora["scales"]
+        scales[1][:, row] = ora["zeros"]
+    else:
+        scales[:, row] = ora["scales"]
+    ws = plan.alloc_workspace()
+    for engine in ("fp6", "int8"):
+        plan.set_gemm_engine(engine)
+        Y = torch.zeros((B, s, w.d_out), dtype=torch.float32, device="cuda")
+        plan.linear_forward_q(torch.from_numpy(q_hi).cuda(), torch.from_numpy(q_lo).cuda(), torch.from_numpy(scales).cuda(),
+                              Y, ws)
+        torch.cuda.synchronize()
+        tl.check_output(Y.cpu().numpy(), ora["Y"], False, f"{w.name} {engine}")
+    plan.destroy()
+
+
 def test_one_plan_two_streams_distinct_workspaces():
     """A plan is read-only in stamp_linear_forward: two streams may run it at the same time on different inputs,
     each with its own workspace, and get what the calls give one after the other."""
