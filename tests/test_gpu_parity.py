@@ -280,6 +280,31 @@ def test_forward_q_from_buffers_packed_on_the_host(case):
     plan.destroy()
 
 
+def test_one_quantized_activation_feeds_several_linears():
+    """One L + Q output feeds several linear layers, each with its own weights and inverse (the paper's block diagram:
+    to_q / to_k / to_v share a quantized input): stamp_quantize_act once, stamp_linear_forward_q per plan."""
+    import torch
+    import paper_2510_26771_amd as st
+    from dataclasses import replace
+    w = _wl("shared_act", batch=2, seq_len=1024, levels=10, k_hi=16, d_in=256, d_out=192, seed=89)
+    inp = make_inputs(w, with_bias=True)
+    Xd = tl.to_device_x(inp, w)
+    plans, refs = [], []
+    for i, d_out in enumerate((192, 320, 64)):
+        wi = replace(w, d_out=d_out, seed=w.seed + 10 * i)
+        Wi, bi = make_inputs(wi, with_bias=True)["W"], make_inputs(wi, with_bias=True)["bias"]
+        plans.append(st.StampPlan(tl.plan_desc_for(wi, "f32"), torch.from_numpy(Wi).cuda(), torch.from_numpy(bi).cuda()))
+        refs.append(so.stamp_linear_forward(inp["X_f32"], Wi, w.xform, w.levels, w.k_hi, bias=bi, dtype=np.float32)["Y"])
+    q_hi, q_lo, scales = plans[0].alloc_act_buffers()
+    plans[0].quantize_act(Xd, q_hi, q_lo, scales, plans[0].alloc_workspace())
+    for plan, ref in zip(plans, refs):
+        Y = torch.zeros(ref.shape, dtype=torch.float32, device="cuda")
+        plan.linear_forward_q(q_hi, q_lo, scales, Y, plan.alloc_workspace())
+        torch.cuda.synchronize()
+        tl.check_output(Y.cpu().numpy(), ref, False, "shared activation")
+        plan.destroy()
+
+
 def test_one_plan_two_streams_distinct_workspaces():
     """A plan is read-only in stamp_linear_forward: two streams may run it at the same time on different inputs,
     each with its own workspace, and get what the calls give one after the other."""
