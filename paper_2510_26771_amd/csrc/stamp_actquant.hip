@@ -697,7 +697,21 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
   const int stride = kTopCh + 1;
   const bool cact = (c_base + ch) < d;
   float* base = abot + (size_t)b * k * d;
-  for (int j = grp; j < k; j += ngrp) s_buf[j * stride + ch] = cact ? base[(size_t)j * d + c_base + ch] : 0.0f;
+  // four independent loads in flight per thread before the first LDS write (one load per loop trip would
+  // pay one memory latency per row)
+  for (int j0 = grp; j0 < k; j0 += 4 * ngrp) {
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * ngrp;
+      v[u] = (cact && j < k) ? base[(size_t)j * d + c_base + ch] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * ngrp;
+      if (j < k) s_buf[j * stride + ch] = v[u];
+    }
+  }
   __syncthreads();
   if (!is2d) {
     for (int st = 2; st <= (1 << L); st <<= 1) {
