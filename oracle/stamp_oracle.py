@@ -30,7 +30,8 @@ form.  Two precisions are offered through the ``dtype`` argument of every floati
 Readings of the paper where it is silent (each also listed in the design document):
 
 * Haar matrix: orthonormal (Theorem 1 needs an orthogonal L), detail = even minus odd,
-  approximations first ("pushes the energy in the first half"), Mallat ordering: after J levels
+  approximations first (each step moves the energy into the leading half of the slots, section
+  "Efficient Energy Concentration"), Mallat ordering: after J levels
   slot 0.. hold the coarsest approximations, then the details from coarse to fine.
 * Operation order of the transform (the paper gives none): a coefficient is the inner product
   with its basis function, +-2^(-l/2) on the wavelet's two halves, so it is evaluated as
@@ -39,7 +40,8 @@ Readings of the paper where it is silent (each also listed in the design documen
   recursion), and each finished coefficient is multiplied ONCE by norm(l) = fl(2^(-l/2)) of its
   level (exact for even l).  The inverse multiplies every coefficient by the same norm(l) first
   and then runs plain butterflies x[2i] = a + d, x[2i+1] = a - d.
-* 2-D: pyramid (recursion on the low-low quarter, "one quarter for 2D signal"); one 2-D level
+* 2-D: pyramid (recursion on the low-low quarter: the same section gives a 2-D step a quarter of the
+  tokens); one 2-D level
   on a 2x2 cell [[p, q], [u, v]] is t0=p+q, t1=p-q, t2=u+v, t3=u-v, LL=t0+t2, W=t1+t3,
   H=t0-t2, D=t1-t3, and a finished level-l coefficient is multiplied once by 2^(-l) (exact).
   STaMP order in 2-D: final LL block row-major, then per level from coarse to fine the blocks
@@ -48,15 +50,17 @@ Readings of the paper where it is silent (each also listed in the design documen
   qmax = 2^(b-1) - 1, scale = absmax / qmax (range-based, no clipping, as in the Background
   section), code = clamp(rne(x * (qmax / absmax)), -qmax, qmax).  A zero row gets scale 0 and
   codes 0.  Rounding is round-half-to-even.
-* Asymmetric quantizer (what the paper's experiments use: "asymmetric quantization with minmax
-  scaling"; Eq. 1 in full): codes in [0, 2^b - 1], scale = range / (2^b - 1) (the printed scale is
-  its reciprocal: Eq. 1 divides by s, and the proof of the range bound uses range / (2^b - 1)),
-  integer offset z = rne(-min / scale) (Eq. 1 adds z to a rounded value and calls the result an
-  integer, so z is rounded; the printed z = -min / s is its real-valued form), code =
-  clamp(rne(x / scale) + z, 0, 2^b - 1), evaluated as rne(fl(x * inv)) with inv = (2^b - 1) / range.
-  The range of a token always contains 0 (min <- min(min, 0), max <- max(max, 0)): the paper does
-  not say what happens to a one-sided token; this keeps 0 exactly representable and z inside the
-  code range.  A zero row gets scale 0, z 0, codes 0.
+* Asymmetric quantizer (the min-max form the paper's experiments use; Background, Eq. 1 in full):
+  codes in [0, 2^b - 1]; range = max - min over the token's channels, exactly as the range-setting
+  sentence of the Background section defines it (a one-sided token keeps its own, narrower range:
+  0 need not lie inside it); scale = range / (2^b - 1) (the printed scale is its reciprocal: Eq. 1
+  divides by s, and the proof of the range bound uses range / (2^b - 1)); integer offset
+  z = rne(-min / scale) (Eq. 1 adds z to a rounded value and calls the result an integer, so z is
+  rounded; it is any integer, negative for an all-positive token); code = clamp(rne(x / scale) + z,
+  0, 2^b - 1), evaluated as rne(fl(x * inv)) with inv = (2^b - 1) / range.
+  The paper does not say what a token with max = min gets (its printed scale divides by zero): here
+  such a token takes range = |value|, so that it is still reproduced to within rounding; a zero
+  token gets scale 0, z 0, codes 0.
 * Weights: per output channel, absmax / 7, round to nearest, no range search.
 * W is [d_in, d_out] and Y = X W.
 
@@ -379,19 +383,22 @@ def qmax_unsigned(bits: int) -> int:
 
 
 def quantize_tokens_asym(T: np.ndarray, bits: np.ndarray, dtype=np.float32) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """Per-token asymmetric min-max quantization of T[s, d] with bits[s] (Background, Eq. 1).
+    """Per-token asymmetric min-max quantization of T[s, d] with bits[s] (Background, Eq. 1 and the
+    range-setting sentence after it).
 
-    lo_i = min(min_j T_ij, 0), hi_i = max(max_j T_ij, 0), range_i = hi_i - lo_i;
+    lo_i = min_j T_ij, hi_i = max_j T_ij, range_i = hi_i - lo_i (a token with hi = lo: range = |hi|);
     scale_i = range_i / (2^b - 1);  inv_i = (2^b - 1) / range_i (two separate divisions);
     z_i = rne(-(lo_i * inv_i));  code_ij = clamp(rne(T_ij * inv_i) + z_i, 0, 2^b - 1).
     Zero rows: scale = inv = z = 0.  Returns (codes uint8 [s, d], scale [s], z [s] as integers
-    held in `dtype`).
+    held in `dtype`; z may lie outside [0, 2^b - 1]).
     """
     T = np.asarray(T, dtype=dtype)
     zero = np.zeros((), dtype=dtype)
-    lo = np.minimum(np.min(T, axis=1), zero)
-    hi = np.maximum(np.max(T, axis=1), zero)
+    lo = np.min(T, axis=1)
+    hi = np.max(T, axis=1)
     rng = hi - lo
+    flat = rng == 0
+    rng[flat] = np.abs(hi[flat])
     qm = np.array([qmax_unsigned(int(b)) for b in bits], dtype=dtype)
     nz = rng > 0
     scale = np.zeros_like(rng)

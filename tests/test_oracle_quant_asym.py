@@ -57,34 +57,81 @@ def test_codes_range_offsets_and_zero(bits, dtype):
     codes, scale, z = so.quantize_tokens_asym(T, b, dtype)
     qm = (1 << bits) - 1
     assert codes.dtype == np.uint8 and codes.max() <= qm
-    assert np.all(z >= 0) and np.all(z <= qm) and np.array_equal(z, np.rint(z))
-    # the range contains 0: one-sided rows get offset 0 (all positive) or qmax (all negative)
-    assert z[1] == 0 and z[2] == qm and z[5] == 0
+    assert np.array_equal(z, np.rint(z))
+    # a token whose range straddles 0 has its offset inside the code range; a one-sided token keeps its own
+    # range max - min, so its offset leaves the code range: below 0 when all entries are positive, above
+    # 2^b - 1 when all are negative
+    for i in (0, 3, 6):
+        assert T[i].min() < 0 < T[i].max() and 0 <= z[i] <= qm
+    assert T[1].min() > 0 and z[1] < 0
+    assert T[2].max() < 0 and z[2] > qm
     # zero row: everything zero
     assert scale[4] == 0 and z[4] == 0 and not codes[4].any()
-    # the minimum of a row with negative entries takes code 0, the maximum takes qmax (to within the
-    # one code that the two separately rounded products can differ by)
-    for i in (0, 3, 6):
+    # the minimum of every row takes code 0, the maximum takes 2^b - 1 (to within the one code that the two
+    # separately rounded products can differ by)
+    for i in (0, 1, 2, 3, 6):
         assert codes[i][np.argmin(T[i])] == 0
         assert codes[i][np.argmax(T[i])] >= qm - 1
-    # 0 is a grid point: code z de-quantizes to exactly 0
-    D = so.dequantize_tokens_asym(z[:, None].astype(np.uint8), scale, z, dtype)
+    # every grid point is a multiple of the scale: code z de-quantizes to exactly 0
+    D = so.dequantize_tokens_asym(np.zeros((T.shape[0], 1), dtype=np.uint8), scale, np.zeros_like(z), dtype)
     assert not D.any()
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_strictly_positive_row_takes_the_printed_range(bits):
+    """Background, range-setting sentence: range = max - min and the offset comes from the minimum, also for
+    a token that does not contain 0.  (A range widened to contain 0 would give scale = max / (2^b - 1) and
+    code(min) > 0 here.)"""
+    qm = (1 << bits) - 1
+    rng = np.random.default_rng(11)
+    x = (10.0 + rng.random((3, 200))).astype(np.float64)      # values in [10, 11)
+    x[1] = -x[1]                                               # strictly negative row
+    x[2] = 7.0 + np.arange(200) / 199.0 * 3.0                  # 7 .. 10, ends attained
+    codes, scale, z = so.quantize_tokens_asym(x, np.full(3, bits), np.float64)
+    span = x.max(axis=1) - x.min(axis=1)
+    assert np.allclose(scale, span / qm, rtol=1e-13)
+    assert np.all(scale < np.abs(x).max(axis=1) / qm / 3)      # far below what a range containing 0 gives
+    for i in range(3):
+        assert codes[i][np.argmin(x[i])] == 0
+        assert codes[i][np.argmax(x[i])] >= qm - 1
+    err = so.dequantize_tokens_asym(codes, scale, z, np.float64) - x
+    assert np.all(np.abs(err) <= scale[:, None] * (0.5 + 1e-9))
+    # per-token error bound of Eq. "range_ubound" with the token's own range
+    assert np.all((err ** 2).sum(axis=1) <= x.shape[1] / 4.0 * span ** 2 / qm ** 2 * (1 + 1e-9))
+    # hand-worked: 4 bits, values 3 .. 6 in steps of 0.2: range 3, scale 0.2, x / scale = 15 .. 30, offset -15
+    xs = (3.0 + 0.2 * np.arange(16))[None, :]
+    c, s_, z_ = so.quantize_tokens_asym(xs, np.array([4]), np.float64)
+    assert abs(s_[0] - 0.2) < 1e-15 and z_[0] == -15 and c[0].tolist() == list(range(16))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_constant_rows(bits):
+    """max = min: the printed scale would divide by zero; the reading taken is range = |value|, which still
+    reproduces the token to within rounding; a zero token gets scale 0."""
+    qm = (1 << bits) - 1
+    x = np.stack([np.full(32, 2.5), np.full(32, -0.75), np.zeros(32)]).astype(np.float32)
+    codes, scale, z = so.quantize_tokens_asym(x, np.full(3, bits))
+    assert np.allclose(scale[:2], np.array([2.5, 0.75]) / qm, rtol=1e-6) and scale[2] == 0
+    assert z.tolist() == [-qm, qm, 0] and not codes.any()
+    d = so.dequantize_tokens_asym(codes, scale, z)
+    assert np.allclose(d, x, rtol=1e-6, atol=0)
 
 
 @pytest.mark.parametrize("bits", [4, 8])
 def test_error_at_most_half_a_step_and_range_bound(bits):
     # no clipping (range-based scale) -> rounding error only: |x_hat - x| <= scale / 2, hence the paper's
-    # bound ||x_hat - x||^2 <= d / 4 * scale^2 with scale = range / (2^b - 1)
+    # bound ||x_hat - x||^2 <= d / 4 * range^2 / (2^b - 1)^2 with range = max - min
     T = _rows(2, s=64, d=256, dtype=np.float64)
     b = np.full(T.shape[0], bits)
     codes, scale, z = so.quantize_tokens_asym(T, b, np.float64)
     err = so.dequantize_tokens_asym(codes, scale, z, np.float64) - T
     assert np.all(np.abs(err) <= scale[:, None] * (0.5 + 1e-9))
     qm = (1 << bits) - 1
-    rng = np.maximum(T.max(axis=1), 0) - np.minimum(T.min(axis=1), 0)
+    rng = T.max(axis=1) - T.min(axis=1)
+    flat = rng == 0
+    rng[flat] = np.abs(T.max(axis=1))[flat]
     assert np.allclose(scale, rng / qm, rtol=1e-12)
-    assert np.all((err ** 2).sum(axis=1) <= T.shape[1] / 4.0 * scale ** 2 * (1 + 1e-9))
+    assert np.all((err ** 2).sum(axis=1) <= T.shape[1] / 4.0 * (rng / qm) ** 2 * (1 + 1e-9))
 
 
 def test_fp32_and_fp64_agree_except_at_rounding_boundaries():

@@ -223,7 +223,7 @@ def test_block_locality_2d():
 
 
 def test_energy_concentration_on_correlated_input():
-    # "each DWT step pushes the energy in the first half": on an AR(1) stream the first k slots
+    # every DWT step moves energy into the leading half of the slots (section "Efficient Energy Concentration"): on an AR(1) stream the first k slots
     # hold far more than k/s of the energy (sanity, no threshold from the paper)
     from gen import get_workload, make_inputs
     w = get_workload("cfg1", n_outlier_channels=0)
