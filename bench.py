@@ -20,7 +20,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, TOP/s
@@ -120,7 +119,6 @@ def main():
     import torch
     import paper_2510_26771_amd as st
     from gen import get_workload, make_inputs
-    import stamp_testlib as tl
 
     st.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -128,9 +126,9 @@ def main():
     w = get_workload(args.workload, act_quant=args.act_quant, **over)
     log(f"generating {w.name}: B={w.batch} s={w.seq_len} d_in={w.d_in} d_out={w.d_out}")
     inp = make_inputs(w)
-    Xd = tl.to_device_x(inp, w)
+    Xd = st.to_device_x(inp, w)
     Wd = torch.from_numpy(inp["W"]).cuda()
-    plan = st.StampPlan(tl.plan_desc_for(w, "bf16"), Wd)
+    plan = st.StampPlan(st.plan_desc_for(w, "bf16"), Wd)
     torch.cuda.synchronize()
     del Wd
     if args.unfused:
@@ -224,7 +222,7 @@ def main():
     # floating-point layers), so its figure is context, not a baseline for this number.
     from dataclasses import replace as _replace
     wi = _replace(w, xform="identity", levels=0, grid_h=0, grid_w=0)
-    plan_i = st.StampPlan(tl.plan_desc_for(wi, "bf16"), torch.from_numpy(inp["W"]).cuda())
+    plan_i = st.StampPlan(st.plan_desc_for(wi, "bf16"), torch.from_numpy(inp["W"]).cuda())
     plan_i.set_gemm_engine(args.engine)
     ws_i = plan_i.alloc_workspace()
     for _ in range(args.warmup):

@@ -22,8 +22,11 @@
  *   - No call allocates device memory except stamp_plan_create (the plan owns its quantized
  *     weights until stamp_plan_destroy).  Scratch memory comes in through `workspace_dev`.
  *   - Every argument error is detected on the host BEFORE anything is launched and reported
- *     through the return code; nothing is launched in that case.  A plan is immutable and may be
- *     used from several streams at once with distinct workspaces.
+ *     through the return code; nothing is launched in that case.  The compute calls only read the
+ *     plan, so one plan may be used from several streams or host threads at once with distinct
+ *     workspaces.  The two switches stamp_plan_set_unfused / stamp_plan_set_gemm_engine are the
+ *     exception: they modify the plan, are meant for tests and measurements, and must not run while
+ *     another thread uses the plan.
  *   - Non-finite inputs give unspecified numbers but never a fault.
  *
  * Tensor layouts
@@ -88,12 +91,15 @@ typedef enum { STAMP_L_IDENTITY = 0, STAMP_L_HAAR1D = 1, STAMP_L_HAAR2D = 2 } st
 /* Activation quantizer (Background, Eq. 1), per transformed token i with b bits:
  *   STAMP_ACT_SYMMETRIC   a = max_j |t_ij|, scale = a / (2^(b-1) - 1), code = rne(t * (1 / scale)) in
  *                         [-(2^(b-1) - 1), 2^(b-1) - 1]; de-quantized value code * scale.
- *   STAMP_ACT_ASYMMETRIC  Eq. 1 in full (the "asymmetric quantization with minmax scaling" of the
- *                         Experiments set-up): lo = min(min_j t_ij, 0), hi = max(max_j t_ij, 0),
- *                         scale = (hi - lo) / (2^b - 1), integer offset z = rne(-lo / scale),
+ *   STAMP_ACT_ASYMMETRIC  Eq. 1 in full with the min-max range of the Background section (what the
+ *                         Experiments set-up uses): lo = min_j t_ij, hi = max_j t_ij, range = hi - lo
+ *                         (the token's own range, whether or not it contains 0; a token with hi = lo
+ *                         takes range = |hi|), scale = range / (2^b - 1), integer offset
+ *                         z = rne(-lo / scale) (any integer: negative for an all-positive token),
  *                         code = clamp(rne(t / scale) + z, 0, 2^b - 1); de-quantized value
  *                         (code - z) * scale.  The library STORES code - 2^(b-1) (two's complement
- *                         int8 / nibble) and returns z next to the scales.
+ *                         int8 / nibble) and returns z next to the scales.  Results are exact as
+ *                         described while |z| < 2^22, i.e. |lo| / range < 2^22 / (2^b - 1).
  * Either way scale and its reciprocal are two fp32 divisions and rne is round-half-to-even. */
 typedef enum { STAMP_ACT_SYMMETRIC = 0, STAMP_ACT_ASYMMETRIC = 1 } stamp_act_quant_t;
 
@@ -122,7 +128,8 @@ typedef struct {
  *   4 bits); bits 8/4/4;
  *   d_in a multiple of 32 and at most 32768 (above 8192, or 4096 for fp32 input or 2-D grids, the transform
  *   + quantization kernel splits the channels over workgroups and reads X twice: row ranges, then codes);
- *   k_hi <= 256; act_quant symmetric or asymmetric. */
+ *   k_hi <= 256; act_quant symmetric or asymmetric; batch <= 65535 and batch * n_top <= 65535 (grid
+ *   dimensions of the transform kernels). */
 
 /* Validates desc, quantizes W per output channel (absmax/7, round to nearest even; section
  * "Large Language Models", Set-up: round-to-nearest weights, one scale per output channel) into
@@ -145,16 +152,20 @@ int32_t stamp_plan_hi_rows(const stamp_plan_t* plan);
 /* host_out[p] = physical row (0 <= row < seq_len) of STaMP slot p; a permutation. */
 stamp_status_t stamp_plan_row_of_coeff(const stamp_plan_t* plan, int32_t* host_out);
 
-/* Steps 1-2 of Algorithm "STaMP Linear": T = L X along the tokens, then per-token symmetric
- * quantization of Eq. 1: scale_i = max_j|T_ij| / qmax_i, code = rne(T_ij * (qmax_i / max)),
- * qmax = 127 for the first k_hi STaMP slots and 7 for the rest.  Outputs in the layouts above.
+/* Steps 1-2 of Algorithm "STaMP Linear": T = L X along the tokens, then per-token quantization of
+ * Eq. 1 in the form the plan's act_quant selects (see stamp_act_quant_t), at 8 bits for the first
+ * k_hi STaMP slots and 4 bits for the rest.  Outputs in the layouts above.
  * One quantized activation may feed several linears (the paper's q/k/v fan-out). */
 stamp_status_t stamp_quantize_act(const stamp_plan_t* plan, const void* X_dev, int8_t* q_hi_dev,
                                   uint8_t* q_lo_dev, float* scales_dev, void* workspace_dev,
                                   size_t workspace_bytes, void* hip_stream);
 
-/* The whole layer, Algorithm "STaMP Linear": quantize_act, integer GEMM on int8 MFMA with i32
- * accumulation, dequantization, inverse transform, bias, store Y. */
+/* The whole layer, Algorithm "STaMP Linear": quantize_act, the integer GEMM on the matrix cores (the
+ * exact integer sums under either engine, see stamp_plan_set_gemm_engine; the default is the FP6 pipeline
+ * for the 4-bit rows and the int8 pipeline for the 8-bit rows), dequantization, inverse transform, bias,
+ * store Y.  The 8-bit rows' integer sums are converted to fp32 exactly while 128 * 7 * d_in < 2^24
+ * (d_in <= 18720); on wider layers a sum beyond 2^24 (only reachable by adversarial inputs) is rounded
+ * to fp32 (relative 2^-24) before it is scaled. */
 stamp_status_t stamp_linear_forward(const stamp_plan_t* plan, const void* X_dev, void* Y_dev,
                                     void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
@@ -202,7 +213,9 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* plan, int32_t stage, co
 
 /* Selects the implementation of steps 3-5: 0 = GEMM with the dequantization and the in-block
  * inverse transform fused into its epilogue (default where the shape allows it), 1 = GEMM writing
- * dequantized fp32 rows to the workspace followed by a separate inverse kernel. */
+ * dequantized fp32 rows to the workspace followed by a separate inverse kernel.
+ * For tests and measurements: it modifies the plan (not thread-safe, no call on the plan may be in
+ * progress on another host thread) and changes stamp_plan_workspace_bytes, which must be queried again. */
 stamp_status_t stamp_plan_set_unfused(stamp_plan_t* plan, int32_t unfused);
 
 /* Matrix pipeline that multiplies the 4-bit rows (step "Y <- X W" of Algorithm "STaMP Linear" for the
@@ -214,7 +227,8 @@ stamp_status_t stamp_plan_set_unfused(stamp_plan_t* plan, int32_t unfused);
  *                    acc / 64 exactly (|acc| <= 49 d_in < 2^24).  Costs one conversion pass over the
  *                    packed rows inside stamp_linear_forward(_q);
  *   STAMP_GEMM_INT8  the codes as int8, int8 x int8 -> int32 MFMA.
- * The 8-bit rows always run on the int8 pipeline.  May be changed between calls; the workspace size
+ * The 8-bit rows always run on the int8 pipeline.  May be changed between calls (it modifies the plan:
+ * not thread-safe, no call on the plan may be in progress on another host thread); the workspace size
  * does not depend on it.  Returns STAMP_ERR_UNSUPPORTED for any other value. */
 typedef enum { STAMP_GEMM_INT8 = 0, STAMP_GEMM_FP6 = 1 } stamp_gemm_engine_t;
 stamp_status_t stamp_plan_set_gemm_engine(stamp_plan_t* plan, int32_t engine);

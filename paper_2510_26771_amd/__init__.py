@@ -17,3 +17,4 @@ from .binding import (  # noqa: F401
     STAMP_L_HAAR1D,
     STAMP_L_HAAR2D,
 )
+from .marshal import plan_desc_for, to_device_x, XFORM_CODE  # noqa: F401

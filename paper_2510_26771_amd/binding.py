@@ -179,7 +179,7 @@ class StampPlan:
         return out
 
     def set_gemm_engine(self, engine):
-        """engine: "int8" (default) or "fp6": the matrix pipeline that multiplies the 4-bit rows."""
+        """engine: "fp6" (default) or "int8": the matrix pipeline that multiplies the 4-bit rows."""
         code = {"int8": 0, "fp6": 1}[engine] if isinstance(engine, str) else int(engine)
         _check(self.lib.stamp_plan_set_gemm_engine(self._h, code), "stamp_plan_set_gemm_engine")
 

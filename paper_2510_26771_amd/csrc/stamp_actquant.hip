@@ -7,10 +7,11 @@
 // Floating-point contract (decides the integer codes, so it is fixed): every coefficient is the
 // difference (or sum) of two block sums built by plain pairwise fp32 adds, multiplied once by
 // norm(l) = fl(2^(-l/2)); absmax a over the row; scale = a / qmax; inv = qmax / a (IEEE
-// divisions); code = rne(fl(T * inv)).  Asymmetric form: hi = max(max T, 0), nlo = max(max -T, 0),
-// range = hi + nlo, scale = range / qmax, inv = qmax / range with qmax = 2^b - 1, z = rne(fl(nlo *
-// inv)), code = clamp(rne(fl(T * inv)) + z, 0, qmax), stored as code - 2^(b-1).  This file is
-// compiled with -ffp-contract=off.
+// divisions); code = rne(fl(T * inv)).  Asymmetric form: hi = max T, nlo = max -T = -min T (the token's own
+// range, whether or not it contains 0), range = hi + nlo (a token with max = min: range = |hi|), scale =
+// range / qmax, inv = qmax / range with qmax = 2^b - 1, z = rne(fl(nlo * inv)) (any integer), code =
+// clamp(rne(fl(T * inv)) + z, 0, qmax), stored as code - 2^(b-1).  This file is compiled with
+// -ffp-contract=off.
 //
 // Kernels:
 //   k_bottom1d / k_bottom2d  one workgroup per (sequence, block of R tokens), all d_in channels;
@@ -43,23 +44,34 @@ __device__ __forceinline__ float haar_norm(int level) {
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// max over the 64 lanes of a non-negative float's bit pattern; result is wave-uniform
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-  int x = (int)v;
-  int y;
-  y = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
+// unsigned max over the 64 lanes (bit patterns of non-negative floats, or order keys of any floats);
+// result is wave-uniform
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  uint32_t y;
+  y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
   x = max(x, y);
-  y = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+  y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
   x = max(x, y);
-  y = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false);  // row_half_mirror
+  y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false);  // row_half_mirror
   x = max(x, y);
-  y = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false);  // row_mirror
+  y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false);  // row_mirror
   x = max(x, y);
-  int a = __builtin_amdgcn_readlane(x, 0);
-  int b = __builtin_amdgcn_readlane(x, 16);
-  int c = __builtin_amdgcn_readlane(x, 32);
-  int d = __builtin_amdgcn_readlane(x, 48);
-  return (uint32_t)max(max(a, b), max(c, d));
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0);
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32);
+  const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+  return max(max(a, b), max(c, d));
+}
+
+// Order key of a float of either sign: a < b as floats  <=>  key(a) < key(b) as unsigned integers
+// (negative: all bits flipped, otherwise the sign bit set).  0 is below the key of every number, so it is
+// the neutral element of an unsigned max.  The asymmetric quantizer reduces max T and max -T in this form.
+__device__ __forceinline__ uint32_t fkey(float f) {
+  const uint32_t b = __float_as_uint(f);
+  return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float fkey_inv(uint32_t k) {
+  return __uint_as_float(k ^ ((uint32_t)((int32_t)~k >> 31) | 0x80000000u));
 }
 
 __device__ __forceinline__ uint32_t absbits(float f) { return __float_as_uint(f) & 0x7FFFFFFFu; }
@@ -93,12 +105,25 @@ __device__ __forceinline__ uint32_t pack8_uint4(const float (&p)[8], float z) {
   return ((acc - (kPackBias + 0x11111110u)) + (zodd != 0.0f ? 0x11111111u : 0u)) ^ 0x88888888u;
 }
 
-// max over the 8 values of max(v, 0) and of max(-v, 0), as bit patterns of non-negative floats
+// max over the 8 values of v and of -v, as order keys
 __device__ __forceinline__ void row_posneg_bits(const float (&v)[8], uint32_t& pos, uint32_t& neg) {
   float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
   float mn = fminf(fminf(fminf(v[0], v[1]), fminf(v[2], v[3])), fminf(fminf(v[4], v[5]), fminf(v[6], v[7])));
-  pos = __float_as_uint(fmaxf(mx, 0.0f));
-  neg = __float_as_uint(fmaxf(-mn, 0.0f));
+  pos = fkey(mx);
+  neg = fkey(-mn);
+}
+
+// range, scale, reciprocal and offset of one token from hi = max T and nlo = max -T, qmax = 2^b - 1
+__device__ __forceinline__ void asym_params(float hi, float nlo, float qmax, float& scale, float& inv, float& z) {
+  float range = __fadd_rn(hi, nlo);
+  if (range == 0.0f) range = fabsf(hi);  // max = min: the token is reproduced through range = |value|
+  scale = 0.0f;
+  inv = 0.0f;
+  if (range > 0.0f) {
+    scale = __fdiv_rn(range, qmax);
+    inv = __fdiv_rn(qmax, range);
+  }
+  z = rintf(__fmul_rn(nlo, inv));
 }
 
 __device__ __forceinline__ void load8(const void* X, size_t elem_off, bool bf16, bool active, float (&v)[8]) {
@@ -168,6 +193,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
     if constexpr (ASYM) {
       uint32_t pos, neg;
       row_posneg_bits(rowv[r], pos, neg);
+      if (!active) pos = neg = 0u;  // lanes beyond the last channel hold zeros, which are not part of the token
       pos = wave_max_u32(pos);
       neg = wave_max_u32(neg);
       if (lane == 0) { part[r * 16 + wave] = pos; part_neg[r * 16 + wave] = neg; }
@@ -184,8 +210,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
   asm volatile("" ::: "memory");
   }
   // lane r prepares row r: a = fl(absmaxU * norm); scale = a / 7; inv = 7 / a
-  // (asymmetric: hi = fl(posU * norm), nlo = fl(negU * norm), range = hi + nlo, scale = range / 15,
-  //  inv = 15 / range, z = rne(fl(nlo * inv)))
+  // (asymmetric: hi = fl(max t * norm), nlo = fl(max -t * norm), then asym_params with qmax = 15)
   float mul_lane = 0.0f;
   [[maybe_unused]] float z_lane = 0.0f;
   {
@@ -202,7 +227,7 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
             s_amax + (arr == part ? 0 : kMaxBlockRows) + rm.e);
         uint32_t bits;
         asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(bits) : "v"(adr1) : "memory");
-        return __uint_as_float(bits);
+        return bits;
       }
       const uint32_t adr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint32_t*)(arr + r * 16);
       u4 v0, v1, v2, v3;
@@ -220,30 +245,25 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
         if (4 * q + 2 < nw) mbits = max(mbits, vv[q].z);
         if (4 * q + 3 < nw) mbits = max(mbits, vv[q].w);
       }
-      return __uint_as_float(mbits);
+      return mbits;
     };
     if constexpr (PASS == 1) {
-      const float mpos = reduce_waves(part);
-      if (tid < NR) gpart_blk[rm.e] = __float_as_uint(mpos);
+      const uint32_t mpos = reduce_waves(part);
+      if (tid < NR) gpart_blk[rm.e] = mpos;
       if constexpr (ASYM) {
-        const float mneg = reduce_waves(part_neg);
-        if (tid < NR) gpart_blk[gpart_neg + rm.e] = __float_as_uint(mneg);
+        const uint32_t mneg = reduce_waves(part_neg);
+        if (tid < NR) gpart_blk[gpart_neg + rm.e] = mneg;
       }
       return;
     }
     const float nrm = IS2D ? ldexpf(1.0f, -rm.level) : haar_norm(rm.level);
     float scale = 0.0f, inv = 0.0f;
     if constexpr (ASYM) {
-      const float hi = __fmul_rn(reduce_waves(part), nrm), nlo = __fmul_rn(reduce_waves(part_neg), nrm);
-      const float range = __fadd_rn(hi, nlo);
-      if (range > 0.0f) {
-        scale = __fdiv_rn(range, 15.0f);
-        inv = __fdiv_rn(15.0f, range);
-      }
-      z_lane = rintf(__fmul_rn(nlo, inv));
+      const float hi = __fmul_rn(fkey_inv(reduce_waves(part)), nrm), nlo = __fmul_rn(fkey_inv(reduce_waves(part_neg)), nrm);
+      asym_params(hi, nlo, 15.0f, scale, inv, z_lane);
       if (tid < NR && write_scales) scales_blk[zeros_off + rm.e] = z_lane;
     } else {
-      const float a = __fmul_rn(reduce_waves(part), nrm);
+      const float a = __fmul_rn(__uint_as_float(reduce_waves(part)), nrm);
       if (a > 0.0f) {
         scale = __fdiv_rn(a, 7.0f);
         inv = __fdiv_rn(7.0f, a);
@@ -295,23 +315,29 @@ __device__ __forceinline__ void finish_top_row(const float (&top)[8], int level,
 #pragma unroll
   for (int c = 0; c < 8; ++c) t[c] = __fmul_rn(top[c], nrm);
   uint32_t pos, neg = 0u;
-  if constexpr (ASYM) row_posneg_bits(t, pos, neg);
-  else pos = row_absmax_bits(t);
+  if constexpr (ASYM) {
+    row_posneg_bits(t, pos, neg);
+    if (!active) pos = neg = 0u;
+  } else {
+    pos = row_absmax_bits(t);
+  }
   pos = wave_max_u32(pos);
   neg = wave_max_u32(neg);
   if (lane == 0) { part[wave] = pos; part[16 + wave] = neg; }
   __syncthreads();
   uint32_t mp = 0u, mn = 0u;
   for (int i = 0; i < nw; ++i) { mp = max(mp, part[i]); mn = max(mn, part[16 + i]); }
-  const float a = __uint_as_float(mp), nlo = __uint_as_float(mn);
   const float qmax = ASYM ? (row8 ? 255.0f : 15.0f) : (row8 ? 127.0f : 7.0f);
-  const float range = ASYM ? __fadd_rn(a, nlo) : a;
   float scale = 0.0f, inv = 0.0f, z = 0.0f;
-  if (range > 0.0f) {
-    scale = __fdiv_rn(range, qmax);
-    inv = __fdiv_rn(qmax, range);
+  if constexpr (ASYM) {
+    asym_params(fkey_inv(mp), fkey_inv(mn), qmax, scale, inv, z);
+  } else {
+    const float a = __uint_as_float(mp);
+    if (a > 0.0f) {
+      scale = __fdiv_rn(a, qmax);
+      inv = __fdiv_rn(qmax, a);
+    }
   }
-  if constexpr (ASYM) z = rintf(__fmul_rn(nlo, inv));
   if (tid == 0) {
     scale_out[0] = scale;
     if constexpr (ASYM) scale_out[zeros_off] = z;
@@ -687,7 +713,7 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
 // ------------------------------------------------------------------------------------------
 constexpr int kTopCh = 32;
 
-// asym: the partial maxima are of max(t, 0); those of max(-t, 0) follow npart words further on.
+// asym: the partial maxima are order keys of max t; those of max -t follow npart words further on.
 // L = number of top levels (0: the block sums are only normalised).
 __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t* __restrict__ rowmax_part, int k, int d,
                                              int is2d, int G, int r_bottom, int L, int asym, size_t npart) {
@@ -759,23 +785,24 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
     const float t = __fmul_rn(s_buf[q * stride + ch], nrm);
     if (cact) base[(size_t)e * d + c_base + ch] = t;
     // max over the 32 channels of this row: lanes of one row are 32 consecutive lanes
-    auto max32 = [](int x) {
-      int yv;
-      yv = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false); x = max(x, yv);
-      yv = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false); x = max(x, yv);
-      yv = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); x = max(x, yv);
-      yv = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); x = max(x, yv);
-      yv = __shfl_xor(x, 16, 64); x = max(x, yv);
+    auto max32 = [](uint32_t x) {
+      uint32_t yv;
+      yv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false); x = max(x, yv);
+      yv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false); x = max(x, yv);
+      yv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false); x = max(x, yv);
+      yv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false); x = max(x, yv);
+      yv = (uint32_t)__shfl_xor((int)x, 16, 64); x = max(x, yv);
       return x;
     };
     const size_t slot = ((size_t)b * k + e) * gridDim.x + blockIdx.x;
     if (!asym) {
-      const int x = max32((int)absbits(t));
-      if (ch == 0) rowmax_part[slot] = (uint32_t)x;
+      const uint32_t x = max32(absbits(t));
+      if (ch == 0) rowmax_part[slot] = x;
     } else {
-      const int xp = max32((int)__float_as_uint(fmaxf(t, 0.0f)));
-      const int xn = max32((int)__float_as_uint(fmaxf(-t, 0.0f)));
-      if (ch == 0) { rowmax_part[slot] = (uint32_t)xp; rowmax_part[npart + slot] = (uint32_t)xn; }
+      // channels beyond d_in contribute the neutral key
+      const uint32_t xp = max32(cact ? fkey(t) : 0u);
+      const uint32_t xn = max32(cact ? fkey(-t) : 0u);
+      if (ch == 0) { rowmax_part[slot] = xp; rowmax_part[npart + slot] = xn; }
     }
   }
 }
@@ -800,24 +827,20 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
     if ((threadIdx.x & 63) == 0) { s_red[threadIdx.x >> 6] = m; s_red[4 + (threadIdx.x >> 6)] = mneg; }
     __syncthreads();
   }
-  const float a = __uint_as_float(max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3])));
-  const float nlo = __uint_as_float(max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7])));
+  const uint32_t mp = max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3]));
+  const uint32_t mn = max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7]));
   // rows beyond the first khi are 4-bit rows (same data path, codes held as int8)
   const bool row8 = p < khi;
   const float qmax_s = row8 ? 127.0f : 7.0f, qmax_u = row8 ? 255.0f : 15.0f;
   float scale = 0.0f, inv = 0.0f, z = 0.0f;
   if (!asym) {
+    const float a = __uint_as_float(mp);
     if (a > 0.0f) {
       scale = __fdiv_rn(a, qmax_s);
       inv = __fdiv_rn(qmax_s, a);
     }
   } else {
-    const float range = __fadd_rn(a, nlo);
-    if (range > 0.0f) {
-      scale = __fdiv_rn(range, qmax_u);
-      inv = __fdiv_rn(qmax_u, range);
-    }
-    z = rintf(__fmul_rn(nlo, inv));
+    asym_params(fkey_inv(mp), fkey_inv(mn), qmax_u, scale, inv, z);
   }
   if (threadIdx.x == 0) {
     scales[(size_t)b * s + (size_t)p * R] = scale;
@@ -871,17 +894,20 @@ __global__ __launch_bounds__(256) void k_quant_rows(const void* __restrict__ X, 
   mneg = wave_max_u32(mneg);
   if ((tid & 63) == 0) { s_red[tid >> 6] = mpos; s_red[4 + (tid >> 6)] = mneg; }
   __syncthreads();
-  const float a = __uint_as_float(max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3])));
-  const float nlo = __uint_as_float(max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7])));
+  const uint32_t mp = max(max(s_red[0], s_red[1]), max(s_red[2], s_red[3]));
+  const uint32_t mn = max(max(s_red[4], s_red[5]), max(s_red[6], s_red[7]));
   const bool hi = pr < k;
   const float qmax = ASYM ? (hi ? 255.0f : 15.0f) : (hi ? 127.0f : 7.0f);
-  const float range = ASYM ? __fadd_rn(a, nlo) : a;
   float scale = 0.0f, inv = 0.0f, z = 0.0f;
-  if (range > 0.0f) {
-    scale = __fdiv_rn(range, qmax);
-    inv = __fdiv_rn(qmax, range);
+  if constexpr (ASYM) {
+    asym_params(fkey_inv(mp), fkey_inv(mn), qmax, scale, inv, z);
+  } else {
+    const float a = __uint_as_float(mp);
+    if (a > 0.0f) {
+      scale = __fdiv_rn(a, qmax);
+      inv = __fdiv_rn(qmax, a);
+    }
   }
-  if constexpr (ASYM) z = rintf(__fmul_rn(nlo, inv));
   if (tid == 0) {
     scales[m] = scale;
     if constexpr (ASYM) scales[zeros_off + m] = z;

@@ -53,6 +53,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   if (d->xform == STAMP_L_IDENTITY) {
     // tokens quantized as they are: any number of 8-bit tokens (none included), no blocks, no inverse
     if (d->k_hi > 256) return STAMP_ERR_UNSUPPORTED;
+    if (d->batch > 65535 || (int64_t)d->batch * d->k_hi > 65535) return STAMP_ERR_UNSUPPORTED;  // grid dimensions
     g->ident = 1;
     g->R = 1;
     *fused_ok = 1;
@@ -100,6 +101,8 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
     *fused_ok = 1;
   }
   g->L = g->J - g->r;
+  // batch and batch * (top rows) are grid dimensions y / z of the transform and inverse kernels
+  if (d->batch > 65535 || (int64_t)d->batch * g->k > 65535) return STAMP_ERR_UNSUPPORTED;
   return STAMP_OK;
 }
 

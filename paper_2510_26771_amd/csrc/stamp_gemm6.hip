@@ -5,7 +5,7 @@
 // mantissa field |c| (a subnormal); |c| = 8 is 1.0 (exponent field 1, mantissa 0): either way the six
 // bits are just sign and 4-bit magnitude.  v_mfma_f32_32x32x64_f8f6f4
 // multiplies such operands exactly and accumulates in fp32; every product is a multiple of 1/64 and a
-// whole sum stays below 2^24 / 64 in magnitude (d_in <= 8192, |c c'| <= 56), so the fp32 accumulator
+// whole sum stays below 2^24 / 64 in magnitude (|c c'| <= 56 and d_in <= 32768: 56 * 32768 < 2^24), so the fp32 accumulator
 // holds acc / 64 EXACTLY, where acc is the integer sum the int8 pipeline computes: same result bit for
 // bit, at twice the matrix rate per clock.  The factor 64 is folded into the row scale.
 //

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "stamp.h"
 
 #define STAMP_HD __host__ __device__ __forceinline__
@@ -140,11 +142,16 @@ struct stamp_plan {
 // Dynamic-LDS limit of a kernel, raised once per device and kernel (the attribute belongs to the device's
 // copy of the function): `done` is the kernel's own table, one size per device.
 constexpr int kStampMaxDevices = 64;
+inline std::mutex& stamp_lds_mutex() {
+  static std::mutex m;  // one lock for all tables: taken once per launch, never contended for long
+  return m;
+}
 inline hipError_t stamp_allow_lds(const void* kernel, size_t bytes, size_t (&done)[kStampMaxDevices]) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= kStampMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(stamp_lds_mutex());  // plans may be used from several host threads
   if (bytes <= done[dev]) return hipSuccess;
   e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
   if (e == hipSuccess) done[dev] = bytes;

@@ -10,28 +10,11 @@ import numpy as np
 from gen import Workload, make_inputs
 from oracle import stamp_oracle as so
 
-XFORM_CODE = {"identity": 0, "haar1d": 1, "haar2d": 2}
+from paper_2510_26771_amd.marshal import XFORM_CODE, plan_desc_for, to_device_x  # noqa: F401  (used by the tests through this module)
 
 
 def log(msg: str):
     print(f"[stamp-test {time.strftime('%H:%M:%S')}] {msg}", flush=True)
-
-
-def plan_desc_for(w: Workload, y_dtype: str = "f32"):
-    import paper_2510_26771_amd as st
-    return st.PlanDesc(batch=w.batch, seq_len=w.seq_len, d_in=w.d_in, d_out=w.d_out, xform=XFORM_CODE[w.xform],
-                       levels=w.levels, grid_h=w.grid_h, grid_w=w.grid_w, k_hi=w.k_hi, bits_hi=w.bits_hi,
-                       bits_lo=w.bits_lo, bits_w=w.bits_w,
-                       x_dtype=st.STAMP_BF16 if w.x_dtype == "bf16" else st.STAMP_F32,
-                       y_dtype=st.STAMP_BF16 if y_dtype == "bf16" else st.STAMP_F32,
-                       act_quant=1 if w.act_quant == "asym" else 0)
-
-
-def to_device_x(inp: dict, w: Workload):
-    import torch
-    if w.x_dtype == "bf16":
-        return torch.from_numpy(inp["X_store"].view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(inp["X_store"]).cuda()
 
 
 def unpack_int4(q_lo: np.ndarray) -> np.ndarray:
@@ -82,7 +65,8 @@ def near_boundary_mask(T: np.ndarray, bits: np.ndarray, asym: bool) -> np.ndarra
     """Elements whose fp32 value T * inv lies within 1 ulp of a rounding boundary (a half-integer)."""
     if asym:
         qm = np.where(bits == 8, np.float32(255), np.float32(15)).astype(np.float32)
-        a = (np.maximum(np.max(T, axis=-1), np.float32(0)) - np.minimum(np.min(T, axis=-1), np.float32(0))).astype(np.float32)
+        a = (np.max(T, axis=-1) - np.min(T, axis=-1)).astype(np.float32)
+        a = np.where(a == 0, np.abs(np.max(T, axis=-1)), a).astype(np.float32)
     else:
         qm = np.where(bits == 8, np.float32(127), np.float32(7)).astype(np.float32)
         a = np.max(np.abs(T), axis=-1)
@@ -133,19 +117,37 @@ def run_oracle(w: Workload, inp: dict, cols: Optional[np.ndarray] = None) -> Dic
     return out
 
 
-def check_output(y_gpu: np.ndarray, y_ref: np.ndarray, y_is_bf16: bool, what: str) -> float:
-    """Output bar: max |y - ref| <= 1e-3 * max|ref| (fp32 stores); a bf16 store may add half a bf16
-    ulp of the element (2^-9 relative) on top, the rounding of the output format itself."""
-    y_gpu = y_gpu.astype(np.float64)
-    y_ref = y_ref.astype(np.float64)
-    scale = float(np.max(np.abs(y_ref)))
-    err = np.abs(y_gpu - y_ref)
-    tol = 1e-3 * scale
-    if y_is_bf16:
-        tol = tol + np.abs(y_ref) * 2.0 ** -8
-    worst = float(np.max(err - tol))
+# fp32 evaluation-order slack of the dequantization + inverse transform, relative to max|Y_ref|: the two
+# sides may order the at most r + J + 3 <= 20 roundings of an output differently (each <= 2^-24 of the column's
+# largest coefficient); 64 * 2^-24 leaves a factor of three.  Observed: 1e-7 .. 3e-7.
+FP32_ORDER_SLACK = 64.0 * 2.0 ** -24
+
+
+def check_output(y_gpu: np.ndarray, y_ref: np.ndarray, y_is_bf16: bool, what: str, stats: Optional[dict] = None) -> float:
+    """Output bar.  fp32 stores: max |y - ref| <= 1e-3 * max|ref| (the stated tolerance), plainly.
+    bf16 stores: the library rounds its fp32 result g to bf16; |g - ref| <= delta = FP32_ORDER_SLACK * max|ref|
+    and rounding is monotonic, so every stored value must lie between the oracle's rounding of ref - delta and
+    of ref + delta (for all but the elements within delta of a rounding boundary that is the oracle's own bf16
+    value; the others are its bf16 neighbour).  The number of stored values that differ from round_to_bf16(ref)
+    is reported in stats["bf16_nonidentical"]."""
     assert np.isfinite(y_gpu).all(), f"{what}: non-finite output"
-    assert worst <= 0.0, f"{what}: max err {float(err.max()):.3e} vs scale {scale:.3e}"
+    ref64 = y_ref.astype(np.float64)
+    scale = float(np.max(np.abs(ref64)))
+    err = np.abs(y_gpu.astype(np.float64) - ref64)
+    if not y_is_bf16:
+        assert float(err.max()) <= 1e-3 * scale, f"{what}: max err {float(err.max()):.3e} vs scale {scale:.3e}"
+    else:
+        delta = FP32_ORDER_SLACK * scale
+        lo = so.round_to_bf16((ref64 - delta).astype(np.float32))
+        hi = so.round_to_bf16((ref64 + delta).astype(np.float32))
+        y = y_gpu.astype(np.float32)
+        bad = int(np.count_nonzero((y < lo) | (y > hi)))
+        assert bad == 0, (f"{what}: {bad} bf16 outputs outside [bf16(ref - delta), bf16(ref + delta)], "
+                          f"max err {float(err.max()):.3e} vs scale {scale:.3e}")
+        nonid = int(np.count_nonzero(y != so.round_to_bf16(y_ref.astype(np.float32))))
+        if stats is not None:
+            stats["bf16_nonidentical"] = stats.get("bf16_nonidentical", 0) + nonid
+            stats["bf16_compared"] = stats.get("bf16_compared", 0) + int(y.size)
     return float(err.max() / scale) if scale > 0 else 0.0
 
 
@@ -158,8 +160,10 @@ def y_to_numpy(Y, y_is_bf16: bool) -> np.ndarray:
 
 def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: Optional[np.ndarray] = None,
               check_acc: bool = True, check_unfused: bool = True,
-              engines: Tuple[str, ...] = ("fp6", "int8")) -> Dict[str, float]:
-    """Everything the ABI exposes, on one workload, against the oracle, under each GEMM engine."""
+              engines: Tuple[str, ...] = ("fp6", "int8"), also_f32_out: bool = False) -> Dict[str, float]:
+    """Everything the ABI exposes, on one workload, against the oracle, under each GEMM engine.
+    also_f32_out: a second plan with fp32 output runs the fused path on the same inputs and is held to the
+    plain 1e-3 bar (for cases whose main plan stores bf16)."""
     import torch
     import paper_2510_26771_amd as st
 
@@ -228,7 +232,7 @@ def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: 
             torch.cuda.synchronize()
             y_np = y_to_numpy(pick(Y), y_bf16)
             tag = ("unfused" if unfused else "fused") + "_" + engine
-            report[f"y_relerr_{tag}"] = check_output(y_np, y_ref, y_bf16, f"{w.name} {tag}")
+            report[f"y_relerr_{tag}"] = check_output(y_np, y_ref, y_bf16, f"{w.name} {tag}", report)
             # and from the separately quantized activation
             Y2 = torch.zeros_like(Y)
             plan.linear_forward_q(q_hi, q_lo, scales, Y2, ws)
@@ -242,6 +246,17 @@ def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: 
                     assert torch.equal(Y, y_first), f"engine {engine} and engine {engines[0]} disagree"
             del Y2, ws
     del y_first
-    log(f"outputs ok: {report}")
     plan.destroy()
+    if also_f32_out and y_bf16:
+        plan32 = st.StampPlan(plan_desc_for(w, "f32"), Wd, bd)
+        ws = plan32.alloc_workspace()
+        for engine in engines:
+            plan32.set_gemm_engine(engine)
+            Y = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=torch.float32, device="cuda")
+            plan32.linear_forward(Xd, Y, ws)
+            torch.cuda.synchronize()
+            report[f"y_relerr_f32out_{engine}"] = check_output(pick(Y).numpy(), y_ref, False, f"{w.name} f32 out {engine}")
+            del Y
+        plan32.destroy()
+    log(f"outputs ok: {report}")
     return report

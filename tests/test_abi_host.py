@@ -72,6 +72,10 @@ def _good(**kw):
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=4, k_hi=8), 3),   # k not a power of four
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=32, grid_w=8, levels=3, k_hi=16), 3),   # non-square grid
     (dict(w_dtype=st.STAMP_BF16), 3),
+    # batch and batch * (top rows) are grid dimensions of the transform kernels: beyond 65535 the plan is refused
+    (dict(batch=65536, seq_len=64, levels=6, k_hi=8), 3),
+    (dict(batch=512, seq_len=1024, levels=10, k_hi=128), 3),
+    (dict(xform=st.STAMP_L_IDENTITY, levels=0, batch=512, k_hi=128, seq_len=256), 3),
 ])
 def test_plan_create_rejects_before_any_device_call(lib, kw, expect):
     assert _create(lib, _good(**kw)) == expect
