@@ -169,6 +169,18 @@ stamp_status_t stamp_quantize_act(const stamp_plan_t* plan, const void* X_dev, i
 stamp_status_t stamp_linear_forward(const stamp_plan_t* plan, const void* X_dev, void* Y_dev,
                                     void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* stamp_linear_forward for callers that cannot allocate or pass device scratch memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation and same kernels; the
+ * scratch memory is a static device array of STAMP_STATIC_SCRATCH_BYTES inside the library (one per GPU, held
+ * until the process ends) instead of a caller workspace.  The call allocates nothing.  A plan whose
+ * stamp_plan_workspace_bytes exceeds STAMP_STATIC_SCRATCH_BYTES is refused with STAMP_ERR_WORKSPACE before
+ * anything is launched.  Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU
+ * (different streams or threads) race; issue them on one stream, or order them with events.  Nothing in the
+ * array has to be cleared between calls (each call writes what it later reads). */
+#define STAMP_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+stamp_status_t stamp_linear_forward_static(const stamp_plan_t* plan, const void* X_dev, void* Y_dev,
+                                           void* hip_stream);
+
 /* Steps 3-5 from an already quantized activation (buffers as written by stamp_quantize_act). */
 stamp_status_t stamp_linear_forward_q(const stamp_plan_t* plan, const int8_t* q_hi_dev,
                                       const uint8_t* q_lo_dev, const float* scales_dev, void* Y_dev,

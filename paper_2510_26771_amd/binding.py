@@ -15,13 +15,14 @@ _LIB_NAME = "libstamp_hip.so"
 
 STAMP_F32, STAMP_BF16 = 0, 1
 STAMP_L_IDENTITY, STAMP_L_HAAR1D, STAMP_L_HAAR2D = 0, 1, 2
+STAMP_STATIC_SCRATCH_BYTES = 64 << 20  # include/stamp.h
 STATUS_NAMES = {0: "STAMP_OK", 1: "STAMP_ERR_NULL", 2: "STAMP_ERR_SHAPE", 3: "STAMP_ERR_UNSUPPORTED",
                 4: "STAMP_ERR_WORKSPACE", 5: "STAMP_ERR_ALLOC", 6: "STAMP_ERR_DEVICE"}
 
 # every symbol include/stamp.h declares
 EXPORTS = ["stamp_plan_create", "stamp_plan_destroy", "stamp_plan_workspace_bytes", "stamp_plan_hi_rows",
            "stamp_plan_row_of_coeff",
-           "stamp_quantize_act", "stamp_linear_forward", "stamp_linear_forward_q", "stamp_inverse",
+           "stamp_quantize_act", "stamp_linear_forward", "stamp_linear_forward_static", "stamp_linear_forward_q", "stamp_inverse",
            "stamp_debug_gemm_acc", "stamp_debug_weight_codes", "stamp_debug_run_stage", "stamp_plan_set_unfused", "stamp_plan_set_gemm_engine",
            "stamp_debug_mfma_rate", "stamp_status_string"]
 
@@ -94,6 +95,8 @@ def load_library():
     lib.stamp_quantize_act.restype = C.c_int
     lib.stamp_linear_forward.argtypes = [vp, vp, vp, vp, sz, vp]
     lib.stamp_linear_forward.restype = C.c_int
+    lib.stamp_linear_forward_static.argtypes = [vp, vp, vp, vp]
+    lib.stamp_linear_forward_static.restype = C.c_int
     lib.stamp_linear_forward_q.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
     lib.stamp_linear_forward_q.restype = C.c_int
     lib.stamp_inverse.argtypes = [vp, vp, i32, vp, vp, sz, vp]
@@ -198,6 +201,11 @@ class StampPlan:
     def linear_forward(self, X, Y, workspace, stream=None):
         _check(self.lib.stamp_linear_forward(self._h, _ptr(X), _ptr(Y), _ptr(workspace), workspace.numel(),
                                              _stream(stream)), "stamp_linear_forward")
+
+    def linear_forward_static(self, X, Y, stream=None):
+        """stamp_linear_forward on the library's static scratch array (no workspace, no allocation)."""
+        _check(self.lib.stamp_linear_forward_static(self._h, _ptr(X), _ptr(Y), _stream(stream)),
+               "stamp_linear_forward_static")
 
     def linear_forward_q(self, q_hi, q_lo, scales, Y, workspace, stream=None):
         _check(self.lib.stamp_linear_forward_q(self._h, _ptr(q_hi), _ptr(q_lo), _ptr(scales), _ptr(Y), _ptr(workspace),

@@ -6,7 +6,30 @@
 
 #include "stamp_internal.h"
 
+// Scratch memory of stamp_linear_forward_static: one array per GPU, part of the loaded code object.  In host
+// code this name only stands for the symbol; the device address comes from hipGetSymbolAddress (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[STAMP_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// device address of `scratch` on the current device, looked up once per device
+stamp_status_t static_scratch(void** out) {
+  static void* ptr[kStampMaxDevices] = {};
+  static std::mutex mu;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStampMaxDevices) return STAMP_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return STAMP_ERR_DEVICE;
+    }
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return STAMP_OK;
+}
 
 inline bool is_pow2(int64_t n) { return n >= 1 && (n & (n - 1)) == 0; }
 inline int ilog2(int64_t n) { int l = 0; while ((int64_t(1) << (l + 1)) <= n) ++l; return l; }
@@ -326,6 +349,15 @@ stamp_status_t stamp_linear_forward(const stamp_plan_t* p, const void* X, void* 
                                        reinterpret_cast<uint32_t*>(at(ws, p->ws_gpart)), st);
   if (e != hipSuccess) return STAMP_ERR_DEVICE;
   return forward_q(p, q_hi, q_lo, scales, Y, ws, st);
+}
+
+stamp_status_t stamp_linear_forward_static(const stamp_plan_t* p, const void* X, void* Y, void* hip_stream) {
+  if (p == nullptr || X == nullptr || Y == nullptr) return STAMP_ERR_NULL;
+  if (p->ws_total > STAMP_STATIC_SCRATCH_BYTES) return STAMP_ERR_WORKSPACE;  // the plan needs more than the static array holds
+  void* ws = nullptr;
+  const stamp_status_t ss = static_scratch(&ws);
+  if (ss != STAMP_OK) return ss;
+  return stamp_linear_forward(p, X, Y, ws, STAMP_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 stamp_status_t stamp_inverse(const stamp_plan_t* p, const float* Yt, int32_t n_cols, void* Y, void* ws, size_t ws_bytes,

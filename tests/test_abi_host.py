@@ -89,6 +89,7 @@ def test_null_arguments(lib):
     assert lib.stamp_plan_row_of_coeff(None, None) == 1
     assert lib.stamp_quantize_act(None, None, None, None, None, None, 0, None) == 1
     assert lib.stamp_linear_forward(None, None, None, None, 0, None) == 1
+    assert lib.stamp_linear_forward_static(None, None, None, None) == 1
     assert lib.stamp_linear_forward_q(None, None, None, None, None, None, 0, None) == 1
     assert lib.stamp_inverse(None, None, 1, None, None, 0, None) == 1
     assert lib.stamp_debug_gemm_acc(None, None, None, None, None) == 1
