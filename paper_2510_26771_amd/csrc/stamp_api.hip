@@ -229,7 +229,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   memset(p, 0, sizeof(*p));
   p->desc = *desc;
   p->geom = g;
-  p->fused_ok = fused_ok;
+  p->fused_ok = fused_ok && (g.ident || g.N % 2 == 0);  // the fused inverse stores pairs of columns: even d_out
   p->unfused = 0;
   p->engine = STAMP_GEMM_FP6;
   p->Kpad = ((g.d + 127) / 128) * 128;

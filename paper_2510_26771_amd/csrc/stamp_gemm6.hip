@@ -20,6 +20,7 @@
 // per 128 columns.  The global image equals the LDS image, so a K step is staged by plain asynchronous
 // 16-byte copies.
 #include "stamp_gemm_common.h"
+#include "stamp_epilogue_reg.h"
 
 namespace {
 
@@ -112,7 +113,10 @@ __global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, c
   const int KT = Kpad >> 7;
   const int kt = frag >> 2, f = frag & 3;
   // fragment f is the (f >> 1)-th half of the 48-byte stream of lane group kg = f & 1
-  uint8_t* dst = b6 + ((size_t)(n >> 7) * KT + kt) * kStageB6 + (size_t)((n & 127) >> 5) * kBlock6 + (f & 1) * 512 + (n & 31) * 16;
+  // output column n = 64 w + 2 l + ni sits in the 32-column block 2 w + ni at row l: a lane of the GEMM then holds
+  // two neighbouring output columns (stamp_epilogue_reg.h)
+  const int blk = ((n & 127) >> 6) * 2 + (n & 1), rowb = (n & 63) >> 1;
+  uint8_t* dst = b6 + ((size_t)(n >> 7) * KT + kt) * kStageB6 + (size_t)blk * kBlock6 + (f & 1) * 512 + rowb * 16;
   for (int p = 0; p < 3; ++p) {
     const int off = (f >> 1) * 24 + p * 8;
     *reinterpret_cast<uint64_t*>(dst + (off >> 4) * kPart + (off & 15)) = part[p];
@@ -124,157 +128,254 @@ __global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, c
 // traffic per product than two independent 256 x 128 workgroups would need (the FP6 pipeline consumes a K
 // step in half the time of the int8 one, which makes that traffic the bound).  Three stages: the loads of
 // steps kt+1 and kt+2 are in flight while step kt is multiplied.
+//
+// The kernel is persistent: one workgroup per CU walks its share of the tiles (the XCD-aware order of
+// tile_of_sid, every workgroup of an XCD taking every wx-th tile of that XCD's range), and the operand
+// pipeline runs on across tile boundaries: the first two K steps of the next tile are requested during the last
+// two steps of the current one, so they, and the stores of the epilogue, are in flight while the epilogue
+// computes.  The epilogue works in registers (stamp_epilogue_reg.h) and leaves the operand stages alone.
 constexpr int BN6 = 256;
-constexpr int kWaves6 = 8;
 constexpr int kStage6 = kStageA6 + 2 * kStageB6;  // 48 KB
 constexpr int kNumStage6 = 3;
-constexpr int kTileBytes6 = kWaves6 * kWaveTileBytes;
+
+// tile of position sid in the walk: 8 M-tiles, then the next N-tile, group of 8 M-tiles after group
+__device__ __forceinline__ void tile_of_sid(int sid, int mt, int nt, int& tm, int& tn) {
+  const int per_group = kGroupM * nt;
+  const int grp = sid / per_group, in_grp = sid - grp * per_group;
+  const int gm = min(kGroupM, mt - grp * kGroupM);
+  tm = grp * kGroupM + in_grp % gm;
+  tn = in_grp / gm;
+}
 
 template <int EPI, int RB, bool IS2D, bool YBF16>
 __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   using Acc = AccF6Lo;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   constexpr int kMainBytes = kNumStage6 * kStage6;
-  constexpr int kRowInfoOff = (EPI >= 2 && kTileBytes6 > kMainBytes) ? kTileBytes6 : kMainBytes;
+  uint8_t* const row_info = smem + kMainBytes;  // two buffers of kRowInfoBytes, alternating from tile to tile
   constexpr int nA = kStageA6 / (512 * 16), nB = 2 * kStageB6 / (512 * 16);  // 16-byte chunks per thread and step: 3 and 3
+  constexpr int kLoadsPerStep = nA + nB;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
   const int wm = wave >> 2, wn = wave & 3;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
-  const int l32 = lane & 31, kg = lane >> 5;
-  int tm, tn;
-  tile_of_block(a.M, a.Npad, BN6, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN6;
   const int KT = a.Kpad / BK;
+  const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN6, total = mt * nt;
+
+  // tiles of this workgroup: the XCD's contiguous range of the walk, every wx-th position from `local` on
+  const int nwg = (int)gridDim.x, xcd = (int)blockIdx.x % kNumXcd, local = (int)blockIdx.x / kNumXcd;
+  const int wx = (nwg - xcd + kNumXcd - 1) / kNumXcd;  // workgroups that run on this XCD
+  const int tall = total / kNumXcd, rem = total % kNumXcd;
+  const int first = xcd * tall + min(xcd, rem), count = tall + (xcd < rem ? 1 : 0);
+  if (local >= count) return;
 
   // global image = LDS image: chunk q = i * 512 + tid of an operand's stage goes to byte 16 q.  The
   // weight stage is two column tiles of 128 (KT * 12 KB apart in memory): chunks 0..767 and 768..1535;
-  // the boundary falls between waves, so the source tile of a pass is wave-uniform.
-  const uint8_t* gA = a.A + (size_t)tm * KT * kStageA6 + tid * 16;
-  const uint8_t* gB[nB];
+  // the boundary falls between waves, so the source tile of a pass is wave-uniform.  Addresses are a
+  // wave-uniform base (tile, K step, pass) plus this thread's constant 32-bit offset.
+  const uint32_t offA = (uint32_t)tid * 16u;
+  const uint32_t offB = (uint32_t)(tid & 255) * 16u + ((wave & 4) ? 4096u : 0u);  // chunk (i * 512 + tid) mod 768, pass by pass:
+  // pass 0: chunks tid (column tile 0); pass 1: chunks 512 + tid: waves 0-3 are chunks 512..767 of tile 0, waves 4-7
+  // chunks 0..255 of tile 1; pass 2: chunks 256 + tid of tile 1
+  // cursor of the requests: K step rq_kt of the tile at position rq_pos of this workgroup's walk (all scalar)
+  int rq_pos = local, rq_kt = 0, rq_stg = 0;
+  const uint8_t* rqA = nullptr;
+  const uint8_t* rqB = nullptr;
+  auto rq_tile = [&]() {
+    int tm_, tn_;
+    tile_of_sid(first + rq_pos, mt, nt, tm_, tn_);
+    rqA = a.A + (size_t)tm_ * KT * kStageA6;
+    rqB = a.Bq + (size_t)(2 * tn_) * KT * kStageB6;
+  };
+  rq_tile();
+  // requests the next K step of the walk into the next stage of the ring; false when the walk is over
+  auto request_next = [&]() -> bool {
+    if (rq_pos >= count) return false;
+    uint8_t* so_ = smem + rq_stg * kStage6 + wave * 1024;
+    const uint8_t* sa_ = rqA + (size_t)rq_kt * kStageA6;
 #pragma unroll
-  for (int i = 0; i < nB; ++i) {
-    const int q = i * 512 + tid;
-    const int half = (i * 512 + wave * 64) >= 768 ? 1 : 0;
-    gB[i] = a.Bq + ((size_t)(2 * tn + half) * KT) * kStageB6 + (size_t)(q - half * 768) * 16;
-  }
-#define STAMP_REQUEST6(KSTEP, STG)                                                                               \
-  do {                                                                                                           \
-    uint8_t* so_ = smem + (STG) * kStage6 + wave * 1024;                                                         \
-    const uint8_t* sa_ = gA + (size_t)(KSTEP) * kStageA6;                                                        \
-    _Pragma("unroll") for (int i = 0; i < nA; ++i)                                                               \
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * 8192),        \
-                                         (void __attribute__((address_space(3)))*)(so_ + i * 8192), 16, 0, 0);   \
-    _Pragma("unroll") for (int i = 0; i < nB; ++i)                                                               \
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(gB[i] + (size_t)(KSTEP) * kStageB6), \
-                                         (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * 8192), 16, 0, 0); \
-  } while (0)
-  constexpr int kLoadsPerStep = nA + nB;
+    for (int i = 0; i < nA; ++i)
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * 8192 + offA),
+                                       (void __attribute__((address_space(3)))*)(so_ + i * 8192), 16, 0, 0);
+    const uint8_t* sb0 = rqB + (size_t)rq_kt * kStageB6;              // column tile 0 of the pair
+    const uint8_t* sb1 = rqB + ((size_t)KT + rq_kt) * kStageB6;       // column tile 1
+    const uint8_t* srcB[nB] = {sb0 + offB,                              // pass 0: waves 0-3 chunks 0..255, waves 4-7 chunks 256..511 of tile 0
+                               (wave & 4) ? (sb1 + offB - 4096) : (sb0 + offB + 8192),  // pass 1
+                               sb1 + offB + 4096};                      // pass 2: chunks 256..767 of tile 1
+#pragma unroll
+    for (int i = 0; i < nB; ++i)
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)srcB[i],
+                                       (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * 8192), 16, 0, 0);
+    rq_stg = (rq_stg == kNumStage6 - 1) ? 0 : rq_stg + 1;
+    if (++rq_kt == KT) {
+      rq_kt = 0;
+      rq_pos += wx;
+      if (rq_pos < count) rq_tile();
+    }
+    return true;
+  };
 
   // LDS byte addresses of part 0 of this lane's 48 bytes in stage 0: 32-row block, then lane * 16
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
-  uint32_t adrA[4], adrB[NI];
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi) adrA[mi] = (uint32_t)((wm * 4 + mi) * kBlock6 + lane * 16);
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni)
-    adrB[ni] = (uint32_t)(kStageA6 + (wn >> 1) * kStageB6 + ((wn & 1) * 2 + ni) * kBlock6 + lane * 16);
+  const uint32_t adrA0 = (uint32_t)((wm * 4) * kBlock6 + lane * 16);
+  const uint32_t adrB0 = (uint32_t)(kStageA6 + (wn >> 1) * kStageB6 + ((wn & 1) * 2) * kBlock6 + lane * 16);
 
-  v16f acc[4][NI];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-  STAMP_REQUEST6(0, 0);
-  if (1 < KT) STAMP_REQUEST6(1, 1);
-  EpiOperands<EPI, RB, IS2D> eo;
-  eo.request(a, m0, n0, lane, wm, wn);
-  if (tid < 256) store_row_info<Acc, EPI>(a, m0, tid, smem + kRowInfoOff);
+  request_next();
+  bool prev_requested = request_next();  // was a request issued one step ago (it may still be in flight)
+  {
+    int tm0, tn0;
+    tile_of_sid(first + local, mt, nt, tm0, tn0);
+    if (tid < 256) store_row_info<Acc, EPI>(a, tm0 * BM, tid, row_info);
+  }
   asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the epilogue operands and steps 0 and 1 have landed
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   asm volatile("" ::: "memory");
+  int landed = 2;  // K steps from here on whose loads are known to have landed (no wait needed)
+  int stg = 0;     // stage of the step about to be multiplied
+  int rbuf = 0;    // row-info buffer of the current tile
 
-  // Step kt: this wave's loads of step kt have landed (those of step kt+1 may still be in flight);
-  // workgroup barrier (all of step kt is visible and the stage of step kt-1 is free); request step kt+2
-  // into that stage; then the two MFMA halves of the step.
-  int stg = 0;  // stage of step kt
-  for (int kt = 0; kt < KT; ++kt) {
-    asm volatile("" ::: "memory");
-    if (kt > 0) {
-      if (kt + 1 < KT) __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStep);  // vmcnt(one step's loads)
-      else __builtin_amdgcn_s_waitcnt(0x0F70);
-    }
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    if (kt + 2 < KT) STAMP_REQUEST6(kt + 2, (stg == 0 ? 2 : stg - 1));
-    __builtin_amdgcn_sched_barrier(0);
+  for (int pos = local; pos < count; pos += wx) {
+    int tm, tn;
+    tile_of_sid(first + pos, mt, nt, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN6;
+    const int nw = n0 + wn * 64;
 
+    v16f acc[4][NI];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // Step kt: this wave's loads of step kt have landed (those of the step after it may still be in flight);
+    // workgroup barrier (all of step kt is visible and the stage of step kt-1 is free); request the step two
+    // ahead into that stage; then the two MFMA halves of the step.
+    //
     // The step's 12 fragments (per MFMA half k: 2 of the weights, 4 of the activations) arrive as 6 x 3
     // 16-byte reads: parts 0 and 1 hold the first half's fragment (6 registers) and the first 2 registers of
     // the second half's, part 2 the rest.  The reads are written out by hand (outputs of a two-read statement
     // are early-clobber: the address register must outlive the first read) and so are the waits: the part-2
     // reads stay in flight under the first half's MFMAs.  A wait names the registers it covers, which keeps
     // the MFMAs behind it.
-    const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
-    u4 a0[4], a1[4], a2[4], b0[NI], b1[NI], b2[NI];
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-      asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3"
-                   : "=&v"(b0[ni]), "=&v"(b1[ni]) : "v"(sa + adrB[ni]), "n"(kPart));
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-      asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:%3"
-                   : "=&v"(a0[mi]), "=&v"(a1[mi]) : "v"(sa + adrA[mi]), "n"(kPart));
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b2[ni]) : "v"(sa + adrB[ni]), "n"(2 * kPart));
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a2[mi]) : "v"(sa + adrA[mi]), "n"(2 * kPart));
-    asm volatile("s_waitcnt lgkmcnt(6)"
-                 : "+v"(a0[0]), "+v"(a0[1]), "+v"(a0[2]), "+v"(a0[3]), "+v"(b0[0]), "+v"(b0[1]),
-                   "+v"(a1[0]), "+v"(a1[1]), "+v"(a1[2]), "+v"(a1[3]), "+v"(b1[0]), "+v"(b1[1]));
-    v6i fa[2][4], fb[2][NI];
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) fb[0][ni] = (v6i)(u6)__builtin_shufflevector(b0[ni], b1[ni], 0, 1, 2, 3, 4, 5);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) fa[0][mi] = (v6i)(u6)__builtin_shufflevector(a0[mi], a1[mi], 0, 1, 2, 3, 4, 5);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    auto step = [&]() __attribute__((always_inline)) {
+      asm volatile("" ::: "memory");
+      if (landed > 0) {
+        --landed;
+      } else {
+        if (prev_requested) __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStep);  // vmcnt(one step's loads)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+      }
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      prev_requested = request_next();
+      __builtin_amdgcn_sched_barrier(0);
+      const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
+      u4 a0[4], a1[4], a2[4], b0[NI], b1[NI], b2[NI];
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[0][mi]), widen(fb[0][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a2[0]), "+v"(a2[1]), "+v"(a2[2]), "+v"(a2[3]), "+v"(b2[0]), "+v"(b2[1]));
+        asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
+                     : "=&v"(b0[ni]), "=&v"(b1[ni]) : "v"(sa + adrB0), "n"(ni * kBlock6), "n"(ni * kBlock6 + kPart));
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) fb[1][ni] = (v6i)(u6)__builtin_shufflevector(b1[ni], b2[ni], 2, 3, 4, 5, 6, 7);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) fa[1][mi] = (v6i)(u6)__builtin_shufflevector(a1[mi], a2[mi], 2, 3, 4, 5, 6, 7);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+      for (int mi = 0; mi < 4; ++mi)
+        asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
+                     : "=&v"(a0[mi]), "=&v"(a1[mi]) : "v"(sa + adrA0), "n"(mi * kBlock6), "n"(mi * kBlock6 + kPart));
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[1][mi]), widen(fb[1][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    stg = (stg == 2) ? 0 : stg + 1;
-  }
-  __syncthreads();
-#undef STAMP_REQUEST6
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b2[ni]) : "v"(sa + adrB0), "n"(ni * kBlock6 + 2 * kPart));
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a2[mi]) : "v"(sa + adrA0), "n"(mi * kBlock6 + 2 * kPart));
+      asm volatile("s_waitcnt lgkmcnt(6)"
+                   : "+v"(a0[0]), "+v"(a0[1]), "+v"(a0[2]), "+v"(a0[3]), "+v"(b0[0]), "+v"(b0[1]),
+                     "+v"(a1[0]), "+v"(a1[1]), "+v"(a1[2]), "+v"(a1[3]), "+v"(b1[0]), "+v"(b1[1]));
+      v6i fa[2][4], fb[2][NI];
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) fb[0][ni] = (v6i)(u6)__builtin_shufflevector(b0[ni], b1[ni], 0, 1, 2, 3, 4, 5);
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) fa[0][mi] = (v6i)(u6)__builtin_shufflevector(a0[mi], a1[mi], 0, 1, 2, 3, 4, 5);
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[0][mi]), widen(fb[0][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a2[0]), "+v"(a2[1]), "+v"(a2[2]), "+v"(a2[3]), "+v"(b2[0]), "+v"(b2[1]));
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) fb[1][ni] = (v6i)(u6)__builtin_shufflevector(b1[ni], b2[ni], 2, 3, 4, 5, 6, 7);
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) fa[1][mi] = (v6i)(u6)__builtin_shufflevector(a1[mi], a2[mi], 2, 3, 4, 5, 6, 7);
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[1][mi]), widen(fb[1][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      stg = (stg == kNumStage6 - 1) ? 0 : stg + 1;
+    };
+    for (int kt = 0; kt < KT; ++kt) step();
 
-  epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave, wm, wn);
+    // Everything requested so far (the next tile's first two steps included) must have landed before the
+    // epilogue issues its stores: the counter retires in order, so a later wait for a load would also wait for
+    // every store before it.  After the epilogue the next two steps therefore need no wait.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    asm volatile("" ::: "memory");
+    landed = 2;
+    // the epilogue's operands from global memory: their latency passes under the lane swaps and the scaling
+    // Per-lane values of the epilogue are derived from an opaque copy of the lane number, so that they are
+    // computed here, once per tile, instead of being carried in registers across the main loop (which has none
+    // to spare: a spilled value would be reloaded with a wait for all outstanding loads inside that loop).
+    int lane_e = lane, tid_e = tid;
+    asm volatile("" : "+v"(lane_e), "+v"(tid_e));
+    RegEpiOperands<EPI, (IS2D ? 2 * RB : RB)> eo;
+    if constexpr (EPI >= 2) eo.request(a, m0, nw, wm, lane_e);
+    // row factors of the next tile: loaded now, written to the other buffer after the epilogue (a barrier of
+    // the next tile's first step publishes them long before its epilogue reads them)
+    float nfac = 0.0f, nrz = 0.0f;
+    int ndst = -1;
+    const bool has_next = pos + wx < count;
+    if (has_next && wave < 4) {
+      int tm1, tn1;
+      tile_of_sid(first + pos + wx, mt, nt, tm1, tn1);
+      compute_row_info<Acc, EPI>(a, tm1 * BM, tid_e, nfac, ndst, nrz);
+    }
+    const uint8_t* ri = row_info + rbuf * kRowInfoBytes;
+    if constexpr (EPI != 2) {
+      // The loads just requested complete here, on every path and in a form the compiler's wait-count bookkeeping
+      // sees: a load it believed pending at the end of the tile would make it wait for ALL loads inside the next
+      // main loop.  (The fused epilogue places this wait after its lane swaps.)
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    }
+    if constexpr (EPI >= 2) {
+      epilogue_reg<EPI, RB, IS2D, YBF16>(a, acc, ri, eo, m0, nw, wm, lane_e);
+    } else {
+      EpiOperands<EPI, RB, IS2D> none;
+      epilogue<Acc, EPI, RB, IS2D, YBF16, true>(a, acc, smem, ri, none, m0, n0, lane_e, wave, wm, wn);
+    }
+    rbuf ^= 1;
+    if (has_next && wave < 4) write_row_info(row_info + rbuf * kRowInfoBytes, tid_e, nfac, ndst, nrz);
+  }
+}
+
+int gemm6_workgroups(int tiles) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+  }
+  return tiles < cus ? tiles : cus;
 }
 
 template <int EPI, int RB, bool IS2D, bool YBF16>
 hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
-  constexpr size_t main_lds = (size_t)kNumStage6 * kStage6;
-  constexpr size_t epi_lds = (EPI >= 2) ? (size_t)kTileBytes6 : 0;
-  constexpr size_t lds = (main_lds > epi_lds ? main_lds : epi_lds) + kRowInfoBytes;
+  constexpr size_t lds = (size_t)kNumStage6 * kStage6 + 2 * kRowInfoBytes;
   static size_t lds_done[kStampMaxDevices] = {};
   hipError_t e = stamp_allow_lds(reinterpret_cast<const void*>(&k_gemm6<EPI, RB, IS2D, YBF16>), lds, lds_done);
   if (e != hipSuccess) return e;
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN6;
-  hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16>), dim3(mt * nt), dim3(512), lds, st, a);
+  hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16>), dim3(gemm6_workgroups(mt * nt)), dim3(512), lds, st, a);
   return hipGetLastError();
 }
 

@@ -265,14 +265,12 @@ struct EpiOperands {
 // accumulator units, of tile row `tid`, written to LDS at row_info (kRowInfoBytes) before the main
 // loop; the main loop's barriers publish them.
 template <typename Acc, int EPI>
-__device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int tid, uint8_t* row_info) {
+__device__ __forceinline__ void compute_row_info(const GemmArgs& a, int m0, int tid, float& fac, int& dst, float& rz) {
   const StampGeom& g = a.g;
-  float* s_rowfac = reinterpret_cast<float*>(row_info);     // [256]
-  int* s_rowdst = reinterpret_cast<int*>(row_info + 1024);  // [256] destination row or -1
-  float* s_rowz = reinterpret_cast<float*>(row_info + 2048);  // [256] (z - 2^(b-1)) / kToAcc
   const int m = m0 + tid;
-  float fac = 0.0f, rz = 0.0f;
-  int dst = -1;
+  fac = 0.0f;
+  rz = 0.0f;
+  dst = -1;
   const size_t zeros_off = (size_t)g.B * g.s;
   if (m < a.M && g.ident) {
     // no sequence transform: row = token, level 0 (norm 1); tokens 0..k-1 of a sequence are the 8-bit rows
@@ -322,9 +320,20 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
       dst = (EPI == 0) ? (b * g.s + p) : m;
     }
   }
-  s_rowfac[tid] = fac;
-  s_rowdst[tid] = dst;
-  s_rowz[tid] = rz;
+}
+
+__device__ __forceinline__ void write_row_info(uint8_t* row_info, int tid, float fac, int dst, float rz) {
+  reinterpret_cast<float*>(row_info)[tid] = fac;        // [256]
+  reinterpret_cast<int*>(row_info + 1024)[tid] = dst;   // [256] destination row or -1
+  reinterpret_cast<float*>(row_info + 2048)[tid] = rz;  // [256] (z - 2^(b-1)) / kToAcc
+}
+
+template <typename Acc, int EPI>
+__device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int tid, uint8_t* row_info) {
+  float fac, rz;
+  int dst;
+  compute_row_info<Acc, EPI>(a, m0, tid, fac, dst, rz);
+  write_row_info(row_info, tid, fac, dst, rz);
 }
 
 // Epilogue of one workgroup tile; to be called after a workgroup barrier that follows the last read
@@ -334,7 +343,9 @@ __device__ __forceinline__ void store_row_info(const GemmArgs& a, int m0, int ti
 // physical rows of [B*s][N]; 8-bit rows: [B*k][N]); 2 = fused in-block inverse + bias -> Y (4-bit
 // rows only); RB = log2 of the block length for EPI 2 (1-D: tokens, 2-D: side); 3 = plans without a
 // sequence transform: dequantized rows + bias -> Y through the same staging (4-bit rows only).
-template <typename Acc, int EPI, int RB, bool IS2D, bool YBF16>
+// PAIRCOLS: the weights are stored so that MFMA column l32 of block ni is column 2 l32 + ni of the wave's 64
+// (the FP6 engine's layout) instead of 32 ni + l32.
+template <typename Acc, int EPI, int RB, bool IS2D, bool YBF16, bool PAIRCOLS = false>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&acc)[4][NI], uint8_t* smem,
                                          const uint8_t* row_info, const EpiOperands<EPI, RB, IS2D>& eo, int m0,
                                          int n0, int lane, int wave, int wm, int wn) {
@@ -347,7 +358,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
   if constexpr (EPI == 0 || EPI == 1) {
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-      const int n = n0 + wn * (32 * NI) + ni * 32 + l32;
+      const int n = n0 + wn * (32 * NI) + (PAIRCOLS ? 2 * l32 + ni : ni * 32 + l32);
       const float swn = a.sw[n];
       const float csn = (EPI == 1 && g.asym) ? a.colsum[n] : 0.0f;
 #pragma unroll
