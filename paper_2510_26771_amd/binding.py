@@ -67,7 +67,8 @@ _lib = None
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, _LIB_NAME)
+    """The in-tree library; STAMP_LIB_PATH names another build of it (kernel variants under measurement)."""
+    return os.environ.get("STAMP_LIB_PATH") or os.path.join(_HERE, _LIB_NAME)
 
 
 def load_library():

@@ -197,8 +197,10 @@ __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI
 
 // EPI 2: fused in-block inverse (RB = log2 of the block length in 1-D, of the block side in 2-D);
 // EPI 3: plans without a sequence transform (rows are tokens).
-template <int EPI, int RB, bool IS2D, bool YBF16, bool VEC>
-__device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f (&accv)[4][NI], const uint8_t* row_info,
+// accv: the wave's accumulators, 4 x NIW blocks; this call handles the column pair PAIR (blocks 2 PAIR, 2 PAIR + 1:
+// the 64 columns from nw on).
+template <int EPI, int RB, bool IS2D, bool YBF16, bool VEC, int NIW, int PAIR>
+__device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f (&accv)[4][NIW], const uint8_t* row_info,
                                                   const RegEpiOperands<EPI, (IS2D ? 2 * RB : RB)>& eo, int m0, int nw,
                                                   int wm, int lane) {
   const StampGeom& g = a.g;
@@ -209,7 +211,7 @@ __device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f 
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = accv[mi][ni][v];
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = accv[mi][2 * PAIR + ni][v];
   const int l32 = lane & 31, kg = lane >> 5;
   const float* s_rowfac = reinterpret_cast<const float*>(row_info);
   const int* s_rowdst = reinterpret_cast<const int*>(row_info + 1024);
@@ -267,14 +269,14 @@ __device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f 
   }
 }
 
-template <int EPI, int RB, bool IS2D, bool YBF16>
-__device__ __forceinline__ void epilogue_reg(const GemmArgs& a, const v16f (&acc)[4][NI], const uint8_t* row_info,
+template <int EPI, int RB, bool IS2D, bool YBF16, int NIW = NI, int PAIR = 0>
+__device__ __forceinline__ void epilogue_reg(const GemmArgs& a, const v16f (&acc)[4][NIW], const uint8_t* row_info,
                                              const RegEpiOperands<EPI, (IS2D ? 2 * RB : RB)>& eo, int m0, int nw, int wm,
                                              int lane) {
   // pairs of columns are stored as one word when d_out is even (the pair then never straddles the end); the
   // fused inverse is only launched on even d_out (odd widths take the separate inverse kernel)
-  if (EPI == 2 || (a.N & 1) == 0) epilogue_reg_impl<EPI, RB, IS2D, YBF16, true>(a, acc, row_info, eo, m0, nw, wm, lane);
-  else epilogue_reg_impl<EPI, RB, IS2D, YBF16, false>(a, acc, row_info, eo, m0, nw, wm, lane);
+  if (EPI == 2 || (a.N & 1) == 0) epilogue_reg_impl<EPI, RB, IS2D, YBF16, true, NIW, PAIR>(a, acc, row_info, eo, m0, nw, wm, lane);
+  else epilogue_reg_impl<EPI, RB, IS2D, YBF16, false, NIW, PAIR>(a, acc, row_info, eo, m0, nw, wm, lane);
 }
 
 }  // namespace stamp_gemm

@@ -150,14 +150,17 @@ __device__ __forceinline__ void tile_of_sid(int sid, int mt, int nt, int& tm, in
 template <int EPI, int RB, bool IS2D, bool YBF16>
 __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   using Acc = AccF6Lo;
+  constexpr int NIW = NI;  // 32-column MFMA blocks per wave along N
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  constexpr int NT = 512;  // threads
   constexpr int kMainBytes = kNumStage6 * kStage6;
   uint8_t* const row_info = smem + kMainBytes;  // two buffers of kRowInfoBytes, alternating from tile to tile
-  constexpr int nA = kStageA6 / (512 * 16), nB = 2 * kStageB6 / (512 * 16);  // 16-byte chunks per thread and step: 3 and 3
+  constexpr int nA = kStageA6 / (NT * 16), nB = 2 * kStageB6 / (NT * 16);  // 16-byte chunks per thread and step
   constexpr int kLoadsPerStep = nA + nB;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
-  const int wm = wave >> 2, wn = wave & 3;  // wave tile: rows [128 wm, +128), columns [64 wn, +64)
+  // wave tile: rows [128 wm, +128), columns [32 NIW wn, +32 NIW)
+  const int wm = wave >> 2, wn = wave & 3;
   const int KT = a.Kpad / BK;
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN6, total = mt * nt;
 
@@ -168,14 +171,11 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   const int first = xcd * tall + min(xcd, rem), count = tall + (xcd < rem ? 1 : 0);
   if (local >= count) return;
 
-  // global image = LDS image: chunk q = i * 512 + tid of an operand's stage goes to byte 16 q.  The
+  // global image = LDS image: chunk q = i * NT + tid of an operand's stage goes to byte 16 q.  The
   // weight stage is two column tiles of 128 (KT * 12 KB apart in memory): chunks 0..767 and 768..1535;
   // the boundary falls between waves, so the source tile of a pass is wave-uniform.  Addresses are a
   // wave-uniform base (tile, K step, pass) plus this thread's constant 32-bit offset.
-  const uint32_t offA = (uint32_t)tid * 16u;
-  const uint32_t offB = (uint32_t)(tid & 255) * 16u + ((wave & 4) ? 4096u : 0u);  // chunk (i * 512 + tid) mod 768, pass by pass:
-  // pass 0: chunks tid (column tile 0); pass 1: chunks 512 + tid: waves 0-3 are chunks 512..767 of tile 0, waves 4-7
-  // chunks 0..255 of tile 1; pass 2: chunks 256 + tid of tile 1
+  const uint32_t off16 = (uint32_t)tid * 16u;
   // cursor of the requests: K step rq_kt of the tile at position rq_pos of this workgroup's walk (all scalar)
   int rq_pos = local, rq_kt = 0, rq_stg = 0;
   const uint8_t* rqA = nullptr;
@@ -194,17 +194,16 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     const uint8_t* sa_ = rqA + (size_t)rq_kt * kStageA6;
 #pragma unroll
     for (int i = 0; i < nA; ++i)
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * 8192 + offA),
-                                       (void __attribute__((address_space(3)))*)(so_ + i * 8192), 16, 0, 0);
-    const uint8_t* sb0 = rqB + (size_t)rq_kt * kStageB6;              // column tile 0 of the pair
-    const uint8_t* sb1 = rqB + ((size_t)KT + rq_kt) * kStageB6;       // column tile 1
-    const uint8_t* srcB[nB] = {sb0 + offB,                              // pass 0: waves 0-3 chunks 0..255, waves 4-7 chunks 256..511 of tile 0
-                               (wave & 4) ? (sb1 + offB - 4096) : (sb0 + offB + 8192),  // pass 1
-                               sb1 + offB + 4096};                      // pass 2: chunks 256..767 of tile 1
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * (NT * 16) + off16),
+                                       (void __attribute__((address_space(3)))*)(so_ + i * (NT * 16)), 16, 0, 0);
 #pragma unroll
-    for (int i = 0; i < nB; ++i)
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)srcB[i],
-                                       (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * 8192), 16, 0, 0);
+    for (int i = 0; i < nB; ++i) {
+      // chunk i * NT + tid of the 1536: column tile 1 from chunk 768 on (a whole number of waves)
+      const bool half = (i * NT + wave * 64) >= 768;
+      const uint8_t* sb_ = rqB + ((size_t)(half ? KT : 0) + rq_kt) * kStageB6 + (half ? (i * NT * 16 - 768 * 16) : (i * NT * 16));
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sb_ + off16),
+                                       (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * (NT * 16)), 16, 0, 0);
+    }
     rq_stg = (rq_stg == kNumStage6 - 1) ? 0 : rq_stg + 1;
     if (++rq_kt == KT) {
       rq_kt = 0;
@@ -237,13 +236,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     int tm, tn;
     tile_of_sid(first + pos, mt, nt, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN6;
-    const int nw = n0 + wn * 64;
+    const int nw = n0 + wn * (32 * NIW);
 
-    v16f acc[4][NI];
+    v16f acc[4][NIW];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
+      for (int j = 0; j < NIW; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
@@ -251,7 +250,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     // workgroup barrier (all of step kt is visible and the stage of step kt-1 is free); request the step two
     // ahead into that stage; then the two MFMA halves of the step.
     //
-    // The step's 12 fragments (per MFMA half k: 2 of the weights, 4 of the activations) arrive as 6 x 3
+    // The step's fragments (per MFMA half k: NIW of the weights, 4 of the activations) arrive as (4 + NIW) x 3
     // 16-byte reads: parts 0 and 1 hold the first half's fragment (6 registers) and the first 2 registers of
     // the second half's, part 2 the rest.  The reads are written out by hand (outputs of a two-read statement
     // are early-clobber: the address register must outlive the first read) and so are the waits: the part-2
@@ -270,9 +269,9 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       prev_requested = request_next();
       __builtin_amdgcn_sched_barrier(0);
       const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
-      u4 a0[4], a1[4], a2[4], b0[NI], b1[NI], b2[NI];
+      u4 a0[4], a1[4], a2[4], b0[NIW], b1[NIW], b2[NIW];
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
+      for (int ni = 0; ni < NIW; ++ni)
         asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
                      : "=&v"(b0[ni]), "=&v"(b1[ni]) : "v"(sa + adrB0), "n"(ni * kBlock6), "n"(ni * kBlock6 + kPart));
 #pragma unroll
@@ -280,7 +279,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
         asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
                      : "=&v"(a0[mi]), "=&v"(a1[mi]) : "v"(sa + adrA0), "n"(mi * kBlock6), "n"(mi * kBlock6 + kPart));
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
+      for (int ni = 0; ni < NIW; ++ni)
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b2[ni]) : "v"(sa + adrB0), "n"(ni * kBlock6 + 2 * kPart));
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi)
@@ -288,25 +287,25 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       asm volatile("s_waitcnt lgkmcnt(6)"
                    : "+v"(a0[0]), "+v"(a0[1]), "+v"(a0[2]), "+v"(a0[3]), "+v"(b0[0]), "+v"(b0[1]),
                      "+v"(a1[0]), "+v"(a1[1]), "+v"(a1[2]), "+v"(a1[3]), "+v"(b1[0]), "+v"(b1[1]));
-      v6i fa[2][4], fb[2][NI];
+      v6i fa[2][4], fb[2][NIW];
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) fb[0][ni] = (v6i)(u6)__builtin_shufflevector(b0[ni], b1[ni], 0, 1, 2, 3, 4, 5);
+      for (int ni = 0; ni < NIW; ++ni) fb[0][ni] = (v6i)(u6)__builtin_shufflevector(b0[ni], b1[ni], 0, 1, 2, 3, 4, 5);
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) fa[0][mi] = (v6i)(u6)__builtin_shufflevector(a0[mi], a1[mi], 0, 1, 2, 3, 4, 5);
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int ni = 0; ni < NIW; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[0][mi]), widen(fb[0][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
       asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a2[0]), "+v"(a2[1]), "+v"(a2[2]), "+v"(a2[3]), "+v"(b2[0]), "+v"(b2[1]));
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) fb[1][ni] = (v6i)(u6)__builtin_shufflevector(b1[ni], b2[ni], 2, 3, 4, 5, 6, 7);
+      for (int ni = 0; ni < NIW; ++ni) fb[1][ni] = (v6i)(u6)__builtin_shufflevector(b1[ni], b2[ni], 2, 3, 4, 5, 6, 7);
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi) fa[1][mi] = (v6i)(u6)__builtin_shufflevector(a1[mi], a2[mi], 2, 3, 4, 5, 6, 7);
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int ni = 0; ni < NIW; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[1][mi]), widen(fb[1][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       stg = (stg == kNumStage6 - 1) ? 0 : stg + 1;
@@ -320,12 +319,12 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     asm volatile("" ::: "memory");
     landed = 2;
-    // the epilogue's operands from global memory: their latency passes under the lane swaps and the scaling
     // Per-lane values of the epilogue are derived from an opaque copy of the lane number, so that they are
     // computed here, once per tile, instead of being carried in registers across the main loop (which has none
     // to spare: a spilled value would be reloaded with a wait for all outstanding loads inside that loop).
     int lane_e = lane, tid_e = tid;
     asm volatile("" : "+v"(lane_e), "+v"(tid_e));
+    // the epilogue's operands from global memory: their latency passes under the lane swaps
     RegEpiOperands<EPI, (IS2D ? 2 * RB : RB)> eo;
     if constexpr (EPI >= 2) eo.request(a, m0, nw, wm, lane_e);
     // row factors of the next tile: loaded now, written to the other buffer after the epilogue (a barrier of
@@ -333,7 +332,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     float nfac = 0.0f, nrz = 0.0f;
     int ndst = -1;
     const bool has_next = pos + wx < count;
-    if (has_next && wave < 4) {
+    if (has_next && tid_e < 256) {
       int tm1, tn1;
       tile_of_sid(first + pos + wx, mt, nt, tm1, tn1);
       compute_row_info<Acc, EPI>(a, tm1 * BM, tid_e, nfac, ndst, nrz);
@@ -353,7 +352,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       epilogue<Acc, EPI, RB, IS2D, YBF16, true>(a, acc, smem, ri, none, m0, n0, lane_e, wave, wm, wn);
     }
     rbuf ^= 1;
-    if (has_next && wave < 4) write_row_info(row_info + rbuf * kRowInfoBytes, tid_e, nfac, ndst, nrz);
+    if (has_next && tid_e < 256) write_row_info(row_info + rbuf * kRowInfoBytes, tid_e, nfac, ndst, nrz);
   }
 }
 
