@@ -167,6 +167,171 @@ def haar1d_matrix(s: int, levels: int) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------------------
+# 1-D Haar DWT of any length, and with the first token left out of the transform.
+#
+# The paper picks the Haar wavelet for needing next to no padding (footnote to the DWT paragraph of section
+# "Efficient Energy Concentration") and, for language models, keeps the first token (the attention sink) out
+# of L and at 8 bits (appendix "Experimental details", LLMs, STaMP paragraph), which leaves s - 1 tokens: an odd
+# number.  It does not say how an odd number of approximations is split.  Reading taken: a level pairs the
+# current approximations (0,1), (2,3), ...; an odd one out is carried to the next level unchanged, as its last
+# approximation (no padding, L stays orthogonal).  A carried token has a different weight than a pair sum, so
+# the normalisation cannot wait until the end: every level is the textbook orthonormal butterfly
+# a = (x0 + x1) * C, d = (x0 - x1) * C with C = fl(1 / sqrt 2), each operation rounded.
+# STaMP order: [token 0 if it is left out] [approximations of the last level] [details coarse to fine].
+# --------------------------------------------------------------------------------------
+
+def ragged_level_sizes(n: int, levels: int):
+    """Numbers of approximations n_0 = n, n_l = ceil(n_(l-1) / 2) after each level."""
+    sizes = [n]
+    for _ in range(levels):
+        sizes.append((sizes[-1] + 1) // 2)
+    return sizes
+
+
+def max_ragged_levels(n: int) -> int:
+    """Levels after which a single approximation is left."""
+    l = 0
+    while n > 1:
+        n = (n + 1) // 2
+        l += 1
+    return l
+
+
+def haar1d_ragged_forward(x: np.ndarray, levels: int, dtype=np.float32, skip_first: bool = False) -> np.ndarray:
+    """J-level orthonormal Haar DWT of x[s, ...] along axis 0 for any s, result in STaMP order."""
+    ft = np.dtype(dtype).type
+    C = ft(0.70710678118654752440)
+    t = np.array(x, dtype=dtype, copy=True)
+    o = 1 if skip_first else 0
+    n = t.shape[0] - o
+    if levels < 0 or levels > max_ragged_levels(max(n, 1)):
+        raise ValueError("more levels than the sequence allows")
+    for _ in range(levels):
+        m = n // 2
+        w = t[o:o + n].copy()
+        t[o:o + m] = (w[0:2 * m:2] + w[1:2 * m:2]) * C
+        if n % 2:
+            t[o + m] = w[n - 1]
+        nn = (n + 1) // 2
+        t[o + nn:o + nn + m] = (w[0:2 * m:2] - w[1:2 * m:2]) * C
+        n = nn
+    return t
+
+
+def haar1d_ragged_inverse(t: np.ndarray, levels: int, dtype=np.float32, skip_first: bool = False) -> np.ndarray:
+    """Inverse (= transpose) of haar1d_ragged_forward."""
+    ft = np.dtype(dtype).type
+    C = ft(0.70710678118654752440)
+    x = np.array(t, dtype=dtype, copy=True)
+    o = 1 if skip_first else 0
+    sizes = ragged_level_sizes(x.shape[0] - o, levels)
+    for l in range(levels, 0, -1):
+        n, nn = sizes[l - 1], sizes[l]
+        m = n // 2
+        a = x[o:o + nn].copy()
+        d = x[o + nn:o + nn + m].copy()
+        x[o:o + 2 * m:2] = (a[:m] + d) * C
+        x[o + 1:o + 2 * m:2] = (a[:m] - d) * C
+        if n % 2:
+            x[o + n - 1] = a[nn - 1]
+    return x
+
+
+def haar1d_ragged_matrix(s: int, levels: int, skip_first: bool = False) -> np.ndarray:
+    """Dense fp64 L (s x s) of the ragged transform, as a product of one-level matrices: level l is the identity
+    outside its n_(l-1) approximations, and inside them has the rows (e_2i + e_2i+1) / sqrt 2 for every pair,
+    e_last for an odd one out, then (e_2i - e_2i+1) / sqrt 2 for every pair."""
+    o = 1 if skip_first else 0
+    L = np.eye(s)
+    n = s - o
+    r = 1.0 / math.sqrt(2.0)
+    for _ in range(levels):
+        H = np.eye(s)
+        m, nn = n // 2, (n + 1) // 2
+        H[o:o + n, o:o + n] = 0.0
+        for i in range(m):
+            H[o + i, o + 2 * i] = r
+            H[o + i, o + 2 * i + 1] = r
+            H[o + nn + i, o + 2 * i] = r
+            H[o + nn + i, o + 2 * i + 1] = -r
+        if n % 2:
+            H[o + m, o + n - 1] = 1.0
+        L = H @ L
+        n = nn
+    return L
+
+
+# --------------------------------------------------------------------------------------
+# Walsh-Hadamard and cosine transforms along the tokens (section "Efficient Energy Concentration": the
+# Fourier-type transforms the paper compares the DWT with).
+#
+# WHT: orthonormal, rows in SEQUENCY order (row q changes sign q times), which is the order in which the
+# rows are the signs of the cosine basis and therefore the order in which "the first k tokens" are the low
+# frequencies.  Evaluated as log2(s) levels of plain butterflies (u, v) -> (u + v, u - v) at distance 1, 2, 4, ...
+# (the Hadamard-ordered fast transform), then reordered, then multiplied once by 2^(-log2(s) / 2).
+# DCT: the orthonormal DCT-II, T_k = c_k sum_n x_n cos(pi (2 n + 1) k / (2 s)), c_0 = sqrt(1 / s), c_k = sqrt(2 / s).
+# Evaluated as the dense product in fp64, whatever `dtype` is, and then rounded to `dtype`: a product of s terms
+# has no canonical fp32 order, and this way the quantized codes do not depend on one.
+# --------------------------------------------------------------------------------------
+
+def wht_sequency_permutation(s: int) -> np.ndarray:
+    """perm[q] = row of the Hadamard-ordered (Sylvester) matrix that has sequency q: the bit reversal of the
+    Gray code of q."""
+    J = s.bit_length() - 1
+    if not _is_pow2(s):
+        raise ValueError("the WHT needs a power-of-two length")
+    q = np.arange(s, dtype=np.int64)
+    g = q ^ (q >> 1)
+    rev = np.zeros_like(g)
+    for b in range(J):
+        rev |= ((g >> b) & 1) << (J - 1 - b)
+    return rev
+
+
+def wht_forward(x: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """Orthonormal sequency-ordered WHT of x[s, ...] along axis 0 (its own inverse)."""
+    t = np.array(x, dtype=dtype, copy=True)
+    s = t.shape[0]
+    J = s.bit_length() - 1
+    perm = wht_sequency_permutation(s)
+    h = 1
+    while h < s:
+        v = t.reshape((s // (2 * h), 2, h) + t.shape[1:])
+        u0 = v[:, 0].copy()
+        u1 = v[:, 1].copy()
+        v[:, 0] = u0 + u1
+        v[:, 1] = u0 - u1
+        h *= 2
+    return t[perm] * haar_norm(J, dtype)
+
+
+def wht_inverse(t: np.ndarray, dtype=np.float32) -> np.ndarray:
+    """The sequency-ordered orthonormal WHT matrix is symmetric and orthogonal: the inverse is the transform."""
+    return wht_forward(t, dtype)
+
+
+def dct_matrix(s: int) -> np.ndarray:
+    """Dense fp64 orthonormal DCT-II matrix C[k, n]."""
+    k = np.arange(s, dtype=np.float64)[:, None]
+    n = np.arange(s, dtype=np.float64)[None, :]
+    C = np.cos(np.pi * (2.0 * n + 1.0) * k / (2.0 * s)) * math.sqrt(2.0 / s)
+    C[0, :] = math.sqrt(1.0 / s)
+    return C
+
+
+def dct_forward(x: np.ndarray, dtype=np.float32) -> np.ndarray:
+    x64 = np.asarray(x, dtype=np.float64)
+    s = x64.shape[0]
+    return (dct_matrix(s) @ x64.reshape(s, -1)).reshape(x64.shape).astype(dtype)
+
+
+def dct_inverse(t: np.ndarray, dtype=np.float32) -> np.ndarray:
+    t64 = np.asarray(t, dtype=np.float64)
+    s = t64.shape[0]
+    return (dct_matrix(s).T @ t64.reshape(s, -1)).reshape(t64.shape).astype(dtype)
+
+
+# --------------------------------------------------------------------------------------
 # 2-D Haar pyramid over an H x W token grid, token t = r * W + c.
 # --------------------------------------------------------------------------------------
 
@@ -309,25 +474,47 @@ def haar2d_matrix(grid_h: int, grid_w: int, levels: int) -> np.ndarray:
 # Transform dispatch
 # --------------------------------------------------------------------------------------
 
-def sequence_forward(x, xform: str, levels: int, grid_h: int = 0, grid_w: int = 0, dtype=np.float32):
+def _is_ragged(s: int, xform: str, skip_first: bool) -> bool:
+    """The 1-D Haar transform takes its ragged form when the first token is left out or the length is not a
+    power of two."""
+    return xform == "haar1d" and (skip_first or not _is_pow2(s))
+
+
+def sequence_forward(x, xform: str, levels: int, grid_h: int = 0, grid_w: int = 0, dtype=np.float32,
+                     skip_first: bool = False):
     """T = L X for one sequence x[s, ...]."""
+    if skip_first and xform != "haar1d":
+        raise ValueError("leaving the first token out is defined for the 1-D Haar transform")
     if xform == "identity":
         return np.array(x, dtype=dtype, copy=True)
     if xform == "haar1d":
+        if _is_ragged(np.shape(x)[0], xform, skip_first):
+            return haar1d_ragged_forward(x, levels, dtype, skip_first)
         return haar1d_forward(x, levels, dtype)
     if xform == "haar2d":
         return haar2d_forward(x, grid_h, grid_w, levels, dtype)
+    if xform == "wht":
+        return wht_forward(x, dtype)
+    if xform == "dct":
+        return dct_forward(x, dtype)
     raise ValueError(f"unknown transform {xform!r}")
 
 
-def sequence_inverse(t, xform: str, levels: int, grid_h: int = 0, grid_w: int = 0, dtype=np.float32):
+def sequence_inverse(t, xform: str, levels: int, grid_h: int = 0, grid_w: int = 0, dtype=np.float32,
+                     skip_first: bool = False):
     """X = L^-1 T for one sequence t[s, ...]."""
     if xform == "identity":
         return np.array(t, dtype=dtype, copy=True)
     if xform == "haar1d":
+        if _is_ragged(np.shape(t)[0], xform, skip_first):
+            return haar1d_ragged_inverse(t, levels, dtype, skip_first)
         return haar1d_inverse(t, levels, dtype)
     if xform == "haar2d":
         return haar2d_inverse(t, grid_h, grid_w, levels, dtype)
+    if xform == "wht":
+        return wht_inverse(t, dtype)
+    if xform == "dct":
+        return dct_inverse(t, dtype)
     raise ValueError(f"unknown transform {xform!r}")
 
 
@@ -428,6 +615,81 @@ def quantize_weight(W: np.ndarray, bits_w: int = 4, dtype=np.float32) -> Tuple[n
 
 
 # --------------------------------------------------------------------------------------
+# Per-block (group) scales (Experiments, LVM set-up and appendix "Experimental details", LVMs: per-block
+# weight and activation quantization with blocks of 64 channels, the setting of the paper's first table).
+# Every token keeps its bit width; inside a token every group of `group` consecutive channels has its own
+# symmetric scale (same arithmetic as quantize_tokens, per group).  Weights: per output channel, one scale
+# per group of `group` consecutive input channels.  The last group may be shorter.
+# --------------------------------------------------------------------------------------
+
+def quantize_tokens_grouped(T: np.ndarray, bits: np.ndarray, group: int = 64, dtype=np.float32):
+    """Returns (codes int8 [s, d], scales [s, G]) with G = ceil(d / group)."""
+    T = np.asarray(T, dtype=dtype)
+    s, d = T.shape
+    G = (d + group - 1) // group
+    codes = np.empty((s, d), dtype=np.int8)
+    scales = np.empty((s, G), dtype=dtype)
+    for g in range(G):
+        c, sc = quantize_tokens(T[:, g * group:(g + 1) * group], bits, dtype)
+        codes[:, g * group:(g + 1) * group] = c
+        scales[:, g] = sc
+    return codes, scales
+
+
+def quantize_weight_grouped(W: np.ndarray, bits_w: int = 4, group: int = 64, dtype=np.float32):
+    """W[d_in, d_out] -> (codes int8 [d_in, d_out], scales [G, d_out])."""
+    W = np.asarray(W, dtype=dtype)
+    d, N = W.shape
+    G = (d + group - 1) // group
+    codes = np.empty((d, N), dtype=np.int8)
+    scales = np.empty((G, N), dtype=dtype)
+    for g in range(G):
+        c, sc = quantize_weight(W[g * group:(g + 1) * group], bits_w, dtype)
+        codes[g * group:(g + 1) * group] = c
+        scales[g] = sc
+    return codes, scales
+
+
+def grouped_dequant_gemm(codes: np.ndarray, sa: np.ndarray, qw: np.ndarray, swg: np.ndarray, group: int = 64,
+                         dtype=np.float32) -> np.ndarray:
+    """Y'[m, n] = sum_g (float(acc_g[m, n]) * sa[m, g]) * swg[g, n], acc_g the exact integer sum over the
+    channels of group g, the groups added in increasing order, every operation rounded to `dtype`."""
+    M, d = codes.shape
+    N = qw.shape[1]
+    G = (d + group - 1) // group
+    Y = np.zeros((M, N), dtype=dtype)
+    for g in range(G):
+        acc = int_gemm(codes[:, g * group:(g + 1) * group], qw[g * group:(g + 1) * group])
+        Y = Y + (acc.astype(dtype) * np.asarray(sa[:, g], dtype=dtype)[:, None]) * np.asarray(swg[g], dtype=dtype)[None, :]
+    return Y
+
+
+def stamp_linear_forward_grouped(X: np.ndarray, W: np.ndarray, xform: str, levels: int, k_hi: int, group: int = 64,
+                                 bits_hi: int = 8, bits_lo: int = 4, bits_w: int = 4, grid_h: int = 0, grid_w: int = 0,
+                                 bias: Optional[np.ndarray] = None, dtype=np.float32,
+                                 skip_first: bool = False) -> Dict[str, np.ndarray]:
+    """Algorithm "STaMP Linear" with per-block scales for activations and weights."""
+    B, s, d = X.shape
+    N = W.shape[1]
+    bits = token_bits(s, k_hi, bits_hi, bits_lo)
+    qw, swg = quantize_weight_grouped(W, bits_w, group, dtype)
+    G = swg.shape[0]
+    T = np.empty((B, s, d), dtype=dtype)
+    codes = np.empty((B, s, d), dtype=np.int8)
+    scales = np.empty((B, s, G), dtype=dtype)
+    Yt = np.empty((B, s, N), dtype=dtype)
+    Y = np.empty((B, s, N), dtype=dtype)
+    for b in range(B):
+        T[b] = sequence_forward(X[b], xform, levels, grid_h, grid_w, dtype, skip_first)
+        codes[b], scales[b] = quantize_tokens_grouped(T[b], bits, group, dtype)
+        Yt[b] = grouped_dequant_gemm(codes[b], scales[b], qw, swg, group, dtype)
+        Y[b] = sequence_inverse(Yt[b], xform, levels, grid_h, grid_w, dtype, skip_first)
+    if bias is not None:
+        Y = Y + np.asarray(bias, dtype=dtype)[None, None, :]
+    return {"T": T, "codes": codes, "scales": scales, "bits": bits, "qw": qw, "swg": swg, "Yt": Yt, "Y": Y}
+
+
+# --------------------------------------------------------------------------------------
 # Integer GEMM
 # --------------------------------------------------------------------------------------
 
@@ -464,7 +726,7 @@ def round_to_bf16(y: np.ndarray) -> np.ndarray:
 
 def quantize_activation(X: np.ndarray, xform: str, levels: int, k_hi: int, bits_hi: int = 8,
                         bits_lo: int = 4, grid_h: int = 0, grid_w: int = 0,
-                        dtype=np.float32, act_quant: str = "sym") -> Dict[str, np.ndarray]:
+                        dtype=np.float32, act_quant: str = "sym", skip_first: bool = False) -> Dict[str, np.ndarray]:
     """Steps 1-2 of the algorithm for X[batch, s, d]: T = L X per sequence, then per-token
     mixed-precision codes and scales, all in STaMP order.  act_quant: "sym" (absmax, signed
     codes) or "asym" (min-max, unsigned codes and integer offsets "zeros")."""
@@ -477,7 +739,7 @@ def quantize_activation(X: np.ndarray, xform: str, levels: int, k_hi: int, bits_
     scales = np.empty((B, s), dtype=dtype)
     zeros = np.zeros((B, s), dtype=dtype)
     for b in range(B):
-        T[b] = sequence_forward(X[b], xform, levels, grid_h, grid_w, dtype)
+        T[b] = sequence_forward(X[b], xform, levels, grid_h, grid_w, dtype, skip_first)
         if asym:
             codes[b], scales[b], zeros[b] = quantize_tokens_asym(T[b], bits, dtype)
         else:
@@ -491,11 +753,15 @@ def quantize_activation(X: np.ndarray, xform: str, levels: int, k_hi: int, bits_
 def linear_from_codes(codes: np.ndarray, scales: np.ndarray, qw: np.ndarray, sw: np.ndarray,
                       xform: str, levels: int, grid_h: int = 0, grid_w: int = 0,
                       bias: Optional[np.ndarray] = None, dtype=np.float32,
-                      zeros: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+                      zeros: Optional[np.ndarray] = None, skip_first: bool = False,
+                      bias_mode: str = "after") -> Dict[str, np.ndarray]:
     """Steps 3-5: integer GEMM, dequantization Y' = (float(acc) * scale_m) * sw_n, inverse
     transform per sequence and output column, bias.  With integer offsets `zeros` (asymmetric
     codes) the de-quantization (code - z) * scale of the Background section turns the sum into
-    acc[m, n] - z_m * sum_c qw[c, n], an exact integer, before it is scaled."""
+    acc[m, n] - z_m * sum_c qw[c, n], an exact integer, before it is scaled.
+    bias_mode: "after" adds 1 bias^T to the inverse-transformed output (the algorithm's last step);
+    "transformed" adds (L 1) bias^T to the transformed output before the inverse (the third form of the
+    commutation identity of section "Method"), with l = L 1 evaluated by the forward transform in `dtype`."""
     B, s, d = codes.shape
     N = qw.shape[1]
     acc = np.empty((B, s, N), dtype=np.int32)
@@ -511,8 +777,13 @@ def linear_from_codes(codes: np.ndarray, scales: np.ndarray, qw: np.ndarray, sw:
             assert np.array_equal(zi.astype(np.float64), np.asarray(zeros[b], dtype=np.float64))
             a = a - zi[:, None] * colsum[None, :]
         Yt[b] = (a.astype(dtype) * np.asarray(scales[b], dtype=dtype)[:, None]) * sw[None, :]
-        Y[b] = sequence_inverse(Yt[b], xform, levels, grid_h, grid_w, dtype)
-    if bias is not None:
+        yt = Yt[b]
+        if bias is not None and bias_mode == "transformed":
+            ell = sequence_forward(np.ones((s, 1), dtype=dtype), xform, levels, grid_h, grid_w, dtype, skip_first)
+            yt = yt + ell * np.asarray(bias, dtype=dtype)[None, :]
+        Y[b] = sequence_inverse(yt, xform, levels, grid_h, grid_w, dtype, skip_first)
+    assert bias_mode in ("after", "transformed")
+    if bias is not None and bias_mode == "after":
         Y = Y + np.asarray(bias, dtype=dtype)[None, None, :]
     return {"acc": acc, "Yt": Yt, "Y": Y}
 
@@ -520,12 +791,13 @@ def linear_from_codes(codes: np.ndarray, scales: np.ndarray, qw: np.ndarray, sw:
 def stamp_linear_forward(X: np.ndarray, W: np.ndarray, xform: str, levels: int, k_hi: int,
                          bits_hi: int = 8, bits_lo: int = 4, bits_w: int = 4, grid_h: int = 0,
                          grid_w: int = 0, bias: Optional[np.ndarray] = None,
-                         dtype=np.float32, act_quant: str = "sym") -> Dict[str, np.ndarray]:
+                         dtype=np.float32, act_quant: str = "sym", skip_first: bool = False,
+                         bias_mode: str = "after") -> Dict[str, np.ndarray]:
     """Algorithm "STaMP Linear" end to end for X[batch, s, d_in], W[d_in, d_out]."""
-    qa = quantize_activation(X, xform, levels, k_hi, bits_hi, bits_lo, grid_h, grid_w, dtype, act_quant)
+    qa = quantize_activation(X, xform, levels, k_hi, bits_hi, bits_lo, grid_h, grid_w, dtype, act_quant, skip_first)
     qw, sw = quantize_weight(W, bits_w, dtype)
     out = linear_from_codes(qa["codes"], qa["scales"], qw, sw, xform, levels, grid_h, grid_w, bias, dtype,
-                            zeros=qa.get("zeros"))
+                            zeros=qa.get("zeros"), skip_first=skip_first, bias_mode=bias_mode)
     out.update(qa)
     out.update({"qw": qw, "sw": sw})
     return out
