@@ -38,7 +38,7 @@ class Workload:
     seq_len: int
     d_in: int
     d_out: int
-    xform: str            # "haar1d", "haar2d" or "identity"
+    xform: str            # "haar1d", "haar2d", "wht", "dct" or "identity"
     levels: int
     grid_h: int = 0       # haar2d only; token t = r * grid_w + c
     grid_w: int = 0
@@ -56,6 +56,9 @@ class Workload:
     seed: int = 0
     act_quant: str = "sym"   # "sym" (absmax, signed codes) or "asym" (min-max, unsigned codes + offsets)
     mean_shift: float = 0.0   # constant added to every activation (skews the per-token ranges)
+    skip_first: bool = False  # the first token is left out of the sequence transform
+    bias_mode: str = "after"  # "after" or "transformed"
+    group_size: int = 0       # 64: per-block scales
 
     @property
     def tokens(self) -> int:

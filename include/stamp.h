@@ -87,7 +87,13 @@ typedef enum { STAMP_F32 = 0, STAMP_BF16 = 1 } stamp_dtype_t;
  * un-transformed (Experiments set-up: inputs without sequence structure) and as the baseline the
  * transform's cost is measured against: tokens are quantized as they are, the first k_hi of every
  * sequence at bits_hi, STaMP order = physical row order = token order, nothing is inverted. */
-typedef enum { STAMP_L_IDENTITY = 0, STAMP_L_HAAR1D = 1, STAMP_L_HAAR2D = 2 } stamp_xform_t;
+typedef enum {
+  STAMP_L_IDENTITY = 0,
+  STAMP_L_HAAR1D = 1,
+  STAMP_L_HAAR2D = 2,
+  STAMP_L_WHT = 3, /* orthonormal Walsh-Hadamard transform along the tokens, rows in sequency order (levels = 0) */
+  STAMP_L_DCT = 4  /* orthonormal DCT-II along the tokens (levels = 0), evaluated in fp64 and rounded to fp32 */
+} stamp_xform_t;
 /* Activation quantizer (Background, Eq. 1), per transformed token i with b bits:
  *   STAMP_ACT_SYMMETRIC   a = max_j |t_ij|, scale = a / (2^(b-1) - 1), code = rne(t * (1 / scale)) in
  *                         [-(2^(b-1) - 1), 2^(b-1) - 1]; de-quantized value code * scale.
@@ -117,9 +123,30 @@ typedef struct {
   int32_t x_dtype, y_dtype, w_dtype; /* stamp_dtype_t; w_dtype must be STAMP_F32 */
   int32_t w_is_out_by_in;   /* 0: W[d_in, d_out];  1: W[d_out, d_in] (the algorithm's X W^T) */
   int32_t act_quant;        /* stamp_act_quant_t: which form of Eq. 1 quantizes the activation */
+  int32_t skip_first;       /* HAAR1D only: 1 = the first token of every sequence is left out of L (it is STaMP slot 0 as
+                               it is; the transform runs over the other seq_len - 1 tokens), the paper's language-model
+                               setting (appendix "Experimental details", LLMs) */
+  int32_t bias_mode;        /* 0: Y = L^-1(..) + 1 bias^T (the algorithm's last step); 1: the transformed bias
+                               (L 1) bias^T is added before the inverse (third form of the commutation identity) */
+  int32_t group_size;       /* 0: one scale per token / per output channel; 64: per-block scales, one per 64 consecutive
+                               input channels, for activations (per token) and weights (per output channel): the
+                               W4A4 setting of the paper's image-model table */
 } stamp_plan_desc_t;
 
-/* Supported by this library (anything else valid returns STAMP_ERR_UNSUPPORTED):
+/* Two implementations serve a plan.
+ * FAST path (the benchmark configurations): HAAR1D on a power-of-two seq_len without skip_first, HAAR2D, IDENTITY, all
+ * with group_size 0 and bias_mode 0; limits below.
+ * GENERAL path: everything else that is valid: HAAR1D of any seq_len (an odd number of approximations at a level: the
+ * last one is carried to the next level unchanged; every level is the orthonormal butterfly (x0 +- x1) * fl(1/sqrt 2))
+ * with 0 <= levels <= the depth that leaves one approximation, skip_first, WHT (seq_len a power of two), DCT, bias_mode 1,
+ * group_size 64.  The transform runs as one kernel per level over fp32 copies of the activation in the workspace, the
+ * quantizer and the GEMM treat the transformed tokens as rows in STaMP order (physical row = STaMP slot), the inverse
+ * again runs level by level.  Limits of the general path: k_hi <= 256 unless group_size = 64; group_size = 64 needs
+ * d_in a multiple of 64 and the symmetric quantizer; d_in a multiple of 32; bits 8/4/4.  With group_size = 64 the
+ * buffers of stamp_quantize_act / stamp_linear_forward_q are: q_hi [batch, seq_len, d_in] int8 codes of ALL tokens in
+ * STaMP order (stamp_plan_hi_rows returns seq_len), q_lo unused (may be NULL), scales [batch, seq_len, d_in / 64].
+ *
+ * Supported by the fast path (anything else valid returns STAMP_ERR_UNSUPPORTED unless the general path takes it):
  *   xform IDENTITY with levels 0, any seq_len and 0 <= k_hi <= 256; or
  *   xform HAAR1D or HAAR2D (square grid) of any depth J, with n_top = max(k_hi, approximations left by J
  *   levels) <= 256 and seq_len/n_top in {8,16,32,64,128} (1-D) or {16,64} (2-D: 4x4 or 8x8 token blocks);
@@ -187,8 +214,10 @@ stamp_status_t stamp_linear_forward_q(const stamp_plan_t* plan, const int8_t* q_
                                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* Step 4 alone: Y = L^-1 Yt for Yt_dev [batch, seq_len, n_cols] fp32 in STaMP order; adds the
- * plan's bias when n_cols == d_out and a bias was given; Y_dev [batch, seq_len, n_cols] y_dtype.
- * STAMP_ERR_UNSUPPORTED for a plan without transform. */
+ * plan's bias (after the inverse, whatever bias_mode says) when n_cols == d_out and a bias was given;
+ * Y_dev [batch, seq_len, n_cols] y_dtype.  Workspace: batch * (top rows, at most 256) * n_cols * 4 bytes on the
+ * fast path; on the general path two buffers of batch * seq_len * n_cols * 4 bytes, each rounded up to 256.
+ * Yt_dev is only read.  STAMP_ERR_UNSUPPORTED for a fast-path plan without transform. */
 stamp_status_t stamp_inverse(const stamp_plan_t* plan, const float* Yt_dev, int32_t n_cols,
                              void* Y_dev, void* workspace_dev, size_t workspace_bytes,
                              void* hip_stream);
@@ -201,8 +230,8 @@ stamp_status_t stamp_inverse(const stamp_plan_t* plan, const float* Yt_dev, int3
 stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* plan, const int8_t* q_hi_dev,
                                     const uint8_t* q_lo_dev, int32_t* acc_dev, void* hip_stream);
 
-/* The plan's weight codes [d_in, d_out] int8 (values -7..7) and scales [d_out], copied to host.
- * Synchronizes the device. */
+/* The plan's weight codes [d_in, d_out] int8 (values -7..7) and scales [d_out] (group_size = 64: [d_in / 64][d_out]),
+ * copied to host.  Synchronizes the device. */
 stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* plan, int8_t* qW_host, float* sw_host);
 
 /* Launches ONE stage of stamp_linear_forward on its own, so that a benchmark can time it between

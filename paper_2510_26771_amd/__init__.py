@@ -16,5 +16,7 @@ from .binding import (  # noqa: F401
     STAMP_L_IDENTITY,
     STAMP_L_HAAR1D,
     STAMP_L_HAAR2D,
+    STAMP_L_WHT,
+    STAMP_L_DCT,
 )
 from .marshal import plan_desc_for, to_device_x, XFORM_CODE  # noqa: F401

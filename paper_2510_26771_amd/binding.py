@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libstamp_hip.so"
 
 STAMP_F32, STAMP_BF16 = 0, 1
-STAMP_L_IDENTITY, STAMP_L_HAAR1D, STAMP_L_HAAR2D = 0, 1, 2
+STAMP_L_IDENTITY, STAMP_L_HAAR1D, STAMP_L_HAAR2D, STAMP_L_WHT, STAMP_L_DCT = 0, 1, 2, 3, 4
 STAMP_STATIC_SCRATCH_BYTES = 64 << 20  # include/stamp.h
 STATUS_NAMES = {0: "STAMP_OK", 1: "STAMP_ERR_NULL", 2: "STAMP_ERR_SHAPE", 3: "STAMP_ERR_UNSUPPORTED",
                 4: "STAMP_ERR_WORKSPACE", 5: "STAMP_ERR_ALLOC", 6: "STAMP_ERR_DEVICE"}
@@ -36,7 +36,7 @@ class StampError(RuntimeError):
 class _Desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "seq_len", "d_in", "d_out", "xform", "levels", "grid_h", "grid_w", "k_hi", "bits_hi", "bits_lo",
-        "bits_w", "x_dtype", "y_dtype", "w_dtype", "w_is_out_by_in", "act_quant")]
+        "bits_w", "x_dtype", "y_dtype", "w_dtype", "w_is_out_by_in", "act_quant", "skip_first", "bias_mode", "group_size")]
 
 
 @dataclass
@@ -58,6 +58,9 @@ class PlanDesc:
     w_dtype: int = STAMP_F32
     w_is_out_by_in: int = 0
     act_quant: int = 0  # 0 symmetric absmax, 1 asymmetric min-max
+    skip_first: int = 0  # 1: the first token is left out of the transform (HAAR1D)
+    bias_mode: int = 0   # 1: transformed bias (L 1) bias^T added before the inverse
+    group_size: int = 0  # 64: per-block scales
 
     def to_c(self) -> _Desc:
         return _Desc(**{n: int(getattr(self, n)) for n, _ in _Desc._fields_})
@@ -228,7 +231,9 @@ class StampPlan:
     def debug_weight_codes(self):
         import numpy as np
         qw = np.empty((self.desc.d_in, self.desc.d_out), dtype=np.int8)
-        sw = np.empty(self.desc.d_out, dtype=np.float32)
+        # per-block scales: one per block of input channels and output column
+        sw = np.empty((self.desc.d_in // self.desc.group_size, self.desc.d_out) if self.desc.group_size
+                      else self.desc.d_out, dtype=np.float32)
         _check(self.lib.stamp_debug_weight_codes(self._h, qw.ctypes.data, sw.ctypes.data), "stamp_debug_weight_codes")
         return qw, sw
 
@@ -238,6 +243,10 @@ class StampPlan:
         d = self.desc
         # at least one row, so that the pointer is valid when a plan keeps no 8-bit token at all
         q_hi = torch.empty((d.batch, max(self.hi_rows(), 1), d.d_in), dtype=torch.int8, device=device)
+        if d.group_size:
+            # per-block scales: q_hi holds every token's codes, q_lo is not used
+            return (q_hi, torch.zeros(16, dtype=torch.uint8, device=device),
+                    torch.zeros((d.batch, d.seq_len, d.d_in // d.group_size), dtype=torch.float32, device=device))
         mp = -(-(d.batch * d.seq_len) // 256) * 256
         kp = -(-d.d_in // 128) * 128
         q_lo = torch.zeros(mp * kp // 2, dtype=torch.uint8, device=device)  # tiled, see include/stamp.h

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libstamp_hip.so")
 
-SOURCES = ["stamp_api.hip", "stamp_actquant.hip", "stamp_weight.hip", "stamp_gemm.hip", "stamp_gemm6.hip", "stamp_inverse.hip", "stamp_probe.hip"]
+SOURCES = ["stamp_api.hip", "stamp_actquant.hip", "stamp_weight.hip", "stamp_gemm.hip", "stamp_gemm6.hip", "stamp_inverse.hip", "stamp_probe.hip", "stamp_general.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

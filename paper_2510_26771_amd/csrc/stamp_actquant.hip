@@ -969,6 +969,17 @@ hipError_t launch_bottom1d(const stamp_plan* p, const void* X, uint8_t* q_lo, fl
 
 }  // namespace
 
+// general path: per-token quantization of the transformed tokens T [B, s, d] fp32 (rows = STaMP slots)
+hipError_t stamp_launch_quant_rows_f32(const stamp_plan* p, const float* T, int8_t* q_hi, uint8_t* q_lo, float* scales,
+                                       hipStream_t st) {
+  const StampGeom& g = p->geom;
+  const dim3 grid_rows(g.s, g.B);
+  const size_t zoff = (size_t)g.B * g.s;
+  if (g.asym) hipLaunchKernelGGL((k_quant_rows<false, true>), grid_rows, dim3(256), 0, st, T, q_hi, q_lo, scales, g.s, g.d, g.k, p->Kpad, zoff);
+  else hipLaunchKernelGGL((k_quant_rows<false, false>), grid_rows, dim3(256), 0, st, T, q_hi, q_lo, scales, g.s, g.d, g.k, p->Kpad, zoff);
+  return hipGetLastError();
+}
+
 bool stamp_top_in_bottom(const stamp_plan* p) {
   return !p->geom.ident && p->geom.L == 0 && stamp_actquant_nsplit(p) == 1;
 }

@@ -35,9 +35,23 @@ inline bool is_pow2(int64_t n) { return n >= 1 && (n & (n - 1)) == 0; }
 inline int ilog2(int64_t n) { int l = 0; while ((int64_t(1) << (l + 1)) <= n) ++l; return l; }
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
-stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok) {
+int max_ragged_levels(int n) {
+  int l = 0;
+  while (n > 1) {
+    n = (n + 1) / 2;
+    ++l;
+  }
+  return l;
+}
+
+stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok, StampGen* gen) {
+  memset(gen, 0, sizeof(*gen));
   if (d->batch < 1 || d->seq_len < 1 || d->d_in < 1 || d->d_out < 1) return STAMP_ERR_SHAPE;
-  if (d->xform != STAMP_L_IDENTITY && d->xform != STAMP_L_HAAR1D && d->xform != STAMP_L_HAAR2D) return STAMP_ERR_SHAPE;
+  if (d->xform < STAMP_L_IDENTITY || d->xform > STAMP_L_DCT) return STAMP_ERR_SHAPE;
+  if (d->skip_first != 0 && d->skip_first != 1) return STAMP_ERR_SHAPE;
+  if (d->skip_first && (d->xform != STAMP_L_HAAR1D || d->seq_len < 2)) return STAMP_ERR_SHAPE;  // defined for the 1-D Haar transform
+  if (d->bias_mode != 0 && d->bias_mode != 1) return STAMP_ERR_SHAPE;
+  if (d->group_size < 0) return STAMP_ERR_SHAPE;
   if (d->k_hi < 0 || d->k_hi > d->seq_len) return STAMP_ERR_SHAPE;
   if (d->bits_hi < 2 || d->bits_hi > 8 || d->bits_lo < 2 || d->bits_lo > 8 || d->bits_w < 2 || d->bits_w > 8)
     return STAMP_ERR_SHAPE;
@@ -49,8 +63,14 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   if ((int64_t)d->batch * d->seq_len > (int64_t)1 << 30) return STAMP_ERR_SHAPE;
 
   int J = 0, side = 0;
-  if (d->xform == STAMP_L_HAAR1D) {
-    if (!is_pow2(d->seq_len)) return STAMP_ERR_SHAPE;
+  const bool ragged = d->xform == STAMP_L_HAAR1D && (d->skip_first || !is_pow2(d->seq_len));
+  if (ragged) {
+    if (d->levels < 0 || d->levels > max_ragged_levels(d->seq_len - d->skip_first)) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_WHT) {
+    if (!is_pow2(d->seq_len) || d->levels != 0) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_DCT) {
+    if (d->levels != 0) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_HAAR1D) {
     J = ilog2(d->seq_len);
     if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
   } else if (d->xform == STAMP_L_HAAR2D) {
@@ -73,6 +93,33 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok)
   g->x_bf16 = d->x_dtype == STAMP_BF16;
   g->y_bf16 = d->y_dtype == STAMP_BF16;
   g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
+  // ---- general path: transforms without the fast path's block structure, transformed bias, per-block scales ----
+  if (ragged || d->xform == STAMP_L_WHT || d->xform == STAMP_L_DCT || d->bias_mode == 1 || d->group_size != 0) {
+    if (d->group_size != 0 && d->group_size != 64) return STAMP_ERR_UNSUPPORTED;
+    if (d->group_size == 64 && (d->d_in % 64 != 0 || g->asym)) return STAMP_ERR_UNSUPPORTED;
+    if (d->group_size == 0 && d->k_hi > 256) return STAMP_ERR_UNSUPPORTED;
+    if (d->seq_len > 65535 || d->batch > 65535 || (int64_t)d->batch * d->k_hi > 65535) return STAMP_ERR_UNSUPPORTED;  // grid dimensions
+    if (d->xform == STAMP_L_DCT && d->seq_len > 16384) return STAMP_ERR_UNSUPPORTED;  // dense s x s matrix in fp64
+    if (d->xform == STAMP_L_HAAR2D && d->grid_h != d->grid_w) return STAMP_ERR_UNSUPPORTED;
+    gen->kind = ragged ? kGenHaarRagged
+                : d->xform == STAMP_L_WHT ? kGenWht
+                : d->xform == STAMP_L_DCT ? kGenDct
+                : d->xform == STAMP_L_HAAR1D ? kGenHaarClassic
+                : d->xform == STAMP_L_HAAR2D ? kGenHaar2d : kGenCopy;
+    gen->levels = d->levels;
+    gen->skip = d->skip_first;
+    gen->group = d->group_size;
+    gen->bias_mode = d->bias_mode;
+    gen->gridH = d->grid_h;
+    gen->gridW = d->grid_w;
+    // the quantizer and the GEMM see the transformed tokens as rows: physical row = STaMP slot, no blocks
+    g->J = 0;
+    g->ident = 1;
+    g->R = 1;
+    if (d->group_size == 64) g->k = d->seq_len;  // every token's codes travel as int8 (khi of them are 8-bit rows)
+    *fused_ok = 0;
+    return STAMP_OK;
+  }
   if (d->xform == STAMP_L_IDENTITY) {
     // tokens quantized as they are: any number of 8-bit tokens (none included), no blocks, no inverse
     if (d->k_hi > 256) return STAMP_ERR_UNSUPPORTED;
@@ -133,6 +180,23 @@ void layout_workspace(stamp_plan* p) {
   const StampGeom& g = p->geom;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  if (p->gen.kind != kGenNone) {
+    // general path: three fp32 copies of the activation and of the transformed output for the level kernels, and
+    // the quantized activation (per-token scales: the buffers of the fast path; per-block scales: int8 codes)
+    const bool grouped = p->gen.group != 0;
+    p->ws_abot = p->ws_rowmax = p->ws_gpart = p->ws_P = p->ws_ytlo = 0;
+    p->ws_qhi = take(grouped ? 0 : (size_t)g.B * g.k * g.d);
+    p->ws_qlo = take(grouped ? 0 : (size_t)p->Mpad * (p->Kpad / 2));
+    p->ws_scales = take(grouped ? 0 : (size_t)2 * g.B * g.s * sizeof(float));
+    p->ws_ythi = take(grouped ? 0 : (size_t)p->hi_ksplit * g.B * g.k * g.N * sizeof(float));
+    p->ws_a6 = take(grouped ? 0 : stamp_a6_bytes(p));
+    for (size_t& o : p->ws_T) o = take((size_t)g.B * g.s * g.d * sizeof(float));
+    for (size_t& o : p->ws_Yt) o = take((size_t)g.B * g.s * g.N * sizeof(float));
+    p->ws_codes8 = take(grouped ? (size_t)g.B * g.s * g.d : 0);
+    p->ws_scalesg = take(grouped ? (size_t)g.B * g.s * (g.d / 64) * sizeof(float) : 0);
+    p->ws_total = off;
+    return;
+  }
   p->ws_abot = take((size_t)g.B * g.k * g.d * sizeof(float));
   p->ws_rowmax = take((size_t)2 * g.B * g.k * ((g.d + 31) / 32) * sizeof(uint32_t));  // partial row maxima (asymmetric: of both signs) per 32-channel slice
   {
@@ -161,6 +225,32 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
                          void* ws, hipStream_t st) {
   float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
   float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
+  if (p->gen.kind != kGenNone) {
+    // general path: dequantized rows in STaMP order -> (transformed bias) -> inverse level by level -> Y
+    float* const yt[3] = {reinterpret_cast<float*>(at(ws, p->ws_Yt[0])), reinterpret_cast<float*>(at(ws, p->ws_Yt[1])),
+                          reinterpret_cast<float*>(at(ws, p->ws_Yt[2]))};
+    if (p->gen.group) {
+      // q_hi carries every token's int8 codes, scales one per token and 64-channel group
+      if (stamp_launch_gemm_grouped(p, q_hi, scales, yt[0], st) != hipSuccess) return STAMP_ERR_DEVICE;
+    } else {
+      if (p->geom.k > 0) {
+        if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
+        if (stamp_launch_merge_hi(p, ythi, p->hi_ksplit, yt[0], st) != hipSuccess) return STAMP_ERR_DEVICE;
+      }
+      if (p->geom.k < p->geom.s) {
+        if (p->engine == STAMP_GEMM_FP6) {
+          uint8_t* a6g = at(ws, p->ws_a6);
+          if (stamp_launch_repack6(p, q_lo, a6g, st) != hipSuccess) return STAMP_ERR_DEVICE;
+          if (stamp_launch_gemm_lo6(p, a6g, scales, 1, yt[0], nullptr, st) != hipSuccess) return STAMP_ERR_DEVICE;
+        } else {
+          if (stamp_launch_gemm_lo(p, q_lo, scales, 1, yt[0], nullptr, st) != hipSuccess) return STAMP_ERR_DEVICE;
+        }
+      }
+    }
+    const bool tbias = p->gen.bias_mode == 1 && p->bias_dev != nullptr;
+    if (tbias && stamp_launch_add_ell_bias(p, yt[0], st) != hipSuccess) return STAMP_ERR_DEVICE;
+    return stamp_gen_inverse(p, yt, p->geom.N, tbias ? nullptr : p->bias_dev, Y, st) == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+  }
   if (p->geom.ident) {
     // no transform: the 8-bit rows' GEMM (partial rows) + their output pass, then the 4-bit rows straight to Y
     if (p->geom.k > 0) {
@@ -197,6 +287,17 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
   return STAMP_OK;
 }
 
+// general path, steps 1-2: forward transform level by level, then the row quantizer
+stamp_status_t gen_quantize(const stamp_plan* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales, void* ws, hipStream_t st) {
+  float* const tb[3] = {reinterpret_cast<float*>(at(ws, p->ws_T[0])), reinterpret_cast<float*>(at(ws, p->ws_T[1])),
+                        reinterpret_cast<float*>(at(ws, p->ws_T[2]))};
+  float* T = nullptr;
+  if (stamp_gen_forward(p, X, tb, &T, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  const hipError_t e = p->gen.group ? stamp_launch_quant_rows_grouped(p, T, q_hi, scales, st)
+                                    : stamp_launch_quant_rows_f32(p, T, q_hi, q_lo, scales, st);
+  return e == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -220,7 +321,8 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   *out = nullptr;
   StampGeom g;
   int fused_ok = 0;
-  stamp_status_t vs = validate(desc, &g, &fused_ok);
+  StampGen gen;
+  stamp_status_t vs = validate(desc, &g, &fused_ok, &gen);
   if (vs != STAMP_OK) return vs;
   if (W_dev == nullptr) return STAMP_ERR_NULL;
 
@@ -229,13 +331,14 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   memset(p, 0, sizeof(*p));
   p->desc = *desc;
   p->geom = g;
+  p->gen = gen;
   p->fused_ok = fused_ok && (g.ident || g.N % 2 == 0);  // the fused inverse stores pairs of columns: even d_out
   p->unfused = 0;
   p->engine = STAMP_GEMM_FP6;
   p->Kpad = ((g.d + 127) / 128) * 128;
   p->Npad = ((g.N + 255) / 256) * 256;
   p->Mpad = ((g.B * g.s + 255) / 256) * 256;
-  p->hi_ksplit = stamp_hi_ksplit(p);
+  p->hi_ksplit = gen.group ? 1 : stamp_hi_ksplit(p);
   layout_workspace(p);
 
   // physical row of every STaMP slot
@@ -272,6 +375,7 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   }
   if (dev_ok) dev_ok = stamp_launch_weight_quant(p, static_cast<const float*>(W_dev), st, colmax) == hipSuccess;
   if (dev_ok) dev_ok = stamp_launch_weight_quant6(p, static_cast<const float*>(W_dev), colmax, st) == hipSuccess;
+  if (dev_ok && gen.kind != kGenNone) dev_ok = stamp_gen_plan_tables(p, static_cast<const float*>(W_dev), st) == hipSuccess;
   // the scratch column maxima must outlive the kernels just enqueued: hipFree waits for the device
   (void)hipFree(colmax);
   if (!dev_ok) {
@@ -289,6 +393,7 @@ stamp_status_t stamp_plan_destroy(stamp_plan_t* p) {
   if (p->sw_dev) (void)hipFree(p->sw_dev);
   if (p->colsum_dev) (void)hipFree(p->colsum_dev);
   if (p->bias_dev) (void)hipFree(p->bias_dev);
+  stamp_gen_plan_free(p);
   free(p->row_of_coeff);
   delete p;
   return STAMP_OK;
@@ -300,6 +405,7 @@ int32_t stamp_plan_hi_rows(const stamp_plan_t* p) { return p ? p->geom.k : 0; }
 
 stamp_status_t stamp_plan_set_unfused(stamp_plan_t* p, int32_t unfused) {
   if (p == nullptr) return STAMP_ERR_NULL;
+  if (p->gen.kind != kGenNone) return STAMP_OK;  // the general path has one implementation
   p->unfused = unfused ? 1 : 0;
   layout_workspace(p);
   return STAMP_OK;
@@ -320,9 +426,14 @@ stamp_status_t stamp_plan_row_of_coeff(const stamp_plan_t* p, int32_t* host_out)
 
 stamp_status_t stamp_quantize_act(const stamp_plan_t* p, const void* X, int8_t* q_hi, uint8_t* q_lo, float* scales,
                                   void* ws, size_t ws_bytes, void* hip_stream) {
-  if (p == nullptr || X == nullptr || q_hi == nullptr || q_lo == nullptr || scales == nullptr) return STAMP_ERR_NULL;
-  if (!ws_ok(p, ws, ws_bytes, p->ws_qhi)) return STAMP_ERR_WORKSPACE;  // needs the block sums and row maxima only
+  if (p == nullptr || X == nullptr || q_hi == nullptr || scales == nullptr) return STAMP_ERR_NULL;
+  if (q_lo == nullptr && !p->gen.group) return STAMP_ERR_NULL;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  if (p->gen.kind != kGenNone) {
+    if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
+    return gen_quantize(p, X, q_hi, q_lo, scales, ws, st);
+  }
+  if (!ws_ok(p, ws, ws_bytes, p->ws_qhi)) return STAMP_ERR_WORKSPACE;  // needs the block sums and row maxima only
   hipError_t e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, reinterpret_cast<float*>(at(ws, p->ws_abot)),
                                        reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)),
                                        reinterpret_cast<uint32_t*>(at(ws, p->ws_gpart)), st);
@@ -331,7 +442,8 @@ stamp_status_t stamp_quantize_act(const stamp_plan_t* p, const void* X, int8_t* 
 
 stamp_status_t stamp_linear_forward_q(const stamp_plan_t* p, const int8_t* q_hi, const uint8_t* q_lo,
                                       const float* scales, void* Y, void* ws, size_t ws_bytes, void* hip_stream) {
-  if (p == nullptr || q_hi == nullptr || q_lo == nullptr || scales == nullptr || Y == nullptr) return STAMP_ERR_NULL;
+  if (p == nullptr || q_hi == nullptr || scales == nullptr || Y == nullptr) return STAMP_ERR_NULL;
+  if (q_lo == nullptr && !p->gen.group) return STAMP_ERR_NULL;
   if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
   return forward_q(p, q_hi, q_lo, scales, Y, ws, reinterpret_cast<hipStream_t>(hip_stream));
 }
@@ -344,6 +456,14 @@ stamp_status_t stamp_linear_forward(const stamp_plan_t* p, const void* X, void* 
   int8_t* q_hi = reinterpret_cast<int8_t*>(at(ws, p->ws_qhi));
   uint8_t* q_lo = at(ws, p->ws_qlo);
   float* scales = reinterpret_cast<float*>(at(ws, p->ws_scales));
+  if (p->gen.kind != kGenNone) {
+    if (p->gen.group) {
+      q_hi = reinterpret_cast<int8_t*>(at(ws, p->ws_codes8));
+      scales = reinterpret_cast<float*>(at(ws, p->ws_scalesg));
+    }
+    const stamp_status_t qs = gen_quantize(p, X, q_hi, q_lo, scales, ws, st);
+    return qs != STAMP_OK ? qs : forward_q(p, q_hi, q_lo, scales, Y, ws, st);
+  }
   hipError_t e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, reinterpret_cast<float*>(at(ws, p->ws_abot)),
                                        reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)),
                                        reinterpret_cast<uint32_t*>(at(ws, p->ws_gpart)), st);
@@ -364,6 +484,15 @@ stamp_status_t stamp_inverse(const stamp_plan_t* p, const float* Yt, int32_t n_c
                              void* hip_stream) {
   if (p == nullptr || Yt == nullptr || Y == nullptr) return STAMP_ERR_NULL;
   if (n_cols < 1) return STAMP_ERR_SHAPE;
+  if (p->gen.kind != kGenNone) {
+    // two [batch, seq_len, n_cols] fp32 buffers for the levels; Yt itself is only read
+    const size_t one = align256((size_t)p->geom.B * p->geom.s * (size_t)n_cols * sizeof(float));
+    if (!ws_ok(p, ws, ws_bytes, 2 * one)) return STAMP_ERR_WORKSPACE;
+    hipStream_t stg = reinterpret_cast<hipStream_t>(hip_stream);
+    float* const yt[3] = {const_cast<float*>(Yt), reinterpret_cast<float*>(ws), reinterpret_cast<float*>(at(ws, one))};
+    const float* gbias = (n_cols == p->geom.N) ? p->bias_dev : nullptr;
+    return stamp_gen_inverse(p, yt, n_cols, gbias, Y, stg) == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
+  }
   if (p->geom.ident) return STAMP_ERR_UNSUPPORTED;  // nothing to invert
   const size_t need = (size_t)p->geom.B * p->geom.k * (size_t)n_cols * sizeof(float);
   if (!ws_ok(p, ws, ws_bytes, need)) return STAMP_ERR_WORKSPACE;
@@ -378,6 +507,7 @@ stamp_status_t stamp_inverse(const stamp_plan_t* p, const float* Yt, int32_t n_c
 stamp_status_t stamp_debug_gemm_acc(const stamp_plan_t* p, const int8_t* q_hi, const uint8_t* q_lo, int32_t* acc,
                                     void* hip_stream) {
   if (p == nullptr || q_hi == nullptr || q_lo == nullptr || acc == nullptr) return STAMP_ERR_NULL;
+  if (p->gen.group) return STAMP_ERR_UNSUPPORTED;  // per-block scales: there is no single integer sum per output
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   // accumulator mode never reads the activation scales
   if (p->geom.k > 0 && stamp_launch_gemm_hi(p, q_hi, nullptr, 0, acc, st) != hipSuccess) return STAMP_ERR_DEVICE;
@@ -399,6 +529,7 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
   if (p == nullptr || X == nullptr || q_hi == nullptr || q_lo == nullptr || scales == nullptr || Y == nullptr)
     return STAMP_ERR_NULL;
   if (stage < 0 || stage > 6) return STAMP_ERR_SHAPE;
+  if (p->gen.kind != kGenNone) return STAMP_ERR_UNSUPPORTED;  // the general path has no separately launchable stages
   if (stage == 6 && p->engine != STAMP_GEMM_FP6) return STAMP_ERR_UNSUPPORTED;
   if (stage == 5 && p->fused_ok && !p->unfused) return STAMP_ERR_UNSUPPORTED;
   if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
@@ -452,6 +583,24 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
 stamp_status_t stamp_debug_weight_codes(const stamp_plan_t* p, int8_t* qW_host, float* sw_host) {
   if (p == nullptr || qW_host == nullptr || sw_host == nullptr) return STAMP_ERR_NULL;
   const int d = p->geom.d, N = p->geom.N;
+  if (p->gen.group) {
+    // per-block scales: codes [d_in, d_out], scales [d_in / 64][d_out]
+    const int Npad = ((N + 127) / 128) * 128, G = d / 64;
+    int8_t* tq = static_cast<int8_t*>(malloc((size_t)Npad * d));
+    float* ts = static_cast<float*>(malloc(sizeof(float) * (size_t)G * Npad));
+    bool ok = tq != nullptr && ts != nullptr && hipDeviceSynchronize() == hipSuccess &&
+              hipMemcpy(tq, p->qWg_dev, (size_t)Npad * d, hipMemcpyDeviceToHost) == hipSuccess &&
+              hipMemcpy(ts, p->swg_dev, sizeof(float) * (size_t)G * Npad, hipMemcpyDeviceToHost) == hipSuccess;
+    if (ok) {
+      for (int n = 0; n < N; ++n)
+        for (int c = 0; c < d; ++c) qW_host[(size_t)c * N + n] = tq[(size_t)n * d + c];
+      for (int gi = 0; gi < G; ++gi)
+        for (int n = 0; n < N; ++n) sw_host[(size_t)gi * N + n] = ts[(size_t)gi * Npad + n];
+    }
+    free(tq);
+    free(ts);
+    return ok ? STAMP_OK : STAMP_ERR_DEVICE;
+  }
   int8_t* tmp = static_cast<int8_t*>(malloc((size_t)p->Npad * p->Kpad));
   if (tmp == nullptr) return STAMP_ERR_ALLOC;
   if (hipDeviceSynchronize() != hipSuccess ||

@@ -33,6 +33,18 @@ struct StampGeom {
   int32_t y_bf16;    // output dtype is bf16
   int32_t asym;      // asymmetric activation codes: stored code - 2^(b-1), offsets z next to the scales
   int32_t ident;     // no sequence transform: tokens 0..k-1 are the 8-bit rows, physical row = token (J = r = 0, R = 1)
+                     // (also set for plans of the general path, whose quantizer and GEMM see transformed tokens as rows)
+};
+
+// General path: the transform runs level by level over fp32 buffers in the workspace (stamp_general.hip).
+enum StampGenKind { kGenNone = 0, kGenCopy, kGenHaarRagged, kGenHaarClassic, kGenHaar2d, kGenWht, kGenDct };
+struct StampGen {
+  int32_t kind;        // StampGenKind
+  int32_t levels;
+  int32_t skip;        // first token left out (ragged Haar)
+  int32_t group;       // 0 or 64
+  int32_t bias_mode;   // 1: transformed bias
+  int32_t gridH, gridW;
 };
 
 // Position inside a block ("e", 0 = the block sum, e >= 1 the in-block detail rows in STaMP
@@ -135,6 +147,14 @@ struct stamp_plan {
   int32_t hi_ksplit;        // parts the depth of the 8-bit rows' GEMM is split into (partial rows in the workspace)
   int32_t unfused;          // 1: separate inverse kernel
   int32_t fused_ok;         // shape allows the fused epilogue
+  StampGen gen;             // general path (kind != kGenNone)
+  float* norm_dev;          // general path: [s] factor of every STaMP slot applied after the butterflies (or nullptr)
+  int32_t* perm_dev;        // general path, WHT: [s] source row of every STaMP slot
+  float* ell_dev;           // general path, transformed bias: [s] l = L 1
+  double* dct_dev;          // general path, DCT: [s][s] orthonormal DCT-II matrix
+  int8_t* qWg_dev;          // per-block scales: weight codes [Npad128][d_in] int8
+  float* swg_dev;           // per-block scales: [d_in / 64][Npad128]
+  size_t ws_T[3], ws_Yt[3], ws_codes8, ws_scalesg;  // general path workspace (byte offsets)
   // workspace layout (byte offsets, 256-aligned)
   size_t ws_abot, ws_rowmax, ws_gpart, ws_qhi, ws_qlo, ws_scales, ws_ythi, ws_P, ws_a6, ws_ytlo, ws_total;
 };
@@ -194,5 +214,18 @@ hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* Yt_hi, int
                                     int ncols, float* P, int ldP, hipStream_t st, int nparts = 1);
 hipError_t stamp_launch_inverse_bottom(const stamp_plan* p, const float* Yt_lo, int src_is_stamp_order,
                                        const float* P, int ldP, int ncols, const float* bias, void* Y, hipStream_t st);
+
+// ---- general path (stamp_general.hip) ----
+hipError_t stamp_gen_plan_tables(stamp_plan* p, const float* W, hipStream_t st);  // device tables and grouped weights
+void stamp_gen_plan_free(stamp_plan* p);
+// X -> transformed tokens T [B, s, d] fp32 in STaMP order; returns the buffer that holds T (one of the three)
+hipError_t stamp_gen_forward(const stamp_plan* p, const void* X, float* const (&buf)[3], float** T_out, hipStream_t st);
+// Yt [B, s, ncols] fp32 in STaMP order (buf[0], only read) -> Y; buf[1], buf[2]: the levels' work buffers
+hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int ncols, const float* bias, void* Y, hipStream_t st);
+hipError_t stamp_launch_quant_rows_f32(const stamp_plan* p, const float* T, int8_t* q_hi, uint8_t* q_lo, float* scales, hipStream_t st);
+hipError_t stamp_launch_quant_rows_grouped(const stamp_plan* p, const float* T, int8_t* codes, float* scales, hipStream_t st);
+hipError_t stamp_launch_gemm_grouped(const stamp_plan* p, const int8_t* codes, const float* scales, float* Yt, hipStream_t st);
+hipError_t stamp_launch_merge_hi(const stamp_plan* p, const float* ythi, int nparts, float* Yt, hipStream_t st);
+hipError_t stamp_launch_add_ell_bias(const stamp_plan* p, float* Yt, hipStream_t st);
 
 #endif  // STAMP_INTERNAL_H_

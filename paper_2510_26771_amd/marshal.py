@@ -5,7 +5,7 @@ from __future__ import annotations
 
 from .binding import PlanDesc, STAMP_BF16, STAMP_F32
 
-XFORM_CODE = {"identity": 0, "haar1d": 1, "haar2d": 2}
+XFORM_CODE = {"identity": 0, "haar1d": 1, "haar2d": 2, "wht": 3, "dct": 4}
 
 
 def plan_desc_for(w, y_dtype: str = "f32") -> PlanDesc:
@@ -14,7 +14,10 @@ def plan_desc_for(w, y_dtype: str = "f32") -> PlanDesc:
                     bits_lo=w.bits_lo, bits_w=w.bits_w,
                     x_dtype=STAMP_BF16 if w.x_dtype == "bf16" else STAMP_F32,
                     y_dtype=STAMP_BF16 if y_dtype == "bf16" else STAMP_F32,
-                    act_quant=1 if w.act_quant == "asym" else 0)
+                    act_quant=1 if w.act_quant == "asym" else 0,
+                    skip_first=int(getattr(w, "skip_first", False)),
+                    bias_mode=1 if getattr(w, "bias_mode", "after") == "transformed" else 0,
+                    group_size=int(getattr(w, "group_size", 0)))
 
 
 def to_device_x(inp: dict, w):

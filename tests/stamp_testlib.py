@@ -29,6 +29,13 @@ def unpack_int4(q_lo: np.ndarray) -> np.ndarray:
     return out
 
 
+def general_path(d) -> bool:
+    """Plans the library serves with its general path (transform level by level, rows in STaMP order)."""
+    pow2 = d.seq_len & (d.seq_len - 1) == 0
+    return (d.xform in (XFORM_CODE["wht"], XFORM_CODE["dct"]) or bool(d.skip_first) or bool(d.bias_mode) or bool(d.group_size)
+            or (d.xform == XFORM_CODE["haar1d"] and not pow2))
+
+
 def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):
     """Device buffers (physical row order) -> numpy codes [B, s, d], scales [B, s] and (asymmetric plans) offsets
     [B, s] in STaMP order.  Asymmetric plans store code - 2^(b-1); the unsigned code is returned."""
@@ -37,9 +44,9 @@ def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):
     assert sorted(row.tolist()) == list(range(d.seq_len)), "row_of_coeff is not a permutation"
     k = plan.hi_rows()  # rows kept in q_hi: the 8-bit tokens and any further approximation coefficients
     assert k >= d.k_hi
-    if d.xform == XFORM_CODE["identity"]:
+    if d.xform == XFORM_CODE["identity"] or general_path(d):
         assert k == d.k_hi
-        assert np.array_equal(row, np.arange(d.seq_len))  # no transform: STaMP order is token order
+        assert np.array_equal(row, np.arange(d.seq_len))  # rows are kept in STaMP order (no transform: token order)
     else:
         assert np.array_equal(row[:k], np.arange(k) * (d.seq_len // k))
     qh = q_hi.cpu().numpy()[:, :k]
@@ -102,7 +109,7 @@ def compare_codes(gpu_codes, gpu_scales, gpu_zeros, ora: Dict[str, np.ndarray]) 
 def run_oracle(w: Workload, inp: dict, cols: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """Oracle results; with `cols` the GEMM / inverse run on those output columns only."""
     qa = so.quantize_activation(inp["X_f32"], w.xform, w.levels, w.k_hi, w.bits_hi, w.bits_lo, w.grid_h, w.grid_w,
-                                act_quant=w.act_quant)
+                                act_quant=w.act_quant, skip_first=w.skip_first)
     qw, sw = so.quantize_weight(inp["W"], w.bits_w)
     bias = inp["bias"]
     if cols is not None:
@@ -111,7 +118,7 @@ def run_oracle(w: Workload, inp: dict, cols: Optional[np.ndarray] = None) -> Dic
     else:
         qw_c, sw_c, bias_c = qw, sw, bias
     out = so.linear_from_codes(qa["codes"], qa["scales"], qw_c, sw_c, w.xform, w.levels, w.grid_h, w.grid_w, bias_c,
-                               zeros=qa.get("zeros"))
+                               zeros=qa.get("zeros"), skip_first=w.skip_first, bias_mode=w.bias_mode)
     out.update(qa)
     out.update({"qw": qw, "sw": sw})
     return out
@@ -258,5 +265,53 @@ def full_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32", cols: 
             report[f"y_relerr_f32out_{engine}"] = check_output(pick(Y).numpy(), y_ref, False, f"{w.name} f32 out {engine}")
             del Y
         plan32.destroy()
+    log(f"outputs ok: {report}")
+    return report
+
+
+def grouped_case(w: Workload, with_bias: bool = False, y_dtype: str = "f32") -> Dict[str, float]:
+    """Per-block (group_size = 64) scales: weight codes and scales, activation codes and scales bit for bit, the
+    layer's output to the output bar, and quantize_act + linear_forward_q against linear_forward."""
+    import torch
+    import paper_2510_26771_amd as st
+
+    assert w.group_size == 64
+    log(f"grouped case {w.name}: B={w.batch} s={w.seq_len} d={w.d_in} N={w.d_out} {w.xform} J={w.levels} k={w.k_hi} "
+        f"x={w.x_dtype} y={y_dtype} bias={with_bias} seed={w.seed} skip_first={w.skip_first}")
+    inp = make_inputs(w, with_bias=with_bias)
+    ora = so.stamp_linear_forward_grouped(inp["X_f32"], inp["W"], w.xform, w.levels, w.k_hi, 64, w.bits_hi, w.bits_lo,
+                                          w.bits_w, w.grid_h, w.grid_w, inp["bias"], skip_first=w.skip_first)
+    log("oracle done")
+    Xd = to_device_x(inp, w)
+    Wd = torch.from_numpy(inp["W"]).cuda()
+    bd = None if inp["bias"] is None else torch.from_numpy(inp["bias"]).cuda()
+    plan = st.StampPlan(plan_desc_for(w, y_dtype), Wd, bd)
+    qw, swg = plan.debug_weight_codes()
+    assert np.array_equal(qw, ora["qw"]), "weight codes differ"
+    assert np.array_equal(swg.view(np.uint32), ora["swg"].view(np.uint32)), "weight scales differ"
+    assert plan.hi_rows() == w.seq_len
+    assert np.array_equal(plan.row_of_coeff(), np.arange(w.seq_len))
+
+    ws = plan.alloc_workspace()
+    q_hi, q_lo, scales = plan.alloc_act_buffers()
+    plan.quantize_act(Xd, q_hi, q_lo, scales, ws)
+    torch.cuda.synchronize()
+    sc = scales.cpu().numpy()
+    assert np.array_equal(sc.view(np.uint32), ora["scales"].view(np.uint32)), "activation scales differ"
+    codes = q_hi.cpu().numpy()
+    n_mis = int(np.count_nonzero(codes != ora["codes"]))
+    assert n_mis == 0, f"{n_mis} activation codes differ"
+
+    y_bf16 = y_dtype == "bf16"
+    Y = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=torch.int16 if y_bf16 else torch.float32, device="cuda")
+    plan.linear_forward(Xd, Y, ws)
+    torch.cuda.synchronize()
+    report: Dict[str, float] = {}
+    report["y_relerr"] = check_output(y_to_numpy(Y, y_bf16), ora["Y"], y_bf16, w.name, report)
+    Y2 = torch.zeros_like(Y)
+    plan.linear_forward_q(q_hi, q_lo, scales, Y2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2), "linear_forward and quantize_act + linear_forward_q disagree"
+    plan.destroy()
     log(f"outputs ok: {report}")
     return report

@@ -50,7 +50,20 @@ def _good(**kw):
 
 
 @pytest.mark.parametrize("kw,expect", [
-    (dict(seq_len=250), 2),                                   # not a power of two
+    (dict(seq_len=250, levels=9), 2),                         # 250 tokens halve (odd ones carried) 8 times at most
+    (dict(seq_len=256, levels=9, skip_first=1), 2),           # 255 tokens after the first: 8 levels exist, 9 do not
+    (dict(skip_first=2), 2),
+    (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=3, skip_first=1), 2),   # only the 1-D Haar transform skips
+    (dict(xform=st.STAMP_L_WHT, seq_len=250, levels=0), 2),   # Walsh-Hadamard needs a power of two
+    (dict(xform=st.STAMP_L_WHT, levels=3), 2),                # WHT and DCT take no level count
+    (dict(xform=st.STAMP_L_DCT, levels=1), 2),
+    (dict(xform=st.STAMP_L_DCT, levels=0, seq_len=32768), 3), # dense DCT matrix beyond 16384 tokens
+    (dict(bias_mode=2), 2),
+    (dict(group_size=-64), 2),
+    (dict(group_size=32), 3),                                 # blocks of 64 channels only
+    (dict(group_size=64, d_in=96), 3),
+    (dict(group_size=64, act_quant=1), 3),
+    (dict(seq_len=500, levels=3, k_hi=300), 3),               # general path: at most 256 8-bit tokens
     (dict(levels=9), 2),                                      # more levels than log2(seq_len)
     (dict(levels=0), 2),
     (dict(k_hi=257), 2),                                      # k > s
