@@ -16,6 +16,7 @@
 // the GEMM then treat the transformed tokens as rows (physical row = STaMP slot); the inverse runs level by level
 // over [B, s, d_out].  The floating-point order of the FORWARD transform is the oracle's (it decides the codes);
 // the inverse and the de-quantization only have to meet the output tolerance.  Compiled with -ffp-contract=off.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <vector>
@@ -47,115 +48,242 @@ __global__ __launch_bounds__(256) void k_gen_cast(const void* __restrict__ X, fl
   dst[idx] = bf16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(X)[idx] << 16) : reinterpret_cast<const float*>(X)[idx];
 }
 
-// dst rows [dst0, dst0 + rows) = src rows [src0, ...) * norm (norm_tab[dst row] if given), optionally through a row
-// permutation: dst row r takes src row perm[r]
-// (src may be dst: every thread reads and writes one element of its own)
-__global__ __launch_bounds__(256) void k_gen_copy_rows(const float* src, float* dst, int seq, int ld,
-                                                       int src0, int dst0, const float* __restrict__ norm_tab,
-                                                       const int* __restrict__ perm) {
-  GEN_INDEX;
-  const int dr = dst0 + i;
-  const int sr = perm != nullptr ? perm[dr] : src0 + i;
-  float v = src[bo + (size_t)sr * ld + c];
-  if (norm_tab != nullptr) v = __fmul_rn(v, norm_tab[dr]);
-  dst[bo + (size_t)dr * ld + c] = v;
+// One element of the input of a transform pass: X itself (bf16 or fp32) or an fp32 work buffer.
+__device__ __forceinline__ float gen_load(const void* in, int kind, size_t idx) {
+  return kind == 2 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(in)[idx] << 16) : reinterpret_cast<const float*>(in)[idx];
+}
+__device__ __forceinline__ void gen_store_y(void* Y, int y_bf16, size_t idx, float v) {
+  if (y_bf16) reinterpret_cast<uint16_t*>(Y)[idx] = f32_to_bf16_rne(v);
+  else reinterpret_cast<float*>(Y)[idx] = v;
 }
 
-// One level of the 1-D Haar transform over the n approximations that start at row o of `src`: pair i < n / 2 ->
-// approximation to row o + i of `dst`, detail to row o + ceil(n / 2) + i of `T`; an odd last approximation is
-// carried to row o + n / 2 of `dst`.  scaled: multiply by C (ragged form); else plain sums (classic form).
-__global__ __launch_bounds__(256) void k_gen_haar1d_fwd(const float* __restrict__ src, float* __restrict__ dst,
-                                                        float* __restrict__ T, int seq, int ld, int o, int n, int scaled) {
+// per-pass factors of the power-of-two ("classic") arithmetic: det[i] multiplies the details of the pass's i-th
+// level, apx the approximations when the pass is the last one
+struct GenNorm {
+  float det[5];
+  float apx;
+};
+
+// NLEV levels of the 1-D Haar transform in one pass.  The current approximations (n_lo of them, rows o + i of `in`)
+// fall into blocks of 2^NLEV; a thread owns one block of one channel, loads it, runs the levels in registers and
+// writes every detail to its STaMP slot in T (the details of a level with n approximations left sit in slots
+// o + n .. ) and the block's one approximation to row o + block of apx_out (of T, times nm.apx, when `last`).
+// Pairs are (2 i, 2 i + 1); an approximation without partner is carried up unchanged, so a short last block is a
+// sub-tree of its own.  scaled: every butterfly is (x0 +- x1) * C (the form for any length); else plain sums and one
+// multiplication per finished coefficient (the power-of-two form).  in_kind: 0 fp32 buffer, 1 X fp32, 2 X bf16; with
+// X as input and o = 1, block 0 also copies token 0 to slot 0.  Grid: x = ceil(ld / 256), y = blocks, z = batch.
+template <int NLEV>
+__global__ __launch_bounds__(256) void k_gen_haar1d_fwd(const void* __restrict__ in, int in_kind, float* __restrict__ apx_out,
+                                                        float* __restrict__ T, int seq, int ld, int o, int n_lo, int scaled,
+                                                        int last, GenNorm nm) {
   GEN_INDEX;
-  const int m = n >> 1, nn = (n + 1) >> 1;
-  if (i < m) {
-    const float x0 = src[bo + (size_t)(o + 2 * i) * ld + c], x1 = src[bo + (size_t)(o + 2 * i + 1) * ld + c];
-    float a = __fadd_rn(x0, x1), dd = __fsub_rn(x0, x1);
-    if (scaled) {
-      a = __fmul_rn(a, kC);
-      dd = __fmul_rn(dd, kC);
+  constexpr int W = 1 << NLEV;
+  float v[W];
+#pragma unroll
+  for (int j = 0; j < W; ++j) {
+    const int gi = i * W + j;
+    v[j] = gi < n_lo ? gen_load(in, in_kind, bo + (size_t)(o + gi) * ld + c) : 0.0f;
+  }
+  int n_prev = n_lo;
+#pragma unroll
+  for (int li = 0; li < NLEV; ++li) {
+    const int n_cur = (n_prev + 1) >> 1;
+#pragma unroll
+    for (int j = 0; j < (W >> (li + 1)); ++j) {
+      const int gi = i * (W >> (li + 1)) + j;
+      if (gi < n_cur) {
+        if (2 * gi + 1 < n_prev) {
+          const float x0 = v[2 * j], x1 = v[2 * j + 1];
+          float a = __fadd_rn(x0, x1), dd = __fsub_rn(x0, x1);
+          if (scaled) {
+            a = __fmul_rn(a, kC);
+            dd = __fmul_rn(dd, kC);
+          } else {
+            dd = __fmul_rn(dd, nm.det[li]);
+          }
+          T[bo + (size_t)(o + n_cur + gi) * ld + c] = dd;
+          v[j] = a;
+        } else {
+          v[j] = v[2 * j];
+        }
+      }
     }
-    dst[bo + (size_t)(o + i) * ld + c] = a;
-    T[bo + (size_t)(o + nn + i) * ld + c] = dd;
-  } else {  // i == m, n odd
-    dst[bo + (size_t)(o + m) * ld + c] = src[bo + (size_t)(o + n - 1) * ld + c];
+    n_prev = n_cur;
   }
+  if (last) T[bo + (size_t)(o + i) * ld + c] = scaled ? v[0] : __fmul_rn(v[0], nm.apx);
+  else apx_out[bo + (size_t)(o + i) * ld + c] = v[0];
+  if (in_kind != 0 && o != 0 && i == 0) T[bo + c] = gen_load(in, in_kind, bo + c);
 }
 
-// Inverse of one level: approximations rows [o, o + nn) of `src`, details rows [o + nn, o + nn + m) of `S` ->
-// rows [o, o + n) of `dst`; both outputs times C (the orthonormal butterfly is its own inverse).
-__global__ __launch_bounds__(256) void k_gen_haar1d_inv(const float* __restrict__ src, const float* __restrict__ S,
-                                                        float* __restrict__ dst, int seq, int ld, int o, int n) {
+// The inverse of such a pass: the block's approximation (row o + block of apx_in) and the details (slots of S) ->
+// the 2^NLEV (or fewer) finer approximations, rows o + i of apx_out, or, when `last`, the tokens themselves: rows
+// o + i of Y (+ bias, output type); then block 0 also writes the token that was left out (slot 0 of S).
+template <int NLEV>
+__global__ __launch_bounds__(256) void k_gen_haar1d_inv(const float* __restrict__ apx_in, const float* __restrict__ S,
+                                                        float* __restrict__ apx_out, void* __restrict__ Y,
+                                                        const float* __restrict__ bias, int y_bf16, int seq, int ld, int o,
+                                                        int n_lo, int last) {
   GEN_INDEX;
-  const int m = n >> 1, nn = (n + 1) >> 1;
-  if (i < m) {
-    const float a = src[bo + (size_t)(o + i) * ld + c], dd = S[bo + (size_t)(o + nn + i) * ld + c];
-    dst[bo + (size_t)(o + 2 * i) * ld + c] = (a + dd) * kC;
-    dst[bo + (size_t)(o + 2 * i + 1) * ld + c] = (a - dd) * kC;
-  } else {
-    dst[bo + (size_t)(o + n - 1) * ld + c] = src[bo + (size_t)(o + m) * ld + c];
+  constexpr int W = 1 << NLEV;
+  int n[NLEV + 1];
+  n[0] = n_lo;
+#pragma unroll
+  for (int li = 0; li < NLEV; ++li) n[li + 1] = (n[li] + 1) >> 1;
+  float v[W];
+  v[0] = apx_in[bo + (size_t)(o + i) * ld + c];
+#pragma unroll
+  for (int li = NLEV - 1; li >= 0; --li) {
+#pragma unroll
+    for (int j = (W >> (li + 1)) - 1; j >= 0; --j) {
+      const int gi = i * (W >> (li + 1)) + j;
+      if (gi < n[li + 1]) {
+        const float a = v[j];
+        if (2 * gi + 1 < n[li]) {
+          const float dd = S[bo + (size_t)(o + n[li + 1] + gi) * ld + c];
+          v[2 * j] = (a + dd) * kC;
+          v[2 * j + 1] = (a - dd) * kC;
+        } else {
+          v[2 * j] = a;
+        }
+      }
+    }
   }
+  const float bv = (last && bias != nullptr) ? bias[c] : 0.0f;
+#pragma unroll
+  for (int j = 0; j < W; ++j) {
+    const int gi = i * W + j;
+    if (gi < n_lo) {
+      const size_t idx = bo + (size_t)(o + gi) * ld + c;
+      if (last) gen_store_y(Y, y_bf16, idx, v[j] + bv);
+      else apx_out[idx] = v[j];
+    }
+  }
+  if (last && o != 0 && i == 0) gen_store_y(Y, y_bf16, bo + c, S[bo + c] + bv);
 }
 
-// One level of the 2-D Haar pyramid on the h x w low-low region (grid pitch gridW, token = r * gridW + c) of `src`:
-// cell (ci, cj) -> low-low to grid position (ci, cj) of `dst` (plain sums), the three details times 2^-level to
-// their STaMP slots in `T` (band_base = slot of the level's first band; bands W, H, D, each (h/2) x (w/2)).
-// blockIdx.y = cell index ci * (w / 2) + cj.
-__global__ __launch_bounds__(256) void k_gen_haar2d_fwd(const float* __restrict__ src, float* __restrict__ dst,
-                                                        float* __restrict__ T, int seq, int ld, int gridW, int w,
-                                                        int band_base, float norm) {
+// NLEV levels of the 2-D Haar pyramid in one pass (square power-of-two grids).  The current low-low region is
+// w_lo x w_lo at the top-left of `in` (grid pitch gridW, token = r * gridW + col); a thread owns one patch of
+// 2^NLEV x 2^NLEV of one channel.  Per level: plain sums for the low-low value, the three details times 2^-level
+// to their STaMP slots (bands W, H, D of the level, each row-major, base[li] = slot of the level's band W).  The
+// patch's low-low value goes to grid position (pi, pj) of ll_out, or, when `last`, times apx_norm to slot
+// pi * (w_lo >> NLEV) + pj of T.  blockIdx.y = pi * (w_lo >> NLEV) + pj.
+struct GenBands {
+  int base[3];
+  float norm[3];
+};
+template <int NLEV>
+__global__ __launch_bounds__(256) void k_gen_haar2d_fwd(const void* __restrict__ in, int in_kind, float* __restrict__ ll_out,
+                                                        float* __restrict__ T, int seq, int ld, int gridW, int w_lo,
+                                                        GenBands bd, int last, float apx_norm) {
   GEN_INDEX;
-  const int w2 = w >> 1, ci = i / w2, cj = i - ci * w2;
-  const size_t r0 = bo + ((size_t)(2 * ci) * gridW + 2 * cj) * ld + c, r1 = r0 + (size_t)gridW * ld;
-  const float p = src[r0], q = src[r0 + ld], u = src[r1], v = src[r1 + ld];
-  const float t0 = __fadd_rn(p, q), t1 = __fsub_rn(p, q), t2 = __fadd_rn(u, v), t3 = __fsub_rn(u, v);
-  dst[bo + ((size_t)ci * gridW + cj) * ld + c] = __fadd_rn(t0, t2);
-  const int cells = (int)gridDim.y;  // (h / 2) * (w / 2)
-  T[bo + (size_t)(band_base + i) * ld + c] = __fmul_rn(__fadd_rn(t1, t3), norm);
-  T[bo + (size_t)(band_base + cells + i) * ld + c] = __fmul_rn(__fsub_rn(t0, t2), norm);
-  T[bo + (size_t)(band_base + 2 * cells + i) * ld + c] = __fmul_rn(__fsub_rn(t1, t3), norm);
+  constexpr int P = 1 << NLEV;
+  const int wp = w_lo >> NLEV, pi = i / wp, pj = i - pi * wp;
+  float v[P][P];
+#pragma unroll
+  for (int a = 0; a < P; ++a)
+#pragma unroll
+    for (int b = 0; b < P; ++b) v[a][b] = gen_load(in, in_kind, bo + ((size_t)(pi * P + a) * gridW + (pj * P + b)) * ld + c);
+#pragma unroll
+  for (int li = 0; li < NLEV; ++li) {
+    const int wl = w_lo >> (li + 1), cells = wl * wl;
+#pragma unroll
+    for (int ca = 0; ca < (P >> (li + 1)); ++ca)
+#pragma unroll
+      for (int cb = 0; cb < (P >> (li + 1)); ++cb) {
+        const float p = v[2 * ca][2 * cb], q = v[2 * ca][2 * cb + 1], u = v[2 * ca + 1][2 * cb], w = v[2 * ca + 1][2 * cb + 1];
+        const float t0 = __fadd_rn(p, q), t1 = __fsub_rn(p, q), t2 = __fadd_rn(u, w), t3 = __fsub_rn(u, w);
+        const int gi = (pi * (P >> (li + 1)) + ca) * wl + (pj * (P >> (li + 1)) + cb);
+        float* const tb = T + bo + (size_t)(bd.base[li] + gi) * ld + c;
+        tb[0] = __fmul_rn(__fadd_rn(t1, t3), bd.norm[li]);
+        tb[(size_t)cells * ld] = __fmul_rn(__fsub_rn(t0, t2), bd.norm[li]);
+        tb[(size_t)2 * cells * ld] = __fmul_rn(__fsub_rn(t1, t3), bd.norm[li]);
+        v[ca][cb] = __fadd_rn(t0, t2);
+      }
+  }
+  if (last) T[bo + (size_t)i * ld + c] = __fmul_rn(v[0][0], apx_norm);
+  else ll_out[bo + ((size_t)pi * gridW + pj) * ld + c] = v[0][0];
 }
 
-// final low-low block (hl x wl at grid pitch gridW of `src`) -> STaMP slots 0 .. hl * wl - 1 of T, times norm
-__global__ __launch_bounds__(256) void k_gen_ll_to_slots(const float* __restrict__ src, float* __restrict__ T, int seq, int ld,
-                                                         int gridW, int wl, float norm) {
+// The inverse of such a pass: the patch's low-low value (grid position (pi, pj) of ll_in, or slot i of S when
+// `first`) and the bands -> the 2^NLEV x 2^NLEV finer low-low values at the top-left of ll_out, or, when `last`,
+// the tokens of Y (+ bias, output type).  Orthonormal butterflies: every output of a level times 1/2.
+template <int NLEV>
+__global__ __launch_bounds__(256) void k_gen_haar2d_inv(const float* __restrict__ ll_in, int first, const float* __restrict__ S,
+                                                        float* __restrict__ ll_out, void* __restrict__ Y,
+                                                        const float* __restrict__ bias, int y_bf16, int seq, int ld, int gridW,
+                                                        int w_lo, GenBands bd, int last) {
   GEN_INDEX;
-  const int r = i / wl, cc = i - r * wl;
-  T[bo + (size_t)i * ld + c] = __fmul_rn(src[bo + ((size_t)r * gridW + cc) * ld + c], norm);
-}
-__global__ __launch_bounds__(256) void k_gen_slots_to_ll(const float* __restrict__ S, float* __restrict__ dst, int seq, int ld,
-                                                         int gridW, int wl) {
-  GEN_INDEX;
-  const int r = i / wl, cc = i - r * wl;
-  dst[bo + ((size_t)r * gridW + cc) * ld + c] = S[bo + (size_t)i * ld + c];
+  constexpr int P = 1 << NLEV;
+  const int wp = w_lo >> NLEV, pi = i / wp, pj = i - pi * wp;
+  float v[P][P];
+  v[0][0] = first ? S[bo + (size_t)i * ld + c] : ll_in[bo + ((size_t)pi * gridW + pj) * ld + c];
+#pragma unroll
+  for (int li = NLEV - 1; li >= 0; --li) {
+    const int wl = w_lo >> (li + 1), cells = wl * wl;
+#pragma unroll
+    for (int ca = (P >> (li + 1)) - 1; ca >= 0; --ca)
+#pragma unroll
+      for (int cb = (P >> (li + 1)) - 1; cb >= 0; --cb) {
+        const int gi = (pi * (P >> (li + 1)) + ca) * wl + (pj * (P >> (li + 1)) + cb);
+        const float* const sb = S + bo + (size_t)(bd.base[li] + gi) * ld + c;
+        const float cLL = v[ca][cb], cW = sb[0], cH = sb[(size_t)cells * ld], cD = sb[(size_t)2 * cells * ld];
+        const float t0 = cLL + cH, t2 = cLL - cH, t1 = cW + cD, t3 = cW - cD;
+        v[2 * ca][2 * cb] = (t0 + t1) * 0.5f;
+        v[2 * ca][2 * cb + 1] = (t0 - t1) * 0.5f;
+        v[2 * ca + 1][2 * cb] = (t2 + t3) * 0.5f;
+        v[2 * ca + 1][2 * cb + 1] = (t2 - t3) * 0.5f;
+      }
+  }
+  const float bv = (last && bias != nullptr) ? bias[c] : 0.0f;
+#pragma unroll
+  for (int a = 0; a < P; ++a)
+#pragma unroll
+    for (int b = 0; b < P; ++b) {
+      const size_t idx = bo + ((size_t)(pi * P + a) * gridW + (pj * P + b)) * ld + c;
+      if (last) gen_store_y(Y, y_bf16, idx, v[a][b] + bv);
+      else ll_out[idx] = v[a][b];
+    }
 }
 
-// Inverse of one 2-D level: low-low (h/2 x w/2 region of `src`, grid layout) and the level's bands (STaMP slots of
-// `S`) -> h x w region of `dst`; every output times 1/2 (the orthonormal 2-D butterfly).
-__global__ __launch_bounds__(256) void k_gen_haar2d_inv(const float* __restrict__ src, const float* __restrict__ S,
-                                                        float* __restrict__ dst, int seq, int ld, int gridW, int w, int band_base) {
+// NLEV stages of the Hadamard-ordered fast WHT in one pass: the stages with strides h_lo, 2 h_lo, ... combine the
+// 2^NLEV rows base + j * h_lo, base = (i / h_lo) * (h_lo << NLEV) + i % h_lo (blockIdx.y = i).  in_kind as above.
+// out_kind 0: fp32 rows in place; 1: the last pass of the forward transform, row r times norm to the STaMP slot
+// inv_perm[r] of T (sequency order); 2: the last pass of the inverse, the same to rows of Y (+ bias, output type).
+template <int NLEV>
+__global__ __launch_bounds__(256) void k_gen_wht(const void* __restrict__ in, int in_kind, float* __restrict__ out,
+                                                 void* __restrict__ Y, int out_kind, const int* __restrict__ inv_perm, float norm,
+                                                 const float* __restrict__ bias, int y_bf16, int seq, int ld, int h_lo) {
   GEN_INDEX;
-  const int w2 = w >> 1, ci = i / w2, cj = i - ci * w2, cells = (int)gridDim.y;
-  const float cLL = src[bo + ((size_t)ci * gridW + cj) * ld + c];
-  const float cW = S[bo + (size_t)(band_base + i) * ld + c], cH = S[bo + (size_t)(band_base + cells + i) * ld + c],
-              cD = S[bo + (size_t)(band_base + 2 * cells + i) * ld + c];
-  const float t0 = cLL + cH, t2 = cLL - cH, t1 = cW + cD, t3 = cW - cD;
-  const size_t r0 = bo + ((size_t)(2 * ci) * gridW + 2 * cj) * ld + c, r1 = r0 + (size_t)gridW * ld;
-  dst[r0] = (t0 + t1) * 0.5f;
-  dst[r0 + ld] = (t0 - t1) * 0.5f;
-  dst[r1] = (t2 + t3) * 0.5f;
-  dst[r1 + ld] = (t2 - t3) * 0.5f;
-}
-
-// One level of the Hadamard-ordered fast WHT: rows j and j + h of every group of 2 h rows -> sum, difference.
-// blockIdx.y = pair index.
-__global__ __launch_bounds__(256) void k_gen_wht_level(const float* __restrict__ src, float* __restrict__ dst, int seq, int ld, int h) {
-  GEN_INDEX;
-  const int blk = i / h, t = i - blk * h;
-  const size_t r0 = bo + (size_t)(blk * 2 * h + t) * ld + c, r1 = r0 + (size_t)h * ld;
-  const float u = src[r0], v = src[r1];
-  dst[r0] = __fadd_rn(u, v);
-  dst[r1] = __fsub_rn(u, v);
+  constexpr int W = 1 << NLEV;
+  const int hp = i / h_lo, t = i - hp * h_lo;
+  const int base = hp * (h_lo << NLEV) + t;
+  float v[W];
+#pragma unroll
+  for (int j = 0; j < W; ++j) v[j] = gen_load(in, in_kind, bo + (size_t)(base + j * h_lo) * ld + c);
+#pragma unroll
+  for (int st = 0; st < NLEV; ++st) {
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+      if ((j & (1 << st)) == 0) {
+        const float u = v[j], w = v[j + (1 << st)];
+        v[j] = __fadd_rn(u, w);
+        v[j + (1 << st)] = __fsub_rn(u, w);
+      }
+    }
+  }
+  const float bv = (out_kind == 2 && bias != nullptr) ? bias[c] : 0.0f;
+#pragma unroll
+  for (int j = 0; j < W; ++j) {
+    const int r = base + j * h_lo;
+    if (out_kind == 0) {
+      out[bo + (size_t)r * ld + c] = v[j];
+    } else {
+      const float x = __fmul_rn(v[j], norm);
+      const size_t idx = bo + (size_t)inv_perm[r] * ld + c;
+      if (out_kind == 1) out[idx] = x;
+      else gen_store_y(Y, y_bf16, idx, x + bv);
+    }
+  }
 }
 
 // dst[k, c] = fl32( sum_n Mx[k, n] * src[n, c] ) in fp64 (Mx = C, or C^T when transposed), per batch.
@@ -498,27 +626,19 @@ hipError_t stamp_gen_plan_tables(stamp_plan* p, const float* W, hipStream_t st) 
   const StampGeom& g = p->geom;
   const int s = g.s;
   hipError_t e = hipSuccess;
-  if (gn.kind == kGenHaarClassic) {
-    std::vector<float> nrm(s);
-    const int na = s >> gn.levels;
-    for (int i = 0; i < na; ++i) nrm[i] = haar_norm_host(gn.levels);
-    for (int l = gn.levels; l >= 1; --l)
-      for (int i = s >> l; i < (s >> (l - 1)); ++i) nrm[i] = haar_norm_host(l);
-    if ((e = upload(&p->norm_dev, nrm, st)) != hipSuccess) return e;
-  }
   if (gn.kind == kGenWht) {
+    // STaMP slot q (sequency q) takes row rev(gray(q)) of the Hadamard-ordered result: stored inverted, the slot of
+    // every row, for the scatter of the transform's last pass
     int J = 0;
     while ((1 << J) < s) ++J;
-    std::vector<int32_t> perm(s);
+    std::vector<int32_t> inv(s);
     for (int q = 0; q < s; ++q) {
       const int gr = q ^ (q >> 1);
       int rev = 0;
       for (int b = 0; b < J; ++b) rev |= ((gr >> b) & 1) << (J - 1 - b);
-      perm[q] = rev;
+      inv[rev] = q;
     }
-    if ((e = upload(&p->perm_dev, perm, st)) != hipSuccess) return e;
-    std::vector<float> nrm(s, haar_norm_host(J));
-    if ((e = upload(&p->norm_dev, nrm, st)) != hipSuccess) return e;
+    if ((e = upload(&p->perm_dev, inv, st)) != hipSuccess) return e;
   }
   if (gn.kind == kGenDct) {
     if ((e = hipMalloc(reinterpret_cast<void**>(&p->dct_dev), sizeof(double) * (size_t)s * s)) != hipSuccess) return e;
@@ -542,136 +662,245 @@ hipError_t stamp_gen_plan_tables(stamp_plan* p, const float* W, hipStream_t st) 
 // ---------------------------------------------------------------------------------------------
 // Forward and inverse transforms
 // ---------------------------------------------------------------------------------------------
+namespace {
+constexpr int kPass1d = 5;  // levels per pass of the 1-D kernels (32 values per thread)
+constexpr int kPass2d = 3;  // of the 2-D kernels (8 x 8 values per thread)
+
+template <int NLEV>
+void launch_haar1d_fwd(dim3 grid, hipStream_t st, const void* in, int in_kind, float* apx_out, float* T, int s, int ld, int o, int n_lo,
+                       int scaled, int last, const GenNorm& nm) {
+  hipLaunchKernelGGL(k_gen_haar1d_fwd<NLEV>, grid, dim3(256), 0, st, in, in_kind, apx_out, T, s, ld, o, n_lo, scaled, last, nm);
+}
+template <int NLEV>
+void launch_haar1d_inv(dim3 grid, hipStream_t st, const float* apx_in, const float* S, float* apx_out, void* Y, const float* bias,
+                       int y_bf16, int s, int ld, int o, int n_lo, int last) {
+  hipLaunchKernelGGL(k_gen_haar1d_inv<NLEV>, grid, dim3(256), 0, st, apx_in, S, apx_out, Y, bias, y_bf16, s, ld, o, n_lo, last);
+}
+template <int NLEV>
+void launch_haar2d_fwd(dim3 grid, hipStream_t st, const void* in, int in_kind, float* ll_out, float* T, int s, int ld, int gridW, int w_lo,
+                       const GenBands& bd, int last, float apx_norm) {
+  hipLaunchKernelGGL(k_gen_haar2d_fwd<NLEV>, grid, dim3(256), 0, st, in, in_kind, ll_out, T, s, ld, gridW, w_lo, bd, last, apx_norm);
+}
+template <int NLEV>
+void launch_haar2d_inv(dim3 grid, hipStream_t st, const float* ll_in, int first, const float* S, float* ll_out, void* Y, const float* bias,
+                       int y_bf16, int s, int ld, int gridW, int w_lo, const GenBands& bd, int last) {
+  hipLaunchKernelGGL(k_gen_haar2d_inv<NLEV>, grid, dim3(256), 0, st, ll_in, first, S, ll_out, Y, bias, y_bf16, s, ld, gridW, w_lo, bd, last);
+}
+template <int NLEV>
+void launch_wht(dim3 grid, hipStream_t st, const void* in, int in_kind, float* out, void* Y, int out_kind, const int* inv_perm, float norm,
+                const float* bias, int y_bf16, int s, int ld, int h_lo) {
+  hipLaunchKernelGGL(k_gen_wht<NLEV>, grid, dim3(256), 0, st, in, in_kind, out, Y, out_kind, inv_perm, norm, bias, y_bf16, s, ld, h_lo);
+}
+
+// slot of band W of 2-D level l: the final low-low block and the bands of the coarser levels come first
+int band_base_2d(const StampGen& gn, int l) {
+  int base = (gn.gridH >> gn.levels) * (gn.gridW >> gn.levels);
+  for (int l2 = gn.levels; l2 > l; --l2) base += 3 * (gn.gridH >> l2) * (gn.gridW >> l2);
+  return base;
+}
+}  // namespace
+
+// X -> T (fp32, STaMP order) in buf[2] (buf[0] when there is nothing to transform); buf[0], buf[1] take the
+// approximations between passes.
 hipError_t stamp_gen_forward(const stamp_plan* p, const void* X, float* const (&buf)[3], float** T_out, hipStream_t st) {
   const StampGen& gn = p->gen;
   const StampGeom& g = p->geom;
   const int s = g.s, d = g.d, B = g.B;
-  float *P = buf[0], *Q = buf[1], *T = buf[2];
-  hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(256), 0, st, X, P, s, d, g.x_bf16);
-  switch (gn.kind) {
-    case kGenCopy:
-      *T_out = P;
-      break;
-    case kGenHaarRagged:
-    case kGenHaarClassic: {
-      const int o = gn.skip ? 1 : 0, scaled = gn.kind == kGenHaarRagged;
-      int n = s - o;
-      for (int l = 0; l < gn.levels; ++l) {
-        hipLaunchKernelGGL(k_gen_haar1d_fwd, rows_grid(d, (n + 1) / 2, B), dim3(256), 0, st, P, Q, T, s, d, o, n, scaled);
-        std::swap(P, Q);
-        n = (n + 1) / 2;
-      }
-      // what is left: the approximations -> slots [o, o + n); token 0, when it is left out, -> slot 0
-      hipLaunchKernelGGL(k_gen_copy_rows, rows_grid(d, n, B), dim3(256), 0, st, P, T, s, d, o, o,
-                         static_cast<const float*>(nullptr), static_cast<const int*>(nullptr));
-      if (o)
-        hipLaunchKernelGGL(k_gen_copy_rows, rows_grid(d, 1, B), dim3(256), 0, st, buf[0], T, s, d, 0, 0,
-                           static_cast<const float*>(nullptr), static_cast<const int*>(nullptr));
-      if (!scaled && gn.levels > 0)  // classic form: one multiplication by the level's norm at the end
-        hipLaunchKernelGGL(k_gen_copy_rows, rows_grid(d, s, B), dim3(256), 0, st, T, T, s, d, 0, 0, p->norm_dev,
-                           static_cast<const int*>(nullptr));
-      *T_out = T;
-      break;
-    }
-    case kGenHaar2d: {
-      int h = gn.gridH, w = gn.gridW;
-      // slot of the first band of level l: the low-low block and the bands of the coarser levels come first
-      for (int l = 1; l <= gn.levels; ++l) {
-        int base = (gn.gridH >> gn.levels) * (gn.gridW >> gn.levels);
-        for (int l2 = gn.levels; l2 > l; --l2) base += 3 * (gn.gridH >> l2) * (gn.gridW >> l2);
-        hipLaunchKernelGGL(k_gen_haar2d_fwd, rows_grid(d, (h / 2) * (w / 2), B), dim3(256), 0, st, P, Q, T, s, d, gn.gridW, w, base,
-                           std::ldexp(1.0f, -l));
-        std::swap(P, Q);
-        h /= 2;
-        w /= 2;
-      }
-      hipLaunchKernelGGL(k_gen_ll_to_slots, rows_grid(d, h * w, B), dim3(256), 0, st, P, T, s, d, gn.gridW, w, std::ldexp(1.0f, -gn.levels));
-      *T_out = T;
-      break;
-    }
-    case kGenWht: {
-      for (int h = 1; h < s; h *= 2) {
-        hipLaunchKernelGGL(k_gen_wht_level, rows_grid(d, s / 2, B), dim3(256), 0, st, P, Q, s, d, h);
-        std::swap(P, Q);
-      }
-      hipLaunchKernelGGL(k_gen_copy_rows, rows_grid(d, s, B), dim3(256), 0, st, P, T, s, d, 0, 0, p->norm_dev, p->perm_dev);
-      *T_out = T;
-      break;
-    }
-    case kGenDct:
-      hipLaunchKernelGGL(k_gen_dct, dim3((d + 63) / 64, (s + 63) / 64, B), dim3(256), 0, st, p->dct_dev, 0, P, T, s, d);
-      *T_out = T;
-      break;
-    default:
-      return hipErrorInvalidValue;
+  const int xk = g.x_bf16 ? 2 : 1;
+  float* const T = buf[2];
+  float* tmp[2] = {buf[0], buf[1]};
+  const bool haar1d = gn.kind == kGenHaarRagged || gn.kind == kGenHaarClassic;
+  if (gn.kind == kGenCopy || ((haar1d || gn.kind == kGenHaar2d) && gn.levels == 0)) {
+    hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(256), 0, st, X, buf[0], s, d, g.x_bf16);
+    *T_out = buf[0];
+    return hipGetLastError();
   }
-  return hipGetLastError();
+  *T_out = T;
+  if (haar1d) {
+    const int o = gn.skip ? 1 : 0, scaled = gn.kind == kGenHaarRagged;
+    const std::vector<int> sz = ragged_sizes(s - o, gn.levels);
+    const void* in = X;
+    int in_kind = xk, flip = 0;
+    for (int l = 0; l < gn.levels;) {
+      const int nlev = std::min(kPass1d, gn.levels - l), last = l + nlev == gn.levels;
+      GenNorm nm = {};
+      for (int i = 0; i < nlev; ++i) nm.det[i] = haar_norm_host(l + 1 + i);
+      nm.apx = haar_norm_host(gn.levels);
+      const dim3 grid = rows_grid(d, sz[l + nlev], B);
+      float* out = tmp[flip];
+      switch (nlev) {
+        case 1: launch_haar1d_fwd<1>(grid, st, in, in_kind, out, T, s, d, o, sz[l], scaled, last, nm); break;
+        case 2: launch_haar1d_fwd<2>(grid, st, in, in_kind, out, T, s, d, o, sz[l], scaled, last, nm); break;
+        case 3: launch_haar1d_fwd<3>(grid, st, in, in_kind, out, T, s, d, o, sz[l], scaled, last, nm); break;
+        case 4: launch_haar1d_fwd<4>(grid, st, in, in_kind, out, T, s, d, o, sz[l], scaled, last, nm); break;
+        default: launch_haar1d_fwd<5>(grid, st, in, in_kind, out, T, s, d, o, sz[l], scaled, last, nm); break;
+      }
+      in = out;
+      in_kind = 0;
+      flip ^= 1;
+      l += nlev;
+    }
+    return hipGetLastError();
+  }
+  if (gn.kind == kGenHaar2d) {
+    const void* in = X;
+    int in_kind = xk, flip = 0;
+    for (int l = 0; l < gn.levels;) {
+      const int nlev = std::min(kPass2d, gn.levels - l), last = l + nlev == gn.levels;
+      GenBands bd = {};
+      for (int i = 0; i < nlev; ++i) {
+        bd.base[i] = band_base_2d(gn, l + 1 + i);
+        bd.norm[i] = std::ldexp(1.0f, -(l + 1 + i));
+      }
+      const int w_lo = gn.gridW >> l, wp = w_lo >> nlev;
+      const dim3 grid = rows_grid(d, wp * wp, B);
+      float* out = tmp[flip];
+      const float an = std::ldexp(1.0f, -gn.levels);
+      switch (nlev) {
+        case 1: launch_haar2d_fwd<1>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, bd, last, an); break;
+        case 2: launch_haar2d_fwd<2>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, bd, last, an); break;
+        default: launch_haar2d_fwd<3>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, bd, last, an); break;
+      }
+      in = out;
+      in_kind = 0;
+      flip ^= 1;
+      l += nlev;
+    }
+    return hipGetLastError();
+  }
+  if (gn.kind == kGenWht) {
+    int J = 0;
+    while ((1 << J) < s) ++J;
+    if (J == 0) {  // one token: the transform is the identity
+      hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(256), 0, st, X, buf[0], s, d, g.x_bf16);
+      *T_out = buf[0];
+      return hipGetLastError();
+    }
+    const void* in = X;
+    int in_kind = xk, flip = 0;
+    for (int l = 0; l < J;) {
+      const int nlev = std::min(kPass1d, J - l), last = l + nlev == J;
+      const dim3 grid = rows_grid(d, s >> nlev, B);
+      float* out = last ? T : tmp[flip];
+      const int ok = last ? 1 : 0;
+      const float nrm = haar_norm_host(J);
+      switch (nlev) {
+        case 1: launch_wht<1>(grid, st, in, in_kind, out, nullptr, ok, p->perm_dev, nrm, nullptr, 0, s, d, 1 << l); break;
+        case 2: launch_wht<2>(grid, st, in, in_kind, out, nullptr, ok, p->perm_dev, nrm, nullptr, 0, s, d, 1 << l); break;
+        case 3: launch_wht<3>(grid, st, in, in_kind, out, nullptr, ok, p->perm_dev, nrm, nullptr, 0, s, d, 1 << l); break;
+        case 4: launch_wht<4>(grid, st, in, in_kind, out, nullptr, ok, p->perm_dev, nrm, nullptr, 0, s, d, 1 << l); break;
+        default: launch_wht<5>(grid, st, in, in_kind, out, nullptr, ok, p->perm_dev, nrm, nullptr, 0, s, d, 1 << l); break;
+      }
+      in = out;
+      in_kind = 0;
+      flip ^= 1;
+      l += nlev;
+    }
+    return hipGetLastError();
+  }
+  if (gn.kind == kGenDct) {
+    hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(256), 0, st, X, buf[0], s, d, g.x_bf16);
+    hipLaunchKernelGGL(k_gen_dct, dim3((d + 63) / 64, (s + 63) / 64, B), dim3(256), 0, st, p->dct_dev, 0, buf[0], T, s, d);
+    return hipGetLastError();
+  }
+  return hipErrorInvalidValue;
 }
 
 // buf[0] = S, the transformed output in STaMP order (only read: the details of every level come from it); buf[1],
-// buf[2] take the approximations of successive levels in turn.
+// buf[2] take the approximations between passes.  The last pass adds the bias and writes Y in the plan's output type.
 hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int ncols, const float* bias, void* Y, hipStream_t st) {
   const StampGen& gn = p->gen;
   const StampGeom& g = p->geom;
   const int s = g.s, B = g.B, ld = ncols;
-  float* S = buf[0];
-  const float* src = S;
-  float* dst = buf[1];
-  auto flip = [&]() {
-    src = dst;
-    dst = (dst == buf[1]) ? buf[2] : buf[1];
-  };
-  switch (gn.kind) {
-    case kGenCopy:
-      break;
-    case kGenHaarRagged:
-    case kGenHaarClassic: {
-      const int o = gn.skip ? 1 : 0;
-      const std::vector<int> sz = ragged_sizes(s - o, gn.levels);
-      for (int l = gn.levels; l >= 1; --l) {
-        hipLaunchKernelGGL(k_gen_haar1d_inv, rows_grid(ld, (sz[l - 1] + 1) / 2, B), dim3(256), 0, st, src, S, dst, s, ld, o, sz[l - 1]);
-        flip();
-      }
-      if (gn.levels > 0 && o)  // the token that was left out of L sits in slot 0
-        hipLaunchKernelGGL(k_gen_copy_rows, rows_grid(ld, 1, B), dim3(256), 0, st, S, const_cast<float*>(src), s, ld, 0, 0,
-                           static_cast<const float*>(nullptr), static_cast<const int*>(nullptr));
-      break;
-    }
-    case kGenHaar2d: {
-      // approximations in grid layout (pitch gridW) in the top-left corner of the work buffers
-      int h = gn.gridH >> gn.levels, w = gn.gridW >> gn.levels;
-      const int ll = h * w;
-      hipLaunchKernelGGL(k_gen_slots_to_ll, rows_grid(ld, ll, B), dim3(256), 0, st, S, dst, s, ld, gn.gridW, w);
-      flip();
-      for (int l = gn.levels; l >= 1; --l) {
-        int base = ll;
-        for (int l2 = gn.levels; l2 > l; --l2) base += 3 * (gn.gridH >> l2) * (gn.gridW >> l2);
-        h *= 2;
-        w *= 2;
-        hipLaunchKernelGGL(k_gen_haar2d_inv, rows_grid(ld, (h / 2) * (w / 2), B), dim3(256), 0, st, src, S, dst, s, ld, gn.gridW, w, base);
-        flip();
-      }
-      break;
-    }
-    case kGenWht: {
-      // the sequency-ordered orthonormal WHT is its own inverse
-      for (int h = 1; h < s; h *= 2) {
-        hipLaunchKernelGGL(k_gen_wht_level, rows_grid(ld, s / 2, B), dim3(256), 0, st, src, dst, s, ld, h);
-        flip();
-      }
-      hipLaunchKernelGGL(k_gen_copy_rows, rows_grid(ld, s, B), dim3(256), 0, st, src, dst, s, ld, 0, 0, p->norm_dev, p->perm_dev);
-      flip();
-      break;
-    }
-    case kGenDct:
-      hipLaunchKernelGGL(k_gen_dct, dim3((ld + 63) / 64, (s + 63) / 64, B), dim3(256), 0, st, p->dct_dev, 1, src, dst, s, ld);
-      flip();
-      break;
-    default:
-      return hipErrorInvalidValue;
+  const float* S = buf[0];
+  float* tmp[2] = {buf[1], buf[2]};
+  const bool haar1d = gn.kind == kGenHaarRagged || gn.kind == kGenHaarClassic;
+  if (gn.kind == kGenCopy || ((haar1d || gn.kind == kGenHaar2d) && gn.levels == 0)) {
+    hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(256), 0, st, S, bias, Y, s, ld, g.y_bf16);
+    return hipGetLastError();
   }
-  hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(256), 0, st, src, bias, Y, s, ld, g.y_bf16);
-  return hipGetLastError();
+  if (haar1d) {
+    const int o = gn.skip ? 1 : 0;
+    const std::vector<int> sz = ragged_sizes(s - o, gn.levels);
+    // passes of up to kPass1d levels counted from the bottom, run from the top
+    std::vector<int> cut{0};
+    while (cut.back() < gn.levels) cut.push_back(std::min(gn.levels, cut.back() + kPass1d));
+    const float* in = S;
+    int flip = 0;
+    for (int pi = (int)cut.size() - 1; pi >= 1; --pi) {
+      const int l_lo = cut[pi - 1], nlev = cut[pi] - l_lo, last = l_lo == 0;
+      const dim3 grid = rows_grid(ld, sz[l_lo + nlev], B);
+      float* out = tmp[flip];
+      switch (nlev) {
+        case 1: launch_haar1d_inv<1>(grid, st, in, S, out, Y, bias, g.y_bf16, s, ld, o, sz[l_lo], last); break;
+        case 2: launch_haar1d_inv<2>(grid, st, in, S, out, Y, bias, g.y_bf16, s, ld, o, sz[l_lo], last); break;
+        case 3: launch_haar1d_inv<3>(grid, st, in, S, out, Y, bias, g.y_bf16, s, ld, o, sz[l_lo], last); break;
+        case 4: launch_haar1d_inv<4>(grid, st, in, S, out, Y, bias, g.y_bf16, s, ld, o, sz[l_lo], last); break;
+        default: launch_haar1d_inv<5>(grid, st, in, S, out, Y, bias, g.y_bf16, s, ld, o, sz[l_lo], last); break;
+      }
+      in = out;
+      flip ^= 1;
+    }
+    return hipGetLastError();
+  }
+  if (gn.kind == kGenHaar2d) {
+    std::vector<int> cut{0};
+    while (cut.back() < gn.levels) cut.push_back(std::min(gn.levels, cut.back() + kPass2d));
+    const float* in = S;
+    int flip = 0, first = 1;
+    for (int pi = (int)cut.size() - 1; pi >= 1; --pi) {
+      const int l_lo = cut[pi - 1], nlev = cut[pi] - l_lo, last = l_lo == 0;
+      GenBands bd = {};
+      for (int i = 0; i < nlev; ++i) bd.base[i] = band_base_2d(gn, l_lo + 1 + i);
+      const int w_lo = gn.gridW >> l_lo, wp = w_lo >> nlev;
+      const dim3 grid = rows_grid(ld, wp * wp, B);
+      float* out = tmp[flip];
+      switch (nlev) {
+        case 1: launch_haar2d_inv<1>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, bd, last); break;
+        case 2: launch_haar2d_inv<2>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, bd, last); break;
+        default: launch_haar2d_inv<3>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, bd, last); break;
+      }
+      in = out;
+      first = 0;
+      flip ^= 1;
+    }
+    return hipGetLastError();
+  }
+  if (gn.kind == kGenWht) {
+    // the sequency-ordered orthonormal WHT is its own inverse
+    int J = 0;
+    while ((1 << J) < s) ++J;
+    if (J == 0) {
+      hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(256), 0, st, S, bias, Y, s, ld, g.y_bf16);
+      return hipGetLastError();
+    }
+    const float* in = S;
+    int flip = 0;
+    for (int l = 0; l < J;) {
+      const int nlev = std::min(kPass1d, J - l), last = l + nlev == J;
+      const dim3 grid = rows_grid(ld, s >> nlev, B);
+      float* out = tmp[flip];
+      const int ok = last ? 2 : 0;
+      const float nrm = haar_norm_host(J);
+      switch (nlev) {
+        case 1: launch_wht<1>(grid, st, in, 0, out, Y, ok, p->perm_dev, nrm, bias, g.y_bf16, s, ld, 1 << l); break;
+        case 2: launch_wht<2>(grid, st, in, 0, out, Y, ok, p->perm_dev, nrm, bias, g.y_bf16, s, ld, 1 << l); break;
+        case 3: launch_wht<3>(grid, st, in, 0, out, Y, ok, p->perm_dev, nrm, bias, g.y_bf16, s, ld, 1 << l); break;
+        case 4: launch_wht<4>(grid, st, in, 0, out, Y, ok, p->perm_dev, nrm, bias, g.y_bf16, s, ld, 1 << l); break;
+        default: launch_wht<5>(grid, st, in, 0, out, Y, ok, p->perm_dev, nrm, bias, g.y_bf16, s, ld, 1 << l); break;
+      }
+      in = out;
+      flip ^= 1;
+      l += nlev;
+    }
+    return hipGetLastError();
+  }
+  if (gn.kind == kGenDct) {
+    hipLaunchKernelGGL(k_gen_dct, dim3((ld + 63) / 64, (s + 63) / 64, B), dim3(256), 0, st, p->dct_dev, 1, S, tmp[0], s, ld);
+    hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(256), 0, st, tmp[0], bias, Y, s, ld, g.y_bf16);
+    return hipGetLastError();
+  }
+  return hipErrorInvalidValue;
 }
 
 hipError_t stamp_launch_quant_rows_grouped(const stamp_plan* p, const float* T, int8_t* codes, float* scales, hipStream_t st) {
