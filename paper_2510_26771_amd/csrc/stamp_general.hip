@@ -34,9 +34,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
-// grid: x = ceil(row_elems / 256), y = rows of this launch, z = batch; one thread per element of a row
+// grid: x = ceil(row_elems / blockDim.x), y = rows of this launch, z = batch; one thread per element of a row
 #define GEN_INDEX                                      \
-  const int c = blockIdx.x * 256 + threadIdx.x;        \
+  const int c = blockIdx.x * blockDim.x + threadIdx.x; \
   const int i = blockIdx.y;                            \
   const size_t bo = (size_t)blockIdx.z * seq * ld;     \
   if (c >= ld) return
@@ -286,49 +286,60 @@ __global__ __launch_bounds__(256) void k_gen_wht(const void* __restrict__ in, in
   }
 }
 
-// dst[k, c] = fl32( sum_n Mx[k, n] * src[n, c] ) in fp64 (Mx = C, or C^T when transposed), per batch.
-// 64 x 64 outputs per workgroup of 256 threads (4 x 4 per thread), 16 values of n per pass through LDS.
+// dst[k, c] = fl32( sum_n Mx[k, n] * src[n, c] ) in fp64 (Mx = C, or C^T when transposed), per batch, on the fp64
+// matrix pipeline: 64 x 64 outputs per workgroup of 4 waves (2 x 2), a wave 32 x 32 = 2 x 2 blocks of
+// v_mfma_f64_16x16x4_f64, 16 values of n per pass through LDS.  A lane feeds A[row lane % 16][n lane / 16] and
+// B[n lane / 16][column lane % 16] and holds D[row 4 i + lane / 16][column lane % 16], i = 0..3 (checked on the chip).
+typedef double v4d __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void k_gen_dct(const double* __restrict__ Cm, int transposed, const float* __restrict__ src,
                                                  float* __restrict__ dst, int seq, int ld) {
   __shared__ double sM[16][65];
   __shared__ double sX[16][65];
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wk = wave >> 1, wc = wave & 1, l16 = lane & 15, lk = lane >> 4;
   const int k0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   const size_t bo = (size_t)blockIdx.z * seq * ld;
-  double acc[4][4] = {};
+  v4d acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) acc[a][b] = (v4d){0.0, 0.0, 0.0, 0.0};
   for (int n0 = 0; n0 < seq; n0 += 16) {
     for (int e = threadIdx.x; e < 16 * 64; e += 256) {
-      const int nn = e >> 6, kk = e & 63;  // consecutive threads: consecutive k
-      const int k = k0 + kk, n = n0 + nn;
+      // the matrix: consecutive threads along its contiguous direction (n as stored, k when transposed)
+      const int nn_m = transposed ? (e >> 6) : (e & 15), kk_m = transposed ? (e & 63) : (e >> 4);
+      const int k = k0 + kk_m, n = n0 + nn_m;
       double mv = 0.0;
       if (k < seq && n < seq) mv = transposed ? Cm[(size_t)n * seq + k] : Cm[(size_t)k * seq + n];
-      sM[nn][kk] = mv;
-      const int cc = c0 + kk;
-      sX[nn][kk] = (n < seq && cc < ld) ? (double)src[bo + (size_t)n * ld + cc] : 0.0;
+      sM[nn_m][kk_m] = mv;
+      const int nn = e >> 6, cc = c0 + (e & 63);
+      sX[nn][e & 63] = (n0 + nn < seq && cc < ld) ? (double)src[bo + (size_t)(n0 + nn) * ld + cc] : 0.0;
     }
     __syncthreads();
 #pragma unroll
-    for (int nn = 0; nn < 16; ++nn) {
-      double mk[4], xc[4];
+    for (int kk = 0; kk < 4; ++kk) {
+      double fa[2], fb[2];
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        mk[a] = sM[nn][ty * 4 + a];
-        xc[a] = sX[nn][tx * 4 + a];
+      for (int a = 0; a < 2; ++a) {
+        fa[a] = sM[kk * 4 + lk][wk * 32 + a * 16 + l16];
+        fb[a] = sX[kk * 4 + lk][wc * 32 + a * 16 + l16];
       }
 #pragma unroll
-      for (int a = 0; a < 4; ++a)
+      for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] += mk[a] * xc[b];
+        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[a], fb[b], acc[a][b], 0, 0, 0);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int k = k0 + ty * 4 + a, cc = c0 + tx * 4 + b;
-      if (k < seq && cc < ld) dst[bo + (size_t)k * ld + cc] = (float)acc[a][b];
-    }
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int k = k0 + wk * 32 + a * 16 + 4 * i + lk, cc = c0 + wc * 32 + b * 16 + l16;
+        if (k < seq && cc < ld) dst[bo + (size_t)k * ld + cc] = (float)acc[a][b][i];
+      }
 }
 
 __global__ void k_gen_dct_matrix(double* __restrict__ Cm, int s) {
@@ -433,8 +444,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 // Y'[m, n] = sum_g (float(acc_g[m, n]) * sa[m, g]) * swg[g, n], acc_g = the integer sum over the 64 channels of group
-// g on v_mfma_i32_32x32x32_i8 (two per group and 32 x 32 block), groups added in increasing order, every floating-
-// point operation rounded on its own.  Workgroup: 4 waves (2 x 2), tile 128 x 128, wave 64 x 64 = 2 x 2 blocks.
+// g on v_mfma_i32_32x32x32_i8 (two per group and 32 x 32 block), groups added in increasing order (conversion,
+// multiplication by the row's scale, fused multiply-add with the column's: three vector instructions per output and
+// group, which is what bounds this kernel: the two MFMAs of a group and block take a quarter of that time).  Workgroup: 4 waves (2 x 2), tile 128 x 128, wave 64 x 64 = 2 x 2 blocks.
 // Lane group kg of an MFMA takes the channels [32 ks + 16 kg, +16) of the group in sub-step ks (both operands alike).
 constexpr int kGPitch = 80;  // bytes per staged row: 64 codes + 16 (conflict-free 16-byte fragment reads)
 __global__ __launch_bounds__(256) void k_gen_gemm_grouped(const int8_t* __restrict__ A, const float* __restrict__ sa,
@@ -506,7 +518,7 @@ __global__ __launch_bounds__(256) void k_gen_gemm_grouped(const int8_t* __restri
           const float swn = sSw[wn * 64 + b * 32 + l32];
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            acc[a][b][4 * q + j] = __fadd_rn(acc[a][b][4 * q + j], __fmul_rn(__fmul_rn((float)iacc[a][b][4 * q + j], s4[j]), swn));
+            acc[a][b][4 * q + j] = __fmaf_rn(__fmul_rn((float)iacc[a][b][4 * q + j], s4[j]), swn, acc[a][b][4 * q + j]);
         }
       }
     }
@@ -524,7 +536,12 @@ __global__ __launch_bounds__(256) void k_gen_gemm_grouped(const int8_t* __restri
     }
 }
 
-inline dim3 rows_grid(int ld, int rows, int B) { return dim3((ld + 255) / 256, rows, B); }
+// workgroups of 256 threads along a row; of one wave when that would leave the chip short of workgroups
+inline int rows_block(int ld, int rows, int B) { return (long)((ld + 255) / 256) * rows * B >= 2048 ? 256 : 64; }
+inline dim3 rows_grid(int ld, int rows, int B) {
+  const int bs = rows_block(ld, rows, B);
+  return dim3((ld + bs - 1) / bs, rows, B);
+}
 
 // sizes of the approximations after every level of the ragged transform over n tokens
 std::vector<int> ragged_sizes(int n, int levels) {
@@ -669,27 +686,27 @@ constexpr int kPass2d = 3;  // of the 2-D kernels (8 x 8 values per thread)
 template <int NLEV>
 void launch_haar1d_fwd(dim3 grid, hipStream_t st, const void* in, int in_kind, float* apx_out, float* T, int s, int ld, int o, int n_lo,
                        int scaled, int last, const GenNorm& nm) {
-  hipLaunchKernelGGL(k_gen_haar1d_fwd<NLEV>, grid, dim3(256), 0, st, in, in_kind, apx_out, T, s, ld, o, n_lo, scaled, last, nm);
+  hipLaunchKernelGGL(k_gen_haar1d_fwd<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, in, in_kind, apx_out, T, s, ld, o, n_lo, scaled, last, nm);
 }
 template <int NLEV>
 void launch_haar1d_inv(dim3 grid, hipStream_t st, const float* apx_in, const float* S, float* apx_out, void* Y, const float* bias,
                        int y_bf16, int s, int ld, int o, int n_lo, int last) {
-  hipLaunchKernelGGL(k_gen_haar1d_inv<NLEV>, grid, dim3(256), 0, st, apx_in, S, apx_out, Y, bias, y_bf16, s, ld, o, n_lo, last);
+  hipLaunchKernelGGL(k_gen_haar1d_inv<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, apx_in, S, apx_out, Y, bias, y_bf16, s, ld, o, n_lo, last);
 }
 template <int NLEV>
 void launch_haar2d_fwd(dim3 grid, hipStream_t st, const void* in, int in_kind, float* ll_out, float* T, int s, int ld, int gridW, int w_lo,
                        const GenBands& bd, int last, float apx_norm) {
-  hipLaunchKernelGGL(k_gen_haar2d_fwd<NLEV>, grid, dim3(256), 0, st, in, in_kind, ll_out, T, s, ld, gridW, w_lo, bd, last, apx_norm);
+  hipLaunchKernelGGL(k_gen_haar2d_fwd<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, in, in_kind, ll_out, T, s, ld, gridW, w_lo, bd, last, apx_norm);
 }
 template <int NLEV>
 void launch_haar2d_inv(dim3 grid, hipStream_t st, const float* ll_in, int first, const float* S, float* ll_out, void* Y, const float* bias,
                        int y_bf16, int s, int ld, int gridW, int w_lo, const GenBands& bd, int last) {
-  hipLaunchKernelGGL(k_gen_haar2d_inv<NLEV>, grid, dim3(256), 0, st, ll_in, first, S, ll_out, Y, bias, y_bf16, s, ld, gridW, w_lo, bd, last);
+  hipLaunchKernelGGL(k_gen_haar2d_inv<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, ll_in, first, S, ll_out, Y, bias, y_bf16, s, ld, gridW, w_lo, bd, last);
 }
 template <int NLEV>
 void launch_wht(dim3 grid, hipStream_t st, const void* in, int in_kind, float* out, void* Y, int out_kind, const int* inv_perm, float norm,
                 const float* bias, int y_bf16, int s, int ld, int h_lo) {
-  hipLaunchKernelGGL(k_gen_wht<NLEV>, grid, dim3(256), 0, st, in, in_kind, out, Y, out_kind, inv_perm, norm, bias, y_bf16, s, ld, h_lo);
+  hipLaunchKernelGGL(k_gen_wht<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, in, in_kind, out, Y, out_kind, inv_perm, norm, bias, y_bf16, s, ld, h_lo);
 }
 
 // slot of band W of 2-D level l: the final low-low block and the bands of the coarser levels come first
@@ -711,7 +728,7 @@ hipError_t stamp_gen_forward(const stamp_plan* p, const void* X, float* const (&
   float* tmp[2] = {buf[0], buf[1]};
   const bool haar1d = gn.kind == kGenHaarRagged || gn.kind == kGenHaarClassic;
   if (gn.kind == kGenCopy || ((haar1d || gn.kind == kGenHaar2d) && gn.levels == 0)) {
-    hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(256), 0, st, X, buf[0], s, d, g.x_bf16);
+    hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(rows_block(d, s, B)), 0, st, X, buf[0], s, d, g.x_bf16);
     *T_out = buf[0];
     return hipGetLastError();
   }
@@ -772,7 +789,7 @@ hipError_t stamp_gen_forward(const stamp_plan* p, const void* X, float* const (&
     int J = 0;
     while ((1 << J) < s) ++J;
     if (J == 0) {  // one token: the transform is the identity
-      hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(256), 0, st, X, buf[0], s, d, g.x_bf16);
+      hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(rows_block(d, s, B)), 0, st, X, buf[0], s, d, g.x_bf16);
       *T_out = buf[0];
       return hipGetLastError();
     }
@@ -799,7 +816,7 @@ hipError_t stamp_gen_forward(const stamp_plan* p, const void* X, float* const (&
     return hipGetLastError();
   }
   if (gn.kind == kGenDct) {
-    hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(256), 0, st, X, buf[0], s, d, g.x_bf16);
+    hipLaunchKernelGGL(k_gen_cast, rows_grid(d, s, B), dim3(rows_block(d, s, B)), 0, st, X, buf[0], s, d, g.x_bf16);
     hipLaunchKernelGGL(k_gen_dct, dim3((d + 63) / 64, (s + 63) / 64, B), dim3(256), 0, st, p->dct_dev, 0, buf[0], T, s, d);
     return hipGetLastError();
   }
@@ -816,7 +833,7 @@ hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int nc
   float* tmp[2] = {buf[1], buf[2]};
   const bool haar1d = gn.kind == kGenHaarRagged || gn.kind == kGenHaarClassic;
   if (gn.kind == kGenCopy || ((haar1d || gn.kind == kGenHaar2d) && gn.levels == 0)) {
-    hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(256), 0, st, S, bias, Y, s, ld, g.y_bf16);
+    hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(rows_block(ld, s, B)), 0, st, S, bias, Y, s, ld, g.y_bf16);
     return hipGetLastError();
   }
   if (haar1d) {
@@ -871,7 +888,7 @@ hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int nc
     int J = 0;
     while ((1 << J) < s) ++J;
     if (J == 0) {
-      hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(256), 0, st, S, bias, Y, s, ld, g.y_bf16);
+      hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(rows_block(ld, s, B)), 0, st, S, bias, Y, s, ld, g.y_bf16);
       return hipGetLastError();
     }
     const float* in = S;
@@ -897,7 +914,7 @@ hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int nc
   }
   if (gn.kind == kGenDct) {
     hipLaunchKernelGGL(k_gen_dct, dim3((ld + 63) / 64, (s + 63) / 64, B), dim3(256), 0, st, p->dct_dev, 1, S, tmp[0], s, ld);
-    hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(256), 0, st, tmp[0], bias, Y, s, ld, g.y_bf16);
+    hipLaunchKernelGGL(k_gen_store_y, rows_grid(ld, s, B), dim3(rows_block(ld, s, B)), 0, st, tmp[0], bias, Y, s, ld, g.y_bf16);
     return hipGetLastError();
   }
   return hipErrorInvalidValue;
@@ -920,13 +937,13 @@ hipError_t stamp_launch_gemm_grouped(const stamp_plan* p, const int8_t* codes, c
 hipError_t stamp_launch_merge_hi(const stamp_plan* p, const float* ythi, int nparts, float* Yt, hipStream_t st) {
   const StampGeom& g = p->geom;
   if (g.k == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_gen_merge_hi, rows_grid(g.N, g.k, g.B), dim3(256), 0, st, ythi, nparts, (size_t)g.B * g.k * (size_t)g.N, Yt, g.s,
+  hipLaunchKernelGGL(k_gen_merge_hi, rows_grid(g.N, g.k, g.B), dim3(rows_block(g.N, g.k, g.B)), 0, st, ythi, nparts, (size_t)g.B * g.k * (size_t)g.N, Yt, g.s,
                      g.N, g.k);
   return hipGetLastError();
 }
 
 hipError_t stamp_launch_add_ell_bias(const stamp_plan* p, float* Yt, hipStream_t st) {
   const StampGeom& g = p->geom;
-  hipLaunchKernelGGL(k_gen_add_ell_bias, rows_grid(g.N, g.s, g.B), dim3(256), 0, st, Yt, p->ell_dev, p->bias_dev, g.s, g.N);
+  hipLaunchKernelGGL(k_gen_add_ell_bias, rows_grid(g.N, g.s, g.B), dim3(rows_block(g.N, g.s, g.B)), 0, st, Yt, p->ell_dev, p->bias_dev, g.s, g.N);
   return hipGetLastError();
 }

@@ -146,6 +146,27 @@ def test_int_gemm_against_triple_loop():
     assert abs(int(acc[0, 0])) < 2 ** 24
 
 
+def test_eight_bit_rows_fp32_conversion_bound():
+    """The de-quantization converts the integer sum to fp32: exact below 2^24.  With 8-bit codes of magnitude up to
+    128 (the stored form of the asymmetric code 0) against weight codes of magnitude 7 the worst case reaches
+    128 * 7 * d_in, so the conversion is exact for every input up to d_in = 18720 (the bound include/stamp.h states);
+    the oracle refuses a sum beyond it instead of rounding silently."""
+    d_ok = 18720
+    q = np.full((1, d_ok), -128, dtype=np.int16)
+    qw = np.full((d_ok, 2), 7, dtype=np.int8); qw[:, 1] = -7
+    acc = so.int_gemm(q, qw)
+    assert acc[0, 0] == -128 * 7 * d_ok and acc[0, 1] == 128 * 7 * d_ok
+    assert abs(int(acc[0, 0])) < 2 ** 24 and float(np.float32(acc[0, 0])) == float(acc[0, 0])
+    d_bad = 18752   # the next multiple of 32 whose worst case passes 2^24
+    assert 128 * 7 * d_bad > 2 ** 24
+    with pytest.raises(AssertionError, match="exact fp32 integer range"):
+        so.int_gemm(np.full((1, d_bad), -128, dtype=np.int16), np.full((d_bad, 1), 7, dtype=np.int8))
+    # symmetric codes stop at 127: exact up to d_in = 18848
+    assert 127 * 7 * 18848 < 2 ** 24 < 127 * 7 * 18880
+    # an odd sum just above 2^24 is what the conversion would round
+    assert float(np.float32(2 ** 24 + 1)) != float(2 ** 24 + 1)
+
+
 def test_round_to_bf16():
     y = np.array([1.0, 1.00390625, 1.01171875, -3.140625, 1.0 + 2.0 ** -9, 0.0], dtype=np.float32)
     r = so.round_to_bf16(y)
