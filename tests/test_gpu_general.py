@@ -160,3 +160,101 @@ def test_full_size_llm_first_token_left_out():
                                      np.arange(0, w.d_out, 128) + rng.integers(0, 128, size=(w.d_out + 127) // 128)]))
     cols = cols[cols < w.d_out]
     tl.full_case(w, with_bias=True, y_dtype="bf16", cols=cols, check_unfused=False, also_f32_out=True)
+
+
+def _random_general(seed: int) -> Workload:
+    """A valid general-path plan: transform, length, depth, quantizer form and the three switches drawn at random."""
+    rng = np.random.default_rng(7000 + seed)
+    kind = str(rng.choice(["ragged", "skip", "wht", "dct", "haar_pow2", "haar2d", "identity"]))
+    kw = dict(batch=int(rng.integers(1, 4)), d_in=int(rng.integers(1, 9)) * 64, d_out=int(rng.integers(1, 300)),
+              seed=8000 + seed, x_dtype=str(rng.choice(["bf16", "f32"])), n_outlier_channels=int(rng.integers(0, 4)),
+              outlier_scale=25.0, mean_shift=float(rng.choice([0.0, 0.7])))
+    group = 64 if rng.random() < 0.35 else 0
+    if not group:
+        kw["act_quant"] = str(rng.choice(["sym", "asym"]))
+    tbias = "transformed" if rng.random() < 0.4 else "after"
+    if kind == "ragged":
+        s = int(rng.integers(3, 700))
+        if s & (s - 1) == 0:
+            s += 1
+        w = dict(xform="haar1d", seq_len=s, levels=int(rng.integers(0, so.max_ragged_levels(s) + 1)))
+    elif kind == "skip":
+        s = int(rng.integers(3, 700))
+        w = dict(xform="haar1d", seq_len=s, levels=int(rng.integers(0, so.max_ragged_levels(s - 1) + 1)), skip_first=True,
+                 first_token_scale=60.0)
+    elif kind == "wht":
+        w = dict(xform="wht", seq_len=1 << int(rng.integers(1, 11)), levels=0)
+    elif kind == "dct":
+        w = dict(xform="dct", seq_len=int(rng.integers(2, 300)), levels=0)
+    elif kind == "haar_pow2":   # a plan the fast path would take, sent to the general path by a switch
+        J = int(rng.integers(3, 10))
+        w = dict(xform="haar1d", seq_len=1 << J, levels=int(rng.integers(1, J + 1)))
+        if not group:
+            tbias = "transformed"
+    elif kind == "haar2d":
+        lg = int(rng.integers(2, 6))
+        w = dict(xform="haar2d", seq_len=1 << (2 * lg), grid_h=1 << lg, grid_w=1 << lg, levels=int(rng.integers(1, lg + 1)),
+                 corr_len=4.0)
+        if not group:
+            tbias = "transformed"
+    else:
+        w = dict(xform="identity", seq_len=int(rng.integers(1, 300)), levels=0)
+        if not group:
+            tbias = "transformed"
+    s = w["seq_len"]
+    k_hi = int(rng.integers(0, min(s, 64) + 1))
+    return _wl(f"rndg{seed}_{kind}", k_hi=k_hi, group_size=group, bias_mode=tbias, **w, **kw)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_general_plans(seed):
+    """Seeded sweep over the general path: every plan it accepts meets the same bars as the fast path's."""
+    w = _random_general(seed)
+    rng = np.random.default_rng(9000 + seed)
+    y_dtype = str(rng.choice(["f32", "bf16"]))
+    if w.group_size:
+        tl.grouped_case(w, with_bias=True, y_dtype=y_dtype)
+    else:
+        r = tl.full_case(w, with_bias=True, y_dtype=y_dtype, check_unfused=False)
+        assert r["code_mismatches"] == 0
+
+
+def test_general_path_under_hip_graph_capture_and_static_scratch():
+    """The general path only enqueues kernels (no allocation, copy or memset): it can be captured into a HIP graph,
+    every replay reproduces the eager result bit for bit, and stamp_linear_forward_static runs it from the
+    library's static scratch array."""
+    import torch
+    import paper_2510_26771_amd as st
+    for w in (_wl("graph_skip", batch=2, seq_len=300, levels=4, skip_first=True, d_in=160, d_out=300, seed=81),
+              _wl("graph_g64_2d", seq_len=256, xform="haar2d", levels=3, grid_h=16, grid_w=16, k_hi=4, d_in=128,
+                  d_out=130, group_size=64, seed=82),
+              _wl("graph_wht_tb", seq_len=128, xform="wht", levels=0, bias_mode="transformed", act_quant="asym", seed=83)):
+        inp = make_inputs(w, with_bias=True)
+        plan = st.StampPlan(tl.plan_desc_for(w, "bf16"), torch.from_numpy(inp["W"]).cuda(),
+                            torch.from_numpy(inp["bias"]).cuda())
+        X = tl.to_device_x(inp, w)
+        ws = plan.alloc_workspace()
+        Y_eager = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=torch.int16, device="cuda")
+        plan.linear_forward(X, Y_eager, ws)
+        torch.cuda.synchronize()
+        Y = torch.zeros_like(Y_eager)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            plan.linear_forward(X, Y, ws)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                plan.linear_forward(X, Y, ws)
+        torch.cuda.current_stream().wait_stream(side)
+        for it in range(3):
+            Y.fill_(-1)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Y, Y_eager), f"{w.name}: replay {it} differs from the eager result"
+        Y.fill_(-1)
+        plan.linear_forward_static(X, Y)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y_eager), f"{w.name}: static scratch and caller workspace disagree"
+        plan.destroy()
