@@ -471,20 +471,29 @@ __global__ __launch_bounds__(256) void k_gen_gemm_grouped(const int8_t* __restri
   const int srow = tid >> 1, shalf = tid & 1;
   const int8_t* gA = A + (size_t)min(m0 + srow, M - 1) * d + shalf * 32;
   const int8_t* gB = Wq + (size_t)(n0 + srow) * d + shalf * 32;  // Npad rows exist
+  // the next group's operands and scales travel from global memory to registers while the current group is
+  // multiplied and rescaled
+  const float* gS = tid < 128 ? sa + (size_t)min(m0 + tid, M - 1) * G : swg + n0 + (tid - 128);
+  const size_t sstep = tid < 128 ? 1 : (size_t)Npad;
+  uint4 a0 = *reinterpret_cast<const uint4*>(gA), a1 = *reinterpret_cast<const uint4*>(gA + 16);
+  uint4 b0 = *reinterpret_cast<const uint4*>(gB), b1 = *reinterpret_cast<const uint4*>(gB + 16);
+  float fs = gS[0];
   for (int g = 0; g < G; ++g) {
-    const uint4 a0 = *reinterpret_cast<const uint4*>(gA + g * 64), a1 = *reinterpret_cast<const uint4*>(gA + g * 64 + 16);
-    const uint4 b0 = *reinterpret_cast<const uint4*>(gB + g * 64), b1 = *reinterpret_cast<const uint4*>(gB + g * 64 + 16);
-    float fsa = 0.0f, fsw = 0.0f;
-    if (tid < 128) fsa = sa[(size_t)min(m0 + tid, M - 1) * G + g];
-    else fsw = swg[(size_t)g * Npad + n0 + (tid - 128)];
     __syncthreads();  // the previous group's fragments have been read
     *reinterpret_cast<uint4*>(sA + srow * kGPitch + shalf * 32) = a0;
     *reinterpret_cast<uint4*>(sA + srow * kGPitch + shalf * 32 + 16) = a1;
     *reinterpret_cast<uint4*>(sB + srow * kGPitch + shalf * 32) = b0;
     *reinterpret_cast<uint4*>(sB + srow * kGPitch + shalf * 32 + 16) = b1;
-    if (tid < 128) sSa[tid] = fsa;
-    else sSw[tid - 128] = fsw;
+    if (tid < 128) sSa[tid] = fs;
+    else sSw[tid - 128] = fs;
     __syncthreads();
+    if (g + 1 < G) {
+      a0 = *reinterpret_cast<const uint4*>(gA + (g + 1) * 64);
+      a1 = *reinterpret_cast<const uint4*>(gA + (g + 1) * 64 + 16);
+      b0 = *reinterpret_cast<const uint4*>(gB + (g + 1) * 64);
+      b1 = *reinterpret_cast<const uint4*>(gB + (g + 1) * 64 + 16);
+      fs = gS[(size_t)(g + 1) * sstep];
+    }
     v16i iacc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -681,7 +690,7 @@ hipError_t stamp_gen_plan_tables(stamp_plan* p, const float* W, hipStream_t st) 
 // ---------------------------------------------------------------------------------------------
 namespace {
 constexpr int kPass1d = 5;  // levels per pass of the 1-D kernels (32 values per thread)
-constexpr int kPass2d = 3;  // of the 2-D kernels (8 x 8 values per thread)
+constexpr int kPass2d = 2;  // of the 2-D kernels (4 x 4 values per thread)
 
 template <int NLEV>
 void launch_haar1d_fwd(dim3 grid, hipStream_t st, const void* in, int in_kind, float* apx_out, float* T, int s, int ld, int o, int n_lo,
