@@ -19,6 +19,8 @@
 // take as long as its MFMAs).  Per tile and K step, activations: 8 blocks = 24 KB, weights: 4 blocks = 12 KB
 // per 128 columns.  The global image equals the LDS image, so a K step is staged by plain asynchronous
 // 16-byte copies.
+#include <type_traits>
+
 #include "stamp_gemm_common.h"
 #include "stamp_epilogue_reg.h"
 
@@ -218,8 +220,9 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   const uint32_t adrA0 = (uint32_t)((wm * 4) * kBlock6 + lane * 16);
   const uint32_t adrB0 = (uint32_t)(kStageA6 + (wn >> 1) * kStageB6 + ((wn & 1) * 2) * kBlock6 + lane * 16);
 
+  // ---- prologue: stages 0 and 1 requested, landed and published by a barrier; stage 2 requested ----
   request_next();
-  bool prev_requested = request_next();  // was a request issued one step ago (it may still be in flight)
+  request_next();
   {
     int tm0, tn0;
     tile_of_sid(first + local, mt, nt, tm0, tn0);
@@ -227,10 +230,37 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   }
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  int landed = 2;  // K steps from here on whose loads are known to have landed (no wait needed)
+  bool prev_requested = request_next();  // was a request issued one step ago (it may still be in flight)
+  int landed = 1;  // steps from here on whose loads are known to have landed (their barrier needs no wait)
   int stg = 0;     // stage of the step about to be multiplied
   int rbuf = 0;    // row-info buffer of the current tile
+
+  // Fragment registers.  A lane's 48 bytes of one 32-row block and K step are the two 24-byte MFMA operands of the
+  // step's halves, read as three 16-byte parts.  The parts of a fragment must land in 12 CONSECUTIVE registers (the
+  // first operand is registers 0..5, the second 6..11), which the register allocator does not arrange for separate
+  // asm outputs (it copies parts into fresh tuples and runs out of registers); the fragments therefore live in fixed
+  // registers v184..v255: two activation sets (block mi + 1 is read while block mi is multiplied) and the weights'
+  // NIW = 2 blocks double-buffered from step to step.
+  static_assert(NIW == 2, "fixed fragment registers are laid out for two weight blocks per wave");
+  struct Frag {
+    u6 h0, h1;
+  };
+#define STAMP_RD3(f, H0, H1, P0, P1, P2, base, off)                                                                   \
+  asm volatile("ds_read_b128 " P0 ", %2 offset:%3\n\tds_read_b128 " P1 ", %2 offset:%4\n\tds_read_b128 " P2 ", %2 offset:%5" \
+               : "=&{" H0 "}"(f.h0), "=&{" H1 "}"(f.h1)                                                               \
+               : "v"(base), "n"(off), "n"((off) + kPart), "n"((off) + 2 * kPart))
+#define STAMP_RD_AS0(base, off) STAMP_RD3(As0, "v[184:189]", "v[190:195]", "v[184:187]", "v[188:191]", "v[192:195]", base, off)
+#define STAMP_RD_AS1(base, off) STAMP_RD3(As1, "v[196:201]", "v[202:207]", "v[196:199]", "v[200:203]", "v[204:207]", base, off)
+#define STAMP_RD_B00(base, off) STAMP_RD3(B00, "v[208:213]", "v[214:219]", "v[208:211]", "v[212:215]", "v[216:219]", base, off)
+#define STAMP_RD_B01(base, off) STAMP_RD3(B01, "v[220:225]", "v[226:231]", "v[220:223]", "v[224:227]", "v[228:231]", base, off)
+#define STAMP_RD_B10(base, off) STAMP_RD3(B10, "v[232:237]", "v[238:243]", "v[232:235]", "v[236:239]", "v[240:243]", base, off)
+#define STAMP_RD_B11(base, off) STAMP_RD3(B11, "v[244:249]", "v[250:255]", "v[244:247]", "v[248:251]", "v[252:255]", base, off)
+  // a wait names the fragments it covers (same registers in and out), which keeps their MFMAs behind it
+#define STAMP_WAIT1(cnt, f, H0, H1) asm volatile("s_waitcnt lgkmcnt(" #cnt ")" : "={" H0 "}"(f.h0), "={" H1 "}"(f.h1) : "0"(f.h0), "1"(f.h1))
+#define STAMP_WAIT_AS0(cnt) STAMP_WAIT1(cnt, As0, "v[184:189]", "v[190:195]")
+#define STAMP_WAIT_AS1(cnt) STAMP_WAIT1(cnt, As1, "v[196:201]", "v[202:207]")
 
   for (int pos = local; pos < count; pos += wx) {
     int tm, tn;
@@ -246,17 +276,55 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // Step kt: this wave's loads of step kt have landed (those of the step after it may still be in flight);
-    // workgroup barrier (all of step kt is visible and the stage of step kt-1 is free); request the step two
-    // ahead into that stage; then the two MFMA halves of the step.
-    //
-    // The step's fragments (per MFMA half k: NIW of the weights, 4 of the activations) arrive as (4 + NIW) x 3
-    // 16-byte reads: parts 0 and 1 hold the first half's fragment (6 registers) and the first 2 registers of
-    // the second half's, part 2 the rest.  The reads are written out by hand (outputs of a two-read statement
-    // are early-clobber: the address register must outlive the first read) and so are the waits: the part-2
-    // reads stay in flight under the first half's MFMAs.  A wait names the registers it covers, which keeps
-    // the MFMAs behind it.
-    auto step = [&]() __attribute__((always_inline)) {
+    Frag As0, As1, B00, B01, B10, B11;  // per tile: no fragment is carried across the epilogue
+    // the four MFMAs of activation block mi: both halves against both weight blocks
+    auto mfma4 = [&](const Frag& A, const Frag& W0, const Frag& W1, auto mi_tag) __attribute__((always_inline)) {
+      constexpr int mi = decltype(mi_tag)::value;
+      acc[mi][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)A.h0), widen((v6i)W0.h0), acc[mi][0], 2, 2, 0, 0, 0, 0);
+      acc[mi][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)A.h0), widen((v6i)W1.h0), acc[mi][1], 2, 2, 0, 0, 0, 0);
+      acc[mi][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)A.h1), widen((v6i)W0.h1), acc[mi][0], 2, 2, 0, 0, 0, 0);
+      acc[mi][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)A.h1), widen((v6i)W1.h1), acc[mi][1], 2, 2, 0, 0, 0, 0);
+    };
+
+    // Step kt (pb = 0: weights in B00, B01, the next step's go to B10, B11; pb = 1: the other way round).  On entry
+    // the reads of the step's weights and of activation block 0 have been issued (by the head of the tile or by the
+    // step before).  Block 1 is requested, block 0 multiplied, block 2 requested, block 1 multiplied, ...: the LDS
+    // reads of a block fly under the MFMAs of the block before.  After block 2 every read of this stage has
+    // returned: the wave waits for its own loads of the NEXT step's stage (the step after that may still be in
+    // flight), meets the others at the workgroup barrier (next stage visible, this stage free), requests the step
+    // three ahead into this stage, issues the reads of the next step's block 0 and weights, and multiplies block 3
+    // under them.  One barrier per step, none between a read and its use.
+    auto step = [&](auto pb_tag) __attribute__((always_inline)) {
+      constexpr int pb = decltype(pb_tag)::value;
+      const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
+      __builtin_amdgcn_sched_barrier(0);
+      STAMP_RD_AS1(sa + adrA0, 1 * kBlock6);
+      if constexpr (pb == 0) {
+        asm volatile("s_waitcnt lgkmcnt(3)"
+                     : "={v[184:189]}"(As0.h0), "={v[190:195]}"(As0.h1), "={v[208:213]}"(B00.h0), "={v[214:219]}"(B00.h1),
+                       "={v[220:225]}"(B01.h0), "={v[226:231]}"(B01.h1)
+                     : "0"(As0.h0), "1"(As0.h1), "2"(B00.h0), "3"(B00.h1), "4"(B01.h0), "5"(B01.h1));
+        mfma4(As0, B00, B01, std::integral_constant<int, 0>{});
+      } else {
+        asm volatile("s_waitcnt lgkmcnt(3)"
+                     : "={v[184:189]}"(As0.h0), "={v[190:195]}"(As0.h1), "={v[232:237]}"(B10.h0), "={v[238:243]}"(B10.h1),
+                       "={v[244:249]}"(B11.h0), "={v[250:255]}"(B11.h1)
+                     : "0"(As0.h0), "1"(As0.h1), "2"(B10.h0), "3"(B10.h1), "4"(B11.h0), "5"(B11.h1));
+        mfma4(As0, B10, B11, std::integral_constant<int, 0>{});
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      STAMP_RD_AS0(sa + adrA0, 2 * kBlock6);
+      STAMP_WAIT_AS1(3);
+      if constexpr (pb == 0) mfma4(As1, B00, B01, std::integral_constant<int, 1>{});
+      else mfma4(As1, B10, B11, std::integral_constant<int, 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+      STAMP_RD_AS1(sa + adrA0, 3 * kBlock6);
+      STAMP_WAIT_AS0(3);
+      if constexpr (pb == 0) mfma4(As0, B00, B01, std::integral_constant<int, 2>{});
+      else mfma4(As0, B10, B11, std::integral_constant<int, 2>{});
+      __builtin_amdgcn_sched_barrier(0);
+      STAMP_WAIT_AS1(0);
+      // ---- the next step's stage ----
       asm volatile("" ::: "memory");
       if (landed > 0) {
         --landed;
@@ -268,49 +336,40 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       asm volatile("" ::: "memory");
       prev_requested = request_next();
       __builtin_amdgcn_sched_barrier(0);
-      const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
-      u4 a0[4], a1[4], a2[4], b0[NIW], b1[NIW], b2[NIW];
-#pragma unroll
-      for (int ni = 0; ni < NIW; ++ni)
-        asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
-                     : "=&v"(b0[ni]), "=&v"(b1[ni]) : "v"(sa + adrB0), "n"(ni * kBlock6), "n"(ni * kBlock6 + kPart));
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-        asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
-                     : "=&v"(a0[mi]), "=&v"(a1[mi]) : "v"(sa + adrA0), "n"(mi * kBlock6), "n"(mi * kBlock6 + kPart));
-#pragma unroll
-      for (int ni = 0; ni < NIW; ++ni)
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(b2[ni]) : "v"(sa + adrB0), "n"(ni * kBlock6 + 2 * kPart));
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a2[mi]) : "v"(sa + adrA0), "n"(mi * kBlock6 + 2 * kPart));
-      asm volatile("s_waitcnt lgkmcnt(6)"
-                   : "+v"(a0[0]), "+v"(a0[1]), "+v"(a0[2]), "+v"(a0[3]), "+v"(b0[0]), "+v"(b0[1]),
-                     "+v"(a1[0]), "+v"(a1[1]), "+v"(a1[2]), "+v"(a1[3]), "+v"(b1[0]), "+v"(b1[1]));
-      v6i fa[2][4], fb[2][NIW];
-#pragma unroll
-      for (int ni = 0; ni < NIW; ++ni) fb[0][ni] = (v6i)(u6)__builtin_shufflevector(b0[ni], b1[ni], 0, 1, 2, 3, 4, 5);
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi) fa[0][mi] = (v6i)(u6)__builtin_shufflevector(a0[mi], a1[mi], 0, 1, 2, 3, 4, 5);
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NIW; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[0][mi]), widen(fb[0][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a2[0]), "+v"(a2[1]), "+v"(a2[2]), "+v"(a2[3]), "+v"(b2[0]), "+v"(b2[1]));
-#pragma unroll
-      for (int ni = 0; ni < NIW; ++ni) fb[1][ni] = (v6i)(u6)__builtin_shufflevector(b1[ni], b2[ni], 2, 3, 4, 5, 6, 7);
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi) fa[1][mi] = (v6i)(u6)__builtin_shufflevector(a1[mi], a2[mi], 2, 3, 4, 5, 6, 7);
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NIW; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(fa[1][mi]), widen(fb[1][ni]), acc[mi][ni], 2, 2, 0, 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
       stg = (stg == kNumStage6 - 1) ? 0 : stg + 1;
+      {
+        // (after the tile's last step these reads fetch the next tile's first fragments, which the epilogue's
+        // registers cannot keep: they are dropped and read again by the next head)
+        const uint32_t sn = lds0 + (uint32_t)(stg * kStage6);
+        STAMP_RD_AS0(sn + adrA0, 0);
+        if constexpr (pb == 0) {
+          STAMP_RD_B10(sn + adrB0, 0);
+          STAMP_RD_B11(sn + adrB0, kBlock6);
+        } else {
+          STAMP_RD_B00(sn + adrB0, 0);
+          STAMP_RD_B01(sn + adrB0, kBlock6);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (pb == 0) mfma4(As1, B00, B01, std::integral_constant<int, 3>{});
+      else mfma4(As1, B10, B11, std::integral_constant<int, 3>{});
+      __builtin_amdgcn_sched_barrier(0);
     };
-    for (int kt = 0; kt < KT; ++kt) step();
+    // head of the tile: the barrier that published its first stage lies behind (prologue, or the last step of the
+    // tile before)
+    {
+      const uint32_t sh = lds0 + (uint32_t)(stg * kStage6);
+      STAMP_RD_AS0(sh + adrA0, 0);
+      STAMP_RD_B00(sh + adrB0, 0);
+      STAMP_RD_B01(sh + adrB0, kBlock6);
+    }
+    for (int kt = 0; kt + 1 < KT; kt += 2) {
+      step(std::integral_constant<int, 0>{});
+      step(std::integral_constant<int, 1>{});
+    }
+    if (KT & 1) step(std::integral_constant<int, 0>{});
+    // the last step's look-ahead reads must have returned before their registers are used for anything else
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
     // Everything requested so far (the next tile's first two steps included) must have landed before the
     // epilogue issues its stores: the counter retires in order, so a later wait for a load would also wait for
