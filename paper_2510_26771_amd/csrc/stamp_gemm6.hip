@@ -257,7 +257,25 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
 #define STAMP_RD_B01(base, off) STAMP_RD3(B01, "v[220:225]", "v[226:231]", "v[220:223]", "v[224:227]", "v[228:231]", base, off)
 #define STAMP_RD_B10(base, off) STAMP_RD3(B10, "v[232:237]", "v[238:243]", "v[232:235]", "v[236:239]", "v[240:243]", base, off)
 #define STAMP_RD_B11(base, off) STAMP_RD3(B11, "v[244:249]", "v[250:255]", "v[244:247]", "v[248:251]", "v[252:255]", base, off)
+  // activation block 0 and the two weight blocks of a step in one statement, parts 0 and 1 of all three first (the
+  // first MFMA half's operands), then the parts 2
+#define STAMP_RD9(fa, fb0, fb1, AH0, AH1, B0H0, B0H1, B1H0, B1H1, A0, A1, A2, B00_, B01_, B02_, B10_, B11_, B12_, basea, baseb)         \
+  asm volatile("ds_read_b128 " A0 ", %6 offset:0\n\tds_read_b128 " A1 ", %6 offset:%8\n\t"                                          \
+               "ds_read_b128 " B00_ ", %7 offset:0\n\tds_read_b128 " B01_ ", %7 offset:%8\n\t"                                      \
+               "ds_read_b128 " B10_ ", %7 offset:%10\n\tds_read_b128 " B11_ ", %7 offset:%11\n\t"                                   \
+               "ds_read_b128 " A2 ", %6 offset:%9\n\tds_read_b128 " B02_ ", %7 offset:%9\n\tds_read_b128 " B12_ ", %7 offset:%12"   \
+               : "=&{" AH0 "}"(fa.h0), "=&{" AH1 "}"(fa.h1), "=&{" B0H0 "}"(fb0.h0), "=&{" B0H1 "}"(fb0.h1), "=&{" B1H0 "}"(fb1.h0),  \
+                 "=&{" B1H1 "}"(fb1.h1)                                                                                              \
+               : "v"(basea), "v"(baseb), "n"(kPart), "n"(2 * kPart), "n"(kBlock6), "n"(kBlock6 + kPart), "n"(kBlock6 + 2 * kPart))
+#define STAMP_RD9_PB0(basea, baseb)                                                                                                  \
+  STAMP_RD9(As0, B00, B01, "v[184:189]", "v[190:195]", "v[208:213]", "v[214:219]", "v[220:225]", "v[226:231]", "v[184:187]", "v[188:191]", \
+            "v[192:195]", "v[208:211]", "v[212:215]", "v[216:219]", "v[220:223]", "v[224:227]", "v[228:231]", basea, baseb)
+#define STAMP_RD9_PB1(basea, baseb)                                                                                                  \
+  STAMP_RD9(As0, B10, B11, "v[184:189]", "v[190:195]", "v[232:237]", "v[238:243]", "v[244:249]", "v[250:255]", "v[184:187]", "v[188:191]", \
+            "v[192:195]", "v[232:235]", "v[236:239]", "v[240:243]", "v[244:247]", "v[248:251]", "v[252:255]", basea, baseb)
   // a wait names the fragments it covers (same registers in and out), which keeps their MFMAs behind it
+#define STAMP_WAIT2(cnt, x, XR, y, YR) asm volatile("s_waitcnt lgkmcnt(" #cnt ")" : "={" XR "}"(x), "={" YR "}"(y) : "0"(x), "1"(y))
+#define STAMP_WAITH(cnt, x, XR) asm volatile("s_waitcnt lgkmcnt(" #cnt ")" : "={" XR "}"(x) : "0"(x))
 #define STAMP_WAIT1(cnt, f, H0, H1) asm volatile("s_waitcnt lgkmcnt(" #cnt ")" : "={" H0 "}"(f.h0), "={" H1 "}"(f.h1) : "0"(f.h0), "1"(f.h1))
 #define STAMP_WAIT_AS0(cnt) STAMP_WAIT1(cnt, As0, "v[184:189]", "v[190:195]")
 #define STAMP_WAIT_AS1(cnt) STAMP_WAIT1(cnt, As1, "v[196:201]", "v[202:207]")
@@ -299,18 +317,31 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       const uint32_t sa = lds0 + (uint32_t)(stg * kStage6);
       __builtin_amdgcn_sched_barrier(0);
       STAMP_RD_AS1(sa + adrA0, 1 * kBlock6);
+      // block 0: of the 12 reads in flight the first 4 feed the first MFMA, 6 the second, 8 the third, 9 the fourth
       if constexpr (pb == 0) {
-        asm volatile("s_waitcnt lgkmcnt(3)"
-                     : "={v[184:189]}"(As0.h0), "={v[190:195]}"(As0.h1), "={v[208:213]}"(B00.h0), "={v[214:219]}"(B00.h1),
-                       "={v[220:225]}"(B01.h0), "={v[226:231]}"(B01.h1)
-                     : "0"(As0.h0), "1"(As0.h1), "2"(B00.h0), "3"(B00.h1), "4"(B01.h0), "5"(B01.h1));
-        mfma4(As0, B00, B01, std::integral_constant<int, 0>{});
+        STAMP_WAIT2(8, As0.h0, "v[184:189]", B00.h0, "v[208:213]");
+        acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B00.h0), acc[0][0], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        STAMP_WAITH(6, B01.h0, "v[220:225]");
+        acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B01.h0), acc[0][1], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        STAMP_WAIT2(4, As0.h1, "v[190:195]", B00.h1, "v[214:219]");
+        acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h1), widen((v6i)B00.h1), acc[0][0], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        STAMP_WAITH(3, B01.h1, "v[226:231]");
+        acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h1), widen((v6i)B01.h1), acc[0][1], 2, 2, 0, 0, 0, 0);
       } else {
-        asm volatile("s_waitcnt lgkmcnt(3)"
-                     : "={v[184:189]}"(As0.h0), "={v[190:195]}"(As0.h1), "={v[232:237]}"(B10.h0), "={v[238:243]}"(B10.h1),
-                       "={v[244:249]}"(B11.h0), "={v[250:255]}"(B11.h1)
-                     : "0"(As0.h0), "1"(As0.h1), "2"(B10.h0), "3"(B10.h1), "4"(B11.h0), "5"(B11.h1));
-        mfma4(As0, B10, B11, std::integral_constant<int, 0>{});
+        STAMP_WAIT2(8, As0.h0, "v[184:189]", B10.h0, "v[232:237]");
+        acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B10.h0), acc[0][0], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        STAMP_WAITH(6, B11.h0, "v[244:249]");
+        acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B11.h0), acc[0][1], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        STAMP_WAIT2(4, As0.h1, "v[190:195]", B10.h1, "v[238:243]");
+        acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h1), widen((v6i)B10.h1), acc[0][0], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        STAMP_WAITH(3, B11.h1, "v[250:255]");
+        acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h1), widen((v6i)B11.h1), acc[0][1], 2, 2, 0, 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
       STAMP_RD_AS0(sa + adrA0, 2 * kBlock6);
@@ -341,14 +372,8 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
         // (after the tile's last step these reads fetch the next tile's first fragments, which the epilogue's
         // registers cannot keep: they are dropped and read again by the next head)
         const uint32_t sn = lds0 + (uint32_t)(stg * kStage6);
-        STAMP_RD_AS0(sn + adrA0, 0);
-        if constexpr (pb == 0) {
-          STAMP_RD_B10(sn + adrB0, 0);
-          STAMP_RD_B11(sn + adrB0, kBlock6);
-        } else {
-          STAMP_RD_B00(sn + adrB0, 0);
-          STAMP_RD_B01(sn + adrB0, kBlock6);
-        }
+        if constexpr (pb == 0) STAMP_RD9_PB1(sn + adrA0, sn + adrB0);
+        else STAMP_RD9_PB0(sn + adrA0, sn + adrB0);
       }
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (pb == 0) mfma4(As1, B00, B01, std::integral_constant<int, 3>{});
@@ -359,9 +384,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     // tile before)
     {
       const uint32_t sh = lds0 + (uint32_t)(stg * kStage6);
-      STAMP_RD_AS0(sh + adrA0, 0);
-      STAMP_RD_B00(sh + adrB0, 0);
-      STAMP_RD_B01(sh + adrB0, kBlock6);
+      STAMP_RD9_PB0(sh + adrA0, sh + adrB0);
     }
     for (int kt = 0; kt + 1 < KT; kt += 2) {
       step(std::integral_constant<int, 0>{});
@@ -371,12 +394,10 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     // the last step's look-ahead reads must have returned before their registers are used for anything else
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
-    // Everything requested so far (the next tile's first two steps included) must have landed before the
-    // epilogue issues its stores: the counter retires in order, so a later wait for a load would also wait for
-    // every store before it.  After the epilogue the next two steps therefore need no wait.
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    asm volatile("" ::: "memory");
+    // Everything requested so far (the next tile's first steps included) must have landed before the epilogue issues
+    // its stores: the counter retires in order, so a later wait for a load would also wait for every store before
+    // it.  The epilogue waits for that itself, after its lane swaps (the plain modes: before they start); after it
+    // the next two steps therefore need no wait.
     landed = 2;
     // Per-lane values of the epilogue are derived from an opaque copy of the lane number, so that they are
     // computed here, once per tile, instead of being carried in registers across the main loop (which has none
