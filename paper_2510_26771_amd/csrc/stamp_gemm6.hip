@@ -189,23 +189,20 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     rqB = a.Bq + (size_t)(2 * tn_) * KT * kStageB6;
   };
   rq_tile();
-  // requests the next K step of the walk into the next stage of the ring; false when the walk is over
-  auto request_next = [&]() -> bool {
-    if (rq_pos >= count) return false;
-    uint8_t* so_ = smem + rq_stg * kStage6 + wave * 1024;
-    const uint8_t* sa_ = rqA + (size_t)rq_kt * kStageA6;
-#pragma unroll
-    for (int i = 0; i < nA; ++i)
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sa_ + i * (NT * 16) + off16),
-                                       (void __attribute__((address_space(3)))*)(so_ + i * (NT * 16)), 16, 0, 0);
-#pragma unroll
-    for (int i = 0; i < nB; ++i) {
-      // chunk i * NT + tid of the 1536: column tile 1 from chunk 768 on (a whole number of waves)
-      const bool half = (i * NT + wave * 64) >= 768;
-      const uint8_t* sb_ = rqB + ((size_t)(half ? KT : 0) + rq_kt) * kStageB6 + (half ? (i * NT * 16 - 768 * 16) : (i * NT * 16));
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sb_ + off16),
-                                       (void __attribute__((address_space(3)))*)(so_ + kStageA6 + i * (NT * 16)), 16, 0, 0);
-    }
+  // A request = the kLoadsPerStep loads of the next K step of the walk into the next stage of the ring.  rq_begin
+  // fixes its addresses and advances the cursor (false when the walk is over), rq_issue<i> issues its i-th load: the
+  // main loop spreads them among its MFMAs (eight waves issuing all their loads at once keep the address unit busy
+  // for several hundred cycles, during which none of them can issue anything else).
+  bool rq_on = false;
+  uint8_t* rq_so = nullptr;
+  const uint8_t* rq_sa = nullptr;
+  const uint8_t* rq_sb = nullptr;
+  auto rq_begin = [&]() -> bool {
+    rq_on = rq_pos < count;
+    if (!rq_on) return false;
+    rq_so = smem + rq_stg * kStage6 + wave * 1024;
+    rq_sa = rqA + (size_t)rq_kt * kStageA6;
+    rq_sb = rqB + (size_t)rq_kt * kStageB6;
     rq_stg = (rq_stg == kNumStage6 - 1) ? 0 : rq_stg + 1;
     if (++rq_kt == KT) {
       rq_kt = 0;
@@ -213,6 +210,32 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       if (rq_pos < count) rq_tile();
     }
     return true;
+  };
+  auto rq_issue = [&](auto i_tag) __attribute__((always_inline)) {
+    constexpr int li = decltype(i_tag)::value;
+    if (!rq_on) return;
+    if constexpr (li < nA) {
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rq_sa + li * (NT * 16) + off16),
+                                       (void __attribute__((address_space(3)))*)(rq_so + li * (NT * 16)), 16, 0, 0);
+    } else {
+      constexpr int i = li - nA;
+      // chunk i * NT + tid of the 1536: column tile 1 (KT stages further on) from chunk 768 on (a whole number of waves)
+      const bool half = (i * NT + wave * 64) >= 768;
+      const uint8_t* sb_ = rq_sb + (half ? (size_t)KT * kStageB6 + (i * NT * 16 - 768 * 16) : (size_t)(i * NT * 16));
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sb_ + off16),
+                                       (void __attribute__((address_space(3)))*)(rq_so + kStageA6 + i * (NT * 16)), 16, 0, 0);
+    }
+  };
+  static_assert(kLoadsPerStep == 6, "the main loop spreads six loads per wave and step");
+  auto request_next = [&]() -> bool {
+    const bool on = rq_begin();
+    rq_issue(std::integral_constant<int, 0>{});
+    rq_issue(std::integral_constant<int, 1>{});
+    rq_issue(std::integral_constant<int, 2>{});
+    rq_issue(std::integral_constant<int, 3>{});
+    rq_issue(std::integral_constant<int, 4>{});
+    rq_issue(std::integral_constant<int, 5>{});
+    return on;
   };
 
   // LDS byte addresses of part 0 of this lane's 48 bytes in stage 0: 32-row block, then lane * 16
@@ -365,7 +388,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       }
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      prev_requested = request_next();
+      prev_requested = rq_begin();
       __builtin_amdgcn_sched_barrier(0);
       stg = (stg == kNumStage6 - 1) ? 0 : stg + 1;
       {
@@ -376,8 +399,27 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
         else STAMP_RD9_PB0(sn + adrA0, sn + adrB0);
       }
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (pb == 0) mfma4(As1, B00, B01, std::integral_constant<int, 3>{});
-      else mfma4(As1, B10, B11, std::integral_constant<int, 3>{});
+      // block 3, the request's loads spread among its MFMAs
+      const Frag& W0 = pb == 0 ? B00 : B10;
+      const Frag& W1 = pb == 0 ? B01 : B11;
+      rq_issue(std::integral_constant<int, 0>{});
+      __builtin_amdgcn_sched_barrier(0);
+      acc[3][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As1.h0), widen((v6i)W0.h0), acc[3][0], 2, 2, 0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      rq_issue(std::integral_constant<int, 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+      acc[3][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As1.h0), widen((v6i)W1.h0), acc[3][1], 2, 2, 0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      rq_issue(std::integral_constant<int, 2>{});
+      __builtin_amdgcn_sched_barrier(0);
+      acc[3][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As1.h1), widen((v6i)W0.h1), acc[3][0], 2, 2, 0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      rq_issue(std::integral_constant<int, 3>{});
+      __builtin_amdgcn_sched_barrier(0);
+      acc[3][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As1.h1), widen((v6i)W1.h1), acc[3][1], 2, 2, 0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      rq_issue(std::integral_constant<int, 4>{});
+      rq_issue(std::integral_constant<int, 5>{});
       __builtin_amdgcn_sched_barrier(0);
     };
     // head of the tile: the barrier that published its first stage lies behind (prologue, or the last step of the
