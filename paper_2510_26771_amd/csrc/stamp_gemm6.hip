@@ -194,6 +194,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   // main loop spreads them among its MFMAs (eight waves issuing all their loads at once keep the address unit busy
   // for several hundred cycles, during which none of them can issue anything else).
   bool rq_on = false;
+  bool rq_tail2 = false;  // the last two loads of the current request are still to be issued
   uint8_t* rq_so = nullptr;
   const uint8_t* rq_sa = nullptr;
   const uint8_t* rq_sb = nullptr;
@@ -345,8 +346,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
         STAMP_WAIT2(8, As0.h0, "v[184:189]", B00.h0, "v[208:213]");
         acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B00.h0), acc[0][0], 2, 2, 0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
+        if (rq_tail2) rq_issue(std::integral_constant<int, 4>{});
+        __builtin_amdgcn_sched_barrier(0);
         STAMP_WAITH(6, B01.h0, "v[220:225]");
         acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B01.h0), acc[0][1], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (rq_tail2) rq_issue(std::integral_constant<int, 5>{});
+        rq_tail2 = false;
         __builtin_amdgcn_sched_barrier(0);
         STAMP_WAIT2(4, As0.h1, "v[190:195]", B00.h1, "v[214:219]");
         acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h1), widen((v6i)B00.h1), acc[0][0], 2, 2, 0, 0, 0, 0);
@@ -357,8 +363,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
         STAMP_WAIT2(8, As0.h0, "v[184:189]", B10.h0, "v[232:237]");
         acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B10.h0), acc[0][0], 2, 2, 0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
+        if (rq_tail2) rq_issue(std::integral_constant<int, 4>{});
+        __builtin_amdgcn_sched_barrier(0);
         STAMP_WAITH(6, B11.h0, "v[244:249]");
         acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B11.h0), acc[0][1], 2, 2, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (rq_tail2) rq_issue(std::integral_constant<int, 5>{});
+        rq_tail2 = false;
         __builtin_amdgcn_sched_barrier(0);
         STAMP_WAIT2(4, As0.h1, "v[190:195]", B10.h1, "v[238:243]");
         acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h1), widen((v6i)B10.h1), acc[0][0], 2, 2, 0, 0, 0, 0);
@@ -418,9 +429,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       __builtin_amdgcn_sched_barrier(0);
       acc[3][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As1.h1), widen((v6i)W1.h1), acc[3][1], 2, 2, 0, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      rq_issue(std::integral_constant<int, 4>{});
-      rq_issue(std::integral_constant<int, 5>{});
-      __builtin_amdgcn_sched_barrier(0);
+      rq_tail2 = true;  // loads 4 and 5 follow among the MFMAs of the next step's block 0 (or after the tile's last step)
     };
     // head of the tile: the barrier that published its first stage lies behind (prologue, or the last step of the
     // tile before)
@@ -433,6 +442,11 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       step(std::integral_constant<int, 1>{});
     }
     if (KT & 1) step(std::integral_constant<int, 0>{});
+    if (rq_tail2) {
+      rq_issue(std::integral_constant<int, 4>{});
+      rq_issue(std::integral_constant<int, 5>{});
+      rq_tail2 = false;
+    }
     // the last step's look-ahead reads must have returned before their registers are used for anything else
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
