@@ -128,14 +128,19 @@ __global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, c
 // Workgroup: 8 waves (2 x 4), tile 256 x 256, one workgroup per CU with two waves on every SIMD, all
 // eight sharing one operand stage: 48 KB per K step for 256 x 256 x 128 products, a third less L2 -> LDS
 // traffic per product than two independent 256 x 128 workgroups would need (the FP6 pipeline consumes a K
-// step in half the time of the int8 one, which makes that traffic the bound).  Three stages: the loads of
-// steps kt+1 and kt+2 are in flight while step kt is multiplied.
+// step in half the time of the int8 one, which makes that traffic the bound).  Three stages: while step kt is
+// multiplied, the stage of step kt+1 has landed or is landing and that of step kt+2 is in flight; the request for
+// step kt+3 goes out late in step kt, into the stage that step kt has just given up.
 //
 // The kernel is persistent: one workgroup per CU walks its share of the tiles (the XCD-aware order of
 // tile_of_sid, every workgroup of an XCD taking every wx-th tile of that XCD's range), and the operand
-// pipeline runs on across tile boundaries: the first two K steps of the next tile are requested during the last
-// two steps of the current one, so they, and the stores of the epilogue, are in flight while the epilogue
+// pipeline runs on across tile boundaries: the first three K steps of the next tile are requested during the last
+// three steps of the current one, so they, and the stores of the epilogue, are in flight while the epilogue
 // computes.  The epilogue works in registers (stamp_epilogue_reg.h) and leaves the operand stages alone.
+//
+// Inside a step nothing waits for what it has just asked for: the LDS reads of an activation block fly under the
+// MFMAs of the block before it, the one workgroup barrier sits before the last block (whose MFMAs cover the reads
+// of the next step's first fragments), and the six loads of a stage request are issued one at a time among MFMAs.
 constexpr int BN6 = 256;
 constexpr int kStage6 = kStageA6 + 2 * kStageB6;  // 48 KB
 constexpr int kNumStage6 = 3;
