@@ -83,6 +83,10 @@ def load_library():
     if not os.path.exists(path):
         raise RuntimeError(f"{path} not found: build it with `python -m paper_2510_26771_amd.build` "
                            "(the STaMP path has no CPU or PyTorch fallback)")
+    # PyTorch supplies the device memory this library works on, so both must talk to ONE HIP runtime: PyTorch's.
+    # The dynamic loader binds this library's HIP dependency to whichever runtime the process loaded first; loaded
+    # before torch, it would bring in the system's runtime next to torch's own, and allocations then fail.
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
     lib.stamp_plan_create.argtypes = [C.POINTER(_Desc), vp, vp, vp, C.POINTER(vp)]
