@@ -355,7 +355,36 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, typename Acc::V (&ac
   const int* s_rowdst = reinterpret_cast<const int*>(row_info + 1024);
   const float* s_rowz = reinterpret_cast<const float*>(row_info + 2048);
 
-  if constexpr (EPI == 0 || EPI == 1) {
+  if constexpr (EPI == 1 && PAIRCOLS && NI == 2) {
+    // a lane holds two neighbouring columns (2 l32, 2 l32 + 1) of every row: one 8-byte store per row when the
+    // output rows keep them 8-byte aligned (even row pitch), else two 4-byte stores
+    const int n = n0 + wn * 64 + 2 * l32;
+    const bool in0 = n < a.N, in1 = n + 1 < a.N;
+    const float sw0 = in0 ? a.sw[n] : 0.0f, sw1 = in1 ? a.sw[n + 1] : 0.0f;
+    const float cs0 = (g.asym && in0) ? a.colsum[n] : 0.0f, cs1 = (g.asym && in1) ? a.colsum[n + 1] : 0.0f;
+    const bool vec = in1 && (a.ld_out & 1) == 0;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int rl = wm * 128 + mi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+        const int dst = s_rowdst[rl];
+        if (dst >= 0 && in0) {
+          const float rz = s_rowz[rl], rf = s_rowfac[rl];
+          // asymmetric: the integer sum over (stored code - offset), exact in one fma (rz = 0 otherwise)
+          const float y0 = (__builtin_fmaf(-rz, cs0, (float)acc[mi][0][v]) * rf) * sw0;
+          const float y1 = (__builtin_fmaf(-rz, cs1, (float)acc[mi][1][v]) * rf) * sw1;
+          float* o = reinterpret_cast<float*>(a.out) + (size_t)dst * a.ld_out + n;
+          if (vec) {
+            *reinterpret_cast<f2*>(o) = f2{y0, y1};
+          } else {
+            o[0] = y0;
+            if (in1) o[1] = y1;
+          }
+        }
+      }
+    }
+  } else if constexpr (EPI == 0 || EPI == 1) {
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int n = n0 + wn * (32 * NI) + (PAIRCOLS ? 2 * l32 + ni : ni * 32 + l32);
