@@ -282,10 +282,6 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
                : "v"(base), "n"(off), "n"((off) + kPart), "n"((off) + 2 * kPart))
 #define STAMP_RD_AS0(base, off) STAMP_RD3(As0, "v[184:189]", "v[190:195]", "v[184:187]", "v[188:191]", "v[192:195]", base, off)
 #define STAMP_RD_AS1(base, off) STAMP_RD3(As1, "v[196:201]", "v[202:207]", "v[196:199]", "v[200:203]", "v[204:207]", base, off)
-#define STAMP_RD_B00(base, off) STAMP_RD3(B00, "v[208:213]", "v[214:219]", "v[208:211]", "v[212:215]", "v[216:219]", base, off)
-#define STAMP_RD_B01(base, off) STAMP_RD3(B01, "v[220:225]", "v[226:231]", "v[220:223]", "v[224:227]", "v[228:231]", base, off)
-#define STAMP_RD_B10(base, off) STAMP_RD3(B10, "v[232:237]", "v[238:243]", "v[232:235]", "v[236:239]", "v[240:243]", base, off)
-#define STAMP_RD_B11(base, off) STAMP_RD3(B11, "v[244:249]", "v[250:255]", "v[244:247]", "v[248:251]", "v[252:255]", base, off)
   // activation block 0 and the two weight blocks of a step in one statement, parts 0 and 1 of all three first (the
   // first MFMA half's operands), then the parts 2
 #define STAMP_RD9(fa, fb0, fb1, AH0, AH1, B0H0, B0H1, B1H0, B1H1, A0, A1, A2, B00_, B01_, B02_, B10_, B11_, B12_, basea, baseb)         \

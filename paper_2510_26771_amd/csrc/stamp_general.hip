@@ -567,13 +567,12 @@ float haar_norm_host(int level) { return std::ldexp((level & 1) ? kC : 1.0f, -(l
 // Plan-time tables
 // ---------------------------------------------------------------------------------------------
 void stamp_gen_plan_free(stamp_plan* p) {
-  if (p->norm_dev) (void)hipFree(p->norm_dev);
   if (p->perm_dev) (void)hipFree(p->perm_dev);
   if (p->ell_dev) (void)hipFree(p->ell_dev);
   if (p->dct_dev) (void)hipFree(p->dct_dev);
   if (p->qWg_dev) (void)hipFree(p->qWg_dev);
   if (p->swg_dev) (void)hipFree(p->swg_dev);
-  p->norm_dev = p->ell_dev = p->swg_dev = nullptr;
+  p->ell_dev = p->swg_dev = nullptr;
   p->perm_dev = nullptr;
   p->dct_dev = nullptr;
   p->qWg_dev = nullptr;

@@ -148,8 +148,7 @@ struct stamp_plan {
   int32_t unfused;          // 1: separate inverse kernel
   int32_t fused_ok;         // shape allows the fused epilogue
   StampGen gen;             // general path (kind != kGenNone)
-  float* norm_dev;          // general path: [s] factor of every STaMP slot applied after the butterflies (or nullptr)
-  int32_t* perm_dev;        // general path, WHT: [s] source row of every STaMP slot
+  int32_t* perm_dev;        // general path, WHT: [s] STaMP slot of every row of the Hadamard-ordered result
   float* ell_dev;           // general path, transformed bias: [s] l = L 1
   double* dct_dev;          // general path, DCT: [s][s] orthonormal DCT-II matrix
   int8_t* qWg_dev;          // per-block scales: weight codes [Npad128][d_in] int8
