@@ -134,14 +134,14 @@ typedef struct {
 } stamp_plan_desc_t;
 
 /* Two implementations serve a plan.
- * FAST path (the benchmark configurations): HAAR1D on a power-of-two seq_len without skip_first, HAAR2D, IDENTITY, all
- * with group_size 0 and bias_mode 0; limits below.
+ * FAST path (the benchmark configurations): HAAR1D on a power-of-two seq_len without skip_first, HAAR2D on a square
+ * grid, IDENTITY, all with group_size 0 and bias_mode 0; limits below.
  * GENERAL path: everything else that is valid: HAAR1D of any seq_len (an odd number of approximations at a level: the
  * last one is carried to the next level unchanged; every level is the orthonormal butterfly (x0 +- x1) * fl(1/sqrt 2))
- * with 0 <= levels <= the depth that leaves one approximation, skip_first, WHT (seq_len a power of two), DCT, bias_mode 1,
- * group_size 64.  The transform runs as one kernel per level over fp32 copies of the activation in the workspace, the
- * quantizer and the GEMM treat the transformed tokens as rows in STaMP order (physical row = STaMP slot), the inverse
- * again runs level by level.  Limits of the general path: k_hi <= 256 unless group_size = 64; group_size = 64 needs
+ * with 0 <= levels <= the depth that leaves one approximation, skip_first, HAAR2D on a rectangular grid (sides powers of
+ * two), WHT (seq_len a power of two), DCT, bias_mode 1, group_size 64.  The transform runs as a few passes (several
+ * levels each) over fp32 copies of the activation in the workspace, the quantizer and the GEMM treat the transformed
+ * tokens as rows in STaMP order (physical row = STaMP slot), the inverse again runs in passes after the GEMM.  Limits of the general path: k_hi <= 256 unless group_size = 64; group_size = 64 needs
  * d_in a multiple of 64 and the symmetric quantizer; d_in a multiple of 32; bits 8/4/4.  With group_size = 64 the
  * buffers of stamp_quantize_act / stamp_linear_forward_q are: q_hi [batch, seq_len, d_in] int8 codes of ALL tokens in
  * STaMP order (stamp_plan_hi_rows returns seq_len), q_lo unused (may be NULL), scales [batch, seq_len, d_in / 64].

@@ -94,13 +94,13 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok,
   g->y_bf16 = d->y_dtype == STAMP_BF16;
   g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
   // ---- general path: transforms without the fast path's block structure, transformed bias, per-block scales ----
-  if (ragged || d->xform == STAMP_L_WHT || d->xform == STAMP_L_DCT || d->bias_mode == 1 || d->group_size != 0) {
+  const bool rect2d = d->xform == STAMP_L_HAAR2D && d->grid_h != d->grid_w;  // the fast path takes square grids only
+  if (ragged || rect2d || d->xform == STAMP_L_WHT || d->xform == STAMP_L_DCT || d->bias_mode == 1 || d->group_size != 0) {
     if (d->group_size != 0 && d->group_size != 64) return STAMP_ERR_UNSUPPORTED;
     if (d->group_size == 64 && (d->d_in % 64 != 0 || g->asym)) return STAMP_ERR_UNSUPPORTED;
     if (d->group_size == 0 && d->k_hi > 256) return STAMP_ERR_UNSUPPORTED;
     if (d->seq_len > 65535 || d->batch > 65535 || (int64_t)d->batch * d->k_hi > 65535) return STAMP_ERR_UNSUPPORTED;  // grid dimensions
     if (d->xform == STAMP_L_DCT && d->seq_len > 16384) return STAMP_ERR_UNSUPPORTED;  // dense s x s matrix in fp64
-    if (d->xform == STAMP_L_HAAR2D && d->grid_h != d->grid_w) return STAMP_ERR_UNSUPPORTED;
     gen->kind = ragged ? kGenHaarRagged
                 : d->xform == STAMP_L_WHT ? kGenWht
                 : d->xform == STAMP_L_DCT ? kGenDct
@@ -149,7 +149,6 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok,
     if (g->r < 3 || g->r > 7) return STAMP_ERR_UNSUPPORTED;
     *fused_ok = g->r <= 6;
   } else {
-    if (d->grid_h != d->grid_w) return STAMP_ERR_UNSUPPORTED;
     const int sa = side >> d->levels;  // approximations per grid side
     if (d->k_hi >= sa * sa) {
       const int lk = ilog2(d->k_hi);

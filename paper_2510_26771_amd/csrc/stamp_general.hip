@@ -161,8 +161,8 @@ __global__ __launch_bounds__(256) void k_gen_haar1d_inv(const float* __restrict_
   if (last && o != 0 && i == 0) gen_store_y(Y, y_bf16, bo + c, S[bo + c] + bv);
 }
 
-// NLEV levels of the 2-D Haar pyramid in one pass (square power-of-two grids).  The current low-low region is
-// w_lo x w_lo at the top-left of `in` (grid pitch gridW, token = r * gridW + col); a thread owns one patch of
+// NLEV levels of the 2-D Haar pyramid in one pass (power-of-two grids).  The current low-low region is
+// h_lo x w_lo (cells_lo = h_lo * w_lo tokens) at the top-left of `in` (grid pitch gridW, token = r * gridW + col); a thread owns one patch of
 // 2^NLEV x 2^NLEV of one channel.  Per level: plain sums for the low-low value, the three details times 2^-level
 // to their STaMP slots (bands W, H, D of the level, each row-major, base[li] = slot of the level's band W).  The
 // patch's low-low value goes to grid position (pi, pj) of ll_out, or, when `last`, times apx_norm to slot
@@ -174,7 +174,7 @@ struct GenBands {
 template <int NLEV>
 __global__ __launch_bounds__(256) void k_gen_haar2d_fwd(const void* __restrict__ in, int in_kind, float* __restrict__ ll_out,
                                                         float* __restrict__ T, int seq, int ld, int gridW, int w_lo,
-                                                        GenBands bd, int last, float apx_norm) {
+                                                        int cells_lo, GenBands bd, int last, float apx_norm) {
   GEN_INDEX;
   constexpr int P = 1 << NLEV;
   const int wp = w_lo >> NLEV, pi = i / wp, pj = i - pi * wp;
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void k_gen_haar2d_fwd(const void* __restrict__
     for (int b = 0; b < P; ++b) v[a][b] = gen_load(in, in_kind, bo + ((size_t)(pi * P + a) * gridW + (pj * P + b)) * ld + c);
 #pragma unroll
   for (int li = 0; li < NLEV; ++li) {
-    const int wl = w_lo >> (li + 1), cells = wl * wl;
+    const int wl = w_lo >> (li + 1), cells = cells_lo >> (2 * (li + 1));
 #pragma unroll
     for (int ca = 0; ca < (P >> (li + 1)); ++ca)
 #pragma unroll
@@ -211,7 +211,7 @@ template <int NLEV>
 __global__ __launch_bounds__(256) void k_gen_haar2d_inv(const float* __restrict__ ll_in, int first, const float* __restrict__ S,
                                                         float* __restrict__ ll_out, void* __restrict__ Y,
                                                         const float* __restrict__ bias, int y_bf16, int seq, int ld, int gridW,
-                                                        int w_lo, GenBands bd, int last) {
+                                                        int w_lo, int cells_lo, GenBands bd, int last) {
   GEN_INDEX;
   constexpr int P = 1 << NLEV;
   const int wp = w_lo >> NLEV, pi = i / wp, pj = i - pi * wp;
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void k_gen_haar2d_inv(const float* __restrict_
   v[0][0] = first ? S[bo + (size_t)i * ld + c] : ll_in[bo + ((size_t)pi * gridW + pj) * ld + c];
 #pragma unroll
   for (int li = NLEV - 1; li >= 0; --li) {
-    const int wl = w_lo >> (li + 1), cells = wl * wl;
+    const int wl = w_lo >> (li + 1), cells = cells_lo >> (2 * (li + 1));
 #pragma unroll
     for (int ca = (P >> (li + 1)) - 1; ca >= 0; --ca)
 #pragma unroll
@@ -703,13 +703,13 @@ void launch_haar1d_inv(dim3 grid, hipStream_t st, const float* apx_in, const flo
 }
 template <int NLEV>
 void launch_haar2d_fwd(dim3 grid, hipStream_t st, const void* in, int in_kind, float* ll_out, float* T, int s, int ld, int gridW, int w_lo,
-                       const GenBands& bd, int last, float apx_norm) {
-  hipLaunchKernelGGL(k_gen_haar2d_fwd<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, in, in_kind, ll_out, T, s, ld, gridW, w_lo, bd, last, apx_norm);
+                       int cells_lo, const GenBands& bd, int last, float apx_norm) {
+  hipLaunchKernelGGL(k_gen_haar2d_fwd<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, in, in_kind, ll_out, T, s, ld, gridW, w_lo, cells_lo, bd, last, apx_norm);
 }
 template <int NLEV>
 void launch_haar2d_inv(dim3 grid, hipStream_t st, const float* ll_in, int first, const float* S, float* ll_out, void* Y, const float* bias,
-                       int y_bf16, int s, int ld, int gridW, int w_lo, const GenBands& bd, int last) {
-  hipLaunchKernelGGL(k_gen_haar2d_inv<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, ll_in, first, S, ll_out, Y, bias, y_bf16, s, ld, gridW, w_lo, bd, last);
+                       int y_bf16, int s, int ld, int gridW, int w_lo, int cells_lo, const GenBands& bd, int last) {
+  hipLaunchKernelGGL(k_gen_haar2d_inv<NLEV>, grid, dim3(rows_block(ld, grid.y, grid.z)), 0, st, ll_in, first, S, ll_out, Y, bias, y_bf16, s, ld, gridW, w_lo, cells_lo, bd, last);
 }
 template <int NLEV>
 void launch_wht(dim3 grid, hipStream_t st, const void* in, int in_kind, float* out, void* Y, int out_kind, const int* inv_perm, float norm,
@@ -777,14 +777,14 @@ hipError_t stamp_gen_forward(const stamp_plan* p, const void* X, float* const (&
         bd.base[i] = band_base_2d(gn, l + 1 + i);
         bd.norm[i] = std::ldexp(1.0f, -(l + 1 + i));
       }
-      const int w_lo = gn.gridW >> l, wp = w_lo >> nlev;
-      const dim3 grid = rows_grid(d, wp * wp, B);
+      const int w_lo = gn.gridW >> l, h_lo = gn.gridH >> l, wp = w_lo >> nlev, hp = h_lo >> nlev;
+      const dim3 grid = rows_grid(d, hp * wp, B);
       float* out = tmp[flip];
       const float an = std::ldexp(1.0f, -gn.levels);
       switch (nlev) {
-        case 1: launch_haar2d_fwd<1>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, bd, last, an); break;
-        case 2: launch_haar2d_fwd<2>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, bd, last, an); break;
-        default: launch_haar2d_fwd<3>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, bd, last, an); break;
+        case 1: launch_haar2d_fwd<1>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, h_lo * w_lo, bd, last, an); break;
+        case 2: launch_haar2d_fwd<2>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, h_lo * w_lo, bd, last, an); break;
+        default: launch_haar2d_fwd<3>(grid, st, in, in_kind, out, T, s, d, gn.gridW, w_lo, h_lo * w_lo, bd, last, an); break;
       }
       in = out;
       in_kind = 0;
@@ -877,13 +877,13 @@ hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int nc
       const int l_lo = cut[pi - 1], nlev = cut[pi] - l_lo, last = l_lo == 0;
       GenBands bd = {};
       for (int i = 0; i < nlev; ++i) bd.base[i] = band_base_2d(gn, l_lo + 1 + i);
-      const int w_lo = gn.gridW >> l_lo, wp = w_lo >> nlev;
-      const dim3 grid = rows_grid(ld, wp * wp, B);
+      const int w_lo = gn.gridW >> l_lo, h_lo = gn.gridH >> l_lo, wp = w_lo >> nlev, hp = h_lo >> nlev;
+      const dim3 grid = rows_grid(ld, hp * wp, B);
       float* out = tmp[flip];
       switch (nlev) {
-        case 1: launch_haar2d_inv<1>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, bd, last); break;
-        case 2: launch_haar2d_inv<2>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, bd, last); break;
-        default: launch_haar2d_inv<3>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, bd, last); break;
+        case 1: launch_haar2d_inv<1>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, h_lo * w_lo, bd, last); break;
+        case 2: launch_haar2d_inv<2>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, h_lo * w_lo, bd, last); break;
+        default: launch_haar2d_inv<3>(grid, st, in, first, S, out, Y, bias, g.y_bf16, s, ld, gn.gridW, w_lo, h_lo * w_lo, bd, last); break;
       }
       in = out;
       first = 0;

@@ -33,7 +33,7 @@ def general_path(d) -> bool:
     """Plans the library serves with its general path (transform level by level, rows in STaMP order)."""
     pow2 = d.seq_len & (d.seq_len - 1) == 0
     return (d.xform in (XFORM_CODE["wht"], XFORM_CODE["dct"]) or bool(d.skip_first) or bool(d.bias_mode) or bool(d.group_size)
-            or (d.xform == XFORM_CODE["haar1d"] and not pow2))
+            or (d.xform == XFORM_CODE["haar1d"] and not pow2) or (d.xform == XFORM_CODE["haar2d"] and d.grid_h != d.grid_w))
 
 
 def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):

@@ -58,6 +58,26 @@ OTHER = [
 ]
 
 
+RECT = [
+    _wl("rect_16x64_J3", batch=2, seq_len=1024, xform="haar2d", grid_h=16, grid_w=64, levels=3, k_hi=16, corr_len=4.0, seed=91),
+    _wl("rect_64x16_J4_asym", seq_len=1024, xform="haar2d", grid_h=64, grid_w=16, levels=4, k_hi=4, corr_len=4.0,
+        act_quant="asym", mean_shift=0.5, x_dtype="bf16", seed=92),
+    _wl("rect_8x32_J1_tb", seq_len=256, xform="haar2d", grid_h=8, grid_w=32, levels=1, k_hi=64, corr_len=3.0,
+        bias_mode="transformed", seed=93),
+    _wl("rect_2x128_J1", seq_len=256, xform="haar2d", grid_h=2, grid_w=128, levels=1, k_hi=8, corr_len=3.0, seed=94),
+]
+
+
+@pytest.mark.parametrize("w", RECT, ids=[w.name for w in RECT])
+def test_2d_haar_on_rectangular_grids(w):
+    tl.full_case(w, with_bias=True, check_unfused=False)
+
+
+def test_rectangular_grid_with_per_block_scales():
+    tl.grouped_case(_wl("rect_g64", seq_len=512, xform="haar2d", grid_h=16, grid_w=32, levels=3, k_hi=8, corr_len=4.0,
+                        group_size=64, seed=95), with_bias=True, y_dtype="bf16")
+
+
 @pytest.mark.parametrize("w", OTHER, ids=[w.name for w in OTHER])
 def test_wht_and_dct_along_the_tokens(w):
     tl.full_case(w, with_bias=True, check_unfused=False)
