@@ -120,7 +120,7 @@ typedef struct {
   int32_t grid_h, grid_w;   /* HAAR2D only; grid_h == grid_w, grid_h*grid_w == seq_len */
   int32_t k_hi;             /* tokens kept at bits_hi; a power of two (2-D: a power of four) */
   int32_t bits_hi, bits_lo, bits_w; /* 8, 4, 4 */
-  int32_t x_dtype, y_dtype, w_dtype; /* stamp_dtype_t; w_dtype must be STAMP_F32 */
+  int32_t x_dtype, y_dtype, w_dtype; /* stamp_dtype_t values; bf16 weights are widened exactly at plan time */
   int32_t w_is_out_by_in;   /* 0: W[d_in, d_out];  1: W[d_out, d_in] (the algorithm's X W^T) */
   int32_t act_quant;        /* stamp_act_quant_t: which form of Eq. 1 quantizes the activation */
   int32_t skip_first;       /* HAAR1D only: 1 = the first token of every sequence is left out of L (it is STaMP slot 0 as

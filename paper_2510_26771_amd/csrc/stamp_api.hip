@@ -85,7 +85,6 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok,
 
   // ---- valid STaMP settings from here on; what follows is what this library implements ----
   if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
-  if (d->w_dtype != STAMP_F32) return STAMP_ERR_UNSUPPORTED;
   if (d->d_in % 32 != 0 || d->d_in > 32768) return STAMP_ERR_UNSUPPORTED;  // wider than one workgroup holds: channel splits, two passes
   memset(g, 0, sizeof(*g));
   g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
@@ -367,16 +366,31 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
     stamp_plan_destroy(p);
     return STAMP_ERR_ALLOC;
   }
+  // weights given in bf16 are widened once (exactly) into a temporary that the plan-time kernels read
+  const float* Wf = static_cast<const float*>(W_dev);
+  float* wtmp = nullptr;
+  if (desc->w_dtype == STAMP_BF16) {
+    const size_t nw = (size_t)g.d * g.N;
+    if (hipMalloc(reinterpret_cast<void**>(&wtmp), nw * sizeof(float)) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)hipFree(colmax);
+      stamp_plan_destroy(p);
+      return STAMP_ERR_ALLOC;
+    }
+    Wf = wtmp;
+  }
   bool dev_ok = true;
-  if (bias_dev != nullptr) {
+  if (wtmp != nullptr) dev_ok = stamp_launch_bf16_to_f32(W_dev, wtmp, (size_t)g.d * g.N, st) == hipSuccess;
+  if (dev_ok && bias_dev != nullptr) {
     dev_ok = hipMemsetAsync(p->bias_dev, 0, sizeof(float) * p->Npad, st) == hipSuccess &&
              hipMemcpyAsync(p->bias_dev, bias_dev, sizeof(float) * g.N, hipMemcpyDeviceToDevice, st) == hipSuccess;
   }
-  if (dev_ok) dev_ok = stamp_launch_weight_quant(p, static_cast<const float*>(W_dev), st, colmax) == hipSuccess;
-  if (dev_ok) dev_ok = stamp_launch_weight_quant6(p, static_cast<const float*>(W_dev), colmax, st) == hipSuccess;
-  if (dev_ok && gen.kind != kGenNone) dev_ok = stamp_gen_plan_tables(p, static_cast<const float*>(W_dev), st) == hipSuccess;
-  // the scratch column maxima must outlive the kernels just enqueued: hipFree waits for the device
+  if (dev_ok) dev_ok = stamp_launch_weight_quant(p, Wf, st, colmax) == hipSuccess;
+  if (dev_ok) dev_ok = stamp_launch_weight_quant6(p, Wf, colmax, st) == hipSuccess;
+  if (dev_ok && gen.kind != kGenNone) dev_ok = stamp_gen_plan_tables(p, Wf, st) == hipSuccess;
+  // the scratch buffers must outlive the kernels just enqueued: hipFree waits for the device
   (void)hipFree(colmax);
+  if (wtmp != nullptr) (void)hipFree(wtmp);
   if (!dev_ok) {
     stamp_plan_destroy(p);
     return STAMP_ERR_DEVICE;

@@ -349,6 +349,12 @@ __global__ void k_gen_dct_matrix(double* __restrict__ Cm, int s) {
   Cm[(size_t)k * s + n] = (k == 0) ? sqrt(1.0 / s) : cos(pi * (2.0 * n + 1.0) * (double)k / (2.0 * s)) * sqrt(2.0 / s);
 }
 
+// bf16 -> fp32, flat (plan time: weights given in bf16)
+__global__ __launch_bounds__(256) void k_gen_cast_flat(const uint16_t* __restrict__ src, float* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+}
+
 // fp32 [B, s, ncols] (+ bias) -> Y in the plan's output type
 __global__ __launch_bounds__(256) void k_gen_store_y(const float* __restrict__ src, const float* __restrict__ bias,
                                                      void* __restrict__ Y, int seq, int ld, int y_bf16) {
@@ -926,6 +932,11 @@ hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int nc
     return hipGetLastError();
   }
   return hipErrorInvalidValue;
+}
+
+hipError_t stamp_launch_bf16_to_f32(const void* src, float* dst, size_t n, hipStream_t st) {
+  hipLaunchKernelGGL(k_gen_cast_flat, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, static_cast<const uint16_t*>(src), dst, n);
+  return hipGetLastError();
 }
 
 hipError_t stamp_launch_quant_rows_grouped(const stamp_plan* p, const float* T, int8_t* codes, float* scales, hipStream_t st) {

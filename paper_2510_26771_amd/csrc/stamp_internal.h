@@ -224,6 +224,7 @@ hipError_t stamp_gen_inverse(const stamp_plan* p, float* const (&buf)[3], int nc
 hipError_t stamp_launch_quant_rows_f32(const stamp_plan* p, const float* T, int8_t* q_hi, uint8_t* q_lo, float* scales, hipStream_t st);
 hipError_t stamp_launch_quant_rows_grouped(const stamp_plan* p, const float* T, int8_t* codes, float* scales, hipStream_t st);
 hipError_t stamp_launch_gemm_grouped(const stamp_plan* p, const int8_t* codes, const float* scales, float* Yt, hipStream_t st);
+hipError_t stamp_launch_bf16_to_f32(const void* src, float* dst, size_t n, hipStream_t st);
 hipError_t stamp_launch_merge_hi(const stamp_plan* p, const float* ythi, int nparts, float* Yt, hipStream_t st);
 hipError_t stamp_launch_add_ell_bias(const stamp_plan* p, float* Yt, hipStream_t st);
 

@@ -441,6 +441,37 @@ def test_degenerate_inputs():
     plan.destroy()
 
 
+def test_bf16_weights_are_widened_exactly():
+    """A plan built from bf16 weights holds the codes and scales of the same values given in fp32."""
+    import torch
+    import paper_2510_26771_amd as st
+    from gen.workloads import f32_to_bf16_bits, bf16_bits_to_f32
+    w = _wl("w_bf16", batch=1, seq_len=256, levels=8, k_hi=8, d_in=160, d_out=200, seed=97)
+    inp = make_inputs(w, with_bias=True)
+    bits = f32_to_bf16_bits(inp["W"])
+    Wr = bf16_bits_to_f32(bits)
+    d32 = tl.plan_desc_for(w, "f32")
+    dbf = tl.plan_desc_for(w, "f32")
+    dbf.w_dtype = st.binding.STAMP_BF16
+    bias = torch.from_numpy(inp["bias"]).cuda()
+    p32 = st.StampPlan(d32, torch.from_numpy(Wr).cuda(), bias)
+    pbf = st.StampPlan(dbf, torch.from_numpy(bits.view(np.int16)).cuda(), bias)
+    q32, s32 = p32.debug_weight_codes()
+    qbf, sbf = pbf.debug_weight_codes()
+    qo, so_ = so.quantize_weight(Wr, w.bits_w)
+    assert np.array_equal(q32, qo) and np.array_equal(qbf, qo)
+    assert np.array_equal(sbf.view(np.uint32), so_.view(np.uint32)) and np.array_equal(s32.view(np.uint32), so_.view(np.uint32))
+    X = tl.to_device_x(inp, w)
+    Y32 = torch.zeros((w.batch, w.seq_len, w.d_out), dtype=torch.float32, device="cuda")
+    Ybf = torch.zeros_like(Y32)
+    p32.linear_forward(X, Y32, p32.alloc_workspace())
+    pbf.linear_forward(X, Ybf, pbf.alloc_workspace())
+    torch.cuda.synchronize()
+    assert torch.equal(Y32, Ybf)
+    p32.destroy()
+    pbf.destroy()
+
+
 def test_w_out_by_in_layout():
     """W given as [d_out, d_in] (the algorithm's X W^T) yields the same plan as its transpose."""
     import torch
