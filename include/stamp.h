@@ -117,8 +117,8 @@ typedef struct {
   int32_t batch, seq_len, d_in, d_out;
   int32_t xform;            /* stamp_xform_t */
   int32_t levels;           /* Haar levels J, 1 <= J <= log2(seq_len) (2-D: log2 of the grid side) */
-  int32_t grid_h, grid_w;   /* HAAR2D only; grid_h == grid_w, grid_h*grid_w == seq_len */
-  int32_t k_hi;             /* tokens kept at bits_hi; a power of two (2-D: a power of four) */
+  int32_t grid_h, grid_w;   /* HAAR2D only; powers of two, grid_h*grid_w == seq_len (fast path: square) */
+  int32_t k_hi;             /* tokens kept at bits_hi, 0 .. seq_len (fast path: a power of two, 2-D a power of four) */
   int32_t bits_hi, bits_lo, bits_w; /* 8, 4, 4 */
   int32_t x_dtype, y_dtype, w_dtype; /* stamp_dtype_t values; bf16 weights are widened exactly at plan time */
   int32_t w_is_out_by_in;   /* 0: W[d_in, d_out];  1: W[d_out, d_in] (the algorithm's X W^T) */
@@ -135,19 +135,23 @@ typedef struct {
 
 /* Two implementations serve a plan.
  * FAST path (the benchmark configurations): HAAR1D on a power-of-two seq_len without skip_first, HAAR2D on a square
- * grid, IDENTITY, all with group_size 0 and bias_mode 0; limits below.
+ * grid, IDENTITY, all with group_size 0 and bias_mode 0, and with a block structure the kernels have (listed below).
  * GENERAL path: everything else that is valid: HAAR1D of any seq_len (an odd number of approximations at a level: the
  * last one is carried to the next level unchanged; every level is the orthonormal butterfly (x0 +- x1) * fl(1/sqrt 2))
  * with 0 <= levels <= the depth that leaves one approximation, skip_first, HAAR2D on a rectangular grid (sides powers of
- * two), WHT (seq_len a power of two), DCT, bias_mode 1, group_size 64.  The transform runs as a few passes (several
- * levels each) over fp32 copies of the activation in the workspace, the quantizer and the GEMM treat the transformed
- * tokens as rows in STaMP order (physical row = STaMP slot), the inverse again runs in passes after the GEMM.  Limits of the general path: k_hi <= 256 unless group_size = 64; group_size = 64 needs
- * d_in a multiple of 64 and the symmetric quantizer; d_in a multiple of 32; bits 8/4/4.  With group_size = 64 the
- * buffers of stamp_quantize_act / stamp_linear_forward_q are: q_hi [batch, seq_len, d_in] int8 codes of ALL tokens in
- * STaMP order (stamp_plan_hi_rows returns seq_len), q_lo unused (may be NULL), scales [batch, seq_len, d_in / 64].
+ * two), WHT (seq_len a power of two), DCT, bias_mode 1, group_size 64, and the HAAR1D / HAAR2D settings outside the
+ * fast path's block structure (any 0 <= k_hi <= seq_len, any depth, any block size).  The transform runs as a few passes
+ * (several levels each) over fp32 copies of the activation in the workspace, the quantizer and the GEMM treat the
+ * transformed tokens as rows in STaMP order (physical row = STaMP slot), the inverse again runs in passes after the GEMM.
+ * Limits of the general path (STAMP_ERR_UNSUPPORTED beyond them): bits 8/4/4; d_in a multiple of 32, at most 32768;
+ * group_size 0 or 64, and 64 needs d_in a multiple of 64 and the symmetric quantizer; seq_len <= 65535, batch <= 65535,
+ * batch * k_hi <= 65535 (grid dimensions); DCT: seq_len <= 16384 (a dense seq_len x seq_len matrix).  With group_size =
+ * 64 the buffers of stamp_quantize_act / stamp_linear_forward_q are: q_hi [batch, seq_len, d_in] int8 codes of ALL
+ * tokens in STaMP order (stamp_plan_hi_rows returns seq_len), q_lo unused (may be NULL), scales [batch, seq_len,
+ * d_in / 64].
  *
- * Supported by the fast path (anything else valid returns STAMP_ERR_UNSUPPORTED unless the general path takes it):
- *   xform IDENTITY with levels 0, any seq_len and 0 <= k_hi <= 256; or
+ * Served by the fast path (any other valid setting goes to the general path, within its limits):
+ *   xform IDENTITY with levels 0, any seq_len and 0 <= k_hi <= seq_len; or
  *   xform HAAR1D or HAAR2D (square grid) of any depth J, with n_top = max(k_hi, approximations left by J
  *   levels) <= 256 and seq_len/n_top in {8,16,32,64,128} (1-D) or {16,64} (2-D: 4x4 or 8x8 token blocks);
  *   k_hi a power of two (four in 2-D) when k_hi >= the number of approximations, any 0 <= k_hi below it
@@ -155,8 +159,8 @@ typedef struct {
  *   4 bits); bits 8/4/4;
  *   d_in a multiple of 32 and at most 32768 (above 8192, or 4096 for fp32 input or 2-D grids, the transform
  *   + quantization kernel splits the channels over workgroups and reads X twice: row ranges, then codes);
- *   k_hi <= 256; act_quant symmetric or asymmetric; batch <= 65535 and batch * n_top <= 65535 (grid
- *   dimensions of the transform kernels). */
+ *   act_quant symmetric or asymmetric; batch <= 65535 and batch * n_top <= 65535 (grid dimensions of the
+ *   transform kernels). */
 
 /* Validates desc, quantizes W per output channel (absmax/7, round to nearest even; section
  * "Large Language Models", Set-up: round-to-nearest weights, one scale per output channel) into

@@ -44,84 +44,10 @@ int max_ragged_levels(int n) {
   return l;
 }
 
-stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok, StampGen* gen) {
-  memset(gen, 0, sizeof(*gen));
-  if (d->batch < 1 || d->seq_len < 1 || d->d_in < 1 || d->d_out < 1) return STAMP_ERR_SHAPE;
-  if (d->xform < STAMP_L_IDENTITY || d->xform > STAMP_L_DCT) return STAMP_ERR_SHAPE;
-  if (d->skip_first != 0 && d->skip_first != 1) return STAMP_ERR_SHAPE;
-  if (d->skip_first && (d->xform != STAMP_L_HAAR1D || d->seq_len < 2)) return STAMP_ERR_SHAPE;  // defined for the 1-D Haar transform
-  if (d->bias_mode != 0 && d->bias_mode != 1) return STAMP_ERR_SHAPE;
-  if (d->group_size < 0) return STAMP_ERR_SHAPE;
-  if (d->k_hi < 0 || d->k_hi > d->seq_len) return STAMP_ERR_SHAPE;
-  if (d->bits_hi < 2 || d->bits_hi > 8 || d->bits_lo < 2 || d->bits_lo > 8 || d->bits_w < 2 || d->bits_w > 8)
-    return STAMP_ERR_SHAPE;
-  if (d->d_in % 2 != 0) return STAMP_ERR_SHAPE;
-  for (int32_t t : {d->x_dtype, d->y_dtype, d->w_dtype})
-    if (t != STAMP_F32 && t != STAMP_BF16) return STAMP_ERR_SHAPE;
-  if (d->w_is_out_by_in != 0 && d->w_is_out_by_in != 1) return STAMP_ERR_SHAPE;
-  if (d->act_quant != STAMP_ACT_SYMMETRIC && d->act_quant != STAMP_ACT_ASYMMETRIC) return STAMP_ERR_SHAPE;
-  if ((int64_t)d->batch * d->seq_len > (int64_t)1 << 30) return STAMP_ERR_SHAPE;
-
-  int J = 0, side = 0;
-  const bool ragged = d->xform == STAMP_L_HAAR1D && (d->skip_first || !is_pow2(d->seq_len));
-  if (ragged) {
-    if (d->levels < 0 || d->levels > max_ragged_levels(d->seq_len - d->skip_first)) return STAMP_ERR_SHAPE;
-  } else if (d->xform == STAMP_L_WHT) {
-    if (!is_pow2(d->seq_len) || d->levels != 0) return STAMP_ERR_SHAPE;
-  } else if (d->xform == STAMP_L_DCT) {
-    if (d->levels != 0) return STAMP_ERR_SHAPE;
-  } else if (d->xform == STAMP_L_HAAR1D) {
-    J = ilog2(d->seq_len);
-    if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
-  } else if (d->xform == STAMP_L_HAAR2D) {
-    if (d->grid_h < 1 || d->grid_w < 1 || (int64_t)d->grid_h * d->grid_w != d->seq_len) return STAMP_ERR_SHAPE;
-    if (!is_pow2(d->grid_h) || !is_pow2(d->grid_w)) return STAMP_ERR_SHAPE;
-    side = d->grid_h < d->grid_w ? d->grid_h : d->grid_w;
-    J = ilog2(side);
-    if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
-  } else if (d->levels != 0) {
-    return STAMP_ERR_SHAPE;  // no transform, no levels
-  }
-
-  // ---- valid STaMP settings from here on; what follows is what this library implements ----
-  if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
-  if (d->d_in % 32 != 0 || d->d_in > 32768) return STAMP_ERR_UNSUPPORTED;  // wider than one workgroup holds: channel splits, two passes
-  memset(g, 0, sizeof(*g));
-  g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
-  g->J = d->levels; g->k = g->khi = d->k_hi;
-  g->x_bf16 = d->x_dtype == STAMP_BF16;
-  g->y_bf16 = d->y_dtype == STAMP_BF16;
-  g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
-  // ---- general path: transforms without the fast path's block structure, transformed bias, per-block scales ----
-  const bool rect2d = d->xform == STAMP_L_HAAR2D && d->grid_h != d->grid_w;  // the fast path takes square grids only
-  if (ragged || rect2d || d->xform == STAMP_L_WHT || d->xform == STAMP_L_DCT || d->bias_mode == 1 || d->group_size != 0) {
-    if (d->group_size != 0 && d->group_size != 64) return STAMP_ERR_UNSUPPORTED;
-    if (d->group_size == 64 && (d->d_in % 64 != 0 || g->asym)) return STAMP_ERR_UNSUPPORTED;
-    if (d->group_size == 0 && d->k_hi > 256) return STAMP_ERR_UNSUPPORTED;
-    if (d->seq_len > 65535 || d->batch > 65535 || (int64_t)d->batch * d->k_hi > 65535) return STAMP_ERR_UNSUPPORTED;  // grid dimensions
-    if (d->xform == STAMP_L_DCT && d->seq_len > 16384) return STAMP_ERR_UNSUPPORTED;  // dense s x s matrix in fp64
-    gen->kind = ragged ? kGenHaarRagged
-                : d->xform == STAMP_L_WHT ? kGenWht
-                : d->xform == STAMP_L_DCT ? kGenDct
-                : d->xform == STAMP_L_HAAR1D ? kGenHaarClassic
-                : d->xform == STAMP_L_HAAR2D ? kGenHaar2d : kGenCopy;
-    gen->levels = d->levels;
-    gen->skip = d->skip_first;
-    gen->group = d->group_size;
-    gen->bias_mode = d->bias_mode;
-    gen->gridH = d->grid_h;
-    gen->gridW = d->grid_w;
-    // the quantizer and the GEMM see the transformed tokens as rows: physical row = STaMP slot, no blocks
-    g->J = 0;
-    g->ident = 1;
-    g->R = 1;
-    if (d->group_size == 64) g->k = d->seq_len;  // every token's codes travel as int8 (khi of them are 8-bit rows)
-    *fused_ok = 0;
-    return STAMP_OK;
-  }
+// Geometry of the fast path (blocks of tokens, top rows); STAMP_ERR_UNSUPPORTED when the setting has none.
+stamp_status_t fast_geometry(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok, int side) {
   if (d->xform == STAMP_L_IDENTITY) {
     // tokens quantized as they are: any number of 8-bit tokens (none included), no blocks, no inverse
-    if (d->k_hi > 256) return STAMP_ERR_UNSUPPORTED;
     if (d->batch > 65535 || (int64_t)d->batch * d->k_hi > 65535) return STAMP_ERR_UNSUPPORTED;  // grid dimensions
     g->ident = 1;
     g->R = 1;
@@ -171,6 +97,95 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok,
   g->L = g->J - g->r;
   // batch and batch * (top rows) are grid dimensions y / z of the transform and inverse kernels
   if (d->batch > 65535 || (int64_t)d->batch * g->k > 65535) return STAMP_ERR_UNSUPPORTED;
+  return STAMP_OK;
+}
+
+stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok, StampGen* gen) {
+  memset(gen, 0, sizeof(*gen));
+  if (d->batch < 1 || d->seq_len < 1 || d->d_in < 1 || d->d_out < 1) return STAMP_ERR_SHAPE;
+  if (d->xform < STAMP_L_IDENTITY || d->xform > STAMP_L_DCT) return STAMP_ERR_SHAPE;
+  if (d->skip_first != 0 && d->skip_first != 1) return STAMP_ERR_SHAPE;
+  if (d->skip_first && (d->xform != STAMP_L_HAAR1D || d->seq_len < 2)) return STAMP_ERR_SHAPE;  // defined for the 1-D Haar transform
+  if (d->bias_mode != 0 && d->bias_mode != 1) return STAMP_ERR_SHAPE;
+  if (d->group_size < 0) return STAMP_ERR_SHAPE;
+  if (d->k_hi < 0 || d->k_hi > d->seq_len) return STAMP_ERR_SHAPE;
+  if (d->bits_hi < 2 || d->bits_hi > 8 || d->bits_lo < 2 || d->bits_lo > 8 || d->bits_w < 2 || d->bits_w > 8)
+    return STAMP_ERR_SHAPE;
+  if (d->d_in % 2 != 0) return STAMP_ERR_SHAPE;
+  for (int32_t t : {d->x_dtype, d->y_dtype, d->w_dtype})
+    if (t != STAMP_F32 && t != STAMP_BF16) return STAMP_ERR_SHAPE;
+  if (d->w_is_out_by_in != 0 && d->w_is_out_by_in != 1) return STAMP_ERR_SHAPE;
+  if (d->act_quant != STAMP_ACT_SYMMETRIC && d->act_quant != STAMP_ACT_ASYMMETRIC) return STAMP_ERR_SHAPE;
+  if ((int64_t)d->batch * d->seq_len > (int64_t)1 << 30) return STAMP_ERR_SHAPE;
+
+  int J = 0, side = 0;
+  const bool ragged = d->xform == STAMP_L_HAAR1D && (d->skip_first || !is_pow2(d->seq_len));
+  if (ragged) {
+    if (d->levels < 0 || d->levels > max_ragged_levels(d->seq_len - d->skip_first)) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_WHT) {
+    if (!is_pow2(d->seq_len) || d->levels != 0) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_DCT) {
+    if (d->levels != 0) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_HAAR1D) {
+    J = ilog2(d->seq_len);
+    if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
+  } else if (d->xform == STAMP_L_HAAR2D) {
+    if (d->grid_h < 1 || d->grid_w < 1 || (int64_t)d->grid_h * d->grid_w != d->seq_len) return STAMP_ERR_SHAPE;
+    if (!is_pow2(d->grid_h) || !is_pow2(d->grid_w)) return STAMP_ERR_SHAPE;
+    side = d->grid_h < d->grid_w ? d->grid_h : d->grid_w;
+    J = ilog2(side);
+    if (d->levels < 1 || d->levels > J) return STAMP_ERR_SHAPE;
+  } else if (d->levels != 0) {
+    return STAMP_ERR_SHAPE;  // no transform, no levels
+  }
+
+  // ---- valid STaMP settings from here on; what follows is what this library implements ----
+  if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
+  if (d->d_in % 32 != 0 || d->d_in > 32768) return STAMP_ERR_UNSUPPORTED;  // wider than one workgroup holds: channel splits, two passes
+  memset(g, 0, sizeof(*g));
+  g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
+  g->J = d->levels; g->k = g->khi = d->k_hi;
+  g->x_bf16 = d->x_dtype == STAMP_BF16;
+  g->y_bf16 = d->y_dtype == STAMP_BF16;
+  g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
+  // ---- the fast path's geometry, where the setting has one ----
+  const bool rect2d = d->xform == STAMP_L_HAAR2D && d->grid_h != d->grid_w;  // the fast path takes square grids only
+  bool need_general = ragged || rect2d || d->xform == STAMP_L_WHT || d->xform == STAMP_L_DCT || d->bias_mode == 1 || d->group_size != 0;
+  if (!need_general) {
+    const stamp_status_t fs = fast_geometry(d, g, fused_ok, side);
+    if (fs == STAMP_OK) return STAMP_OK;
+    // a valid setting outside the fast path's block structure (block sizes, more than 256 top rows, an 8-bit token
+    // count that is not a power of two, ...): the general path takes it
+    need_general = true;
+    memset(g, 0, sizeof(*g));
+    g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
+    g->k = g->khi = d->k_hi;
+    g->x_bf16 = d->x_dtype == STAMP_BF16;
+    g->y_bf16 = d->y_dtype == STAMP_BF16;
+    g->asym = d->act_quant == STAMP_ACT_ASYMMETRIC;
+  }
+  // ---- general path: transforms without the fast path's block structure, transformed bias, per-block scales ----
+  if (d->group_size != 0 && d->group_size != 64) return STAMP_ERR_UNSUPPORTED;
+  if (d->group_size == 64 && (d->d_in % 64 != 0 || g->asym)) return STAMP_ERR_UNSUPPORTED;
+  if (d->seq_len > 65535 || d->batch > 65535 || (int64_t)d->batch * d->k_hi > 65535) return STAMP_ERR_UNSUPPORTED;  // grid dimensions
+  if (d->xform == STAMP_L_DCT && d->seq_len > 16384) return STAMP_ERR_UNSUPPORTED;  // dense s x s matrix in fp64
+  gen->kind = ragged ? kGenHaarRagged
+              : d->xform == STAMP_L_WHT ? kGenWht
+              : d->xform == STAMP_L_DCT ? kGenDct
+              : d->xform == STAMP_L_HAAR1D ? kGenHaarClassic
+              : d->xform == STAMP_L_HAAR2D ? kGenHaar2d : kGenCopy;
+  gen->levels = d->levels;
+  gen->skip = d->skip_first;
+  gen->group = d->group_size;
+  gen->bias_mode = d->bias_mode;
+  gen->gridH = d->grid_h;
+  gen->gridW = d->grid_w;
+  // the quantizer and the GEMM see the transformed tokens as rows: physical row = STaMP slot, no blocks
+  g->J = 0;
+  g->ident = 1;
+  g->R = 1;
+  if (d->group_size == 64) g->k = d->seq_len;  // every token's codes travel as int8 (khi of them are 8-bit rows)
+  *fused_ok = 0;
   return STAMP_OK;
 }
 

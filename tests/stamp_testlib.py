@@ -29,11 +29,29 @@ def unpack_int4(q_lo: np.ndarray) -> np.ndarray:
     return out
 
 
+def _has_fast_blocks(d) -> bool:
+    """Whether a Haar setting has the block structure the library's fast path serves (include/stamp.h)."""
+    pow2 = lambda n: n >= 1 and n & (n - 1) == 0
+    if d.xform == XFORM_CODE["haar1d"]:
+        na = d.seq_len >> d.levels
+        if d.k_hi >= na and not pow2(d.k_hi):
+            return False
+        n_top = max(d.k_hi, na)
+        return n_top <= 256 and d.seq_len // n_top in (8, 16, 32, 64, 128)
+    side = d.grid_h >> d.levels
+    if d.k_hi >= side * side and not (pow2(d.k_hi) and (d.k_hi.bit_length() - 1) % 2 == 0):
+        return False
+    n_top = max(d.k_hi, side * side)
+    return n_top <= 256 and d.seq_len // n_top in (16, 64)
+
+
 def general_path(d) -> bool:
     """Plans the library serves with its general path (transform level by level, rows in STaMP order)."""
     pow2 = d.seq_len & (d.seq_len - 1) == 0
-    return (d.xform in (XFORM_CODE["wht"], XFORM_CODE["dct"]) or bool(d.skip_first) or bool(d.bias_mode) or bool(d.group_size)
-            or (d.xform == XFORM_CODE["haar1d"] and not pow2) or (d.xform == XFORM_CODE["haar2d"] and d.grid_h != d.grid_w))
+    if (d.xform in (XFORM_CODE["wht"], XFORM_CODE["dct"]) or bool(d.skip_first) or bool(d.bias_mode) or bool(d.group_size)
+            or (d.xform == XFORM_CODE["haar1d"] and not pow2) or (d.xform == XFORM_CODE["haar2d"] and d.grid_h != d.grid_w)):
+        return True
+    return d.xform != XFORM_CODE["identity"] and not _has_fast_blocks(d)
 
 
 def gpu_codes_in_stamp_order(plan, q_hi, q_lo, scales):

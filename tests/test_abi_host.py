@@ -63,7 +63,6 @@ def _good(**kw):
     (dict(group_size=32), 3),                                 # blocks of 64 channels only
     (dict(group_size=64, d_in=96), 3),
     (dict(group_size=64, act_quant=1), 3),
-    (dict(seq_len=500, levels=3, k_hi=300), 3),               # general path: at most 256 8-bit tokens
     (dict(levels=9), 2),                                      # more levels than log2(seq_len)
     (dict(levels=0), 2),
     (dict(k_hi=257), 2),                                      # k > s
@@ -74,15 +73,10 @@ def _good(**kw):
     (dict(bits_hi=9), 2),
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=8, levels=3), 2),   # grid != seq_len
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=5), 2),  # too many levels
-    (dict(seq_len=4096, levels=3), 3),                        # 512 approximations: more than the top part holds
-    (dict(k_hi=12), 3),                                       # k not a power of two
-    (dict(k_hi=128), 3),                                      # blocks of 2 tokens
     (dict(bits_lo=3), 3),
     (dict(d_in=48), 3),                                       # d_in not a multiple of 32
     (dict(d_in=32800), 3),                                    # wider than the channel splits go
     (dict(xform=st.STAMP_L_IDENTITY, levels=2), 2),          # no transform has no levels
-    (dict(xform=st.STAMP_L_IDENTITY, levels=0, k_hi=300, seq_len=512), 3),   # more than 256 8-bit tokens
-    (dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=4, k_hi=8), 3),   # k not a power of four
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=32, grid_w=8, levels=4, k_hi=16), 2),   # more levels than the short side has
     (dict(w_dtype=7), 2),
     # batch and batch * (top rows) are grid dimensions of the transform kernels: beyond 65535 the plan is refused
@@ -92,6 +86,23 @@ def _good(**kw):
 ])
 def test_plan_create_rejects_before_any_device_call(lib, kw, expect):
     assert _create(lib, _good(**kw)) == expect
+
+
+@pytest.mark.parametrize("kw", [
+    dict(seq_len=500, levels=3, k_hi=300),                      # more than 256 8-bit tokens
+    dict(seq_len=4096, levels=3),                               # 512 approximations: more than the fast path's top part holds
+    dict(k_hi=12),                                              # k not a power of two
+    dict(k_hi=128),                                             # blocks of 2 tokens
+    dict(xform=st.STAMP_L_IDENTITY, levels=0, k_hi=300, seq_len=512),
+    dict(xform=st.STAMP_L_HAAR2D, grid_h=16, grid_w=16, levels=4, k_hi=8),    # k not a power of four
+    dict(xform=st.STAMP_L_HAAR2D, grid_h=32, grid_w=8, levels=3, k_hi=16),    # rectangular grid
+    dict(seq_len=250, levels=8),                                # not a power of two
+    dict(w_dtype=st.STAMP_BF16),
+])
+def test_settings_outside_the_fast_path_are_accepted(lib, kw):
+    """Valid STaMP settings without the fast path's block structure are served by the general path: validation
+    passes, and without a GPU the first device allocation is what fails."""
+    assert _create(lib, _good(**kw)) == 5
 
 
 def test_null_arguments(lib):

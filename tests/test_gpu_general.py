@@ -78,6 +78,30 @@ def test_rectangular_grid_with_per_block_scales():
                         group_size=64, seed=95), with_bias=True, y_dtype="bf16")
 
 
+# Valid settings on power-of-two sequences and square grids that have no fast-path block structure: served by the
+# general path (and identity plans with many 8-bit tokens, which stay on the per-token kernel).
+NO_BLOCKS = [
+    _wl("k12_of_256", batch=2, seq_len=256, levels=8, k_hi=12, seed=101),                       # k not a power of two
+    _wl("blocks_of_2", seq_len=256, levels=8, k_hi=128, seed=102),
+    _wl("blocks_of_512", seq_len=1024, levels=10, k_hi=2, x_dtype="bf16", seed=103),
+    _wl("top_512", seq_len=4096, levels=3, k_hi=64, d_in=128, d_out=72, seed=104),               # 512 approximations
+    _wl("k300_of_512_asym", seq_len=512, levels=3, k_hi=300, act_quant="asym", mean_shift=0.5, seed=105),
+    _wl("k0_of_512", seq_len=512, levels=9, k_hi=0, seed=106),
+    _wl("all_8bit", seq_len=64, levels=2, k_hi=64, seed=107),
+    _wl("grid16_k8", seq_len=256, xform="haar2d", grid_h=16, grid_w=16, levels=4, k_hi=8, corr_len=4.0, seed=108),
+    _wl("grid32_J1", batch=2, seq_len=1024, xform="haar2d", grid_h=32, grid_w=32, levels=1, k_hi=16, corr_len=4.0,
+        seed=109),                                                                                # 2x2 token blocks
+    _wl("grid2_J1", seq_len=4, xform="haar2d", grid_h=2, grid_w=2, levels=1, k_hi=1, corr_len=2.0, seed=110),
+    _wl("ident_k300", seq_len=512, xform="identity", levels=0, k_hi=300, seed=111),
+    _wl("ident_all_8bit", batch=2, seq_len=100, xform="identity", levels=0, k_hi=100, act_quant="asym", seed=112),
+]
+
+
+@pytest.mark.parametrize("w", NO_BLOCKS, ids=[w.name for w in NO_BLOCKS])
+def test_settings_without_the_fast_paths_block_structure(w):
+    tl.full_case(w, with_bias=True, check_unfused=w.xform == "identity")
+
+
 @pytest.mark.parametrize("w", OTHER, ids=[w.name for w in OTHER])
 def test_wht_and_dct_along_the_tokens(w):
     tl.full_case(w, with_bias=True, check_unfused=False)
@@ -237,6 +261,31 @@ def test_random_general_plans(seed):
     else:
         r = tl.full_case(w, with_bias=True, y_dtype=y_dtype, check_unfused=False)
         assert r["code_mismatches"] == 0
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_haar_plans_of_any_block_structure(seed):
+    """Seeded sweep over plain Haar settings (power-of-two sequences, square or rectangular grids) with any depth and
+    any number of 8-bit tokens: whichever path serves the plan, the result meets the same bars."""
+    rng = np.random.default_rng(7600 + seed)
+    kw = dict(batch=int(rng.integers(1, 3)), d_in=int(rng.integers(1, 7)) * 32, d_out=int(rng.integers(1, 260)),
+              seed=8600 + seed, x_dtype=str(rng.choice(["bf16", "f32"])), act_quant=str(rng.choice(["sym", "asym"])),
+              mean_shift=float(rng.choice([0.0, 0.7])))
+    if rng.random() < 0.5:
+        J = int(rng.integers(1, 12))
+        kw.update(xform="haar1d", seq_len=1 << J, levels=int(rng.integers(1, J + 1)))
+    else:
+        lh, lw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        kw.update(xform="haar2d", seq_len=1 << (lh + lw), grid_h=1 << lh, grid_w=1 << lw,
+                  levels=int(rng.integers(1, min(lh, lw) + 1)), corr_len=4.0)
+    s = kw["seq_len"]
+    k_hi = int(rng.integers(0, s + 1)) if rng.random() < 0.5 else int(rng.integers(0, min(s, 48) + 1))
+    w = _wl(f"rndb{seed}", k_hi=k_hi, **kw)
+    y_dtype = str(rng.choice(["f32", "bf16"]))
+    general = tl.general_path(tl.plan_desc_for(w, y_dtype))
+    tl.log(f"{w.name}: {w.xform} s={s} grid={w.grid_h}x{w.grid_w} J={w.levels} k={k_hi} general={general}")
+    r = tl.full_case(w, with_bias=True, y_dtype=y_dtype, check_unfused=not general)
+    assert r["code_mismatches"] == 0
 
 
 def test_general_path_under_hip_graph_capture_and_static_scratch():
