@@ -158,6 +158,29 @@ def test_wide_layers_channel_split(w):
     assert r["code_mismatches"] == 0
 
 
+# Deep layers (d_in >= 3072: at least 24 K steps of the GEMM, the operand ring wraps many times within a tile) at small
+# M and N: every block length of the fused inverse (8 .. 64 tokens), both quantizer forms, both output types, tiles
+# with rows and columns beyond the matrix, an odd number of K steps.
+DEEP = [
+    _wl("deep_r64", batch=2, seq_len=256, levels=8, k_hi=4, d_in=3072, d_out=130, seed=131),
+    _wl("deep_r32_asym", batch=1, seq_len=256, levels=8, k_hi=8, d_in=3200, d_out=264, seed=132, act_quant="asym",
+        mean_shift=0.4),
+    _wl("deep_r16", batch=3, seq_len=256, levels=8, k_hi=16, d_in=3136, d_out=72, seed=133, first_token_scale=100.0),
+    _wl("deep_r8_J3_few_asym", batch=1, seq_len=512, levels=3, k_hi=8, d_in=4096, d_out=200, seed=134, act_quant="asym",
+        mean_shift=-0.5, n_outlier_channels=20),
+    _wl("deep_small_m", batch=1, seq_len=64, levels=6, k_hi=1, d_in=3072, d_out=64, seed=135),
+    _wl("deep_r8_f32in", batch=2, seq_len=128, levels=7, k_hi=16, d_in=3104, d_out=300, x_dtype="f32", seed=136),
+    _wl("deep_r32_odd_steps", batch=2, seq_len=512, levels=9, k_hi=16, d_in=3328, d_out=96, seed=137),
+]
+
+
+@pytest.mark.parametrize("y_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("w", DEEP, ids=[w.name for w in DEEP])
+def test_deep_layers(w, y_dtype):
+    r = tl.full_case(w, with_bias=True, y_dtype=y_dtype)
+    assert r["code_mismatches"] == 0
+
+
 # Plans without a sequence transform: the layers the paper leaves un-transformed and the baseline the
 # transform's cost is measured against.  Per-token quantization of X itself, tokens 0..k-1 at 8 bits (k any
 # number, none included), ragged shapes, both quantizer forms, both engines, bf16 and fp32 output.
