@@ -183,65 +183,67 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   // the boundary falls between waves, so the source tile of a pass is wave-uniform.  Addresses are a
   // wave-uniform base (tile, K step, pass) plus this thread's constant 32-bit offset.
   const uint32_t off16 = (uint32_t)tid * 16u;
-  // cursor of the requests: K step rq_kt of the tile at position rq_pos of this workgroup's walk (all scalar)
+  // cursor of the requests: K step rq_kt of the tile at position rq_pos of this workgroup's walk (all scalar).  The
+  // loads address memory through two buffer descriptors (the tile's activation panel; its two weight panels, KT * 12 KB
+  // apart) + a scalar byte offset + this thread's constant 32-bit offset: no vector address arithmetic per load.
   int rq_pos = local, rq_kt = 0, rq_stg = 0;
-  const uint8_t* rqA = nullptr;
-  const uint8_t* rqB = nullptr;
+  __amdgpu_buffer_rsrc_t rdA, rdB;
   auto rq_tile = [&]() {
     int tm_, tn_;
     tile_of_sid(first + rq_pos, mt, nt, tm_, tn_);
-    rqA = a.A + (size_t)tm_ * KT * kStageA6;
-    rqB = a.Bq + (size_t)(2 * tn_) * KT * kStageB6;
+    rdA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.A + (size_t)tm_ * KT * kStageA6), 0, 0x7fffffff, 0x00020000);
+    rdB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.Bq + (size_t)(2 * tn_) * KT * kStageB6), 0, 0x7fffffff, 0x00020000);
   };
   rq_tile();
   // A request = the kLoadsPerStep loads of the next K step of the walk into the next stage of the ring.  rq_begin
-  // fixes its addresses and advances the cursor (false when the walk is over), rq_issue<i> issues its i-th load: the
+  // fixes its addresses and advances the cursor, rq_issue<i> issues its i-th load: the
   // main loop spreads them among its MFMAs (eight waves issuing all their loads at once keep the address unit busy
   // for several hundred cycles, during which none of them can issue anything else).
-  bool rq_on = false;
   bool rq_tail2 = false;  // the last two loads of the current request are still to be issued
   uint8_t* rq_so = nullptr;
-  const uint8_t* rq_sa = nullptr;
-  const uint8_t* rq_sb = nullptr;
-  auto rq_begin = [&]() -> bool {
-    rq_on = rq_pos < count;
-    if (!rq_on) return false;
-    rq_so = smem + rq_stg * kStage6 + wave * 1024;
-    rq_sa = rqA + (size_t)rq_kt * kStageA6;
-    rq_sb = rqB + (size_t)rq_kt * kStageB6;
-    rq_stg = (rq_stg == kNumStage6 - 1) ? 0 : rq_stg + 1;
-    if (++rq_kt == KT) {
+  uint32_t rq_oa = 0, rq_ob = 0;  // byte offsets of the request's K step in the activation / weight panels
+  auto rq_begin = [&]() {
+    if (__builtin_expect(rq_kt == KT, 0)) {  // the tile of the request before this one is complete: its descriptors are no longer needed
       rq_kt = 0;
       rq_pos += wx;
-      if (rq_pos < count) rq_tile();
+      if (rq_pos < count) {
+        rq_tile();
+      } else {
+        // the walk is over: the remaining requests read nothing (a descriptor without records; the loads still count,
+        // so every wait of the main loop is for the same number of them)
+        rdA = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0, 0x00020000);
+        rdB = rdA;
+      }
     }
-    return true;
+    rq_so = smem + rq_stg * kStage6 + wave * 1024;
+    rq_oa = (uint32_t)rq_kt * (uint32_t)kStageA6;
+    rq_ob = (uint32_t)rq_kt * (uint32_t)kStageB6;
+    rq_stg = (rq_stg == kNumStage6 - 1) ? 0 : rq_stg + 1;
+    ++rq_kt;
   };
   auto rq_issue = [&](auto i_tag) __attribute__((always_inline)) {
     constexpr int li = decltype(i_tag)::value;
-    if (!rq_on) return;
     if constexpr (li < nA) {
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rq_sa + li * (NT * 16) + off16),
-                                       (void __attribute__((address_space(3)))*)(rq_so + li * (NT * 16)), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdA, (void __attribute__((address_space(3)))*)(rq_so + li * (NT * 16)), 16, off16,
+                                               rq_oa + (uint32_t)(li * (NT * 16)), 0, 0);
     } else {
       constexpr int i = li - nA;
       // chunk i * NT + tid of the 1536: column tile 1 (KT stages further on) from chunk 768 on (a whole number of waves)
       const bool half = (i * NT + wave * 64) >= 768;
-      const uint8_t* sb_ = rq_sb + (half ? (size_t)KT * kStageB6 + (i * NT * 16 - 768 * 16) : (size_t)(i * NT * 16));
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sb_ + off16),
-                                       (void __attribute__((address_space(3)))*)(rq_so + kStageA6 + i * (NT * 16)), 16, 0, 0);
+      const uint32_t ob = rq_ob + (half ? (uint32_t)KT * (uint32_t)kStageB6 + (uint32_t)(i * NT * 16 - 768 * 16) : (uint32_t)(i * NT * 16));
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdB, (void __attribute__((address_space(3)))*)(rq_so + kStageA6 + i * (NT * 16)), 16,
+                                               off16, ob, 0, 0);
     }
   };
   static_assert(kLoadsPerStep == 6, "the main loop spreads six loads per wave and step");
-  auto request_next = [&]() -> bool {
-    const bool on = rq_begin();
+  auto request_next = [&]() {
+    rq_begin();
     rq_issue(std::integral_constant<int, 0>{});
     rq_issue(std::integral_constant<int, 1>{});
     rq_issue(std::integral_constant<int, 2>{});
     rq_issue(std::integral_constant<int, 3>{});
     rq_issue(std::integral_constant<int, 4>{});
     rq_issue(std::integral_constant<int, 5>{});
-    return on;
   };
 
   // LDS byte addresses of part 0 of this lane's 48 bytes in stage 0: 32-row block, then lane * 16
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  bool prev_requested = request_next();  // was a request issued one step ago (it may still be in flight)
+  request_next();
   int landed = 1;  // steps from here on whose loads are known to have landed (their barrier needs no wait)
   int stg = 0;     // stage of the step about to be multiplied
   int rbuf = 0;    // row-info buffer of the current tile
@@ -395,12 +397,11 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       if (landed > 0) {
         --landed;
       } else {
-        if (prev_requested) __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStep);  // vmcnt(one step's loads)
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStep);  // vmcnt(one step's loads): the request of the step before may be in flight
       }
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      prev_requested = rq_begin();
+      rq_begin();
       __builtin_amdgcn_sched_barrier(0);
       stg = (stg == kNumStage6 - 1) ? 0 : stg + 1;
       {
