@@ -126,20 +126,36 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   // Operand staging: asynchronous global -> LDS loads (16 bytes per lane, a wave instruction fills 1 KB
   // of contiguous LDS; the XOR swizzle is applied on the global-address side).  No registers are held
   // while a K step is in flight and nothing has to be copied into LDS by the waves.
-#define STAMP_REQUEST(KSTEP, STG)                                                                          \
-  do {                                                                                                     \
-    uint8_t* so_ = smem + (STG) * stage + wave * 1024;                                                     \
-    const size_t ka_ = (size_t)(KSTEP) * kStepA, kb_ = (size_t)(KSTEP) * kStepB;                           \
-    _Pragma("unroll") for (int i = 0; i < nA; ++i) {                                                       \
-      const uint8_t* src_ = A_INT4 ? (baseGA + ka_ + offA[i]) : (baseGA + min(ka_ + offA[i], lastA));      \
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src_,                \
-                                       (void __attribute__((address_space(3)))*)(so_ + i * (NT * 16)), 16, 0, 0); \
-    }                                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < nB; ++i)                                                         \
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(baseGB + kb_ + offB[i]), \
-                                         (void __attribute__((address_space(3)))*)(so_ + bytesA + i * (NT * 16)), 16, 0, 0); \
-  } while (0)
-
+  // Addresses: a buffer descriptor per operand (scalar base; the 8-bit rows' descriptor ends with the buffer, so a
+  // chunk past the end of the last row reads zeros) + a scalar byte offset per K step + the thread's constant 32-bit
+  // offset of the pass: no vector address arithmetic per load.
+  const size_t restA = A_INT4 ? (size_t)0x7fffffff : (lastA + 16);
+  // (the builtins exist in the device pass only; the host pass, which needs no more than the kernel's signature,
+  // sees an empty request)
+  __amdgpu_buffer_rsrc_t rdA, rdB;
+#if defined(__HIP_DEVICE_COMPILE__)
+  rdA = __builtin_amdgcn_make_buffer_rsrc((void*)baseGA, 0, (int)(restA < (size_t)0x7fffffff ? restA : (size_t)0x7fffffff), 0x00020000);
+  rdB = __builtin_amdgcn_make_buffer_rsrc((void*)baseGB, 0, 0x7fffffff, 0x00020000);
+#else
+  (void)kStepA, (void)kStepB, (void)baseGB, (void)restA, (void)rdA, (void)rdB;
+#endif
+  auto request = [&](int kstep, int stg) __attribute__((always_inline)) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint8_t* so_ = smem + stg * stage + wave * 1024;
+    const uint32_t ka_ = (uint32_t)kstep * (uint32_t)kStepA, kb_ = (uint32_t)kstep * (uint32_t)kStepB;
+#pragma unroll
+    for (int i = 0; i < nA; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdA, (void __attribute__((address_space(3)))*)(so_ + i * (NT * 16)), 16, offA[i], ka_, 0, 0);
+#pragma unroll
+    for (int i = 0; i < nB; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdB, (void __attribute__((address_space(3)))*)(so_ + bytesA + i * (NT * 16)), 16, offB[i],
+                                               kb_, 0, 0);
+#else
+    (void)kstep;
+    (void)stg;
+#endif
+  };
+#define STAMP_REQUEST(KSTEP, STG) request((int)(KSTEP), (int)(STG))
 
   STAMP_REQUEST(kt0, 0);
   EpiOperands<EPI, RB, IS2D> eo;
