@@ -250,6 +250,149 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave, wm, wn);
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The 8-bit rows when the whole batch has at most 128 of them (e.g. 64 8-bit tokens of one sequence): the GEMM is a
+// stream of the stored weights (1 byte per weight, tens of MB) against a few rows, bound by how many bytes are in
+// flight, not by the matrix pipe.  Tile: MB (64 or 128) rows x 128 columns per workgroup of 4 waves (wave w: the 32
+// columns 32 w.., all rows), K step 128, a ring of three stages of MB x 128 + 128 x 128 bytes filled by asynchronous
+// loads two steps ahead, two workgroups per CU, the depth split over several workgroups per tile (partial rows, added
+// by the consumer as for the large tiles).  Same operand layout in LDS, same fragment order and the same
+// dequantization (EPI 1 of the shared epilogue) as k_gemm<false, 1, ...>: identical results.
+template <int MB>
+__global__ __launch_bounds__(256, 2) void k_gemm_hi_few(const GemmArgs a_in) {
+  GemmArgs a = a_in;
+  using Acc = AccI8Hi;
+  constexpr int NT = 256, BNF = 128, MI = MB / 32, NS = 3;
+  constexpr int bytesA = MB * 128, bytesB = BNF * 128, stage = bytesA + bytesB;
+  constexpr int nA = MB * 8 / NT, nB = BNF * 8 / NT;  // 16-byte chunks per thread and step
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  uint8_t* const row_info = smem + NS * stage;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, kg = lane >> 5;
+  const int KT = a.Kpad / BK;
+  const int tn = (int)blockIdx.x / a.ksplit, split = (int)blockIdx.x - tn * a.ksplit;
+  const int kt0 = (int)((long long)KT * split / a.ksplit), kt1 = (int)((long long)KT * (split + 1) / a.ksplit);
+  a.out = reinterpret_cast<float*>(a.out) + (size_t)split * a.split_stride;
+  if (split > 0) a.g.asym = 0;  // the zero-point term of asymmetric codes goes with part 0 only
+  const int n0 = tn * BNF;
+
+  // global -> LDS: chunk q = i * NT + tid of an operand's stage goes to byte 16 q = (row q / 8, slot q % 8); the slot
+  // holds the row's chunk (slot ^ swizzle(row)), applied on the global side
+  const int rowA0 = tid >> 3, slot = tid & 7;
+  const uint32_t kofs = (uint32_t)((slot ^ ((rowA0 >> 1) & 7)) * 16);
+  uint32_t offA[nA], offB[nB];
+#pragma unroll
+  for (int i = 0; i < nA; ++i) offA[i] = (uint32_t)min(rowA0 + i * (NT / 8), a.M - 1) * (uint32_t)a.a_row_bytes + kofs;
+#pragma unroll
+  for (int i = 0; i < nB; ++i) offB[i] = (uint32_t)((rowA0 + i * (NT / 8)) * 128) + kofs;
+  const uint8_t* baseGB = a.Bq + stamp_w_offset(n0, 0, a.Kpad);
+  const size_t restA = a.a_last16 + 16;
+  __amdgpu_buffer_rsrc_t rdA, rdB;
+#if defined(__HIP_DEVICE_COMPILE__)
+  rdA = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, (int)(restA < (size_t)0x7fffffff ? restA : (size_t)0x7fffffff), 0x00020000);
+  rdB = __builtin_amdgcn_make_buffer_rsrc((void*)baseGB, 0, 0x7fffffff, 0x00020000);
+#else
+  (void)baseGB, (void)restA, (void)rdA, (void)rdB;
+#endif
+  auto request = [&](int kstep, int stg) __attribute__((always_inline)) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint8_t* so_ = smem + stg * stage + wave * 1024;
+    const uint32_t ka_ = (uint32_t)kstep * 128u, kb_ = (uint32_t)kstep * (uint32_t)(128 * 128);
+#pragma unroll
+    for (int i = 0; i < nA; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdA, (void __attribute__((address_space(3)))*)(so_ + i * (NT * 16)), 16, offA[i], ka_, 0, 0);
+#pragma unroll
+    for (int i = 0; i < nB; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rdB, (void __attribute__((address_space(3)))*)(so_ + bytesA + i * (NT * 16)), 16, offB[i],
+                                               kb_, 0, 0);
+#else
+    (void)kstep, (void)stg;
+#endif
+  };
+
+  // LDS -> fragments (hand-written reads: the compiler orders every LDS read it can see behind ALL asynchronous loads)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
+  const uint32_t baseA = (uint32_t)(l32 * 128 + (((4 * kg) ^ ((l32 >> 1) & 7)) << 4));
+  const int nl = wave * 32 + l32;
+  const uint32_t baseB = (uint32_t)(bytesA + nl * 128 + (((4 * kg) ^ ((nl >> 1) & 7)) << 4));
+
+  v16i acc[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0;
+
+  const int nsteps = kt1 - kt0;
+  request(kt0, 0);
+  if (nsteps > 1) request(kt0 + 1, 1);
+  if (tid < MB) store_row_info<Acc, 1>(a, 0, tid, row_info);
+  for (int i = 0; i < nsteps; ++i) {
+    asm volatile("" ::: "memory");
+    if (i + 1 < nsteps) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(nA + nB) : "memory");  // the next step's loads may stay in flight
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (i + 2 < nsteps) request(kt0 + i + 2, (i + 2) % NS);  // into the stage of step i - 1, which every wave has left
+    const uint32_t st = lds0 + (uint32_t)((i % NS) * stage);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u4 wb, wa[MI];
+      asm volatile("ds_read_b128 %0, %1" : "=v"(wb) : "v"(st + (baseB ^ (uint32_t)(ks << 4))));
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wa[mi]) : "v"(st + (baseA ^ (uint32_t)(ks << 4))), "n"(mi * 32 * 128));
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wb), "+v"(wa[0]), "+v"(wa[MI - 1]));
+      if constexpr (MI == 4) asm volatile("" : "+v"(wa[1]), "+v"(wa[2]));
+      v4i fb;
+      fb[0] = (int)wb.x; fb[1] = (int)wb.y; fb[2] = (int)wb.z; fb[3] = (int)wb.w;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const u4 w = wa[mi];
+        // natural channel order -> the order of the stored weights: evens then odds per 8 channels
+        v4i fa;
+        fa[0] = (int)__builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
+        fa[1] = (int)__builtin_amdgcn_perm(w.y, w.x, 0x07050301u);
+        fa[2] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x06040200u);
+        fa[3] = (int)__builtin_amdgcn_perm(w.w, w.z, 0x07050301u);
+        acc[mi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[mi], 0, 0, 0);
+      }
+    }
+  }
+  __syncthreads();  // the row table (and, for a part without steps, nothing else) is complete
+
+  const StampGeom& g = a.g;
+  const float* s_rowfac = reinterpret_cast<const float*>(row_info);
+  const int* s_rowdst = reinterpret_cast<const int*>(row_info + 1024);
+  const float* s_rowz = reinterpret_cast<const float*>(row_info + 2048);
+  const int n = n0 + nl;
+  const float swn = a.sw[n];
+  const float csn = g.asym ? a.colsum[n] : 0.0f;
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rl = mi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+      const int dst = s_rowdst[rl];
+      if (dst >= 0 && n < a.N) {
+        // asymmetric: the integer sum over (stored code - offset), exact in one fma
+        const float af = g.asym ? __builtin_fmaf(-s_rowz[rl], csn, (float)acc[mi][v]) : (float)acc[mi][v];
+        reinterpret_cast<float*>(a.out)[(size_t)dst * a.ld_out + n] = (af * s_rowfac[rl]) * swn;
+      }
+    }
+  }
+}
+
+template <int MB>
+hipError_t launch_hi_few(const GemmArgs& a, hipStream_t st) {
+  constexpr size_t lds = 3 * (size_t)(MB * 128 + 128 * 128) + kRowInfoBytes;
+  static size_t lds_done[kStampMaxDevices] = {};
+  hipError_t e = stamp_allow_lds(reinterpret_cast<const void*>(&k_gemm_hi_few<MB>), lds, lds_done);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((k_gemm_hi_few<MB>), dim3((a.Npad / 128) * a.ksplit), dim3(256), lds, st, a);
+  return hipGetLastError();
+}
+
 template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16, int WN>
 hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
   constexpr int BN = 64 * WN;
@@ -305,9 +448,21 @@ bool stamp_hi_rows_are_block_sums(const stamp_plan* p) { return !p->geom.ident &
 
 // The few 8-bit rows make few tiles: when they would leave most CUs idle, the depth of every tile is split
 // over 2..4 workgroups (partial rows, added by the top inverse).
+// at most this many 8-bit rows over the whole batch: the kernel for few rows
+constexpr int kHiFewRows = 128;
+
 int stamp_hi_ksplit(const stamp_plan* p) {
   const int M = p->geom.B * p->geom.k;
   if (M == 0 || stamp_hi_rows_are_block_sums(p)) return 1;  // no partial rows when the GEMM writes the block sums itself
+  if (M <= kHiFewRows) {
+    // few rows: about two workgroups per CU, each with at least four K steps; the partial rows of a part cost
+    // 8 M d_out bytes of traffic, so no more parts than that buys
+    const int tiles = p->Npad / 128, KT = p->Kpad / stamp_gemm::BK;
+    int s = (2 * device_cus() + tiles - 1) / tiles;
+    if (s > KT / 4) s = KT / 4;
+    if (s > 4) s = 4;
+    return s < 1 ? 1 : s;
+  }
   const int mt = (M + stamp_gemm::BM - 1) / stamp_gemm::BM;
   const int tiles = mt * (p->Npad / (stamp_hi_wide_tiles(M, p->Npad) ? 256 : 128));
   const int KT = p->Kpad / stamp_gemm::BK;
@@ -352,6 +507,8 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
     if (ld_out > 0) a.ld_out = ld_out;
     a.ksplit = p->hi_ksplit;
     a.split_stride = (size_t)a.M * a.N;
+    if (a.M <= 64) return launch_hi_few<64>(a, st);
+    if (a.M <= kHiFewRows) return launch_hi_few<128>(a, st);
     return launch<false, 1, 0, false>(a, st);
   }
   return hipErrorInvalidValue;
