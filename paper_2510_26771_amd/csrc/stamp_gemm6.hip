@@ -140,7 +140,8 @@ __global__ __launch_bounds__(256) void k_w_quant6(const float* __restrict__ W, c
 //
 // Inside a step nothing waits for what it has just asked for: the LDS reads of an activation block fly under the
 // MFMAs of the block before it, the one workgroup barrier sits before the last block (whose MFMAs cover the reads
-// of the next step's first fragments), and the six loads of a stage request are issued one at a time among MFMAs.
+// of the next step's first fragments), and the six loads of a stage request are issued one at a time among MFMAs (three in that last
+// block, three in the first two blocks of the next step).
 constexpr int BN6 = 256;
 constexpr int kStage6 = kStageA6 + 2 * kStageB6;  // 48 KB
 constexpr int kNumStage6 = 3;
@@ -199,7 +200,9 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   // fixes its addresses and advances the cursor, rq_issue<i> issues its i-th load: the
   // main loop spreads them among its MFMAs (eight waves issuing all their loads at once keep the address unit busy
   // for several hundred cycles, during which none of them can issue anything else).
-  bool rq_tail2 = false;  // the last two loads of the current request are still to be issued
+  // Of a request's six loads three go out among the MFMAs of the step's last block, the others in the next step: two
+  // in its first block (rq_tail2: still to be issued), the last before its second block (rq_tail3)
+  bool rq_tail2 = false, rq_tail3 = false;
   uint8_t* rq_so = nullptr;
   uint32_t rq_oa = 0, rq_ob = 0;  // byte offsets of the request's K step in the activation / weight panels
   auto rq_begin = [&]() {
@@ -349,12 +352,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
         STAMP_WAIT2(8, As0.h0, "v[184:189]", B00.h0, "v[208:213]");
         acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B00.h0), acc[0][0], 2, 2, 0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (rq_tail2) rq_issue(std::integral_constant<int, 4>{});
+        if (rq_tail2) rq_issue(std::integral_constant<int, 3>{});
         __builtin_amdgcn_sched_barrier(0);
         STAMP_WAITH(6, B01.h0, "v[220:225]");
         acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B01.h0), acc[0][1], 2, 2, 0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (rq_tail2) rq_issue(std::integral_constant<int, 5>{});
+        if (rq_tail2) rq_issue(std::integral_constant<int, 4>{});
+        rq_tail3 = rq_tail2;
         rq_tail2 = false;
         __builtin_amdgcn_sched_barrier(0);
         STAMP_WAIT2(4, As0.h1, "v[190:195]", B00.h1, "v[214:219]");
@@ -366,12 +370,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
         STAMP_WAIT2(8, As0.h0, "v[184:189]", B10.h0, "v[232:237]");
         acc[0][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B10.h0), acc[0][0], 2, 2, 0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (rq_tail2) rq_issue(std::integral_constant<int, 4>{});
+        if (rq_tail2) rq_issue(std::integral_constant<int, 3>{});
         __builtin_amdgcn_sched_barrier(0);
         STAMP_WAITH(6, B11.h0, "v[244:249]");
         acc[0][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As0.h0), widen((v6i)B11.h0), acc[0][1], 2, 2, 0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (rq_tail2) rq_issue(std::integral_constant<int, 5>{});
+        if (rq_tail2) rq_issue(std::integral_constant<int, 4>{});
+        rq_tail3 = rq_tail2;
         rq_tail2 = false;
         __builtin_amdgcn_sched_barrier(0);
         STAMP_WAIT2(4, As0.h1, "v[190:195]", B10.h1, "v[238:243]");
@@ -382,11 +387,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       }
       __builtin_amdgcn_sched_barrier(0);
       STAMP_RD_AS0(sa + adrA0, 2 * kBlock6);
+      if (rq_tail3) rq_issue(std::integral_constant<int, 5>{});
       STAMP_WAIT_AS1(3);
       if constexpr (pb == 0) mfma4(As1, B00, B01, std::integral_constant<int, 1>{});
       else mfma4(As1, B10, B11, std::integral_constant<int, 1>{});
       __builtin_amdgcn_sched_barrier(0);
       STAMP_RD_AS1(sa + adrA0, 3 * kBlock6);
+      rq_tail3 = false;
       STAMP_WAIT_AS0(3);
       if constexpr (pb == 0) mfma4(As0, B00, B01, std::integral_constant<int, 2>{});
       else mfma4(As0, B10, B11, std::integral_constant<int, 2>{});
@@ -427,11 +434,10 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       __builtin_amdgcn_sched_barrier(0);
       acc[3][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As1.h1), widen((v6i)W0.h1), acc[3][0], 2, 2, 0, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      rq_issue(std::integral_constant<int, 3>{});
       __builtin_amdgcn_sched_barrier(0);
       acc[3][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen((v6i)As1.h1), widen((v6i)W1.h1), acc[3][1], 2, 2, 0, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      rq_tail2 = true;  // loads 4 and 5 follow among the MFMAs of the next step's block 0 (or after the tile's last step)
+      rq_tail2 = true;  // loads 3, 4 and 5 follow among the MFMAs of the next step (or after the tile's last step)
     };
     // head of the tile: the barrier that published its first stage lies behind (prologue, or the last step of the
     // tile before)
@@ -445,6 +451,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
     }
     if (KT & 1) step(std::integral_constant<int, 0>{});
     if (rq_tail2) {
+      rq_issue(std::integral_constant<int, 3>{});
       rq_issue(std::integral_constant<int, 4>{});
       rq_issue(std::integral_constant<int, 5>{});
       rq_tail2 = false;
