@@ -153,7 +153,7 @@ __device__ __forceinline__ void dfs2d_reg(const float (&acc)[4][NI][16], float a
 // rowz0 = that row's entry of the per-row tables.  Per block: c = (acc - rowz * colsum) * rowfac in place, the
 // dequantized coefficient without the weight scale (symmetric plans have rowz = 0 and colsum operand 0: the fma
 // then leaves the sum as it is), then the depth-first inverse.
-template <int RB, bool IS2D, int T, int NB, bool YBF16, bool VEC, int NP>
+template <int RB, bool IS2D, int T, int NB, bool YBF16, bool VEC, bool SYM, int NP>
 __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI][16], const f2 (&P)[NP], f2 bias, f2 cs,
                                            RegOut<YBF16, VEC>& o, const float* rowfac0, const float* rowz0, int mrow0,
                                            int n) {
@@ -167,13 +167,17 @@ __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI
 #pragma unroll
       for (int e4 = 0; e4 < R; e4 += 4) {
         const f4 rf = *reinterpret_cast<const f4*>(rowfac0 + 2 * T * R + e4);
-        const f4 rz = *reinterpret_cast<const f4*>(rowz0 + 2 * T * R + e4);
+        f4 rz = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (!SYM) rz = *reinterpret_cast<const f4*>(rowz0 + 2 * T * R + e4);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int e = e4 + u;
 #pragma unroll
-          for (int ni = 0; ni < NI; ++ni)
-            acc[RM::mi(T, e)][ni][RM::v(T, e)] = __builtin_fmaf(-rz[u], cs[ni], acc[RM::mi(T, e)][ni][RM::v(T, e)]) * rf[u];
+          for (int ni = 0; ni < NI; ++ni) {
+            // SYM (a kernel for symmetric plans): no offset term, the fma would add a zero
+            if constexpr (SYM) acc[RM::mi(T, e)][ni][RM::v(T, e)] *= rf[u];
+            else acc[RM::mi(T, e)][ni][RM::v(T, e)] = __builtin_fmaf(-rz[u], cs[ni], acc[RM::mi(T, e)][ni][RM::v(T, e)]) * rf[u];
+          }
         }
         // keeps the factor reads of later groups from being hoisted (they would all be live at once)
         if ((e4 & 12) == 12) __builtin_amdgcn_sched_barrier(0);
@@ -191,7 +195,7 @@ __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI
         dfs2d_reg<RB, T, 0, 0, 0, RegOut<YBF16, VEC>>(acc, 0.0f, 0.0f, o);
       }
     }
-    blocks_reg<RB, IS2D, T + 1, NB, YBF16, VEC, NP>(a, acc, P, bias, cs, o, rowfac0, rowz0, mrow0, n);
+    blocks_reg<RB, IS2D, T + 1, NB, YBF16, VEC, SYM, NP>(a, acc, P, bias, cs, o, rowfac0, rowz0, mrow0, n);
   }
 }
 
@@ -199,7 +203,7 @@ __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI
 // EPI 3: plans without a sequence transform (rows are tokens).
 // accv: the wave's accumulators, 4 x NIW blocks; this call handles the column pair PAIR (blocks 2 PAIR, 2 PAIR + 1:
 // the 64 columns from nw on).
-template <int EPI, int RB, bool IS2D, bool YBF16, bool VEC, int NIW, int PAIR>
+template <int EPI, int RB, bool IS2D, bool YBF16, bool VEC, int NIW, int PAIR, bool SYM>
 __device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f (&accv)[4][NIW], const uint8_t* row_info,
                                                   const RegEpiOperands<EPI, (IS2D ? 2 * RB : RB)>& eo, int m0, int nw,
                                                   int wm, int lane) {
@@ -264,19 +268,19 @@ __device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f 
     o.nvalid = nvalid;
     o.tok_stride = (size_t)a.N;
     o.row_stride = (size_t)g.gridW * a.N;
-    blocks_reg<RB, IS2D, 0, nb, YBF16, VEC>(a, acc, eo.P, eo.bias, eo.cs, o, s_rowfac + wm * 128 + kg * R, s_rowz + wm * 128 + kg * R,
+    blocks_reg<RB, IS2D, 0, nb, YBF16, VEC, SYM>(a, acc, eo.P, eo.bias, eo.cs, o, s_rowfac + wm * 128 + kg * R, s_rowz + wm * 128 + kg * R,
                                             m0 + wm * 128 + kg * R, n);
   }
 }
 
-template <int EPI, int RB, bool IS2D, bool YBF16, int NIW = NI, int PAIR = 0>
+template <int EPI, int RB, bool IS2D, bool YBF16, int NIW = NI, int PAIR = 0, bool SYM = false>
 __device__ __forceinline__ void epilogue_reg(const GemmArgs& a, const v16f (&acc)[4][NIW], const uint8_t* row_info,
                                              const RegEpiOperands<EPI, (IS2D ? 2 * RB : RB)>& eo, int m0, int nw, int wm,
                                              int lane) {
   // pairs of columns are stored as one word when d_out is even (the pair then never straddles the end); the
   // fused inverse is only launched on even d_out (odd widths take the separate inverse kernel)
-  if (EPI == 2 || (a.N & 1) == 0) epilogue_reg_impl<EPI, RB, IS2D, YBF16, true, NIW, PAIR>(a, acc, row_info, eo, m0, nw, wm, lane);
-  else epilogue_reg_impl<EPI, RB, IS2D, YBF16, false, NIW, PAIR>(a, acc, row_info, eo, m0, nw, wm, lane);
+  if (EPI == 2 || (a.N & 1) == 0) epilogue_reg_impl<EPI, RB, IS2D, YBF16, true, NIW, PAIR, SYM>(a, acc, row_info, eo, m0, nw, wm, lane);
+  else epilogue_reg_impl<EPI, RB, IS2D, YBF16, false, NIW, PAIR, SYM>(a, acc, row_info, eo, m0, nw, wm, lane);
 }
 
 }  // namespace stamp_gemm

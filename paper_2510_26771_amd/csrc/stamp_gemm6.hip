@@ -155,7 +155,8 @@ __device__ __forceinline__ void tile_of_sid(int sid, int mt, int nt, int& tm, in
   tn = in_grp / gm;
 }
 
-template <int EPI, int RB, bool IS2D, bool YBF16>
+// SYM: a fused-mode kernel for plans with symmetric activation codes (no offset term in the epilogue)
+template <int EPI, int RB, bool IS2D, bool YBF16, bool SYM = false>
 __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   using Acc = AccF6Lo;
   constexpr int NIW = NI;  // 32-column MFMA blocks per wave along N
@@ -491,7 +492,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     }
     if constexpr (EPI >= 2) {
-      epilogue_reg<EPI, RB, IS2D, YBF16>(a, acc, ri, eo, m0, nw, wm, lane_e);
+      epilogue_reg<EPI, RB, IS2D, YBF16, NI, 0, SYM>(a, acc, ri, eo, m0, nw, wm, lane_e);
     } else {
       EpiOperands<EPI, RB, IS2D> none;
       epilogue<Acc, EPI, RB, IS2D, YBF16, true>(a, acc, smem, ri, none, m0, n0, lane_e, wave, wm, wn);
@@ -512,15 +513,23 @@ int gemm6_workgroups(int tiles) {
   return tiles < cus ? tiles : cus;
 }
 
-template <int EPI, int RB, bool IS2D, bool YBF16>
-hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
+template <int EPI, int RB, bool IS2D, bool YBF16, bool SYM>
+hipError_t launch_k(const GemmArgs& a, hipStream_t st) {
   constexpr size_t lds = (size_t)kNumStage6 * kStage6 + 2 * kRowInfoBytes;
   static size_t lds_done[kStampMaxDevices] = {};
-  hipError_t e = stamp_allow_lds(reinterpret_cast<const void*>(&k_gemm6<EPI, RB, IS2D, YBF16>), lds, lds_done);
+  hipError_t e = stamp_allow_lds(reinterpret_cast<const void*>(&k_gemm6<EPI, RB, IS2D, YBF16, SYM>), lds, lds_done);
   if (e != hipSuccess) return e;
   const int mt = (a.M + BM - 1) / BM, nt = a.Npad / BN6;
-  hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16>), dim3(gemm6_workgroups(mt * nt)), dim3(512), lds, st, a);
+  hipLaunchKernelGGL((k_gemm6<EPI, RB, IS2D, YBF16, SYM>), dim3(gemm6_workgroups(mt * nt)), dim3(512), lds, st, a);
   return hipGetLastError();
+}
+
+template <int EPI, int RB, bool IS2D, bool YBF16>
+hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
+  if constexpr (EPI == 2) {
+    if (!a.g.asym) return launch_k<EPI, RB, IS2D, YBF16, true>(a, st);
+  }
+  return launch_k<EPI, RB, IS2D, YBF16, false>(a, st);
 }
 
 template <int EPI, int RB, bool IS2D>
