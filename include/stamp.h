@@ -144,6 +144,7 @@ typedef struct {
  * (several levels each) over fp32 copies of the activation in the workspace, the quantizer and the GEMM treat the
  * transformed tokens as rows in STaMP order (physical row = STaMP slot), the inverse again runs in passes after the GEMM.
  * Limits of the general path (STAMP_ERR_UNSUPPORTED beyond them): bits 8/4/4; d_in a multiple of 32, at most 32768;
+ * d_out at most 2^21 (both paths);
  * group_size 0 or 64, and 64 needs d_in a multiple of 64 and the symmetric quantizer; seq_len <= 65535, batch <= 65535,
  * batch * k_hi <= 65535 (grid dimensions); DCT: seq_len <= 16384 (a dense seq_len x seq_len matrix).  With group_size =
  * 64 the buffers of stamp_quantize_act / stamp_linear_forward_q are: q_hi [batch, seq_len, d_in] int8 codes of ALL

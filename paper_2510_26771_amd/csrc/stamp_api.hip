@@ -142,6 +142,7 @@ stamp_status_t validate(const stamp_plan_desc_t* d, StampGeom* g, int* fused_ok,
   // ---- valid STaMP settings from here on; what follows is what this library implements ----
   if (d->bits_hi != 8 || d->bits_lo != 4 || d->bits_w != 4) return STAMP_ERR_UNSUPPORTED;
   if (d->d_in % 32 != 0 || d->d_in > 32768) return STAMP_ERR_UNSUPPORTED;  // wider than one workgroup holds: channel splits, two passes
+  if (d->d_out > (1 << 21)) return STAMP_ERR_UNSUPPORTED;  // the GEMM epilogues address a tile's 256 output rows with 32-bit byte offsets
   memset(g, 0, sizeof(*g));
   g->B = d->batch; g->s = d->seq_len; g->d = d->d_in; g->N = d->d_out;
   g->J = d->levels; g->k = g->khi = d->k_hi;

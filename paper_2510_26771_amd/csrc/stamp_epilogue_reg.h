@@ -65,6 +65,18 @@ __device__ __forceinline__ void put_pair(void* Y, size_t idx, float v0, float v1
   }
 }
 
+// The same pair at a 32-bit byte offset from a wave-uniform base (the tile's first output row): the address is the
+// scalar base plus one 32-bit vector offset, no 64-bit vector arithmetic per store.
+template <bool YBF16>
+__device__ __forceinline__ void put_pair_at(char* base, uint32_t byte_off, float v0, float v1) {
+  if constexpr (YBF16) {
+    const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f2){v0, v1}, bf2));  // v_cvt_pk_bf16_f32, RNE
+    __builtin_nontemporal_store(w, reinterpret_cast<uint32_t*>(base + byte_off));  // Y is not read again here
+  } else {
+    __builtin_nontemporal_store((f2){v0, v1}, reinterpret_cast<f2*>(base + byte_off));
+  }
+}
+
 // Operands of the epilogue that come from global memory: requested during the last K step of a tile.
 template <int EPI, int RL>
 struct RegEpiOperands {
@@ -89,18 +101,22 @@ struct RegEpiOperands {
 };
 
 // Where a lane stores the tokens of one block, two neighbouring columns per token.
-template <bool YBF16, bool VEC>
+// B32 (1-D plans): Y is the tile's first output row and base / tok_stride are 32-bit BYTE offsets from it (256 rows
+// of d_out elements: below 2^32 for d_out up to 2^21, which plan creation checks); otherwise element indices into Y.
+template <bool YBF16, bool VEC, bool B32>
 struct RegOut {
+  typedef typename std::conditional<B32, uint32_t, size_t>::type IDX;
   void* Y;
-  size_t base;        // element index of token 0 of the block, first of the two columns
-  size_t tok_stride;  // d_out
-  size_t row_stride;  // 2-D: grid_w * d_out
+  IDX base;           // token 0 of the block, first of the two columns
+  IDX tok_stride;     // d_out
+  IDX row_stride;     // 2-D: grid_w * d_out
   float sw0, sw1;     // weight scales of the two columns
   float off0, off1;   // block sum + bias
   int nvalid;
   // v = the token's signed sum of detail coefficients, still without the weight scale
-  __device__ __forceinline__ void put(size_t idx, float v0, float v1) const {
-    put_pair<YBF16, VEC>(Y, idx, __builtin_fmaf(v0, sw0, off0), __builtin_fmaf(v1, sw1, off1), nvalid);
+  __device__ __forceinline__ void put(IDX idx, float v0, float v1) const {
+    if constexpr (B32) put_pair_at<YBF16>(reinterpret_cast<char*>(Y), idx, __builtin_fmaf(v0, sw0, off0), __builtin_fmaf(v1, sw1, off1));
+    else put_pair<YBF16, VEC>(Y, idx, __builtin_fmaf(v0, sw0, off0), __builtin_fmaf(v1, sw1, off1), nvalid);
   }
 };
 
@@ -111,7 +127,7 @@ template <int RL, int T, int M, int I, typename Out>
 __device__ __forceinline__ void dfs1d_reg(const float (&acc)[4][NI][16], float a0, float a1, const Out& o) {
   using RM = RegMap<RL>;
   if constexpr (M == RL) {
-    o.put(o.base + (size_t)I * o.tok_stride, a0, a1);
+    o.put(o.base + (typename Out::IDX)I * o.tok_stride, a0, a1);
     if constexpr ((I & 7) == 7) __builtin_amdgcn_sched_barrier(0);  // bounds how far stores and their addresses run ahead
   } else {
     constexpr int e = (1 << M) + I;
@@ -126,7 +142,7 @@ template <int RB, int T, int M, int IY, int IX, typename Out>
 __device__ __forceinline__ void dfs2d_reg(const float (&acc)[4][NI][16], float a0, float a1, const Out& o) {
   using RM = RegMap<2 * RB>;
   if constexpr (M == RB) {
-    o.put(o.base + (size_t)IY * o.row_stride + (size_t)IX * o.tok_stride, a0, a1);
+    o.put(o.base + (typename Out::IDX)IY * o.row_stride + (typename Out::IDX)IX * o.tok_stride, a0, a1);
     if constexpr ((IY & 1) && (IX & 1)) __builtin_amdgcn_sched_barrier(0);
   } else {
     constexpr int gl = 1 << M, e0 = IY * gl + IX;
@@ -155,8 +171,8 @@ __device__ __forceinline__ void dfs2d_reg(const float (&acc)[4][NI][16], float a
 // then leaves the sum as it is), then the depth-first inverse.
 template <int RB, bool IS2D, int T, int NB, bool YBF16, bool VEC, bool SYM, int NP>
 __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI][16], const f2 (&P)[NP], f2 bias, f2 cs,
-                                           RegOut<YBF16, VEC>& o, const float* rowfac0, const float* rowz0, int mrow0,
-                                           int n) {
+                                           RegOut<YBF16, VEC, !IS2D>& o, const float* rowfac0, const float* rowz0, int mrow0,
+                                           int n, int m0) {
   if constexpr (T < NB) {
     constexpr int RL = IS2D ? 2 * RB : RB;
     constexpr int R = 1 << RL;
@@ -185,17 +201,18 @@ __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI
       o.off0 = P[T][0] + bias[0];
       o.off1 = P[T][1] + bias[1];
       if constexpr (!IS2D) {
-        o.base = (size_t)mrow * a.N + n;  // token 0 of block j of sequence b is physical row b s + j R
-        dfs1d_reg<RL, T, 0, 0, RegOut<YBF16, VEC>>(acc, 0.0f, 0.0f, o);
+        // token 0 of block j of sequence b is physical row b s + j R; bytes from the tile's first row
+        o.base = ((uint32_t)(mrow - m0) * (uint32_t)a.N + (uint32_t)n) * (uint32_t)(YBF16 ? 2 : 4);
+        dfs1d_reg<RL, T, 0, 0, RegOut<YBF16, VEC, true>>(acc, 0.0f, 0.0f, o);
       } else {
         const int b = mrow / g.s, pr = mrow - b * g.s;
         const int j = pr / g.R;
         const int bi = j / g.G, bj = j - bi * g.G;
         o.base = ((size_t)b * g.s + (size_t)(bi << RB) * g.gridW + (size_t)(bj << RB)) * a.N + n;
-        dfs2d_reg<RB, T, 0, 0, 0, RegOut<YBF16, VEC>>(acc, 0.0f, 0.0f, o);
+        dfs2d_reg<RB, T, 0, 0, 0, RegOut<YBF16, VEC, false>>(acc, 0.0f, 0.0f, o);
       }
     }
-    blocks_reg<RB, IS2D, T + 1, NB, YBF16, VEC, SYM, NP>(a, acc, P, bias, cs, o, rowfac0, rowz0, mrow0, n);
+    blocks_reg<RB, IS2D, T + 1, NB, YBF16, VEC, SYM, NP>(a, acc, P, bias, cs, o, rowfac0, rowz0, mrow0, n, m0);
   }
 }
 
@@ -261,15 +278,22 @@ __device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f 
     // load it believed pending at the end of the tile would make it wait for ALL loads inside the next main loop.
     asm volatile("" ::: "memory");       // no load may sink below the wait
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing but those loads is outstanding (no store was issued yet)
-    RegOut<YBF16, VEC> o;
-    o.Y = a.out;
+    RegOut<YBF16, VEC, !IS2D> o;
     o.sw0 = eo.sw[0];
     o.sw1 = eo.sw[1];
     o.nvalid = nvalid;
-    o.tok_stride = (size_t)a.N;
-    o.row_stride = (size_t)g.gridW * a.N;
+    if constexpr (!IS2D) {
+      constexpr int esize = YBF16 ? 2 : 4;
+      o.Y = reinterpret_cast<char*>(a.out) + (size_t)m0 * a.N * esize;
+      o.tok_stride = (uint32_t)a.N * (uint32_t)esize;
+      o.row_stride = 0;
+    } else {
+      o.Y = a.out;
+      o.tok_stride = (size_t)a.N;
+      o.row_stride = (size_t)g.gridW * a.N;
+    }
     blocks_reg<RB, IS2D, 0, nb, YBF16, VEC, SYM>(a, acc, eo.P, eo.bias, eo.cs, o, s_rowfac + wm * 128 + kg * R, s_rowz + wm * 128 + kg * R,
-                                            m0 + wm * 128 + kg * R, n);
+                                            m0 + wm * 128 + kg * R, n, m0);
   }
 }
 

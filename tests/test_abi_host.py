@@ -76,6 +76,7 @@ def _good(**kw):
     (dict(bits_lo=3), 3),
     (dict(d_in=48), 3),                                       # d_in not a multiple of 32
     (dict(d_in=32800), 3),                                    # wider than the channel splits go
+    (dict(d_out=(1 << 21) + 2), 3),                           # 256 output rows no longer fit 32-bit byte offsets
     (dict(xform=st.STAMP_L_IDENTITY, levels=2), 2),          # no transform has no levels
     (dict(xform=st.STAMP_L_HAAR2D, grid_h=32, grid_w=8, levels=4, k_hi=16), 2),   # more levels than the short side has
     (dict(w_dtype=7), 2),
