@@ -171,6 +171,11 @@ DEEP = [
     _wl("deep_small_m", batch=1, seq_len=64, levels=6, k_hi=1, d_in=3072, d_out=64, seed=135),
     _wl("deep_r8_f32in", batch=2, seq_len=128, levels=7, k_hi=16, d_in=3104, d_out=300, x_dtype="f32", seed=136),
     _wl("deep_r32_odd_steps", batch=2, seq_len=512, levels=9, k_hi=16, d_in=3328, d_out=96, seed=137),
+    # the widest layer the library takes (256 K steps; the exactness argument of the FP6 engine is stated for this depth)
+    _wl("deep_max_width", batch=1, seq_len=64, levels=6, k_hi=8, d_in=32768, d_out=72, seed=138, n_outlier_channels=60,
+        outlier_scale=40.0),
+    _wl("deep_max_width_asym_f32in", batch=1, seq_len=128, levels=7, k_hi=4, d_in=32768, d_out=40, x_dtype="f32", seed=139,
+        act_quant="asym", mean_shift=0.3),
 ]
 
 
