@@ -34,6 +34,15 @@ struct RegMap {
   }
 };
 
+// Four independent swaps in one statement: the wait states are needed once before the first and once after the last
+// (nothing else can come between them).
+__device__ __forceinline__ void swap32x4(float& x0, float& y0, float& x1, float& y1, float& x2, float& y2, float& x3, float& y3) {
+  asm volatile(
+      "s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_permlane32_swap_b32 %2, %3\n\tv_permlane32_swap_b32 %4, %5\n\t"
+      "v_permlane32_swap_b32 %6, %7\n\ts_nop 1"
+      : "+v"(x0), "+v"(y0), "+v"(x1), "+v"(y1), "+v"(x2), "+v"(y2), "+v"(x3), "+v"(y3));
+}
+
 __device__ __forceinline__ void swap32(float& x, float& y) {
   // lanes 32..63 of x <-> lanes 0..31 of y.  Written as an asm statement: the builtin form is treated as
   // rematerialisable, i.e. executed once per result with both inputs kept alive, which doubles the live
@@ -272,7 +281,11 @@ __device__ __forceinline__ void epilogue_reg_impl(const GemmArgs& a, const v16f 
       for (int t = 0; t < nb; ++t)
 #pragma unroll
         for (int e = 0; e < R; ++e)
-          if ((e & 4) == 0) swap32(acc[RM::mi(t, e)][ni][RM::v(t, e)], acc[RM::mi(t, e | 4)][ni][RM::v(t, e | 4)]);
+          if ((e & 7) == 0)  // rows e .. e + 3 against e + 4 .. e + 7
+            swap32x4(acc[RM::mi(t, e)][ni][RM::v(t, e)], acc[RM::mi(t, e + 4)][ni][RM::v(t, e + 4)],
+                     acc[RM::mi(t, e + 1)][ni][RM::v(t, e + 1)], acc[RM::mi(t, e + 5)][ni][RM::v(t, e + 5)],
+                     acc[RM::mi(t, e + 2)][ni][RM::v(t, e + 2)], acc[RM::mi(t, e + 6)][ni][RM::v(t, e + 6)],
+                     acc[RM::mi(t, e + 3)][ni][RM::v(t, e + 3)], acc[RM::mi(t, e + 7)][ni][RM::v(t, e + 7)]);
     // Every load requested before the epilogue (its operands, the next tile's row factors) has to be complete
     // here, stated in a form the compiler's wait-count bookkeeping sees: the uses below sit under branches, and a
     // load it believed pending at the end of the tile would make it wait for ALL loads inside the next main loop.
