@@ -255,7 +255,8 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
 // stream of the stored weights (1 byte per weight, tens of MB) against a few rows, bound by how many bytes are in
 // flight, not by the matrix pipe.  Tile: MB (64 or 128) rows x 128 columns per workgroup of 4 waves (wave w: the 32
 // columns 32 w.., all rows), K step 128, a ring of three stages of MB x 128 + 128 x 128 bytes filled by asynchronous
-// loads two steps ahead, two workgroups per CU, the depth split over several workgroups per tile (partial rows, added
+// loads two steps ahead, two workgroups per CU (one for 128 rows), the depth split over several workgroups per tile
+// (partial rows, added
 // by the consumer as for the large tiles).  Same operand layout in LDS, same fragment order and the same
 // dequantization (EPI 1 of the shared epilogue) as k_gemm<false, 1, ...>: identical results.
 template <int MB>
@@ -443,8 +444,9 @@ bool stamp_hi_wide_tiles(int M, int Npad) {
 }
 
 // Plans without top levels: the dequantized top rows ARE the block sums P of the inverse (the top inverse has
-// nothing to do), so the 8-bit rows' GEMM writes them where the 4-bit rows' epilogue reads them.
-bool stamp_hi_rows_are_block_sums(const stamp_plan* p) { return !p->geom.ident && p->geom.L == 0; }
+// nothing to do), so the 8-bit rows' GEMM writes them where the 4-bit rows' epilogue reads them, unless its depth
+// is split (then the partial rows go through the top inverse like any others: it adds the parts and moves nothing).
+bool stamp_hi_rows_are_block_sums(const stamp_plan* p) { return !p->geom.ident && p->geom.L == 0 && p->hi_ksplit <= 1; }
 
 // The few 8-bit rows make few tiles: when they would leave most CUs idle, the depth of every tile is split
 // over 2..4 workgroups (partial rows, added by the top inverse).
@@ -453,7 +455,7 @@ constexpr int kHiFewRows = 128;
 
 int stamp_hi_ksplit(const stamp_plan* p) {
   const int M = p->geom.B * p->geom.k;
-  if (M == 0 || stamp_hi_rows_are_block_sums(p)) return 1;  // no partial rows when the GEMM writes the block sums itself
+  if (M == 0) return 1;
   if (M <= kHiFewRows) {
     // few rows: enough parts for one workgroup per CU, each with at least four K steps; a part's partial rows cost
     // 8 M d_out bytes of traffic (written here, read by the consumer), which more parts than that do not repay

@@ -12,6 +12,7 @@
 
 namespace {
 
+typedef float f4v __attribute__((ext_vector_type(4)));
 constexpr int kCols = 32;
 constexpr int kStride = kCols + 1;
 constexpr float kInvSqrt2 = 0.70710678118654752440f;
@@ -184,9 +185,37 @@ hipError_t stamp_launch_hi_rows_out(const stamp_plan* p, const float* Yt_hi, voi
   return hipGetLastError();
 }
 
+namespace {
+// plans without top levels, split depth: P[row][n] = sum of the parts' rows (no transform, no reordering)
+__global__ __launch_bounds__(256) void k_sum_parts(const float* __restrict__ src, int nparts, size_t part_stride,
+                                                   float* __restrict__ P, int ldP, int ncols) {
+  const int row = blockIdx.y;
+  const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (n >= ncols) return;
+  const size_t idx = (size_t)row * ncols + n;
+  if (n + 3 < ncols && (ncols & 3) == 0) {
+    f4v v = *reinterpret_cast<const f4v*>(src + idx);
+    for (int part = 1; part < nparts; ++part) v += *reinterpret_cast<const f4v*>(src + idx + part * part_stride);
+    *reinterpret_cast<f4v*>(P + (size_t)row * ldP + n) = v;
+  } else {
+    for (int c = n; c < ncols && c < n + 4; ++c) {
+      float v = src[(size_t)row * ncols + c];
+      for (int part = 1; part < nparts; ++part) v += src[(size_t)row * ncols + c + part * part_stride];
+      P[(size_t)row * ldP + c] = v;
+    }
+  }
+}
+}  // namespace
+
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* src, int src_is_stamp, int ncols, float* P,
                                     int ldP, hipStream_t st, int nparts) {
   const StampGeom& g = p->geom;
+  if (g.L == 0 && !src_is_stamp) {
+    // nothing to invert and the rows are in place already: only the parts of a split depth are added
+    hipLaunchKernelGGL(k_sum_parts, dim3((ncols + 1023) / 1024, g.B * g.k), dim3(256), 0, st, src, nparts,
+                       (size_t)g.B * g.k * (size_t)ncols, P, ldP, ncols);
+    return hipGetLastError();
+  }
   const size_t lds = (size_t)g.k * kStride * sizeof(float);
   hipLaunchKernelGGL(k_inverse_top, dim3((ncols + kCols - 1) / kCols, g.B), dim3(256), lds, st, src,
                      src_is_stamp ? g.s : g.k, src_is_stamp, P, ldP, ncols, g, nparts, (size_t)g.B * g.k * (size_t)ncols);
