@@ -185,10 +185,20 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
   // the boundary falls between waves, so the source tile of a pass is wave-uniform.  Addresses are a
   // wave-uniform base (tile, K step, pass) plus this thread's constant 32-bit offset.
   const uint32_t off16 = (uint32_t)tid * 16u;
-  // cursor of the requests: K step rq_kt of the tile at position rq_pos of this workgroup's walk (all scalar).  The
+  // cursor of the requests: request rq_kt of the tile at position rq_pos of this workgroup's walk (all scalar).  The
   // loads address memory through two buffer descriptors (the tile's activation panel; its two weight panels, KT * 12 KB
   // apart) + a scalar byte offset + this thread's constant 32-bit offset: no vector address arithmetic per load.
-  int rq_pos = local, rq_kt = 0, rq_stg = 0;
+  // K step of a tile's first request.  The workgroups of an XCD that share an operand panel (same row or column of
+  // the XCD's 8 x 4 window of tiles) ask for a line at the same moment when they walk K in step: one misses L2, the
+  // others wait on the same miss.  Started a few K steps apart (every tile walks all KT steps once, from its own
+  // start, wrapping: an fp32 sum of these integers is exact in any order), most of them find the line in L2.
+  int rq_k0;
+  {
+    int tm0_, tn0_;
+    tile_of_sid(first + local, mt, nt, tm0_, tn0_);
+    rq_k0 = (((tm0_ & 7) + 2 * (tn0_ & 3)) & 7) % KT;
+  }
+  int rq_pos = local, rq_kt = 0, rq_stg = 0, rq_kk = rq_k0;  // rq_kt counts the tile's requests, rq_kk is their K step
   __amdgpu_buffer_rsrc_t rdA, rdB;
   auto rq_tile = [&]() {
     int tm_, tn_;
@@ -220,8 +230,9 @@ __global__ __launch_bounds__(512, 1) void k_gemm6(const GemmArgs a) {
       }
     }
     rq_so = smem + rq_stg * kStage6 + wave * 1024;
-    rq_oa = (uint32_t)rq_kt * (uint32_t)kStageA6;
-    rq_ob = (uint32_t)rq_kt * (uint32_t)kStageB6;
+    rq_oa = (uint32_t)rq_kk * (uint32_t)kStageA6;
+    rq_ob = (uint32_t)rq_kk * (uint32_t)kStageB6;
+    rq_kk = (rq_kk == KT - 1) ? 0 : rq_kk + 1;
     rq_stg = (rq_stg == kNumStage6 - 1) ? 0 : rq_stg + 1;
     ++rq_kt;
   };
