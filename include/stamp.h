@@ -58,7 +58,9 @@
  *               (((m / 256) * (Kp / 128) + c / 128) * 256 + m % 256) * 64 + (c % 128) / 2,
  *             i.e. [Mp/256][Kp/128][256 rows][64 bytes]; the buffer holds Mp * Kp / 2 bytes.
  *             Rows r with r % R == 0 (the rows whose coefficient lives in q_hi), rows >= batch *
- *             seq_len and channels >= d_in are never written and their content is ignored.
+ *             seq_len and channels >= d_in need not be filled: stamp_linear_forward_q ignores their
+ *             content.  (stamp_quantize_act may write rows r % R == 0: it puts the packed form of the
+ *             4-bit approximations there as well, for stamp_linear_forward's own use.)
  */
 #ifndef STAMP_H_
 #define STAMP_H_

@@ -305,10 +305,12 @@ __device__ __forceinline__ void flush_rows(float (&rowv)[NR][8], MetaFn meta, in
 // Plans without top levels: the block sum, times the norm of the blocks' level, is STaMP slot j.  The whole
 // workgroup reduces its range over the channels and quantizes it like any other top row: 8 bits for the first
 // khi slots, 4-bit codes held as int8 beyond.  Called after the last streaming step (no loads in flight).
+// The 4-bit ones also go, packed like every other 4-bit row, to the block's row 0 of q_lo (q_lo_row: this thread's
+// word of it), which no other coefficient uses: the 4-bit rows' GEMM can then take the block sum from its own rows.
 template <bool IS2D, bool ASYM>
 __device__ __forceinline__ void finish_top_row(const float (&top)[8], int level, uint32_t* part /* >= 32 words, free */,
-                                               int8_t* q_hi_row, float* scale_out, size_t zeros_off, bool row8,
-                                               bool active, int tid) {
+                                               int8_t* q_hi_row, uint8_t* q_lo_row, float* scale_out, size_t zeros_off,
+                                               bool row8, bool active, int tid) {
   const int lane = tid & 63, wave = tid >> 6, nw = (int)(blockDim.x >> 6);
   const float nrm = IS2D ? ldexpf(1.0f, -level) : haar_norm(level);
   float t[8];
@@ -343,14 +345,18 @@ __device__ __forceinline__ void finish_top_row(const float (&top)[8], int level,
     if constexpr (ASYM) scale_out[zeros_off] = z;
   }
   const float qlo = ASYM ? 0.0f : -qmax, qhi = qmax, shift = ASYM ? (row8 ? 128.0f : 8.0f) : 0.0f;
-  uint32_t w[2] = {0u, 0u};
+  uint32_t w[2] = {0u, 0u}, w4 = 0u;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     float q = __fadd_rn(rintf(__fmul_rn(t[i], inv)), z);
     q = fminf(fmaxf(q, qlo), qhi) - shift;
     w[i >> 2] |= ((uint32_t)((int)q) & 0xFFu) << (8 * (i & 3));
+    w4 |= ((uint32_t)((int)q) & 0xFu) << (4 * i);
   }
-  if (active) *reinterpret_cast<uint2*>(q_hi_row) = make_uint2(w[0], w[1]);
+  if (active) {
+    *reinterpret_cast<uint2*>(q_hi_row) = make_uint2(w[0], w[1]);
+    if (!row8) *reinterpret_cast<uint32_t*>(q_lo_row) = w4;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -546,8 +552,8 @@ __global__ __launch_bounds__(1024) void k_bottom1d(const void* __restrict__ X, u
   if constexpr (PASS == 0) {
     if (sp.q_hi != nullptr) {
       // s_max[R/4 & 1] was last used two steps ago: every thread has passed a barrier since
-      finish_top_row<false, ASYM>(top, RLOG, &s_max[(R / 4) & 1][0], sp.q_hi + ((size_t)b * k + j) * d + c0, scales + row0,
-                                  zeros_off, j < sp.khi, active, tid);
+      finish_top_row<false, ASYM>(top, RLOG, &s_max[(R / 4) & 1][0], sp.q_hi + ((size_t)b * k + j) * d + c0,
+                                  q_lo + stamp_qlo_offset(row0, 0, Kpad) + q_off, scales + row0, zeros_off, j < sp.khi, active, tid);
       return;
     }
   }
@@ -694,8 +700,8 @@ __global__ __launch_bounds__(512) void k_bottom2d(const void* __restrict__ X, ui
   if constexpr (PASS == 0) {
     if (sp.q_hi != nullptr) {
       constexpr int nsteps = (g == 4) ? 1 : 4;
-      finish_top_row<true, ASYM>(top, RLOG, &s_max[nsteps & 1][0], sp.q_hi + ((size_t)b * k + j) * d + c0, scales + prow0,
-                                 zeros_off, j < sp.khi, active, tid);
+      finish_top_row<true, ASYM>(top, RLOG, &s_max[nsteps & 1][0], sp.q_hi + ((size_t)b * k + j) * d + c0,
+                                 q_lo + stamp_qlo_offset(prow0, c0, Kpad), scales + prow0, zeros_off, j < sp.khi, active, tid);
       return;
     }
   }
@@ -812,7 +818,7 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
 __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop, const uint32_t* __restrict__ rowmax_part,
                                                   int nslices, int8_t* __restrict__ q_hi, float* __restrict__ scales,
                                                   int k, int khi, int d, int s, int R, int asym, size_t npart,
-                                                  size_t zeros_off) {
+                                                  size_t zeros_off, uint8_t* __restrict__ q_lo, int Kpad) {
   __shared__ uint32_t s_red[8];
   const int p = blockIdx.x, b = blockIdx.y;
   {
@@ -852,14 +858,18 @@ __global__ __launch_bounds__(256) void k_quant_hi(const float* __restrict__ ttop
   for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
     const float4 t = *reinterpret_cast<const float4*>(src + c);
     const float v[4] = {t.x, t.y, t.z, t.w};
-    uint32_t w = 0;
+    uint32_t w = 0, w4 = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float q = __fadd_rn(rintf(__fmul_rn(v[i], inv)), z);
       q = fminf(fmaxf(q, qlo), qhi) - shift;
       w |= ((uint32_t)((int)q) & 0xFFu) << (8 * i);
+      w4 |= ((uint32_t)((int)q) & 0xFu) << (4 * i);
     }
     *reinterpret_cast<uint32_t*>(dst + c) = w;
+    // plans without top levels: a 4-bit row also goes, packed, to its block's row 0 of q_lo (see finish_top_row)
+    if (q_lo != nullptr && !row8)
+      *reinterpret_cast<uint16_t*>(q_lo + stamp_qlo_offset((size_t)b * s + (size_t)p * R, c, Kpad)) = (uint16_t)w4;
   }
 }
 
@@ -1075,6 +1085,6 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_quant_hi, dim3(g.k, g.B), dim3(256), 0, st, abot, rowmax, nslices, q_hi, scales, g.k, g.khi, g.d, g.s, g.R,
-                     g.asym, npart, zeros_off);
+                     g.asym, npart, zeros_off, g.L == 0 ? q_lo : nullptr, p->Kpad);
   return hipGetLastError();
 }

@@ -220,7 +220,11 @@ void layout_workspace(stamp_plan* p) {
   p->ws_qhi = take((size_t)g.B * g.k * g.d);
   p->ws_qlo = take((size_t)p->Mpad * (p->Kpad / 2));
   p->ws_scales = take((size_t)2 * g.B * g.s * sizeof(float));  // scales, then offsets (asymmetric plans)
-  p->ws_ythi = take((size_t)p->hi_ksplit * g.B * g.k * g.N * sizeof(float));  // partial rows per part of a split depth
+  {
+    // partial rows per part of a split depth, for either set of rows the 8-bit rows' GEMM may be run over
+    const size_t all = (size_t)p->hi_ksplit * g.k, own = (size_t)p->hi_ksplit_own * g.khi;
+    p->ws_ythi = take((all > own ? all : own) * g.B * g.N * sizeof(float));
+  }
   p->ws_P = take((size_t)g.B * g.k * p->Npad * sizeof(float));
   p->ws_a6 = take(stamp_a6_bytes(p));
   p->ws_ytlo = off;
@@ -235,8 +239,28 @@ inline bool ws_ok(const stamp_plan* p, const void* ws, size_t bytes, size_t need
 
 inline uint8_t* at(void* ws, size_t off) { return reinterpret_cast<uint8_t*>(ws) + off; }
 
+// Plans without top levels that keep only some of the block sums at 8 bits (0 < khi < k), default route (FP6
+// engine, fused inverse): the 4-bit block sums are rows of the 4-bit rows' GEMM (the quantizer has put their packed
+// codes at coefficient 0 of their blocks), and the 8-bit rows' GEMM runs over the first khi rows of every sequence only.
+inline bool own_top(const stamp_plan* p) {
+  const StampGeom& g = p->geom;
+  return p->gen.kind == kGenNone && !g.ident && g.L == 0 && g.khi > 0 && g.khi < g.k && p->engine == STAMP_GEMM_FP6 &&
+         p->fused_ok && !p->unfused;
+}
+
+// block sums of the first khi blocks of every sequence -> P [B * khi][Npad]
+inline hipError_t stamp_launch_block_sums_own(const stamp_plan* p, const int8_t* q_hi, const float* scales, float* ythi,
+                                              float* P, hipStream_t st) {
+  if (p->hi_ksplit_own <= 1) return stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad, true);
+  const hipError_t e = stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st, 0, true);
+  if (e != hipSuccess) return e;
+  return stamp_launch_sum_parts(ythi, p->hi_ksplit_own, p->geom.B * p->geom.khi, p->geom.N, P, p->Npad, st);
+}
+
+// codes_are_ours: q_hi / q_lo were written by this library's quantizer (which also fills the rows of q_lo that
+// own_top reads); buffers a caller packed need not hold them
 stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t* q_lo, const float* scales, void* Y,
-                         void* ws, hipStream_t st) {
+                         void* ws, hipStream_t st, bool codes_are_ours) {
   float* ythi = reinterpret_cast<float*>(at(ws, p->ws_ythi));
   float* P = reinterpret_cast<float*>(at(ws, p->ws_P));
   if (p->gen.kind != kGenNone) {
@@ -279,18 +303,21 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
     }
     return stamp_launch_gemm_lo(p, q_lo, scales, 3, Y, nullptr, st) == hipSuccess ? STAMP_OK : STAMP_ERR_DEVICE;
   }
-  if (stamp_hi_rows_are_block_sums(p)) {
+  const bool fused = p->fused_ok && !p->unfused;
+  const bool own = codes_are_ours && own_top(p);
+  if (own) {
+    if (stamp_launch_block_sums_own(p, q_hi, scales, ythi, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
+  } else if (stamp_hi_rows_are_block_sums(p)) {
     if (stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad) != hipSuccess) return STAMP_ERR_DEVICE;
   } else {
     if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
     if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit) != hipSuccess) return STAMP_ERR_DEVICE;
   }
-  const bool fused = p->fused_ok && !p->unfused;
   float* ytlo = reinterpret_cast<float*>(at(ws, p->ws_ytlo));
   if (p->engine == STAMP_GEMM_FP6) {
     uint8_t* a6 = at(ws, p->ws_a6);
     if (stamp_launch_repack6(p, q_lo, a6, st) != hipSuccess) return STAMP_ERR_DEVICE;
-    if (stamp_launch_gemm_lo6(p, a6, scales, fused ? 2 : 1, fused ? Y : ytlo, fused ? P : nullptr, st) != hipSuccess)
+    if (stamp_launch_gemm_lo6(p, a6, scales, fused ? 2 : 1, fused ? Y : ytlo, fused ? P : nullptr, st, own) != hipSuccess)
       return STAMP_ERR_DEVICE;
   } else {
     if (stamp_launch_gemm_lo(p, q_lo, scales, fused ? 2 : 1, fused ? Y : ytlo, fused ? P : nullptr, st) != hipSuccess)
@@ -352,7 +379,8 @@ stamp_status_t stamp_plan_create(const stamp_plan_desc_t* desc, const void* W_de
   p->Kpad = ((g.d + 127) / 128) * 128;
   p->Npad = ((g.N + 255) / 256) * 256;
   p->Mpad = ((g.B * g.s + 255) / 256) * 256;
-  p->hi_ksplit = gen.group ? 1 : stamp_hi_ksplit(p);
+  p->hi_ksplit = gen.group ? 1 : stamp_hi_ksplit(p, g.k);
+  p->hi_ksplit_own = gen.group ? 1 : stamp_hi_ksplit(p, g.khi);
   layout_workspace(p);
 
   // physical row of every STaMP slot
@@ -474,7 +502,7 @@ stamp_status_t stamp_linear_forward_q(const stamp_plan_t* p, const int8_t* q_hi,
   if (p == nullptr || q_hi == nullptr || scales == nullptr || Y == nullptr) return STAMP_ERR_NULL;
   if (q_lo == nullptr && !p->gen.group) return STAMP_ERR_NULL;
   if (!ws_ok(p, ws, ws_bytes, p->ws_total)) return STAMP_ERR_WORKSPACE;
-  return forward_q(p, q_hi, q_lo, scales, Y, ws, reinterpret_cast<hipStream_t>(hip_stream));
+  return forward_q(p, q_hi, q_lo, scales, Y, ws, reinterpret_cast<hipStream_t>(hip_stream), false);
 }
 
 stamp_status_t stamp_linear_forward(const stamp_plan_t* p, const void* X, void* Y, void* ws, size_t ws_bytes,
@@ -491,13 +519,13 @@ stamp_status_t stamp_linear_forward(const stamp_plan_t* p, const void* X, void* 
       scales = reinterpret_cast<float*>(at(ws, p->ws_scalesg));
     }
     const stamp_status_t qs = gen_quantize(p, X, q_hi, q_lo, scales, ws, st);
-    return qs != STAMP_OK ? qs : forward_q(p, q_hi, q_lo, scales, Y, ws, st);
+    return qs != STAMP_OK ? qs : forward_q(p, q_hi, q_lo, scales, Y, ws, st, true);
   }
   hipError_t e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, reinterpret_cast<float*>(at(ws, p->ws_abot)),
                                        reinterpret_cast<uint32_t*>(at(ws, p->ws_rowmax)),
                                        reinterpret_cast<uint32_t*>(at(ws, p->ws_gpart)), st);
   if (e != hipSuccess) return STAMP_ERR_DEVICE;
-  return forward_q(p, q_hi, q_lo, scales, Y, ws, st);
+  return forward_q(p, q_hi, q_lo, scales, Y, ws, st, true);
 }
 
 stamp_status_t stamp_linear_forward_static(const stamp_plan_t* p, const void* X, void* Y, void* hip_stream) {
@@ -591,15 +619,19 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
     case 0: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 1); break;
     case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 2); break;
     case 2:
-      e = stamp_hi_rows_are_block_sums(p) ? stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad)
-                                          : stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st);
+      if (own_top(p)) e = stamp_launch_block_sums_own(p, q_hi, scales, ythi, P, st);
+      else
+        e = stamp_hi_rows_are_block_sums(p) ? stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad)
+                                            : stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st);
       break;
     case 3:  // nothing to launch when the plan has no top levels
-      if (!stamp_hi_rows_are_block_sums(p)) e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit);
+      if (!own_top(p) && !stamp_hi_rows_are_block_sums(p))
+        e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit);
       break;
     case 4:
       if (p->engine == STAMP_GEMM_FP6)
-        e = stamp_launch_gemm_lo6(p, at(ws, p->ws_a6), scales, fused ? 2 : 1, fused ? Y : (void*)ytlo, fused ? P : nullptr, st);
+        e = stamp_launch_gemm_lo6(p, at(ws, p->ws_a6), scales, fused ? 2 : 1, fused ? Y : (void*)ytlo, fused ? P : nullptr, st,
+                                  own_top(p));
       else
         e = stamp_launch_gemm_lo(p, q_lo, scales, fused ? 2 : 1, fused ? Y : (void*)ytlo, fused ? P : nullptr, st);
       break;

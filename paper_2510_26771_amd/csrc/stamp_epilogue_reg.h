@@ -103,7 +103,11 @@ struct RegEpiOperands {
 #pragma unroll
       for (int t = 0; t < nb; ++t) {
         const int mrow = min(m0 + wm * 128 + (2 * t + kg) * R, a.M - 1);
-        P[t] = *reinterpret_cast<const f2*>(a.P + (size_t)(mrow / R) * a.Npad + n);
+        // P holds the first pk block sums of every sequence (all k of them unless the blocks beyond khi carry their
+        // own, see blocks_reg); blocks beyond read a row that is there and is not used
+        const int blk = mrow / R, pk = a.own_top ? a.g.khi : a.g.k;
+        const int b = blk / a.g.k, j = blk - b * a.g.k;
+        P[t] = *reinterpret_cast<const f2*>(a.P + (size_t)(b * pk + min(j, pk - 1)) * a.Npad + n);
       }
     }
   }
@@ -207,8 +211,11 @@ __device__ __forceinline__ void blocks_reg(const GemmArgs& a, float (&acc)[4][NI
         // keeps the factor reads of later groups from being hoisted (they would all be live at once)
         if ((e4 & 12) == 12) __builtin_amdgcn_sched_barrier(0);
       }
-      o.off0 = P[T][0] + bias[0];
-      o.off1 = P[T][1] + bias[1];
+      // The block sum comes from the 8-bit rows' GEMM (P), or - plans without top levels, blocks from khi on, marked
+      // in the row table - it is the block's own coefficient 0, dequantized above like every other row.
+      const bool own = reinterpret_cast<const int*>(rowfac0)[256 + 2 * T * R] == 1;
+      o.off0 = (own ? acc[RM::mi(T, 0)][0][RM::v(T, 0)] * o.sw0 : P[T][0]) + bias[0];
+      o.off1 = (own ? acc[RM::mi(T, 0)][1][RM::v(T, 0)] * o.sw1 : P[T][1]) + bias[1];
       if constexpr (!IS2D) {
         // token 0 of block j of sequence b is physical row b s + j R; bytes from the tile's first row
         o.base = ((uint32_t)(mrow - m0) * (uint32_t)a.N + (uint32_t)n) * (uint32_t)(YBF16 ? 2 : 4);

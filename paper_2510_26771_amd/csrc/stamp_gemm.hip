@@ -25,6 +25,9 @@ using namespace stamp_gemm;
 
 // WN = waves along N: 2 -> 4 waves, tile 256 x 128, two workgroups per CU; 4 -> 8 waves, tile 256 x 256,
 // one workgroup per CU (fewer, larger tiles: for the few 8-bit rows, whose whole GEMM is one round of tiles).
+// 8-bit rows: row of A that row m of the GEMM multiplies (the first a_seq_used of every sequence's a_seq_rows)
+__device__ __forceinline__ int a_row_of(const GemmArgs& a, int m) { return m + (m / a.a_seq_used) * (a.a_seq_rows - a.a_seq_used); }
+
 template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16, int WN>
 __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const GemmArgs a_in) {
   GemmArgs a = a_in;
@@ -83,11 +86,11 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
     if constexpr (A_INT4) {
       offA[i] = (uint32_t)((rowA0 + i * rowsPerPassA) * 64 + koffA);
     } else {
-      offA[i] = (uint32_t)(min(m0 + rowA0 + i * rowsPerPassA, a.M - 1) - m0) * (uint32_t)a.a_row_bytes + koffA;
+      offA[i] = (uint32_t)(a_row_of(a, min(m0 + rowA0 + i * rowsPerPassA, a.M - 1)) - a_row_of(a, m0)) * (uint32_t)a.a_row_bytes + koffA;
     }
   }
   if constexpr (A_INT4) baseGA += (size_t)tm * KT * (256 * 64);
-  else baseGA += (size_t)m0 * a.a_row_bytes;
+  else baseGA += (size_t)a_row_of(a, m0) * a.a_row_bytes;
   // byte offset (from baseGA) of the last 16-byte chunk that may be read
   const size_t lastA = a.a_last16 - (size_t)(baseGA - a.A);
   const int colB0 = tid >> 3, slotB = tid & 7;
@@ -284,7 +287,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_hi_few(const GemmArgs a_in) {
   const uint32_t kofs = (uint32_t)((slot ^ ((rowA0 >> 1) & 7)) * 16);
   uint32_t offA[nA], offB[nB];
 #pragma unroll
-  for (int i = 0; i < nA; ++i) offA[i] = (uint32_t)min(rowA0 + i * (NT / 8), a.M - 1) * (uint32_t)a.a_row_bytes + kofs;
+  for (int i = 0; i < nA; ++i) offA[i] = (uint32_t)a_row_of(a, min(rowA0 + i * (NT / 8), a.M - 1)) * (uint32_t)a.a_row_bytes + kofs;
 #pragma unroll
   for (int i = 0; i < nB; ++i) offB[i] = (uint32_t)((rowA0 + i * (NT / 8)) * 128) + kofs;
   const uint8_t* baseGB = a.Bq + stamp_w_offset(n0, 0, a.Kpad);
@@ -453,8 +456,8 @@ bool stamp_hi_rows_are_block_sums(const stamp_plan* p) { return !p->geom.ident &
 // at most this many 8-bit rows over the whole batch: the kernel for few rows
 constexpr int kHiFewRows = 128;
 
-int stamp_hi_ksplit(const stamp_plan* p) {
-  const int M = p->geom.B * p->geom.k;
+int stamp_hi_ksplit(const stamp_plan* p, int rows_per_seq) {
+  const int M = p->geom.B * rows_per_seq;
   if (M == 0) return 1;
   if (M <= kHiFewRows) {
     // few rows: enough parts for one workgroup per CU, each with at least four K steps; a part's partial rows cost
@@ -495,11 +498,13 @@ stamp_gemm::GemmArgs stamp_gemm_args(const stamp_plan* p, const float* scales, v
   a.ld_out = p->geom.N;
   a.ksplit = 1;
   a.split_stride = 0;
+  a.a_seq_rows = a.a_seq_used = 1;
+  a.own_top = 0;
   return a;
 }
 
 hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode, void* out,
-                                hipStream_t st, int ld_out) {
+                                hipStream_t st, int ld_out, bool first_khi_only) {
   GemmArgs a = stamp_gemm_args(p, scales, out);
   a.A = reinterpret_cast<const uint8_t*>(q_hi);
   a.M = p->geom.B * p->geom.k;
@@ -509,6 +514,14 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
   if (mode == 1) {
     if (ld_out > 0) a.ld_out = ld_out;
     a.ksplit = p->hi_ksplit;
+    if (first_khi_only) {
+      // the kernels see a plan of khi top rows per sequence; only the rows of A keep their places
+      a.a_seq_rows = p->geom.k;
+      a.a_seq_used = p->geom.khi;
+      a.g.k = p->geom.khi;
+      a.M = p->geom.B * p->geom.khi;
+      a.ksplit = p->hi_ksplit_own;
+    }
     a.split_stride = (size_t)a.M * a.N;
     if (a.M <= 64) return launch_hi_few<64>(a, st);
     if (a.M <= kHiFewRows) return launch_hi_few<128>(a, st);

@@ -571,12 +571,13 @@ hipError_t stamp_launch_repack6(const stamp_plan* p, const uint8_t* q_lo, uint8_
 }
 
 hipError_t stamp_launch_gemm_lo6(const stamp_plan* p, const uint8_t* a6, const float* scales, int mode, void* out,
-                                 const float* P, hipStream_t st) {
+                                 const float* P, hipStream_t st, int own_top) {
   GemmArgs a = stamp_gemm_args(p, scales, out);
   a.A = a6;
   a.Bq = p->qW6_dev;
   a.M = p->geom.B * p->geom.s;
   a.P = P;
+  a.own_top = (mode == 2) ? own_top : 0;
   if (mode == 0) return launch<0, 0, false>(a, st);
   if (mode == 1) return launch<1, 0, false>(a, st);
   if (mode == 3) return launch<3, 0, false>(a, st);

@@ -57,6 +57,10 @@ struct GemmArgs {
   int ld_out;            // dequantized mode (EPI 1): floats between consecutive rows of `out`
   int ksplit;            // 8-bit rows, dequantized mode: the depth is split over this many workgroups per tile,
   size_t split_stride;   // each writing its partial rows to out + split * split_stride (floats)
+  int a_seq_rows;        // 8-bit rows: rows every sequence has in A, and how many of them (the first ones) this
+  int a_seq_used;        // GEMM multiplies: row m of the GEMM is row m + (m / a_seq_used) (a_seq_rows - a_seq_used) of A
+  int own_top;           // 4-bit rows, fused mode: coefficient 0 of the blocks from g.khi on is a 4-bit row of A (see
+                         // compute_row_info); P then holds g.khi rows per sequence
   StampGeom g;
 };
 
@@ -295,8 +299,11 @@ __device__ __forceinline__ void compute_row_info(const GemmArgs& a, int m0, int 
     if constexpr (Acc::kLoRows) {
       const int b = m / g.s, pr = m - b * g.s;
       const int j = pr / g.R, e = pr - j * g.R;
-      if (e != 0) {
-        const int level = g.is2d ? stamp_level_of_e_2d(e, g.r) : stamp_level_of_e_1d(e, g.r);
+      // own_top (plans without top levels, 1-D): the block sums beyond the first khi are 4-bit rows like any other and
+      // sit at coefficient 0 of their block, level = that of the whole block; dst 1 marks them for the epilogue
+      const bool own = e == 0 && a.own_top != 0 && j >= g.khi;
+      if (e != 0 || own) {
+        const int level = own ? g.r : (g.is2d ? stamp_level_of_e_2d(e, g.r) : stamp_level_of_e_1d(e, g.r));
         if constexpr (EPI != 0) {
           fac = a.scales[m] * haar_norm_dev(level, g.is2d) * Acc::kToAcc;
           if (g.asym) rz = (a.scales[zeros_off + m] - Acc::kZeroShift) * (1.0f / Acc::kToAcc);
@@ -305,7 +312,7 @@ __device__ __forceinline__ void compute_row_info(const GemmArgs& a, int m0, int 
           const int p = g.is2d ? stamp_slot_of_block_e_2d(j / g.G, j % g.G, e, g.G) : stamp_slot_of_block_e_1d(j, e, g.k);
           dst = b * g.s + p;
         } else {
-          dst = m;
+          dst = own ? 1 : m;
         }
       }
     } else {

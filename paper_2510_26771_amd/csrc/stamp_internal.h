@@ -145,6 +145,7 @@ struct stamp_plan {
   uint8_t* qW6_dev;         // the same weight codes as E2M3 numbers in the operand layout of the FP6 GEMM
   int32_t engine;           // matrix pipeline of the 4-bit rows' GEMM: STAMP_GEMM_INT8 or STAMP_GEMM_FP6
   int32_t hi_ksplit;        // parts the depth of the 8-bit rows' GEMM is split into (partial rows in the workspace)
+  int32_t hi_ksplit_own;    // the same when only the first khi top rows go through that GEMM (stamp_own_top)
   int32_t unfused;          // 1: separate inverse kernel
   int32_t fused_ok;         // shape allows the fused epilogue
   StampGen gen;             // general path (kind != kGenNone)
@@ -191,10 +192,14 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
 // [hi_ksplit][B*k, N] partial rows, lo -> Yt_lo [B*s, N] physical rows), 2 = lo rows with fused in-block inverse -> Y,
 // 3 = lo rows of an identity plan: dequantized + bias -> Y.
 bool stamp_hi_wide_tiles(int M, int Npad);
-int stamp_hi_ksplit(const stamp_plan* p);
+int stamp_hi_ksplit(const stamp_plan* p, int rows_per_seq);
 // ld_out > 0 (mode 1): row stride of `out` in floats instead of d_out
+// first_khi_only (mode 1): only the first khi rows of every sequence are multiplied, depth split into
+// hi_ksplit_own parts, rows of `out` numbered b * khi + p
 hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const float* scales, int mode,
-                                void* out, hipStream_t st, int ld_out = 0);
+                                void* out, hipStream_t st, int ld_out = 0, bool first_khi_only = false);
+// P[row][0..ncols) = sum over the parts of src[part][row][0..ncols), rows < nrows
+hipError_t stamp_launch_sum_parts(const float* src, int nparts, int nrows, int ncols, float* P, int ldP, hipStream_t st);
 bool stamp_hi_rows_are_block_sums(const stamp_plan* p);
 hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const float* scales, int mode,
                                 void* out, const float* P, hipStream_t st);
@@ -204,8 +209,10 @@ size_t stamp_a6_bytes(const stamp_plan* p);
 size_t stamp_b6_bytes(const stamp_plan* p);
 hipError_t stamp_launch_weight_quant6(const stamp_plan* p, const float* W, const uint32_t* colmax, hipStream_t st);
 hipError_t stamp_launch_repack6(const stamp_plan* p, const uint8_t* q_lo, uint8_t* a6, hipStream_t st);
+// own_top (mode 2, plans without top levels): the blocks from khi on take their sum from their own coefficient 0,
+// a 4-bit row of a6 like any other (the quantizer writes it there as well), and P holds khi rows per sequence
 hipError_t stamp_launch_gemm_lo6(const stamp_plan* p, const uint8_t* a6, const float* scales, int mode, void* out,
-                                 const float* P, hipStream_t st);
+                                 const float* P, hipStream_t st, int own_top = 0);
 // identity plans: 8-bit rows' dequantized partial rows [nparts][B*k][N] (+ bias) -> Y rows of tokens 0..k-1
 hipError_t stamp_launch_hi_rows_out(const stamp_plan* p, const float* Yt_hi, void* Y, hipStream_t st, int nparts);
 // P: block sums [B*k][ldP]; nparts partial sources (each B*k*ncols floats apart) are added while reading

@@ -207,14 +207,18 @@ __global__ __launch_bounds__(256) void k_sum_parts(const float* __restrict__ src
 }
 }  // namespace
 
+hipError_t stamp_launch_sum_parts(const float* src, int nparts, int nrows, int ncols, float* P, int ldP, hipStream_t st) {
+  hipLaunchKernelGGL(k_sum_parts, dim3((ncols + 1023) / 1024, nrows), dim3(256), 0, st, src, nparts,
+                     (size_t)nrows * (size_t)ncols, P, ldP, ncols);
+  return hipGetLastError();
+}
+
 hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* src, int src_is_stamp, int ncols, float* P,
                                     int ldP, hipStream_t st, int nparts) {
   const StampGeom& g = p->geom;
   if (g.L == 0 && !src_is_stamp) {
     // nothing to invert and the rows are in place already: only the parts of a split depth are added
-    hipLaunchKernelGGL(k_sum_parts, dim3((ncols + 1023) / 1024, g.B * g.k), dim3(256), 0, st, src, nparts,
-                       (size_t)g.B * g.k * (size_t)ncols, P, ldP, ncols);
-    return hipGetLastError();
+    return stamp_launch_sum_parts(src, nparts, g.B * g.k, ncols, P, ldP, st);
   }
   const size_t lds = (size_t)g.k * kStride * sizeof(float);
   hipLaunchKernelGGL(k_inverse_top, dim3((ncols + kCols - 1) / kCols, g.B), dim3(256), lds, st, src,

@@ -119,6 +119,14 @@ FEWER_HI = [
         d_out=128, corr_len=6.0, seed=60),
     _wl("few_2d_J3_k3_asym", batch=2, seq_len=4096, xform="haar2d", levels=3, grid_h=64, grid_w=64, k_hi=3, d_in=64,
         d_out=72, corr_len=8.0, seed=66, act_quant="asym", mean_shift=-0.5),
+    # more 8-bit rows over the batch than the few-rows kernel takes, and more than one tile of them
+    _wl("few_1d_J3_k70_b3", batch=3, seq_len=1024, levels=3, k_hi=70, d_in=192, d_out=264, seed=67),
+    _wl("few_1d_J4_k100_b4_asym", batch=4, seq_len=2048, levels=4, k_hi=100, d_in=128, d_out=136, seed=68,
+        act_quant="asym", mean_shift=0.3),
+    # channels split over workgroups: the top rows are quantized by the separate kernel
+    _wl("few_1d_J3_k9_wide", batch=2, seq_len=256, levels=3, k_hi=9, d_in=4128, d_out=64, seed=69, x_dtype="f32"),
+    _wl("few_2d_J2_k7_wide_asym", batch=1, seq_len=256, xform="haar2d", levels=2, grid_h=16, grid_w=16, k_hi=7,
+        d_in=4128, d_out=72, corr_len=4.0, seed=70, act_quant="asym", mean_shift=0.2),
 ]
 PARTIAL = PARTIAL + FEWER_HI
 
