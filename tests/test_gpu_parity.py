@@ -270,6 +270,31 @@ def test_random_valid_plans(seed):
     assert r["code_mismatches"] == 0
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_plans_with_4bit_approximations(seed):
+    """Seeded sweep over the plans without top levels whose 8-bit tokens are fewer than the approximations (the
+    paper's language-model setting): the 4-bit approximations go through the 4-bit rows' GEMM as row 0 of their block,
+    the 8-bit rows' GEMM over the first k_hi rows of every sequence (few-rows and tiled kernels, split depth or not,
+    one or several sequences, channel splits of the transform kernel)."""
+    rng = np.random.default_rng(7000 + seed)
+    d_in = int(rng.choice([32, 96, 160, 512, 1024, 2080, 4128, 4608]))
+    kw = dict(batch=int(rng.integers(1, 5)), d_in=d_in, d_out=int(rng.integers(1, 300)) * 2, seed=8000 + seed,
+              x_dtype=str(rng.choice(["bf16", "f32"])), act_quant=str(rng.choice(["sym", "asym"])),
+              mean_shift=float(rng.choice([0.0, 0.5, -1.0])), n_outlier_channels=int(rng.integers(0, 4)), outlier_scale=25.0)
+    if rng.random() < 0.6:
+        r = int(rng.integers(3, 7))
+        lk = int(rng.integers(1, 8 if d_in <= 1024 else 6))
+        w = _wl(f"few{seed}_1d_J{r}", xform="haar1d", seq_len=(1 << r) << lk, k_hi=int(rng.integers(1, 1 << lk)), levels=r, **kw)
+    else:
+        r = int(rng.integers(2, 4))
+        lg = int(rng.integers(1, 4 if r == 2 else 3))
+        side = (1 << r) << lg
+        w = _wl(f"few{seed}_2d_J{r}", xform="haar2d", seq_len=side * side, grid_h=side, grid_w=side,
+                k_hi=int(rng.integers(1, 1 << (2 * lg))), levels=r, corr_len=4.0, **kw)
+    res = tl.full_case(w, with_bias=bool(seed & 1), y_dtype=("bf16" if seed % 3 == 0 else "f32"), check_unfused=(seed % 4 == 0))
+    assert res["code_mismatches"] == 0
+
+
 @pytest.mark.parametrize("case", ["1d", "2d_asym", "1d_fewer_hi"])
 def test_forward_q_from_buffers_packed_on_the_host(case):
     """stamp_linear_forward_q on code / scale buffers that the HOST packs from the oracle's results, following only
