@@ -269,7 +269,9 @@ stamp_status_t stamp_plan_set_unfused(stamp_plan_t* plan, int32_t unfused);
 /* Matrix pipeline that multiplies the 4-bit rows (step "Y <- X W" of Algorithm "STaMP Linear" for the
  * rows quantized to bits_lo = 4 against the 4-bit weights).  Both compute the same integer sums
  * acc[m, n] = sum_c code[m, c] * qW[c, n] exactly, so every result of the library is bit-identical
- * under either setting:
+ * under either setting (one exception, to fp32 rounding: in plans without top levels that keep fewer 8-bit
+ * tokens than approximations, stamp_linear_forward under STAMP_GEMM_FP6 multiplies the 4-bit approximations
+ * in one piece, where the other setting may add them up from dequantized partial sums over parts of the depth):
  *   STAMP_GEMM_FP6   (default) the codes as 6-bit floating point numbers code / 8 (E2M3, exact),
  *                    FP6 x FP6 -> fp32 MFMA, twice the int8 rate per clock; the fp32 accumulator holds
  *                    acc / 64 exactly (|acc| <= 49 d_in < 2^24).  Costs one conversion pass over the
