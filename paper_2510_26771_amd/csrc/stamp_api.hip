@@ -309,6 +309,8 @@ stamp_status_t forward_q(const stamp_plan* p, const int8_t* q_hi, const uint8_t*
     if (stamp_launch_block_sums_own(p, q_hi, scales, ythi, P, st) != hipSuccess) return STAMP_ERR_DEVICE;
   } else if (stamp_hi_rows_are_block_sums(p)) {
     if (stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad) != hipSuccess) return STAMP_ERR_DEVICE;
+  } else if (stamp_hi_top_fused(p)) {
+    if (stamp_launch_gemm_hi(p, q_hi, scales, 2, P, st, p->Npad) != hipSuccess) return STAMP_ERR_DEVICE;
   } else {
     if (stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st) != hipSuccess) return STAMP_ERR_DEVICE;
     if (stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit) != hipSuccess) return STAMP_ERR_DEVICE;
@@ -620,12 +622,13 @@ stamp_status_t stamp_debug_run_stage(const stamp_plan_t* p, int32_t stage, const
     case 1: e = stamp_launch_actquant(p, X, q_hi, q_lo, scales, abot, rowmax, gpart, st, 2); break;
     case 2:
       if (own_top(p)) e = stamp_launch_block_sums_own(p, q_hi, scales, ythi, P, st);
+      else if (stamp_hi_top_fused(p)) e = stamp_launch_gemm_hi(p, q_hi, scales, 2, P, st, p->Npad);
       else
         e = stamp_hi_rows_are_block_sums(p) ? stamp_launch_gemm_hi(p, q_hi, scales, 1, P, st, p->Npad)
                                             : stamp_launch_gemm_hi(p, q_hi, scales, 1, ythi, st);
       break;
-    case 3:  // nothing to launch when the plan has no top levels
-      if (!own_top(p) && !stamp_hi_rows_are_block_sums(p))
+    case 3:  // nothing to launch when the plan has no top levels, or when the 8-bit rows' GEMM has run them
+      if (!own_top(p) && !stamp_hi_rows_are_block_sums(p) && !stamp_hi_top_fused(p))
         e = stamp_launch_inverse_top(p, ythi, 0, p->geom.N, P, p->Npad, st, p->hi_ksplit);
       break;
     case 4:

@@ -25,6 +25,158 @@ using namespace stamp_gemm;
 
 // WN = waves along N: 2 -> 4 waves, tile 256 x 128, two workgroups per CU; 4 -> 8 waves, tile 256 x 256,
 // one workgroup per CU (fewer, larger tiles: for the few 8-bit rows, whose whole GEMM is one round of tiles).
+// Epilogue of the 8-bit rows' GEMM that also runs the top levels of the inverse transform (the J - r levels over the
+// k top coefficients of every sequence and output column): the tile's 256 rows are 256 / k whole sequences (k is a
+// power of two, at most 256), so the block sums P of those sequences come out of the tile itself and the dequantized
+// rows never go to memory.  Per pass of 32 WN columns (one 32-column MFMA block of every wave): the dequantized values,
+// same arithmetic as the plain de-quantizing epilogue, go to LDS at [sequence][natural position][column] (the
+// operand stages are free by now), the butterflies run in place as in k_inverse_top (same order of additions:
+// same bits), and row r of the result is block sum m0 + r.  Workgroup-wide: call from all threads.
+template <typename Acc, int WN>
+__device__ __forceinline__ void epilogue_top_inverse(const GemmArgs& a, typename Acc::V (&acc)[4][NI], uint8_t* smem,
+                                                     uint8_t* row_info, int m0, int n0, int lane, int wm, int wn, int tid) {
+  const StampGeom& g = a.g;
+  constexpr int CW = 32 * WN, NT = 128 * WN;  // columns per pass; threads = 4 groups of CW
+  float* s_buf = reinterpret_cast<float*>(smem);  // [256][CW]
+  const float* s_rowfac = reinterpret_cast<const float*>(row_info);
+  int* s_rowpos = reinterpret_cast<int*>(row_info + 1024);  // staging row of every tile row
+  const float* s_rowz = reinterpret_cast<const float*>(row_info + 2048);
+  const int l32 = lane & 31, kg = lane >> 5;
+  const int k = g.k, nseq = 256 / k;
+  // tile row seq * k + (slot e of natural position q) is staged at row seq * k + q
+  for (int t = tid; t < 256; t += NT) {
+    const int seq = t / k, q = t - seq * k;
+    int e, lvl;
+    if (!g.is2d) e = stamp_top_slot_1d(q, k, g.L, &lvl);
+    else e = stamp_top_slot_2d(q / g.G, q % g.G, g.G, g.L, &lvl);
+    s_rowpos[seq * k + e] = t;
+  }
+  __syncthreads();
+  const int ch = tid % CW, grp = tid / CW;  // 4 groups
+  float* P = reinterpret_cast<float*>(a.out);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) {
+    const int n = n0 + wn * (32 * NI) + ni * 32 + l32;
+    const float swn = a.sw[n];
+    const float csn = g.asym ? a.colsum[n] : 0.0f;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int rl = wm * 128 + mi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+        float y = 0.0f;  // rows beyond the last sequence
+        if (m0 + rl < a.M) {
+          const float af = g.asym ? __builtin_fmaf(-s_rowz[rl], csn, (float)acc[mi][ni][v]) : (float)acc[mi][ni][v];
+          y = (af * s_rowfac[rl]) * swn;
+        }
+        s_buf[s_rowpos[rl] * CW + wn * 32 + l32] = y;
+      }
+    }
+    __syncthreads();
+    // staged column ch = 32 w + l is output column n0 + 64 w + 32 ni + l (P is padded to whole tiles: no column check)
+    const int nout = n0 + (ch >> 5) * (32 * NI) + ni * 32 + (ch & 31);
+    // The coarse levels (pairs 16 or more rows apart; 2-D: cells of 8 x 8 and more) touch one row in 16 and run in
+    // place in LDS; the fine levels of 16 neighbouring rows (2-D: of a 4 x 4 cell) run in registers, from where the
+    // results go to P.  Every level adds and subtracts the same pairs as k_inverse_top does.
+    const bool small_grid = g.is2d && g.G < 4;  // 2 x 2 blocks per sequence: all in LDS
+    if (!g.is2d) {
+      for (int st = 1 << g.L; st >= 32; st >>= 1) {
+        const int npair = 256 / st;  // over all stacked sequences: st divides k
+        for (int i = grp; i < npair; i += 4) {
+          float* pa = &s_buf[(i * st) * CW + ch];
+          float* pd = &s_buf[(i * st + (st >> 1)) * CW + ch];
+          const float x = *pa, dd = *pd;
+          *pa = x + dd;
+          *pd = x - dd;
+        }
+        __syncthreads();
+      }
+      const int top = 1 << g.L;
+      for (int u = grp; u < 16; u += 4) {
+        float v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = s_buf[(16 * u + i) * CW + ch];
+#pragma unroll
+        for (int st = 16; st >= 2; st >>= 1) {
+          if (st <= top) {
+#pragma unroll
+            for (int i0 = 0; i0 < 16; i0 += st) {
+              const float x = v[i0], dd = v[i0 + (st >> 1)];
+              v[i0] = x + dd;
+              v[i0 + (st >> 1)] = x - dd;
+            }
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int r = 16 * u + i;
+          if (m0 + r < a.M) P[(size_t)(m0 + r) * a.ld_out + nout] = v[i];
+        }
+      }
+    } else {
+      for (int st = 1 << g.L; st >= (small_grid ? 2 : 8); st >>= 1) {
+        const int nc = g.G / st, h = st >> 1, cells = nc * nc;
+        for (int i = grp; i < nseq * cells; i += 4) {
+          const int seq = i / cells, c = i - seq * cells;
+          const int cy = c / nc, cx = c - cy * nc;
+          float* p00 = &s_buf[(seq * k + (cy * st) * g.G + cx * st) * CW + ch];
+          float* p01 = p00 + h * CW;
+          float* p10 = p00 + h * g.G * CW;
+          float* p11 = p10 + h * CW;
+          const float cLL = *p00, cW = *p01, cH = *p10, cD = *p11;
+          const float t0 = cLL + cH, t2 = cLL - cH, t1 = cW + cD, t3 = cW - cD;
+          *p00 = t0 + t1;
+          *p01 = t0 - t1;
+          *p10 = t2 + t3;
+          *p11 = t2 - t3;
+        }
+        __syncthreads();
+      }
+      if (small_grid) {
+        for (int r = grp; r < 256; r += 4)
+          if (m0 + r < a.M) P[(size_t)(m0 + r) * a.ld_out + nout] = s_buf[r * CW + ch];
+      } else {
+        const int nc4 = g.G >> 2, cells = nc4 * nc4;  // 4 x 4 cells per sequence; nseq * cells = 16
+        for (int u = grp; u < nseq * cells; u += 4) {
+          const int seq = u / cells, c = u - seq * cells;
+          const int cy = c / nc4, cx = c - cy * nc4;
+          const int base = seq * k + (cy * 4) * g.G + cx * 4;
+          float v[4][4];
+#pragma unroll
+          for (int dy = 0; dy < 4; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < 4; ++dx) v[dy][dx] = s_buf[(base + dy * g.G + dx) * CW + ch];
+#pragma unroll
+          for (int st = 4; st >= 2; st >>= 1) {
+            if (st <= (1 << g.L)) {
+              const int h = st >> 1;
+#pragma unroll
+              for (int y0 = 0; y0 < 4; y0 += st)
+#pragma unroll
+                for (int x0 = 0; x0 < 4; x0 += st) {
+                  const float cLL = v[y0][x0], cW = v[y0][x0 + h], cH = v[y0 + h][x0], cD = v[y0 + h][x0 + h];
+                  const float t0 = cLL + cH, t2 = cLL - cH, t1 = cW + cD, t3 = cW - cD;
+                  v[y0][x0] = t0 + t1;
+                  v[y0][x0 + h] = t0 - t1;
+                  v[y0 + h][x0] = t2 + t3;
+                  v[y0 + h][x0 + h] = t2 - t3;
+                }
+            }
+          }
+#pragma unroll
+          for (int dy = 0; dy < 4; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < 4; ++dx) {
+              const int r = base + dy * g.G + dx;
+              if (m0 + r < a.M) P[(size_t)(m0 + r) * a.ld_out + nout] = v[dy][dx];
+            }
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // 8-bit rows: row of A that row m of the GEMM multiplies (the first a_seq_used of every sequence's a_seq_rows)
 __device__ __forceinline__ int a_row_of(const GemmArgs& a, int m) { return m + (m / a.a_seq_used) * (a.a_seq_rows - a.a_seq_used); }
 
@@ -250,7 +402,8 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
   __syncthreads();
 #undef STAMP_REQUEST
 
-  epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave, wm, wn);
+  if constexpr (EPI == 4) epilogue_top_inverse<Acc, WN>(a, acc, smem, smem + kRowInfoOff, m0, n0, lane, wm, wn, tid);
+  else epilogue<Acc, EPI, RB, IS2D, YBF16>(a, acc, smem, smem + kRowInfoOff, eo, m0, n0, lane, wave, wm, wn);
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -415,7 +568,7 @@ hipError_t launch_y(const GemmArgs& a, hipStream_t st) {
 template <bool A_INT4, int EPI, int RB, bool IS2D>
 hipError_t launch(const GemmArgs& a, hipStream_t st) {
   // the output type only matters to the fused epilogue
-  if constexpr (EPI >= 2) {
+  if constexpr (EPI == 2 || EPI == 3) {
     if (a.g.y_bf16) return launch_y<A_INT4, EPI, RB, IS2D, true, 2>(a, st);
   }
   if constexpr (!A_INT4) {
@@ -451,10 +604,20 @@ bool stamp_hi_wide_tiles(int M, int Npad) {
 // is split (then the partial rows go through the top inverse like any others: it adds the parts and moves nothing).
 bool stamp_hi_rows_are_block_sums(const stamp_plan* p) { return !p->geom.ident && p->geom.L == 0 && p->hi_ksplit <= 1; }
 
-// The few 8-bit rows make few tiles: when they would leave most CUs idle, the depth of every tile is split
-// over 2..4 workgroups (partial rows, added by the top inverse).
 // at most this many 8-bit rows over the whole batch: the kernel for few rows
 constexpr int kHiFewRows = 128;
+
+// Plans with top levels whose 8-bit rows' GEMM keeps its depth in one piece and runs the tiled kernel: a tile of 256
+// rows holds whole sequences (k divides 256), so its epilogue can run the top levels of the inverse itself and write
+// the block sums (no partial rows in memory, no k_inverse_top).
+bool stamp_hi_top_fused(const stamp_plan* p) {
+  const StampGeom& g = p->geom;
+  return p->gen.kind == kGenNone && !g.ident && g.L > 0 && p->hi_ksplit <= 1 && g.B * g.k > kHiFewRows && g.k <= 256 &&
+         (g.k & (g.k - 1)) == 0;
+}
+
+// The few 8-bit rows make few tiles: when they would leave most CUs idle, the depth of every tile is split
+// over 2..4 workgroups (partial rows, added by the top inverse).
 
 int stamp_hi_ksplit(const stamp_plan* p, int rows_per_seq) {
   const int M = p->geom.B * rows_per_seq;
@@ -526,6 +689,12 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
     if (a.M <= 64) return launch_hi_few<64>(a, st);
     if (a.M <= kHiFewRows) return launch_hi_few<128>(a, st);
     return launch<false, 1, 0, false>(a, st);
+  }
+  if (mode == 2) {
+    // dequantization + top levels of the inverse in the tile: out = the block sums P, ld_out floats per row
+    if (!stamp_hi_top_fused(p) || ld_out <= 0) return hipErrorInvalidValue;
+    a.ld_out = ld_out;
+    return launch<false, 4, 0, false>(a, st);
   }
   return hipErrorInvalidValue;
 }

@@ -201,6 +201,8 @@ hipError_t stamp_launch_gemm_hi(const stamp_plan* p, const int8_t* q_hi, const f
 // P[row][0..ncols) = sum over the parts of src[part][row][0..ncols), rows < nrows
 hipError_t stamp_launch_sum_parts(const float* src, int nparts, int nrows, int ncols, float* P, int ldP, hipStream_t st);
 bool stamp_hi_rows_are_block_sums(const stamp_plan* p);
+// mode 2 of stamp_launch_gemm_hi is available: dequantization + top levels of the inverse in the GEMM's tiles, out = P
+bool stamp_hi_top_fused(const stamp_plan* p);
 hipError_t stamp_launch_gemm_lo(const stamp_plan* p, const uint8_t* q_lo, const float* scales, int mode,
                                 void* out, const float* P, hipStream_t st);
 // FP6 engine of the 4-bit rows: operand sizes, plan-time weight codes (colmax: bit patterns of the column

@@ -137,6 +137,28 @@ def test_partial_depth_cases(w):
     assert r["code_mismatches"] == 0
 
 
+# Many 8-bit rows against a wide layer: the 8-bit rows' GEMM keeps its depth in one piece (tiled kernel, 256 x 128 or
+# 256 x 256 tiles) and runs the top levels of the inverse in its own epilogue (the tile holds whole sequences: 1 to 16
+# of them, the last tile only partly filled), writing the block sums directly.
+TOP_IN_GEMM = [
+    _wl("topfused_1d_k64_b3", batch=3, seq_len=512, levels=9, k_hi=64, d_in=64, d_out=16640, seed=71),
+    _wl("topfused_1d_k64_b5_wide_asym", batch=5, seq_len=512, levels=9, k_hi=64, d_in=32, d_out=16650, seed=72,
+        act_quant="asym", mean_shift=0.4),
+    _wl("topfused_2d_k16_b9", batch=9, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=16, d_in=32,
+        d_out=33000, corr_len=4.0, seed=73),
+    _wl("topfused_1d_k256", batch=1, seq_len=2048, levels=11, k_hi=256, d_in=32, d_out=16640, seed=74),
+    _wl("topfused_1d_k16_L2_b10", batch=10, seq_len=512, levels=7, k_hi=16, d_in=32, d_out=16640, seed=75),
+    _wl("topfused_2d_k64_L1_b3_asym", batch=3, seq_len=1024, xform="haar2d", levels=3, grid_h=32, grid_w=32, k_hi=64,
+        d_in=32, d_out=16640, corr_len=6.0, seed=76, act_quant="asym", mean_shift=-0.3),
+]
+
+
+@pytest.mark.parametrize("w", TOP_IN_GEMM, ids=[w.name for w in TOP_IN_GEMM])
+def test_top_levels_inverted_in_the_8bit_rows_gemm(w):
+    r = tl.full_case(w, with_bias=True)
+    assert r["code_mismatches"] == 0
+
+
 # Layers wider than one workgroup of the transform kernel holds (8192 bf16 channels in 1-D, 4096 for fp32
 # input and in 2-D): the channels are split over workgroups and the kernel runs twice (row maxima, then
 # codes).  Shapes of real layers: an LLM down-projection (d_in 11008 / 14336), the second MLP layer of an
