@@ -159,7 +159,8 @@ typedef struct {
  *   levels) <= 256 and seq_len/n_top in {8,16,32,64,128} (1-D) or {16,64} (2-D: 4x4 or 8x8 token blocks);
  *   k_hi a power of two (four in 2-D) when k_hi >= the number of approximations, any 0 <= k_hi below it
  *   (e.g. the 3-level transform of 2048 tokens with 64 8-bit tokens: 256 approximations, 192 of them at
- *   4 bits); bits 8/4/4;
+ *   4 bits); in that second case n_top may exceed 256 (3 levels on 8192 tokens: 1024 approximations) as long
+ *   as d_in is at most 8192 (4096 for fp32 input or 2-D grids); bits 8/4/4;
  *   d_in a multiple of 32 and at most 32768 (above 8192, or 4096 for fp32 input or 2-D grids, the transform
  *   + quantization kernel splits the channels over workgroups and reads X twice: row ranges, then codes);
  *   act_quant symmetric or asymmetric; batch <= 65535 and batch * n_top <= 65535 (grid dimensions of the
@@ -222,7 +223,7 @@ stamp_status_t stamp_linear_forward_q(const stamp_plan_t* plan, const int8_t* q_
 
 /* Step 4 alone: Y = L^-1 Yt for Yt_dev [batch, seq_len, n_cols] fp32 in STaMP order; adds the
  * plan's bias (after the inverse, whatever bias_mode says) when n_cols == d_out and a bias was given;
- * Y_dev [batch, seq_len, n_cols] y_dtype.  Workspace: batch * (top rows, at most 256) * n_cols * 4 bytes on the
+ * Y_dev [batch, seq_len, n_cols] y_dtype.  Workspace: batch * stamp_plan_hi_rows(plan) * n_cols * 4 bytes on the
  * fast path; on the general path two buffers of batch * seq_len * n_cols * 4 bytes, each rounded up to 256.
  * Yt_dev is only read.  STAMP_ERR_UNSUPPORTED for a fast-path plan without transform. */
 stamp_status_t stamp_inverse(const stamp_plan_t* plan, const float* Yt_dev, int32_t n_cols,

@@ -76,7 +76,11 @@ __global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ s
   const int n = n_base + ch;
   const bool nact = n < ncols;
   const int k = g.k;
-  for (int q = grp; q < k; q += ngrp) {
+  // plans without top levels may have more than 256 top rows: nothing is transformed, every workgroup (blockIdx.z)
+  // moves its own 256 of them
+  const int q0 = (int)blockIdx.z * 256, kq = min(k - q0, 256);
+  for (int ql = grp; ql < kq; ql += ngrp) {
+    const int q = q0 + ql;
     int e, lvl_top;
     if (!g.is2d) {
       e = stamp_top_slot_1d(q, k, g.L, &lvl_top);
@@ -91,12 +95,12 @@ __global__ __launch_bounds__(256) void k_inverse_top(const float* __restrict__ s
       for (int part = 1; part < nparts; ++part) v += src[idx + part * part_stride];
     }
     if (apply_norm) v *= haar_norm_dev(g.r + lvl_top, g.is2d);
-    s_buf[q * kStride + ch] = v;
+    s_buf[ql * kStride + ch] = v;
   }
   __syncthreads();
-  inverse_inplace(s_buf, k, g.G, g.is2d, g.L, ch, grp, ngrp);
-  for (int q = grp; q < k; q += ngrp)
-    if (nact) P[((size_t)b * k + q) * ldP + n] = s_buf[q * kStride + ch];
+  inverse_inplace(s_buf, kq, g.G, g.is2d, g.L, ch, grp, ngrp);  // L > 0: kq = k
+  for (int ql = grp; ql < kq; ql += ngrp)
+    if (nact) P[((size_t)b * k + q0 + ql) * ldP + n] = s_buf[ql * kStride + ch];
 }
 
 // src rows of block (b, j): physical (b*s + j*R + e) or STaMP slot order; Y [B, s, ncols].
@@ -220,8 +224,10 @@ hipError_t stamp_launch_inverse_top(const stamp_plan* p, const float* src, int s
     // nothing to invert and the rows are in place already: only the parts of a split depth are added
     return stamp_launch_sum_parts(src, nparts, g.B * g.k, ncols, P, ldP, st);
   }
-  const size_t lds = (size_t)g.k * kStride * sizeof(float);
-  hipLaunchKernelGGL(k_inverse_top, dim3((ncols + kCols - 1) / kCols, g.B), dim3(256), lds, st, src,
+  if (g.k > 256 && g.L != 0) return hipErrorInvalidValue;  // plan creation admits that many top rows only without top levels
+  const int kl = g.k < 256 ? g.k : 256;
+  const size_t lds = (size_t)kl * kStride * sizeof(float);
+  hipLaunchKernelGGL(k_inverse_top, dim3((ncols + kCols - 1) / kCols, g.B, (g.k + 255) / 256), dim3(256), lds, st, src,
                      src_is_stamp ? g.s : g.k, src_is_stamp, P, ldP, ncols, g, nparts, (size_t)g.B * g.k * (size_t)ncols);
   return hipGetLastError();
 }

@@ -123,6 +123,13 @@ FEWER_HI = [
     _wl("few_1d_J3_k70_b3", batch=3, seq_len=1024, levels=3, k_hi=70, d_in=192, d_out=264, seed=67),
     _wl("few_1d_J4_k100_b4_asym", batch=4, seq_len=2048, levels=4, k_hi=100, d_in=128, d_out=136, seed=68,
         act_quant="asym", mean_shift=0.3),
+    # more than 256 approximations (3 levels on 4096 / 8192 tokens, 2 levels on a 128 x 128 grid)
+    _wl("few_1d_J3_512top", batch=2, seq_len=4096, levels=3, k_hi=64, d_in=128, d_out=192, seed=77),
+    _wl("few_1d_J3_1024top_asym", batch=1, seq_len=8192, levels=3, k_hi=64, d_in=96, d_out=130, seed=78,
+        act_quant="asym", mean_shift=0.4, x_dtype="f32"),
+    _wl("few_1d_J3_512top_k0", batch=3, seq_len=4096, levels=3, k_hi=0, d_in=64, d_out=72, seed=79),
+    _wl("few_2d_J2_1024top", batch=1, seq_len=16384, xform="haar2d", levels=2, grid_h=128, grid_w=128, k_hi=64,
+        d_in=64, d_out=72, corr_len=8.0, seed=80),
     # channels split over workgroups: the top rows are quantized by the separate kernel
     _wl("few_1d_J3_k9_wide", batch=2, seq_len=256, levels=3, k_hi=9, d_in=4128, d_out=64, seed=69, x_dtype="f32"),
     _wl("few_2d_J2_k7_wide_asym", batch=1, seq_len=256, xform="haar2d", levels=2, grid_h=16, grid_w=16, k_hi=7,
@@ -575,7 +582,7 @@ def test_w_out_by_in_layout():
     p2.destroy()
 
 
-@pytest.mark.parametrize("case", ["1d", "2d", "1d_partial", "2d_partial"])
+@pytest.mark.parametrize("case", ["1d", "2d", "1d_partial", "2d_partial", "1d_many_top"])
 def test_stamp_inverse_entry_point(case):
     """stamp_inverse alone on random STaMP-ordered input against the oracle's inverse."""
     import torch
@@ -584,6 +591,8 @@ def test_stamp_inverse_entry_point(case):
         w = _wl("inv1d", batch=2, seq_len=512, levels=9, k_hi=16, d_in=64, d_out=96)
     elif case == "1d_partial":
         w = _wl("inv1d_partial", batch=2, seq_len=512, levels=6, k_hi=16, d_in=64, d_out=96)
+    elif case == "1d_many_top":  # 512 approximations, no top levels
+        w = _wl("inv1d_many_top", batch=2, seq_len=4096, levels=3, k_hi=16, d_in=64, d_out=96)
     elif case == "2d_partial":
         w = _wl("inv2d_partial", batch=2, seq_len=1024, xform="haar2d", levels=3, grid_h=32, grid_w=32, k_hi=16,
                 d_in=64, d_out=96)
@@ -600,7 +609,7 @@ def test_stamp_inverse_entry_point(case):
         if ncols == w.d_out:
             ref = ref + inp["bias"][None, None, :]
         Y = torch.empty((w.batch, w.seq_len, ncols), dtype=torch.float32, device="cuda")
-        ws = torch.empty(max(plan.workspace_bytes(), w.batch * w.k_hi * ncols * 4), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(max(plan.workspace_bytes(), w.batch * plan.hi_rows() * ncols * 4), dtype=torch.uint8, device="cuda")
         plan.inverse(torch.from_numpy(Yt).cuda(), ncols, Y, ws)
         torch.cuda.synchronize()
         err = np.max(np.abs(Y.cpu().numpy() - ref)) / np.max(np.abs(ref))
@@ -688,6 +697,15 @@ def test_full_size_llm_three_levels_64_hi_tokens():
     """cfg2's shape in the setting of the paper's language-model experiments: 3 levels, 64 8-bit tokens (of the 256
     approximations the first 64 are 8-bit, the other 192 are 4-bit rows), asymmetric min-max quantizer."""
     _full_size(get_workload("cfg2", levels=3, act_quant="asym"), 14)
+
+
+@pytest.mark.timeout(900)
+def test_full_size_cfg3_three_levels_64_hi_tokens():
+    """cfg3's shape (8 sequences of 4096 tokens) in the paper's language-model setting: 3 levels leave 512
+    approximations per sequence, 64 of them 8-bit tokens; served by the fast path (no top levels)."""
+    w = get_workload("cfg3", levels=3)
+    assert not tl.general_path(tl.plan_desc_for(w, "bf16"))
+    _full_size(w, 8, with_bias=False)
 
 
 @pytest.mark.timeout(900)
