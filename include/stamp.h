@@ -159,8 +159,8 @@ typedef struct {
  *   levels) <= 256 and seq_len/n_top in {8,16,32,64,128} (1-D) or {16,64} (2-D: 4x4 or 8x8 token blocks);
  *   k_hi a power of two (four in 2-D) when k_hi >= the number of approximations, any 0 <= k_hi below it
  *   (e.g. the 3-level transform of 2048 tokens with 64 8-bit tokens: 256 approximations, 192 of them at
- *   4 bits); in that second case n_top may exceed 256 (3 levels on 8192 tokens: 1024 approximations) as long
- *   as d_in is at most 8192 (4096 for fp32 input or 2-D grids); bits 8/4/4;
+ *   4 bits); in that second case n_top may exceed 256 (3 levels on 8192 tokens: 1024 approximations);
+ *   bits 8/4/4;
  *   d_in a multiple of 32 and at most 32768 (above 8192, or 4096 for fp32 input or 2-D grids, the transform
  *   + quantization kernel splits the channels over workgroups and reads X twice: row ranges, then codes);
  *   act_quant symmetric or asymmetric; batch <= 65535 and batch * n_top <= 65535 (grid dimensions of the

@@ -729,19 +729,23 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
   const int stride = kTopCh + 1;
   const bool cact = (c_base + ch) < d;
   float* base = abot + (size_t)b * k * d;
+  // Plans without top levels may have more than 256 block sums per sequence: nothing is transformed, so every
+  // workgroup (blockIdx.z) takes its own 256 rows [q0, q0 + kq); with top levels kq = k.
+  const int q0 = (int)blockIdx.z * 256, kq = min(k - q0, 256);
+  base += (size_t)q0 * d;
   // four independent loads in flight per thread before the first LDS write (one load per loop trip would
   // pay one memory latency per row)
-  for (int j0 = grp; j0 < k; j0 += 4 * ngrp) {
+  for (int j0 = grp; j0 < kq; j0 += 4 * ngrp) {
     float v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int j = j0 + u * ngrp;
-      v[u] = (cact && j < k) ? base[(size_t)j * d + c_base + ch] : 0.0f;
+      v[u] = (cact && j < kq) ? base[(size_t)j * d + c_base + ch] : 0.0f;
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int j = j0 + u * ngrp;
-      if (j < k) s_buf[j * stride + ch] = v[u];
+      if (j < kq) s_buf[j * stride + ch] = v[u];
     }
   }
   __syncthreads();
@@ -778,7 +782,7 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
     }
   }
   // normalise, scatter to STaMP order, row absmax over this slice
-  for (int q = grp; q < k; q += ngrp) {
+  for (int q = grp; q < kq; q += ngrp) {
     int e, lvl_top;  // level counted within the top part (1 = first top level); slot 0 gets the deepest
     if (!is2d) {
       e = stamp_top_slot_1d(q, k, L, &lvl_top);
@@ -786,6 +790,7 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
       const int y = q / G, x = q - y * G;
       e = stamp_top_slot_2d(y, x, G, L, &lvl_top);
     }
+    // (q0 > 0 only without top levels, where slot = position: e = q, counted from q0 like `base`)
     const int level = r_bottom + lvl_top;
     const float nrm = is2d ? ldexpf(1.0f, -level) : haar_norm(level);
     const float t = __fmul_rn(s_buf[q * stride + ch], nrm);
@@ -800,7 +805,7 @@ __global__ __launch_bounds__(256) void k_top(float* __restrict__ abot, uint32_t*
       yv = (uint32_t)__shfl_xor((int)x, 16, 64); x = max(x, yv);
       return x;
     };
-    const size_t slot = ((size_t)b * k + e) * gridDim.x + blockIdx.x;
+    const size_t slot = ((size_t)b * k + q0 + e) * gridDim.x + blockIdx.x;
     if (!asym) {
       const uint32_t x = max32(absbits(t));
       if (ch == 0) rowmax_part[slot] = x;
@@ -1077,10 +1082,11 @@ hipError_t stamp_launch_actquant(const stamp_plan* p, const void* X, int8_t* q_h
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (!(part & 2) || top_in_bottom) return hipSuccess;
-  const size_t lds = (size_t)g.k * (kTopCh + 1) * sizeof(float);
+  if (g.k > 256 && g.L != 0) return hipErrorInvalidValue;  // plan creation admits that many top rows only without top levels
+  const size_t lds = (size_t)(g.k < 256 ? g.k : 256) * (kTopCh + 1) * sizeof(float);
   const int nslices = (g.d + kTopCh - 1) / kTopCh;
   const size_t npart = (size_t)g.B * g.k * nslices;
-  hipLaunchKernelGGL(k_top, dim3(nslices, g.B), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d, g.G, g.r, g.L, g.asym,
+  hipLaunchKernelGGL(k_top, dim3(nslices, g.B, (g.k + 255) / 256), dim3(256), lds, st, abot, rowmax, g.k, g.d, g.is2d, g.G, g.r, g.L, g.asym,
                      npart);
   e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -54,11 +54,8 @@ stamp_status_t fast_geometry(const stamp_plan_desc_t* d, StampGeom* g, int* fuse
     *fused_ok = 1;
     return STAMP_OK;
   }
-  // More than 256 top rows: only where nothing holds a sequence's top rows in LDS, i.e. plans without top levels
-  // (fewer 8-bit tokens than approximations) whose channels fit one workgroup of the transform kernel (the bottom
-  // kernel then quantizes the block sums itself).  E.g. 3 levels and 64 8-bit tokens on 4096 or 8192 tokens.
-  const int32_t chan_max = (d->xform == STAMP_L_HAAR2D || d->x_dtype != STAMP_BF16) ? 4096 : 8192;
-  const bool one_split = d->d_in <= chan_max;
+  // More than 256 top rows: only where no kernel needs all top rows of a sequence in LDS at once, i.e. plans
+  // without top levels (fewer 8-bit tokens than approximations).  E.g. 3 levels and 64 8-bit tokens on 4096 or 8192 tokens.
   // Blocks.  With at least as many 8-bit tokens as level-J approximations, the blocks hold seq_len / k_hi tokens
   // (the top part runs the remaining levels over the k_hi block sums).  With fewer, the blocks hold the 2^J
   // (4^J) tokens of one approximation, the top part is the approximations themselves, and those beyond the
@@ -73,7 +70,7 @@ stamp_status_t fast_geometry(const stamp_plan_desc_t* d, StampGeom* g, int* fuse
       g->k = na;
       g->khi = d->k_hi;
     }
-    if (g->k > 256 && !(d->k_hi < na && one_split)) return STAMP_ERR_UNSUPPORTED;
+    if (g->k > 256 && d->k_hi >= na) return STAMP_ERR_UNSUPPORTED;
     g->R = d->seq_len / g->k;
     g->r = ilog2(g->R);
     if (g->r < 3 || g->r > 7) return STAMP_ERR_UNSUPPORTED;
@@ -90,7 +87,7 @@ stamp_status_t fast_geometry(const stamp_plan_desc_t* d, StampGeom* g, int* fuse
       g->k = sa * sa;
       g->khi = d->k_hi;
     }
-    if (g->k > 256 && !(d->k_hi < sa * sa && one_split)) return STAMP_ERR_UNSUPPORTED;
+    if (g->k > 256 && d->k_hi >= sa * sa) return STAMP_ERR_UNSUPPORTED;
     g->is2d = 1;
     g->R = d->seq_len / g->k;
     g->g = side / g->G;

@@ -32,19 +32,18 @@ def unpack_int4(q_lo: np.ndarray) -> np.ndarray:
 def _has_fast_blocks(d) -> bool:
     """Whether a Haar setting has the block structure the library's fast path serves (include/stamp.h)."""
     pow2 = lambda n: n >= 1 and n & (n - 1) == 0
-    # more than 256 top rows: only without top levels and with the channels in one workgroup of the transform kernel
-    one_split = d.d_in <= (8192 if (d.xform == XFORM_CODE["haar1d"] and d.x_dtype == 1) else 4096)
+    # more than 256 top rows: only without top levels (fewer 8-bit tokens than approximations)
     if d.xform == XFORM_CODE["haar1d"]:
         na = d.seq_len >> d.levels
         if d.k_hi >= na and not pow2(d.k_hi):
             return False
         n_top = max(d.k_hi, na)
-        return (n_top <= 256 or (d.k_hi < na and one_split)) and d.seq_len // n_top in (8, 16, 32, 64, 128)
+        return (n_top <= 256 or d.k_hi < na) and d.seq_len // n_top in (8, 16, 32, 64, 128)
     side = d.grid_h >> d.levels
     if d.k_hi >= side * side and not (pow2(d.k_hi) and (d.k_hi.bit_length() - 1) % 2 == 0):
         return False
     n_top = max(d.k_hi, side * side)
-    return (n_top <= 256 or (d.k_hi < side * side and one_split)) and d.seq_len // n_top in (16, 64)
+    return (n_top <= 256 or d.k_hi < side * side) and d.seq_len // n_top in (16, 64)
 
 
 def general_path(d) -> bool:

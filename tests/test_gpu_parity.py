@@ -130,6 +130,9 @@ FEWER_HI = [
     _wl("few_1d_J3_512top_k0", batch=3, seq_len=4096, levels=3, k_hi=0, d_in=64, d_out=72, seed=79),
     _wl("few_2d_J2_1024top", batch=1, seq_len=16384, xform="haar2d", levels=2, grid_h=128, grid_w=128, k_hi=64,
         d_in=64, d_out=72, corr_len=8.0, seed=80),
+    _wl("few_1d_J3_512top_wide", batch=1, seq_len=4096, levels=3, k_hi=64, d_in=11008, d_out=64, seed=81),
+    _wl("few_2d_J2_1024top_wide_asym", batch=1, seq_len=16384, xform="haar2d", levels=2, grid_h=128, grid_w=128,
+        k_hi=5, d_in=4128, d_out=40, corr_len=8.0, seed=82, act_quant="asym", mean_shift=0.2),
     # channels split over workgroups: the top rows are quantized by the separate kernel
     _wl("few_1d_J3_k9_wide", batch=2, seq_len=256, levels=3, k_hi=9, d_in=4128, d_out=64, seed=69, x_dtype="f32"),
     _wl("few_2d_J2_k7_wide_asym", batch=1, seq_len=256, xform="haar2d", levels=2, grid_h=16, grid_w=16, k_hi=7,
