@@ -158,6 +158,9 @@ TOP_IN_GEMM = [
         d_out=33000, corr_len=4.0, seed=73),
     _wl("topfused_1d_k256", batch=1, seq_len=2048, levels=11, k_hi=256, d_in=32, d_out=16640, seed=74),
     _wl("topfused_1d_k16_L2_b10", batch=10, seq_len=512, levels=7, k_hi=16, d_in=32, d_out=16640, seed=75),
+    _wl("topfused_2d_k4_b40", batch=40, seq_len=64, xform="haar2d", levels=3, grid_h=8, grid_w=8, k_hi=4, d_in=32,
+        d_out=16640, corr_len=2.0, seed=83),
+    _wl("topfused_1d_k2_b70", batch=70, seq_len=16, levels=4, k_hi=2, d_in=32, d_out=16640, seed=84),
     _wl("topfused_2d_k64_L1_b3_asym", batch=3, seq_len=1024, xform="haar2d", levels=3, grid_h=32, grid_w=32, k_hi=64,
         d_in=32, d_out=16640, corr_len=6.0, seed=76, act_quant="asym", mean_shift=-0.3),
 ]
