@@ -23,15 +23,14 @@ namespace {
 using namespace stamp_gemm;
 
 
-// WN = waves along N: 2 -> 4 waves, tile 256 x 128, two workgroups per CU; 4 -> 8 waves, tile 256 x 256,
-// one workgroup per CU (fewer, larger tiles: for the few 8-bit rows, whose whole GEMM is one round of tiles).
 // Epilogue of the 8-bit rows' GEMM that also runs the top levels of the inverse transform (the J - r levels over the
 // k top coefficients of every sequence and output column): the tile's 256 rows are 256 / k whole sequences (k is a
 // power of two, at most 256), so the block sums P of those sequences come out of the tile itself and the dequantized
 // rows never go to memory.  Per pass of 32 WN columns (one 32-column MFMA block of every wave): the dequantized values,
 // same arithmetic as the plain de-quantizing epilogue, go to LDS at [sequence][natural position][column] (the
-// operand stages are free by now), the butterflies run in place as in k_inverse_top (same order of additions:
-// same bits), and row r of the result is block sum m0 + r.  Workgroup-wide: call from all threads.
+// operand stages are free by now), the butterflies add and subtract the same pairs in the same order as
+// k_inverse_top does (same bits: the coarse levels in place in LDS, the finest ones in registers), and row r of the
+// result is block sum m0 + r.  Workgroup-wide: call from all threads.
 template <typename Acc, int WN>
 __device__ __forceinline__ void epilogue_top_inverse(const GemmArgs& a, typename Acc::V (&acc)[4][NI], uint8_t* smem,
                                                      uint8_t* row_info, int m0, int n0, int lane, int wm, int wn, int tid) {
@@ -180,6 +179,9 @@ __device__ __forceinline__ void epilogue_top_inverse(const GemmArgs& a, typename
 // 8-bit rows: row of A that row m of the GEMM multiplies (the first a_seq_used of every sequence's a_seq_rows)
 __device__ __forceinline__ int a_row_of(const GemmArgs& a, int m) { return m + (m / a.a_seq_used) * (a.a_seq_rows - a.a_seq_used); }
 
+// WN = waves along N: 2 -> 4 waves, tile 256 x 128, two workgroups per CU; 4 -> 8 waves, tile 256 x 256,
+// one workgroup per CU (fewer, larger tiles: for the few 8-bit rows, whose whole GEMM is one round of tiles).
+// EPI 4 (8-bit rows): de-quantization + the top levels of the inverse, block sums written directly (epilogue_top_inverse).
 template <bool A_INT4, int EPI, int RB, bool IS2D, bool YBF16, int WN>
 __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const GemmArgs a_in) {
   GemmArgs a = a_in;
