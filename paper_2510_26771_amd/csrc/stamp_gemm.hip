@@ -370,12 +370,16 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
+      // both operands' fragments of sub-step ks + 1 are read while sub-step ks is multiplied
+      u4 wa[2][4];
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) wa[0][mi] = *reinterpret_cast<const u4*>(st + baseA + mi * blkA);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        u4 wa[4];
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) wa[mi] = *reinterpret_cast<const u4*>(st + (baseA ^ (ks << 4)) + mi * blkA);
         if (ks < 3) {
+#pragma unroll
+          for (int mi = 0; mi < 4; ++mi)
+            wa[(ks + 1) & 1][mi] = *reinterpret_cast<const u4*>(st + (baseA ^ ((ks + 1) << 4)) + mi * blkA);
 #pragma unroll
           for (int ni = 0; ni < NI; ++ni) {
             const u4 w = *reinterpret_cast<const u4*>(st + (baseB ^ ((ks + 1) << 4)) + ni * blkB);
@@ -385,7 +389,7 @@ __global__ __launch_bounds__(128 * WN, (WN == 2 ? 2 : 1)) void k_gemm(const Gemm
         }
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi) {
-          const u4 w = wa[mi];
+          const u4 w = wa[ks & 1][mi];
           // natural channel order -> the order of the stored weights: evens then odds per 8 channels
           v4i fa;
           fa[0] = (int)__builtin_amdgcn_perm(w.y, w.x, 0x06040200u);
