@@ -473,7 +473,11 @@ def test_forward_under_hip_graph_capture():
     import paper_2510_26771_amd as st
     for w in (_wl("graph_1d", batch=2, seq_len=512, levels=9, k_hi=16, d_in=160, d_out=300, seed=81),
               _wl("graph_2d", batch=1, seq_len=256, xform="haar2d", levels=4, grid_h=16, grid_w=16, k_hi=4, d_in=96,
-                  d_out=128, seed=82, act_quant="asym")):
+                  d_out=128, seed=82, act_quant="asym"),
+              # no top levels, 4-bit approximations in the 4-bit rows' GEMM, the 8-bit rows' depth split (parts added by a kernel)
+              _wl("graph_1d_few", batch=2, seq_len=1024, levels=3, k_hi=8, d_in=1024, d_out=192, seed=85),
+              # the 8-bit rows' GEMM runs the top levels of the inverse itself
+              _wl("graph_1d_topfused", batch=3, seq_len=512, levels=9, k_hi=64, d_in=64, d_out=16640, seed=86)):
         inp = make_inputs(w, with_bias=True)
         plan = st.StampPlan(tl.plan_desc_for(w, "bf16"), torch.from_numpy(inp["W"]).cuda(),
                             torch.from_numpy(inp["bias"]).cuda())
